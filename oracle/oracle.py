@@ -1,0 +1,229 @@
+"""ctypes front end of the CPU oracle (oracle.c) plus the index bookkeeping.
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+bench's cpu_baseline leg; never by the product package.  The arithmetic lives
+in oracle.c; this file only marshals numpy arrays and keeps the inverted lists
+(stable append per list, Sec. 5.1 "Inverted files": the vectors of a cluster
+are stored contiguously).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+METRIC_L2 = 0
+METRIC_IP = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_SO = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile oracle.c with gcc.  Contraction is off and fmaf is explicit, so
+    the canon arithmetic is the IEEE one on any x86-64 with FMA."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-mfma", "-fopenmp", "-shared", "-fPIC",
+               "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_SO)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    lib.or_canon_l2.restype = ctypes.c_float
+    lib.or_canon_l2.argtypes = [f32p, f32p, ctypes.c_int]
+    lib.or_canon_ip.restype = ctypes.c_float
+    lib.or_canon_ip.argtypes = [f32p, f32p, ctypes.c_int]
+    lib.or_num_threads.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
+
+
+def num_threads():
+    return int(_load().or_num_threads())
+
+
+def canon_l2(a, b):
+    a, pa = _f32(a)
+    b, pb = _f32(b)
+    assert a.shape == b.shape and a.ndim == 1
+    return np.float32(_load().or_canon_l2(pa, pb, a.shape[0]))
+
+
+def canon_ip(a, b):
+    a, pa = _f32(a)
+    b, pb = _f32(b)
+    assert a.shape == b.shape and a.ndim == 1
+    return np.float32(_load().or_canon_ip(pa, pb, a.shape[0]))
+
+
+def flat_search(x, q, k, metric=METRIC_L2):
+    """Eq. 2: the k best database rows for every query row, best first."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    nb, d = x.shape
+    nq = q.shape[0]
+    assert q.shape[1] == d
+    D = np.empty((nq, k), dtype=np.float32)
+    I = np.empty((nq, k), dtype=np.int64)
+    _load().or_flat_search(_ptr(x), ctypes.c_int64(nb), _ptr(q), ctypes.c_int64(nq),
+                           ctypes.c_int(d), ctypes.c_int(metric), ctypes.c_int(k), _ptr(D), _ptr(I))
+    return D, I
+
+
+def assign(x, centroids, metric=METRIC_L2):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+    n, d = x.shape
+    nlist = centroids.shape[0]
+    out = np.empty(n, dtype=np.int32)
+    _load().or_assign(_ptr(x), ctypes.c_int64(n), _ptr(centroids), ctypes.c_int(nlist),
+                      ctypes.c_int(d), ctypes.c_int(metric), _ptr(out))
+    return out
+
+
+def coarse_probe(q, centroids, nprobe, metric=METRIC_L2):
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+    nq, d = q.shape
+    nlist = centroids.shape[0]
+    nprobe = min(nprobe, nlist)
+    probes = np.empty((nq, nprobe), dtype=np.int32)
+    cdist = np.empty((nq, nprobe), dtype=np.float32)
+    _load().or_coarse_probe(_ptr(q), ctypes.c_int64(nq), _ptr(centroids), ctypes.c_int(nlist),
+                            ctypes.c_int(d), ctypes.c_int(metric), ctypes.c_int(nprobe),
+                            _ptr(probes), _ptr(cdist))
+    return probes, cdist
+
+
+def pq_encode(x, list_of, centroids, codebooks, nbits):
+    """codebooks: [M, 2**nbits, dsub].  Returns uint8 [n, M*nbits/8]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+    codebooks = np.ascontiguousarray(codebooks, dtype=np.float32)
+    list_of = np.ascontiguousarray(list_of, dtype=np.int32)
+    n, d = x.shape
+    M, K, dsub = codebooks.shape
+    assert K == 1 << nbits and M * dsub == d and (M * nbits) % 8 == 0
+    codes = np.empty((n, M * nbits // 8), dtype=np.uint8)
+    _load().or_pq_encode(_ptr(x), ctypes.c_int64(n), ctypes.c_int(d), _ptr(list_of),
+                         _ptr(centroids), ctypes.c_int(M), ctypes.c_int(nbits), _ptr(codebooks),
+                         _ptr(codes))
+    return codes
+
+
+def pq_decode(codes, list_of, centroids, codebooks, nbits):
+    """D(C(x)) in float64: centroid + concatenated sub-codewords."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+    codebooks = np.ascontiguousarray(codebooks, dtype=np.float32)
+    list_of = np.ascontiguousarray(list_of, dtype=np.int32)
+    n = codes.shape[0]
+    M, K, dsub = codebooks.shape
+    d = M * dsub
+    out = np.empty((n, d), dtype=np.float64)
+    _load().or_pq_decode(_ptr(codes), ctypes.c_int64(n), ctypes.c_int(d), _ptr(list_of),
+                         _ptr(centroids), ctypes.c_int(M), ctypes.c_int(nbits), _ptr(codebooks),
+                         _ptr(out))
+    return out
+
+
+def recall(I_found, I_true, n=None):
+    """n-recall@k (Sec. 3.3 "Accuracy metrics"): fraction of the n ground-truth
+    nearest neighbours found among the k returned ids.  n = None means n = k
+    (the intersection measure)."""
+    I_found = np.asarray(I_found)
+    I_true = np.asarray(I_true)
+    n = I_true.shape[1] if n is None else n
+    hits = 0
+    for a in range(I_found.shape[0]):
+        hits += len(set(I_true[a, :n].tolist()) & set(I_found[a].tolist()) - {-1})
+    return hits / float(I_found.shape[0] * n)
+
+
+class OracleIVFPQ:
+    """IVF-PQ index held as plain numpy arrays (Sec. 5.1).
+
+    add():    O2 assignment, O3/O4 residual encoding, O5 stable append.
+    search(): O6 probes, O7 ADC on the decoded vector, O8 selection.
+    """
+
+    def __init__(self, d, metric, centroids, codebooks, nbits):
+        self.d = int(d)
+        self.metric = int(metric)
+        self.centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+        self.codebooks = np.ascontiguousarray(codebooks, dtype=np.float32)
+        self.nbits = int(nbits)
+        self.nlist = self.centroids.shape[0]
+        self.M = self.codebooks.shape[0]
+        assert self.centroids.shape[1] == self.d
+        assert self.codebooks.shape == (self.M, 1 << self.nbits, self.d // self.M)
+        self.code_size = self.M * self.nbits // 8
+        # in add order
+        self.add_ids = np.empty(0, dtype=np.int64)
+        self.add_list_of = np.empty(0, dtype=np.int32)
+        self.add_codes = np.empty((0, self.code_size), dtype=np.uint8)
+        self._relayout()
+
+    @property
+    def ntotal(self):
+        return self.add_ids.shape[0]
+
+    def _relayout(self):
+        order = np.argsort(self.add_list_of, kind="stable")
+        self.ids = np.ascontiguousarray(self.add_ids[order])
+        self.codes = np.ascontiguousarray(self.add_codes[order])
+        sizes = np.bincount(self.add_list_of, minlength=self.nlist).astype(np.int64)
+        self.list_offsets = np.zeros(self.nlist + 1, dtype=np.int64)
+        np.cumsum(sizes, out=self.list_offsets[1:])
+
+    def add(self, x, ids=None):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        n = x.shape[0]
+        if ids is None:  # sequential ids continue from ntotal (Sec. 8.1)
+            ids = np.arange(self.ntotal, self.ntotal + n, dtype=np.int64)
+        list_of = assign(x, self.centroids, self.metric)
+        codes = pq_encode(x, list_of, self.centroids, self.codebooks, self.nbits)
+        self.add_ids = np.concatenate([self.add_ids, np.asarray(ids, dtype=np.int64)])
+        self.add_list_of = np.concatenate([self.add_list_of, list_of])
+        self.add_codes = np.concatenate([self.add_codes, codes])
+        self._relayout()
+        return list_of, codes
+
+    def list_sizes(self):
+        return np.diff(self.list_offsets)
+
+    def search(self, q, k, nprobe, form=0, return_stats=False):
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        nq = q.shape[0]
+        npr = min(nprobe, self.nlist)
+        D = np.empty((nq, k), dtype=np.float32)
+        I = np.empty((nq, k), dtype=np.int64)
+        nscanned = np.zeros(nq, dtype=np.int64)
+        probes = np.empty((nq, npr), dtype=np.int32)
+        _load().or_ivfpq_search(
+            _ptr(q), ctypes.c_int64(nq), ctypes.c_int(self.d), ctypes.c_int(self.metric),
+            ctypes.c_int(self.nlist), _ptr(self.centroids), ctypes.c_int(self.M),
+            ctypes.c_int(self.nbits), _ptr(self.codebooks), _ptr(self.list_offsets),
+            _ptr(self.codes), _ptr(self.ids), ctypes.c_int(k), ctypes.c_int(nprobe),
+            ctypes.c_int(form), _ptr(D), _ptr(I), _ptr(nscanned), _ptr(probes))
+        if return_stats:
+            return D, I, nscanned, probes
+        return D, I

@@ -1,0 +1,367 @@
+"""Pins for the CPU oracle: each test checks it against something other than
+itself -- the paper's definitions evaluated another way (numpy float64
+library routines), closed forms, invariants, exhaustive search on tiny inputs.
+No GPU needed."""
+import itertools
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+L2, IP = 0, 1
+
+
+def np_pairwise(q, x, metric):
+    q64, x64 = q.astype(np.float64), x.astype(np.float64)
+    if metric == L2:
+        return ((q64[:, None, :] - x64[None, :, :]) ** 2).sum(-1)
+    return q64 @ x64.T
+
+
+def np_topk(dist, k, metric):
+    """Eq. 2 with numpy: stable argsort on the fp32-rounded distances."""
+    d32 = dist.astype(np.float32)
+    key = d32 if metric == L2 else -d32
+    idx = np.argsort(key, axis=1, kind="stable")[:, :k]
+    return np.take_along_axis(d32, idx, axis=1), idx
+
+
+# --------------------------------------------------------------------- O1 flat
+
+@pytest.mark.parametrize("metric", [L2, IP])
+def test_flat_matches_numpy_library_route(oracle, metric):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((700, 24), dtype=np.float32)
+    q = rng.standard_normal((33, 24), dtype=np.float32)
+    D, I = oracle.flat_search(x, q, 10, metric)
+    Dn, In = np_topk(np_pairwise(q, x, metric), 10, metric)
+    np.testing.assert_array_equal(I, In)
+    np.testing.assert_allclose(D, Dn, rtol=1e-6)
+
+
+def test_flat_closed_form_grid(oracle):
+    # Database = points (i, 0) for i = 0..19, query at the origin: the squared
+    # distance of point i is i*i (METRIC_L2 is the squared distance).
+    x = np.stack([np.arange(20, dtype=np.float32), np.zeros(20, dtype=np.float32)], axis=1)
+    q = np.zeros((1, 2), dtype=np.float32)
+    D, I = oracle.flat_search(x, q, 5, L2)
+    assert I[0].tolist() == [0, 1, 2, 3, 4]
+    assert D[0].tolist() == [0.0, 1.0, 4.0, 9.0, 16.0]
+    # inner product with q = (1, 0): score i, best = largest
+    q = np.array([[1.0, 0.0]], dtype=np.float32)
+    D, I = oracle.flat_search(x, q, 3, IP)
+    assert I[0].tolist() == [19, 18, 17]
+    assert D[0].tolist() == [19.0, 18.0, 17.0]
+
+
+def test_flat_k1_is_eq1_argmin(oracle):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((500, 16), dtype=np.float32)
+    q = rng.standard_normal((40, 16), dtype=np.float32)
+    _, I = oracle.flat_search(x, q, 1, L2)
+    np.testing.assert_array_equal(I[:, 0], np_pairwise(q, x, L2).argmin(1))
+
+
+def test_flat_ties_go_to_smaller_id_and_padding(oracle):
+    x = np.array([[1, 0], [0, 1], [-1, 0], [0, -1]], dtype=np.float32)  # all at distance 1
+    q = np.zeros((1, 2), dtype=np.float32)
+    D, I = oracle.flat_search(x, q, 6, L2)
+    assert I[0].tolist() == [0, 1, 2, 3, -1, -1]
+    assert D[0, :4].tolist() == [1.0] * 4 and np.isposinf(D[0, 4:]).all()
+    D, I = oracle.flat_search(x, q, 6, IP)
+    assert I[0].tolist() == [0, 1, 2, 3, -1, -1] and np.isneginf(D[0, 4:]).all()
+
+
+def test_cosine_l2_ip_equivalence_on_unit_vectors(oracle):
+    # Table "metric equivalences": on unit vectors ||q-x||^2 = 2 - 2<q,x>, so
+    # L2 and IP searches return the same neighbours.
+    cfg = S.config("C4", nb=3000, nq=50, ncomp=20)
+    x, q = S.make_data(cfg)
+    Dl, Il = oracle.flat_search(x, q, 10, L2)
+    Di, Ii = oracle.flat_search(x, q, 10, IP)
+    np.testing.assert_allclose(Dl, 2.0 - 2.0 * Di, atol=2e-6)
+    # ids agree wherever neighbouring scores are not within rounding of a tie
+    gap_ok = np.abs(np.diff(Di.astype(np.float64), axis=1)) > 1e-6
+    same = Il == Ii
+    assert same[:, 1:-1][gap_ok[:, :-1] & gap_ok[:, 1:]].all()
+    assert same.mean() > 0.99
+
+
+def test_canon_equals_exact_on_integer_data(oracle):
+    # SIFT-like data are small integers: every partial sum is an integer below
+    # 2^24, so fp32 in any order, the canon chain and fp64 agree bit for bit.
+    cfg = S.config("C2", nb=400, nq=20, ncomp=5)
+    x, q = S.make_data(cfg)
+    assert (x == np.rint(x)).all() and x.min() >= 0 and x.max() <= 255
+    exact = np_pairwise(q, x, L2)
+    assert exact.max() < 2 ** 24
+    for a in range(5):
+        for i in range(0, 400, 37):
+            assert float(oracle.canon_l2(q[a], x[i])) == exact[a, i]
+            assert float(oracle.canon_ip(q[a], x[i])) == float(np_pairwise(q, x, IP)[a, i])
+    D, _ = oracle.flat_search(x, q, 7, L2)
+    np.testing.assert_array_equal(D, np.sort(exact, axis=1)[:, :7].astype(np.float32))
+
+
+def test_canon_is_the_sequential_fma_chain(oracle):
+    # a = (1, 2^-12), b = 0: the chain is fma(2^-12, 2^-12, 1) = 1 + 2^-24,
+    # which rounds to 1 in fp32 (ties to even) -- an fp64 accumulation
+    # would keep the low term.
+    a = np.array([1.0, 2.0 ** -12], dtype=np.float32)
+    b = np.zeros(2, dtype=np.float32)
+    assert float(oracle.canon_l2(a, b)) == 1.0
+    # fused: fma(x, x, -0.0...) keeps the exact product before the single
+    # rounding: (1 + 2^-12)^2 = 1 + 2^-11 + 2^-24 -> fp32 gives 1 + 2^-11
+    a = np.array([1.0 + 2.0 ** -12], dtype=np.float32)
+    assert float(oracle.canon_l2(a, np.zeros(1, np.float32))) == 1.0 + 2.0 ** -11
+    # ... and a non-zero accumulator joins before that single rounding:
+    # 2^-24 + (1 + 2^-11 + 2^-24) = 1 + 2^-11 + 2^-23 exactly, whereas rounding the
+    # product first would lose both 2^-24 terms to ties-to-even.
+    a = np.array([2.0 ** -12, 1.0 + 2.0 ** -12], dtype=np.float32)
+    assert float(oracle.canon_l2(a, np.zeros(2, np.float32))) == 1.0 + 2.0 ** -11 + 2.0 ** -23
+    assert float(oracle.canon_ip(a, a)) == 1.0 + 2.0 ** -11 + 2.0 ** -23
+    # order of summation is index order: big first swallows the small ones
+    a = np.array([4096.0, 1.0, 1.0], dtype=np.float32)  # 2^24 + 1 + 1
+    assert float(oracle.canon_l2(a, np.zeros(3, np.float32))) == 2.0 ** 24
+    a = np.array([1.0, 1.0, 4096.0], dtype=np.float32)
+    assert float(oracle.canon_l2(a, np.zeros(3, np.float32))) == 2.0 ** 24 + 2.0
+
+
+# ------------------------------------------------------------ O2/O6 assignment
+
+def test_assign_is_flat_search_over_centroids(oracle):
+    # Sec. 5.1: the probed lists are the nprobe nearest centroids "as in Eq. 2".
+    cfg = S.config("C3", nb=3000, nq=64, ncomp=10, nlist=40)
+    x, q = S.make_data(cfg)
+    cent = S.make_centroids(x, 40, cfg["seed"])
+    a = oracle.assign(x, cent, L2)
+    _, I1 = oracle.flat_search(cent, x, 1, L2)          # integer data: exact, no rounding issue
+    np.testing.assert_array_equal(a, I1[:, 0])
+    probes, cd = oracle.coarse_probe(q, cent, 8, L2)
+    D8, I8 = oracle.flat_search(cent, q, 8, L2)
+    np.testing.assert_array_equal(probes, I8)
+    np.testing.assert_array_equal(cd, D8)
+    # centroids that are database rows are their own nearest centroid (distance 0)
+    a_c = oracle.assign(cent, cent, L2)
+    d_self = np_pairwise(cent, cent, L2)
+    np.testing.assert_array_equal(a_c, d_self.argmin(1))
+
+
+def test_assign_ip_metric_is_argmax(oracle):
+    rng = np.random.default_rng(5)
+    x = rng.integers(-8, 9, size=(300, 12)).astype(np.float32)   # integers: exact arithmetic
+    cent = rng.integers(-8, 9, size=(17, 12)).astype(np.float32)
+    a = oracle.assign(x, cent, IP)
+    np.testing.assert_array_equal(a, np_pairwise(x, cent, IP).argmax(1))
+
+
+def test_assign_tie_goes_to_smaller_list(oracle):
+    cent = np.array([[1, 0], [0, 1], [1, 0]], dtype=np.float32)      # list 0 and 2 identical
+    x = np.array([[1, 0], [0.5, 0.5]], dtype=np.float32)
+    assert oracle.assign(x, cent, L2).tolist() == [0, 0]
+    assert oracle.assign(x, cent, IP).tolist() == [0, 0]
+
+
+# ------------------------------------------------------------------ O4 encode
+
+def test_pq_with_one_subquantizer_is_a_plain_vq(oracle):
+    # Quantizer hierarchy (Sec. 4.1): PQ with M = 1 is the k-means quantizer, so
+    # encoding with a zero coarse centroid equals assignment to the same table.
+    rng = np.random.default_rng(7)
+    table = rng.standard_normal((256, 6), dtype=np.float32)
+    x = rng.standard_normal((500, 6), dtype=np.float32)
+    zero_c = np.zeros((1, 6), dtype=np.float32)
+    codes = oracle.pq_encode(x, np.zeros(500, np.int32), zero_c, table[None], 8)
+    np.testing.assert_array_equal(codes[:, 0].astype(np.int32), oracle.assign(x, table, L2))
+
+
+def _exact_code_case(rng, nlist, M, K, dsub, n):
+    """x = centroid + concatenated codewords, everything on a dyadic grid so
+    that all sums and differences are exact in fp32."""
+    d = M * dsub
+    cent = rng.integers(-64, 64, size=(nlist, d)).astype(np.float32) * 8.0   # well separated
+    cb = np.empty((M, K, dsub), dtype=np.float32)
+    for m in range(M):   # distinct codewords per sub-quantizer, small vs. centroid spacing
+        flat = rng.permutation(7 ** dsub)[:K]
+        digits = np.stack([(flat // 7 ** u) % 7 for u in range(dsub)], axis=1)
+        cb[m] = (digits - 3).astype(np.float32) * 0.25
+    lists = rng.integers(0, nlist, size=n)
+    codes = rng.integers(0, K, size=(n, M))
+    x = cent[lists].copy()
+    for m in range(M):
+        x[:, m * dsub:(m + 1) * dsub] += cb[m][codes[:, m]]
+    return cent, cb, lists.astype(np.int32), codes, x
+
+
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_encode_closed_form_when_residual_is_a_codeword(oracle, nbits):
+    rng = np.random.default_rng(11)
+    K = 1 << nbits
+    M, dsub = 6, 3
+    cent, cb, lists, codes, x = _exact_code_case(rng, 9, M, K, dsub, 400)
+    got_lists = oracle.assign(x, cent, L2)
+    # centroid spacing (>= 8) dwarfs the residuals (<= 0.75 per component) unless two
+    # random centroids coincide; then ties go to the smaller one
+    np.testing.assert_array_equal(np.abs(cent[got_lists] - cent[lists]).max(1) == 0, True)
+    got = oracle.pq_encode(x, got_lists, cent, cb, nbits)
+    if nbits == 8:
+        np.testing.assert_array_equal(got, codes.astype(np.uint8))
+    else:  # byte i = c_{2i} | c_{2i+1} << 4
+        packed = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
+        np.testing.assert_array_equal(got, packed)
+        assert got.shape[1] == M * 4 // 8          # code size = M * ceil(log2 K) bits
+    dec = oracle.pq_decode(got, got_lists, cent, cb, nbits)
+    np.testing.assert_array_equal(dec, x.astype(np.float64))   # zero reconstruction error
+
+
+def test_encode_duplicate_codeword_takes_smaller_index(oracle):
+    cb = np.zeros((1, 16, 2), dtype=np.float32)
+    cb[0, 5] = cb[0, 9] = [1.0, 1.0]
+    cb[0, 0] = [9.0, 9.0]
+    cb[0, 1:5] = 7.0; cb[0, 6:9] = 7.0; cb[0, 10:] = 7.0
+    x = np.array([[1.0, 1.0]], dtype=np.float32)
+    codes = oracle.pq_encode(np.concatenate([x, x], 1), np.zeros(1, np.int32),
+                             np.zeros((1, 4), np.float32), np.concatenate([cb, cb]), 4)
+    assert codes.tolist() == [[5 | (5 << 4)]]
+
+
+def test_encode_minimises_reconstruction_error_exhaustively(oracle):
+    rng = np.random.default_rng(13)
+    M, K, dsub, nlist = 2, 16, 2, 3
+    d = M * dsub
+    cent = rng.standard_normal((nlist, d), dtype=np.float32)
+    cb = rng.standard_normal((M, K, dsub), dtype=np.float32)
+    x = rng.standard_normal((40, d), dtype=np.float32)
+    lists = oracle.assign(x, cent, L2)
+    codes = oracle.pq_encode(x, lists, cent, cb, 4)
+    dec = oracle.pq_decode(codes, lists, cent, cb, 4)
+    err = ((dec - x) ** 2).sum(1)
+    for i in range(40):
+        best = np.inf
+        for j0, j1 in itertools.product(range(K), repeat=2):
+            cand = cent[lists[i]].astype(np.float64) + np.concatenate([cb[0, j0], cb[1, j1]])
+            best = min(best, ((cand - x[i]) ** 2).sum())
+        assert err[i] <= best * (1 + 1e-6) + 1e-12
+
+
+def test_decode_layout_M_K_dsub(oracle):
+    # codebooks[m][j] is the j-th codeword of sub-quantizer m, dsub floats.
+    M, K, dsub = 3, 256, 2
+    cb = np.zeros((M, K, dsub), dtype=np.float32)
+    for m in range(M):
+        for j in range(K):
+            cb[m, j] = [100 * m + j, -(100 * m + j)]
+    cent = np.array([[1, 2, 3, 4, 5, 6]], dtype=np.float32)
+    codes = np.array([[7, 200, 31]], dtype=np.uint8)
+    dec = oracle.pq_decode(codes, np.zeros(1, np.int32), cent, cb, 8)
+    assert dec[0].tolist() == [1 + 7, 2 - 7, 3 + 300, 4 - 300, 5 + 231, 6 - 231]
+
+
+# -------------------------------------------------------------- O7 ADC, O8 select
+
+def _c1_index(oracle, metric=L2, nbits=8, **kw):
+    cfg = S.config("C1", **kw)
+    x, q = S.make_data(cfg)
+    M = cfg["M"] if nbits == 8 else 16
+    cent = S.make_centroids(x, cfg["nlist"], cfg["seed"])
+    cb = S.make_codebooks(x, cent, M, nbits, cfg["seed"])
+    ix = oracle.OracleIVFPQ(cfg["d"], metric, cent, cb, nbits)
+    ix.add(x)
+    return cfg, x, q, ix
+
+
+@pytest.mark.parametrize("metric,nbits", [(L2, 8), (IP, 8), (L2, 4), (IP, 4)])
+def test_adc_equals_distance_to_decoded_vector(oracle, metric, nbits):
+    # Eq. 5: the ADC distance is the distance from q to D(C(x)); Eq. 8: the sum
+    # of table look-ups equals it.  Probe all lists => the result must equal a
+    # flat search over the decoded database, and the LUT form must agree.
+    cfg, x, q, ix = _c1_index(oracle, metric, nbits, nb=2000, nq=30)
+    D0, I0 = ix.search(q, 10, ix.nlist, form=0)
+    D1, I1 = ix.search(q, 10, ix.nlist, form=1)
+    dec = oracle.pq_decode(ix.add_codes, ix.add_list_of, ix.centroids, ix.codebooks, nbits)
+    Dn, In = np_topk(np_pairwise(q, dec, metric), 10, metric)
+    np.testing.assert_array_equal(I0, In)
+    np.testing.assert_allclose(D0, Dn, rtol=1e-6)
+    scale = (q.astype(np.float64) ** 2).sum(1, keepdims=True) + 1.0
+    assert (np.abs(D1.astype(np.float64) - D0) <= 1e-5 * np.maximum(np.abs(D0), scale)).all()
+    assert (I1 == I0).mean() > 0.98
+
+
+def test_exact_codes_and_all_probes_reproduce_flat_search(oracle):
+    rng = np.random.default_rng(17)
+    cent, cb, lists, codes, x = _exact_code_case(rng, 9, 6, 256, 3, 1500)
+    q = (x[rng.integers(0, 1500, 25)] + rng.integers(-2, 3, size=(25, 18)) * 0.125).astype(np.float32)
+    ix = oracle.OracleIVFPQ(18, L2, cent, cb, 8)
+    ix.add(x)
+    D, I = ix.search(q, 10, 9)
+    Df, If = oracle.flat_search(x, q, 10, L2)
+    np.testing.assert_array_equal(D, Df)         # dyadic data: exact in fp64 either way
+    # duplicates in x (same list, same codes) are equal-distance ties: compare up to ties
+    for a in range(25):
+        assert sorted(zip(D[a].tolist(), I[a].tolist())) == sorted(zip(Df[a].tolist(), If[a].tolist()))
+    assert oracle.recall(I, If) == 1.0 and oracle.recall(I, If, 1) == 1.0
+
+
+def test_probe_count_monotonicity_and_scanned_count(oracle):
+    cfg, x, q, ix = _c1_index(oracle)
+    sizes = ix.list_sizes()
+    assert sizes.sum() == cfg["nb"]
+    prev = None
+    for nprobe in (1, 2, 4, 8, 16, 99):
+        D, I, nscanned, probes = ix.search(q, 10, nprobe, return_stats=True)
+        assert probes.shape[1] == min(nprobe, 16)                 # clamped to nlist
+        np.testing.assert_array_equal(nscanned, sizes[probes].sum(1))   # Eq. N_distances, scan term
+        pr, _ = oracle.coarse_probe(q, ix.centroids, nprobe)
+        np.testing.assert_array_equal(probes, pr)
+        if prev is not None:   # a superset of candidates can only improve every rank
+            assert (D <= prev).all()
+        prev = D
+        assert (np.diff(D, axis=1) >= 0).all()
+    # balanced-list estimate of the scan term: nprobe * N / nlist times the imbalance factor
+    imbalance = (sizes.astype(np.float64) ** 2).sum() * 16 / sizes.sum() ** 2
+    assert 1.0 <= imbalance < 3.0
+
+
+def test_select_equals_full_sort_of_candidates(oracle):
+    cfg, x, q, ix = _c1_index(oracle, nb=3000, nq=20)
+    D, I, _, probes = ix.search(q, 25, 3, return_stats=True)
+    dec = oracle.pq_decode(ix.add_codes, ix.add_list_of, ix.centroids, ix.codebooks, 8)
+    for a in range(20):
+        cand = np.flatnonzero(np.isin(ix.add_list_of, probes[a]))
+        dist = np_pairwise(q[a:a + 1], dec[cand], L2)[0].astype(np.float32)
+        order = np.lexsort((cand, dist))[:25]
+        np.testing.assert_array_equal(I[a], cand[order])
+        np.testing.assert_allclose(D[a], dist[order], rtol=1e-6)
+
+
+def test_fewer_candidates_than_k_pads_with_minus_one(oracle):
+    cfg, x, q, ix = _c1_index(oracle, nb=40, nq=5)
+    D, I, nscanned, _ = ix.search(q, 30, 2, return_stats=True)
+    for a in range(5):
+        n = int(nscanned[a])
+        assert n < 30
+        assert (I[a, :n] >= 0).all() and (I[a, n:] == -1).all() and np.isposinf(D[a, n:]).all()
+
+
+def test_add_in_pieces_and_custom_ids(oracle):
+    cfg, x, q, ix = _c1_index(oracle, nb=1200, nq=10)
+    ix2 = oracle.OracleIVFPQ(cfg["d"], L2, ix.centroids, ix.codebooks, 8)
+    ids = np.arange(1200, dtype=np.int64) * 3 + 5
+    ix2.add(x[:500], ids[:500])
+    ix2.add(x[500:], ids[500:])
+    D, I = ix.search(q, 10, 4)
+    D2, I2 = ix2.search(q, 10, 4)
+    np.testing.assert_array_equal(D, D2)
+    np.testing.assert_array_equal(I * 3 + 5, I2)
+    ix3 = oracle.OracleIVFPQ(cfg["d"], L2, ix.centroids, ix.codebooks, 8)
+    ix3.add(x[:500]); ix3.add(x[500:])        # sequential ids continue from ntotal
+    np.testing.assert_array_equal(ix3.search(q, 10, 4)[1], I)
+
+
+def test_recall_definitions(oracle):
+    It = np.array([[1, 2, 3, 4]])
+    assert oracle.recall(np.array([[4, 3, 2, 1]]), It) == 1.0
+    assert oracle.recall(np.array([[9, 1, 8, 7]]), It) == 0.25
+    assert oracle.recall(np.array([[9, 1, 8, 7]]), It, 1) == 1.0      # 1-recall@4
+    assert oracle.recall(np.array([[2, 9, 8, -1]]), It, 1) == 0.0
