@@ -1,0 +1,156 @@
+/*
+ * vs.h -- C ABI of the MI355X (gfx950) vector-search library.
+ *
+ * Batched IVF-PQ search and flat exact k-NN search as described in
+ * "The Faiss Library" (arXiv 2401.08281): Sec. 3 (Eq. 1-2, brute-force
+ * search, metrics), Sec. 4 (Eq. 5 asymmetric distance computation, product
+ * quantizer, Eq. 8 look-up tables), Sec. 5.1 (inverted files, residual
+ * encoding), App. A.4 "GPU Faiss" (the four GPU stages).
+ *
+ * General conventions
+ *   - Every array pointer is a DEVICE pointer on the current HIP device,
+ *     row-major and contiguous, owned by the caller unless stated otherwise.
+ *     The library never frees or keeps caller pointers beyond the call.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Work is enqueued on it.  vs_flat_search and vs_ivfpq_search return with
+ *     the work enqueued; outputs are valid after the stream is synchronised.
+ *     vs_ivfpq_create and vs_ivfpq_add synchronise the stream before
+ *     returning.
+ *   - metric VS_METRIC_L2 is the SQUARED Euclidean distance (smaller is
+ *     better); VS_METRIC_IP is the inner product (larger is better).
+ *     Results are ordered best first (Eq. 2).
+ *   - Empty result slots (fewer than k candidates): id = -1 and distance
+ *     +inf (L2) / -inf (IP), placed last (Sec. 8.1: negative ids are invalid).
+ *   - Every function returns VS_OK or a negative error code; a message for
+ *     the calling thread's last error is available from vs_last_error().
+ *     Nothing throws across this boundary.  Inputs containing NaN are
+ *     undefined behaviour of the ordering, never of memory safety.
+ *   - Calls on the same index, or flat searches on the same device, must not
+ *     overlap in time (they share scratch buffers).
+ */
+#ifndef VS_H_
+#define VS_H_
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define VS_API __attribute__((visibility("default")))
+#else
+#define VS_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vs_ivfpq vs_ivfpq; /* opaque; created and destroyed by the library */
+
+enum { VS_METRIC_L2 = 0, VS_METRIC_IP = 1 };
+
+enum {
+  VS_OK = 0,
+  VS_ERR_INVALID_ARG = -1, /* null pointer, size out of range, shape mismatch */
+  VS_ERR_UNSUPPORTED = -2, /* a combination this build has no kernel for */
+  VS_ERR_OOM = -3,         /* device or host allocation failed */
+  VS_ERR_DEVICE = -4       /* a HIP call failed; vs_last_error() has the HIP text */
+};
+
+#define VS_MAX_K 1024 /* largest k and largest nprobe accepted */
+
+/*
+ * Flat exact k-NN search (Sec. 3.2 "Brute force search", Eq. 2).
+ *   x        [nb, d] fp32 database rows; row i has id i.  nb < 2^31.
+ *   q        [nq, d] fp32 queries.
+ *   out_dist [nq, k] fp32, out_ids [nq, k] int64: for each query the k best
+ *            database rows, best first.
+ * Distances are evaluated in fp32 as one fused-multiply-add chain per
+ * (query, row) pair in dimension order; ties go to the smaller id.
+ * nq == 0 is a no-op.  nb == 0 fills the outputs with empty slots.
+ * Errors: null pointers (with nq > 0), d < 1, k < 1 or k > VS_MAX_K, unknown metric.
+ */
+VS_API int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
+                   int32_t metric, int32_t k, float* out_dist, int64_t* out_ids,
+                   void* hip_stream);
+
+/*
+ * Create an empty IVF-PQ index (Sec. 5.1 "Inverted files"; Sec. 4.1 product
+ * quantizer).  Training is not part of this library: the nlist coarse
+ * centroids and the M sub-codebooks are inputs and are copied.
+ *   centroids [nlist, d] fp32.
+ *   codebooks [M, 2^nbits, d/M] fp32: codebooks[m][j] is codeword j of
+ *             sub-quantizer m.
+ * Vectors are encoded as residuals to their list's centroid (by_residual,
+ * Sec. 5.1 "Encoding residuals") under both metrics.  Under VS_METRIC_IP,
+ * list assignment and probing also use the inner product (argmax).
+ * Errors: null pointers, d < 1, nlist < 1, M < 1, d % M != 0,
+ * nbits not in {4, 8} (UNSUPPORTED), M odd with nbits == 4, unknown metric.
+ */
+VS_API int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, int32_t M,
+                    int32_t nbits, const float* centroids, const float* codebooks,
+                    void* hip_stream);
+
+/*
+ * Add n vectors (Sec. 5.1; Sec. 8.1 for ids): each vector goes to the list of
+ * its best centroid (ties: smaller list number), its residual is PQ-encoded
+ * (each sub-vector to its nearest codeword in squared L2, ties: smaller code)
+ * and (code, id) is appended to the list, after the entries already there and
+ * in the order given.
+ *   x   [n, d] fp32.
+ *   ids [n] int64 >= 0, or NULL for sequential ids starting at the current
+ *       ntotal.
+ * Both decisions are taken on the fp32 fused-multiply-add chain described
+ * for vs_flat_search, so they are reproducible bit for bit on any IEEE
+ * machine.  Code bytes: nbits == 8: byte m = c_m; nbits == 4: byte i =
+ * c_{2i} | c_{2i+1} << 4.
+ * The list storage is re-laid-out contiguously; the call synchronises.
+ * n == 0 is a no-op.  The total number of stored vectors must stay < 2^32.
+ */
+VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, void* hip_stream);
+
+/*
+ * Batched IVF-PQ search (Sec. 5.1; Eq. 5; Eq. 8; App. A.4).
+ * For every query: the nprobe best centroids are found exactly (nprobe is
+ * clamped to nlist), a look-up table LUT_m[j] is built per (query, probed
+ * list) on the query's residual to the list centroid (per query for IP, plus
+ * the centroid's inner product as a per-list bias), every code of the probed
+ * lists is scored as sum_m LUT_m[c_m], and the k best over all probed lists
+ * are returned best first with their stored ids.
+ *   q [nq, d] fp32; out_dist [nq, k] fp32; out_ids [nq, k] int64.
+ * Errors: null pointers (with nq > 0), k or nprobe < 1 or > VS_MAX_K.
+ */
+VS_API int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                    float* out_dist, int64_t* out_ids, void* hip_stream);
+
+/* Frees the index and all device memory it owns.  NULL is allowed. */
+VS_API void vs_ivfpq_destroy(vs_ivfpq* ix);
+
+/* ---- introspection (used by parity checks) ------------------------------ */
+
+/* Number of stored vectors; -1 if ix is NULL. */
+VS_API int64_t vs_ivfpq_ntotal(const vs_ivfpq* ix);
+/* Bytes per stored code = M * nbits / 8; -1 if ix is NULL. */
+VS_API int32_t vs_ivfpq_code_size(const vs_ivfpq* ix);
+/* sizes: DEVICE [nlist] int64, number of entries per list. */
+VS_API int vs_ivfpq_get_list_sizes(const vs_ivfpq* ix, int64_t* sizes, void* hip_stream);
+/* Storage-order dump: entry s of the list-contiguous store has id ids[s]
+ * and lives in list list_of[s].  DEVICE [ntotal] each; either may be NULL. */
+VS_API int vs_ivfpq_get_assignments(const vs_ivfpq* ix, int64_t* ids, int32_t* list_of,
+                             void* hip_stream);
+/* codes: DEVICE [ntotal, code_size] uint8 in the same storage order. */
+VS_API int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stream);
+/* Coarse quantizer alone (first stage of vs_ivfpq_search): the nprobe best
+ * lists per query, best first.  probes: DEVICE [nq, min(nprobe, nlist)] int32;
+ * coarse_dist: DEVICE, same shape, fp32, may be NULL. */
+VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
+                    int32_t* probes, float* coarse_dist, void* hip_stream);
+
+/* Message of the calling thread's most recent error ("" if none). */
+VS_API const char* vs_last_error(void);
+
+/* Library version string. */
+VS_API const char* vs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VS_H_ */

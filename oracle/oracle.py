@@ -182,6 +182,22 @@ class OracleIVFPQ:
         self.add_codes = np.empty((0, self.code_size), dtype=np.uint8)
         self._relayout()
 
+    @classmethod
+    def from_storage(cls, d, metric, centroids, codebooks, nbits, list_offsets, codes, ids):
+        """Wraps an already laid-out store (list l owns rows list_offsets[l] ..
+        list_offsets[l+1] of codes / ids) so that search() can run on it."""
+        ix = cls(d, metric, centroids, codebooks, nbits)
+        ix.list_offsets = np.ascontiguousarray(list_offsets, dtype=np.int64)
+        ix.codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1, ix.code_size)
+        ix.ids = np.ascontiguousarray(ids, dtype=np.int64)
+        assert ix.list_offsets.shape[0] == ix.nlist + 1
+        assert ix.list_offsets[-1] == ix.ids.shape[0] == ix.codes.shape[0]
+        sizes = np.diff(ix.list_offsets)
+        ix.add_ids = ix.ids
+        ix.add_codes = ix.codes
+        ix.add_list_of = np.repeat(np.arange(ix.nlist, dtype=np.int32), sizes)
+        return ix
+
     @property
     def ntotal(self):
         return self.add_ids.shape[0]

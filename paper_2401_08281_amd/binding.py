@@ -1,0 +1,236 @@
+"""ctypes binding of libvs.so: same names as the C ABI in include/vs.h.
+
+Argument marshalling only.  Tensors must be CUDA/HIP tensors, contiguous, of
+the dtype the ABI states; the current torch stream is handed over as the HIP
+stream.  There is no CPU fallback: if the library is missing, loading fails.
+"""
+import ctypes
+import os
+
+import torch
+
+METRIC_L2 = 0
+METRIC_IP = 1
+VS_MAX_K = 1024
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvs.so")
+_lib = None
+
+
+class VSError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("vs error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib():
+    """Loads libvs.so (building it first only if it is not there at all)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build
+        build.build_lib()
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.vs_flat_search.restype = ctypes.c_int
+    L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_create.restype = ctypes.c_int
+    L.vs_ivfpq_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_add.restype = ctypes.c_int
+    L.vs_ivfpq_add.argtypes = [vp, vp, i64, vp, vp]
+    L.vs_ivfpq_search.restype = ctypes.c_int
+    L.vs_ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_destroy.restype = None
+    L.vs_ivfpq_destroy.argtypes = [vp]
+    L.vs_ivfpq_ntotal.restype = i64
+    L.vs_ivfpq_ntotal.argtypes = [vp]
+    L.vs_ivfpq_code_size.restype = i32
+    L.vs_ivfpq_code_size.argtypes = [vp]
+    L.vs_ivfpq_get_list_sizes.restype = ctypes.c_int
+    L.vs_ivfpq_get_list_sizes.argtypes = [vp, vp, vp]
+    L.vs_ivfpq_get_assignments.restype = ctypes.c_int
+    L.vs_ivfpq_get_assignments.argtypes = [vp, vp, vp, vp]
+    L.vs_ivfpq_get_codes.restype = ctypes.c_int
+    L.vs_ivfpq_get_codes.argtypes = [vp, vp, vp]
+    L.vs_ivfpq_coarse.restype = ctypes.c_int
+    L.vs_ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp]
+    L.vs_last_error.restype = ctypes.c_char_p
+    L.vs_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise VSError(rc, lib().vs_last_error().decode())
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda):
+        raise TypeError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t
+
+
+def _p(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None and t.numel() > 0 else ctypes.c_void_p(0)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def vs_last_error():
+    return lib().vs_last_error().decode()
+
+
+def vs_version():
+    return lib().vs_version().decode()
+
+
+def vs_flat_search(x, q, k, metric=METRIC_L2, out_dist=None, out_ids=None):
+    x = _dev(x, torch.float32, "x")
+    q = _dev(q, torch.float32, "q")
+    nb, d = x.shape
+    nq = q.shape[0]
+    if q.shape[1] != d:
+        raise ValueError("x and q differ in dimension")
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_flat_search(_p(x), nb, _p(q), nq, d, metric, k, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_ivfpq_create(d, metric, nlist, M, nbits, centroids, codebooks):
+    centroids = _dev(centroids, torch.float32, "centroids")
+    codebooks = _dev(codebooks, torch.float32, "codebooks")
+    if centroids is not None and centroids.numel() != nlist * d:
+        raise ValueError("centroids must hold nlist * d floats")
+    if codebooks is not None and M > 0 and d % M == 0 and 0 < nbits <= 16 and \
+            codebooks.numel() != (1 << nbits) * d:
+        raise ValueError("codebooks must hold M * 2^nbits * (d / M) floats")
+    h = ctypes.c_void_p(0)
+    _check(lib().vs_ivfpq_create(ctypes.byref(h), d, metric, nlist, M, nbits, _p(centroids),
+                                 _p(codebooks), _stream()))
+    return h
+
+
+def vs_ivfpq_destroy(h):
+    lib().vs_ivfpq_destroy(h)
+
+
+def vs_ivfpq_add(h, x, ids=None):
+    x = _dev(x, torch.float32, "x")
+    ids = _dev(ids, torch.int64, "ids")
+    if ids is not None and ids.numel() != x.shape[0]:
+        raise ValueError("ids must hold one id per row of x")
+    _check(lib().vs_ivfpq_add(h, _p(x), x.shape[0], _p(ids), _stream()))
+
+
+def vs_ivfpq_search(h, q, k, nprobe, out_dist=None, out_ids=None):
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_ivfpq_search(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_ivfpq_ntotal(h):
+    return int(lib().vs_ivfpq_ntotal(h))
+
+
+def vs_ivfpq_code_size(h):
+    return int(lib().vs_ivfpq_code_size(h))
+
+
+def vs_ivfpq_get_list_sizes(h, nlist, device):
+    sizes = torch.empty(nlist, dtype=torch.int64, device=device)
+    _check(lib().vs_ivfpq_get_list_sizes(h, _p(sizes), _stream()))
+    return sizes
+
+
+def vs_ivfpq_get_assignments(h, device):
+    n = vs_ivfpq_ntotal(h)
+    ids = torch.empty(n, dtype=torch.int64, device=device)
+    list_of = torch.empty(n, dtype=torch.int32, device=device)
+    _check(lib().vs_ivfpq_get_assignments(h, _p(ids), _p(list_of), _stream()))
+    return ids, list_of
+
+
+def vs_ivfpq_get_codes(h, device):
+    n = vs_ivfpq_ntotal(h)
+    codes = torch.empty((n, vs_ivfpq_code_size(h)), dtype=torch.uint8, device=device)
+    if n > 0:
+        _check(lib().vs_ivfpq_get_codes(h, _p(codes), _stream()))
+    return codes
+
+
+def vs_ivfpq_coarse(h, q, nprobe, nlist):
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    npr = max(min(nprobe, nlist), 0)
+    probes = torch.empty((nq, npr), dtype=torch.int32, device=q.device)
+    cdist = torch.empty((nq, npr), dtype=torch.float32, device=q.device)
+    _check(lib().vs_ivfpq_coarse(h, _p(q), nq, nprobe, _p(probes), _p(cdist), _stream()))
+    return probes, cdist
+
+
+class IVFPQ:
+    """Owner of one vs_ivfpq handle (thin convenience over the functions above)."""
+
+    def __init__(self, d, metric, centroids, codebooks, nbits):
+        self.d, self.metric, self.nbits = int(d), int(metric), int(nbits)
+        self.nlist = int(centroids.shape[0])
+        self.M = int(codebooks.shape[0])
+        self.device = centroids.device
+        self.h = vs_ivfpq_create(self.d, self.metric, self.nlist, self.M, self.nbits, centroids,
+                                 codebooks)
+
+    def close(self):
+        if getattr(self, "h", None) is not None:
+            vs_ivfpq_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def ntotal(self):
+        return vs_ivfpq_ntotal(self.h)
+
+    def add(self, x, ids=None):
+        vs_ivfpq_add(self.h, x, ids)
+
+    def search(self, q, k, nprobe, out_dist=None, out_ids=None):
+        return vs_ivfpq_search(self.h, q, k, nprobe, out_dist, out_ids)
+
+    def coarse(self, q, nprobe):
+        return vs_ivfpq_coarse(self.h, q, nprobe, self.nlist)
+
+    def list_sizes(self):
+        return vs_ivfpq_get_list_sizes(self.h, self.nlist, self.device)
+
+    def assignments(self):
+        return vs_ivfpq_get_assignments(self.h, self.device)
+
+    def codes(self):
+        return vs_ivfpq_get_codes(self.h, self.device)

@@ -1,0 +1,372 @@
+// Host runtime and C ABI of libvs (see include/vs.h for the contract).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/vs.h"
+#include "internal.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail(e_ == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "%s: %s", #expr, \
+                  hipGetErrorString(e_));                                                 \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Grow-only device scratch buffer.
+struct Scratch {
+  void* p = nullptr;
+  size_t bytes = 0;
+  int reserve(size_t need) {
+    if (need <= bytes) return VS_OK;
+    if (p) { HIP_TRY(hipFree(p)); p = nullptr; bytes = 0; }
+    HIP_TRY(hipMalloc(&p, need));
+    bytes = need;
+    return VS_OK;
+  }
+  void release() { if (p) (void)hipFree(p); p = nullptr; bytes = 0; }
+};
+
+// Carves aligned sub-buffers out of one allocation.
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; }
+};
+
+// scratch of vs_flat_search, one per device
+std::mutex g_flat_mu;
+Scratch g_flat_scratch[16];
+
+// Budget for a materialised distance tile: small enough to live in the
+// 256 MB last-level cache between the kernel that writes it and the
+// selection kernel that reads it back.
+constexpr size_t kTileBytes = 128ull << 20;
+
+// k best rows of B for every row of A, as keys [na, k].  mat: scratch for tile_rows x tile_cols.
+void knn_keys(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric, int k,
+              float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, hipStream_t st) {
+  launch_fill_u64(keys, na * k, 0xFFFFFFFFFFFFFFFFull, st);
+  for (int64_t a0 = 0; a0 < na; a0 += tile_rows) {
+    const int64_t ra = std::min(tile_rows, na - a0);
+    for (int64_t b0 = 0; b0 < nb; b0 += tile_cols) {
+      const int64_t cb = std::min(tile_cols, nb - b0);
+      launch_canon_matrix(A + a0 * d, ra, B + b0 * d, cb, d, metric, mat, tile_cols, st);
+      launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0, st);
+    }
+  }
+}
+
+void tile_shape(int64_t na, int64_t nb, int64_t* rows, int64_t* cols) {
+  int64_t c = std::min<int64_t>(nb, 16384);
+  c = (c + 63) / 64 * 64;
+  int64_t r = (int64_t)(kTileBytes / sizeof(float)) / c;
+  r = std::max<int64_t>(64, r / 64 * 64);
+  r = std::min(r, (na + 63) / 64 * 64);
+  *rows = r;
+  *cols = c;
+}
+
+}  // namespace
+
+struct vs_ivfpq {
+  IvfpqDims g{};
+  int device = 0;
+  float* centroids = nullptr;   // [nlist, d]
+  float* codebooks = nullptr;   // [M, K, dsub]
+  int64_t ntotal = 0;
+  uint8_t* codes = nullptr;     // [ntotal, code_size], list-contiguous
+  int64_t* ids = nullptr;       // [ntotal]
+  int64_t* list_off = nullptr;  // device [nlist + 1]
+  std::vector<int64_t> h_off;   // host copy
+  mutable Scratch scratch;
+};
+
+extern "C" {
+
+const char* vs_last_error(void) { return g_err; }
+const char* vs_version(void) { return "vs 0.1 (gfx950)"; }
+
+int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
+                   int32_t metric, int32_t k, float* out_dist, int64_t* out_ids,
+                   void* hip_stream) {
+  if (nq < 0 || nb < 0) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: negative size");
+  if (d < 1) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: d = %d < 1", d);
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: unknown metric %d", metric);
+  if (nb >= (1ll << 31)) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: nb must be < 2^31");
+  if (nq == 0) return VS_OK;
+  if (!q || !out_dist || !out_ids || (nb > 0 && !x)) return fail(VS_ERR_INVALID_ARG, "vs_flat_search: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_flat_search: device %d", dev);
+
+  int64_t rows, cols;
+  tile_shape(nq, std::max<int64_t>(nb, 1), &rows, &cols);
+  Carver cv;
+  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
+  const size_t o_keys = cv.take((size_t)nq * k * sizeof(u64));
+  std::lock_guard<std::mutex> lock(g_flat_mu);
+  Scratch& sc = g_flat_scratch[dev];
+  if (int rc = sc.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(sc.p);
+  float* mat = reinterpret_cast<float*>(base + o_mat);
+  u64* keys = reinterpret_cast<u64*>(base + o_keys);
+  knn_keys(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, st);
+  launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, int32_t M,
+                    int32_t nbits, const float* centroids, const float* codebooks,
+                    void* hip_stream) {
+  if (!out) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: out is null");
+  *out = nullptr;
+  if (!centroids || !codebooks) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: null pointer");
+  if (d < 1 || nlist < 1 || M < 1) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: d, nlist, M must be >= 1");
+  if (d % M != 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: d = %d is not a multiple of M = %d", d, M);
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: unknown metric %d", metric);
+  if (nbits != 4 && nbits != 8) return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_create: nbits = %d (only 4 and 8)", nbits);
+  if (nbits == 4 && (M & 1)) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_create: M must be even with 4-bit codes");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  vs_ivfpq* ix = new (std::nothrow) vs_ivfpq();
+  if (!ix) return fail(VS_ERR_OOM, "vs_ivfpq_create: host allocation failed");
+  ix->g.d = d; ix->g.metric = metric; ix->g.nlist = nlist; ix->g.M = M; ix->g.nbits = nbits;
+  ix->g.K = 1 << nbits; ix->g.dsub = d / M; ix->g.code_size = M * nbits / 8;
+  ix->h_off.assign((size_t)nlist + 1, 0);
+  auto cleanup = [&](int rc) { vs_ivfpq_destroy(ix); return rc; };
+#define TRY_C(expr)                                                                         \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return cleanup(fail(e_ == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "%s: %s", \
+                          #expr, hipGetErrorString(e_)));                                   \
+  } while (0)
+  TRY_C(hipGetDevice(&ix->device));
+  const size_t cb = (size_t)nlist * d * sizeof(float);
+  const size_t tb = (size_t)M * ix->g.K * ix->g.dsub * sizeof(float);
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->centroids), cb));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->codebooks), tb));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->list_off), ((size_t)nlist + 1) * sizeof(int64_t)));
+  TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemcpyAsync(ix->codebooks, codebooks, tb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));
+  TRY_C(hipStreamSynchronize(st));
+#undef TRY_C
+  *out = ix;
+  return VS_OK;
+}
+
+void vs_ivfpq_destroy(vs_ivfpq* ix) {
+  if (!ix) return;
+  if (ix->centroids) (void)hipFree(ix->centroids);
+  if (ix->codebooks) (void)hipFree(ix->codebooks);
+  if (ix->list_off) (void)hipFree(ix->list_off);
+  if (ix->codes) (void)hipFree(ix->codes);
+  if (ix->ids) (void)hipFree(ix->ids);
+  ix->scratch.release();
+  delete ix;
+}
+
+int64_t vs_ivfpq_ntotal(const vs_ivfpq* ix) { return ix ? ix->ntotal : -1; }
+int32_t vs_ivfpq_code_size(const vs_ivfpq* ix) { return ix ? ix->g.code_size : -1; }
+
+int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_add: index is null");
+  if (n < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_add: n < 0");
+  if (n == 0) return VS_OK;
+  if (!x) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_add: x is null");
+  if (ix->ntotal + n >= (1ll << 32)) return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_add: more than 2^32 - 1 stored vectors");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const IvfpqDims& g = ix->g;
+
+  // scratch: best keys [n] | list_of [n] | one byte per (vector, m) [n, M] | dest [n] | new offsets
+  Carver cv;
+  const size_t o_keys = cv.take((size_t)n * sizeof(u64));
+  const size_t o_list = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_tmp = cv.take((size_t)n * g.M);
+  const size_t o_dest = cv.take((size_t)n * sizeof(int64_t));
+  const size_t o_off = cv.take(((size_t)g.nlist + 1) * sizeof(int64_t));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  u64* keys = reinterpret_cast<u64*>(base + o_keys);
+  int32_t* list_of = reinterpret_cast<int32_t*>(base + o_list);
+  uint8_t* tmp_codes = reinterpret_cast<uint8_t*>(base + o_tmp);
+  int64_t* dest = reinterpret_cast<int64_t*>(base + o_dest);
+  int64_t* new_off = reinterpret_cast<int64_t*>(base + o_off);
+
+  // 1. list assignment: best centroid on the canon chain, ties to the smaller list
+  launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
+  launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
+  launch_keys_to_index32(keys, n, list_of, st);
+  // 2. residual PQ codes
+  launch_pq_encode(g, x, n, list_of, ix->centroids, ix->codebooks, tmp_codes, st);
+
+  // 3. stable placement: the new entries of a list follow its old ones, in the order given.
+  //    (bookkeeping on the host: one pass over n list numbers)
+  std::vector<int32_t> h_list((size_t)n);
+  HIP_TRY(hipMemcpyAsync(h_list.data(), list_of, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  std::vector<int64_t> add_cnt((size_t)g.nlist, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t l = h_list[(size_t)i];
+    if (l < 0 || l >= g.nlist) return fail(VS_ERR_DEVICE, "vs_ivfpq_add: assignment kernel produced list %d", l);
+    ++add_cnt[(size_t)l];
+  }
+  std::vector<int64_t> h_new((size_t)g.nlist + 1, 0), cursor((size_t)g.nlist);
+  for (int l = 0; l < g.nlist; ++l) {
+    const int64_t old_sz = ix->h_off[(size_t)l + 1] - ix->h_off[(size_t)l];
+    h_new[(size_t)l + 1] = h_new[(size_t)l] + old_sz + add_cnt[(size_t)l];
+    cursor[(size_t)l] = h_new[(size_t)l] + old_sz;
+  }
+  std::vector<int64_t> h_dest((size_t)n);
+  for (int64_t i = 0; i < n; ++i) h_dest[(size_t)i] = cursor[(size_t)h_list[(size_t)i]]++;
+  HIP_TRY(hipMemcpyAsync(dest, h_dest.data(), (size_t)n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(new_off, h_new.data(), h_new.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+
+  // 4. new contiguous storage
+  const int64_t total = ix->ntotal + n;
+  uint8_t* codes = nullptr;
+  int64_t* new_ids = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&codes), (size_t)total * g.code_size));
+  if (hipMalloc(reinterpret_cast<void**>(&new_ids), (size_t)total * sizeof(int64_t)) != hipSuccess) {
+    (void)hipFree(codes);
+    return fail(VS_ERR_OOM, "vs_ivfpq_add: id storage allocation failed");
+  }
+  launch_relayout(g, ix->codes, ix->ids, ix->ntotal, ix->list_off, new_off, tmp_codes, ids,
+                  ix->ntotal, dest, n, codes, new_ids, st);
+  hipError_t e = hipMemcpyAsync(ix->list_off, new_off, h_new.size() * sizeof(int64_t), hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) {
+    (void)hipFree(codes); (void)hipFree(new_ids);
+    return fail(VS_ERR_DEVICE, "vs_ivfpq_add: %s", hipGetErrorString(e));
+  }
+  if (ix->codes) (void)hipFree(ix->codes);
+  if (ix->ids) (void)hipFree(ix->ids);
+  ix->codes = codes; ix->ids = new_ids; ix->ntotal = total; ix->h_off.swap(h_new);
+  return VS_OK;
+}
+
+// coarse quantizer: keys [nq, npr] of the npr best lists per query
+static int coarse_keys(const vs_ivfpq* ix, const float* q, int64_t nq, int npr, float* mat,
+                       int64_t rows, int64_t cols, u64* ckeys, hipStream_t st) {
+  knn_keys(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys, st);
+  return VS_OK;
+}
+
+int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
+                    int32_t* probes, float* coarse_dist, void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_coarse: index is null");
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_coarse: nq < 0");
+  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_coarse: nprobe = %d outside [1, %d]", nprobe, VS_MAX_K);
+  if (nq == 0) return VS_OK;
+  if (!q || !probes) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_coarse: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int npr = std::min<int>(nprobe, ix->g.nlist);
+  int64_t rows, cols;
+  tile_shape(nq, ix->g.nlist, &rows, &cols);
+  Carver cv;
+  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
+  const size_t o_ck = cv.take((size_t)nq * npr * sizeof(u64));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  u64* ckeys = reinterpret_cast<u64*>(base + o_ck);
+  coarse_keys(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, st);
+  launch_keys_to_probes(ckeys, nq * npr, ix->g.metric, probes, coarse_dist, st);
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                    float* out_dist, int64_t* out_ids, void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: index is null");
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: nq < 0");
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: nprobe = %d outside [1, %d]", nprobe, VS_MAX_K);
+  if (nq == 0) return VS_OK;
+  if (!q || !out_dist || !out_ids) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const IvfpqDims& g = ix->g;
+  const int npr = std::min<int>(nprobe, g.nlist);
+
+  // probe splits: enough workgroups to fill the chip when nq is small
+  int nsplit = (int)std::min<int64_t>(npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
+  const int ppb = (npr + nsplit - 1) / nsplit;
+  nsplit = (npr + ppb - 1) / ppb;
+
+  int64_t rows, cols;
+  tile_shape(nq, g.nlist, &rows, &cols);
+  Carver cv;
+  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
+  const size_t o_ck = cv.take((size_t)nq * npr * sizeof(u64));
+  const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
+  const size_t o_cd = cv.take((size_t)nq * npr * sizeof(float));
+  const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  u64* ckeys = reinterpret_cast<u64*>(base + o_ck);
+  int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
+  float* cdist = reinterpret_cast<float*>(base + o_cd);
+  u64* partial = reinterpret_cast<u64*>(base + o_part);
+
+  coarse_keys(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, st);
+  launch_keys_to_probes(ckeys, nq * npr, g.metric, probes, cdist, st);
+  if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
+                        ix->list_off, ix->codes, k, partial, st) != 0)
+    return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
+  launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfpq_get_list_sizes(const vs_ivfpq* ix, int64_t* sizes, void* hip_stream) {
+  if (!ix || !sizes) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_list_sizes: null pointer");
+  launch_list_sizes(ix->list_off, ix->g.nlist, sizes, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfpq_get_assignments(const vs_ivfpq* ix, int64_t* ids, int32_t* list_of,
+                             void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_assignments: index is null");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (ix->ntotal == 0) return VS_OK;
+  if (ids) HIP_TRY(hipMemcpyAsync(ids, ix->ids, (size_t)ix->ntotal * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+  if (list_of) launch_list_of_storage(ix->list_off, ix->g.nlist, ix->ntotal, list_of, st);
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stream) {
+  if (!ix || !codes) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_codes: null pointer");
+  if (ix->ntotal == 0) return VS_OK;
+  HIP_TRY(hipMemcpyAsync(codes, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(hip_stream)));
+  return VS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+// Host-side declarations shared by the translation units of libvs.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned long long u64;
+typedef unsigned int u32;
+
+// ---- canon distance tiles (kernels_dist.hip) --------------------------------
+// out[a * ldo + b] = canon distance of A row a and B row b.
+void launch_canon_matrix(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric,
+                         float* out, int64_t ldo, hipStream_t st);
+// best[a] = min over b of key(canon(A_a, B_b), b); best must hold KEY_EMPTY on entry.
+void launch_canon_argbest(const float* A, int64_t na, const float* B, int64_t nb, int d,
+                          int metric, u64* best, hipStream_t st);
+
+// ---- selection (kernels_select.hip) -----------------------------------------
+void launch_fill_u64(u64* p, int64_t n, u64 v, hipStream_t st);
+// keys[r][0..k) <- k best of (first ? {} : keys[r][0..k)) U {key(mat[r][c], col_base + c)}
+void launch_row_select(const float* mat, int64_t ld, int64_t nrows, int64_t ncols, u32 col_base,
+                       int metric, int k, u64* keys, bool first, hipStream_t st);
+// keys -> (value, int64 id); idmap == NULL: id = index, else id = idmap[index]; empty -> (-1, +-inf)
+void launch_keys_to_results(const u64* keys, int64_t n, int metric, float* out_dist,
+                            int64_t* out_ids, const int64_t* idmap, hipStream_t st);
+// keys -> (int32 index, value); used for probes
+void launch_keys_to_probes(const u64* keys, int64_t n, int metric, int32_t* out_idx,
+                           float* out_val, hipStream_t st);
+void launch_keys_to_index32(const u64* keys, int64_t n, int32_t* out_idx, hipStream_t st);
+
+// ---- IVF-PQ (kernels_ivfpq.hip) ----------------------------------------------
+struct IvfpqDims {
+  int d, metric, nlist, M, nbits, K, dsub, code_size;
+};
+// tmp_codes[i][m] = PQ code of sub-vector m of the residual of x_i (one byte per m)
+void launch_pq_encode(const IvfpqDims& g, const float* x, int64_t n, const int32_t* list_of,
+                      const float* centroids, const float* codebooks, uint8_t* tmp_codes,
+                      hipStream_t st);
+// move old entries to their new offsets and scatter the new ones
+void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t* old_ids,
+                     int64_t old_total, const int64_t* old_off, const int64_t* new_off,
+                     const uint8_t* tmp_codes, const int64_t* new_ids_or_null, int64_t id_base,
+                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids,
+                     hipStream_t st);
+void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
+                            hipStream_t st);
+void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_t st);
+// partial[q][s][0..k): k best keys (value, storage position) of the probes handled by split s
+int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                      const float* codebooks, const int32_t* probes, const float* cdist,
+                      int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
+                      int k, u64* partial, hipStream_t st);
+void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
+                        const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);

@@ -1,0 +1,407 @@
+// IVF-PQ kernels for gfx950: residual PQ encoding, list re-layout, the fused
+// look-up-table build + ADC scan + wavefront k-selection, and the merge across
+// probe splits.
+#include "common.hpp"
+#include "internal.hpp"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// PQ encoding (Sec. 4.1 product quantizer; Sec. 5.1 residual encoding).
+// One lane per (vector, sub-quantizer m); a workgroup covers 256 vectors of
+// one m and keeps that sub-codebook in LDS, read as broadcasts.  The residual
+// is one fp32 subtraction per component; the nearest codeword is taken on the
+// canon chain (diff, fma) over the dsub components; a strict '<' while walking
+// j upward keeps the smaller code on ties.
+// ---------------------------------------------------------------------------
+template <int DSUB>
+__global__ __launch_bounds__(256) void pq_encode_kernel(const float* __restrict__ x, int64_t n,
+                                                        int d, int dsub_rt, int K,
+                                                        const int32_t* __restrict__ list_of,
+                                                        const float* __restrict__ centroids,
+                                                        const float* __restrict__ codebooks, int M,
+                                                        uint8_t* __restrict__ tmp_codes) {
+  extern __shared__ __attribute__((aligned(16))) float T[];  // [K][dsub]
+  const int m = blockIdx.y;
+  const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+  const float* __restrict__ Tm = codebooks + (int64_t)m * K * dsub;
+  for (int e = threadIdx.x; e < K * dsub; e += 256) T[e] = Tm[e];
+  __syncthreads();
+  const int64_t i = blockIdx.x * 256ll + threadIdx.x;
+  if (i >= n) return;
+  const float* __restrict__ xi = x + i * d + m * dsub;
+  const float* __restrict__ c = centroids + (int64_t)list_of[i] * d + m * dsub;
+  int best = 0;
+  float bd = __builtin_inff();
+  if (DSUB > 0) {
+    float r[DSUB > 0 ? DSUB : 1];
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) r[u] = xi[u] - c[u];
+    for (int j = 0; j < K; ++j) {
+      float acc = 0.f;
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) {
+        const float diff = r[u] - T[j * DSUB + u];
+        acc = __builtin_fmaf(diff, diff, acc);
+      }
+      if (acc < bd) { bd = acc; best = j; }
+    }
+  } else {
+    for (int j = 0; j < K; ++j) {
+      float acc = 0.f;
+      for (int u = 0; u < dsub; ++u) {
+        const float r = xi[u] - c[u];
+        const float diff = r - T[j * dsub + u];
+        acc = __builtin_fmaf(diff, diff, acc);
+      }
+      if (acc < bd) { bd = acc; best = j; }
+    }
+  }
+  tmp_codes[i * M + m] = (uint8_t)best;
+}
+
+// same, sub-codebook read from global memory (sub-codebooks too large for LDS)
+__global__ __launch_bounds__(256) void pq_encode_global_kernel(
+    const float* __restrict__ x, int64_t n, int d, int dsub, int K,
+    const int32_t* __restrict__ list_of, const float* __restrict__ centroids,
+    const float* __restrict__ codebooks, int M, uint8_t* __restrict__ tmp_codes) {
+  const int m = blockIdx.y;
+  const float* __restrict__ T = codebooks + (int64_t)m * K * dsub;
+  const int64_t i = blockIdx.x * 256ll + threadIdx.x;
+  if (i >= n) return;
+  const float* __restrict__ xi = x + i * d + m * dsub;
+  const float* __restrict__ c = centroids + (int64_t)list_of[i] * d + m * dsub;
+  int best = 0;
+  float bd = __builtin_inff();
+  for (int j = 0; j < K; ++j) {
+    float acc = 0.f;
+    for (int u = 0; u < dsub; ++u) {
+      const float r = xi[u] - c[u];
+      const float diff = r - T[j * dsub + u];
+      acc = __builtin_fmaf(diff, diff, acc);
+    }
+    if (acc < bd) { bd = acc; best = j; }
+  }
+  tmp_codes[i * M + m] = (uint8_t)best;
+}
+
+// ---------------------------------------------------------------------------
+// list storage
+// ---------------------------------------------------------------------------
+// list that owns storage position p: the l with off[l] <= p < off[l+1]
+__device__ __forceinline__ int list_of_position(const int64_t* __restrict__ off, int nlist,
+                                                int64_t p) {
+  int lo = 0, hi = nlist;  // invariant: off[lo] <= p < off[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off[mid] <= p) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ void move_old_kernel(const uint8_t* __restrict__ old_codes,
+                                const int64_t* __restrict__ old_ids, int64_t old_total,
+                                const int64_t* __restrict__ old_off,
+                                const int64_t* __restrict__ new_off, int nlist, int cs,
+                                uint8_t* __restrict__ codes, int64_t* __restrict__ ids) {
+  const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (p >= old_total) return;
+  const int l = list_of_position(old_off, nlist, p);
+  const int64_t np = new_off[l] + (p - old_off[l]);
+  ids[np] = old_ids[p];
+  for (int b = 0; b < cs; ++b) codes[np * cs + b] = old_codes[p * cs + b];
+}
+
+__global__ void scatter_new_kernel(const uint8_t* __restrict__ tmp_codes,
+                                   const int64_t* __restrict__ new_ids, int64_t id_base,
+                                   const int64_t* __restrict__ dest, int64_t n, int M, int nbits,
+                                   int cs, uint8_t* __restrict__ codes, int64_t* __restrict__ ids) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int64_t p = dest[i];
+  ids[p] = new_ids ? new_ids[i] : id_base + i;
+  const uint8_t* __restrict__ t = tmp_codes + i * M;
+  if (nbits == 8) {
+    for (int b = 0; b < cs; ++b) codes[p * cs + b] = t[b];
+  } else {  // two 4-bit codes per byte, even m in the low nibble
+    for (int b = 0; b < cs; ++b) codes[p * cs + b] = (uint8_t)(t[2 * b] | (t[2 * b + 1] << 4));
+  }
+}
+
+__global__ void list_of_storage_kernel(const int64_t* __restrict__ off, int nlist, int64_t total,
+                                       int32_t* __restrict__ list_of) {
+  const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (p < total) list_of[p] = list_of_position(off, nlist, p);
+}
+
+__global__ void list_sizes_kernel(const int64_t* __restrict__ off, int nlist,
+                                  int64_t* __restrict__ sizes) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l < nlist) sizes[l] = off[l + 1] - off[l];
+}
+
+// ---------------------------------------------------------------------------
+// Fused LUT build + ADC scan + k-selection (Sec. 4 Eq. 5 and Eq. 8; Sec. 5.1;
+// App. A.4: tables staged in on-chip memory, lists streamed from HBM).
+//
+// One workgroup (4 wavefronts) serves one query and a contiguous range of its
+// probes.  Per probed list l:
+//   L2: r = q - c_l (fp32), LUT[m][j] = canon_l2(r_m, T_m[j]) into LDS;
+//   IP: LUT[m][j] = canon_ip(q_m, T_m[j]) once per workgroup, bias = <q, c_l>
+//       (the coarse score of the probe);
+// then every lane takes one code of the list per step (codes of a list are
+// contiguous, so a wavefront reads 64 * code_size consecutive bytes), sums
+// its M table entries in m order and offers (distance, storage position) to
+// its wavefront's WaveSelect.  At the end wavefront 0 absorbs the other
+// three and writes the k best keys of this (query, split).
+// ---------------------------------------------------------------------------
+template <int NBITS>
+__device__ __forceinline__ float adc_bytes(const float* __restrict__ lut, u32 word, int m_base,
+                                           float dist) {
+  // consumes 4 code bytes = 4 (NBITS=8) or 8 (NBITS=4) sub-quantizers starting at m_base
+  constexpr int K = 1 << NBITS;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const u32 byte = (word >> (8 * b)) & 0xFFu;
+    if (NBITS == 8) {
+      dist += lut[(m_base + b) * K + byte];
+    } else {
+      dist += lut[(m_base + 2 * b) * K + (byte & 15u)];
+      dist += lut[(m_base + 2 * b + 1) * K + (byte >> 4)];
+    }
+  }
+  return dist;
+}
+
+template <int NBITS>
+__global__ __launch_bounds__(256) void ivfpq_scan_kernel(
+    const float* __restrict__ q, int d, int metric, int M, int dsub,
+    const float* __restrict__ centroids, const float* __restrict__ codebooks,
+    const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb,
+    int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int cs,
+    int k, int tot, u64* __restrict__ partial) {
+  constexpr int K = 1 << NBITS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
+  float* lut = reinterpret_cast<float*>(slots + 4 * tot);       // M * K
+  float* rs = lut + M * K;                                      // d
+
+  const int64_t qi = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const float* __restrict__ qv = q + qi * d;
+  const int p_begin = split * ppb;
+  const int p_end = min(nprobe, p_begin + ppb);
+
+  WaveSelect ws;
+  ws.init(slots + wave * tot, tot, k);
+
+  if (metric == 1) {  // per-query tables
+    for (int e = threadIdx.x; e < M * K; e += 256) {
+      const int m = e >> NBITS;
+      const float* __restrict__ T = codebooks + (int64_t)e * dsub;
+      float acc = 0.f;
+      for (int u = 0; u < dsub; ++u) acc = __builtin_fmaf(qv[m * dsub + u], T[u], acc);
+      lut[e] = acc;
+    }
+    __syncthreads();
+  }
+
+  for (int p = p_begin; p < p_end; ++p) {
+    const int l = probes[qi * nprobe + p];
+    if (l < 0) continue;
+    const int64_t begin = list_off[l], end = list_off[l + 1];
+    if (begin == end) continue;  // uniform over the workgroup
+    float bias = 0.f;
+    if (metric == 0) {
+      const float* __restrict__ c = centroids + (int64_t)l * d;
+      __syncthreads();  // previous list's scan is done with lut
+      for (int t = threadIdx.x; t < d; t += 256) rs[t] = qv[t] - c[t];
+      __syncthreads();
+      for (int e = threadIdx.x; e < M * K; e += 256) {
+        const int m = e >> NBITS;
+        const float* __restrict__ T = codebooks + (int64_t)e * dsub;
+        const float* r = rs + m * dsub;
+        float acc = 0.f;
+        for (int u = 0; u < dsub; ++u) {
+          const float diff = r[u] - T[u];
+          acc = __builtin_fmaf(diff, diff, acc);
+        }
+        lut[e] = acc;
+      }
+      __syncthreads();
+    } else {
+      bias = cdist[qi * nprobe + p];
+    }
+    for (int64_t i0 = begin + wave * VS_WAVE; i0 < end; i0 += 4 * VS_WAVE) {
+      const int64_t i = i0 + lane;
+      const bool valid = i < end;
+      float dist = bias;
+      if (valid) {
+        const uint8_t* __restrict__ cp = codes + i * cs;
+        if ((cs & 15) == 0) {
+          for (int w = 0; w < (cs >> 4); ++w) {
+            const uint4 v = reinterpret_cast<const uint4*>(cp)[w];
+            const int mb = w * (NBITS == 8 ? 16 : 32);
+            dist = adc_bytes<NBITS>(lut, v.x, mb, dist);
+            dist = adc_bytes<NBITS>(lut, v.y, mb + (NBITS == 8 ? 4 : 8), dist);
+            dist = adc_bytes<NBITS>(lut, v.z, mb + (NBITS == 8 ? 8 : 16), dist);
+            dist = adc_bytes<NBITS>(lut, v.w, mb + (NBITS == 8 ? 12 : 24), dist);
+          }
+        } else if ((cs & 3) == 0) {
+          for (int w = 0; w < (cs >> 2); ++w)
+            dist = adc_bytes<NBITS>(lut, reinterpret_cast<const u32*>(cp)[w],
+                                    w * (NBITS == 8 ? 4 : 8), dist);
+        } else {
+          for (int b = 0; b < cs; ++b) {
+            const u32 byte = cp[b];
+            if (NBITS == 8) dist += lut[b * K + byte];
+            else { dist += lut[(2 * b) * K + (byte & 15u)]; dist += lut[(2 * b + 1) * K + (byte >> 4)]; }
+          }
+        }
+      }
+      ws.push(valid, make_key(dist, (u32)i, metric));
+    }
+  }
+  ws.finish();
+  __syncthreads();
+  if (wave == 0) {
+    for (int w = 1; w < 4; ++w) {
+      const volatile u64* other = slots + w * tot;
+      for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
+        const int j = j0 + lane;
+        const u64 key = j < k ? other[j] : KEY_EMPTY;
+        ws.push(j < k && key != KEY_EMPTY, key);
+      }
+    }
+    ws.finish();
+    u64* out = partial + ((int64_t)qi * nsplit + split) * k;
+    for (int j = lane; j < k; j += VS_WAVE) out[j] = ws.s[j];
+  }
+}
+
+// One wavefront per query: k best of the nsplit partial lists, then
+// (value, stored id).  Storage position -> id goes through the ids array
+// (Sec. 8.1: IVF indexes store the 64-bit id next to each code).
+__global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__ partial,
+                                                         int nsplit, int k, int tot, int metric,
+                                                         const int64_t* __restrict__ ids,
+                                                         float* __restrict__ out_dist,
+                                                         int64_t* __restrict__ out_ids) {
+  extern __shared__ u64 mslots[];
+  const int64_t qi = blockIdx.x;
+  const int lane = lane_id();
+  WaveSelect ws;
+  ws.init(mslots, tot, k);
+  const u64* __restrict__ src = partial + qi * (int64_t)nsplit * k;
+  const int n = nsplit * k;
+  for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
+    const int j = j0 + lane;
+    const u64 key = j < n ? src[j] : KEY_EMPTY;
+    ws.push(j < n && key != KEY_EMPTY, key);
+  }
+  ws.finish();
+  for (int j = lane; j < k; j += VS_WAVE) {
+    const u64 key = ws.s[j];
+    float v; int64_t id;
+    if (key == KEY_EMPTY) { v = metric ? -__builtin_inff() : __builtin_inff(); id = -1; }
+    else { v = key_value(key, metric); id = ids[key_index(key)]; }
+    out_dist[qi * k + j] = v;
+    out_ids[qi * k + j] = id;
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+void launch_pq_encode(const IvfpqDims& g, const float* x, int64_t n, const int32_t* list_of,
+                      const float* centroids, const float* codebooks, uint8_t* tmp_codes,
+                      hipStream_t st) {
+  if (n <= 0) return;
+  const dim3 grid((unsigned)((n + 255) / 256), (unsigned)g.M), block(256);
+  const size_t shmem = (size_t)g.K * g.dsub * sizeof(float);
+  if (shmem > 48 * 1024) {
+    hipLaunchKernelGGL(pq_encode_global_kernel, grid, block, 0, st, x, n, g.d, g.dsub, g.K, list_of,
+                       centroids, codebooks, g.M, tmp_codes);
+    return;
+  }
+#define LAUNCH(DS) \
+  hipLaunchKernelGGL((pq_encode_kernel<DS>), grid, block, shmem, st, x, n, g.d, g.dsub, g.K, list_of, \
+                     centroids, codebooks, g.M, tmp_codes)
+  switch (g.dsub) {
+    case 2: LAUNCH(2); break;
+    case 3: LAUNCH(3); break;
+    case 4: LAUNCH(4); break;
+    case 8: LAUNCH(8); break;
+    case 12: LAUNCH(12); break;
+    case 16: LAUNCH(16); break;
+    default: LAUNCH(0); break;
+  }
+#undef LAUNCH
+}
+
+void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t* old_ids,
+                     int64_t old_total, const int64_t* old_off, const int64_t* new_off,
+                     const uint8_t* tmp_codes, const int64_t* new_ids_or_null, int64_t id_base,
+                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids,
+                     hipStream_t st) {
+  if (old_total > 0)
+    hipLaunchKernelGGL(move_old_kernel, dim3((unsigned)((old_total + 255) / 256)), dim3(256), 0, st,
+                       old_codes, old_ids, old_total, old_off, new_off, g.nlist, g.code_size, codes,
+                       ids);
+  if (n_new > 0)
+    hipLaunchKernelGGL(scatter_new_kernel, dim3((unsigned)((n_new + 255) / 256)), dim3(256), 0, st,
+                       tmp_codes, new_ids_or_null, id_base, dest, n_new, g.M, g.nbits, g.code_size,
+                       codes, ids);
+}
+
+void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
+                            hipStream_t st) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(list_of_storage_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     off, nlist, total, list_of);
+}
+
+void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_t st) {
+  hipLaunchKernelGGL(list_sizes_kernel, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, off,
+                     nlist, sizes);
+}
+
+int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                      const float* codebooks, const int32_t* probes, const float* cdist,
+                      int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
+                      int k, u64* partial, hipStream_t st) {
+  if (nq <= 0) return 0;
+  const int ppb = (nprobe + nsplit - 1) / nsplit;
+  const int tot = select_slots_for_k(k);
+  const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
+                       (size_t)g.d * sizeof(float);
+  if (shmem > 160 * 1024) return -1;
+  const dim3 grid((unsigned)(nq * nsplit)), block(256);
+  if (g.nbits == 8) {
+    if (shmem > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ivfpq_scan_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    hipLaunchKernelGGL((ivfpq_scan_kernel<8>), grid, block, shmem, st, q, g.d, g.metric, g.M, g.dsub,
+                       centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off, codes,
+                       g.code_size, k, tot, partial);
+  } else {
+    if (shmem > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ivfpq_scan_kernel<4>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    hipLaunchKernelGGL((ivfpq_scan_kernel<4>), grid, block, shmem, st, q, g.d, g.metric, g.M, g.dsub,
+                       centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off, codes,
+                       g.code_size, k, tot, partial);
+  }
+  return 0;
+}
+
+void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
+                        const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
+  if (nq <= 0) return;
+  const int tot = select_slots_for_k(k);
+  const size_t shmem = (size_t)tot * sizeof(u64);
+  hipLaunchKernelGGL(ivfpq_merge_kernel, dim3((unsigned)nq), dim3(64), shmem, st, partial, nsplit, k,
+                     tot, metric, ids, out_dist, out_ids);
+}

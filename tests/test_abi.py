@@ -1,0 +1,79 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the
+device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vs.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2401_08281_amd as vs
+    return vs.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return re.findall(r"VS_API\s+[\w\s\*]+?\b(vs_\w+)\s*\(", text)
+
+
+def test_header_declares_the_boundary():
+    names = declared_symbols()
+    for must in ("vs_flat_search", "vs_ivfpq_create", "vs_ivfpq_add", "vs_ivfpq_search",
+                 "vs_ivfpq_destroy", "vs_last_error"):
+        assert must in names
+    assert len(names) == len(set(names)) >= 13
+
+
+def test_library_exports_every_declared_symbol(L):
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+    assert L.vs_version().decode().startswith("vs ")
+
+
+def test_no_internal_symbols_leak(L):
+    import subprocess
+    import paper_2401_08281_amd.build as b
+    out = subprocess.run(["nm", "-D", "--defined-only", b.lib_path()], capture_output=True, text=True).stdout
+    exported = [l.split()[-1] for l in out.splitlines() if " T " in l]
+    assert sorted(exported) == sorted(declared_symbols())
+
+
+def test_argument_errors_are_reported_without_a_device(L):
+    nul = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(16)   # never dereferenced: validation fails first
+    INVALID, UNSUPPORTED = -1, -2
+    assert L.vs_flat_search(one, 10, one, 1, 0, 0, 1, one, one, nul) == INVALID      # d < 1
+    assert b"d = 0" in L.vs_last_error()
+    assert L.vs_flat_search(one, 10, one, 1, 4, 0, 0, one, one, nul) == INVALID      # k < 1
+    assert L.vs_flat_search(one, 10, one, 1, 4, 0, 1025, one, one, nul) == INVALID   # k > VS_MAX_K
+    assert L.vs_flat_search(one, 10, one, 1, 4, 7, 1, one, one, nul) == INVALID      # metric
+    assert L.vs_flat_search(one, 10, nul, 1, 4, 0, 1, one, one, nul) == INVALID      # null q
+    assert L.vs_flat_search(one, -1, one, 1, 4, 0, 1, one, one, nul) == INVALID
+    assert L.vs_flat_search(nul, 10, nul, 0, 4, 0, 1, nul, nul, nul) == 0            # nq == 0: no-op
+    h = ctypes.c_void_p(0)
+    ref = ctypes.byref(h)
+    assert L.vs_ivfpq_create(ref, 32, 0, 16, 5, 8, one, one, nul) == INVALID         # d % M
+    assert b"multiple" in L.vs_last_error()
+    assert L.vs_ivfpq_create(ref, 32, 0, 16, 8, 6, one, one, nul) == UNSUPPORTED     # nbits
+    assert L.vs_ivfpq_create(ref, 30, 0, 16, 5, 4, one, one, nul) == INVALID         # odd M, 4 bit
+    assert L.vs_ivfpq_create(ref, 32, 0, 0, 8, 8, one, one, nul) == INVALID          # nlist
+    assert L.vs_ivfpq_create(ref, 32, 0, 16, 8, 8, nul, one, nul) == INVALID         # null centroids
+    assert L.vs_ivfpq_create(None, 32, 0, 16, 8, 8, one, one, nul) == INVALID
+    assert h.value is None
+    assert L.vs_ivfpq_add(nul, one, 5, nul, nul) == INVALID
+    assert L.vs_ivfpq_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
+    assert L.vs_ivfpq_ntotal(nul) == -1 and L.vs_ivfpq_code_size(nul) == -1
+    L.vs_ivfpq_destroy(nul)                                                           # allowed
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    import paper_2401_08281_amd as vs
+    with pytest.raises(TypeError):
+        vs.vs_flat_search(torch.zeros(4, 2), torch.zeros(1, 2), 1)

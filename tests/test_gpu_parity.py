@@ -1,0 +1,255 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, on the
+same seeded inputs.  Needs a real MI355X."""
+import sys
+import zlib
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from parity_util import EXTRA, check_search, storage_map
+
+pytestmark = pytest.mark.gpu
+
+L2, IP = 0, 1
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def vs():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2401_08281_amd as vs_
+    vs_.lib()            # fails loudly when libvs.so is missing
+    return vs_
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------ flat search
+
+FLAT_CASES = [
+    # name, nb, nq, d, k, metric, kind
+    ("c1_l2", 10_000, 100, 32, 10, L2, "gauss"),
+    ("c1_ip", 10_000, 100, 32, 10, IP, "gauss"),
+    ("odd_d_ragged", 4_133, 67, 18, 7, L2, "gauss"),
+    ("k1", 3_000, 50, 24, 1, L2, "gauss"),
+    ("k100_two_chunks", 40_000, 70, 16, 100, L2, "gauss"),
+    ("k1024", 5_000, 9, 8, 1024, L2, "gauss"),
+    ("k1024_ip", 3_000, 5, 8, 1024, IP, "gauss"),
+    ("nb_smaller_than_k", 37, 5, 12, 64, L2, "gauss"),
+    ("single_query", 2_000, 1, 40, 10, IP, "gauss"),
+]
+
+
+@pytest.mark.parametrize("name,nb,nq,d,k,metric,kind", FLAT_CASES, ids=[c[0] for c in FLAT_CASES])
+def test_flat_matches_oracle(vs, oracle, name, nb, nq, d, k, metric, kind):
+    say("flat %s nb=%d nq=%d d=%d k=%d metric=%d" % (name, nb, nq, d, k, metric))
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    x = rng.standard_normal((nb, d), dtype=np.float32)
+    q = rng.standard_normal((nq, d), dtype=np.float32)
+    D, I = vs.vs_flat_search(dev(x), dev(q), k, metric)
+    D, I = host(D), host(I)
+    Do, Io = oracle.flat_search(x, q, min(k + EXTRA, max(nb, k)), metric)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+    same = check_search(D, I, Do, Io, metric, q, xn)
+    assert same > 0.999
+
+
+def test_flat_sift_like_is_bit_exact(vs, oracle):
+    # integer-valued data: every arithmetic gives the exact distance
+    cfg = S.config("C2", nb=60_000, nq=128, ncomp=50)
+    say("flat sift-like nb=%d nq=%d k=100" % (cfg["nb"], cfg["nq"]))
+    x, q = S.make_data(cfg)
+    D, I = vs.vs_flat_search(dev(x), dev(q), 100, L2)
+    D, I = host(D), host(I)
+    Do, Io = oracle.flat_search(x, q, 100, L2)
+    np.testing.assert_array_equal(D, Do)
+    # equal distances are ordered by id on both sides
+    np.testing.assert_array_equal(I, Io)
+
+
+def test_flat_empty_database_and_no_queries(vs):
+    import torch
+    say("flat nb=0 / nq=0")
+    x = torch.empty((0, 8), dtype=torch.float32, device="cuda")
+    q = torch.randn((3, 8), dtype=torch.float32, device="cuda")
+    D, I = vs.vs_flat_search(x, q, 4, L2)
+    assert (host(I) == -1).all() and np.isposinf(host(D)).all()
+    D, I = vs.vs_flat_search(x, q, 4, IP)
+    assert (host(I) == -1).all() and np.isneginf(host(D)).all()
+    D, I = vs.vs_flat_search(q, x, 4, L2)
+    assert D.shape == (0, 4)
+
+
+# ------------------------------------------------------------------ IVF-PQ
+
+def build_both(vs, oracle, cfg, x, pieces=1, custom_ids=False):
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], cfg["metric"], dev(cent), dev(cb), cfg["nbits"])
+    orc = oracle.OracleIVFPQ(cfg["d"], cfg["metric"], cent, cb, cfg["nbits"])
+    ids = (np.arange(x.shape[0], dtype=np.int64) * 7 + 3) if custom_ids else None
+    bounds = np.linspace(0, x.shape[0], pieces + 1).astype(int)
+    for s, e in zip(bounds[:-1], bounds[1:]):
+        ix.add(dev(x[s:e]), dev(ids[s:e]) if custom_ids else None)
+        orc.add(x[s:e], ids[s:e] if custom_ids else None)
+    return ix, orc
+
+
+def check_storage(ix, orc):
+    """assignments and codes bit-exact, as the map id -> (list, code)."""
+    ids, list_of = ix.assignments()
+    ids, list_of, codes = host(ids), host(list_of), host(ix.codes())
+    assert ix.ntotal == orc.ntotal == ids.shape[0]
+    g = storage_map(ids, list_of, codes)
+    o = storage_map(orc.add_ids, orc.add_list_of, orc.add_codes)
+    np.testing.assert_array_equal(g[0], o[0])
+    np.testing.assert_array_equal(g[1], o[1])
+    np.testing.assert_array_equal(g[2], o[2])
+    np.testing.assert_array_equal(host(ix.list_sizes()), orc.list_sizes())
+    # lists are contiguous and in list order; within a list, entries keep add order
+    assert (np.diff(list_of) >= 0).all()
+    np.testing.assert_array_equal(ids, orc.ids)
+    np.testing.assert_array_equal(codes, orc.codes)
+
+
+IVF_CASES = {
+    "c1": (S.config("C1"), [(10, 4), (10, 1), (10, 16), (10, 99), (1, 4), (100, 8)]),
+    "c3_small": (S.config("C3", nb=100_000, nq=200, ncomp=100, nlist=512), [(10, 1), (10, 16), (10, 64)]),
+    "c4_small": (S.config("C4", nb=50_000, nq=100, ncomp=100, nlist=256), [(100, 64), (10, 3)]),
+    "c5_small": (S.config("C5", nb=20_000, nq=100, ncomp=50, nlist=128), [(10, 32), (100, 128)]),
+    "pq4_l2": (S.config("C1", nb=5_000, M=16, nbits=4), [(10, 4)]),
+    "ip_8bit": (S.config("C4", nb=20_000, nq=64, ncomp=40, nlist=64, metric=1, M=8), [(10, 8)]),
+    "odd_shapes": (S.config("C1", nb=3_001, nq=33, d=30, M=5, nlist=7), [(10, 3), (300, 7)]),
+}
+
+
+@pytest.mark.parametrize("name", list(IVF_CASES))
+def test_ivfpq_matches_oracle(vs, oracle, name):
+    cfg, searches = IVF_CASES[name]
+    say("ivfpq %s nb=%d d=%d nlist=%d M=%d nbits=%d metric=%d" % (
+        name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"], cfg["nbits"], cfg["metric"]))
+    x, q = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x)
+    check_storage(ix, orc)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        probes, cdist = ix.coarse(dev(q), nprobe)
+        po, co = oracle.coarse_probe(q, orc.centroids, nprobe, cfg["metric"])
+        np.testing.assert_array_equal(host(probes), po)       # probe order is bit-exact
+        np.testing.assert_array_equal(host(cdist), co)
+        D, I = ix.search(dev(q), k, nprobe)
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        same = check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        assert same > 0.99, same
+    ix.close()
+
+
+def test_ivfpq_add_in_pieces_with_custom_ids(vs, oracle):
+    cfg = S.config("C1", nb=6_000)
+    say("ivfpq pieces + custom ids")
+    x, q = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x, pieces=3, custom_ids=True)
+    check_storage(ix, orc)
+    D, I = ix.search(dev(q), 10, 4)
+    Do, Io = orc.search(q, 10 + EXTRA, 4)
+    check_search(host(D), host(I), Do, Io, L2)
+    ix.close()
+
+
+def test_ivfpq_empty_index_and_padding(vs, oracle):
+    cfg = S.config("C1", nb=60, nq=7)
+    say("ivfpq empty index, then fewer candidates than k")
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(S.config("C1"), S.make_data(S.config("C1"))[0])
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    D, I = ix.search(dev(q), 5, 4)
+    assert (host(I) == -1).all() and np.isposinf(host(D)).all()
+    orc = oracle.OracleIVFPQ(cfg["d"], L2, cent, cb, 8)
+    ix.add(dev(x)); orc.add(x)
+    D, I = ix.search(dev(q), 40, 2)
+    Do, Io = orc.search(q, 40 + EXTRA, 2)
+    check_search(host(D), host(I), Do, Io, L2)
+    assert (host(I) == -1).any()
+    ix.close()
+
+
+def test_search_is_deterministic(vs):
+    cfg = S.config("C1")
+    say("determinism")
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x))
+    r1 = [host(t).copy() for t in ix.search(dev(q), 10, 4)]
+    r2 = [host(t).copy() for t in ix.search(dev(q), 10, 4)]
+    np.testing.assert_array_equal(r1[0], r2[0])
+    np.testing.assert_array_equal(r1[1], r2[1])
+    ix.close()
+
+
+# ------------------------------------------------- full-size configurations
+
+def test_c3_full_size_sampled(vs, oracle):
+    """IVF4096,PQ16x8 on 1M vectors in the launch configuration the bench times.
+    The oracle cannot add 1M vectors in seconds, so assignments and codes are checked
+    bit-exactly on a seeded sample, and the oracle then searches the GPU-built
+    store for a seeded subset of the queries."""
+    cfg = S.config("C3")
+    say("C3 full size: nb=%d nlist=%d" % (cfg["nb"], cfg["nlist"]))
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x))
+    ids, list_of = ix.assignments()
+    ids, list_of, codes = host(ids), host(list_of), host(ix.codes())
+    sizes = host(ix.list_sizes())
+    assert sizes.sum() == cfg["nb"] and (np.sort(ids) == np.arange(cfg["nb"])).all()
+    rng = np.random.default_rng(5)
+    sample = np.sort(rng.choice(cfg["nb"], 4000, replace=False))
+    say("  oracle assign + encode on %d sampled vectors" % sample.size)
+    lo = oracle.assign(x[sample], cent, L2)
+    co = oracle.pq_encode(x[sample], lo, cent, cb, 8)
+    pos = np.empty(cfg["nb"], dtype=np.int64); pos[ids] = np.arange(cfg["nb"])
+    np.testing.assert_array_equal(list_of[pos[sample]], lo)
+    np.testing.assert_array_equal(codes[pos[sample]], co)
+    offsets = np.zeros(cfg["nlist"] + 1, dtype=np.int64); np.cumsum(sizes, out=offsets[1:])
+    orc = oracle.OracleIVFPQ.from_storage(cfg["d"], L2, cent, cb, 8, offsets, codes, ids)
+    qs = np.sort(rng.choice(cfg["nq"], 200, replace=False))
+    dq = dev(q)
+    for nprobe in (1, 16, 64):
+        say("  search all %d queries, nprobe=%d; oracle on %d of them" % (cfg["nq"], nprobe, qs.size))
+        D, I = ix.search(dq, 10, nprobe)
+        Do, Io = orc.search(q[qs], 10 + EXTRA, nprobe)
+        check_search(host(D)[qs], host(I)[qs], Do, Io, L2)
+    ix.close()
+
+
+def test_c2_full_size_sampled(vs, oracle):
+    """Flat search, 1M x 128, k = 100: all 10k queries on the GPU, the oracle on a
+    seeded sample of them (data are integer-valued, so distances are exact)."""
+    cfg = S.config("C2")
+    say("C2 full size: nb=%d nq=%d k=%d" % (cfg["nb"], cfg["nq"], cfg["k"]))
+    x, q = S.make_data(cfg)
+    D, I = vs.vs_flat_search(dev(x), dev(q), 100, L2)
+    D, I = host(D), host(I)
+    qs = np.sort(np.random.default_rng(6).choice(cfg["nq"], 48, replace=False))
+    say("  oracle on %d sampled queries" % qs.size)
+    Do, Io = oracle.flat_search(x, q[qs], 100, L2)
+    np.testing.assert_array_equal(D[qs], Do)
+    np.testing.assert_array_equal(I[qs], Io)
+    assert (np.diff(D, axis=1) >= 0).all() and (I >= 0).all()
