@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the IVF-PQ search hot path on one MI355X.
+
+A "step" is one pass of the whole path -- coarse quantizer, look-up-table
+construction, ADC scan, k-selection and merge -- over the full query batch of
+the workload, through the C ABI (vs_ivfpq_search), with all inputs resident
+in HBM.  Index construction is outside the timed region.
+
+Prints ONE JSON line.  `value` is queries/s; `roofline` describes the
+dominant kernel (the fused LUT + scan kernel), timed live with HIP events
+that the library records on the same stream around that launch;
+`cpu_baseline` is the CPU oracle timed on the host cores on a bounded sample
+of the same queries.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3", choices=["C1", "C3", "C2"])
+    ap.add_argument("--nprobe", type=int, default=None)
+    ap.add_argument("--nb", type=int, default=None, help="override database size (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (every box here has one); "
+              "--gpus %d is not supported. See DESIGN.md for how the path would shard." % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2401_08281_amd as vs
+    import synth_inputs as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    vs.lib()
+
+    over = {}
+    if args.nb:
+        over["nb"] = args.nb
+    cfg = S.config(args.workload, **over)
+    if args.nprobe and "nprobe" in cfg:
+        cfg["nprobe"] = args.nprobe
+    t0 = time.time()
+    x, q = S.make_data(cfg)
+    log("data %s: x %s q %s in %.1fs" % (args.workload, x.shape, q.shape, time.time() - t0))
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    nq, k, metric = cfg["nq"], cfg["k"], cfg["metric"]
+
+    if args.workload == "C2":
+        return bench_flat(args, cfg, x, q, xd, qd)
+
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], metric, torch.from_numpy(cent).cuda(), torch.from_numpy(cb).cuda(),
+                  cfg["nbits"])
+    torch.cuda.synchronize()
+    t0 = time.time()
+    ix.add(xd)
+    torch.cuda.synchronize()
+    t_add = time.time() - t0
+    log("index built: ntotal=%d in %.2fs" % (ix.ntotal, t_add))
+    nprobe = cfg["nprobe"]
+    code_size = cfg["M"] * cfg["nbits"] // 8
+
+    # algorithmic work of the scan: codes visited by the batch
+    sizes = ix.list_sizes()
+    probes, _ = ix.coarse(qd, nprobe)
+    scanned = int(sizes[probes.long()].sum().item())
+    pairs = int(probes.numel())
+    imbalance = float((sizes.double() ** 2).sum().item() * cfg["nlist"] / float(cfg["nb"]) ** 2)
+
+    D = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+    for _ in range(args.warmup):
+        ix.search(qd, k, nprobe, D, I)
+    torch.cuda.synchronize()
+    vs.vs_profile_enable(True)
+    vs.vs_profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ix.search(qd, k, nprobe, D, I)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = vs.vs_profile_read()
+    vs.vs_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    qps = nq / (ms_per_step * 1e-3)
+    stage_ms = {s: (v[0] / v[1] if v[1] else 0.0) for s, v in prof.items()}
+    log("per-launch ms: " + ", ".join("%s=%.3f" % (s, v) for s, v in stage_ms.items() if v))
+
+    scan_ms = stage_ms["scan"]
+    algo_bytes = scanned * code_size
+    achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+
+    # accuracy against exact search (GPU flat search, itself checked against the oracle by the tests)
+    Dg, Ig = vs.vs_flat_search(xd, qd, k, metric)
+    torch.cuda.synchronize()
+    I_h, Ig_h = I.cpu().numpy(), Ig.cpu().numpy()
+    hit_k = np.mean([len(set(I_h[a].tolist()) & set(Ig_h[a].tolist())) / float(k) for a in range(nq)])
+    hit_1 = np.mean([Ig_h[a, 0] in I_h[a] for a in range(nq)])
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe)
+
+    traffic = load_traffic("ivfpq_scan_%s_nprobe%d" % (args.workload, nprobe))
+    out = {
+        "metric": "IVF-PQ queries/sec at fixed nprobe & recall@10; ADC-scan HBM GB/s vs peak",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: IVF%d,PQ%dx%d L2, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
+            args.workload, cfg["nlist"], cfg["M"], cfg["nbits"], cfg["nb"], cfg["d"], nq, k, nprobe),
+            "nprobe": nprobe, "k": k, "recall_k_at_k": round(float(hit_k), 4),
+            "recall_1_at_k": round(float(hit_1), 4), "scanned_codes_per_query": scanned / nq,
+            "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
+            "stage_ms_per_launch": {s: round(v, 4) for s, v in stage_ms.items() if v}},
+        "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
+                     "kernel_ms": scan_ms, "pairs_per_launch": pairs},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe):
+    """The oracle's IVF-PQ search on the GPU-built store, bounded sample of queries."""
+    import numpy as np
+    import oracle
+    ids, _ = ix.assignments()
+    sizes = ix.list_sizes().cpu().numpy()
+    off = np.zeros(cfg["nlist"] + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    orc = oracle.OracleIVFPQ.from_storage(cfg["d"], cfg["metric"], cent, cb, cfg["nbits"], off,
+                                          ix.codes().cpu().numpy(), ids.cpu().numpy())
+    n = min(cfg["nq"], 200)
+    t0 = time.perf_counter(); orc.search(q[:n], k, nprobe); dt = time.perf_counter() - t0
+    # size the timed sample for ~10 s of CPU work: more queries, then whole-batch repeats
+    want = n * 10.0 / max(dt, 1e-3)
+    n2 = int(min(cfg["nq"], max(n, want)))
+    reps = int(max(1, min(50, round(want / n2))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        orc.search(q[:n2], k, nprobe)
+    dt = time.perf_counter() - t0
+    log("oracle: %d queries x %d passes in %.2fs on %d threads" % (n2, reps, dt, oracle.num_threads()))
+    return {"value": n2 * reps / dt, "unit": "queries/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "first %d of %d queries x %d passes, same index and nprobe, %.1f s" % (
+                n2, cfg["nq"], reps, dt)}
+
+
+def bench_flat(args, cfg, x, q, xd, qd):
+    """Secondary workload: flat exact search (C2).  Same JSON shape, its own metric name."""
+    import torch
+    import oracle
+    import paper_2401_08281_amd as vs
+    nq, k, metric, d, nb = cfg["nq"], cfg["k"], cfg["metric"], cfg["d"], cfg["nb"]
+    D = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+    for _ in range(args.warmup):
+        vs.vs_flat_search(xd, qd, k, metric, D, I)
+    torch.cuda.synchronize()
+    vs.vs_profile_enable(True); vs.vs_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        vs.vs_flat_search(xd, qd, k, metric, D, I)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = vs.vs_profile_read(); vs.vs_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dist_ms_total = prof["flat_dist"][0] / args.steps
+    flops = 3.0 * nq * nb * d      # sub + fma per pair and dimension
+    achieved = flops / (dist_ms_total * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        n = 16
+        t0 = time.perf_counter(); oracle.flat_search(x, q[:n], k, metric); dt = time.perf_counter() - t0
+        cpu = {"value": n / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "first %d of %d queries, %.1f s" % (n, nq, dt)}
+    out = {
+        "metric": "flat exact k-NN queries/sec", "value": nq / (ms_per_step * 1e-3),
+        "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C2: flat L2, nb=%d d=%d nq=%d k=%d" % (nb, d, nq, k),
+                   "stage_ms_per_step": {s: round(v[0] / args.steps, 3) for s, v in prof.items() if v[1]}},
+        "roofline": {"bound": "alu", "kernel": "canon_matrix_kernel", "achieved": achieved,
+                     "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def load_traffic(key):
+    """HBM bytes per launch measured with rocprofv3 --pmc in separate runs, if recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(key)
+    except (OSError, ValueError):
+        return None
+
+
+if __name__ == "__main__":
+    sys.exit(main())

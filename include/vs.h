@@ -144,6 +144,27 @@ VS_API int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stre
 VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
                     int32_t* probes, float* coarse_dist, void* hip_stream);
 
+/* ---- stage timing (used by benchmarks) ----------------------------------- */
+
+enum {
+  VS_STAGE_COARSE_DIST = 0,   /* query x centroid distance tiles                 */
+  VS_STAGE_COARSE_SELECT = 1, /* top-nprobe selection                            */
+  VS_STAGE_SCAN = 2,          /* fused LUT build + ADC scan + k-selection        */
+  VS_STAGE_MERGE = 3,         /* merge across probe splits, id translation       */
+  VS_STAGE_FLAT_DIST = 4,     /* flat search: query x database distance tiles    */
+  VS_STAGE_FLAT_SELECT = 5,   /* flat search: k-selection                        */
+  VS_NUM_STAGES = 6
+};
+
+/* on != 0: from now on vs_ivfpq_search and vs_flat_search bracket every kernel
+ * launch of the stages above with a pair of HIP events recorded on the caller's
+ * stream (the launches themselves are unchanged).  Off by default. */
+VS_API int vs_profile_enable(int on);
+/* Waits for all recorded events, adds up the elapsed milliseconds per stage
+ * into stage_ms[VS_NUM_STAGES] (HOST pointer) and the number of kernel launches
+ * per stage into launches[VS_NUM_STAGES] (HOST pointer), then forgets them. */
+VS_API int vs_profile_read(double* stage_ms, int64_t* launches);
+
 /* Message of the calling thread's most recent error ("" if none). */
 VS_API const char* vs_last_error(void);
 

@@ -22,5 +22,7 @@ from .binding import (  # noqa: F401
     vs_ivfpq_ntotal,
     vs_ivfpq_search,
     vs_last_error,
+    vs_profile_enable,
+    vs_profile_read,
     vs_version,
 )

@@ -56,6 +56,10 @@ def lib():
     L.vs_ivfpq_get_codes.argtypes = [vp, vp, vp]
     L.vs_ivfpq_coarse.restype = ctypes.c_int
     L.vs_ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp]
+    L.vs_profile_enable.restype = ctypes.c_int
+    L.vs_profile_enable.argtypes = [ctypes.c_int]
+    L.vs_profile_read.restype = ctypes.c_int
+    L.vs_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     L.vs_last_error.restype = ctypes.c_char_p
     L.vs_version.restype = ctypes.c_char_p
     _lib = L
@@ -93,6 +97,21 @@ def vs_last_error():
 
 def vs_version():
     return lib().vs_version().decode()
+
+
+STAGES = ("coarse_dist", "coarse_select", "scan", "merge", "flat_dist", "flat_select")
+
+
+def vs_profile_enable(on):
+    _check(lib().vs_profile_enable(1 if on else 0))
+
+
+def vs_profile_read():
+    """Returns {stage: (total_ms, launches)} for the calls made since the last read."""
+    ms = (ctypes.c_double * len(STAGES))()
+    n = (ctypes.c_int64 * len(STAGES))()
+    _check(lib().vs_profile_read(ms, n))
+    return {s: (float(ms[i]), int(n[i])) for i, s in enumerate(STAGES)}
 
 
 def vs_flat_search(x, q, k, metric=METRIC_L2, out_dist=None, out_ids=None):

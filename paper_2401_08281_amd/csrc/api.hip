@@ -59,6 +59,28 @@ struct Carver {
 std::mutex g_flat_mu;
 Scratch g_flat_scratch[16];
 
+// ---- optional stage timing ---------------------------------------------------
+struct ProfRec { int stage; hipEvent_t a, b; };
+std::mutex g_prof_mu;
+std::vector<ProfRec> g_prof;
+bool g_prof_on = false;
+
+// Brackets the launches made inside its scope with two events on the stream.
+struct StageTimer {
+  int stage; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; bool on;
+  StageTimer(int stage_, hipStream_t st_) : stage(stage_), st(st_), on(g_prof_on) {
+    if (!on) return;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(a, st);
+  }
+  ~StageTimer() {
+    if (!on) return;
+    (void)hipEventRecord(b, st);
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    g_prof.push_back({stage, a, b});
+  }
+};
+
 // Budget for a materialised distance tile: small enough to live in the
 // 256 MB last-level cache between the kernel that writes it and the
 // selection kernel that reads it back.
@@ -66,14 +88,21 @@ constexpr size_t kTileBytes = 128ull << 20;
 
 // k best rows of B for every row of A, as keys [na, k].  mat: scratch for tile_rows x tile_cols.
 void knn_keys(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric, int k,
-              float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, hipStream_t st) {
+              float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, hipStream_t st,
+              int stage_dist, int stage_select) {
   launch_fill_u64(keys, na * k, 0xFFFFFFFFFFFFFFFFull, st);
   for (int64_t a0 = 0; a0 < na; a0 += tile_rows) {
     const int64_t ra = std::min(tile_rows, na - a0);
     for (int64_t b0 = 0; b0 < nb; b0 += tile_cols) {
       const int64_t cb = std::min(tile_cols, nb - b0);
-      launch_canon_matrix(A + a0 * d, ra, B + b0 * d, cb, d, metric, mat, tile_cols, st);
-      launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0, st);
+      {
+        StageTimer t(stage_dist, st);
+        launch_canon_matrix(A + a0 * d, ra, B + b0 * d, cb, d, metric, mat, tile_cols, st);
+      }
+      {
+        StageTimer t(stage_select, st);
+        launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0, st);
+      }
     }
   }
 }
@@ -106,6 +135,30 @@ struct vs_ivfpq {
 extern "C" {
 
 const char* vs_last_error(void) { return g_err; }
+
+int vs_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  g_prof_on = on != 0;
+  return VS_OK;
+}
+
+int vs_profile_read(double* stage_ms, int64_t* launches) {
+  if (!stage_ms || !launches) return fail(VS_ERR_INVALID_ARG, "vs_profile_read: null pointer");
+  std::lock_guard<std::mutex> lock(g_prof_mu);
+  for (int s = 0; s < VS_NUM_STAGES; ++s) { stage_ms[s] = 0.0; launches[s] = 0; }
+  int rc = VS_OK;
+  for (const ProfRec& r : g_prof) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e != hipSuccess) rc = fail(VS_ERR_DEVICE, "vs_profile_read: %s", hipGetErrorString(e));
+    else if (r.stage >= 0 && r.stage < VS_NUM_STAGES) { stage_ms[r.stage] += ms; ++launches[r.stage]; }
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+  return rc;
+}
 const char* vs_version(void) { return "vs 0.1 (gfx950)"; }
 
 int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
@@ -134,7 +187,7 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   char* base = static_cast<char*>(sc.p);
   float* mat = reinterpret_cast<float*>(base + o_mat);
   u64* keys = reinterpret_cast<u64*>(base + o_keys);
-  knn_keys(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, st);
+  knn_keys(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, st, VS_STAGE_FLAT_DIST, VS_STAGE_FLAT_SELECT);
   launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
   HIP_TRY(hipGetLastError());
   return VS_OK;
@@ -274,7 +327,8 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
 // coarse quantizer: keys [nq, npr] of the npr best lists per query
 static int coarse_keys(const vs_ivfpq* ix, const float* q, int64_t nq, int npr, float* mat,
                        int64_t rows, int64_t cols, u64* ckeys, hipStream_t st) {
-  knn_keys(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys, st);
+  knn_keys(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys, st,
+           VS_STAGE_COARSE_DIST, VS_STAGE_COARSE_SELECT);
   return VS_OK;
 }
 
@@ -335,10 +389,16 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
 
   coarse_keys(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, st);
   launch_keys_to_probes(ckeys, nq * npr, g.metric, probes, cdist, st);
-  if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
-                        ix->list_off, ix->codes, k, partial, st) != 0)
-    return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
-  launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  {
+    StageTimer t(VS_STAGE_SCAN, st);
+    if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
+                          ix->list_off, ix->codes, k, partial, st) != 0)
+      return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
+  }
+  {
+    StageTimer t(VS_STAGE_MERGE, st);
+    launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  }
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
