@@ -59,12 +59,13 @@ __device__ __forceinline__ void wave_lds_sync() {
 // TOT slots are sorted with a bitonic network and the reservoir is emptied.
 // TOT is a power of two >= k + 64.
 struct WaveSelect {
-  volatile u64* s;  // this wavefront's TOT slots
-  int tot, k, cnt;  // cnt: reservoir fill (wave-uniform)
-  u64 thresh;       // wave-uniform
+  volatile u64* s;       // this wavefront's TOT slots
+  volatile u64* shared;  // optional: a bound shared by the wavefronts of a workgroup (LDS), or null
+  int tot, k, cnt;       // cnt: reservoir fill (wave-uniform)
+  u64 thresh;            // k-th best key this wavefront holds (wave-uniform)
 
-  __device__ __forceinline__ void init(u64* slots, int tot_, int k_) {
-    s = slots; tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
+  __device__ __forceinline__ void init(u64* slots, int tot_, int k_, u64* shared_ = nullptr) {
+    s = slots; shared = shared_; tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
     for (int i = lane_id(); i < tot; i += VS_WAVE) s[i] = KEY_EMPTY;
     wave_lds_sync();
   }
@@ -92,11 +93,19 @@ struct WaveSelect {
     sort_all();
     cnt = 0;
     thresh = s[k - 1];
+    // The k-th best key of ANY subset bounds the k-th best of the whole: publish it so
+    // that sibling wavefronts reject candidates that cannot make the workgroup's top k.
+    if (shared && lane_id() == 0 && thresh != KEY_EMPTY)
+      atomicMin(const_cast<u64*>(shared), thresh);
   }
 
-  // Every lane of the wavefront must call this together.
-  __device__ __forceinline__ void push(bool valid, u64 key) {
-    bool pass = valid && key < thresh;
+  // Every lane of the wavefront must call this together.  use_shared: also
+  // reject against the workgroup bound.  It must be false when re-inserting
+  // keys that other wavefronts already hold (one of them IS the bound).
+  __device__ __forceinline__ void push(bool valid, u64 key, bool use_shared = false) {
+    u64 th = thresh;
+    if (use_shared) { const u64 sh = *shared; th = sh < th ? sh : th; }
+    bool pass = valid && key < th;
     u64 mask = __ballot(pass);
     if (mask == 0) return;
     int pos = k + cnt + __popcll(mask & ((1ull << lane_id()) - 1ull));

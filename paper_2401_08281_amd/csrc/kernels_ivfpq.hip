@@ -1,6 +1,8 @@
 // IVF-PQ kernels for gfx950: residual PQ encoding, list re-layout, the fused
 // look-up-table build + ADC scan + wavefront k-selection, and the merge across
 // probe splits.
+#include <algorithm>
+
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -280,6 +282,150 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// Register-resident-codebook variant for 8-bit codes (K = 256) and shapes known
+// at compile time.  Lane j of the workgroup owns codeword j of EVERY
+// sub-quantizer: M * DSUB floats in registers, loaded once per workgroup.  The
+// workgroups are persistent: each walks over (query, probe split) items, so
+// the codebook is read from memory once per workgroup, not once per list.
+// Building a table then costs, per lane, M * DSUB (sub, fma) pairs against the
+// residual, which every lane reads from LDS as broadcasts, and M conflict-free
+// LDS stores.  The first 256 codes of a list are requested from memory before
+// the table is built, so their latency hides under the arithmetic.
+// ---------------------------------------------------------------------------
+template <int M>
+struct CodeWords {           // one PQ code of M bytes held in registers
+  static constexpr int W = M / 4;
+  u32 w[W];
+  __device__ __forceinline__ void load(const uint8_t* __restrict__ p) {
+    if constexpr (M % 16 == 0) {
+#pragma unroll
+      for (int i = 0; i < M / 16; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+      }
+    } else if constexpr (M % 8 == 0) {
+#pragma unroll
+      for (int i = 0; i < M / 8; ++i) {
+        const uint2 v = reinterpret_cast<const uint2*>(p)[i];
+        w[2 * i] = v.x; w[2 * i + 1] = v.y;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < W; ++i) w[i] = reinterpret_cast<const u32*>(p)[i];
+    }
+  }
+  __device__ __forceinline__ float adc(const float* __restrict__ lut, float dist) const {
+#pragma unroll
+    for (int i = 0; i < W; ++i) dist = adc_bytes<8>(lut, w[i], 4 * i, dist);
+    return dist;
+  }
+};
+
+template <int M, int DSUB>
+__global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
+    const float* __restrict__ q, int metric, const float* __restrict__ centroids,
+    const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
+    const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int k, int tot,
+    u64* __restrict__ partial) {
+  constexpr int K = 256, D = M * DSUB;
+  static_assert(D <= 256, "one lane per dimension writes the residual");
+  static_assert(M % 4 == 0, "codes are read as 32-bit words");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
+  u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
+  float* lut = reinterpret_cast<float*>(bound + 2);             // M * K
+  float* rs = lut + M * K;                                      // D
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+
+  float T[D];  // codeword `tid` of every sub-quantizer
+#pragma unroll
+  for (int m = 0; m < M; ++m)
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) T[m * DSUB + u] = codebooks[((int64_t)m * K + tid) * DSUB + u];
+
+  for (int64_t item = blockIdx.x; item < nitems; item += gridDim.x) {
+    const int64_t qi = item / nsplit;
+    const int split = (int)(item % nsplit);
+    const float* __restrict__ qv = q + qi * D;
+    const int p_begin = split * ppb;
+    const int p_end = min(nprobe, p_begin + ppb);
+
+    WaveSelect ws;
+    ws.init(slots + wave * tot, tot, k, bound);
+    if (tid == 0) *bound = KEY_EMPTY;
+
+    if (metric == 1) {  // inner product: one table per query
+      if (tid < D) rs[tid] = qv[tid];
+      __syncthreads();
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        float acc = 0.f;
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(rs[m * DSUB + u], T[m * DSUB + u], acc);
+        lut[m * K + tid] = acc;
+      }
+    }
+    __syncthreads();   // bound, and the IP table, are visible
+
+    for (int p = p_begin; p < p_end; ++p) {
+      const int l = probes[qi * nprobe + p];
+      if (l < 0) continue;
+      const int64_t begin = list_off[l], end = list_off[l + 1];
+      if (begin == end) continue;  // uniform over the workgroup
+      // request this lane's first code now; it is consumed after the table is built
+      CodeWords<M> cw;
+      int64_t i = begin + tid;
+      bool valid = i < end;
+      if (valid) cw.load(codes + i * M);
+      float bias = 0.f;
+      if (metric == 0) {
+        if (tid < D) rs[tid] = qv[tid] - centroids[(int64_t)l * D + tid];
+        __syncthreads();   // residual visible; every wavefront is done with the previous table
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+          float acc = 0.f;
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u) {
+            const float diff = rs[m * DSUB + u] - T[m * DSUB + u];
+            acc = __builtin_fmaf(diff, diff, acc);
+          }
+          lut[m * K + tid] = acc;
+        }
+        __syncthreads();   // table visible
+      } else {
+        bias = cdist[qi * nprobe + p];
+      }
+      for (;;) {
+        const float dist = valid ? cw.adc(lut, bias) : 0.f;
+        ws.push(valid, make_key(dist, (u32)i, metric), true);
+        i += 256;
+        if (i - tid >= end) break;           // uniform: i - tid is the chunk base
+        valid = i < end;
+        if (valid) cw.load(codes + i * M);
+      }
+    }
+    ws.finish();
+    __syncthreads();
+    if (wave == 0) {
+      for (int w = 1; w < 4; ++w) {
+        const volatile u64* other = slots + w * tot;
+        for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
+          const int j = j0 + lane;
+          const u64 key = j < k ? other[j] : KEY_EMPTY;
+          ws.push(j < k && key != KEY_EMPTY, key, false);
+        }
+      }
+      ws.finish();
+      u64* out = partial + item * k;
+      for (int j = lane; j < k; j += VS_WAVE) out[j] = ws.s[j];
+    }
+    __syncthreads();   // wavefront 0 has read the other slots; next item may reset them
+  }
+}
+
 // One wavefront per query: k best of the nsplit partial lists, then
 // (value, stored id).  Storage position -> id goes through the ids array
 // (Sec. 8.1: IVF indexes store the 64-bit id next to each code).
@@ -368,6 +514,26 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
                      nlist, sizes);
 }
 
+template <int M, int DSUB>
+static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                            const float* codebooks, const int32_t* probes, const float* cdist,
+                            int nprobe, int ppb, int nsplit, const int64_t* list_off,
+                            const uint8_t* codes, int k, int tot, u64* partial, hipStream_t st) {
+  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)M * 256 * sizeof(float) +
+                       (size_t)M * DSUB * sizeof(float);
+  auto kern = &ivfpq_scan_reg_kernel<M, DSUB>;
+  if (shmem > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  const int64_t nitems = nq * nsplit;
+  // persistent workgroups: a few per CU (256 CUs), each walks over many items
+  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(4, (160 * 1024) / (int64_t)shmem));
+  const int64_t grid = std::min<int64_t>(nitems, 256 * per_cu);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, g.metric, centroids,
+                     codebooks, probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, k, tot,
+                     partial);
+}
+
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
@@ -377,7 +543,19 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)g.d * sizeof(float);
-  if (shmem > 160 * 1024) return -1;
+  if (shmem + 64 > 160 * 1024) return -1;
+#define REG(MM, DS)                                                                              \
+  if (g.nbits == 8 && g.M == MM && g.dsub == DS) {                                               \
+    launch_scan_reg<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit,  \
+                            list_off, codes, k, tot, partial, st);                               \
+    return 0;                                                                                    \
+  }
+  REG(16, 8)   // PQ16x8 on d = 128
+  REG(32, 3)   // PQ32x8 on d = 96
+  REG(8, 4)    // PQ8x8 on d = 32
+  REG(8, 8)    // PQ8x8 on d = 64
+  REG(16, 4)   // PQ16x8 on d = 64
+#undef REG
   const dim3 grid((unsigned)(nq * nsplit)), block(256);
   if (g.nbits == 8) {
     if (shmem > 48 * 1024)
