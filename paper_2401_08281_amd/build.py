@@ -28,13 +28,14 @@ def is_stale():
     return any(os.path.getmtime(p) > t for p in deps)
 
 
-def build_lib(verbose=False, jobs=4):
-    """Compiles every translation unit and links libvs.so.  Always rebuilds."""
+def build_lib(verbose=False, jobs=4, extra_flags=(), out=None, tag=""):
+    """Compiles every translation unit and links libvs.so.  Always rebuilds.
+    extra_flags / out / tag produce a differently-flagged variant next to it."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs, procs = [], []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(CSRC, src.replace(".hip", tag + ".o"))
+        cmd = [hipcc] + FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
@@ -42,11 +43,12 @@ def build_lib(verbose=False, jobs=4):
         if len(procs) >= jobs:
             _drain(procs)
     _drain(procs)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    target = out or LIB
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", target] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return target
 
 
 def _drain(procs):

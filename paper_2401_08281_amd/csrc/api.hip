@@ -392,7 +392,7 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   {
     StageTimer t(VS_STAGE_SCAN, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
-                          ix->list_off, ix->codes, k, partial, st) != 0)
+                          ix->list_off, ix->codes, ix->ntotal, k, partial, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
   }
   {

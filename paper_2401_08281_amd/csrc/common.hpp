@@ -47,6 +47,84 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- cross-lane exchange and register-resident bitonic sort ------------------
+// lane i receives the value held by lane i ^ X.  X = 1, 2, 4, 8 stay inside a
+// row of 16 lanes and use DPP modifiers (no LDS traffic); 16 and 32 cross rows
+// and go through ds_bpermute.
+template <int X>
+__device__ __forceinline__ u32 lane_xor_u32(u32 v) {
+  const int s = (int)v;
+  if constexpr (X == 1) {
+    return (u32)__builtin_amdgcn_update_dpp(0, s, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+  } else if constexpr (X == 2) {
+    return (u32)__builtin_amdgcn_update_dpp(0, s, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+  } else if constexpr (X == 4) {
+    // lanes with bit 2 clear (banks 0, 2 of each row) read lane + 4, the others lane - 4
+    int r = __builtin_amdgcn_update_dpp(0, s, 0x104, 0xF, 0x5, false);      // row_shl:4
+    r = __builtin_amdgcn_update_dpp(r, s, 0x114, 0xF, 0xA, false);          // row_shr:4
+    return (u32)r;
+  } else if constexpr (X == 8) {
+    return (u32)__builtin_amdgcn_update_dpp(0, s, 0x128, 0xF, 0xF, false);  // row_ror:8
+  } else {
+    return (u32)__shfl_xor(s, X);
+  }
+}
+template <int X>
+__device__ __forceinline__ u64 lane_xor_u64(u64 v) {
+  const u32 lo = lane_xor_u32<X>((u32)v), hi = lane_xor_u32<X>((u32)(v >> 32));
+  return ((u64)hi << 32) | lo;
+}
+
+// One compare-exchange step of the bitonic network at lane distance X for
+// element index e (ascending block when (e & size) == 0).
+template <int X>
+__device__ __forceinline__ u64 bitonic_lane_step(u64 v, int e, int stride, int size) {
+  const u64 o = lane_xor_u64<X>(v);
+  const bool keep_min = ((e & stride) == 0) == ((e & size) == 0);
+  const u64 lo = v < o ? v : o, hi = v < o ? o : v;
+  return keep_min ? lo : hi;
+}
+
+// Sorts the 64 * R keys held by one wavefront, ascending in element order
+// e = lane * R + r.  Strides below R are register-to-register; the rest cross lanes.
+template <int R>
+__device__ __forceinline__ void wave_sort_regs(u64 (&v)[R]) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int size = 2; size <= 64 * R; size <<= 1) {
+#pragma unroll
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      if (stride >= R) {
+        const int X = stride / R;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const int e = lane * R + r;
+          switch (X) {
+            case 1: v[r] = bitonic_lane_step<1>(v[r], e, stride, size); break;
+            case 2: v[r] = bitonic_lane_step<2>(v[r], e, stride, size); break;
+            case 4: v[r] = bitonic_lane_step<4>(v[r], e, stride, size); break;
+            case 8: v[r] = bitonic_lane_step<8>(v[r], e, stride, size); break;
+            case 16: v[r] = bitonic_lane_step<16>(v[r], e, stride, size); break;
+            default: v[r] = bitonic_lane_step<32>(v[r], e, stride, size); break;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          if ((r & stride) == 0) {
+            const int e = lane * R + r;
+            const bool up = (e & size) == 0;
+            const u64 a = v[r], b = v[r | stride];
+            const bool sw = (a > b) == up;
+            v[r] = sw ? b : a;
+            v[r | stride] = sw ? a : b;
+          }
+        }
+      }
+    }
+  }
+}
+
 // ---- wavefront-level k-selection ------------------------------------------
 // One wavefront keeps the k smallest keys of a stream (App. A.4: k-selection
 // is the critical GPU stage; Sec. 3.2: for larger k use an unordered reservoir
@@ -55,23 +133,30 @@ __device__ __forceinline__ void wave_lds_sync() {
 // ascending after every trim; slots [k, TOT) are the reservoir.  A candidate
 // enters the reservoir only if it beats the current k-th best (`thresh`), so
 // once the threshold has tightened almost every candidate costs one compare.
-// When the reservoir cannot take another full wavefront of candidates, all
-// TOT slots are sorted with a bitonic network and the reservoir is emptied.
-// TOT is a power of two >= k + 64.
+// When the reservoir cannot take another full wavefront of candidates, the
+// live slots are sorted and the reservoir is emptied.  TOT is a power of two
+// >= k + 64.  R > 0: TOT == 64 * R and the sort runs in registers (R keys per
+// lane, DPP exchanges); R == 0: any TOT, bitonic network through LDS.
+template <int R>
 struct WaveSelect {
   volatile u64* s;       // this wavefront's TOT slots
   volatile u64* shared;  // optional: a bound shared by the wavefronts of a workgroup (LDS), or null
   int tot, k, cnt;       // cnt: reservoir fill (wave-uniform)
   u64 thresh;            // k-th best key this wavefront holds (wave-uniform)
+#ifdef VS_SCAN_TIMING
+  unsigned long long trim_cycles = 0;
+#endif
 
   __device__ __forceinline__ void init(u64* slots, int tot_, int k_, u64* shared_ = nullptr) {
     s = slots; shared = shared_; tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
-    for (int i = lane_id(); i < tot; i += VS_WAVE) s[i] = KEY_EMPTY;
+    for (int i = lane_id(); i < k; i += VS_WAVE) s[i] = KEY_EMPTY;
     wave_lds_sync();
   }
 
-  __device__ __forceinline__ void sort_all() {
+  __device__ __forceinline__ void sort_lds() {
     const int lane = lane_id();
+    for (int i = k + cnt + lane; i < tot; i += VS_WAVE) s[i] = KEY_EMPTY;
+    wave_lds_sync();
     for (int size = 2; size <= tot; size <<= 1) {
       for (int stride = size >> 1; stride > 0; stride >>= 1) {
         for (int i = lane; i < (tot >> 1); i += VS_WAVE) {
@@ -86,22 +171,44 @@ struct WaveSelect {
     }
   }
 
-  // Sorts everything, keeps the best k, empties the reservoir.
-  __device__ __forceinline__ void trim() {
-    for (int i = k + cnt + lane_id(); i < tot; i += VS_WAVE) s[i] = KEY_EMPTY;
+  __device__ __forceinline__ void sort_regs() {
+    // live slots are [0, k + cnt); the rest count as empty
+    const int lane = lane_id(), live = k + cnt;
+    wave_lds_sync();   // reservoir writes of this wavefront are visible to all its lanes
+    u64 v[R > 0 ? R : 1];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int e = lane * R + r;
+      v[r] = e < live ? s[e] : KEY_EMPTY;
+    }
+    wave_sort_regs<(R > 0 ? R : 1)>(v);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int e = lane * R + r;
+      if (e < k) s[e] = v[r];
+    }
     wave_lds_sync();
-    sort_all();
+  }
+
+  // Sorts the live slots, keeps the best k, empties the reservoir.
+  __device__ __forceinline__ void trim() {
+#ifdef VS_SCAN_TIMING
+    const unsigned long long t0_ = clock64();
+#endif
+    if constexpr (R > 0) sort_regs(); else sort_lds();
     cnt = 0;
     thresh = s[k - 1];
     // The k-th best key of ANY subset bounds the k-th best of the whole: publish it so
     // that sibling wavefronts reject candidates that cannot make the workgroup's top k.
     if (shared && lane_id() == 0 && thresh != KEY_EMPTY)
       atomicMin(const_cast<u64*>(shared), thresh);
+#ifdef VS_SCAN_TIMING
+    trim_cycles += clock64() - t0_;
+#endif
   }
 
   // Every lane of the wavefront must call this together.  use_shared: also
-  // reject against the workgroup bound.  It must be false when re-inserting
-  // keys that other wavefronts already hold (one of them IS the bound).
+  // reject against the workgroup bound.
   __device__ __forceinline__ void push(bool valid, u64 key, bool use_shared = false) {
     u64 th = thresh;
     if (use_shared) { const u64 sh = *shared; th = sh < th ? sh : th; }
@@ -116,14 +223,54 @@ struct WaveSelect {
 
   // After finish(), slots [0, k) hold the k best keys in ascending order.
   __device__ __forceinline__ void finish() {
+    if (cnt > 0) trim();
     wave_lds_sync();
-    trim();
   }
 };
 
-// Total slots a wavefront needs for a given k.
+// Total slots a wavefront needs for a given k, and the register-sort width
+// (keys per lane) that goes with it: 0 = sort through LDS.
 static inline int select_slots_for_k(int k) {
   int tot = 128;
   while (tot < k + 64) tot <<= 1;
   return tot;
+}
+static inline int select_regs_for_slots(int tot) { return tot <= 256 ? tot / 64 : 0; }
+
+// ---- merge of sorted key lists by ranking -----------------------------------
+// `nl` ascending lists of k keys each (padded with KEY_EMPTY) sit at
+// base + w * stride.  Keys are unique, so the number of keys smaller than x over
+// all lists is x's position in the merged order; every key whose rank is below
+// k goes straight to out[rank].  All lanes of the workgroup take part; no
+// sorting.  out must not alias the lists.
+__device__ __forceinline__ int count_less(const u64* __restrict__ L, int k, u64 x) {
+  if (k <= 16) {
+    int c = 0;
+    for (int j = 0; j < k; ++j) c += L[j] < x ? 1 : 0;
+    return c;
+  }
+  int lo = 0, hi = k;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (L[mid] < x) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// Call after a workgroup barrier (the lists are read as ordinary, stable memory).
+__device__ __forceinline__ void block_rank_merge(const u64* __restrict__ base, int stride, int nl,
+                                                 int k, u64* __restrict__ out) {
+  const int nthreads = blockDim.x;
+  int total = 0;    // number of real keys over all lists
+  for (int w = 0; w < nl; ++w) total += count_less(base + w * stride, k, KEY_EMPTY);
+  for (int c = threadIdx.x; c < nl * k; c += nthreads) {
+    const int w = c / k, j = c - w * k;
+    const u64 x = base[w * stride + j];
+    if (x == KEY_EMPTY) continue;
+    int rank = j;
+    for (int w2 = 0; w2 < nl; ++w2)
+      if (w2 != w) rank += count_less(base + w2 * stride, k, x);
+    if (rank < k) out[rank] = x;
+  }
+  for (int r = total + threadIdx.x; r < k; r += nthreads) out[r] = KEY_EMPTY;
 }

@@ -48,6 +48,6 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      int k, u64* partial, hipStream_t st);
+                      int64_t ntotal, int k, u64* partial, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);

@@ -175,7 +175,7 @@ __device__ __forceinline__ float adc_bytes(const float* __restrict__ lut, u32 wo
   return dist;
 }
 
-template <int NBITS>
+template <int NBITS, int R>
 __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
     const float* __restrict__ q, int d, int metric, int M, int dsub,
     const float* __restrict__ centroids, const float* __restrict__ codebooks,
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   const int p_begin = split * ppb;
   const int p_end = min(nprobe, p_begin + ppb);
 
-  WaveSelect ws;
+  WaveSelect<R> ws;
   ws.init(slots + wave * tot, tot, k);
 
   if (metric == 1) {  // per-query tables
@@ -267,19 +267,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   }
   ws.finish();
   __syncthreads();
-  if (wave == 0) {
-    for (int w = 1; w < 4; ++w) {
-      const volatile u64* other = slots + w * tot;
-      for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
-        const int j = j0 + lane;
-        const u64 key = j < k ? other[j] : KEY_EMPTY;
-        ws.push(j < k && key != KEY_EMPTY, key);
-      }
-    }
-    ws.finish();
-    u64* out = partial + ((int64_t)qi * nsplit + split) * k;
-    for (int j = lane; j < k; j += VS_WAVE) out[j] = ws.s[j];
-  }
+  block_rank_merge(slots, tot, 4, k, partial + ((int64_t)qi * nsplit + split) * k);
 }
 
 // ---------------------------------------------------------------------------
@@ -322,113 +310,179 @@ struct CodeWords {           // one PQ code of M bytes held in registers
   }
 };
 
-template <int M, int DSUB>
+#ifdef VS_SCAN_TIMING
+// debug builds only: cycles spent per phase, summed over wavefront 0 of every workgroup
+__device__ unsigned long long g_scan_cycles[8];
+#define TICK(slot)                                                        \
+  do {                                                                    \
+    if (tid == 0) {                                                       \
+      const unsigned long long now_ = clock64();                     \
+      tacc[slot] += now_ - tprev;                                         \
+      tprev = now_;                                                       \
+    }                                                                     \
+  } while (0)
+#else
+#define TICK(slot) do {} while (0)
+#endif
+
+template <int M, int DSUB, int METRIC, int R>
 __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
-    const float* __restrict__ q, int metric, const float* __restrict__ centroids,
+    const float* __restrict__ q, const float* __restrict__ centroids,
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
-    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int k, int tot,
-    u64* __restrict__ partial) {
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int64_t ntotal,
+    int k, int tot, u64* __restrict__ partial) {
   constexpr int K = 256, D = M * DSUB;
-  static_assert(D <= 256, "one lane per dimension writes the residual");
-  static_assert(M % 4 == 0, "codes are read as 32-bit words");
+  constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
+  static_assert(256 % M == 0 && M % 4 == 0, "M must divide 256 and codes are read as 32-bit words");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
   u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
-  float* lut = reinterpret_cast<float*>(bound + 2);             // M * K
-  float* rs = lut + M * K;                                      // D
+  float* lut0 = reinterpret_cast<float*>(bound + 2);            // 2 x M * K (double buffer)
+  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + 2 * M * K);  // ppb
+  int64_t* s_end = s_begin + ppb;                               // ppb
+  int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int m_own = tid / TPM, jj = tid % TPM;
+  const int64_t last = ntotal > 0 ? ntotal - 1 : 0;             // clamp for speculative code loads
+#ifdef VS_SCAN_TIMING
+  unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long tprev = clock64();
+#endif
 
-  float T[D];  // codeword `tid` of every sub-quantizer
+  // Lane (m_own, jj) owns codewords jj, jj + TPM, ... of sub-quantizer m_own: M codewords
+  // of DSUB floats = D registers, loaded once per workgroup.
+  float T[M * DSUB];
 #pragma unroll
-  for (int m = 0; m < M; ++m)
+  for (int i = 0; i < M; ++i)
 #pragma unroll
-    for (int u = 0; u < DSUB; ++u) T[m * DSUB + u] = codebooks[((int64_t)m * K + tid) * DSUB + u];
+    for (int u = 0; u < DSUB; ++u)
+      T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jj + TPM * i) * DSUB + u];
 
   for (int64_t item = blockIdx.x; item < nitems; item += gridDim.x) {
     const int64_t qi = item / nsplit;
     const int split = (int)(item % nsplit);
-    const float* __restrict__ qv = q + qi * D;
     const int p_begin = split * ppb;
-    const int p_end = min(nprobe, p_begin + ppb);
+    const int np = ntotal > 0 ? min(nprobe, p_begin + ppb) - p_begin : 0;
+    float qm[DSUB];                                             // this lane's slice of the query
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) qm[u] = q[qi * D + m_own * DSUB + u];
 
-    WaveSelect ws;
+    WaveSelect<R> ws;
     ws.init(slots + wave * tot, tot, k, bound);
     if (tid == 0) *bound = KEY_EMPTY;
-
-    if (metric == 1) {  // inner product: one table per query
-      if (tid < D) rs[tid] = qv[tid];
-      __syncthreads();
+    // the item's probes and list extents, fetched in one parallel round
+    for (int p = tid; p < np; p += 256) {
+      const int l = probes[qi * nprobe + p_begin + p];
+      s_list[p] = l >= 0 ? l : 0;
+      s_begin[p] = l >= 0 ? list_off[l] : 0;
+      s_end[p] = l >= 0 ? list_off[l + 1] : 0;
+    }
+    if (METRIC == 1) {  // inner product: one table per query
 #pragma unroll
-      for (int m = 0; m < M; ++m) {
+      for (int i = 0; i < M; ++i) {
         float acc = 0.f;
 #pragma unroll
-        for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(rs[m * DSUB + u], T[m * DSUB + u], acc);
-        lut[m * K + tid] = acc;
+        for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qm[u], T[i * DSUB + u], acc);
+        lut0[m_own * K + jj + TPM * i] = acc;
       }
     }
-    __syncthreads();   // bound, and the IP table, are visible
+    __syncthreads();   // probes, bound and the IP table are visible
+    TICK(0);
 
-    for (int p = p_begin; p < p_end; ++p) {
-      const int l = probes[qi * nprobe + p];
-      if (l < 0) continue;
-      const int64_t begin = list_off[l], end = list_off[l + 1];
-      if (begin == end) continue;  // uniform over the workgroup
-      // request this lane's first code now; it is consumed after the table is built
-      CodeWords<M> cw;
-      int64_t i = begin + tid;
-      bool valid = i < end;
-      if (valid) cw.load(codes + i * M);
-      float bias = 0.f;
-      if (metric == 0) {
-        if (tid < D) rs[tid] = qv[tid] - centroids[(int64_t)l * D + tid];
-        __syncthreads();   // residual visible; every wavefront is done with the previous table
+    // Software pipeline over the item's lists (L2 metric): iteration p builds table p into
+    // lut[p & 1] from registers only (query slice, centroid slice, codewords), then -- after
+    // ONE barrier -- scans list p.  The first 256 codes and the centroid slice of list p + 1
+    // are requested at the top of iteration p, a full iteration ahead.  These requests are
+    // unconditional (indices clamped into range; lanes past a list's end are masked when
+    // they are consumed), so the number of loads in flight is the same on every path.
+    CodeWords<M> cw, cw_n;
+    int64_t i_cur = 0;
+    bool v_cur = false;
+    float cm[DSUB], cm_n[DSUB];
 #pragma unroll
-        for (int m = 0; m < M; ++m) {
+    for (int u = 0; u < DSUB; ++u) cm[u] = cm_n[u] = 0.f;
+    if (np > 0) {
+      i_cur = s_begin[0] + tid;
+      v_cur = i_cur < s_end[0];
+      cw.load(codes + min(i_cur, last) * M);
+      if (METRIC == 0) {
+        const int l0 = s_list[0];
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u) cm[u] = centroids[(int64_t)l0 * D + m_own * DSUB + u];
+      }
+    }
+    TICK(1);
+    for (int p = 0; p < np; ++p) {
+      float* __restrict__ lut = METRIC == 0 ? lut0 + (p & 1) * (M * K) : lut0;
+      const int64_t end = s_end[p];
+      // requests for the next iteration (the last iteration re-requests its own list)
+      const int pn = min(p + 1, np - 1);
+      const int64_t i_n = s_begin[pn] + tid;
+      const bool v_n = (p + 1 < np) && (i_n < s_end[pn]);
+      cw_n.load(codes + min(i_n, last) * M);
+      float bias = 0.f;
+      if (METRIC == 0) {
+        const int l1 = s_list[pn];
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u) cm_n[u] = centroids[(int64_t)l1 * D + m_own * DSUB + u];
+        float r[DSUB];
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u) r[u] = qm[u] - cm[u];
+#pragma unroll
+        for (int i = 0; i < M; ++i) {
           float acc = 0.f;
 #pragma unroll
           for (int u = 0; u < DSUB; ++u) {
-            const float diff = rs[m * DSUB + u] - T[m * DSUB + u];
+            const float diff = r[u] - T[i * DSUB + u];
             acc = __builtin_fmaf(diff, diff, acc);
           }
-          lut[m * K + tid] = acc;
+          lut[m_own * K + jj + TPM * i] = acc;
         }
-        __syncthreads();   // table visible
+        TICK(2);
+        __syncthreads();   // table p visible; scan p - 1 (on the other buffer) finished everywhere
+        TICK(3);
       } else {
-        bias = cdist[qi * nprobe + p];
+        bias = cdist[qi * nprobe + p_begin + p];
       }
+      // scan list p; the next chunk of a long list is requested before the current one is summed
+      CodeWords<M> cw2;
       for (;;) {
-        const float dist = valid ? cw.adc(lut, bias) : 0.f;
-        ws.push(valid, make_key(dist, (u32)i, metric), true);
-        i += 256;
-        if (i - tid >= end) break;           // uniform: i - tid is the chunk base
-        valid = i < end;
-        if (valid) cw.load(codes + i * M);
+        const int64_t i2 = i_cur + 256;
+        const bool more = i2 - tid < end;      // uniform: i2 - tid is the next chunk's base
+        const bool v2 = i2 < end;
+        if (more) cw2.load(codes + min(i2, last) * M);
+        const float dist = v_cur ? cw.adc(lut, bias) : 0.f;
+        ws.push(v_cur, make_key(dist, (u32)i_cur, METRIC), true);
+        if (!more) break;
+        cw = cw2; i_cur = i2; v_cur = v2;
       }
+      cw = cw_n; i_cur = i_n; v_cur = v_n;
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) cm[u] = cm_n[u];
+      TICK(4);
     }
     ws.finish();
     __syncthreads();
-    if (wave == 0) {
-      for (int w = 1; w < 4; ++w) {
-        const volatile u64* other = slots + w * tot;
-        for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
-          const int j = j0 + lane;
-          const u64 key = j < k ? other[j] : KEY_EMPTY;
-          ws.push(j < k && key != KEY_EMPTY, key, false);
-        }
-      }
-      ws.finish();
-      u64* out = partial + item * k;
-      for (int j = lane; j < k; j += VS_WAVE) out[j] = ws.s[j];
-    }
-    __syncthreads();   // wavefront 0 has read the other slots; next item may reset them
+    TICK(5);
+    block_rank_merge(slots, tot, 4, k, partial + item * k);
+    __syncthreads();   // the slots have been read; the next item may reset them
+    TICK(6);
+#ifdef VS_SCAN_TIMING
+    if (tid == 0) { tacc[7] += ws.trim_cycles; }
+#endif
   }
+#ifdef VS_SCAN_TIMING
+  if (tid == 0)
+    for (int t = 0; t < 8; ++t) atomicAdd(&g_scan_cycles[t], tacc[t]);
+#endif
 }
 
 // One wavefront per query: k best of the nsplit partial lists, then
 // (value, stored id).  Storage position -> id goes through the ids array
 // (Sec. 8.1: IVF indexes store the 64-bit id next to each code).
+template <int R>
 __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__ partial,
                                                          int nsplit, int k, int tot, int metric,
                                                          const int64_t* __restrict__ ids,
@@ -437,7 +491,7 @@ __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__
   extern __shared__ u64 mslots[];
   const int64_t qi = blockIdx.x;
   const int lane = lane_id();
-  WaveSelect ws;
+  WaveSelect<R> ws;
   ws.init(mslots, tot, k);
   const u64* __restrict__ src = partial + qi * (int64_t)nsplit * k;
   const int n = nsplit * k;
@@ -514,72 +568,108 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
                      nlist, sizes);
 }
 
-template <int M, int DSUB>
+template <int M, int DSUB, int METRIC, int R>
 static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
-                            const uint8_t* codes, int k, int tot, u64* partial, hipStream_t st) {
-  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)M * 256 * sizeof(float) +
-                       (size_t)M * DSUB * sizeof(float);
-  auto kern = &ivfpq_scan_reg_kernel<M, DSUB>;
+                            const uint8_t* codes, int64_t ntotal, int k, int tot, u64* partial,
+                            hipStream_t st) {
+  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)2 * M * 256 * sizeof(float) +
+                       (size_t)ppb * 20 + 16;
+  auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   const int64_t nitems = nq * nsplit;
-  // persistent workgroups: a few per CU (256 CUs), each walks over many items
-  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(4, (160 * 1024) / (int64_t)shmem));
-  const int64_t grid = std::min<int64_t>(nitems, 256 * per_cu);
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, g.metric, centroids,
-                     codebooks, probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, k, tot,
+  // persistent workgroups: as many as are resident at once on the 256 CUs, each walks over items
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, shmem) != hipSuccess || per_cu < 1)
+    per_cu = 1;
+  const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
+                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, ntotal, k, tot,
                      partial);
+}
+
+template <int M, int DSUB>
+static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
+                                const float* centroids, const float* codebooks,
+                                const int32_t* probes, const float* cdist, int nprobe, int ppb,
+                                int nsplit, const int64_t* list_off, const uint8_t* codes,
+                                int64_t ntotal, int k, int tot, u64* partial, hipStream_t st) {
+#define GO(MET, RR)                                                                               \
+  launch_scan_reg<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,   \
+                                    nsplit, list_off, codes, ntotal, k, tot, partial, st)
+  const int r = select_regs_for_slots(tot);
+  if (g.metric == 0) { if (r == 2) GO(0, 2); else if (r == 4) GO(0, 4); else GO(0, 0); }
+  else               { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
+#undef GO
+}
+
+template <int NBITS, int R>
+static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
+                                const float* centroids, const float* codebooks,
+                                const int32_t* probes, const float* cdist, int nprobe, int ppb,
+                                int nsplit, const int64_t* list_off, const uint8_t* codes, int k,
+                                int tot, size_t shmem, u64* partial, hipStream_t st) {
+  auto kern = &ivfpq_scan_kernel<NBITS, R>;
+  if (shmem > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, g.metric,
+                     g.M, g.dsub, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off,
+                     codes, g.code_size, k, tot, partial);
 }
 
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      int k, u64* partial, hipStream_t st) {
+                      int64_t ntotal, int k, u64* partial, hipStream_t st) {
   if (nq <= 0) return 0;
   const int ppb = (nprobe + nsplit - 1) / nsplit;
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)g.d * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
+  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + (size_t)ppb * 20 + 32;
 #define REG(MM, DS)                                                                              \
-  if (g.nbits == 8 && g.M == MM && g.dsub == DS) {                                               \
-    launch_scan_reg<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit,  \
-                            list_off, codes, k, tot, partial, st);                               \
+  if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
+    launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
+                                nsplit, list_off, codes, ntotal, k, tot, partial, st);           \
     return 0;                                                                                    \
   }
   REG(16, 8)   // PQ16x8 on d = 128
   REG(32, 3)   // PQ32x8 on d = 96
   REG(8, 4)    // PQ8x8 on d = 32
-  REG(8, 8)    // PQ8x8 on d = 64
-  REG(16, 4)   // PQ16x8 on d = 64
 #undef REG
-  const dim3 grid((unsigned)(nq * nsplit)), block(256);
-  if (g.nbits == 8) {
-    if (shmem > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ivfpq_scan_kernel<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    hipLaunchKernelGGL((ivfpq_scan_kernel<8>), grid, block, shmem, st, q, g.d, g.metric, g.M, g.dsub,
-                       centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off, codes,
-                       g.code_size, k, tot, partial);
-  } else {
-    if (shmem > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ivfpq_scan_kernel<4>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    hipLaunchKernelGGL((ivfpq_scan_kernel<4>), grid, block, shmem, st, q, g.d, g.metric, g.M, g.dsub,
-                       centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off, codes,
-                       g.code_size, k, tot, partial);
-  }
+#define GEN(NB, RR)                                                                              \
+  launch_scan_generic<NB, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
+                              list_off, codes, k, tot, shmem, partial, st)
+  const int r = select_regs_for_slots(tot);
+  if (g.nbits == 8) { if (r == 2) GEN(8, 2); else if (r == 4) GEN(8, 4); else GEN(8, 0); }
+  else              { if (r == 2) GEN(4, 2); else if (r == 4) GEN(4, 4); else GEN(4, 0); }
+#undef GEN
   return 0;
 }
+
+#ifdef VS_SCAN_TIMING
+extern "C" __attribute__((visibility("default"))) int vs_debug_scan_cycles(unsigned long long* out8) {
+  unsigned long long zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_scan_cycles), sizeof(zero)) != hipSuccess) return -1;
+  if (hipMemcpyToSymbol(HIP_SYMBOL(g_scan_cycles), zero, sizeof(zero)) != hipSuccess) return -1;
+  return 0;
+}
+#endif
 
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return;
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)tot * sizeof(u64);
-  hipLaunchKernelGGL(ivfpq_merge_kernel, dim3((unsigned)nq), dim3(64), shmem, st, partial, nsplit, k,
-                     tot, metric, ids, out_dist, out_ids);
+  const dim3 grid((unsigned)nq), block(64);
+  switch (select_regs_for_slots(tot)) {
+    case 2: hipLaunchKernelGGL((ivfpq_merge_kernel<2>), grid, block, shmem, st, partial, nsplit, k, tot, metric, ids, out_dist, out_ids); break;
+    case 4: hipLaunchKernelGGL((ivfpq_merge_kernel<4>), grid, block, shmem, st, partial, nsplit, k, tot, metric, ids, out_dist, out_ids); break;
+    default: hipLaunchKernelGGL((ivfpq_merge_kernel<0>), grid, block, shmem, st, partial, nsplit, k, tot, metric, ids, out_dist, out_ids); break;
+  }
 }

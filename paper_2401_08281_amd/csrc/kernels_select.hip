@@ -10,34 +10,26 @@ __global__ void fill_u64_kernel(u64* p, int64_t n, u64 v) {
 }
 
 // One workgroup (4 wavefronts) per row.  Each wavefront selects over a
-// quarter of the columns with its own WaveSelect; wavefront 0 then absorbs
-// the other three.  When the row continues an earlier chunk, the k-th best
-// key so far seeds every wavefront's threshold, so that nearly all columns
-// are rejected by a single compare.
+// quarter of the columns with its own WaveSelect; the four sorted results and
+// the row's previous best k (when the row continues an earlier chunk) are then
+// merged by ranking.  The previous k-th best key seeds every wavefront's
+// threshold, so that nearly all columns are rejected by a single compare.
+template <int R>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ mat, int64_t ld,
                                                          int64_t ncols, u32 col_base, int metric,
                                                          int k, int tot, u64* __restrict__ keys,
                                                          int first) {
-  extern __shared__ u64 slots[];  // 4 * tot
+  extern __shared__ u64 slots[];  // 5 * tot: four wavefronts, then the previous best k
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int64_t row = blockIdx.x;
   const float* __restrict__ m = mat + row * ld;
   u64* kr = keys + row * (int64_t)k;
+  u64* prev = slots + 4 * tot;
 
-  WaveSelect ws;
+  WaveSelect<R> ws;
   ws.init(slots + wave * tot, tot, k);
-  if (!first) {
-    ws.thresh = kr[k - 1];                      // may be KEY_EMPTY: then nothing is rejected
-    if (wave == 0) {                            // previous best k re-enter through wavefront 0
-      ws.thresh = KEY_EMPTY;
-      for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
-        const int j = j0 + lane;
-        const u64 key = j < k ? kr[j] : KEY_EMPTY;
-        ws.push(j < k && key != KEY_EMPTY, key);
-      }
-      ws.finish();                              // threshold = k-th best so far
-    }
-  }
+  for (int j = threadIdx.x; j < k; j += 256) prev[j] = first ? KEY_EMPTY : kr[j];
+  if (!first) ws.thresh = kr[k - 1];            // may be KEY_EMPTY: then nothing is rejected
   for (int64_t c0 = wave * VS_WAVE; c0 < ncols; c0 += 4 * VS_WAVE) {
     const int64_t c = c0 + lane;
     const bool valid = c < ncols;
@@ -46,18 +38,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   }
   ws.finish();
   __syncthreads();
-  if (wave == 0) {
-    for (int w = 1; w < 4; ++w) {
-      const volatile u64* other = slots + w * tot;
-      for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
-        const int j = j0 + lane;
-        const u64 key = j < k ? other[j] : KEY_EMPTY;
-        ws.push(j < k && key != KEY_EMPTY, key);
-      }
-    }
-    ws.finish();
-    for (int j = lane; j < k; j += VS_WAVE) kr[j] = ws.s[j];
-  }
+  block_rank_merge(slots, tot, 5, k, kr);
 }
 
 __global__ void keys_to_results_kernel(const u64* __restrict__ keys, int64_t n, int metric,
@@ -101,9 +82,22 @@ void launch_row_select(const float* mat, int64_t ld, int64_t nrows, int64_t ncol
                        int metric, int k, u64* keys, bool first, hipStream_t st) {
   if (nrows <= 0) return;
   const int tot = select_slots_for_k(k);
-  const size_t shmem = (size_t)4 * tot * sizeof(u64);
-  hipLaunchKernelGGL(row_select_kernel, dim3((unsigned)nrows), dim3(256), shmem, st, mat, ld, ncols,
-                     col_base, metric, k, tot, keys, first ? 1 : 0);
+  const size_t shmem = (size_t)5 * tot * sizeof(u64);
+  const dim3 grid((unsigned)nrows), block(256);
+#define LAUNCH(RR)                                                                                 \
+  do {                                                                                             \
+    if (shmem > 48 * 1024)                                                                         \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_select_kernel<RR>),             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);           \
+    hipLaunchKernelGGL((row_select_kernel<RR>), grid, block, shmem, st, mat, ld, ncols, col_base,  \
+                       metric, k, tot, keys, first ? 1 : 0);                                       \
+  } while (0)
+  switch (select_regs_for_slots(tot)) {
+    case 2: LAUNCH(2); break;
+    case 4: LAUNCH(4); break;
+    default: LAUNCH(0); break;
+  }
+#undef LAUNCH
 }
 
 void launch_keys_to_results(const u64* keys, int64_t n, int metric, float* out_dist,
