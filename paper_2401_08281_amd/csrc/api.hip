@@ -86,13 +86,17 @@ struct StageTimer {
 // selection kernel that reads it back.
 constexpr size_t kTileBytes = 128ull << 20;
 
-// k best rows of B for every row of A, as keys [na, k].  mat: scratch for tile_rows x tile_cols.
-void knn_keys(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric, int k,
-              float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, hipStream_t st,
-              int stage_dist, int stage_select) {
-  launch_fill_u64(keys, na * k, 0xFFFFFFFFFFFFFFFFull, st);
+// k best rows of B for every row of A, written to `out` best first.  mat: scratch for
+// tile_rows x tile_cols; keys: scratch [na, k], needed only when B spans several column tiles.
+void knn_select(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric, int k,
+                float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, const SelectOut& out,
+                hipStream_t st, int stage_dist, int stage_select) {
   for (int64_t a0 = 0; a0 < na; a0 += tile_rows) {
     const int64_t ra = std::min(tile_rows, na - a0);
+    SelectOut o;
+    o.val = out.val ? out.val + a0 * k : nullptr;
+    o.id64 = out.id64 ? out.id64 + a0 * k : nullptr;
+    o.idx32 = out.idx32 ? out.idx32 + a0 * k : nullptr;
     for (int64_t b0 = 0; b0 < nb; b0 += tile_cols) {
       const int64_t cb = std::min(tile_cols, nb - b0);
       {
@@ -101,7 +105,8 @@ void knn_keys(const float* A, int64_t na, const float* B, int64_t nb, int d, int
       }
       {
         StageTimer t(stage_select, st);
-        launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0, st);
+        launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0,
+                          b0 + cb >= nb, o, st);
       }
     }
   }
@@ -187,8 +192,16 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   char* base = static_cast<char*>(sc.p);
   float* mat = reinterpret_cast<float*>(base + o_mat);
   u64* keys = reinterpret_cast<u64*>(base + o_keys);
-  knn_keys(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, st, VS_STAGE_FLAT_DIST, VS_STAGE_FLAT_SELECT);
-  launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
+  SelectOut out;
+  out.val = out_dist;
+  out.id64 = out_ids;
+  if (nb == 0) {   // nothing to select from: all slots empty
+    launch_fill_u64(keys, nq * k, 0xFFFFFFFFFFFFFFFFull, st);
+    launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
+  } else {
+    knn_select(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, out, st, VS_STAGE_FLAT_DIST,
+               VS_STAGE_FLAT_SELECT);
+  }
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
@@ -324,12 +337,15 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
   return VS_OK;
 }
 
-// coarse quantizer: keys [nq, npr] of the npr best lists per query
-static int coarse_keys(const vs_ivfpq* ix, const float* q, int64_t nq, int npr, float* mat,
-                       int64_t rows, int64_t cols, u64* ckeys, hipStream_t st) {
-  knn_keys(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys, st,
-           VS_STAGE_COARSE_DIST, VS_STAGE_COARSE_SELECT);
-  return VS_OK;
+// coarse quantizer: the npr best lists per query, best first, with their canon values
+static void coarse_select(const vs_ivfpq* ix, const float* q, int64_t nq, int npr, float* mat,
+                          int64_t rows, int64_t cols, u64* ckeys, int32_t* probes, float* cdist,
+                          hipStream_t st) {
+  SelectOut out;
+  out.val = cdist;
+  out.idx32 = probes;
+  knn_select(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys,
+             out, st, VS_STAGE_COARSE_DIST, VS_STAGE_COARSE_SELECT);
 }
 
 int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
@@ -349,8 +365,8 @@ int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t npro
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
   u64* ckeys = reinterpret_cast<u64*>(base + o_ck);
-  coarse_keys(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, st);
-  launch_keys_to_probes(ckeys, nq * npr, ix->g.metric, probes, coarse_dist, st);
+  coarse_select(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, probes,
+                coarse_dist, st);
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
@@ -387,15 +403,16 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   float* cdist = reinterpret_cast<float*>(base + o_cd);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
 
-  coarse_keys(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, st);
-  launch_keys_to_probes(ckeys, nq * npr, g.metric, probes, cdist, st);
+  coarse_select(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, probes,
+                cdist, st);
   {
     StageTimer t(VS_STAGE_SCAN, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
-                          ix->list_off, ix->codes, ix->ntotal, k, partial, st) != 0)
+                          ix->list_off, ix->codes, ix->ntotal, k, partial, ix->ids, out_dist,
+                          out_ids, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
   }
-  {
+  if (nsplit > 1) {
     StageTimer t(VS_STAGE_MERGE, st);
     launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
   }

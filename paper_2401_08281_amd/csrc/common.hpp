@@ -47,6 +47,16 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Workgroup barrier that orders LDS traffic only.  Unlike __syncthreads() it
+// does not wait for outstanding global loads or stores, so prefetches that
+// were issued before the barrier stay in flight across it.  Use it where the
+// data exchanged between wavefronts lives in LDS.
+__device__ __forceinline__ void block_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---- cross-lane exchange and register-resident bitonic sort ------------------
 // lane i receives the value held by lane i ^ X.  X = 1, 2, 4, 8 stay inside a
 // row of 16 lanes and use DPP modifiers (no LDS traffic); 16 and 32 cross rows
@@ -257,12 +267,30 @@ __device__ __forceinline__ int count_less(const u64* __restrict__ L, int k, u64 
   return lo;
 }
 
+// Where selected keys go: raw keys (to be merged again later) and / or final
+// results (value, 64-bit id through an optional id map, 32-bit index).  Null
+// members are skipped.  Empty slots become id -1 and value +inf (L2) / -inf (IP).
+struct KeySink {
+  u64* keys;
+  float* val;
+  int64_t* id64;
+  int32_t* idx32;
+  const int64_t* idmap;
+  int metric;
+  __device__ __forceinline__ void put(int64_t at, u64 key) const {
+    if (keys) keys[at] = key;
+    const bool empty = key == KEY_EMPTY;
+    if (val) val[at] = empty ? (metric ? -__builtin_inff() : __builtin_inff()) : key_value(key, metric);
+    if (id64) id64[at] = empty ? -1 : (idmap ? idmap[key_index(key)] : (int64_t)key_index(key));
+    if (idx32) idx32[at] = empty ? -1 : (int32_t)key_index(key);
+  }
+};
+
 // Call after a workgroup barrier (the lists are read as ordinary, stable memory).
+// Output slot of rank r is sink[at0 + r].
 __device__ __forceinline__ void block_rank_merge(const u64* __restrict__ base, int stride, int nl,
-                                                 int k, u64* __restrict__ out) {
+                                                 int k, const KeySink& sink, int64_t at0) {
   const int nthreads = blockDim.x;
-  int total = 0;    // number of real keys over all lists
-  for (int w = 0; w < nl; ++w) total += count_less(base + w * stride, k, KEY_EMPTY);
   for (int c = threadIdx.x; c < nl * k; c += nthreads) {
     const int w = c / k, j = c - w * k;
     const u64 x = base[w * stride + j];
@@ -270,7 +298,11 @@ __device__ __forceinline__ void block_rank_merge(const u64* __restrict__ base, i
     int rank = j;
     for (int w2 = 0; w2 < nl; ++w2)
       if (w2 != w) rank += count_less(base + w2 * stride, k, x);
-    if (rank < k) out[rank] = x;
+    if (rank < k) sink.put(at0 + rank, x);
   }
-  for (int r = total + threadIdx.x; r < k; r += nthreads) out[r] = KEY_EMPTY;
+  if (threadIdx.x < k) {   // pad the ranks that no real key fills
+    int total = 0;
+    for (int w = 0; w < nl; ++w) total += count_less(base + w * stride, k, KEY_EMPTY);
+    for (int r = total + threadIdx.x; r < k; r += nthreads) sink.put(at0 + r, KEY_EMPTY);
+  }
 }

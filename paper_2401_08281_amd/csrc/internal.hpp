@@ -16,9 +16,18 @@ void launch_canon_argbest(const float* A, int64_t na, const float* B, int64_t nb
 
 // ---- selection (kernels_select.hip) -----------------------------------------
 void launch_fill_u64(u64* p, int64_t n, u64 v, hipStream_t st);
-// keys[r][0..k) <- k best of (first ? {} : keys[r][0..k)) U {key(mat[r][c], col_base + c)}
+// Final outputs of a selection; any member may be null.
+struct SelectOut {
+  float* val = nullptr;       // [nrows, k] best values
+  int64_t* id64 = nullptr;    // [nrows, k] indices as int64
+  int32_t* idx32 = nullptr;   // [nrows, k] indices as int32
+};
+// keys[r][0..k) <- k best of (first ? {} : keys[r][0..k)) U {key(mat[r][c], col_base + c)}.
+// When `last`, the result goes to `out` instead (already ordered best first) and keys is
+// not written; keys may be null if first && last.
 void launch_row_select(const float* mat, int64_t ld, int64_t nrows, int64_t ncols, u32 col_base,
-                       int metric, int k, u64* keys, bool first, hipStream_t st);
+                       int metric, int k, u64* keys, bool first, bool last, const SelectOut& out,
+                       hipStream_t st);
 // keys -> (value, int64 id); idmap == NULL: id = index, else id = idmap[index]; empty -> (-1, +-inf)
 void launch_keys_to_results(const u64* keys, int64_t n, int metric, float* out_dist,
                             int64_t* out_ids, const int64_t* idmap, hipStream_t st);
@@ -44,10 +53,12 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
                             hipStream_t st);
 void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_t st);
-// partial[q][s][0..k): k best keys (value, storage position) of the probes handled by split s
+// nsplit > 1: partial[q][s][0..k) = k best keys (value, storage position) of the probes handled by
+// split s.  nsplit == 1: final results go straight to out_dist / out_ids (ids[position]).
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      int64_t ntotal, int k, u64* partial, hipStream_t st);
+                      int64_t ntotal, int k, u64* partial, const int64_t* ids, float* out_dist,
+                      int64_t* out_ids, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);

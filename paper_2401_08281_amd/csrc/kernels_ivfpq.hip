@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
     const float* __restrict__ centroids, const float* __restrict__ codebooks,
     const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb,
     int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int cs,
-    int k, int tot, u64* __restrict__ partial) {
+    int k, int tot, KeySink sink) {
   constexpr int K = 1 << NBITS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   }
   ws.finish();
   __syncthreads();
-  block_rank_merge(slots, tot, 4, k, partial + ((int64_t)qi * nsplit + split) * k);
+  block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
 }
 
 // ---------------------------------------------------------------------------
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int64_t ntotal,
-    int k, int tot, u64* __restrict__ partial) {
+    int k, int tot, KeySink sink) {
   constexpr int K = 256, D = M * DSUB;
   constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
   static_assert(256 % M == 0 && M % 4 == 0, "M must divide 256 and codes are read as 32-bit words");
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
         lut0[m_own * K + jj + TPM * i] = acc;
       }
     }
-    __syncthreads();   // probes, bound and the IP table are visible
+    block_sync_lds();   // probes, bound and the IP table are visible
     TICK(0);
 
     // Software pipeline over the item's lists (L2 metric): iteration p builds table p into
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
           lut[m_own * K + jj + TPM * i] = acc;
         }
         TICK(2);
-        __syncthreads();   // table p visible; scan p - 1 (on the other buffer) finished everywhere
+        block_sync_lds();   // table p visible; scan p - 1 (on the other buffer) finished everywhere
         TICK(3);
       } else {
         bias = cdist[qi * nprobe + p_begin + p];
@@ -464,10 +464,10 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       TICK(4);
     }
     ws.finish();
-    __syncthreads();
+    block_sync_lds();
     TICK(5);
-    block_rank_merge(slots, tot, 4, k, partial + item * k);
-    __syncthreads();   // the slots have been read; the next item may reset them
+    block_rank_merge(slots, tot, 4, k, sink, item * k);
+    block_sync_lds();   // the slots have been read; the next item may reset them
     TICK(6);
 #ifdef VS_SCAN_TIMING
     if (tid == 0) { tacc[7] += ws.trim_cycles; }
@@ -572,7 +572,7 @@ template <int M, int DSUB, int METRIC, int R>
 static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
-                            const uint8_t* codes, int64_t ntotal, int k, int tot, u64* partial,
+                            const uint8_t* codes, int64_t ntotal, int k, int tot, KeySink sink,
                             hipStream_t st) {
   const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)2 * M * 256 * sizeof(float) +
                        (size_t)ppb * 20 + 16;
@@ -588,7 +588,7 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
                      probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, ntotal, k, tot,
-                     partial);
+                     sink);
 }
 
 template <int M, int DSUB>
@@ -596,10 +596,10 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                int64_t ntotal, int k, int tot, u64* partial, hipStream_t st) {
+                                int64_t ntotal, int k, int tot, KeySink sink, hipStream_t st) {
 #define GO(MET, RR)                                                                               \
   launch_scan_reg<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,   \
-                                    nsplit, list_off, codes, ntotal, k, tot, partial, st)
+                                    nsplit, list_off, codes, ntotal, k, tot, sink, st)
   const int r = select_regs_for_slots(tot);
   if (g.metric == 0) { if (r == 2) GO(0, 2); else if (r == 4) GO(0, 4); else GO(0, 0); }
   else               { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
@@ -611,21 +611,27 @@ static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes, int k,
-                                int tot, size_t shmem, u64* partial, hipStream_t st) {
+                                int tot, size_t shmem, KeySink sink, hipStream_t st) {
   auto kern = &ivfpq_scan_kernel<NBITS, R>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, g.metric,
                      g.M, g.dsub, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off,
-                     codes, g.code_size, k, tot, partial);
+                     codes, g.code_size, k, tot, sink);
 }
 
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      int64_t ntotal, int k, u64* partial, hipStream_t st) {
+                      int64_t ntotal, int k, u64* partial, const int64_t* ids, float* out_dist,
+                      int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return 0;
+  KeySink sink;
+  sink.metric = g.metric;
+  sink.idx32 = nullptr;
+  if (nsplit == 1) { sink.keys = nullptr; sink.val = out_dist; sink.id64 = out_ids; sink.idmap = ids; }
+  else             { sink.keys = partial; sink.val = nullptr; sink.id64 = nullptr; sink.idmap = nullptr; }
   const int ppb = (nprobe + nsplit - 1) / nsplit;
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
@@ -635,7 +641,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                nsplit, list_off, codes, ntotal, k, tot, partial, st);           \
+                                nsplit, list_off, codes, ntotal, k, tot, sink, st);              \
     return 0;                                                                                    \
   }
   REG(16, 8)   // PQ16x8 on d = 128
@@ -644,7 +650,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #undef REG
 #define GEN(NB, RR)                                                                              \
   launch_scan_generic<NB, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
-                              list_off, codes, k, tot, shmem, partial, st)
+                              list_off, codes, k, tot, shmem, sink, st)
   const int r = select_regs_for_slots(tot);
   if (g.nbits == 8) { if (r == 2) GEN(8, 2); else if (r == 4) GEN(8, 4); else GEN(8, 0); }
   else              { if (r == 2) GEN(4, 2); else if (r == 4) GEN(4, 4); else GEN(4, 0); }

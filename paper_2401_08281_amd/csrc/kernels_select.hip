@@ -18,12 +18,12 @@ template <int R>
 __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict__ mat, int64_t ld,
                                                          int64_t ncols, u32 col_base, int metric,
                                                          int k, int tot, u64* __restrict__ keys,
-                                                         int first) {
+                                                         int first, int last, SelectOut out) {
   extern __shared__ u64 slots[];  // 5 * tot: four wavefronts, then the previous best k
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int64_t row = blockIdx.x;
   const float* __restrict__ m = mat + row * ld;
-  u64* kr = keys + row * (int64_t)k;
+  const u64* kr = first ? nullptr : keys + row * (int64_t)k;
   u64* prev = slots + 4 * tot;
 
   WaveSelect<R> ws;
@@ -38,7 +38,14 @@ __global__ __launch_bounds__(256) void row_select_kernel(const float* __restrict
   }
   ws.finish();
   __syncthreads();
-  block_rank_merge(slots, tot, 5, k, kr);
+  KeySink sink;
+  sink.keys = last ? nullptr : keys;
+  sink.val = last ? out.val : nullptr;
+  sink.id64 = last ? out.id64 : nullptr;
+  sink.idx32 = last ? out.idx32 : nullptr;
+  sink.idmap = nullptr;
+  sink.metric = metric;
+  block_rank_merge(slots, tot, 5, k, sink, row * (int64_t)k);
 }
 
 __global__ void keys_to_results_kernel(const u64* __restrict__ keys, int64_t n, int metric,
@@ -79,7 +86,8 @@ void launch_fill_u64(u64* p, int64_t n, u64 v, hipStream_t st) {
 }
 
 void launch_row_select(const float* mat, int64_t ld, int64_t nrows, int64_t ncols, u32 col_base,
-                       int metric, int k, u64* keys, bool first, hipStream_t st) {
+                       int metric, int k, u64* keys, bool first, bool last, const SelectOut& out,
+                       hipStream_t st) {
   if (nrows <= 0) return;
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)5 * tot * sizeof(u64);
@@ -90,7 +98,7 @@ void launch_row_select(const float* mat, int64_t ld, int64_t nrows, int64_t ncol
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_select_kernel<RR>),             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);           \
     hipLaunchKernelGGL((row_select_kernel<RR>), grid, block, shmem, st, mat, ld, ncols, col_base,  \
-                       metric, k, tot, keys, first ? 1 : 0);                                       \
+                       metric, k, tot, keys, first ? 1 : 0, last ? 1 : 0, out);                    \
   } while (0)
   switch (select_regs_for_slots(tot)) {
     case 2: LAUNCH(2); break;
