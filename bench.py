@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--nprobe", type=int, default=None)
     ap.add_argument("--nb", type=int, default=None, help="override database size (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
+                         "--pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every box here has one); "
@@ -55,6 +58,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     vs.lib()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     over = {}
     if args.nb:
@@ -107,10 +118,10 @@ def main():
     vs.vs_profile_enable(False)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     qps = nq / (ms_per_step * 1e-3)
-    stage_ms = {s: (v[0] / v[1] if v[1] else 0.0) for s, v in prof.items()}
-    log("per-launch ms: " + ", ".join("%s=%.3f" % (s, v) for s, v in stage_ms.items() if v))
+    stage_ms = {s: v[0] / args.steps for s, v in prof.items()}        # per step, all launches
+    log("per-step ms: " + ", ".join("%s=%.3f" % (s, v) for s, v in stage_ms.items() if v))
 
-    scan_ms = stage_ms["scan"]
+    scan_ms = prof["scan"][0] / max(prof["scan"][1], 1)               # per launch (one per step)
     algo_bytes = scanned * code_size
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
 
@@ -136,8 +147,8 @@ def main():
             "nprobe": nprobe, "k": k, "recall_k_at_k": round(float(hit_k), 4),
             "recall_1_at_k": round(float(hit_1), 4), "scanned_codes_per_query": scanned / nq,
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
-            "stage_ms_per_launch": {s: round(v, 4) for s, v in stage_ms.items() if v}},
-        "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_kernel", "achieved": achieved,
+            "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v}},
+        "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_reg_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
                      "kernel_ms": scan_ms, "pairs_per_launch": pairs},
@@ -223,7 +234,8 @@ def load_traffic(key):
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(key)
+            rec = json.load(f).get(key)
+            return rec["hbm_bytes_per_launch"] if rec else None
     except (OSError, ValueError):
         return None
 
