@@ -165,6 +165,23 @@ VS_API int vs_profile_enable(int on);
  * per stage into launches[VS_NUM_STAGES] (HOST pointer), then forgets them. */
 VS_API int vs_profile_read(double* stage_ms, int64_t* launches);
 
+/* ---- run-time options and counters ----------------------------------------- */
+
+/* "knn_path": how exact k-nearest-row problems (coarse quantizer, list
+ *   assignment, flat search) are evaluated.  0 (default): matrix-core shortlist
+ *   + exact re-rank where a kernel exists (d in {32, 64, 96, 128}, k <= 150),
+ *   canon distance tiles otherwise; 1: canon tiles only; 2: same as 0.
+ *   Both routes return identical results.
+ * "knn_eps_scale": multiplies the error bound used to prove a shortlist
+ *   sufficient (default 1; a negative value sends every row to the exact
+ *   fallback -- for tests).
+ * Options are process-wide. */
+VS_API int vs_set_option(const char* name, double value);
+/* counters[0] = rows evaluated through the matrix-core route, counters[1] = rows
+ * among them that needed the exact fallback, since the previous call (HOST
+ * pointer to 2 int64).  Synchronises the device. */
+VS_API int vs_counters_read(int64_t* counters);
+
 /* Message of the calling thread's most recent error ("" if none). */
 VS_API const char* vs_last_error(void);
 

@@ -24,5 +24,7 @@ from .binding import (  # noqa: F401
     vs_last_error,
     vs_profile_enable,
     vs_profile_read,
+    vs_set_option,
+    vs_counters_read,
     vs_version,
 )

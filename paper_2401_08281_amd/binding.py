@@ -60,6 +60,10 @@ def lib():
     L.vs_profile_enable.argtypes = [ctypes.c_int]
     L.vs_profile_read.restype = ctypes.c_int
     L.vs_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.vs_set_option.restype = ctypes.c_int
+    L.vs_set_option.argtypes = [ctypes.c_char_p, ctypes.c_double]
+    L.vs_counters_read.restype = ctypes.c_int
+    L.vs_counters_read.argtypes = [ctypes.POINTER(i64)]
     L.vs_last_error.restype = ctypes.c_char_p
     L.vs_version.restype = ctypes.c_char_p
     _lib = L
@@ -112,6 +116,17 @@ def vs_profile_read():
     n = (ctypes.c_int64 * len(STAGES))()
     _check(lib().vs_profile_read(ms, n))
     return {s: (float(ms[i]), int(n[i])) for i, s in enumerate(STAGES)}
+
+
+def vs_set_option(name, value):
+    _check(lib().vs_set_option(name.encode(), float(value)))
+
+
+def vs_counters_read():
+    """Returns (rows through the matrix-core route, rows that needed the exact fallback)."""
+    c = (ctypes.c_int64 * 2)()
+    _check(lib().vs_counters_read(c))
+    return int(c[0]), int(c[1])
 
 
 def vs_flat_search(x, q, k, metric=METRIC_L2, out_dist=None, out_ids=None):

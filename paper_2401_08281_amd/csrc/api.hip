@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -68,7 +69,7 @@ bool g_prof_on = false;
 // Brackets the launches made inside its scope with two events on the stream.
 struct StageTimer {
   int stage; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; bool on;
-  StageTimer(int stage_, hipStream_t st_) : stage(stage_), st(st_), on(g_prof_on) {
+  StageTimer(int stage_, hipStream_t st_) : stage(stage_), st(st_), on(g_prof_on && stage_ >= 0) {
     if (!on) return;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
     (void)hipEventRecord(a, st);
@@ -86,31 +87,10 @@ struct StageTimer {
 // selection kernel that reads it back.
 constexpr size_t kTileBytes = 128ull << 20;
 
-// k best rows of B for every row of A, written to `out` best first.  mat: scratch for
-// tile_rows x tile_cols; keys: scratch [na, k], needed only when B spans several column tiles.
-void knn_select(const float* A, int64_t na, const float* B, int64_t nb, int d, int metric, int k,
-                float* mat, int64_t tile_rows, int64_t tile_cols, u64* keys, const SelectOut& out,
-                hipStream_t st, int stage_dist, int stage_select) {
-  for (int64_t a0 = 0; a0 < na; a0 += tile_rows) {
-    const int64_t ra = std::min(tile_rows, na - a0);
-    SelectOut o;
-    o.val = out.val ? out.val + a0 * k : nullptr;
-    o.id64 = out.id64 ? out.id64 + a0 * k : nullptr;
-    o.idx32 = out.idx32 ? out.idx32 + a0 * k : nullptr;
-    for (int64_t b0 = 0; b0 < nb; b0 += tile_cols) {
-      const int64_t cb = std::min(tile_cols, nb - b0);
-      {
-        StageTimer t(stage_dist, st);
-        launch_canon_matrix(A + a0 * d, ra, B + b0 * d, cb, d, metric, mat, tile_cols, st);
-      }
-      {
-        StageTimer t(stage_select, st);
-        launch_row_select(mat, tile_cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0,
-                          b0 + cb >= nb, o, st);
-      }
-    }
-  }
-}
+// ---- run-time options (vs_set_option) -----------------------------------------
+std::atomic<int> g_knn_path{0};          // 0 auto, 1 canon tiles only, 2 MFMA shortlist whenever supported
+std::atomic<float> g_knn_eps_scale{1.f}; // multiplies the error bound of the MFMA shortlist test
+std::atomic<long long> g_knn_mfma_rows{0};
 
 void tile_shape(int64_t na, int64_t nb, int64_t* rows, int64_t* cols) {
   int64_t c = std::min<int64_t>(nb, 16384);
@@ -120,6 +100,112 @@ void tile_shape(int64_t na, int64_t nb, int64_t* rows, int64_t* cols) {
   r = std::min(r, (na + 63) / 64 * 64);
   *rows = r;
   *cols = c;
+}
+
+// Device buffers of one prepared MFMA operand, carved from scratch or owned by an index.
+struct Planes {
+  unsigned short* hi = nullptr;
+  unsigned short* lo = nullptr;
+  float* norm = nullptr;
+  PrepInfo* info = nullptr;
+};
+size_t planes_bytes(int64_t n, int d) {
+  return 2 * align_up((size_t)n * d * sizeof(unsigned short)) + align_up((size_t)n * sizeof(float)) +
+         align_up(sizeof(PrepInfo));
+}
+Planes carve_planes(char* base, int64_t n, int d) {
+  Planes p;
+  size_t o = 0;
+  p.hi = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));
+  p.lo = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));
+  p.norm = reinterpret_cast<float*>(base + o); o += align_up((size_t)n * sizeof(float));
+  p.info = reinterpret_cast<PrepInfo*>(base + o);
+  return p;
+}
+MfmaOperand operand(const float* x, int64_t n, const Planes& p) {
+  MfmaOperand m;
+  m.x = x; m.hi = p.hi; m.lo = p.lo; m.norm = p.norm; m.info = p.info; m.n = n;
+  return m;
+}
+
+// Exact k best rows of B for every row of A (canon values, ties to the smaller index),
+// written best first to `out`.  Two routes with identical results:
+//   canon tiles:    canon_matrix + row_select over (row tile, column tile) pairs;
+//   MFMA shortlist: bf16 matrix-core contraction -> kp candidates per row -> canon re-rank,
+//                   with a per-row sufficiency test and an exact fallback.
+struct KnnPlan {
+  bool mfma = false;
+  int nsplit = 1;
+  int64_t rows = 0, cols = 0;     // canon tile shape
+  size_t bytes = 0;               // scratch needed
+};
+KnnPlan knn_plan(int64_t na, int64_t nb, int d, int k, bool b_prepared) {
+  KnnPlan p;
+  const int path = g_knn_path.load();
+  p.mfma = path != 1 && nb > 0 && mfma_knn_supported(d, k);
+  if (p.mfma) {
+    size_t b = planes_bytes(na, d);
+    if (!b_prepared) b += planes_bytes(nb, d);
+    b += align_up(mfma_knn_shortlist_bytes(na, nb, k, &p.nsplit));
+    b += align_up(sizeof(int)) + align_up((size_t)na * sizeof(int));
+    p.bytes = b;
+  } else {
+    tile_shape(na, std::max<int64_t>(nb, 1), &p.rows, &p.cols);
+    p.bytes = align_up((size_t)p.rows * p.cols * sizeof(float)) + align_up((size_t)na * k * sizeof(u64));
+  }
+  return p;
+}
+
+void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const float* B, int64_t nb,
+             int d, int metric, int k, const Planes* b_planes, const SelectOut& out, hipStream_t st,
+             int stage_dist, int stage_select) {
+  if (plan.mfma) {
+    size_t o = 0;
+    Planes pa = carve_planes(ws + o, na, d); o += planes_bytes(na, d);
+    Planes pb;
+    if (b_planes) pb = *b_planes;
+    else { pb = carve_planes(ws + o, nb, d); o += planes_bytes(nb, d); }
+    int ns = 1;
+    const size_t sl = align_up(mfma_knn_shortlist_bytes(na, nb, k, &ns));
+    u64* shortlist = reinterpret_cast<u64*>(ws + o); o += sl;
+    int* fb_count = reinterpret_cast<int*>(ws + o); o += align_up(sizeof(int));
+    int* fb_rows = reinterpret_cast<int*>(ws + o);
+    const MfmaOperand oa = operand(A, na, pa), ob = operand(B, nb, pb);
+    {
+      StageTimer t(stage_dist, st);
+      launch_prep(A, na, d, pa.hi, pa.lo, pa.norm, pa.info, st);
+      if (!b_planes) launch_prep(B, nb, d, pb.hi, pb.lo, pb.norm, pb.info, st);
+      launch_mfma_shortlist(oa, ob, d, metric, k, plan.nsplit, shortlist, st);
+    }
+    {
+      StageTimer t(stage_select, st);
+      launch_rerank(oa, ob, d, metric, k, plan.nsplit, shortlist, g_knn_eps_scale.load(), out,
+                    fb_count, fb_rows, st);
+    }
+    g_knn_mfma_rows += na;
+    return;
+  }
+  float* mat = reinterpret_cast<float*>(ws);
+  u64* keys = reinterpret_cast<u64*>(ws + align_up((size_t)plan.rows * plan.cols * sizeof(float)));
+  for (int64_t a0 = 0; a0 < na; a0 += plan.rows) {
+    const int64_t ra = std::min(plan.rows, na - a0);
+    SelectOut o;
+    o.val = out.val ? out.val + a0 * k : nullptr;
+    o.id64 = out.id64 ? out.id64 + a0 * k : nullptr;
+    o.idx32 = out.idx32 ? out.idx32 + a0 * k : nullptr;
+    for (int64_t b0 = 0; b0 < nb; b0 += plan.cols) {
+      const int64_t cb = std::min(plan.cols, nb - b0);
+      {
+        StageTimer t(stage_dist, st);
+        launch_canon_matrix(A + a0 * d, ra, B + b0 * d, cb, d, metric, mat, plan.cols, st);
+      }
+      {
+        StageTimer t(stage_select, st);
+        launch_row_select(mat, plan.cols, ra, cb, (u32)b0, metric, k, keys + a0 * k, b0 == 0,
+                          b0 + cb >= nb, o, st);
+      }
+    }
+  }
 }
 
 }  // namespace
@@ -134,6 +220,9 @@ struct vs_ivfpq {
   int64_t* ids = nullptr;       // [ntotal]
   int64_t* list_off = nullptr;  // device [nlist + 1]
   std::vector<int64_t> h_off;   // host copy
+  void* plane_mem = nullptr;    // bf16 head/tail planes + norms of the centroids (MFMA route)
+  Planes c_planes;
+  bool has_planes = false;
   mutable Scratch scratch;
 };
 
@@ -164,7 +253,28 @@ int vs_profile_read(double* stage_ms, int64_t* launches) {
   g_prof.clear();
   return rc;
 }
-const char* vs_version(void) { return "vs 0.1 (gfx950)"; }
+const char* vs_version(void) { return "vs 0.2 (gfx950)"; }
+
+int vs_set_option(const char* name, double value) {
+  if (!name) return fail(VS_ERR_INVALID_ARG, "vs_set_option: name is null");
+  if (!strcmp(name, "knn_path")) {
+    if (value != 0 && value != 1 && value != 2) return fail(VS_ERR_INVALID_ARG, "vs_set_option: knn_path must be 0, 1 or 2");
+    g_knn_path = (int)value;
+    return VS_OK;
+  }
+  if (!strcmp(name, "knn_eps_scale")) { g_knn_eps_scale = (float)value; return VS_OK; }
+  return fail(VS_ERR_INVALID_ARG, "vs_set_option: unknown option '%s'", name);
+}
+
+int vs_counters_read(int64_t* counters) {
+  if (!counters) return fail(VS_ERR_INVALID_ARG, "vs_counters_read: null pointer");
+  HIP_TRY(hipDeviceSynchronize());
+  unsigned long long fb = 0;
+  if (read_fallback_total(&fb) != 0) return fail(VS_ERR_DEVICE, "vs_counters_read: cannot read the device counter");
+  counters[0] = g_knn_mfma_rows.exchange(0);
+  counters[1] = (int64_t)fb;
+  return VS_OK;
+}
 
 int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
                    int32_t metric, int32_t k, float* out_dist, int64_t* out_ids,
@@ -181,26 +291,21 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_flat_search: device %d", dev);
 
-  int64_t rows, cols;
-  tile_shape(nq, std::max<int64_t>(nb, 1), &rows, &cols);
-  Carver cv;
-  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
-  const size_t o_keys = cv.take((size_t)nq * k * sizeof(u64));
+  const KnnPlan plan = knn_plan(nq, nb, d, k, false);
   std::lock_guard<std::mutex> lock(g_flat_mu);
   Scratch& sc = g_flat_scratch[dev];
-  if (int rc = sc.reserve(cv.off)) return rc;
+  if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
   char* base = static_cast<char*>(sc.p);
-  float* mat = reinterpret_cast<float*>(base + o_mat);
-  u64* keys = reinterpret_cast<u64*>(base + o_keys);
   SelectOut out;
   out.val = out_dist;
   out.id64 = out_ids;
   if (nb == 0) {   // nothing to select from: all slots empty
+    u64* keys = reinterpret_cast<u64*>(base);
     launch_fill_u64(keys, nq * k, 0xFFFFFFFFFFFFFFFFull, st);
     launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
   } else {
-    knn_select(q, nq, x, nb, d, metric, k, mat, rows, cols, keys, out, st, VS_STAGE_FLAT_DIST,
-               VS_STAGE_FLAT_SELECT);
+    knn_run(plan, base, q, nq, x, nb, d, metric, k, nullptr, out, st, VS_STAGE_FLAT_DIST,
+            VS_STAGE_FLAT_SELECT);
   }
   HIP_TRY(hipGetLastError());
   return VS_OK;
@@ -240,6 +345,13 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
   TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
   TRY_C(hipMemcpyAsync(ix->codebooks, codebooks, tb, hipMemcpyDeviceToDevice, st));
   TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));
+  if (mfma_knn_supported(d, 1)) {
+    TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
+    ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
+    launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
+                ix->c_planes.info, st);
+    ix->has_planes = true;
+  }
   TRY_C(hipStreamSynchronize(st));
 #undef TRY_C
   *out = ix;
@@ -253,6 +365,7 @@ void vs_ivfpq_destroy(vs_ivfpq* ix) {
   if (ix->list_off) (void)hipFree(ix->list_off);
   if (ix->codes) (void)hipFree(ix->codes);
   if (ix->ids) (void)hipFree(ix->ids);
+  if (ix->plane_mem) (void)hipFree(ix->plane_mem);
   ix->scratch.release();
   delete ix;
 }
@@ -270,7 +383,12 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
   const IvfpqDims& g = ix->g;
 
   // scratch: best keys [n] | list_of [n] | one byte per (vector, m) [n, M] | dest [n] | new offsets
+  // | work space of the MFMA assignment, in pieces of at most kAssignPiece vectors
+  constexpr int64_t kAssignPiece = 1 << 20;
+  KnnPlan plan = knn_plan(std::min(n, kAssignPiece), g.nlist, g.d, 1, ix->has_planes);
+  if (!plan.mfma) plan.bytes = 0;
   Carver cv;
+  const size_t o_knn = cv.take(plan.bytes);
   const size_t o_keys = cv.take((size_t)n * sizeof(u64));
   const size_t o_list = cv.take((size_t)n * sizeof(int32_t));
   const size_t o_tmp = cv.take((size_t)n * g.M);
@@ -285,9 +403,19 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
   int64_t* new_off = reinterpret_cast<int64_t*>(base + o_off);
 
   // 1. list assignment: best centroid on the canon chain, ties to the smaller list
-  launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
-  launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
-  launch_keys_to_index32(keys, n, list_of, st);
+  if (plan.mfma) {
+    for (int64_t i0 = 0; i0 < n; i0 += kAssignPiece) {
+      const int64_t ni = std::min(kAssignPiece, n - i0);
+      SelectOut o;
+      o.idx32 = list_of + i0;
+      knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
+              ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1);
+    }
+  } else {
+    launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
+    launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
+    launch_keys_to_index32(keys, n, list_of, st);
+  }
   // 2. residual PQ codes
   launch_pq_encode(g, x, n, list_of, ix->centroids, ix->codebooks, tmp_codes, st);
 
@@ -338,14 +466,14 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
 }
 
 // coarse quantizer: the npr best lists per query, best first, with their canon values
-static void coarse_select(const vs_ivfpq* ix, const float* q, int64_t nq, int npr, float* mat,
-                          int64_t rows, int64_t cols, u64* ckeys, int32_t* probes, float* cdist,
-                          hipStream_t st) {
+static void coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
+                          int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st) {
   SelectOut out;
   out.val = cdist;
   out.idx32 = probes;
-  knn_select(q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr, mat, rows, cols, ckeys,
-             out, st, VS_STAGE_COARSE_DIST, VS_STAGE_COARSE_SELECT);
+  knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
+          ix->has_planes ? &ix->c_planes : nullptr, out, st, VS_STAGE_COARSE_DIST,
+          VS_STAGE_COARSE_SELECT);
 }
 
 int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
@@ -357,16 +485,9 @@ int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t npro
   if (!q || !probes) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_coarse: null pointer");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int npr = std::min<int>(nprobe, ix->g.nlist);
-  int64_t rows, cols;
-  tile_shape(nq, ix->g.nlist, &rows, &cols);
-  Carver cv;
-  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
-  const size_t o_ck = cv.take((size_t)nq * npr * sizeof(u64));
-  if (int rc = ix->scratch.reserve(cv.off)) return rc;
-  char* base = static_cast<char*>(ix->scratch.p);
-  u64* ckeys = reinterpret_cast<u64*>(base + o_ck);
-  coarse_select(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, probes,
-                coarse_dist, st);
+  const KnnPlan plan = knn_plan(nq, ix->g.nlist, ix->g.d, npr, ix->has_planes);
+  if (int rc = ix->scratch.reserve(plan.bytes)) return rc;
+  coarse_select(ix, plan, static_cast<char*>(ix->scratch.p), q, nq, npr, probes, coarse_dist, st);
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
@@ -388,23 +509,19 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   const int ppb = (npr + nsplit - 1) / nsplit;
   nsplit = (npr + ppb - 1) / ppb;
 
-  int64_t rows, cols;
-  tile_shape(nq, g.nlist, &rows, &cols);
+  const KnnPlan plan = knn_plan(nq, g.nlist, g.d, npr, ix->has_planes);
   Carver cv;
-  const size_t o_mat = cv.take((size_t)rows * cols * sizeof(float));
-  const size_t o_ck = cv.take((size_t)nq * npr * sizeof(u64));
+  const size_t o_knn = cv.take(plan.bytes);
   const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
   const size_t o_cd = cv.take((size_t)nq * npr * sizeof(float));
   const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
-  u64* ckeys = reinterpret_cast<u64*>(base + o_ck);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
   float* cdist = reinterpret_cast<float*>(base + o_cd);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
 
-  coarse_select(ix, q, nq, npr, reinterpret_cast<float*>(base + o_mat), rows, cols, ckeys, probes,
-                cdist, st);
+  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st);
   {
     StageTimer t(VS_STAGE_SCAN, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,

@@ -147,18 +147,32 @@ __device__ __forceinline__ void wave_sort_regs(u64 (&v)[R]) {
 // live slots are sorted and the reservoir is emptied.  TOT is a power of two
 // >= k + 64.  R > 0: TOT == 64 * R and the sort runs in registers (R keys per
 // lane, DPP exchanges); R == 0: any TOT, bitonic network through LDS.
+// LDS pointers carry their address space in the type, so that every access below is
+// a ds_* instruction (not a flat access that has to discover its aperture at run time).
+typedef __attribute__((address_space(3))) volatile u64* lds_u64_ptr;
+__device__ __forceinline__ lds_u64_ptr to_lds(u64* p) { return (lds_u64_ptr)p; }
+
 template <int R>
 struct WaveSelect {
-  volatile u64* s;       // this wavefront's TOT slots
-  volatile u64* shared;  // optional: a bound shared by the wavefronts of a workgroup (LDS), or null
+  lds_u64_ptr s;         // this wavefront's TOT slots
+  lds_u64_ptr shared;    // optional: a bound shared by the wavefronts of a workgroup, or null
+  bool has_shared;
   int tot, k, cnt;       // cnt: reservoir fill (wave-uniform)
   u64 thresh;            // k-th best key this wavefront holds (wave-uniform)
 #ifdef VS_SCAN_TIMING
   unsigned long long trim_cycles = 0;
 #endif
 
+  // attach to existing state (slots hold k sorted keys plus cnt_ reservoir entries)
+  __device__ __forceinline__ void attach(u64* slots, int tot_, int k_, int cnt_, u64 thresh_) {
+    s = to_lds(slots); shared = (lds_u64_ptr)0; has_shared = false;
+    tot = tot_; k = k_; cnt = cnt_; thresh = thresh_;
+  }
+
   __device__ __forceinline__ void init(u64* slots, int tot_, int k_, u64* shared_ = nullptr) {
-    s = slots; shared = shared_; tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
+    s = to_lds(slots); has_shared = shared_ != nullptr;
+    shared = has_shared ? to_lds(shared_) : (lds_u64_ptr)0;
+    tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
     for (int i = lane_id(); i < k; i += VS_WAVE) s[i] = KEY_EMPTY;
     wave_lds_sync();
   }
@@ -210,8 +224,9 @@ struct WaveSelect {
     thresh = s[k - 1];
     // The k-th best key of ANY subset bounds the k-th best of the whole: publish it so
     // that sibling wavefronts reject candidates that cannot make the workgroup's top k.
-    if (shared && lane_id() == 0 && thresh != KEY_EMPTY)
-      atomicMin(const_cast<u64*>(shared), thresh);
+    if (has_shared && lane_id() == 0 && thresh != KEY_EMPTY)
+      __hip_atomic_fetch_min((__attribute__((address_space(3))) u64*)shared, thresh,
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #ifdef VS_SCAN_TIMING
     trim_cycles += clock64() - t0_;
 #endif

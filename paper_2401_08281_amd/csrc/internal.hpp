@@ -62,3 +62,34 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
                       int64_t* out_ids, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
+
+// ---- MFMA shortlist + exact re-rank (kernels_mfma.hip) --------------------------
+// What operand preparation learns about a matrix (device memory).
+struct PrepInfo {
+  u32 all_int;        // every value is an integer
+  u32 all_bf16;       // every value is exactly representable in bf16
+  u32 max_norm_bits;  // bits of the largest squared row norm (non-negative float)
+  u32 pad;
+};
+struct MfmaOperand {
+  const float* x;             // [n, d] original fp32 rows
+  const unsigned short* hi;   // [n, d] bf16 heads
+  const unsigned short* lo;   // [n, d] bf16 tails
+  const float* norm;          // [n] squared norms
+  const PrepInfo* info;
+  int64_t n;
+};
+bool mfma_knn_supported(int d, int k);
+int mfma_knn_kp(int k);
+void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
+                 float* norm, PrepInfo* info, hipStream_t st);
+// bytes of the shortlist buffer [na, nsplit, kp] and the column split count to use
+size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out);
+void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
+                           int nsplit, u64* shortlist, hipStream_t st);
+// exact k best per row of A from the shortlists; rows that cannot be proven exact are
+// recomputed over all of B.  fb_count: 1 int, fb_rows: A.n ints (device scratch).
+void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k, int nsplit,
+                   const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
+                   int* fb_rows, hipStream_t st);
+int read_fallback_total(unsigned long long* out);

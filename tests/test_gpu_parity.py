@@ -253,3 +253,57 @@ def test_c2_full_size_sampled(vs, oracle):
     np.testing.assert_array_equal(D[qs], Do)
     np.testing.assert_array_equal(I[qs], Io)
     assert (np.diff(D, axis=1) >= 0).all() and (I >= 0).all()
+
+
+# ------------------------------------------------- the two k-nearest-row routes
+
+ROUTE_CASES = [
+    # name, nb, nq, d, k, metric, kind
+    ("gauss_d32_k10", 20_000, 300, 32, 10, L2, "gauss"),
+    ("gauss_d128_k100", 30_000, 150, 128, 100, L2, "gauss"),
+    ("gauss_d96_k64_ip", 9_000, 77, 96, 64, IP, "gauss"),
+    ("gauss_d64_k1", 5_000, 1000, 64, 1, L2, "gauss"),
+    ("unit_d96_k20", 15_000, 100, 96, 20, L2, "unit"),
+    ("sift_d128_k100", 50_000, 100, 128, 100, L2, "sift"),
+    ("tiny_nb_d32", 50, 10, 32, 40, L2, "gauss"),
+]
+
+
+@pytest.mark.parametrize("name,nb,nq,d,k,metric,kind", ROUTE_CASES, ids=[c[0] for c in ROUTE_CASES])
+def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, metric, kind):
+    """Flat search through the MFMA shortlist + re-rank must return exactly what the
+    canon distance tiles return (values and ids), also when every row is forced through
+    the exact fallback; both agree with the oracle."""
+    say("routes %s nb=%d nq=%d d=%d k=%d metric=%d" % (name, nb, nq, d, k, metric))
+    if kind == "gauss":
+        rng = np.random.default_rng(zlib.crc32(name.encode()))
+        x = rng.standard_normal((nb, d), dtype=np.float32)
+        q = rng.standard_normal((nq, d), dtype=np.float32)
+    elif kind == "unit":
+        x, q = S.make_data(S.config("C4", nb=nb, nq=nq, d=d, ncomp=30))
+    else:
+        x, q = S.make_data(S.config("C2", nb=nb, nq=nq, d=d, ncomp=30))
+    xd, qd = dev(x), dev(q)
+    try:
+        vs.vs_set_option("knn_path", 1)
+        Dc, Ic = [host(t).copy() for t in vs.vs_flat_search(xd, qd, k, metric)]
+        vs.vs_set_option("knn_path", 0)
+        vs.vs_counters_read()
+        Dm, Im = [host(t).copy() for t in vs.vs_flat_search(xd, qd, k, metric)]
+        rows, fallback = vs.vs_counters_read()
+        say("  matrix-core route: %d rows, %d needed the exact fallback" % (rows, fallback))
+        assert rows == nq
+        vs.vs_set_option("knn_eps_scale", -1.0)
+        Df, If = [host(t).copy() for t in vs.vs_flat_search(xd, qd, k, metric)]
+        rows, fallback = vs.vs_counters_read()
+        assert fallback == nq
+    finally:
+        vs.vs_set_option("knn_eps_scale", 1.0)
+        vs.vs_set_option("knn_path", 0)
+    np.testing.assert_array_equal(Dm, Dc)
+    np.testing.assert_array_equal(Im, Ic)
+    np.testing.assert_array_equal(Df, Dc)
+    np.testing.assert_array_equal(If, Ic)
+    Do, Io = oracle.flat_search(x, q, min(k + EXTRA, max(nb, k)), metric)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+    check_search(Dm, Im, Do, Io, metric, q, xn)
