@@ -110,11 +110,13 @@ struct Planes {
   PrepInfo* info = nullptr;
 };
 size_t planes_bytes(int64_t n, int d) {
+  n = mfma_padded_rows(n);
   return 2 * align_up((size_t)n * d * sizeof(unsigned short)) + align_up((size_t)n * sizeof(float)) +
          align_up(sizeof(PrepInfo));
 }
 Planes carve_planes(char* base, int64_t n, int d) {
   Planes p;
+  n = mfma_padded_rows(n);
   size_t o = 0;
   p.hi = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));
   p.lo = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));

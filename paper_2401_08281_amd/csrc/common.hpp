@@ -57,6 +57,15 @@ __device__ __forceinline__ void block_sync_lds() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Waits until every global load issued so far by this wavefront has returned.  Placed
+// after a prologue that fills long-lived registers (codebooks, MFMA operand fragments), it
+// lets the loop that follows keep its own prefetches in flight: without it the compiler has
+// to assume, at every use of those registers inside the loop, that the prologue's loads may
+// still be pending, and waits for everything -- the loop's prefetches included.
+__device__ __forceinline__ void wait_all_global_loads() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // gfx9 encoding: vmcnt(0), expcnt and lgkmcnt unconstrained
+}
+
 // ---- cross-lane exchange and register-resident bitonic sort ------------------
 // lane i receives the value held by lane i ^ X.  X = 1, 2, 4, 8 stay inside a
 // row of 16 lanes and use DPP modifiers (no LDS traffic); 16 and 32 cross rows
@@ -80,25 +89,27 @@ __device__ __forceinline__ u32 lane_xor_u32(u32 v) {
   }
 }
 template <int X>
-__device__ __forceinline__ u64 lane_xor_u64(u64 v) {
+__device__ __forceinline__ u64 lane_xor(u64 v) {
   const u32 lo = lane_xor_u32<X>((u32)v), hi = lane_xor_u32<X>((u32)(v >> 32));
   return ((u64)hi << 32) | lo;
 }
+template <int X>
+__device__ __forceinline__ u32 lane_xor(u32 v) { return lane_xor_u32<X>(v); }
 
 // One compare-exchange step of the bitonic network at lane distance X for
 // element index e (ascending block when (e & size) == 0).
-template <int X>
-__device__ __forceinline__ u64 bitonic_lane_step(u64 v, int e, int stride, int size) {
-  const u64 o = lane_xor_u64<X>(v);
+template <int X, typename T>
+__device__ __forceinline__ T bitonic_lane_step(T v, int e, int stride, int size) {
+  const T o = lane_xor<X>(v);
   const bool keep_min = ((e & stride) == 0) == ((e & size) == 0);
-  const u64 lo = v < o ? v : o, hi = v < o ? o : v;
+  const T lo = v < o ? v : o, hi = v < o ? o : v;
   return keep_min ? lo : hi;
 }
 
-// Sorts the 64 * R keys held by one wavefront, ascending in element order
+// Sorts the 64 * R keys (u32 or u64) held by one wavefront, ascending in element order
 // e = lane * R + r.  Strides below R are register-to-register; the rest cross lanes.
-template <int R>
-__device__ __forceinline__ void wave_sort_regs(u64 (&v)[R]) {
+template <int R, typename T>
+__device__ __forceinline__ void wave_sort_regs(T (&v)[R]) {
   const int lane = lane_id();
 #pragma unroll
   for (int size = 2; size <= 64 * R; size <<= 1) {
@@ -124,7 +135,7 @@ __device__ __forceinline__ void wave_sort_regs(u64 (&v)[R]) {
           if ((r & stride) == 0) {
             const int e = lane * R + r;
             const bool up = (e & size) == 0;
-            const u64 a = v[r], b = v[r | stride];
+            const T a = v[r], b = v[r | stride];
             const bool sw = (a > b) == up;
             v[r] = sw ? b : a;
             v[r | stride] = sw ? a : b;
@@ -205,7 +216,7 @@ struct WaveSelect {
       const int e = lane * R + r;
       v[r] = e < live ? s[e] : KEY_EMPTY;
     }
-    wave_sort_regs<(R > 0 ? R : 1)>(v);
+    wave_sort_regs(v);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int e = lane * R + r;

@@ -80,6 +80,8 @@ struct MfmaOperand {
   int64_t n;
 };
 bool mfma_knn_supported(int d, int k);
+// operand planes hold this many rows (the tail is zero padding)
+int64_t mfma_padded_rows(int64_t n);
 int mfma_knn_kp(int k);
 void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
                  float* norm, PrepInfo* info, hipStream_t st);

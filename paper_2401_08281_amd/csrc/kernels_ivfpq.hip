@@ -359,6 +359,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
 #pragma unroll
     for (int u = 0; u < DSUB; ++u)
       T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jj + TPM * i) * DSUB + u];
+  wait_all_global_loads();   // the codebook is in registers from here on
 
   for (int64_t item = blockIdx.x; item < nitems; item += gridDim.x) {
     const int64_t qi = item / nsplit;

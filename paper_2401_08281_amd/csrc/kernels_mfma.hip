@@ -28,6 +28,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned short bf16_rn_bits(float f) {
   u32 u = __float_as_uint(f);
@@ -44,8 +45,8 @@ __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
 // One lane per 8 consecutive elements (d % 8 == 0), 256 lanes per workgroup,
 // RB = 2048 / d ... rows per workgroup; row sums are added in a fixed order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, int64_t n, int d,
-                                                   int rows_per_block,
+__global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, int64_t n,
+                                                   int64_t n_pad, int d, int rows_per_block,
                                                    unsigned short* __restrict__ hi,
                                                    unsigned short* __restrict__ lo,
                                                    float* __restrict__ norm,
@@ -84,6 +85,12 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
     *reinterpret_cast<uint4*>(hi + off) = hv;
     *reinterpret_cast<uint4*>(lo + off) = lv;
   }
+  else if (r < rows_per_block && row0 + r < n_pad) {   // padding rows: zeros (never selected)
+    const int64_t off = (row0 + r) * d + c * 8;
+    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+    *reinterpret_cast<uint4*>(hi + off) = z;
+    *reinterpret_cast<uint4*>(lo + off) = z;
+  }
   part[tid] = ss;
   if (!is_int) flags[0] = 0u;
   if (!is_bf16) flags[1] = 0u;
@@ -93,6 +100,8 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
     for (int j = 0; j < cpr; ++j) s += part[tid * cpr + j];
     norm[row0 + tid] = s;
     atomicMax(&info->max_norm_bits, __float_as_uint(s));    // s >= 0: bit order = value order
+  } else if (tid < rows_per_block && row0 + tid < n_pad) {
+    norm[row0 + tid] = 0.f;
   }
   if (tid == 0) {
     if (!flags[0]) atomicAnd(&info->all_int, 0u);
@@ -105,43 +114,67 @@ __global__ void prep_info_init_kernel(PrepInfo* info) {
 }
 
 // ---------------------------------------------------------------------------
-// Approximate kp-best rows of B for each row of A.
-// Workgroup = 4 wavefronts = (32 * RB rows of A) x (a range of B rows, 256 per step).
-// Each wavefront holds the A fragments of ALL the workgroup's rows in registers
-// for the whole kernel and streams its own 64 B rows per step straight from
-// memory into MFMA operand registers (no LDS for operands: lane l of a 32x32x16
-// tile needs 16 contiguous bytes of row l % 32).  The 32*RB x 256 tile of
-// approximate values is staged in LDS; then every wavefront runs the
-// threshold-filtered WaveSelect for the rows it owns (one select state per row,
-// kept in LDS).  B fragments of the next step are requested right after the
-// MFMAs of this step have been issued, so they fly during staging and selection.
+// Shortlist of at least kp approximately-best rows of B for each row of A.
+//
+// Tiling.  Workgroup = 4 wavefronts; wavefront w owns 32 * RB rows of A whose bf16
+// fragments stay in its registers for the whole kernel.  The workgroup walks over a
+// range of B in steps of 64 rows; each step's 64 x d bf16 tile is copied once from
+// memory into LDS (double buffered, padded rows: conflict-free 128-bit reads) and is
+// read by all four wavefronts, so one byte of B feeds 128 * RB rows of A.  Per step a
+// wavefront issues 2 * RB * (d / 16) v_mfma_f32_32x32x16_bf16 (x3 when the operands
+// need the head/tail split).
+//
+// Selection uses TWO sweeps over the columns instead of a running top-k, so that the
+// inner loops carry no selection state beyond registers:
+//   MODE 0 (minima): every accumulator position keeps the minimum of its values
+//     m = |x|^2 - 2<q,x> (L2) or m = -<q,x> (IP) over a phase of the sweep and writes
+//     it out at the end of the phase: a row gets G group minima, each attained by a
+//     different column.
+//   tau kernel: tau(row) = kp-th smallest group minimum, so at least kp columns of the
+//     row have m <= tau -- and, the groups being large, not many more.
+//   MODE 1 (collect): the tiles are recomputed (bit-identical) and every column with
+//     m <= tau(row) is appended to the row's candidate list.
+// The matrix cores do the contraction twice; they are far from being the limit here.
+// Every column that is NOT listed has m > tau >= (kp-th smallest listed m), which is
+// what the re-rank kernel's sufficiency test needs.
 // ---------------------------------------------------------------------------
-template <int KSTEPS, int RB, int R, int METRIC>
+template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
 __global__ __launch_bounds__(256)
-void mfma_knn_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
-                     const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
-                     const unsigned short* __restrict__ Bhi, const unsigned short* __restrict__ Blo,
-                     const float* __restrict__ Bnorm, const PrepInfo* __restrict__ Binfo, int64_t nb,
-                     int nsplit, int64_t cols_per_split, int kp, int cap,
-                     u64* __restrict__ shortlist) {
-  constexpr int D = KSTEPS * 16, BM = 32 * RB, LD = 256 + 4, ROWS_PER_WAVE = BM / 4;
+void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
+                       const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
+                       const unsigned short* __restrict__ Bhi, const unsigned short* __restrict__ Blo,
+                       const float* __restrict__ Bnorm, const PrepInfo* __restrict__ Binfo, int64_t nb,
+                       int nsplit, int64_t cols_per_split, int nphase, int64_t cols_per_phase,
+                       float* __restrict__ minima, int g_raw,       // MODE 0 out: [na][g_raw]
+                       const float* __restrict__ tau,               // MODE 1 in:  [na]
+                       int* __restrict__ cnt, u64* __restrict__ shortlist, int cap) {  // MODE 1 out
+  constexpr int D = KSTEPS * 16, BN = 64, LDB = D + 8;            // LDS row stride in bf16 elements
+  constexpr int NPL = THREE ? 2 : 1;                              // planes of B in LDS
+  constexpr int CHUNKS = BN * (D / 8);                            // 16-byte chunks per plane per step
+  constexpr int CPT = (CHUNKS + 255) / 256;                       // chunks per lane
+  constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
+  // both variants are launched; the one that does not match the operands' flags leaves at once
+  if ((!(Ainfo->all_bf16 && Binfo->all_bf16)) != THREE) return;
+
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* stage = reinterpret_cast<float*>(smem);                       // BM x LD
-  u64* slots = reinterpret_cast<u64*>(stage + BM * LD);                // BM x cap
-  u64* thr = slots + (size_t)BM * cap;                                 // BM
-  int* cnts = reinterpret_cast<int*>(thr + BM);                        // BM
+  unsigned short* bt = reinterpret_cast<unsigned short*>(smem);   // [2 buffers][NPL][BN][LDB]
+  float* bns = reinterpret_cast<float*>(bt + 2 * NPL * BN * LDB); // [2][BN] norms (+inf past the end)
+  // MODE 1: per-row candidate counters of this workgroup and one candidate queue per wavefront
+  int* cnt_s = reinterpret_cast<int*>(bns + 2 * BN);              // [128 * RB]
+  u64* qkey = reinterpret_cast<u64*>(cnt_s + 128 * RB) + (threadIdx.x >> 6) * 128;   // [4][128]
+  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + 128 * RB) + 4 * 128) +
+              (threadIdx.x >> 6) * 128;                           // [4][128]
+  int qn = 0;                                                     // queue fill (wave-uniform)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
   const int64_t rt = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
-  const int64_t row0 = rt * BM;
+  const int64_t row0 = rt * (128 * RB) + wave * (32 * RB);        // this wavefront's first row
   const int64_t c_begin = (int64_t)split * cols_per_split;
   const int64_t c_end = min(nb, c_begin + cols_per_split);
-  const bool three = !(Ainfo->all_bf16 && Binfo->all_bf16);            // uniform
 
   // A fragments: lane holds row (l % 32) of each 32-row block, dims 8 * (l / 32) .. + 7 of each k-step
-  bf16x8 ah[RB][KSTEPS], al[RB][KSTEPS];
-  float an[RB][16];
+  bf16x8 ah[RB][KSTEPS], al[THREE ? RB : 1][THREE ? KSTEPS : 1];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int64_t ar = min(row0 + rb * 32 + (lane & 31), na - 1);
@@ -149,112 +182,225 @@ void mfma_knn_kernel(const unsigned short* __restrict__ Ahi, const unsigned shor
     for (int kk = 0; kk < KSTEPS; ++kk) {
       const int64_t off = ar * D + kk * 16 + 8 * (lane >> 5);
       ah[rb][kk] = *reinterpret_cast<const bf16x8*>(Ahi + off);
-      al[rb][kk] = *reinterpret_cast<const bf16x8*>(Alo + off);
+      if constexpr (THREE) al[rb][kk] = *reinterpret_cast<const bf16x8*>(Alo + off);
     }
+  }
+  // per accumulator register: running minimum (MODE 0) or threshold and |q|^2 (MODE 1)
+  float mn[RB][2][16], tr[RB][16], an[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int64_t r = min(row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), na - 1);
-      an[rb][v] = METRIC == 0 ? Anorm[r] : 0.f;
+      tr[rb][v] = MODE == 1 ? tau[r] : 0.f;
+      an[rb][v] = (MODE == 1 && METRIC == 0) ? Anorm[r] : 0.f;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) mn[rb][cb][v] = __builtin_inff();
     }
+
+  // global -> registers -> LDS staging of one 64-row B tile (spelled as macros so that the
+  // staging registers stay registers).  B planes are padded to a multiple of 64 rows, so a
+  // tile is one contiguous block of memory: lane offsets are fixed 32-bit numbers.
+  u32x4 stg[NPL][CPT];
+  float stn = 0.f;
+  int g_off[CPT], l_off[CPT];
+#pragma unroll
+  for (int i = 0; i < CPT; ++i) {
+    const int ch = tid + 256 * i;
+    g_off[i] = ch * 8;                                            // chunk ch of the tile, in elements
+    l_off[i] = (ch / (D / 8)) * LDB + (ch % (D / 8)) * 8;
   }
-  for (int i = tid; i < BM; i += 256) { thr[i] = KEY_EMPTY; cnts[i] = 0; }
-  for (int i = tid; i < BM * kp; i += 256) slots[(size_t)(i / kp) * cap + (i % kp)] = KEY_EMPTY;
-  block_sync_lds();
+#define FETCH_TILE(CT)                                                                           \
+  do {                                                                                           \
+    const unsigned short* __restrict__ th_ = Bhi + (CT) * D;                                     \
+    const unsigned short* __restrict__ tl_ = Blo + (CT) * D;                                     \
+    _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                         \
+      stg[0][i_] = *reinterpret_cast<const u32x4*>(th_ + g_off[i_]);                             \
+      if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(tl_ + g_off[i_]);  \
+    }                                                                                            \
+    stn = Bnorm[(CT) + (tid & 63)];               /* consumed only when the tile is stashed */  \
+  } while (0)
+#define STASH_TILE(BUF, CT)                                                                      \
+  do {                                                                                           \
+    _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                         \
+      _Pragma("unroll") for (int pl_ = 0; pl_ < NPL; ++pl_)                                      \
+        *reinterpret_cast<u32x4*>(bt + ((BUF) * NPL + pl_) * BN * LDB + l_off[i_]) = stg[pl_][i_]; \
+    }                                                                                            \
+    if (tid < BN)                                                                                \
+      bns[(BUF) * BN + tid] = (CT) + tid < c_end ? (METRIC == 0 ? stn : 0.f) : __builtin_inff(); \
+  } while (0)
+  static_assert(CHUNKS % 256 == 0, "every lane stages the same number of chunks");
 
-  bf16x8 bh[2][KSTEPS], bl[2][KSTEPS];
-  float bn[2];
-  auto load_b = [&](int64_t ct) {
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      const int64_t col = min(ct + wave * 64 + cb * 32 + (lane & 31), nb - 1);
-#pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk) {
-        const int64_t off = col * D + kk * 16 + 8 * (lane >> 5);
-        bh[cb][kk] = *reinterpret_cast<const bf16x8*>(Bhi + off);
-        if (three) bl[cb][kk] = *reinterpret_cast<const bf16x8*>(Blo + off);
-      }
-      bn[cb] = METRIC == 0 ? Bnorm[col] : 0.f;
+  if (MODE == 1) for (int i = tid; i < 128 * RB; i += 256) cnt_s[i] = 0;
+  // Takes n <= 64 queued candidates (the newest ones) and appends each to its row's list:
+  // one LDS atomic per candidate for the position, all lanes in parallel.
+  auto drain = [&](int n) {
+    wave_lds_sync();
+    const int e = qn - n + lane;
+    if (lane < n) {
+      const int rl = qrow[e];
+      const u64 key = qkey[e];
+      const int pos = atomicAdd(&cnt_s[rl], 1);
+      const int64_t r = rt * (128 * RB) + rl;
+      if (pos < cap) shortlist[(r * nsplit + split) * (int64_t)cap + pos] = key;
     }
+    qn -= n;
+    wave_lds_sync();
   };
-  if (c_begin < c_end) load_b(c_begin);
-
-  for (int64_t ct = c_begin; ct < c_end; ct += 256) {
-    floatx16 acc[RB][2];
+  if (c_begin < c_end) { FETCH_TILE(c_begin); STASH_TILE(0, c_begin); }
+  wait_all_global_loads();   // A fragments, thresholds and norms are in registers from here on
+  block_sync_lds();
+  int buf = 0;
+  for (int64_t ct = c_begin; ct < c_end; ct += BN, buf ^= 1) {
+    const bool more = ct + BN < c_end;
+    if (more) FETCH_TILE(ct + BN);                                // in flight during the MFMAs
+    floatx16 m[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.f;
+        for (int v = 0; v < 16; ++v) m[rb][cb][v] = 0.f;
+    const unsigned short* __restrict__ bth = bt + (buf * NPL) * BN * LDB;
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk)
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      bf16x8 bh[2], bl[2];
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const int o = (cb * 32 + (lane & 31)) * LDB + kk * 16 + 8 * (lane >> 5);
+        bh[cb] = *reinterpret_cast<const bf16x8*>(bth + o);
+        if constexpr (THREE) bl[cb] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + o);
+      }
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bh[cb], m[rb][cb], 0, 0, 0);
+          if constexpr (THREE) {
+            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bl[cb], m[rb][cb], 0, 0, 0);
+            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], bh[cb], m[rb][cb], 0, 0, 0);
+          }
+        }
+    }
+    const float b0 = bns[buf * BN + (lane & 31)], b1 = bns[buf * BN + 32 + (lane & 31)];
+    if (MODE == 0) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bh[cb][kk], acc[rb][cb], 0, 0, 0);
-    if (three) {
 #pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk)
+          for (int v = 0; v < 16; ++v)
+            mn[rb][cb][v] = fminf(mn[rb][cb][v], __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0));
+      // end of a phase: flush the group minima (after the last step, also pad the phases left)
+      const int ph = (int)((ct - c_begin) / cols_per_phase);
+      const int ph_next = more ? (int)((ct + BN - c_begin) / cols_per_phase) : nphase;
+      for (int p2 = ph; p2 < ph_next; ++p2) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int64_t r = row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              if (r < na)
+                minima[r * g_raw + (split * nphase + p2) * 64 + cb * 32 + (lane & 31)] = mn[rb][cb][v];
+              mn[rb][cb][v] = __builtin_inff();
+            }
+      }
+    } else {
+      bool any[RB][2];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          any[rb][cb] = false;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            m[rb][cb][v] = __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0);
+            any[rb][cb] = any[rb][cb] || m[rb][cb][v] <= tr[rb][v];
+          }
+        }
+      {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int cb = 0; cb < 2; ++cb) {
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bl[cb][kk], acc[rb][cb], 0, 0, 0);
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], bh[cb][kk], acc[rb][cb], 0, 0, 0);
+            if (__ballot(any[rb][cb]) == 0) continue;             // nothing of this 32 x 32 block passes
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int rl = wave * (32 * RB) + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              const bool pass = m[rb][cb][v] <= tr[rb][v] && rt * (128 * RB) + rl < na;
+              const u64 mask = __ballot(pass);
+              if (mask != 0) {
+                if (pass) {
+                  const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
+                  // approximate value: |q|^2 + m for L2, <q,x> = -m for IP
+                  const float val = METRIC == 0 ? an[rb][v] + m[rb][cb][v] : -m[rb][cb][v];
+                  qkey[e] = make_key(val, (u32)(ct + cb * 32 + (lane & 31)), METRIC);
+                  qrow[e] = rl;
+                }
+                qn += __popcll(mask);
+                if (qn >= 64) drain(64);
+              }
+            }
           }
-    }
-    const float bn0 = bn[0], bn1 = bn[1];
-    if (ct + 256 < c_end) load_b(ct + 256);     // in flight during staging and selection
-
-    // stage the tile: value (row i, col j) at stage[i][j]
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int i = rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          const int j = wave * 64 + cb * 32 + (lane & 31);
-          float val = acc[rb][cb][v];
-          if (METRIC == 0) val = (an[rb][v] + (cb ? bn1 : bn0)) - 2.f * val;
-          stage[i * LD + j] = val;
-        }
-    block_sync_lds();
-
-    // selection: this wavefront owns rows wave * ROWS_PER_WAVE ..
-    for (int rr = 0; rr < ROWS_PER_WAVE; ++rr) {
-      const int i = wave * ROWS_PER_WAVE + rr;
-      const u64 th = thr[i];
-      u64 key[4];
-      bool any = false;
-#pragma unroll
-      for (int c4 = 0; c4 < 4; ++c4) {
-        const int64_t col = ct + c4 * 64 + lane;
-        key[c4] = col < c_end ? make_key(stage[i * LD + c4 * 64 + lane], (u32)col, METRIC) : KEY_EMPTY;
-        any = any || key[c4] < th;
       }
-      if (__ballot(any) == 0) continue;          // nothing in this row beats its kp-th best
-      WaveSelect<R> ws;
-      ws.attach(slots + (size_t)i * cap, cap, kp, cnts[i], th);
-#pragma unroll
-      for (int c4 = 0; c4 < 4; ++c4) ws.push(key[c4] != KEY_EMPTY, key[c4]);
-      if (lane == 0) { cnts[i] = ws.cnt; thr[i] = ws.thresh; }
     }
+    if (more) STASH_TILE(buf ^ 1, ct + BN);
     block_sync_lds();
   }
-
-  // flush: sorted kp best per owned row
-  for (int rr = 0; rr < ROWS_PER_WAVE; ++rr) {
-    const int i = wave * ROWS_PER_WAVE + rr;
-    WaveSelect<R> ws;
-    ws.attach(slots + (size_t)i * cap, cap, kp, cnts[i], thr[i]);
-    ws.finish();
-    if (row0 + i < na) {
-      u64* out = shortlist + ((row0 + i) * nsplit + split) * (int64_t)kp;
-      for (int j = lane; j < kp; j += VS_WAVE) out[j] = ws.s[j];
+#undef FETCH_TILE
+#undef STASH_TILE
+  if (MODE == 1) {
+    if (qn > 0) drain(qn);
+    block_sync_lds();
+    for (int i = tid; i < 128 * RB; i += 256) {
+      const int64_t r = rt * (128 * RB) + i;
+      if (r < na) cnt[r * nsplit + split] = cnt_s[i];
     }
   }
+  if (MODE == 0 && c_begin >= c_end) {                            // empty split: all its groups are +inf
+    for (int ph = 0; ph < nphase; ++ph)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int64_t r = row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (r < na) minima[r * g_raw + (split * nphase + ph) * 64 + cb * 32 + (lane & 31)] = __builtin_inff();
+          }
+  }
+}
+
+// tau(row) = kp-th smallest of the row's g_raw group minima (min-combined down to 64 * RG
+// values first), clamped below +inf; also clears the row's candidate count.
+template <int RG>
+__global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ minima, int g_raw,
+                                                  int64_t na, int kp, float* __restrict__ tau) {
+  const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
+  if (row >= na) return;
+  const int lane = lane_id();
+  const float* __restrict__ src = minima + row * g_raw;
+  u32 v[RG];
+#pragma unroll
+  for (int r = 0; r < RG; ++r) v[r] = order_f32(__builtin_inff());
+  // value j goes to slot j % (64 * RG): lane (j / RG) % 64, register j % RG
+  for (int j0 = 0; j0 < g_raw; j0 += 64 * RG) {
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+      const int j = j0 + lane * RG + r;
+      if (j < g_raw) { const u32 o = order_f32(src[j]); v[r] = o < v[r] ? o : v[r]; }
+    }
+  }
+  wave_sort_regs(v);
+  u32 pick = 0;
+#pragma unroll
+  for (int r = 0; r < RG; ++r)
+    if (lane * RG + r == kp - 1) pick = v[r];
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) pick |= (u32)__shfl_xor((int)pick, off);
+  if (lane == 0) tau[row] = fminf(unorder_f32(pick), 3.4028234e38f);
 }
 
 // ---------------------------------------------------------------------------
@@ -285,7 +431,8 @@ __device__ __forceinline__ float canon_row(const float* __restrict__ qs, const f
 
 template <int R, int METRIC>
 __global__ __launch_bounds__(64) void rerank_kernel(
-    const u64* __restrict__ shortlist, int nsplit, int kp, const float* __restrict__ A,
+    const u64* __restrict__ shortlist, const int* __restrict__ cnt, int nsplit, int cap, int kp,
+    const float* __restrict__ A,
     const float* __restrict__ B, int d, int k, const float* __restrict__ Anorm,
     const PrepInfo* __restrict__ Ainfo, const PrepInfo* __restrict__ Binfo, float eps_scale,
     SelectOut out, int* __restrict__ fb_count, int* __restrict__ fb_rows) {
@@ -300,12 +447,17 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   // global kp best approximate keys of this row
   WaveSelect<R> ws;
   ws.init(slots, 64 * R, kp);
-  const u64* __restrict__ src = shortlist + row * (int64_t)nsplit * kp;
-  const int n = nsplit * kp;
-  for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
-    const int j = j0 + lane;
-    const u64 key = j < n ? src[j] : KEY_EMPTY;
-    ws.push(j < n && key != KEY_EMPTY, key);
+  bool truncated = false;
+  for (int sp = 0; sp < nsplit; ++sp) {
+    const u64* __restrict__ src = shortlist + (row * nsplit + sp) * (int64_t)cap;
+    const int listed = cnt[row * nsplit + sp];
+    truncated = truncated || listed > cap;
+    const int n = min(listed, cap);
+    for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
+      const int j = j0 + lane;
+      const u64 key = j < n ? src[j] : KEY_EMPTY;
+      ws.push(j < n && key != KEY_EMPTY, key);
+    }
   }
   ws.finish();
   const u64 tkey = ws.s[kp - 1];                                // kp-th best approximate key
@@ -320,7 +472,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(
     const u32 idx = key_index(ak);
     v[r] = make_key(canon_row<METRIC>(qs, B + (int64_t)idx * d, d, vec), idx, METRIC);
   }
-  wave_sort_regs<R>(v);
+  wave_sort_regs(v);
   wave_lds_sync();
 #pragma unroll
   for (int r = 0; r < R; ++r) slots[lane * R + r] = v[r];
@@ -344,6 +496,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   } else if (tkey != KEY_EMPTY && vk == KEY_EMPTY) {
     ok = true;   // cannot happen: kp >= k candidates exist
   }
+  if (truncated) ok = false;                                    // a candidate list was truncated
   if (eps_scale < 0.f) ok = false;                              // test hook: force the fallback
   if (!ok && lane == 0) {
     const int f = atomicAdd(fb_count, 1);
@@ -402,6 +555,8 @@ __global__ void zero_int_kernel(int* p) { *p = 0; }
 
 // ------------------------------------------------------------------ launchers
 
+int64_t mfma_padded_rows(int64_t n) { return (n + 63) / 64 * 64; }
+
 bool mfma_knn_supported(int d, int k) {
   return (d == 32 || d == 64 || d == 96 || d == 128) && k <= 150;
 }
@@ -417,54 +572,91 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
   hipLaunchKernelGGL(prep_info_init_kernel, dim3(1), dim3(1), 0, st, info);
   if (n <= 0) return;
   const int rpb = 2048 / d;                          // d <= 128 here, d % 8 == 0
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n + rpb - 1) / rpb)), dim3(256), 0, st, x, n, d, rpb,
-                     hi, lo, norm, info);
+  const int64_t n_pad = mfma_padded_rows(n);
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n_pad + rpb - 1) / rpb)), dim3(256), 0, st, x, n,
+                     n_pad, d, rpb, hi, lo, norm, info);
 }
+
+namespace {
+struct MfmaPlan {
+  int RB, nsplit, nphase, g_raw, rg, kp, cap;
+  int64_t cols_per_split, cols_per_phase, row_tiles;
+  size_t o_minima, o_tau, o_cnt, bytes;      // offsets behind the shortlist [na][nsplit][cap]
+};
+size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+MfmaPlan make_plan(int64_t na, int64_t nb, int k) {
+  MfmaPlan p;
+  p.kp = mfma_knn_kp(k);
+  p.cap = std::max(64, 3 * p.kp);
+  p.rg = p.kp <= 32 ? 1 : (p.kp <= 64 ? 2 : (p.kp <= 128 ? 4 : 8));
+  p.RB = na >= 8192 ? 2 : 1;
+  p.row_tiles = (na + 128 * p.RB - 1) / (128 * p.RB);
+  const int64_t col_steps = std::max<int64_t>(1, (nb + 63) / 64);
+  int64_t ns = std::max<int64_t>(1, 256 / p.row_tiles);
+  ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
+  ns = std::min<int64_t>(ns, 16);
+  p.nsplit = (int)ns;
+  const int64_t steps_per_split = (col_steps + ns - 1) / ns;
+  p.cols_per_split = steps_per_split * 64;
+  int64_t nph = (p.rg + ns - 1) / ns;
+  nph = std::max<int64_t>(1, std::min(nph, steps_per_split));
+  p.nphase = (int)nph;
+  p.cols_per_phase = (steps_per_split + nph - 1) / nph * 64;
+  p.g_raw = 64 * p.nsplit * p.nphase;
+  size_t o = up256((size_t)na * p.nsplit * p.cap * sizeof(u64));
+  p.o_minima = o; o += up256((size_t)na * p.g_raw * sizeof(float));
+  p.o_tau = o; o += up256((size_t)na * sizeof(float));
+  p.o_cnt = o; o += up256((size_t)na * p.nsplit * sizeof(int));
+  p.bytes = o;
+  return p;
+}
+}  // namespace
 
 size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out) {
-  const int kp = mfma_knn_kp(k);
-  const int BM = kp <= 64 ? 64 : 32;
-  const int64_t row_tiles = (na + BM - 1) / BM;
-  const int64_t col_steps = (nb + 255) / 256;
-  int64_t nsplit = std::max<int64_t>(1, (768 + row_tiles - 1) / row_tiles);
-  nsplit = std::min(nsplit, col_steps);
-  nsplit = std::min<int64_t>(nsplit, 64);
-  *nsplit_out = (int)nsplit;
-  return (size_t)na * nsplit * kp * sizeof(u64);
+  const MfmaPlan p = make_plan(na, nb, k);
+  *nsplit_out = p.nsplit;
+  return p.bytes;
 }
 
-template <int KSTEPS, int RB, int R, int METRIC>
-static void launch_mfma_t(const MfmaOperand& A, const MfmaOperand& B, int nsplit, int kp,
-                          u64* shortlist, hipStream_t st) {
-  constexpr int BM = 32 * RB;
-  const int cap = 64 * R;
-  const size_t shmem = (size_t)BM * (256 + 4) * sizeof(float) + (size_t)BM * cap * sizeof(u64) +
-                       (size_t)BM * (sizeof(u64) + sizeof(int)) + 16;
-  auto kern = &mfma_knn_kernel<KSTEPS, RB, R, METRIC>;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-  const int64_t row_tiles = (A.n + BM - 1) / BM;
-  const int64_t col_steps = (B.n + 255) / 256;
-  const int64_t cols_per_split = (col_steps + nsplit - 1) / nsplit * 256;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(row_tiles * nsplit)), dim3(256), shmem, st, A.hi, A.lo,
-                     A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, nsplit, cols_per_split, kp,
-                     cap, shortlist);
+template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
+static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
+                           hipStream_t st) {
+  constexpr int D = KSTEPS * 16, NPL = THREE ? 2 : 1;
+  const size_t shmem = (size_t)2 * NPL * 64 * (D + 8) * sizeof(unsigned short) + 2 * 64 * sizeof(float) +
+                       (size_t)128 * RB * sizeof(int) + 4 * 128 * (sizeof(u64) + sizeof(int));
+  auto kern = &mfma_sweep_kernel<KSTEPS, RB, METRIC, MODE, THREE>;
+  if (shmem > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.row_tiles * p.nsplit)), dim3(256), shmem, st, A.hi, A.lo,
+                     A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
+                     p.nphase, p.cols_per_phase, reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
+                     reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
+                     reinterpret_cast<u64*>(work), p.cap);
 }
 
-template <int KSTEPS, int METRIC>
-static void launch_mfma_k(const MfmaOperand& A, const MfmaOperand& B, int nsplit, int kp,
-                          u64* shortlist, hipStream_t st) {
-  if (kp <= 64) launch_mfma_t<KSTEPS, 2, 2, METRIC>(A, B, nsplit, kp, shortlist, st);
-  else          launch_mfma_t<KSTEPS, 1, 4, METRIC>(A, B, nsplit, kp, shortlist, st);
+template <int KSTEPS, int METRIC, int MODE>
+static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
+                           hipStream_t st) {
+  // both operand-precision variants are enqueued; the kernel that does not match the flags
+  // written by operand preparation returns immediately (the flags live in device memory)
+  if (p.RB == 2) {
+    launch_sweep_t<KSTEPS, 2, METRIC, MODE, false>(p, A, B, work, st);
+    launch_sweep_t<KSTEPS, 2, METRIC, MODE, true>(p, A, B, work, st);
+  } else {
+    launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
+    launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
+  }
 }
 
-void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
-                           int nsplit, u64* shortlist, hipStream_t st) {
-  const int kp = mfma_knn_kp(k);
-#define GO(KS)                                                                     \
-  do {                                                                             \
-    if (metric == 0) launch_mfma_k<KS, 0>(A, B, nsplit, kp, shortlist, st);        \
-    else             launch_mfma_k<KS, 1>(A, B, nsplit, kp, shortlist, st);        \
+template <int MODE>
+static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
+                         int metric, char* work, hipStream_t st) {
+#define GO(KS)                                                                      \
+  do {                                                                              \
+    if (metric == 0) launch_sweep_k<KS, 0, MODE>(p, A, B, work, st);                \
+    else             launch_sweep_k<KS, 1, MODE>(p, A, B, work, st);                \
   } while (0)
   switch (d / 16) {
     case 2: GO(2); break;
@@ -475,16 +667,38 @@ void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, in
 #undef GO
 }
 
+void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
+                           int nsplit, u64* shortlist, hipStream_t st) {
+  (void)nsplit;
+  const MfmaPlan p = make_plan(A.n, B.n, k);
+  char* work = reinterpret_cast<char*>(shortlist);
+  launch_sweep<0>(p, A, B, d, metric, work, st);
+  const dim3 grid((unsigned)((A.n + 3) / 4)), block(256);
+  float* tau = reinterpret_cast<float*>(work + p.o_tau);
+  const float* minima = reinterpret_cast<const float*>(work + p.o_minima);
+  switch (p.rg) {
+    case 1: hipLaunchKernelGGL((tau_kernel<1>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
+    case 2: hipLaunchKernelGGL((tau_kernel<2>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
+    case 4: hipLaunchKernelGGL((tau_kernel<4>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
+    default: hipLaunchKernelGGL((tau_kernel<8>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
+  }
+  launch_sweep<1>(p, A, B, d, metric, work, st);
+}
+
 void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k, int nsplit,
                    const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
                    int* fb_rows, hipStream_t st) {
-  const int kp = mfma_knn_kp(k);
+  (void)nsplit;
+  const MfmaPlan p = make_plan(A.n, B.n, k);
+  const int kp = p.kp;
+  const int* cnt = reinterpret_cast<const int*>(reinterpret_cast<const char*>(shortlist) + p.o_cnt);
   hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, fb_count);
   const int R = kp <= 64 ? 2 : 4;
   const size_t sh = (size_t)64 * R * sizeof(u64) + (size_t)d * sizeof(float);
 #define RR(RV, MET)                                                                               \
-  hipLaunchKernelGGL((rerank_kernel<RV, MET>), dim3((unsigned)A.n), dim3(64), sh, st, shortlist, nsplit, \
-                     kp, A.x, B.x, d, k, A.norm, A.info, B.info, eps_scale, out, fb_count, fb_rows)
+  hipLaunchKernelGGL((rerank_kernel<RV, MET>), dim3((unsigned)A.n), dim3(64), sh, st, shortlist,  \
+                     cnt, p.nsplit, p.cap, kp, A.x, B.x, d, k, A.norm, A.info, B.info, eps_scale, out, \
+                     fb_count, fb_rows)
   if (R == 2) { if (metric == 0) RR(2, 0); else RR(2, 1); }
   else        { if (metric == 0) RR(4, 0); else RR(4, 1); }
 #undef RR
