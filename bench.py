@@ -35,7 +35,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C3", "C2"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C3", "C2", "C4", "C5"])
     ap.add_argument("--nprobe", type=int, default=None)
     ap.add_argument("--nb", type=int, default=None, help="override database size (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -74,20 +74,31 @@ def main():
     if args.nprobe and "nprobe" in cfg:
         cfg["nprobe"] = args.nprobe
     t0 = time.time()
-    x, q = S.make_data(cfg)
-    log("data %s: x %s q %s in %.1fs" % (args.workload, x.shape, q.shape, time.time() - t0))
-    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    big = cfg["nb"] * cfg["d"] * 4 > (8 << 30)       # generated on the device, added in pieces
+    if big:
+        xd, qd = S.make_data_device(cfg)
+        torch.cuda.synchronize()
+        x, q = None, qd.cpu().numpy()
+    else:
+        x, q = S.make_data(cfg)
+        xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    log("data %s: x %s q %s in %.1fs" % (args.workload, tuple(xd.shape), q.shape, time.time() - t0))
     nq, k, metric = cfg["nq"], cfg["k"], cfg["metric"]
 
     if args.workload == "C2":
         return bench_flat(args, cfg, x, q, xd, qd)
 
-    cent, cb = S.make_index_params(cfg, x)
+    cent, cb = S.make_index_params_device(cfg, xd) if big else S.make_index_params(cfg, x)
     ix = vs.IVFPQ(cfg["d"], metric, torch.from_numpy(cent).cuda(), torch.from_numpy(cb).cuda(),
                   cfg["nbits"])
     torch.cuda.synchronize()
     t0 = time.time()
-    ix.add(xd)
+    piece = 10_000_000
+    for s0 in range(0, cfg["nb"], piece):
+        ix.add(xd[s0:s0 + piece])
+        if big:
+            torch.cuda.synchronize()
+            log("  added %d / %d (%.1fs)" % (min(s0 + piece, cfg["nb"]), cfg["nb"], time.time() - t0))
     torch.cuda.synchronize()
     t_add = time.time() - t0
     log("index built: ntotal=%d in %.2fs" % (ix.ntotal, t_add))
@@ -126,11 +137,12 @@ def main():
     achieved = algo_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
 
     # accuracy against exact search (GPU flat search, itself checked against the oracle by the tests)
-    Dg, Ig = vs.vs_flat_search(xd, qd, k, metric)
+    nrec = nq if not big else 1000                    # exact search over 1e8 rows: first 1000 queries
+    Dg, Ig = vs.vs_flat_search(xd, qd[:nrec].contiguous(), k, metric)
     torch.cuda.synchronize()
     I_h, Ig_h = I.cpu().numpy(), Ig.cpu().numpy()
-    hit_k = np.mean([len(set(I_h[a].tolist()) & set(Ig_h[a].tolist())) / float(k) for a in range(nq)])
-    hit_1 = np.mean([Ig_h[a, 0] in I_h[a] for a in range(nq)])
+    hit_k = np.mean([len(set(I_h[a].tolist()) & set(Ig_h[a].tolist())) / float(k) for a in range(nrec)])
+    hit_1 = np.mean([Ig_h[a, 0] in I_h[a] for a in range(nrec)])
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -142,8 +154,9 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: IVF%d,PQ%dx%d L2, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
-            args.workload, cfg["nlist"], cfg["M"], cfg["nbits"], cfg["nb"], cfg["d"], nq, k, nprobe),
+        "config": {"workload": "%s: IVF%d,PQ%dx%d %s, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
+            args.workload, cfg["nlist"], cfg["M"], cfg["nbits"], "IP" if metric else "L2", cfg["nb"],
+            cfg["d"], nq, k, nprobe),
             "nprobe": nprobe, "k": k, "recall_k_at_k": round(float(hit_k), 4),
             "recall_1_at_k": round(float(hit_1), 4), "scanned_codes_per_query": scanned / nq,
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),

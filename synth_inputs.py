@@ -134,3 +134,58 @@ def make_index_params(cfg, x):
     cent = make_centroids(x, cfg["nlist"], cfg["seed"])
     cb = make_codebooks(x, cent, cfg["M"], cfg["nbits"], cfg["seed"])
     return cent, cb
+
+
+# ---- on-device generation for the configurations too large for host memory ------
+# Same recipes as above, drawn with torch's generator ON THE DEVICE in chunks; the bytes that
+# reach the oracle are copied back from these tensors (CPU and GPU random streams are not
+# interchangeable, so the data are generated once and shared).
+
+def make_data_device(cfg, device="cuda", chunk=4_000_000):
+    """Returns (x [nb, d], q [nq, d]) fp32 torch tensors on `device` (kind 'unit' only)."""
+    import torch
+    assert cfg["kind"] == "unit"
+    g = torch.Generator(device=device)
+    g.manual_seed(cfg["seed"])
+    nb, nq, d = cfg["nb"], cfg["nq"], cfg["d"]
+    centres = torch.randn((cfg["ncomp"], d), generator=g, device=device, dtype=torch.float32)
+
+    def draw(n):
+        out = torch.empty((n, d), device=device, dtype=torch.float32)
+        for s in range(0, n, chunk):
+            e = min(n, s + chunk)
+            comp = torch.randint(0, cfg["ncomp"], (e - s,), generator=g, device=device)
+            v = centres[comp]
+            v += cfg["sigma"] * torch.randn((e - s, d), generator=g, device=device, dtype=torch.float32)
+            v /= v.norm(dim=1, keepdim=True).clamp_min(1e-30)
+            out[s:e] = v
+        return out
+
+    x = draw(nb)
+    if "query_noise" in cfg:
+        pick = torch.randint(0, nb, (nq,), generator=g, device=device)
+        q = x[pick] + cfg["query_noise"] * torch.randn((nq, d), generator=g, device=device, dtype=torch.float32)
+        q /= q.norm(dim=1, keepdim=True).clamp_min(1e-30)
+    else:
+        q = draw(nq)
+    return x, q
+
+
+def make_index_params_device(cfg, x):
+    """Centroids / codebooks for a device-resident x: the sampled rows are copied to the
+    host and go through the same numpy recipe.  Returns numpy arrays."""
+    import torch
+    rng = np.random.default_rng(cfg["seed"] + 7919)
+    rows = np.sort(rng.choice(cfg["nb"], cfg["nlist"], replace=False))
+    cent = x[torch.from_numpy(rows).to(x.device)].cpu().numpy()
+    K = 1 << cfg["nbits"]
+    rng2 = np.random.default_rng(cfg["seed"] + 104729)
+    rows2 = np.sort(rng2.choice(cfg["nb"], K, replace=False))
+    sample = x[torch.from_numpy(rows2).to(x.device)].cpu().numpy()
+    d, M = cfg["d"], cfg["M"]
+    c64 = cent.astype(np.float64)
+    s64 = sample.astype(np.float64)
+    d2 = (s64 ** 2).sum(1)[:, None] - 2.0 * s64 @ c64.T + (c64 ** 2).sum(1)[None, :]
+    res = (s64 - c64[d2.argmin(axis=1)]).astype(np.float32)
+    cb = np.ascontiguousarray(res.reshape(K, M, d // M).transpose(1, 0, 2))
+    return np.ascontiguousarray(cent), cb
