@@ -307,3 +307,65 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
     Do, Io = oracle.flat_search(x, q, min(k + EXTRA, max(nb, k)), metric)
     xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
     check_search(Dm, Im, Do, Io, metric, q, xn)
+
+
+# ------------------------------------------------- the two largest configurations
+
+def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
+    """Full-size C4 / C5: data are drawn on the device; the oracle checks list assignment
+    and PQ codes bit-exactly on a seeded sample of the database, then searches the GPU-built
+    store (copied to the host) for a seeded sample of the queries."""
+    import torch
+    cfg = S.config(name)
+    say("%s full size: nb=%d d=%d nlist=%d M=%d nbits=%d metric=%d" % (
+        name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"], cfg["nbits"], cfg["metric"]))
+    xd, qd = S.make_data_device(cfg)
+    cent, cb = S.make_index_params_device(cfg, xd)
+    ix = vs.IVFPQ(cfg["d"], cfg["metric"], dev(cent), dev(cb), cfg["nbits"])
+    piece = 10_000_000
+    for s0 in range(0, cfg["nb"], piece):
+        ix.add(xd[s0:s0 + piece])
+        say("  added %d" % min(s0 + piece, cfg["nb"]))
+    assert ix.ntotal == cfg["nb"]
+    ids, list_of = ix.assignments()
+    sizes = host(ix.list_sizes())
+    assert sizes.sum() == cfg["nb"]
+    rng = np.random.default_rng(7)
+    sample = np.sort(rng.choice(cfg["nb"], n_sample, replace=False))
+    xs = xd[torch.from_numpy(sample).cuda()].cpu().numpy()
+    say("  oracle assign + encode on %d sampled vectors" % n_sample)
+    lo = oracle.assign(xs, cent, cfg["metric"])
+    co = oracle.pq_encode(xs, lo, cent, cb, cfg["nbits"])
+    # storage position of every id (ids are sequential): invert on the device
+    pos = torch.empty(cfg["nb"], dtype=torch.int64, device="cuda")
+    pos[ids] = torch.arange(cfg["nb"], dtype=torch.int64, device="cuda")
+    ps = pos[torch.from_numpy(sample).cuda()]
+    np.testing.assert_array_equal(host(list_of[ps]), lo)
+    codes_d = ix.codes()
+    np.testing.assert_array_equal(host(codes_d[ps]), co)
+    del pos, ps
+    offsets = np.zeros(cfg["nlist"] + 1, dtype=np.int64); np.cumsum(sizes, out=offsets[1:])
+    orc = oracle.OracleIVFPQ.from_storage(cfg["d"], cfg["metric"], cent, cb, cfg["nbits"], offsets,
+                                          host(codes_d), host(ids))
+    del codes_d
+    q = host(qd)
+    qs = np.sort(rng.choice(cfg["nq"], n_queries, replace=False))
+    xn = 1.5      # unit-norm data (decoded vectors are close to unit norm)
+    for k, nprobe in searches:
+        say("  search all %d queries k=%d nprobe=%d; oracle on %d of them" % (cfg["nq"], k, nprobe, qs.size))
+        probes, cdist = ix.coarse(qd, nprobe)
+        po, co_ = oracle.coarse_probe(q[qs], cent, nprobe, cfg["metric"])
+        np.testing.assert_array_equal(host(probes)[qs], po)
+        np.testing.assert_array_equal(host(cdist)[qs], co_)
+        D, I = ix.search(qd, k, nprobe)
+        Do, Io = orc.search(q[qs], k + EXTRA, nprobe)
+        check_search(host(D)[qs], host(I)[qs], Do, Io, cfg["metric"], q[qs], xn)
+    ix.close()
+
+
+def test_c4_full_size_sampled(vs, oracle):
+    _large_config_sampled(vs, oracle, "C4", 1500, 100, [(100, 64)])
+
+
+def test_c5_full_size_sampled(vs, oracle):
+    _large_config_sampled(vs, oracle, "C5", 500, 100, [(10, 32)])
