@@ -325,7 +325,7 @@ __device__ unsigned long long g_scan_cycles[8];
 #define TICK(slot) do {} while (0)
 #endif
 
-template <int M, int DSUB, int METRIC, int R>
+template <int M, int DSUB, int METRIC, int R, int NBUF>
 __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     const float* __restrict__ q, const float* __restrict__ centroids,
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
@@ -338,8 +338,8 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
   u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
-  float* lut0 = reinterpret_cast<float*>(bound + 2);            // 2 x M * K (double buffer)
-  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + 2 * M * K);  // ppb
+  float* lut0 = reinterpret_cast<float*>(bound + 2);            // NBUF x M * K
+  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + NBUF * M * K);  // ppb
   int64_t* s_end = s_begin + ppb;                               // ppb
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
 
@@ -416,7 +416,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     }
     TICK(1);
     for (int p = 0; p < np; ++p) {
-      float* __restrict__ lut = METRIC == 0 ? lut0 + (p & 1) * (M * K) : lut0;
+      float* __restrict__ lut = (METRIC == 0 && NBUF == 2) ? lut0 + (p & 1) * (M * K) : lut0;
       const int64_t end = s_end[p];
       // requests for the next iteration (the last iteration re-requests its own list)
       const int pn = min(p + 1, np - 1);
@@ -431,6 +431,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
         float r[DSUB];
 #pragma unroll
         for (int u = 0; u < DSUB; ++u) r[u] = qm[u] - cm[u];
+        if (NBUF == 1 && p > 0) block_sync_lds();   // single table: scan p - 1 finished everywhere
 #pragma unroll
         for (int i = 0; i < M; ++i) {
           float acc = 0.f;
@@ -569,15 +570,15 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
                      nlist, sizes);
 }
 
-template <int M, int DSUB, int METRIC, int R>
+template <int M, int DSUB, int METRIC, int R, int NBUF>
 static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
                             const uint8_t* codes, int64_t ntotal, int k, int tot, KeySink sink,
                             hipStream_t st) {
-  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)2 * M * 256 * sizeof(float) +
+  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * 256 * sizeof(float) +
                        (size_t)ppb * 20 + 16;
-  auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R>;
+  auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -598,12 +599,15 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
                                 int64_t ntotal, int k, int tot, KeySink sink, hipStream_t st) {
-#define GO(MET, RR)                                                                               \
-  launch_scan_reg<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,   \
-                                    nsplit, list_off, codes, ntotal, k, tot, sink, st)
+#define GO(MET, RR, NB)                                                                           \
+  launch_scan_reg<M, DSUB, MET, RR, NB>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
+                                        nsplit, list_off, codes, ntotal, k, tot, sink, st)
   const int r = select_regs_for_slots(tot);
-  if (g.metric == 0) { if (r == 2) GO(0, 2); else if (r == 4) GO(0, 4); else GO(0, 0); }
-  else               { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
+  // L2 tables alternate between two buffers (one barrier per list); the single inner-product
+  // table needs one.  A single L2 table with a third resident workgroup per CU measured
+  // slower at 1500-code lists: the 168-register budget it needs spills the codebook.
+  if (g.metric == 1)  { if (r == 2) GO(1, 2, 1); else if (r == 4) GO(1, 4, 1); else GO(1, 0, 1); }
+  else                { if (r == 2) GO(0, 2, 2); else if (r == 4) GO(0, 4, 2); else GO(0, 0, 2); }
 #undef GO
 }
 
@@ -638,7 +642,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)g.d * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
-  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + (size_t)ppb * 20 + 32;
+  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + (size_t)ppb * 20 + 32;  // two tables
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \

@@ -133,6 +133,10 @@ IVF_CASES = {
     "c5_small": (S.config("C5", nb=20_000, nq=100, ncomp=50, nlist=128), [(10, 32), (100, 128)]),
     "pq4_l2": (S.config("C1", nb=5_000, M=16, nbits=4), [(10, 4)]),
     "ip_8bit": (S.config("C4", nb=20_000, nq=64, ncomp=40, nlist=64, metric=1, M=8), [(10, 8)]),
+    # long lists (>= 1024 codes per list on average): the single-table scan variant
+    "c4_long_lists": (S.config("C4", nb=40_000, nq=100, ncomp=100, nlist=32), [(100, 8), (10, 32)]),
+    "c3_long_lists": (S.config("C3", nb=40_000, nq=100, ncomp=100, nlist=16), [(10, 4)]),
+    "c1_long_lists": (S.config("C1", nb=20_000, nlist=8), [(10, 3), (500, 8)]),
     "odd_shapes": (S.config("C1", nb=3_001, nq=33, d=30, M=5, nlist=7), [(10, 3), (300, 7)]),
 }
 
