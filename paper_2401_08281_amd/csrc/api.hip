@@ -150,6 +150,7 @@ KnnPlan knn_plan(int64_t na, int64_t nb, int d, int k, bool b_prepared) {
     if (!b_prepared) b += planes_bytes(nb, d);
     b += align_up(mfma_knn_shortlist_bytes(na, nb, k, &p.nsplit));
     b += align_up(sizeof(int)) + align_up((size_t)na * sizeof(int));
+    b += align_up(mfma_knn_fallback_bytes(na, nb, k));
     p.bytes = b;
   } else {
     tile_shape(na, std::max<int64_t>(nb, 1), &p.rows, &p.cols);
@@ -171,7 +172,8 @@ void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const fl
     const size_t sl = align_up(mfma_knn_shortlist_bytes(na, nb, k, &ns));
     u64* shortlist = reinterpret_cast<u64*>(ws + o); o += sl;
     int* fb_count = reinterpret_cast<int*>(ws + o); o += align_up(sizeof(int));
-    int* fb_rows = reinterpret_cast<int*>(ws + o);
+    int* fb_rows = reinterpret_cast<int*>(ws + o); o += align_up((size_t)na * sizeof(int));
+    u64* fb_partial = reinterpret_cast<u64*>(ws + o);
     const MfmaOperand oa = operand(A, na, pa), ob = operand(B, nb, pb);
     {
       StageTimer t(stage_dist, st);
@@ -182,7 +184,7 @@ void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const fl
     {
       StageTimer t(stage_select, st);
       launch_rerank(oa, ob, d, metric, k, plan.nsplit, shortlist, g_knn_eps_scale.load(), out,
-                    fb_count, fb_rows, st);
+                    fb_count, fb_rows, fb_partial, st);
     }
     g_knn_mfma_rows += na;
     return;

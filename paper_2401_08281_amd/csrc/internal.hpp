@@ -69,7 +69,7 @@ struct PrepInfo {
   u32 all_int;        // every value is an integer
   u32 all_bf16;       // every value is exactly representable in bf16
   u32 max_norm_bits;  // bits of the largest squared row norm (non-negative float)
-  u32 pad;
+  u32 all_nonneg;     // no value is negative
 };
 struct MfmaOperand {
   const float* x;             // [n, d] original fp32 rows
@@ -90,8 +90,10 @@ size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out);
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
                            int nsplit, u64* shortlist, hipStream_t st);
 // exact k best per row of A from the shortlists; rows that cannot be proven exact are
-// recomputed over all of B.  fb_count: 1 int, fb_rows: A.n ints (device scratch).
+// recomputed over all of B.  fb_count: 1 int, fb_rows: A.n ints, fb_partial:
+// mfma_knn_fallback_bytes(...) bytes (device scratch; may be null when that is 0).
+size_t mfma_knn_fallback_bytes(int64_t na, int64_t nb, int k);
 void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k, int nsplit,
                    const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
-                   int* fb_rows, hipStream_t st);
+                   int* fb_rows, u64* fb_partial, hipStream_t st);
 int read_fallback_total(unsigned long long* out);

@@ -11,12 +11,14 @@
 // every bit-exact decision of the library is defined in) and the k best of those
 // are returned.  A row's answer is provably the canon answer when
 //     t' - eps > v_k        (L2; mirrored for the inner product)
-// where t' is the kp-th best approximate value (every row outside the shortlist
-// is at least that far), v_k the k-th best canon value inside it, and eps a
-// bound on |approximate - canon| for that row.  Rows that fail the test are
+// where t' is a lower bound on the approximate value of every row that was not
+// re-ranked (the listing threshold, or the kp-th best listed value when more than
+// kp rows were listed), v_k the k-th best canon value inside the shortlist, and
+// eps a bound on |approximate - canon| for that row.  Rows that fail the test are
 // recomputed by canon_rows_kernel over all columns, so the output never depends
 // on the approximation.
 #include <algorithm>
+#include <cmath>
 
 #include "common.hpp"
 #include "internal.hpp"
@@ -52,15 +54,15 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
                                                    float* __restrict__ norm,
                                                    PrepInfo* __restrict__ info) {
   __shared__ float part[256];
-  __shared__ u32 flags[2];
+  __shared__ u32 flags[3];
   const int cpr = d / 8;                               // chunks per row
   const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
   const int tid = threadIdx.x;
-  if (tid < 2) flags[tid] = 1u;
+  if (tid < 3) flags[tid] = 1u;
   __syncthreads();
   const int r = tid / cpr, c = tid - r * cpr;
   float ss = 0.f;
-  bool is_int = true, is_bf16 = true;
+  bool is_int = true, is_bf16 = true, is_nonneg = true;
   if (r < rows_per_block && row0 + r < n) {
     const int64_t off = (row0 + r) * d + c * 8;
     float v[8];
@@ -75,6 +77,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
       l[t] = bf16_rn_bits(rem);
       is_bf16 = is_bf16 && rem == 0.f;
       is_int = is_int && v[t] == __builtin_rintf(v[t]);
+      is_nonneg = is_nonneg && v[t] >= 0.f;
       ss = __builtin_fmaf(v[t], v[t], ss);
     }
     uint4 hv, lv;
@@ -94,6 +97,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
   part[tid] = ss;
   if (!is_int) flags[0] = 0u;
   if (!is_bf16) flags[1] = 0u;
+  if (!is_nonneg) flags[2] = 0u;
   __syncthreads();
   if (tid < rows_per_block && row0 + tid < n) {
     float s = 0.f;
@@ -106,11 +110,12 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
   if (tid == 0) {
     if (!flags[0]) atomicAnd(&info->all_int, 0u);
     if (!flags[1]) atomicAnd(&info->all_bf16, 0u);
+    if (!flags[2]) atomicAnd(&info->all_nonneg, 0u);
   }
 }
 
 __global__ void prep_info_init_kernel(PrepInfo* info) {
-  info->all_int = 1u; info->all_bf16 = 1u; info->max_norm_bits = 0u; info->pad = 0u;
+  info->all_int = 1u; info->all_bf16 = 1u; info->max_norm_bits = 0u; info->all_nonneg = 1u;
 }
 
 // ---------------------------------------------------------------------------
@@ -129,22 +134,27 @@ __global__ void prep_info_init_kernel(PrepInfo* info) {
 //   MODE 0 (minima): every accumulator position keeps the minimum of its values
 //     m = |x|^2 - 2<q,x> (L2) or m = -<q,x> (IP) over a phase of the sweep and writes
 //     it out at the end of the phase: a row gets G group minima, each attained by a
-//     different column.
-//   tau kernel: tau(row) = kp-th smallest group minimum, so at least kp columns of the
-//     row have m <= tau -- and, the groups being large, not many more.
-//   MODE 1 (collect): the tiles are recomputed (bit-identical) and every column with
-//     m <= tau(row) is appended to the row's candidate list.
-// The matrix cores do the contraction twice; they are far from being the limit here.
-// Every column that is NOT listed has m > tau >= (kp-th smallest listed m), which is
-// what the re-rank kernel's sufficiency test needs.
+//     different column.  When B is long this sweep computes every S-th row of B only.
+//   tau kernel: tau(row) = r-th smallest group minimum, so at least r columns of the
+//     row have m <= tau.  With S = 1, r = kp.  With S > 1 the minima describe a 1/S
+//     sample of the columns and r is chosen so that about r * S columns, and very
+//     probably at least k, lie below tau; nothing is assumed about that number --
+//     the re-rank test catches rows with too few or too many.
+//   MODE 1 (collect): every tile is computed, with the accumulators started at the row
+//     thresholds so that "m <= tau(row)" is a comparison of the finished accumulator with
+//     a per-column number; every column that passes is appended to the row's list.  The
+//     test is the same inequality as MODE 0's m, evaluated in a different rounding order.
+// Every column that is NOT listed has m > tau, which is what the re-rank kernel's
+// sufficiency test needs.
 // ---------------------------------------------------------------------------
 template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, 2)
 void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
                        const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
                        const unsigned short* __restrict__ Bhi, const unsigned short* __restrict__ Blo,
                        const float* __restrict__ Bnorm, const PrepInfo* __restrict__ Binfo, int64_t nb,
-                       int nsplit, int64_t cols_per_split, int nphase, int64_t cols_per_phase,
+                       int nsplit, int64_t cols_per_split, int stride, int nphase,
+                       int64_t cols_per_phase,
                        float* __restrict__ minima, int g_raw,       // MODE 0 out: [na][g_raw]
                        const float* __restrict__ tau,               // MODE 1 in:  [na]
                        int* __restrict__ cnt, u64* __restrict__ shortlist, int cap) {  // MODE 1 out
@@ -172,6 +182,10 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   const int64_t row0 = rt * (128 * RB) + wave * (32 * RB);        // this wavefront's first row
   const int64_t c_begin = (int64_t)split * cols_per_split;
   const int64_t c_end = min(nb, c_begin + cols_per_split);
+  // A step covers 64 * stride rows of B and computes every stride-th of them (stride = 1:
+  // all of them).  Rows past the padded end of B are read from its last row and masked.
+  const int64_t col_step = (int64_t)BN * stride;
+  const int64_t b_last = (nb + 63) / 64 * 64 - 1;
 
   // A fragments: lane holds row (l % 32) of each 32-row block, dims 8 * (l / 32) .. + 7 of each k-step
   bf16x8 ah[RB][KSTEPS], al[THREE ? RB : 1][THREE ? KSTEPS : 1];
@@ -185,40 +199,56 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
       if constexpr (THREE) al[rb][kk] = *reinterpret_cast<const bf16x8*>(Alo + off);
     }
   }
-  // per accumulator register: running minimum (MODE 0) or threshold and |q|^2 (MODE 1)
-  float mn[RB][2][16], tr[RB][16], an[RB][16];
+  // Per accumulator register: running minimum (MODE 0), or (MODE 1) the threshold in the
+  // units of the contraction: m <= tau  <=>  <q,x> + tau / s >= b / s  with s = 2 (L2:
+  // m = |x|^2 - 2 <q,x>, b = |x|^2) or s = 1 (IP: m = -<q,x>, b = 0).  The collect sweep
+  // starts every accumulator at tau / s instead of 0, so its test is one comparison of the
+  // finished accumulator with the column's b / s and costs no arithmetic per element.
+  constexpr float INV_S = METRIC == 0 ? 0.5f : 1.f;
+  float mn[RB][2][16];
+  floatx16 tr[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int64_t r = min(row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), na - 1);
-      tr[rb][v] = MODE == 1 ? tau[r] : 0.f;
-      an[rb][v] = (MODE == 1 && METRIC == 0) ? Anorm[r] : 0.f;
+      tr[rb][v] = MODE == 1 ? tau[r] * INV_S : 0.f;
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) mn[rb][cb][v] = __builtin_inff();
     }
 
   // global -> registers -> LDS staging of one 64-row B tile (spelled as macros so that the
-  // staging registers stay registers).  B planes are padded to a multiple of 64 rows, so a
-  // tile is one contiguous block of memory: lane offsets are fixed 32-bit numbers.
+  // staging registers stay registers).  B planes are padded to a multiple of 64 rows; tile
+  // row r is row CT + r * stride of B.
   u32x4 stg[NPL][CPT];
   float stn = 0.f;
-  int g_off[CPT], l_off[CPT];
+  int g_row[CPT], g_col[CPT], g_lin[CPT], l_off[CPT];
 #pragma unroll
   for (int i = 0; i < CPT; ++i) {
-    const int ch = tid + 256 * i;
-    g_off[i] = ch * 8;                                            // chunk ch of the tile, in elements
+    const int ch = tid + 256 * i;                                 // chunk ch of the tile
+    g_lin[i] = ch * 8;
+    g_row[i] = (ch / (D / 8)) * stride;
+    g_col[i] = (ch % (D / 8)) * 8;
     l_off[i] = (ch / (D / 8)) * LDB + (ch % (D / 8)) * 8;
   }
 #define FETCH_TILE(CT)                                                                           \
   do {                                                                                           \
-    const unsigned short* __restrict__ th_ = Bhi + (CT) * D;                                     \
-    const unsigned short* __restrict__ tl_ = Blo + (CT) * D;                                     \
-    _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                         \
-      stg[0][i_] = *reinterpret_cast<const u32x4*>(th_ + g_off[i_]);                             \
-      if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(tl_ + g_off[i_]);  \
-    }                                                                                            \
-    stn = Bnorm[(CT) + (tid & 63)];               /* consumed only when the tile is stashed */  \
+    if constexpr (MODE == 1) {   /* every row: the tile is one contiguous block of memory */     \
+      const unsigned short* __restrict__ th_ = Bhi + (CT) * D;                                   \
+      const unsigned short* __restrict__ tl_ = Blo + (CT) * D;                                   \
+      _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                       \
+        stg[0][i_] = *reinterpret_cast<const u32x4*>(th_ + g_lin[i_]);                           \
+        if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(tl_ + g_lin[i_]); \
+      }                                                                                          \
+      stn = Bnorm[(CT) + (tid & 63)];                                                            \
+    } else {                                                                                     \
+      _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                       \
+        const int64_t o_ = min((CT) + g_row[i_], b_last) * D + g_col[i_];                        \
+        stg[0][i_] = *reinterpret_cast<const u32x4*>(Bhi + o_);                                  \
+        if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(Blo + o_);       \
+      }                                                                                          \
+      stn = Bnorm[min((CT) + (int64_t)(tid & 63) * stride, b_last)];                             \
+    }                                             /* stn is consumed only at the stash */        \
   } while (0)
 #define STASH_TILE(BUF, CT)                                                                      \
   do {                                                                                           \
@@ -227,7 +257,9 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
         *reinterpret_cast<u32x4*>(bt + ((BUF) * NPL + pl_) * BN * LDB + l_off[i_]) = stg[pl_][i_]; \
     }                                                                                            \
     if (tid < BN)                                                                                \
-      bns[(BUF) * BN + tid] = (CT) + tid < c_end ? (METRIC == 0 ? stn : 0.f) : __builtin_inff(); \
+      bns[(BUF) * BN + tid] =                                                                    \
+          (CT) + (int64_t)tid * stride < c_end                                                   \
+              ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();        \
   } while (0)
   static_assert(CHUNKS % 256 == 0, "every lane stages the same number of chunks");
 
@@ -251,16 +283,10 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   wait_all_global_loads();   // A fragments, thresholds and norms are in registers from here on
   block_sync_lds();
   int buf = 0;
-  for (int64_t ct = c_begin; ct < c_end; ct += BN, buf ^= 1) {
-    const bool more = ct + BN < c_end;
-    if (more) FETCH_TILE(ct + BN);                                // in flight during the MFMAs
+  for (int64_t ct = c_begin; ct < c_end; ct += col_step, buf ^= 1) {
+    const bool more = ct + col_step < c_end;
+    if (more) FETCH_TILE(ct + col_step);                          // in flight during the MFMAs
     floatx16 m[RB][2];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) m[rb][cb][v] = 0.f;
     const unsigned short* __restrict__ bth = bt + (buf * NPL) * BN * LDB;
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
@@ -275,7 +301,9 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bh[cb], m[rb][cb], 0, 0, 0);
+          // the first product starts from 0 (MODE 0) or from the row thresholds (MODE 1)
+          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bh[cb],
+                                                              kk == 0 ? tr[rb] : m[rb][cb], 0, 0, 0);
           if constexpr (THREE) {
             m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bl[cb], m[rb][cb], 0, 0, 0);
             m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], bh[cb], m[rb][cb], 0, 0, 0);
@@ -293,7 +321,7 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
             mn[rb][cb][v] = fminf(mn[rb][cb][v], __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0));
       // end of a phase: flush the group minima (after the last step, also pad the phases left)
       const int ph = (int)((ct - c_begin) / cols_per_phase);
-      const int ph_next = more ? (int)((ct + BN - c_begin) / cols_per_phase) : nphase;
+      const int ph_next = more ? (int)((ct + col_step - c_begin) / cols_per_phase) : nphase;
       for (int p2 = ph; p2 < ph_next; ++p2) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -308,45 +336,46 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
             }
       }
     } else {
+      // b0 / b1 hold b / s here.  Largest accumulator of each 32 x 32 block against the
+      // column's bound: one v_max3 per two elements, one comparison per block.
       bool any[RB][2];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-          any[rb][cb] = false;
+          float mx = m[rb][cb][0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, m[rb][cb][v]);
+          any[rb][cb] = mx >= (cb ? b1 : b0);
+        }
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          if (__ballot(any[rb][cb]) == 0) continue;               // nothing of this 32 x 32 block passes
+          const float hb = cb ? b1 : b0;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            m[rb][cb][v] = __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0);
-            any[rb][cb] = any[rb][cb] || m[rb][cb][v] <= tr[rb][v];
-          }
-        }
-      {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
-            if (__ballot(any[rb][cb]) == 0) continue;             // nothing of this 32 x 32 block passes
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int rl = wave * (32 * RB) + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-              const bool pass = m[rb][cb][v] <= tr[rb][v] && rt * (128 * RB) + rl < na;
-              const u64 mask = __ballot(pass);
-              if (mask != 0) {
-                if (pass) {
-                  const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
-                  // approximate value: |q|^2 + m for L2, <q,x> = -m for IP
-                  const float val = METRIC == 0 ? an[rb][v] + m[rb][cb][v] : -m[rb][cb][v];
-                  qkey[e] = make_key(val, (u32)(ct + cb * 32 + (lane & 31)), METRIC);
-                  qrow[e] = rl;
-                }
-                qn += __popcll(mask);
-                if (qn >= 64) drain(64);
+            const int rl = wave * (32 * RB) + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const bool pass = m[rb][cb][v] >= hb && rt * (128 * RB) + rl < na;
+            const u64 mask = __ballot(pass);
+            if (mask != 0) {
+              if (pass) {
+                const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
+                // approximate value from the accumulator a = tau / s + <q,x>:
+                // L2: |q|^2 + |x|^2 - 2 <q,x> = |q|^2 + 2 (b / s - (a - tau / s));  IP: <q,x>
+                const float dotv = m[rb][cb][v] - tr[rb][v];
+                const float val = METRIC == 0 ? Anorm[rt * (128 * RB) + rl] + 2.f * (hb - dotv) : dotv;
+                qkey[e] = make_key(val, (u32)(ct + cb * 32 + (lane & 31)), METRIC);
+                qrow[e] = rl;
               }
+              qn += __popcll(mask);
+              if (qn >= 64) drain(64);
             }
           }
-      }
+        }
     }
-    if (more) STASH_TILE(buf ^ 1, ct + BN);
+    if (more) STASH_TILE(buf ^ 1, ct + col_step);
     block_sync_lds();
   }
 #undef FETCH_TILE
@@ -374,7 +403,7 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
 }
 
 // tau(row) = kp-th smallest of the row's g_raw group minima (min-combined down to 64 * RG
-// values first), clamped below +inf; also clears the row's candidate count.
+// values first), clamped below +inf.
 template <int RG>
 __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ minima, int g_raw,
                                                   int64_t na, int kp, float* __restrict__ tau) {
@@ -431,9 +460,9 @@ __device__ __forceinline__ float canon_row(const float* __restrict__ qs, const f
 
 template <int R, int METRIC>
 __global__ __launch_bounds__(64) void rerank_kernel(
-    const u64* __restrict__ shortlist, const int* __restrict__ cnt, int nsplit, int cap, int kp,
-    const float* __restrict__ A,
-    const float* __restrict__ B, int d, int k, const float* __restrict__ Anorm,
+    const u64* __restrict__ shortlist, const int* __restrict__ cnt, const float* __restrict__ tau,
+    int nsplit, int cap, int kp, const float* __restrict__ A,
+    const float* __restrict__ B, int64_t nb, int d, int k, const float* __restrict__ Anorm,
     const PrepInfo* __restrict__ Ainfo, const PrepInfo* __restrict__ Binfo, float eps_scale,
     SelectOut out, int* __restrict__ fb_count, int* __restrict__ fb_rows) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -448,10 +477,12 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   WaveSelect<R> ws;
   ws.init(slots, 64 * R, kp);
   bool truncated = false;
+  int64_t total = 0;                                            // columns with m <= tau
   for (int sp = 0; sp < nsplit; ++sp) {
     const u64* __restrict__ src = shortlist + (row * nsplit + sp) * (int64_t)cap;
     const int listed = cnt[row * nsplit + sp];
     truncated = truncated || listed > cap;
+    total += listed;
     const int n = min(listed, cap);
     for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
       const int j = j0 + lane;
@@ -480,21 +511,39 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   const lds_u64_ptr sorted = to_lds(slots);
   const u64 vk = sorted[k - 1];                                 // k-th best canon key
 
-  // is the shortlist provably sufficient?
+  // Is the shortlist provably sufficient?  Every column that is not listed has m > tau, i.e.
+  // an approximate value beyond `ub`; every listed column that was not re-ranked is no better
+  // than the kp-th best approximate key.
   bool ok = true;
-  if (tkey != KEY_EMPTY && vk != KEY_EMPTY) {
+  if (vk == KEY_EMPTY) {
+    ok = total >= nb;                    // fewer than k candidates: right only if every column is listed
+  } else {
     const float na2 = Anorm[row], nb2 = __uint_as_float(Binfo->max_norm_bits);
+    // Integer data exactly representable in bf16: every number the sweeps and this kernel
+    // form is a multiple of 1/2 below 2^23 in magnitude, hence exact, when N = max|q|^2 +
+    // max|x|^2 satisfies 1.5 N < 2^23 (|<q,x>| <= N / 2, |tau| / 2 <= N), or N < 2^23 when
+    // no value is negative (0 <= <q,x>, -|q|^2 <= tau <= |x|^2).
+    const float nsum = __uint_as_float(Ainfo->max_norm_bits) + nb2;
+    const bool nonneg = Ainfo->all_nonneg && Binfo->all_nonneg;
     const bool exact = Ainfo->all_int && Binfo->all_int && Ainfo->all_bf16 && Binfo->all_bf16 &&
-                       (__uint_as_float(Ainfo->max_norm_bits) + nb2 < 16777216.f);
-    const bool three = !(Ainfo->all_bf16 && Binfo->all_bf16);
-    // |approx - canon| <= eps: bf16 head/tail split drops terms below 2^-15 |q||x| per product;
-    // fp32 accumulation and the canon chain each stay below d 2^-22 (|q|^2 + |x|^2)
-    const float coef = (three ? 6.2e-5f : 0.f) + (float)d * 4.8e-7f;
-    const float eps = exact ? 0.f : eps_scale * coef * (na2 + nb2);
-    const float tv = key_value(tkey, METRIC), kv = key_value(vk, METRIC);
-    ok = METRIC == 0 ? (tv - eps > kv) : (tv + eps < kv);
-  } else if (tkey != KEY_EMPTY && vk == KEY_EMPTY) {
-    ok = true;   // cannot happen: kp >= k candidates exist
+                       (nonneg ? nsum < 8388608.f : nsum < 5592405.f);
+    if (!exact) {   // (exact: approximate = canon bit for bit, so the k best listed keys are the answer)
+      const bool three = !(Ainfo->all_bf16 && Binfo->all_bf16);
+      // |approx - canon| <= eps: bf16 head/tail split drops terms below 2^-15 |q||x| per product;
+      // fp32 accumulation and the canon chain each stay below d 2^-22 (|q|^2 + |x|^2); the
+      // collect sweep's own rounding (a few ulps of |tau| / 2 + |<q,x>|) is the last term
+      const float coef = (three ? 6.2e-5f : 0.f) + (float)d * 4.8e-7f + 2e-6f;
+      const float eps = eps_scale * coef * (na2 + nb2);
+      const float tau_v = tau[row];
+      const float ub = METRIC == 0 ? na2 + tau_v : -tau_v;
+      const float kv = key_value(vk, METRIC);
+      float tv = ub;
+      if (total > kp && tkey != KEY_EMPTY) {
+        const float t2 = key_value(tkey, METRIC);
+        tv = METRIC == 0 ? fminf(tv, t2) : fmaxf(tv, t2);
+      }
+      ok = METRIC == 0 ? (tv - eps > kv) : (tv + eps < kv);
+    }
   }
   if (truncated) ok = false;                                    // a candidate list was truncated
   if (eps_scale < 0.f) ok = false;                              // test hook: force the fallback
@@ -512,11 +561,16 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   }
 }
 
-// Canon over ALL columns for the rows listed in fb_rows (persistent workgroups).
+// Canon over ALL columns for the rows listed in fb_rows.  Persistent workgroups walk over
+// (listed row, column chunk) tasks, so that even a single listed row is spread over the
+// chip; with more than one chunk the k best of each chunk go to `partial` as keys and
+// canon_rows_merge_kernel picks the k best of a row's chunks.
 template <int R, int METRIC>
 __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict__ A,
                                                          const float* __restrict__ B, int64_t nb,
-                                                         int d, int k, int tot, SelectOut out,
+                                                         int d, int k, int tot, int64_t chunk_cols,
+                                                         int nchunk, u64* __restrict__ partial,
+                                                         SelectOut out,
                                                          const int* __restrict__ fb_count,
                                                          const int* __restrict__ fb_rows) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -527,25 +581,69 @@ __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict
   const int count = *fb_count;
   if (blockIdx.x == 0 && threadIdx.x == 0 && count > 0)
     atomicAdd(&g_fallback_total, (unsigned long long)count);
-  for (int f = blockIdx.x; f < count; f += gridDim.x) {
+  const int64_t tasks = (int64_t)count * nchunk;
+  for (int64_t task = blockIdx.x; task < tasks; task += gridDim.x) {
+    const int64_t f = task / nchunk;
+    const int ch = (int)(task - f * nchunk);
     const int64_t row = fb_rows[f];
+    const int64_t c_begin = ch * chunk_cols, c_end = min(nb, c_begin + chunk_cols);
     __syncthreads();
     for (int t = threadIdx.x; t < d; t += 256) qs[t] = A[row * d + t];
     WaveSelect<R> ws;
     ws.init(slots + wave * tot, tot, k);
     __syncthreads();
-    for (int64_t c0 = 0; c0 < nb; c0 += 256) {
+    for (int64_t c0 = c_begin; c0 < c_end; c0 += 256) {
       const int64_t c = c0 + threadIdx.x;
-      const bool valid = c < nb;
+      const bool valid = c < c_end;
       const float val = valid ? canon_row<METRIC>(qs, B + c * d, d, vec) : 0.f;
       ws.push(valid, make_key(val, (u32)c, METRIC));
     }
     ws.finish();
     __syncthreads();
     KeySink sink;
-    sink.keys = nullptr; sink.val = out.val; sink.id64 = out.id64; sink.idx32 = out.idx32;
     sink.idmap = nullptr; sink.metric = METRIC;
-    block_rank_merge(slots, tot, 4, k, sink, row * (int64_t)k);
+    if (nchunk == 1) {
+      sink.keys = nullptr; sink.val = out.val; sink.id64 = out.id64; sink.idx32 = out.idx32;
+      block_rank_merge(slots, tot, 4, k, sink, row * (int64_t)k);
+    } else {
+      sink.keys = partial; sink.val = nullptr; sink.id64 = nullptr; sink.idx32 = nullptr;
+      block_rank_merge(slots, tot, 4, k, sink, task * (int64_t)k);
+    }
+  }
+}
+
+// One wavefront per listed row: k best of its nchunk * k partial keys.
+template <int R, int METRIC>
+__global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restrict__ partial,
+                                                              int nchunk, int k, int tot,
+                                                              SelectOut out,
+                                                              const int* __restrict__ fb_count,
+                                                              const int* __restrict__ fb_rows) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // tot
+  const int lane = lane_id();
+  const int count = *fb_count;
+  for (int f = blockIdx.x; f < count; f += gridDim.x) {
+    const int64_t row = fb_rows[f];
+    WaveSelect<R> ws;
+    ws.init(slots, tot, k);
+    const u64* __restrict__ src = partial + (int64_t)f * nchunk * k;
+    const int n = nchunk * k;
+    for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
+      const int j = j0 + lane;
+      const u64 key = j < n ? src[j] : KEY_EMPTY;
+      ws.push(j < n && key != KEY_EMPTY, key);
+    }
+    ws.finish();
+    for (int j = lane; j < k; j += VS_WAVE) {
+      const u64 key = ws.s[j];
+      const bool empty = key == KEY_EMPTY;
+      const int64_t at = row * (int64_t)k + j;
+      if (out.val) out.val[at] = empty ? (METRIC ? -__builtin_inff() : __builtin_inff()) : key_value(key, METRIC);
+      if (out.id64) out.id64[at] = empty ? -1 : (int64_t)key_index(key);
+      if (out.idx32) out.idx32[at] = empty ? -1 : (int32_t)key_index(key);
+    }
+    wave_lds_sync();
   }
 }
 
@@ -579,7 +677,7 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
 
 namespace {
 struct MfmaPlan {
-  int RB, nsplit, nphase, g_raw, rg, kp, cap;
+  int RB, nsplit, nphase, g_raw, rg, kp, kp_tau, stride, cap;
   int64_t cols_per_split, cols_per_phase, row_tiles;
   size_t o_minima, o_tau, o_cnt, bytes;      // offsets behind the shortlist [na][nsplit][cap]
 };
@@ -589,20 +687,45 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k) {
   MfmaPlan p;
   p.kp = mfma_knn_kp(k);
   p.cap = std::max(64, 3 * p.kp);
-  p.rg = p.kp <= 32 ? 1 : (p.kp <= 64 ? 2 : (p.kp <= 128 ? 4 : 8));
-  p.RB = na >= 8192 ? 2 : 1;
+  // One 32-row block of A per wavefront: small enough in registers for two workgroups per
+  // CU, whose matrix-core and vector phases then overlap (measured faster than two row
+  // blocks per wavefront at half the occupancy).  Splits of B fill the 512 resident slots.
+  p.RB = 1;
   p.row_tiles = (na + 128 * p.RB - 1) / (128 * p.RB);
   const int64_t col_steps = std::max<int64_t>(1, (nb + 63) / 64);
-  int64_t ns = std::max<int64_t>(1, 256 / p.row_tiles);
+  int64_t ns = std::max<int64_t>(1, 512 / p.row_tiles);
   ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
   ns = std::min<int64_t>(ns, 16);
   p.nsplit = (int)ns;
   const int64_t steps_per_split = (col_steps + ns - 1) / ns;
   p.cols_per_split = steps_per_split * 64;
+  // The minima sweep visits every S-th tile once a split has enough of them: tau then comes
+  // from a 1/S sample of the columns.  With S = 1 the kp-th smallest group minimum guarantees
+  // kp listed columns; with S > 1 the rank is chosen so that about S * kp_tau columns are
+  // expected below tau, at least k of them except with small probability (rows that end up
+  // with fewer, or with more than their lists hold, fail the re-rank test and are recomputed).
+  p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, steps_per_split / 32));
+  if (p.stride == 1) {
+    p.kp_tau = p.kp;
+  } else {
+    const double ks = (double)k / p.stride;
+    p.kp_tau = std::min(p.kp, (int)std::ceil(ks + 4.0 * std::sqrt(ks) + 2.0));
+    // Room for the listed columns -- in EVERY split: when B is stored in cluster order a
+    // row's candidates all fall into one of them.  Their number is about S times a
+    // gamma(kp_tau) variable (a little more, as two of the best sampled columns may share
+    // a group); r + 5.5 sqrt(r) + 8 is beyond its 1 - 1e-6 quantile for every r.
+    const double r = p.kp_tau;
+    p.cap = std::max(64, (int)std::ceil(1.15 * p.stride * (r + 5.5 * std::sqrt(r) + 8.0)) + 16);
+  }
+  // groups: at least 8 per wanted rank, so that two of the best values rarely share a group
+  const int want = (p.kp_tau + 7) / 8;
+  p.rg = want <= 1 ? 1 : (want <= 2 ? 2 : (want <= 4 ? 4 : 8));
+  if (p.stride == 1) p.rg = p.kp <= 32 ? 1 : (p.kp <= 64 ? 2 : (p.kp <= 128 ? 4 : 8));
+  const int64_t visited = (steps_per_split + p.stride - 1) / p.stride;   // tiles per split
   int64_t nph = (p.rg + ns - 1) / ns;
-  nph = std::max<int64_t>(1, std::min(nph, steps_per_split));
+  nph = std::max<int64_t>(1, std::min(nph, visited));
   p.nphase = (int)nph;
-  p.cols_per_phase = (steps_per_split + nph - 1) / nph * 64;
+  p.cols_per_phase = (visited + nph - 1) / nph * 64 * p.stride;
   p.g_raw = 64 * p.nsplit * p.nphase;
   size_t o = up256((size_t)na * p.nsplit * p.cap * sizeof(u64));
   p.o_minima = o; o += up256((size_t)na * p.g_raw * sizeof(float));
@@ -612,6 +735,22 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k) {
   return p;
 }
 }  // namespace
+
+namespace {
+struct FallbackPlan { int64_t chunk_cols; int nchunk; };
+// column chunks of the exact fallback: at least 32768 columns each, at most 64 chunks
+FallbackPlan fallback_plan(int64_t nb) {
+  FallbackPlan f;
+  f.chunk_cols = std::max<int64_t>(32768, ((nb + 63) / 64 + 255) / 256 * 256);
+  f.nchunk = (int)std::max<int64_t>(1, (nb + f.chunk_cols - 1) / f.chunk_cols);
+  return f;
+}
+}  // namespace
+
+size_t mfma_knn_fallback_bytes(int64_t na, int64_t nb, int k) {
+  const FallbackPlan f = fallback_plan(nb);
+  return f.nchunk == 1 ? 0 : (size_t)na * f.nchunk * k * sizeof(u64);
+}
 
 size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out) {
   const MfmaPlan p = make_plan(na, nb, k);
@@ -631,7 +770,8 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.row_tiles * p.nsplit)), dim3(256), shmem, st, A.hi, A.lo,
                      A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
-                     p.nphase, p.cols_per_phase, reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
+                     MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
+                     reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
                      reinterpret_cast<u64*>(work), p.cap);
 }
@@ -641,13 +781,8 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                            hipStream_t st) {
   // both operand-precision variants are enqueued; the kernel that does not match the flags
   // written by operand preparation returns immediately (the flags live in device memory)
-  if (p.RB == 2) {
-    launch_sweep_t<KSTEPS, 2, METRIC, MODE, false>(p, A, B, work, st);
-    launch_sweep_t<KSTEPS, 2, METRIC, MODE, true>(p, A, B, work, st);
-  } else {
-    launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
-    launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
-  }
+  launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
+  launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
 }
 
 template <int MODE>
@@ -677,38 +812,46 @@ void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, in
   float* tau = reinterpret_cast<float*>(work + p.o_tau);
   const float* minima = reinterpret_cast<const float*>(work + p.o_minima);
   switch (p.rg) {
-    case 1: hipLaunchKernelGGL((tau_kernel<1>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
-    case 2: hipLaunchKernelGGL((tau_kernel<2>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
-    case 4: hipLaunchKernelGGL((tau_kernel<4>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
-    default: hipLaunchKernelGGL((tau_kernel<8>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp, tau); break;
+    case 1: hipLaunchKernelGGL((tau_kernel<1>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
+    case 2: hipLaunchKernelGGL((tau_kernel<2>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
+    case 4: hipLaunchKernelGGL((tau_kernel<4>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
+    default: hipLaunchKernelGGL((tau_kernel<8>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
   }
   launch_sweep<1>(p, A, B, d, metric, work, st);
 }
 
 void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k, int nsplit,
                    const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
-                   int* fb_rows, hipStream_t st) {
+                   int* fb_rows, u64* fb_partial, hipStream_t st) {
   (void)nsplit;
   const MfmaPlan p = make_plan(A.n, B.n, k);
   const int kp = p.kp;
   const int* cnt = reinterpret_cast<const int*>(reinterpret_cast<const char*>(shortlist) + p.o_cnt);
+  const float* tau = reinterpret_cast<const float*>(reinterpret_cast<const char*>(shortlist) + p.o_tau);
   hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, fb_count);
   const int R = kp <= 64 ? 2 : 4;
   const size_t sh = (size_t)64 * R * sizeof(u64) + (size_t)d * sizeof(float);
 #define RR(RV, MET)                                                                               \
   hipLaunchKernelGGL((rerank_kernel<RV, MET>), dim3((unsigned)A.n), dim3(64), sh, st, shortlist,  \
-                     cnt, p.nsplit, p.cap, kp, A.x, B.x, d, k, A.norm, A.info, B.info, eps_scale, out, \
-                     fb_count, fb_rows)
+                     cnt, tau, p.nsplit, p.cap, kp, A.x, B.x, B.n, d, k, A.norm, A.info, B.info,   \
+                     eps_scale, out, fb_count, fb_rows)
   if (R == 2) { if (metric == 0) RR(2, 0); else RR(2, 1); }
   else        { if (metric == 0) RR(4, 0); else RR(4, 1); }
 #undef RR
   // rows whose shortlist could not be proven sufficient: canon over all columns
   const int tot = select_slots_for_k(k);
   const size_t sh2 = (size_t)4 * tot * sizeof(u64) + (size_t)d * sizeof(float);
-  const int grid = (int)std::min<int64_t>(A.n, 1024);
+  const FallbackPlan fp = fallback_plan(B.n);
+  const int grid = (int)std::min<int64_t>(A.n * fp.nchunk, 2048);
 #define CR(RV, MET)                                                                              \
-  hipLaunchKernelGGL((canon_rows_kernel<RV, MET>), dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d, k, \
-                     tot, out, fb_count, fb_rows)
+  do {                                                                                           \
+    hipLaunchKernelGGL((canon_rows_kernel<RV, MET>), dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d, \
+                       k, tot, fp.chunk_cols, fp.nchunk, fb_partial, out, fb_count, fb_rows);    \
+    if (fp.nchunk > 1)                                                                           \
+      hipLaunchKernelGGL((canon_rows_merge_kernel<RV, MET>), dim3((unsigned)std::min<int64_t>(A.n, 1024)), \
+                         dim3(64), (size_t)tot * sizeof(u64), st, fb_partial, fp.nchunk, k, tot, out, \
+                         fb_count, fb_rows);                                                     \
+  } while (0)
   const int R2 = select_regs_for_slots(tot);
   if (R2 == 2) { if (metric == 0) CR(2, 0); else CR(2, 1); }
   else         { if (metric == 0) CR(4, 0); else CR(4, 1); }

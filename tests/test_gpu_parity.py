@@ -270,6 +270,9 @@ ROUTE_CASES = [
     ("unit_d96_k20", 15_000, 100, 96, 20, L2, "unit"),
     ("sift_d128_k100", 50_000, 100, 128, 100, L2, "sift"),
     ("tiny_nb_d32", 50, 10, 32, 40, L2, "gauss"),
+    # long database in cluster order: the threshold comes from a sample of the columns
+    ("sift_sorted_d128_k100", 200_000, 64, 128, 100, L2, "sift_sorted"),
+    ("unit_sorted_d96_k10", 150_000, 96, 96, 10, L2, "unit_sorted"),
 ]
 
 
@@ -283,10 +286,12 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
         rng = np.random.default_rng(zlib.crc32(name.encode()))
         x = rng.standard_normal((nb, d), dtype=np.float32)
         q = rng.standard_normal((nq, d), dtype=np.float32)
-    elif kind == "unit":
+    elif kind.startswith("unit"):
         x, q = S.make_data(S.config("C4", nb=nb, nq=nq, d=d, ncomp=30))
     else:
         x, q = S.make_data(S.config("C2", nb=nb, nq=nq, d=d, ncomp=30))
+    if kind.endswith("sorted"):
+        x = np.ascontiguousarray(x[np.lexsort(x[:, :3].T)])
     xd, qd = dev(x), dev(q)
     try:
         vs.vs_set_option("knn_path", 1)
