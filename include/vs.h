@@ -3,9 +3,9 @@
  *
  * Batched IVF-PQ search and flat exact k-NN search as described in
  * "The Faiss Library" (arXiv 2401.08281): Sec. 3 (Eq. 1-2, brute-force
- * search, metrics), Sec. 4 (Eq. 5 asymmetric distance computation, product
- * quantizer, Eq. 8 look-up tables), Sec. 5.1 (inverted files, residual
- * encoding), App. A.4 "GPU Faiss" (the four GPU stages).
+ * search, metrics), Sec. 4 (Eq. 8 asymmetric distance computation, product
+ * quantizer, Eq. 12 look-up tables), Sec. 5.1 (inverted files, residual
+ * encoding), App. A.3 "Optimization", paragraph "GPU Faiss" (the four GPU stages).
  *
  * General conventions
  *   - Every array pointer is a DEVICE pointer on the current HIP device,
@@ -20,7 +20,7 @@
  *     better); VS_METRIC_IP is the inner product (larger is better).
  *     Results are ordered best first (Eq. 2).
  *   - Empty result slots (fewer than k candidates): id = -1 and distance
- *     +inf (L2) / -inf (IP), placed last (Sec. 8.1: negative ids are invalid).
+ *     +inf (L2) / -inf (IP), placed last (Sec. 6.1: negative ids are invalid).
  *   - Every function returns VS_OK or a negative error code; a message for
  *     the calling thread's last error is available from vs_last_error().
  *     Nothing throws across this boundary.  Inputs containing NaN are
@@ -58,7 +58,7 @@ enum {
 #define VS_MAX_K 1024 /* largest k and largest nprobe accepted */
 
 /*
- * Flat exact k-NN search (Sec. 3.2 "Brute force search", Eq. 2).
+ * Flat exact k-NN search (Sec. 3.1 "Brute force search", Eq. 2).
  *   x        [nb, d] fp32 database rows; row i has id i.  nb < 2^31.
  *   q        [nq, d] fp32 queries.
  *   out_dist [nq, k] fp32, out_ids [nq, k] int64: for each query the k best
@@ -90,7 +90,7 @@ VS_API int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nl
                     void* hip_stream);
 
 /*
- * Add n vectors (Sec. 5.1; Sec. 8.1 for ids): each vector goes to the list of
+ * Add n vectors (Sec. 5.1; Sec. 6.1 for ids): each vector goes to the list of
  * its best centroid (ties: smaller list number), its residual is PQ-encoded
  * (each sub-vector to its nearest codeword in squared L2, ties: smaller code)
  * and (code, id) is appended to the list, after the entries already there and
@@ -108,7 +108,7 @@ VS_API int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nl
 VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, void* hip_stream);
 
 /*
- * Batched IVF-PQ search (Sec. 5.1; Eq. 5; Eq. 8; App. A.4).
+ * Batched IVF-PQ search (Sec. 5.1; Eq. 8 ADC; Eq. 12 look-up tables; App. A.3 "GPU Faiss").
  * For every query: the nprobe best centroids are found exactly (nprobe is
  * clamped to nlist), a look-up table LUT_m[j] is built per (query, probed
  * list) on the query's residual to the list centroid (per query for IP, plus

@@ -9,11 +9,11 @@
  * definition states.
  *
  * Conventions
- *   - vectors are rows of row-major fp32 matrices (Sec. 2 "notations", App. A.1)
- *   - metric 0 = L2, returned SQUARED (App. "metrics" table: METRIC_L2 is the
+ *   - vectors are rows of row-major fp32 matrices (Sec. 3 Table 1 "notations", App. A.1)
+ *   - metric 0 = L2, returned SQUARED (App. A.6 "Faiss metric types": METRIC_L2 is the
  *     squared Euclidean distance); metric 1 = inner product, larger is better
- *     (Sec. 3.1 "Distance measures": argmin becomes argmax)
- *   - ids are int64, -1 marks an empty result slot (Sec. 8.1: the sign bit is
+ *     (Sec. 3 "Distance measures": argmin becomes argmax)
+ *   - ids are int64, -1 marks an empty result slot (Sec. 6.1: the sign bit is
  *     reserved for invalid ids)
  *   - ties: the smaller index / id wins (the paper leaves ties open)
  *
@@ -231,7 +231,7 @@ void or_pq_decode(const uint8_t *codes, int64_t n, int d, const int32_t *list_of
   }
 }
 
-/* ---- O6-O8: IVF-PQ search (Sec. 5.1, Eq. 5 ADC, Eq. 8 LUT) -------------
+/* ---- O6-O8: IVF-PQ search (Sec. 5.1, Eq. 8 ADC, Eq. 12 LUT) -------------
  * The index is given as plain arrays: list l owns rows
  * [list_offsets[l], list_offsets[l+1]) of `codes` and `ids`.
  *

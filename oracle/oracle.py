@@ -146,7 +146,7 @@ def pq_decode(codes, list_of, centroids, codebooks, nbits):
 
 
 def recall(I_found, I_true, n=None):
-    """n-recall@k (Sec. 3.3 "Accuracy metrics"): fraction of the n ground-truth
+    """n-recall@k (Sec. 3.2 "Metrics for approximate nearest neighbor search"): fraction of the n ground-truth
     nearest neighbours found among the k returned ids.  n = None means n = k
     (the intersection measure)."""
     I_found = np.asarray(I_found)
@@ -213,7 +213,7 @@ class OracleIVFPQ:
     def add(self, x, ids=None):
         x = np.ascontiguousarray(x, dtype=np.float32)
         n = x.shape[0]
-        if ids is None:  # sequential ids continue from ntotal (Sec. 8.1)
+        if ids is None:  # sequential ids continue from ntotal (Sec. 6.1)
             ids = np.arange(self.ntotal, self.ntotal + n, dtype=np.int64)
         list_of = assign(x, self.centroids, self.metric)
         codes = pq_encode(x, list_of, self.centroids, self.codebooks, self.nbits)

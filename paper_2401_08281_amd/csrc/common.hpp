@@ -147,8 +147,8 @@ __device__ __forceinline__ void wave_sort_regs(T (&v)[R]) {
 }
 
 // ---- wavefront-level k-selection ------------------------------------------
-// One wavefront keeps the k smallest keys of a stream (App. A.4: k-selection
-// is the critical GPU stage; Sec. 3.2: for larger k use an unordered reservoir
+// One wavefront keeps the k smallest keys of a stream (App. A.3 "GPU Faiss": k-selection
+// is the critical GPU stage; Sec. 3.1: for larger k use an unordered reservoir
 // that is trimmed back to k when it overflows).  State: TOT 64-bit slots in
 // LDS owned by the wavefront.  Slots [0, k) hold the best k seen so far,
 // ascending after every trim; slots [k, TOT) are the reservoir.  A candidate

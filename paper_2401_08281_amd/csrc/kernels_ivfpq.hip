@@ -143,8 +143,9 @@ __global__ void list_sizes_kernel(const int64_t* __restrict__ off, int nlist,
 }
 
 // ---------------------------------------------------------------------------
-// Fused LUT build + ADC scan + k-selection (Sec. 4 Eq. 5 and Eq. 8; Sec. 5.1;
-// App. A.4: tables staged in on-chip memory, lists streamed from HBM).
+// Fused LUT build + ADC scan + k-selection (Sec. 4 Eq. 8 (ADC) and Eq. 12 (look-up
+// tables); Sec. 5.1; App. A.3 "GPU Faiss": tables staged in on-chip memory, lists
+// streamed from HBM).
 //
 // One workgroup (4 wavefronts) serves one query and a contiguous range of its
 // probes.  Per probed list l:
@@ -483,7 +484,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
 
 // One wavefront per query: k best of the nsplit partial lists, then
 // (value, stored id).  Storage position -> id goes through the ids array
-// (Sec. 8.1: IVF indexes store the 64-bit id next to each code).
+// (Sec. 6.1: IVF indexes store the 64-bit id next to each code).
 template <int R>
 __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__ partial,
                                                          int nsplit, int k, int tot, int metric,

@@ -1,6 +1,6 @@
 // MFMA shortlist + exact re-rank for k-nearest rows (coarse quantizer, flat search).
 //
-// Sec. 3.2 of the paper: with large query batches distances are computed through
+// Sec. 3.1 of the paper: with large query batches distances are computed through
 // the matrix-multiplication decomposition ||q||^2 + ||x||^2 - 2<q, x>.  Here the
 // contraction runs on the gfx950 matrix cores in bf16 (v_mfma_f32_32x32x16_bf16):
 // every fp32 operand is split into a bf16 head and a bf16 tail, and

@@ -273,7 +273,7 @@ def _c1_index(oracle, metric=L2, nbits=8, **kw):
 
 @pytest.mark.parametrize("metric,nbits", [(L2, 8), (IP, 8), (L2, 4), (IP, 4)])
 def test_adc_equals_distance_to_decoded_vector(oracle, metric, nbits):
-    # Eq. 5: the ADC distance is the distance from q to D(C(x)); Eq. 8: the sum
+    # Eq. 8: the ADC distance is the distance from q to D(C(x)); Eq. 12: the sum
     # of table look-ups equals it.  Probe all lists => the result must equal a
     # flat search over the decoded database, and the LUT form must agree.
     cfg, x, q, ix = _c1_index(oracle, metric, nbits, nb=2000, nq=30)
