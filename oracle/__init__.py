@@ -9,6 +9,7 @@ from .oracle import (  # noqa: F401
     canon_l2,
     coarse_probe,
     flat_search,
+    refine,
     num_threads,
     pq_decode,
     pq_encode,

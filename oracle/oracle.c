@@ -134,6 +134,38 @@ void or_flat_search(const float *x, int64_t nb, const float *q, int64_t nq, int 
   }
 }
 
+/* ---- Refinement of a shortlist (Sec. 3.5 "Refining") ------------------
+ * A first, approximate search returns kc candidate ids per query; the accurate
+ * second stage computes the exact distance (the definition of Eq. 1, as in
+ * or_flat_search: fp64 sum, rounded once) between the query and each candidate
+ * vector and keeps the k best, best first, ties to the smaller id.  Entries of
+ * the shortlist that are not row numbers of x (the -1 of an empty slot) are
+ * skipped; every other entry is taken as given. */
+void or_refine(const float *x, int64_t nb, const float *q, int64_t nq, int d, int metric,
+               const int64_t *cand, int kc, int k, float *D, int64_t *I) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t a = 0; a < nq; ++a) {
+    const float *qa = q + a * d;
+    topk_t h;
+    topk_init(&h, k, metric, D + a * k, I + a * k);
+    for (int j = 0; j < kc; ++j) {
+      const int64_t i = cand[a * kc + j];
+      if (i < 0 || i >= nb) continue;
+      const float *xi = x + i * d;
+      double acc = 0.0;
+      if (metric == OR_METRIC_L2) {
+        for (int t = 0; t < d; ++t) {
+          double diff = (double)qa[t] - (double)xi[t];
+          acc += diff * diff;
+        }
+      } else {
+        for (int t = 0; t < d; ++t) acc += (double)qa[t] * (double)xi[t];
+      }
+      topk_push(&h, (float)acc, i);
+    }
+  }
+}
+
 /* ---- O2: list assignment; O6: probe selection (Sec. 5.1) --------------- */
 
 /* list(x) = the best centroid under the index metric by canon arithmetic,

@@ -88,6 +88,24 @@ def flat_search(x, q, k, metric=METRIC_L2):
     return D, I
 
 
+def refine(x, q, cand, k, metric=METRIC_L2):
+    """Sec. 3.5 "Refining": exact distances between each query and the vectors of its
+    shortlist `cand` [nq, kc] (row numbers of x; entries outside [0, nb) are skipped), then
+    the k best, best first."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    cand = np.ascontiguousarray(cand, dtype=np.int64)
+    nb, d = x.shape
+    nq, kc = cand.shape
+    assert q.shape == (nq, d)
+    D = np.empty((nq, k), dtype=np.float32)
+    I = np.empty((nq, k), dtype=np.int64)
+    _load().or_refine(_ptr(x), ctypes.c_int64(nb), _ptr(q), ctypes.c_int64(nq), ctypes.c_int(d),
+                      ctypes.c_int(metric), _ptr(cand), ctypes.c_int(kc), ctypes.c_int(k),
+                      _ptr(D), _ptr(I))
+    return D, I
+
+
 def assign(x, centroids, metric=METRIC_L2):
     x = np.ascontiguousarray(x, dtype=np.float32)
     centroids = np.ascontiguousarray(centroids, dtype=np.float32)

@@ -365,3 +365,61 @@ def test_recall_definitions(oracle):
     assert oracle.recall(np.array([[9, 1, 8, 7]]), It) == 0.25
     assert oracle.recall(np.array([[9, 1, 8, 7]]), It, 1) == 1.0      # 1-recall@4
     assert oracle.recall(np.array([[2, 9, 8, -1]]), It, 1) == 0.0
+
+
+# ------------------------------------------------------------- refinement
+
+@pytest.mark.parametrize("metric", [L2, IP])
+def test_refine_matches_numpy_on_the_shortlist(oracle, metric):
+    # Sec. 3.5: the second stage computes accurate distances only for the shortlist.
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal((300, 12), dtype=np.float32)
+    q = rng.standard_normal((9, 12), dtype=np.float32)
+    cand = np.stack([rng.choice(300, 40, replace=False) for _ in range(9)]).astype(np.int64)
+    D, I = oracle.refine(x, q, cand, 7, metric)
+    full = np_pairwise(q, x, metric).astype(np.float32)
+    for a in range(9):
+        c = np.sort(cand[a])                             # ascending ids: stable sort = ties to the smaller id
+        v = full[a, c]
+        order = np.argsort(v if metric == L2 else -v, kind="stable")[:7]
+        np.testing.assert_array_equal(I[a], c[order])
+        np.testing.assert_allclose(D[a], v[order], rtol=1e-6)
+
+
+def test_refine_with_every_row_listed_is_flat_search(oracle):
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal((120, 8), dtype=np.float32)
+    q = rng.standard_normal((6, 8), dtype=np.float32)
+    cand = np.stack([rng.permutation(120) for _ in range(6)]).astype(np.int64)
+    D, I = oracle.refine(x, q, cand, 15, L2)
+    Df, If = oracle.flat_search(x, q, 15, L2)
+    np.testing.assert_array_equal(I, If)
+    np.testing.assert_array_equal(D, Df)
+
+
+def test_refine_skips_empty_slots_pads_and_breaks_ties_by_id(oracle):
+    x = np.array([[0, 0], [3, 0], [0, 3], [1, 0], [5, 5]], dtype=np.float32)
+    q = np.zeros((1, 2), dtype=np.float32)
+    cand = np.array([[2, -1, 1, 7, 3, -1]], dtype=np.int64)      # 7 is not a row of x
+    D, I = oracle.refine(x, q, cand, 5, L2)
+    assert I[0].tolist() == [3, 1, 2, -1, -1]                    # rows 1 and 2 tie at 9: smaller id first
+    assert D[0, :3].tolist() == [1.0, 9.0, 9.0] and np.isposinf(D[0, 3:]).all()
+    D, I = oracle.refine(x, q + 1, cand, 2, IP)                  # q = (1, 1): scores 3, 3, 1
+    assert I[0].tolist() == [1, 2] and D[0].tolist() == [3.0, 3.0]
+
+
+def test_refining_an_ivfpq_shortlist_never_loses_recall(oracle):
+    # A true k-nearest neighbour that is in the shortlist is among the k exact best of the
+    # shortlist, so k-recall@k after refinement >= k-recall@k of the first stage's own top k.
+    cfg, x, q, ix = _c1_index(oracle, nb=3000, nq=40)
+    _, It = oracle.flat_search(x, q, 10, L2)
+    D1, I1 = ix.search(q, 60, 4)
+    Dr, Ir = oracle.refine(x, q, I1, 10, L2)
+    assert oracle.recall(Ir, It) >= oracle.recall(I1[:, :10], It)
+    assert oracle.recall(Ir, It) > oracle.recall(I1[:, :10], It) + 0.05     # and here it gains
+    # refined distances are exact distances: they equal flat search's wherever the id matches
+    Df, If = oracle.flat_search(x, q, 3000, L2)
+    for a in range(40):
+        pos = {int(i): j for j, i in enumerate(If[a])}
+        for j in range(10):
+            assert Dr[a, j] == Df[a, pos[int(Ir[a, j])]]
