@@ -47,6 +47,10 @@ def main():
                          "1M x 128-d; C5: IVF16384,PQ64x4 inner product on 10M x 768-d; C2: flat search")
     ap.add_argument("--nprobe", type=int, default=None)
     ap.add_argument("--nb", type=int, default=None, help="override database size (debug)")
+    ap.add_argument("--refine", type=int, default=0, metavar="K2",
+                    help="after the timed search, also time the second stage vs_refine(search's k results "
+                         "-> K2 best by exact distance) and report it under config.refine (the headline "
+                         "value stays the search alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
@@ -156,6 +160,33 @@ def main():
     hit_10 = np.mean([len(set(I_h[a, :k10].tolist()) & set(Ig_h[a, :k10].tolist())) / float(k10)
                       for a in range(nrec)])
 
+    refine = None
+    if args.refine > 0:
+        # second stage (Sec. 3.5): exact distances for the k results of the first stage
+        k2 = min(args.refine, k)
+        D2 = torch.empty((nq, k2), dtype=torch.float32, device="cuda")
+        I2 = torch.empty((nq, k2), dtype=torch.int64, device="cuda")
+        for _ in range(args.warmup):
+            vs.vs_refine(xd, qd, I, k2, metric, D2, I2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            vs.vs_refine(xd, qd, I, k2, metric, D2, I2)
+        torch.cuda.synchronize()
+        r_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        I2_h = I2.cpu().numpy()
+        hit_r = np.mean([len(set(I2_h[a].tolist()) & set(Ig_h[a, :k2].tolist())) / float(k2)
+                         for a in range(nrec)])
+        hit_f = np.mean([len(set(I_h[a, :k2].tolist()) & set(Ig_h[a, :k2].tolist())) / float(k2)
+                         for a in range(nrec)])
+        gathered = float((I >= 0).sum().item()) * cfg["d"] * 4
+        refine = {"k_in": k, "k_out": k2, "ms_per_step": round(r_ms, 4),
+                  "gather_GBps": round(gathered / (r_ms * 1e-3) / 1e9, 1),
+                  "recall_%d_at_%d_first_stage" % (k2, k2): round(float(hit_f), 4),
+                  "recall_%d_at_%d_refined" % (k2, k2): round(float(hit_r), 4),
+                  "queries_per_s_search_plus_refine": nq / ((ms_per_step + r_ms) * 1e-3)}
+        log("refine %d -> %d: %.3f ms, recall %.4f -> %.4f" % (k, k2, r_ms, hit_f, hit_r))
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe)
@@ -173,7 +204,8 @@ def main():
             "recall_1_at_k": round(float(hit_1), 4), "recall_10_at_10": round(float(hit_10), 4),
             "recall_queries": int(nrec), "scanned_codes_per_query": scanned / nq,
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
-            "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v}},
+            "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v},
+            **({"refine": refine} if refine else {})},
         "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_reg_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,

@@ -73,6 +73,27 @@ VS_API int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq
                    void* hip_stream);
 
 /*
+ * Re-rank a shortlist with exact distances (Sec. 3.5 "Refining"; the "RFlat" suffix
+ * of App. A.2's index factory): the second, accurate stage behind a fast first
+ * search such as vs_ivfpq_search run with kc > k.
+ *   x        [nb, d] fp32, the uncompressed database rows; row i has id i.  nb < 2^32.
+ *   q        [nq, d] fp32 queries (the ones the shortlist was computed for).
+ *   cand_ids [nq, kc] int64: each query's shortlist.  Entries outside [0, nb) -- the -1
+ *            of an empty slot -- are skipped; every other entry is taken as given (an id
+ *            listed twice is returned twice).
+ *   out_dist [nq, k] fp32, out_ids [nq, k] int64: the k best candidates by exact
+ *            distance, best first, ties to the smaller id; empty slots as above.
+ * Distances are the same fp32 chains as in vs_flat_search, so a candidate's value
+ * here equals its value there bit for bit.
+ * Errors: null pointers (with nq > 0), d < 1, kc < 1, k < 1 or k > VS_MAX_K, unknown
+ * metric, nb >= 2^32; VS_ERR_UNSUPPORTED when d and k together exceed the on-chip memory
+ * of a workgroup (d above roughly 5000 at k = 1024).
+ */
+VS_API int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
+              int32_t metric, const int64_t* cand_ids, int32_t kc, int32_t k, float* out_dist,
+              int64_t* out_ids, void* hip_stream);
+
+/*
  * Create an empty IVF-PQ index (Sec. 5.1 "Inverted files"; Sec. 4.1 product
  * quantizer).  Training is not part of this library: the nlist coarse
  * centroids and the M sub-codebooks are inputs and are copied.
@@ -153,10 +174,11 @@ enum {
   VS_STAGE_MERGE = 3,         /* merge across probe splits, id translation       */
   VS_STAGE_FLAT_DIST = 4,     /* flat search: query x database distance tiles    */
   VS_STAGE_FLAT_SELECT = 5,   /* flat search: k-selection                        */
-  VS_NUM_STAGES = 6
+  VS_STAGE_REFINE = 6,        /* vs_refine: exact distances of a shortlist + selection */
+  VS_NUM_STAGES = 7
 };
 
-/* on != 0: from now on vs_ivfpq_search and vs_flat_search bracket every kernel
+/* on != 0: from now on vs_ivfpq_search, vs_flat_search and vs_refine bracket every kernel
  * launch of the stages above with a pair of HIP events recorded on the caller's
  * stream (the launches themselves are unchanged).  Off by default. */
 VS_API int vs_profile_enable(int on);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     VSError,
     lib,
     vs_flat_search,
+    vs_refine,
     vs_ivfpq_add,
     vs_ivfpq_coarse,
     vs_ivfpq_code_size,

@@ -36,6 +36,8 @@ def lib():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.vs_flat_search.restype = ctypes.c_int
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_refine.restype = ctypes.c_int
+    L.vs_refine.argtypes = [vp, i64, vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
     L.vs_ivfpq_create.restype = ctypes.c_int
     L.vs_ivfpq_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i32, vp, vp, vp]
     L.vs_ivfpq_add.restype = ctypes.c_int
@@ -103,7 +105,7 @@ def vs_version():
     return lib().vs_version().decode()
 
 
-STAGES = ("coarse_dist", "coarse_select", "scan", "merge", "flat_dist", "flat_select")
+STAGES = ("coarse_dist", "coarse_select", "scan", "merge", "flat_dist", "flat_select", "refine")
 
 
 def vs_profile_enable(on):
@@ -143,6 +145,28 @@ def vs_flat_search(x, q, k, metric=METRIC_L2, out_dist=None, out_ids=None):
     _dev(out_dist, torch.float32, "out_dist")
     _dev(out_ids, torch.int64, "out_ids")
     _check(lib().vs_flat_search(_p(x), nb, _p(q), nq, d, metric, k, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_refine(x, q, cand_ids, k, metric=METRIC_L2, out_dist=None, out_ids=None):
+    x = _dev(x, torch.float32, "x")
+    q = _dev(q, torch.float32, "q")
+    cand_ids = _dev(cand_ids, torch.int64, "cand_ids")
+    nb, d = x.shape
+    nq = q.shape[0]
+    if q.shape[1] != d:
+        raise ValueError("x and q differ in dimension")
+    if cand_ids.dim() != 2 or cand_ids.shape[0] != nq:
+        raise ValueError("cand_ids must be [nq, kc]")
+    kc = cand_ids.shape[1]
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_refine(_p(x), nb, _p(q), nq, d, metric, _p(cand_ids), kc, k, _p(out_dist),
+                           _p(out_ids), _stream()))
     return out_dist, out_ids
 
 

@@ -5,7 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvs.so")
-SOURCES = ["api.hip", "kernels_dist.hip", "kernels_select.hip", "kernels_ivfpq.hip", "kernels_mfma.hip"]
+SOURCES = ["api.hip", "kernels_dist.hip", "kernels_select.hip", "kernels_ivfpq.hip", "kernels_mfma.hip",
+           "kernels_refine.hip"]
 HEADERS = ["common.hpp", "internal.hpp", os.path.join("..", "..", "include", "vs.h")]
 
 FLAGS = [

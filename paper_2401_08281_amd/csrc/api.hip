@@ -315,6 +315,29 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   return VS_OK;
 }
 
+int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d, int32_t metric,
+              const int64_t* cand_ids, int32_t kc, int32_t k, float* out_dist, int64_t* out_ids,
+              void* hip_stream) {
+  if (nq < 0 || nb < 0) return fail(VS_ERR_INVALID_ARG, "vs_refine: negative size");
+  if (d < 1) return fail(VS_ERR_INVALID_ARG, "vs_refine: d = %d < 1", d);
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_refine: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (kc < 1) return fail(VS_ERR_INVALID_ARG, "vs_refine: kc = %d < 1", kc);
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_refine: unknown metric %d", metric);
+  if (nb >= (1ll << 32)) return fail(VS_ERR_INVALID_ARG, "vs_refine: nb must be < 2^32");
+  if (nq == 0) return VS_OK;
+  if (!q || !cand_ids || !out_dist || !out_ids || (nb > 0 && !x)) return fail(VS_ERR_INVALID_ARG, "vs_refine: null pointer");
+  // per wavefront: the selection slots and the query, four wavefronts per workgroup
+  const size_t lds = refine_lds_bytes(d, k);
+  if (lds > 160 * 1024) return fail(VS_ERR_UNSUPPORTED, "vs_refine: d = %d with k = %d needs %zu bytes of LDS", d, k, lds);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  {
+    StageTimer t(VS_STAGE_REFINE, st);
+    launch_refine(x, nb, q, nq, d, metric, cand_ids, kc, k, out_dist, out_ids, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
 int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, int32_t M,
                     int32_t nbits, const float* centroids, const float* codebooks,
                     void* hip_stream) {

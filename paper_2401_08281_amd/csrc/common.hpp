@@ -273,6 +273,33 @@ static inline int select_slots_for_k(int k) {
 }
 static inline int select_regs_for_slots(int tot) { return tot <= 256 ? tot / 64 : 0; }
 
+// ---- canon distance of one pair ------------------------------------------------
+// The fp32 chain every exact decision of the library is defined in: dimension order,
+// diff = a - b rounded, acc = fma(diff, diff, acc) (inner product: acc = fma(a, b, acc)).
+// qs may live in LDS (read as broadcasts); b is a row in global memory; vec: d % 4 == 0.
+template <int METRIC>
+__device__ __forceinline__ float canon_row(const float* __restrict__ qs, const float* __restrict__ b,
+                                           int d, bool vec) {
+  float acc = 0.f;
+  if (vec) {
+    for (int t = 0; t < d; t += 4) {
+      const float4 bv = *reinterpret_cast<const float4*>(b + t);
+      const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (METRIC == 0) { const float diff = qs[t + u] - bb[u]; acc = __builtin_fmaf(diff, diff, acc); }
+        else acc = __builtin_fmaf(qs[t + u], bb[u], acc);
+      }
+    }
+  } else {
+    for (int t = 0; t < d; ++t) {
+      if (METRIC == 0) { const float diff = qs[t] - b[t]; acc = __builtin_fmaf(diff, diff, acc); }
+      else acc = __builtin_fmaf(qs[t], b[t], acc);
+    }
+  }
+  return acc;
+}
+
 // ---- merge of sorted key lists by ranking -----------------------------------
 // `nl` ascending lists of k keys each (padded with KEY_EMPTY) sit at
 // base + w * stride.  Keys are unique, so the number of keys smaller than x over

@@ -97,3 +97,10 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
                    const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
                    int* fb_rows, u64* fb_partial, hipStream_t st);
 int read_fallback_total(unsigned long long* out);
+
+// ---- kernels_refine.hip --------------------------------------------------------
+// k best of each query's kc candidates by canon distance to the candidates' rows of x
+size_t refine_lds_bytes(int d, int k);   // LDS of one workgroup; the launch needs it to fit
+void launch_refine(const float* x, int64_t nb, const float* q, int64_t nq, int d, int metric,
+                   const int64_t* cand, int kc, int k, float* out_dist, int64_t* out_ids,
+                   hipStream_t st);

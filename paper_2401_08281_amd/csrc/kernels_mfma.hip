@@ -435,29 +435,6 @@ __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ mini
 // ---------------------------------------------------------------------------
 // Exact re-rank: one wavefront per row of A.
 // ---------------------------------------------------------------------------
-template <int METRIC>
-__device__ __forceinline__ float canon_row(const float* __restrict__ qs, const float* __restrict__ b,
-                                           int d, bool vec) {
-  float acc = 0.f;
-  if (vec) {
-    for (int t = 0; t < d; t += 4) {
-      const float4 bv = *reinterpret_cast<const float4*>(b + t);
-      const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (METRIC == 0) { const float diff = qs[t + u] - bb[u]; acc = __builtin_fmaf(diff, diff, acc); }
-        else acc = __builtin_fmaf(qs[t + u], bb[u], acc);
-      }
-    }
-  } else {
-    for (int t = 0; t < d; ++t) {
-      if (METRIC == 0) { const float diff = qs[t] - b[t]; acc = __builtin_fmaf(diff, diff, acc); }
-      else acc = __builtin_fmaf(qs[t], b[t], acc);
-    }
-  }
-  return acc;
-}
-
 template <int R, int METRIC>
 __global__ __launch_bounds__(64) void rerank_kernel(
     const u64* __restrict__ shortlist, const int* __restrict__ cnt, const float* __restrict__ tau,

@@ -56,6 +56,17 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_flat_search(one, 10, nul, 1, 4, 0, 1, one, one, nul) == INVALID      # null q
     assert L.vs_flat_search(one, -1, one, 1, 4, 0, 1, one, one, nul) == INVALID
     assert L.vs_flat_search(nul, 10, nul, 0, 4, 0, 1, nul, nul, nul) == 0            # nq == 0: no-op
+    # vs_refine(x, nb, q, nq, d, metric, cand, kc, k, out_dist, out_ids, stream)
+    assert L.vs_refine(one, 10, one, 1, 0, 0, one, 5, 1, one, one, nul) == INVALID       # d < 1
+    assert L.vs_refine(one, 10, one, 1, 4, 0, one, 0, 1, one, one, nul) == INVALID       # kc < 1
+    assert b"kc = 0" in L.vs_last_error()
+    assert L.vs_refine(one, 10, one, 1, 4, 0, one, 5, 0, one, one, nul) == INVALID       # k < 1
+    assert L.vs_refine(one, 10, one, 1, 4, 0, one, 5, 1025, one, one, nul) == INVALID    # k > VS_MAX_K
+    assert L.vs_refine(one, 10, one, 1, 4, 3, one, 5, 1, one, one, nul) == INVALID       # metric
+    assert L.vs_refine(one, 10, one, 1, 4, 0, nul, 5, 1, one, one, nul) == INVALID       # null shortlist
+    assert L.vs_refine(one, 1 << 32, one, 1, 4, 0, one, 5, 1, one, one, nul) == INVALID  # ids must fit 32 bits
+    assert L.vs_refine(one, 10, one, 1, 20000, 0, one, 5, 1024, one, one, nul) == UNSUPPORTED   # LDS
+    assert L.vs_refine(nul, 10, nul, 0, 4, 0, nul, 5, 1, nul, nul, nul) == 0             # nq == 0: no-op
     h = ctypes.c_void_p(0)
     ref = ctypes.byref(h)
     assert L.vs_ivfpq_create(ref, 32, 0, 16, 5, 8, one, one, nul) == INVALID         # d % M

@@ -318,6 +318,83 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
     check_search(Dm, Im, Do, Io, metric, q, xn)
 
 
+# ------------------------------------------------- refinement of a shortlist
+
+REFINE_CASES = [
+    # name, nb, nq, d, kc, k, metric
+    ("gauss_d32", 5_000, 100, 32, 100, 10, L2),
+    ("gauss_d96_ip", 3_000, 37, 96, 70, 70, IP),          # k = kc: a pure re-ordering
+    ("gauss_d30_large_k", 4_000, 9, 30, 1500, 1000, L2),  # odd d, selection in LDS (k > 192)
+    ("gauss_d768", 2_000, 21, 768, 33, 5, IP),
+]
+
+
+@pytest.mark.parametrize("name,nb,nq,d,kc,k,metric", REFINE_CASES, ids=[c[0] for c in REFINE_CASES])
+def test_refine_matches_oracle(vs, oracle, name, nb, nq, d, kc, k, metric):
+    say("refine %s nb=%d nq=%d d=%d kc=%d k=%d metric=%d" % (name, nb, nq, d, kc, k, metric))
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    x = rng.standard_normal((nb, d), dtype=np.float32)
+    q = rng.standard_normal((nq, d), dtype=np.float32)
+    cand = np.stack([rng.choice(nb, kc, replace=False) for _ in range(nq)]).astype(np.int64)
+    cand[rng.random(cand.shape) < 0.05] = -1              # empty slots of a first stage
+    cand[0, :] = -1                                        # a query with nothing to refine
+    cand[1, : kc - 2] = -1                                 # and one with two candidates
+    D, I = [host(t) for t in vs.vs_refine(dev(x), dev(q), dev(cand), k, metric)]
+    Do, Io = oracle.refine(x, q, cand, k, metric)
+    assert (I[0] == -1).all() and (I[1, min(2, k):] == -1).all()
+    np.testing.assert_array_equal(I == -1, Io == -1)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+    # candidates are distinct, so the oracle's k best ARE the answer: same ids except where
+    # two oracle distances are within the tolerance, same distances within the tolerance
+    Dx, Ix = oracle.refine(x, q, cand, min(k + EXTRA, kc), metric)
+    check_search(D, I, Dx, Ix, metric, q, xn)
+
+
+def test_refine_on_integer_data_equals_flat_search_bits(vs, oracle):
+    """Exact distances on integer data are exact in every summation order: re-ranking a
+    shuffled superset of flat search's answer returns flat search's answer bit for bit."""
+    cfg = S.config("C2", nb=20_000, nq=64, ncomp=30)
+    say("refine on integer data vs flat search")
+    x, q = S.make_data(cfg)
+    Df, If = [host(t) for t in vs.vs_flat_search(dev(x), dev(q), 50, L2)]
+    rng = np.random.default_rng(5)
+    extra = rng.integers(0, cfg["nb"], size=(64, 30))
+    cand = np.concatenate([If, extra], axis=1)
+    for a in range(64):                                    # distinct ids per query, shuffled
+        u = np.unique(cand[a])
+        row = np.full(80, -1, dtype=np.int64)
+        row[: u.size] = rng.permutation(u)
+        cand[a] = row
+    D, I = [host(t) for t in vs.vs_refine(dev(x), dev(q), dev(cand), 50, L2)]
+    np.testing.assert_array_equal(I, If)
+    np.testing.assert_array_equal(D, Df)
+    Do, Io = oracle.refine(x, q, cand, 50, L2)
+    np.testing.assert_array_equal(I, Io)
+    np.testing.assert_array_equal(D, Do)
+
+
+def test_ivfpq_search_then_refine_pipeline(vs, oracle):
+    """First stage IVF-PQ with a shortlist of 100, second stage exact: the pipeline agrees
+    with the oracle's pipeline and gains recall over the first stage's own top 10."""
+    cfg = S.config("C3", nb=100_000, nq=200, ncomp=100, nlist=512)
+    say("ivfpq -> refine pipeline")
+    x, q = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x)
+    D1, I1 = ix.search(dev(q), 100, 16)
+    Dr, Ir = [host(t) for t in vs.vs_refine(dev(x), dev(q), I1, 10, L2)]
+    Do1, Io1 = orc.search(q, 100, 16)
+    # the two first stages may order near-ties differently; refine the GPU's own shortlist
+    # with the oracle (integer data: exact values, so the comparison is bit for bit)
+    Dor, Ior = oracle.refine(x, q, host(I1), 10, L2)
+    np.testing.assert_array_equal(Ir, Ior)
+    np.testing.assert_array_equal(Dr, Dor)
+    _, It = oracle.flat_search(x, q, 10, L2)
+    r1, r2 = oracle.recall(host(I1)[:, :10], It), oracle.recall(Ir, It)
+    say("  10-recall@10: first stage %.3f, refined %.3f" % (r1, r2))
+    assert r2 >= r1 and r2 > r1 + 0.1
+    ix.close()
+
+
 # ------------------------------------------------- the two largest configurations
 
 def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
