@@ -9,6 +9,8 @@ from .oracle import (  # noqa: F401
     canon_l2,
     coarse_probe,
     flat_search,
+    kmeans,
+    train_ivfpq,
     refine,
     num_threads,
     pq_decode,

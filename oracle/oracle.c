@@ -204,6 +204,54 @@ void or_coarse_probe(const float *q, int64_t nq, const float *centroids, int nli
   }
 }
 
+/* ---- k-means (Sec. 4.1 "The k-means vector quantizer": Lloyd's two conditions,
+ * applied in turn) ------------------------------------------------------------
+ * Each of the niter rounds (1) assigns every training vector to its nearest
+ * centroid -- canon L2, ties to the smaller centroid number, the rule of
+ * or_assign -- and (2) moves every centroid to the mean of the vectors assigned
+ * to it: float64 sum in the order of the vectors, divided by the count, rounded
+ * to fp32.  A centroid that received no vector keeps its position (the paper
+ * does not say; this is the reading taken).  centroids: in = the initial
+ * centroids, out = the trained ones.  objective[r], if asked for, is the mean
+ * over the training vectors of the canon distance to the assigned centroid in
+ * round r's step (1), summed in float64 in the order of the vectors. */
+void or_kmeans(const float *x, int64_t n, int d, int K, int niter, float *centroids,
+               double *objective) {
+  int32_t *a = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+  float *best = (float *)malloc((size_t)(n > 0 ? n : 1) * sizeof(float));
+  double *sum = (double *)malloc((size_t)K * d * sizeof(double));
+  int64_t *cnt = (int64_t *)malloc((size_t)K * sizeof(int64_t));
+  for (int r = 0; r < niter; ++r) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+      int bj = 0;
+      float bd = canon(x + i * d, centroids, d, OR_METRIC_L2);
+      for (int j = 1; j < K; ++j) {
+        float dj = canon(x + i * d, centroids + (int64_t)j * d, d, OR_METRIC_L2);
+        if (dj < bd) { bd = dj; bj = j; }
+      }
+      a[i] = bj;
+      best[i] = bd;
+    }
+    double obj = 0.0;
+    for (int64_t i = 0; i < n; ++i) obj += (double)best[i];
+    if (objective) objective[r] = n > 0 ? obj / (double)n : 0.0;
+    for (int64_t t = 0; t < (int64_t)K * d; ++t) sum[t] = 0.0;
+    for (int j = 0; j < K; ++j) cnt[j] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+      double *sj = sum + (int64_t)a[i] * d;
+      for (int t = 0; t < d; ++t) sj[t] += (double)x[i * d + t];
+      ++cnt[a[i]];
+    }
+    for (int j = 0; j < K; ++j) {
+      if (cnt[j] == 0) continue;
+      for (int t = 0; t < d; ++t)
+        centroids[(int64_t)j * d + t] = (float)(sum[(int64_t)j * d + t] / (double)cnt[j]);
+    }
+  }
+  free(a); free(best); free(sum); free(cnt);
+}
+
 /* ---- O3/O4: residual PQ encoding (Sec. 4.1 "product quantizer", Sec. 5.1
  * "Encoding residuals") ---------------------------------------------------
  * codebooks: [M][K][dsub] fp32, K = 2^nbits, dsub = d / M.

@@ -106,6 +106,43 @@ def refine(x, q, cand, k, metric=METRIC_L2):
     return D, I
 
 
+def kmeans(x, init, niter):
+    """Sec. 4.1: niter rounds of Lloyd's iteration from the centroids `init` [K, d].
+    Returns (centroids [K, d] fp32, objective [niter] float64: the mean squared distance to
+    the assigned centroid at each round's assignment step)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    c = np.array(init, dtype=np.float32, order="C", copy=True)
+    n, d = x.shape
+    K = c.shape[0]
+    assert c.shape[1] == d
+    obj = np.zeros(max(niter, 0), dtype=np.float64)
+    _load().or_kmeans(_ptr(x), ctypes.c_int64(n), ctypes.c_int(d), ctypes.c_int(K),
+                      ctypes.c_int(niter), _ptr(c), _ptr(obj))
+    return c, obj
+
+
+def train_ivfpq(x, metric, init_centroids, init_codebooks, nbits, niter):
+    """Training of an IVF-PQ index's parameters (Sec. 5.1: the coarse quantizer is a k-means;
+    Sec. 4.1: each sub-quantizer of the product quantizer is a k-means on its sub-vectors, here
+    of the residuals, Sec. 5.1 "Encoding residuals"):
+      1. coarse centroids = k-means on x from init_centroids;
+      2. every training vector goes to its best centroid under the index metric (or_assign);
+      3. residual = x - centroid, one fp32 subtraction per component;
+      4. sub-codebook m = k-means on the m-th slices of the residuals from init_codebooks[m].
+    Returns (centroids, codebooks [M, K, dsub], objectives [1 + M, niter])."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    M, K, dsub = init_codebooks.shape
+    assert K == 1 << nbits and M * dsub == x.shape[1]
+    objs = np.zeros((1 + M, niter), dtype=np.float64)
+    cent, objs[0] = kmeans(x, init_centroids, niter)
+    a = assign(x, cent, metric)
+    res = x - cent[a]
+    cbs = np.empty_like(np.asarray(init_codebooks, dtype=np.float32))
+    for m in range(M):
+        cbs[m], objs[1 + m] = kmeans(res[:, m * dsub:(m + 1) * dsub], init_codebooks[m], niter)
+    return cent, cbs, objs
+
+
 def assign(x, centroids, metric=METRIC_L2):
     x = np.ascontiguousarray(x, dtype=np.float32)
     centroids = np.ascontiguousarray(centroids, dtype=np.float32)

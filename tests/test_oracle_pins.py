@@ -423,3 +423,105 @@ def test_refining_an_ivfpq_shortlist_never_loses_recall(oracle):
         pos = {int(i): j for j, i in enumerate(If[a])}
         for j in range(10):
             assert Dr[a, j] == Df[a, pos[int(Ir[a, j])]]
+
+
+# ------------------------------------------------------------------ k-means
+
+def _np_lloyd_round(x, c):
+    """One round written with numpy in float64 (only used on integer data, where the
+    nearest centroid is the same in every arithmetic)."""
+    d2 = ((x[:, None, :].astype(np.float64) - c[None, :, :].astype(np.float64)) ** 2).sum(-1)
+    a = d2.argmin(axis=1)                                   # first minimum = smaller centroid number
+    new = c.copy()
+    for j in range(c.shape[0]):
+        if (a == j).any():
+            new[j] = x[a == j].astype(np.float64).mean(axis=0).astype(np.float32)
+    return new, d2.min(axis=1).mean()
+
+
+def test_kmeans_round_is_assign_then_mean(oracle):
+    # Sec. 4.1: k-means applies Lloyd's two conditions in turn.
+    rng = np.random.default_rng(31)
+    x = rng.integers(-20, 21, size=(400, 6)).astype(np.float32)
+    c0 = x[rng.permutation(400)[:7]].copy()
+    c, obj = oracle.kmeans(x, c0, 3)
+    ref = c0
+    for r in range(3):
+        ref, o = _np_lloyd_round(x, ref)
+        # round 0 works on integers (exact); later centroids are fractions, so the fp32 chain
+        # of the reported objective is within fp32 rounding of the float64 value
+        assert abs(obj[r] - o) <= (1e-12 if r == 0 else 1e-6) * max(1.0, o)
+    np.testing.assert_allclose(c, ref, rtol=1e-6, atol=0)
+    # the nearest-centroid rule is or_assign's
+    a = oracle.assign(x, c0)
+    first = np.stack([x[a == j].astype(np.float64).mean(0) if (a == j).any() else c0[j] for j in range(7)])
+    np.testing.assert_allclose(oracle.kmeans(x, c0, 1)[0], first.astype(np.float32), rtol=1e-6)
+
+
+def test_kmeans_objective_never_increases(oracle):
+    # Both of Lloyd's steps can only lower the mean squared error.
+    rng = np.random.default_rng(32)
+    x = rng.standard_normal((3000, 10), dtype=np.float32)
+    c0 = x[:25].copy()
+    c, obj = oracle.kmeans(x, c0, 12)
+    assert (np.diff(obj) <= 1e-7 * obj[:-1]).all(), obj
+    assert obj[-1] < 0.9 * obj[0]
+    # the objective reported for a round is the MSE of assigning to that round's input centroids
+    a = oracle.assign(x, c0)
+    mse0 = ((x.astype(np.float64) - c0[a].astype(np.float64)) ** 2).sum(1).mean()
+    assert abs(obj[0] - mse0) <= 1e-6 * mse0
+
+
+def test_kmeans_finds_separated_blobs_and_stays_there(oracle):
+    rng = np.random.default_rng(33)
+    centres = np.array([[0, 0], [100, 0], [0, 100], [100, 100]], dtype=np.float32)
+    lab = rng.integers(0, 4, size=800)
+    x = (centres[lab] + rng.standard_normal((800, 2))).astype(np.float32)
+    init = np.stack([x[np.flatnonzero(lab == j)[0]] for j in range(4)])       # one point of each blob
+    c, obj = oracle.kmeans(x, init, 4)
+    means = np.stack([x[lab == j].astype(np.float64).mean(0) for j in range(4)]).astype(np.float32)
+    np.testing.assert_allclose(c, means, rtol=1e-6)
+    c2, obj2 = oracle.kmeans(x, c, 3)                                          # a fixed point
+    np.testing.assert_array_equal(c2, c)
+    assert (obj2 == obj2[0]).all()
+
+
+def test_kmeans_degenerate_cases(oracle):
+    rng = np.random.default_rng(34)
+    x = rng.standard_normal((50, 4), dtype=np.float32)
+    c, obj = oracle.kmeans(x, x, 2)                     # one centroid per point: zero error, nothing moves
+    np.testing.assert_array_equal(c, x)
+    assert (obj == 0).all()
+    far = np.concatenate([x[:3], np.full((1, 4), 1e6, dtype=np.float32)])
+    c, _ = oracle.kmeans(x, far, 3)                      # the far centroid never gets a vector: it stays
+    np.testing.assert_array_equal(c[3], far[3])
+    assert not np.array_equal(c[:3], far[:3])
+    dup = np.stack([x[0], x[0], x[1]])                   # identical centroids: the smaller number takes all
+    c, _ = oracle.kmeans(x, dup, 1)
+    np.testing.assert_array_equal(c[1], x[0])
+    c, obj = oracle.kmeans(x, x[:5], 0)                  # no round: the initial centroids come back
+    np.testing.assert_array_equal(c, x[:5])
+
+
+def test_trained_parameters_lower_the_quantization_error(oracle):
+    # Training = k-means for the coarse quantizer and for every sub-quantizer on residual
+    # sub-vectors: each of them lowers its own MSE, and the PQ reconstruction error drops.
+    cfg = S.config("C1", nb=4000, nq=20)
+    x, q = S.make_data(cfg)
+    cent0, cb0 = S.make_index_params(cfg, x)
+    cent, cb, objs = oracle.train_ivfpq(x, L2, cent0, cb0, 8, 6)
+    assert (np.diff(objs, axis=1) <= 1e-7 * objs[:, :-1]).all()
+    def recon_mse(ce, cbk):
+        a = oracle.assign(x, ce)
+        codes = oracle.pq_encode(x, a, ce, cbk, 8)
+        xr = oracle.pq_decode(codes, a, ce, cbk, 8)
+        return ((x.astype(np.float64) - xr) ** 2).sum(1).mean()
+    assert recon_mse(cent, cb) < 0.8 * recon_mse(cent0, cb0)
+    # the residual k-means saw exactly x - c[assign]: its first objective is the MSE of coding
+    # the residual slices with the initial codebook
+    a = oracle.assign(x, cent)
+    res = x - cent[a]
+    for m in (0, 5):
+        sl = res[:, m * 4:(m + 1) * 4]
+        d2 = ((sl[:, None, :].astype(np.float64) - cb0[m][None].astype(np.float64)) ** 2).sum(-1).min(1)
+        assert abs(objs[1 + m, 0] - d2.mean()) <= 1e-5 * d2.mean()
