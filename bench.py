@@ -51,6 +51,10 @@ def main():
                     help="after the timed search, also time the second stage vs_refine(search's k results "
                          "-> K2 best by exact distance) and report it under config.refine (the headline "
                          "value stays the search alone)")
+    ap.add_argument("--train", type=int, default=0, metavar="NITER",
+                    help="train the coarse centroids and the PQ codebooks with NITER rounds of k-means "
+                         "(vs_ivfpq_train, from the sampled parameters, on the first min(nb, 256 * nlist) "
+                         "vectors) before building the index; reported under config.train")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
@@ -102,6 +106,21 @@ def main():
         return bench_flat(args, cfg, x, q, xd, qd)
 
     cent, cb = S.make_index_params_device(cfg, xd) if big else S.make_index_params(cfg, x)
+    train = None
+    if args.train > 0:
+        n_train = min(cfg["nb"], 256 * cfg["nlist"])
+        cent_d, cb_d = torch.from_numpy(cent).cuda(), torch.from_numpy(cb).cuda()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        objs = vs.vs_ivfpq_train(xd[:n_train], metric, cent_d, cb_d, cfg["nbits"], args.train)
+        torch.cuda.synchronize()
+        t_train = time.time() - t0
+        cent, cb = cent_d.cpu().numpy(), cb_d.cpu().numpy()
+        train = {"niter": args.train, "n_train": int(n_train), "seconds": round(t_train, 2),
+                 "coarse_mse_first_last": [objs[0][0], objs[0][-1]],
+                 "pq_mse_first_last": [float(sum(o[0] for o in objs[1:])), float(sum(o[-1] for o in objs[1:]))]}
+        log("trained in %.2fs: coarse MSE %.4g -> %.4g, PQ residual MSE %.4g -> %.4g" % (
+            t_train, objs[0][0], objs[0][-1], train["pq_mse_first_last"][0], train["pq_mse_first_last"][1]))
     ix = vs.IVFPQ(cfg["d"], metric, torch.from_numpy(cent).cuda(), torch.from_numpy(cb).cuda(),
                   cfg["nbits"])
     torch.cuda.synchronize()
@@ -205,7 +224,7 @@ def main():
             "recall_queries": int(nrec), "scanned_codes_per_query": scanned / nq,
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v},
-            **({"refine": refine} if refine else {})},
+            **({"refine": refine} if refine else {}), **({"train": train} if train else {})},
         "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_reg_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,

@@ -94,6 +94,41 @@ VS_API int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int
               int64_t* out_ids, void* hip_stream);
 
 /*
+ * Lloyd's k-means (Sec. 4.1 "The k-means vector quantizer"): niter rounds of
+ *   (1) every training vector goes to its nearest centroid (squared L2 on the fp32 chain
+ *       of vs_flat_search, ties to the smaller centroid number);
+ *   (2) every centroid moves to the mean of its vectors (float64 sum in the order of the
+ *       vectors, divided by their number, rounded to fp32); a centroid that received no
+ *       vector stays where it is.
+ *   x          [n, d] fp32 training vectors, n < 2^31.
+ *   centroids  [K, d] fp32: in, the initial centroids; out, the trained ones.
+ *   objective  HOST pointer to niter doubles, or NULL: the mean squared distance of the
+ *              training vectors to their centroid at step (1) of every round.
+ * Synchronises the stream every round (the assignment is read back to order the vectors).
+ * Errors: null pointers, d < 1, K < 1, niter < 0, n outside [0, 2^31).
+ */
+VS_API int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter,
+              float* centroids, double* objective, void* hip_stream);
+
+/*
+ * Parameters of an IVF-PQ index from training vectors (Sec. 5.1: the coarse quantizer is a
+ * k-means; Sec. 4.1: each sub-quantizer of the product quantizer is a k-means; Sec. 5.1
+ * "Encoding residuals": the product quantizer is trained on residuals):
+ *   1. centroids <- vs_kmeans(x) from the given initial centroids;
+ *   2. every training vector goes to its best centroid under `metric`, as in vs_ivfpq_add;
+ *   3. residual = vector - centroid, one fp32 subtraction per component;
+ *   4. codebooks[m] <- vs_kmeans(m-th slices of the residuals) from the given codebooks[m].
+ *   centroids [nlist, d], codebooks [M, 2^nbits, d / M]: DEVICE, in = initial, out = trained.
+ *   objective HOST pointer to (1 + M) * niter doubles, or NULL: row 0 the coarse k-means,
+ *             row 1 + m sub-quantizer m.
+ * Needs n * d floats of device memory for the residuals.  Blocks until done.
+ * Errors: as vs_ivfpq_create for the shape; n outside [1, 2^31); niter < 0; null pointers.
+ */
+VS_API int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, int32_t nlist,
+                   int32_t M, int32_t nbits, int32_t niter, float* centroids, float* codebooks,
+                   double* objective, void* hip_stream);
+
+/*
  * Create an empty IVF-PQ index (Sec. 5.1 "Inverted files"; Sec. 4.1 product
  * quantizer).  Training is not part of this library: the nlist coarse
  * centroids and the M sub-codebooks are inputs and are copied.

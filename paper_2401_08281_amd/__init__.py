@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lib,
     vs_flat_search,
     vs_refine,
+    vs_kmeans,
+    vs_ivfpq_train,
     vs_ivfpq_add,
     vs_ivfpq_coarse,
     vs_ivfpq_code_size,

@@ -36,6 +36,10 @@ def lib():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.vs_flat_search.restype = ctypes.c_int
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_kmeans.restype = ctypes.c_int
+    L.vs_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_train.restype = ctypes.c_int
+    L.vs_ivfpq_train.argtypes = [vp, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.vs_refine.restype = ctypes.c_int
     L.vs_refine.argtypes = [vp, i64, vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
     L.vs_ivfpq_create.restype = ctypes.c_int
@@ -168,6 +172,39 @@ def vs_refine(x, q, cand_ids, k, metric=METRIC_L2, out_dist=None, out_ids=None):
     _check(lib().vs_refine(_p(x), nb, _p(q), nq, d, metric, _p(cand_ids), kc, k, _p(out_dist),
                            _p(out_ids), _stream()))
     return out_dist, out_ids
+
+
+def vs_kmeans(x, centroids, niter):
+    """Trains `centroids` [K, d] (device tensor, updated in place) on x [n, d]; returns the
+    objective of every round as a list of floats."""
+    x = _dev(x, torch.float32, "x")
+    centroids = _dev(centroids, torch.float32, "centroids")
+    n, d = x.shape
+    K = centroids.shape[0]
+    if centroids.dim() != 2 or centroids.shape[1] != d:
+        raise ValueError("centroids must be [K, d]")
+    obj = (ctypes.c_double * max(niter, 1))()
+    _check(lib().vs_kmeans(_p(x), n, d, K, niter, _p(centroids), obj, _stream()))
+    return [float(obj[r]) for r in range(max(niter, 0))]
+
+
+def vs_ivfpq_train(x, metric, centroids, codebooks, nbits, niter):
+    """Trains centroids [nlist, d] and codebooks [M, 2^nbits, d / M] (device tensors, updated
+    in place) on x [n, d]; returns the objectives as a list of 1 + M lists."""
+    x = _dev(x, torch.float32, "x")
+    centroids = _dev(centroids, torch.float32, "centroids")
+    codebooks = _dev(codebooks, torch.float32, "codebooks")
+    n, d = x.shape
+    nlist = centroids.shape[0]
+    if codebooks.dim() != 3 or centroids.dim() != 2 or centroids.shape[1] != d:
+        raise ValueError("centroids must be [nlist, d] and codebooks [M, K, dsub]")
+    M = codebooks.shape[0]
+    if codebooks.shape[1] != 1 << nbits or M * codebooks.shape[2] != d:
+        raise ValueError("codebooks must be [M, 2^nbits, d / M]")
+    obj = (ctypes.c_double * ((1 + M) * max(niter, 1)))()
+    _check(lib().vs_ivfpq_train(_p(x), n, d, metric, nlist, M, nbits, niter, _p(centroids),
+                                _p(codebooks), obj, _stream()))
+    return [[float(obj[r * niter + t]) for t in range(niter)] for r in range(1 + M)]
 
 
 def vs_ivfpq_create(d, metric, nlist, M, nbits, centroids, codebooks):

@@ -338,6 +338,148 @@ int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
   return VS_OK;
 }
 
+namespace {
+
+// Best row of B [nb, d] for every row of A [n, d] (k-nearest-rows with k = 1, in pieces of 2^20
+// rows): idx [n] and, if asked for, the canon value val [n].  `sc` is grown as needed.
+int nearest_rows(const float* A, int64_t n, const float* B, int64_t nb, int d, int metric,
+                 int32_t* idx, float* val, Scratch& sc, hipStream_t st) {
+  constexpr int64_t kPiece = 1 << 20;
+  const KnnPlan plan = knn_plan(std::min(n, kPiece), nb, d, 1, false);
+  if (int rc = sc.reserve(plan.bytes)) return rc;
+  for (int64_t i0 = 0; i0 < n; i0 += kPiece) {
+    const int64_t ni = std::min(kPiece, n - i0);
+    SelectOut o;
+    o.idx32 = idx + i0;
+    o.val = val ? val + i0 : nullptr;
+    knn_run(plan, static_cast<char*>(sc.p), A + i0 * d, ni, B, nb, d, metric, 1, nullptr, o, st, -1, -1);
+  }
+  return VS_OK;
+}
+
+// niter rounds of Lloyd's iteration on device data.  dev_buf: idx [n] int32 | val [n] fp32 |
+// order [n] int32 | off [K + 1] int64, carved by the caller; sc: scratch of the assignment.
+int kmeans_rounds(const float* x, int64_t n, int d, int K, int niter, float* centroids,
+                  double* objective, int32_t* idx, float* val, int32_t* order, int64_t* off,
+                  Scratch& sc, hipStream_t st) {
+  std::vector<int32_t> h_idx((size_t)n), h_order((size_t)n);
+  std::vector<float> h_val((size_t)n);
+  std::vector<int64_t> h_off((size_t)K + 1), cursor((size_t)K);
+  for (int r = 0; r < niter; ++r) {
+    // (1) nearest centroid of every vector: canon L2, ties to the smaller centroid number
+    if (int rc = nearest_rows(x, n, centroids, K, d, VS_METRIC_L2, idx, val, sc, st)) return rc;
+    HIP_TRY(hipMemcpyAsync(h_idx.data(), idx, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(h_val.data(), val, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    // host bookkeeping, one pass over n numbers: the objective, and the vectors of every
+    // centroid in ascending order (a stable counting sort)
+    double obj = 0.0;
+    std::fill(h_off.begin(), h_off.end(), 0);
+    for (int64_t i = 0; i < n; ++i) {
+      const int32_t j = h_idx[(size_t)i];
+      if (j < 0 || j >= K) return fail(VS_ERR_DEVICE, "k-means: assignment produced centroid %d", j);
+      obj += (double)h_val[(size_t)i];
+      ++h_off[(size_t)j + 1];
+    }
+    if (objective) objective[r] = n > 0 ? obj / (double)n : 0.0;
+    for (int j = 0; j < K; ++j) { h_off[(size_t)j + 1] += h_off[(size_t)j]; cursor[(size_t)j] = h_off[(size_t)j]; }
+    for (int64_t i = 0; i < n; ++i) h_order[(size_t)cursor[(size_t)h_idx[(size_t)i]]++] = (int32_t)i;
+    HIP_TRY(hipMemcpyAsync(order, h_order.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(off, h_off.data(), h_off.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    // (2) every centroid moves to the mean of its vectors
+    launch_segmented_mean(x, d, order, off, K, centroids, st);
+    HIP_TRY(hipStreamSynchronize(st));   // the host arrays are reused by the next round
+  }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+struct DeviceBuf {   // a plain allocation released on scope exit
+  void* p = nullptr;
+  ~DeviceBuf() { if (p) (void)hipFree(p); }
+  int alloc(size_t bytes) { HIP_TRY(hipMalloc(&p, std::max<size_t>(bytes, 256))); return VS_OK; }
+};
+
+}  // namespace
+
+int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter, float* centroids,
+              double* objective, void* hip_stream) {
+  if (n < 0 || n >= (1ll << 31)) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: n outside [0, 2^31)");
+  if (d < 1 || K < 1) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: d = %d, K = %d must be >= 1", d, K);
+  if (niter < 0) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: niter < 0");
+  if (!centroids || (n > 0 && !x)) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: null pointer");
+  if (niter == 0) return VS_OK;
+  if (n == 0) {   // nothing to assign: every centroid stays, the objective is 0
+    if (objective) for (int r = 0; r < niter; ++r) objective[r] = 0.0;
+    return VS_OK;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_kmeans: device %d", dev);
+  Carver cv;
+  const size_t o_idx = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_val = cv.take((size_t)n * sizeof(float));
+  const size_t o_order = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_off = cv.take(((size_t)K + 1) * sizeof(int64_t));
+  DeviceBuf buf;
+  if (int rc = buf.alloc(cv.off)) return rc;
+  char* b = static_cast<char*>(buf.p);
+  std::lock_guard<std::mutex> lock(g_flat_mu);
+  return kmeans_rounds(x, n, d, K, niter, centroids, objective, reinterpret_cast<int32_t*>(b + o_idx),
+                       reinterpret_cast<float*>(b + o_val), reinterpret_cast<int32_t*>(b + o_order),
+                       reinterpret_cast<int64_t*>(b + o_off), g_flat_scratch[dev], st);
+}
+
+int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, int32_t nlist, int32_t M,
+                   int32_t nbits, int32_t niter, float* centroids, float* codebooks,
+                   double* objective, void* hip_stream) {
+  if (n < 1 || n >= (1ll << 31)) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: n outside [1, 2^31)");
+  if (d < 1 || nlist < 1 || M < 1) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: d, nlist, M must be >= 1");
+  if (d % M != 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: d = %d is not a multiple of M = %d", d, M);
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: unknown metric %d", metric);
+  if (nbits != 4 && nbits != 8) return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_train: nbits = %d (only 4 and 8)", nbits);
+  if (niter < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: niter < 0");
+  if (!x || !centroids || !codebooks) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_train: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_train: device %d", dev);
+  const int K = 1 << nbits, dsub = d / M, kmax = std::max(nlist, K);
+  Carver cv;
+  const size_t o_idx = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_val = cv.take((size_t)n * sizeof(float));
+  const size_t o_order = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_off = cv.take(((size_t)kmax + 1) * sizeof(int64_t));
+  const size_t o_res = cv.take((size_t)n * d * sizeof(float));
+  DeviceBuf buf;
+  if (int rc = buf.alloc(cv.off)) return rc;
+  char* b = static_cast<char*>(buf.p);
+  int32_t* idx = reinterpret_cast<int32_t*>(b + o_idx);
+  float* val = reinterpret_cast<float*>(b + o_val);
+  int32_t* order = reinterpret_cast<int32_t*>(b + o_order);
+  int64_t* off = reinterpret_cast<int64_t*>(b + o_off);
+  float* res = reinterpret_cast<float*>(b + o_res);
+  std::lock_guard<std::mutex> lock(g_flat_mu);
+  Scratch& sc = g_flat_scratch[dev];
+  // 1. coarse quantizer: k-means on the training vectors
+  if (int rc = kmeans_rounds(x, n, d, nlist, niter, centroids, objective, idx, val, order, off, sc, st)) return rc;
+  // 2. + 3. list of every training vector under the index metric (as vs_ivfpq_add), residuals
+  if (int rc = nearest_rows(x, n, centroids, nlist, d, metric, idx, nullptr, sc, st)) return rc;
+  launch_residual_slices(x, n, d, dsub, centroids, idx, res, st);
+  // 4. one k-means per sub-quantizer on its slice of the residuals
+  for (int m = 0; m < M; ++m) {
+    if (int rc = kmeans_rounds(res + (size_t)m * n * dsub, n, dsub, K, niter,
+                               codebooks + (size_t)m * K * dsub,
+                               objective ? objective + (size_t)(1 + m) * niter : nullptr, idx, val,
+                               order, off, sc, st))
+      return rc;
+  }
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
 int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, int32_t M,
                     int32_t nbits, const float* centroids, const float* codebooks,
                     void* hip_stream) {

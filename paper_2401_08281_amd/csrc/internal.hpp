@@ -98,6 +98,15 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
                    int* fb_rows, u64* fb_partial, hipStream_t st);
 int read_fallback_total(unsigned long long* out);
 
+// ---- kernels_train.hip ---------------------------------------------------------
+// centroids[j] <- mean of the rows x[order[off[j] .. off[j + 1])] (float64 sum in that order);
+// a centroid with an empty range keeps its value
+void launch_segmented_mean(const float* x, int d, const int32_t* order, const int64_t* off, int K,
+                           float* centroids, hipStream_t st);
+// out[m][i][:] = (x[i] - centroids[list_of[i]])[m * dsub : (m + 1) * dsub], out is [d / dsub][n][dsub]
+void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,
+                            const int32_t* list_of, float* out, hipStream_t st);
+
 // ---- kernels_refine.hip --------------------------------------------------------
 // k best of each query's kc candidates by canon distance to the candidates' rows of x
 size_t refine_lds_bytes(int d, int k);   // LDS of one workgroup; the launch needs it to fit

@@ -395,6 +395,71 @@ def test_ivfpq_search_then_refine_pipeline(vs, oracle):
     ix.close()
 
 
+# ------------------------------------------------- k-means and parameter training
+
+KMEANS_CASES = [
+    # name, n, d, K, niter, kind
+    ("gauss_d32_k16", 5_000, 32, 16, 5, "gauss"),            # matrix-core route, three passes
+    ("sift_d128_k64", 20_000, 128, 64, 4, "sift"),            # matrix-core route, exact data in round 0
+    ("unit_d96_k300", 30_000, 96, 300, 3, "unit"),
+    ("subvectors_d4_k256", 20_000, 4, 256, 4, "gauss"),       # a sub-quantizer's shape: canon tiles
+    ("odd_d30_k7", 3_001, 30, 7, 6, "gauss"),
+    ("more_centroids_than_vectors", 40, 8, 64, 2, "gauss"),
+]
+
+
+@pytest.mark.parametrize("name,n,d,K,niter,kind", KMEANS_CASES, ids=[c[0] for c in KMEANS_CASES])
+def test_kmeans_matches_oracle_bit_for_bit(vs, oracle, name, n, d, K, niter, kind):
+    """Assignment is canon on both sides and the means are float64 sums in a fixed order, so
+    the trained centroids are identical; the objective is a float64 sum of identical terms."""
+    import torch
+    say("kmeans %s n=%d d=%d K=%d niter=%d" % (name, n, d, K, niter))
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    if kind == "gauss":
+        x = rng.standard_normal((n, d), dtype=np.float32)
+    elif kind == "unit":
+        x, _ = S.make_data(S.config("C4", nb=n, nq=1, d=d, ncomp=30))
+    else:
+        x, _ = S.make_data(S.config("C2", nb=n, nq=1, d=d, ncomp=30))
+    init = x[rng.permutation(n)[:K]].copy() if K <= n else rng.standard_normal((K, d), dtype=np.float32)
+    if name == "odd_d30_k7":
+        init[3] = 1e4                                          # a centroid no vector ever picks
+    c = dev(init.copy())
+    obj = vs.vs_kmeans(dev(x), c, niter)
+    co, objo = oracle.kmeans(x, init, niter)
+    np.testing.assert_array_equal(host(c), co)
+    np.testing.assert_allclose(np.array(obj), objo, rtol=1e-12)
+    if name == "odd_d30_k7":
+        np.testing.assert_array_equal(host(c)[3], init[3])
+
+
+@pytest.mark.parametrize("name", ["c1", "pq4_l2", "ip_8bit"])
+def test_ivfpq_training_matches_oracle_bit_for_bit(vs, oracle, name):
+    cfg = dict(IVF_CASES[name][0])
+    cfg["nb"] = min(cfg["nb"], 6_000)
+    say("train %s nb=%d d=%d nlist=%d M=%d nbits=%d metric=%d" % (
+        name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"], cfg["nbits"], cfg["metric"]))
+    x, q = S.make_data(cfg)
+    cent0, cb0 = S.make_index_params(cfg, x)
+    cent, cb = dev(cent0.copy()), dev(cb0.copy())
+    objs = vs.vs_ivfpq_train(dev(x), cfg["metric"], cent, cb, cfg["nbits"], 4)
+    ce, cbk, objo = oracle.train_ivfpq(x, cfg["metric"], cent0, cb0, cfg["nbits"], 4)
+    np.testing.assert_array_equal(host(cent), ce)
+    np.testing.assert_array_equal(host(cb), cbk)
+    np.testing.assert_allclose(np.array(objs), objo, rtol=1e-12)
+    # the trained parameters make a working index: storage and search agree with the oracle
+    ix = vs.IVFPQ(cfg["d"], cfg["metric"], cent, cb, cfg["nbits"])
+    ix.add(dev(x))
+    orc = oracle.OracleIVFPQ(cfg["d"], cfg["metric"], ce, cbk, cfg["nbits"])
+    orc.add(x)
+    check_storage(ix, orc)
+    D, I = ix.search(dev(q), 10, 4)
+    Do, Io = orc.search(q, 10 + EXTRA, 4)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
+    check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+    ix.close()
+
+
 # ------------------------------------------------- the two largest configurations
 
 def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
