@@ -389,6 +389,50 @@ void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
   free(probes); free(cdist);
 }
 
+/* ---- IVF-Flat search (Sec. 5.1 "Inverted files" with vectors stored as they
+ * are; App. A.3 lists it among the GPU indexes) ---------------------------------
+ * Same two steps as IVF-PQ -- the nprobe best lists by or_coarse_probe, then a
+ * selection over the entries of those lists -- but an entry is the vector
+ * itself, so its distance is the definition (float64 sum, rounded once), as in
+ * or_flat_search.  vecs: [ntotal, d] in list order (list l owns rows
+ * list_offsets[l] .. list_offsets[l + 1]). */
+void or_ivfflat_search(const float *q, int64_t nq, int d, int metric, int nlist,
+                       const float *centroids, const int64_t *list_offsets, const float *vecs,
+                       const int64_t *ids, int k, int nprobe, float *D, int64_t *I,
+                       int64_t *nscanned, int32_t *probes_out) {
+  if (nprobe > nlist) nprobe = nlist;
+  int32_t *probes = (int32_t *)malloc(sizeof(int32_t) * nq * nprobe);
+  float *cdist = (float *)malloc(sizeof(float) * nq * nprobe);
+  or_coarse_probe(q, nq, centroids, nlist, d, metric, nprobe, probes, cdist);
+  if (probes_out) memcpy(probes_out, probes, sizeof(int32_t) * nq * nprobe);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t a = 0; a < nq; ++a) {
+    const float *qa = q + a * d;
+    topk_t h;
+    topk_init(&h, k, metric, D + a * k, I + a * k);
+    int64_t visited = 0;
+    for (int p = 0; p < nprobe; ++p) {
+      const int l = probes[a * nprobe + p];
+      for (int64_t s = list_offsets[l]; s < list_offsets[l + 1]; ++s) {
+        const float *xs = vecs + s * d;
+        double acc = 0.0;
+        if (metric == OR_METRIC_L2) {
+          for (int t = 0; t < d; ++t) {
+            double diff = (double)qa[t] - (double)xs[t];
+            acc += diff * diff;
+          }
+        } else {
+          for (int t = 0; t < d; ++t) acc += (double)qa[t] * (double)xs[t];
+        }
+        topk_push(&h, (float)acc, ids[s]);
+        ++visited;
+      }
+    }
+    if (nscanned) nscanned[a] = visited;
+  }
+  free(probes); free(cdist);
+}
+
 int or_num_threads(void) {
 #ifdef _OPENMP
   extern int omp_get_max_threads(void);

@@ -213,6 +213,67 @@ def recall(I_found, I_true, n=None):
     return hits / float(I_found.shape[0] * n)
 
 
+class OracleIVFFlat:
+    """IVF index that stores the vectors themselves (Sec. 5.1), as plain numpy arrays.
+    add(): assignment as in OracleIVFPQ, stable append; search(): probes, exact distances to
+    the vectors of the probed lists, selection."""
+
+    def __init__(self, d, metric, centroids):
+        self.d = int(d)
+        self.metric = int(metric)
+        self.centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+        self.nlist = self.centroids.shape[0]
+        assert self.centroids.shape[1] == self.d
+        self.add_ids = np.empty(0, dtype=np.int64)
+        self.add_list_of = np.empty(0, dtype=np.int32)
+        self.add_vecs = np.empty((0, self.d), dtype=np.float32)
+        self._relayout()
+
+    @property
+    def ntotal(self):
+        return self.add_ids.shape[0]
+
+    def _relayout(self):
+        order = np.argsort(self.add_list_of, kind="stable")
+        self.ids = np.ascontiguousarray(self.add_ids[order])
+        self.vecs = np.ascontiguousarray(self.add_vecs[order])
+        sizes = np.bincount(self.add_list_of, minlength=self.nlist).astype(np.int64)
+        self.list_offsets = np.zeros(self.nlist + 1, dtype=np.int64)
+        np.cumsum(sizes, out=self.list_offsets[1:])
+
+    def add(self, x, ids=None):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        n = x.shape[0]
+        if ids is None:  # sequential ids continue from ntotal (Sec. 6.1)
+            ids = np.arange(self.ntotal, self.ntotal + n, dtype=np.int64)
+        list_of = assign(x, self.centroids, self.metric)
+        self.add_ids = np.concatenate([self.add_ids, np.asarray(ids, dtype=np.int64)])
+        self.add_list_of = np.concatenate([self.add_list_of, list_of])
+        self.add_vecs = np.concatenate([self.add_vecs, x])
+        self._relayout()
+        return list_of
+
+    def list_sizes(self):
+        return np.diff(self.list_offsets)
+
+    def search(self, q, k, nprobe, return_stats=False):
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        nq = q.shape[0]
+        npr = min(nprobe, self.nlist)
+        D = np.empty((nq, k), dtype=np.float32)
+        I = np.empty((nq, k), dtype=np.int64)
+        nscanned = np.zeros(nq, dtype=np.int64)
+        probes = np.empty((nq, npr), dtype=np.int32)
+        _load().or_ivfflat_search(
+            _ptr(q), ctypes.c_int64(nq), ctypes.c_int(self.d), ctypes.c_int(self.metric),
+            ctypes.c_int(self.nlist), _ptr(self.centroids), _ptr(self.list_offsets),
+            _ptr(self.vecs), _ptr(self.ids), ctypes.c_int(k), ctypes.c_int(nprobe), _ptr(D),
+            _ptr(I), _ptr(nscanned), _ptr(probes))
+        if return_stats:
+            return D, I, nscanned, probes
+        return D, I
+
+
 class OracleIVFPQ:
     """IVF-PQ index held as plain numpy arrays (Sec. 5.1).
 

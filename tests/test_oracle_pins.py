@@ -525,3 +525,63 @@ def test_trained_parameters_lower_the_quantization_error(oracle):
         sl = res[:, m * 4:(m + 1) * 4]
         d2 = ((sl[:, None, :].astype(np.float64) - cb0[m][None].astype(np.float64)) ** 2).sum(-1).min(1)
         assert abs(objs[1 + m, 0] - d2.mean()) <= 1e-5 * d2.mean()
+
+
+# ------------------------------------------------------------------ IVF-Flat
+
+def _ivfflat(oracle, nb=2000, nq=30, metric=L2, nlist=16):
+    cfg = S.config("C1", nb=nb, nq=nq, nlist=nlist, metric=metric)
+    x, q = S.make_data(cfg)
+    cent = S.make_centroids(x, nlist, cfg["seed"])
+    ix = oracle.OracleIVFFlat(cfg["d"], metric, cent)
+    ix.add(x)
+    return x, q, cent, ix
+
+
+@pytest.mark.parametrize("metric", [L2, IP])
+def test_ivfflat_with_all_lists_probed_is_flat_search(oracle, metric):
+    # Sec. 5.1: the inverted file only restricts which vectors are compared with the query.
+    x, q, cent, ix = _ivfflat(oracle, metric=metric)
+    D, I = ix.search(q, 12, 16)
+    Df, If = oracle.flat_search(x, q, 12, metric)
+    np.testing.assert_array_equal(I, If)
+    np.testing.assert_array_equal(D, Df)
+
+
+def test_ivfflat_visits_exactly_the_probed_lists(oracle):
+    x, q, cent, ix = _ivfflat(oracle)
+    a = oracle.assign(x, cent)
+    prev = 0.0
+    _, It = oracle.flat_search(x, q, 10, L2)
+    for nprobe in (1, 3, 8, 16):
+        D, I, nscanned, probes = ix.search(q, 10, nprobe, return_stats=True)
+        po, _ = oracle.coarse_probe(q, cent, nprobe, L2)
+        np.testing.assert_array_equal(probes, po)
+        full = np_pairwise(q, x, L2).astype(np.float32)
+        for qi in range(q.shape[0]):
+            members = np.flatnonzero(np.isin(a, probes[qi]))          # ascending ids
+            assert nscanned[qi] == members.size
+            v = full[qi, members]
+            order = np.argsort(v, kind="stable")[:10]
+            np.testing.assert_array_equal(I[qi, :order.size], members[order])
+            np.testing.assert_allclose(D[qi, :order.size], v[order], rtol=1e-6)
+        r = oracle.recall(I, It)
+        assert r >= prev                                               # more lists never lose a neighbour
+        prev = r
+    assert prev == 1.0
+
+
+def test_ivfflat_add_in_pieces_custom_ids_and_padding(oracle):
+    x, q, cent, ix = _ivfflat(oracle, nb=300)
+    ix2 = oracle.OracleIVFFlat(32, L2, cent)
+    ids = np.arange(300, dtype=np.int64) * 7 + 3
+    ix2.add(x[:100], ids[:100]); ix2.add(x[100:], ids[100:])
+    D, I = ix.search(q, 5, 4)
+    D2, I2 = ix2.search(q, 5, 4)
+    np.testing.assert_array_equal(D, D2)
+    np.testing.assert_array_equal(I * 7 + 3, I2)
+    np.testing.assert_array_equal(ix.list_sizes(), ix2.list_sizes())
+    D, I, nscanned, _ = ix.search(q, 200, 1, return_stats=True)       # k larger than one list
+    for qi in range(q.shape[0]):
+        n = int(nscanned[qi])
+        assert (I[qi, :n] >= 0).all() and (I[qi, n:] == -1).all() and np.isposinf(D[qi, n:]).all()
