@@ -55,6 +55,9 @@ def main():
                     help="train the coarse centroids and the PQ codebooks with NITER rounds of k-means "
                          "(vs_ivfpq_train, from the sampled parameters, on the first min(nb, 256 * nlist) "
                          "vectors) before building the index; reported under config.train")
+    ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat"],
+                    help="ivfflat: the same workload's vectors and centroids in an IVF-Flat index "
+                         "(secondary line; the default ivfpq is the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
@@ -106,6 +109,8 @@ def main():
         return bench_flat(args, cfg, x, q, xd, qd)
 
     cent, cb = S.make_index_params_device(cfg, xd) if big else S.make_index_params(cfg, x)
+    if args.index == "ivfflat":
+        return bench_ivfflat(args, cfg, x, q, xd, qd, cent)
     train = None
     if args.train > 0:
         n_train = min(cfg["nb"], 256 * cfg["nlist"])
@@ -314,6 +319,73 @@ def bench_flat(args, cfg, x, q, xd, qd):
         "config": {"workload": "C2: flat L2, nb=%d d=%d nq=%d k=%d" % (nb, d, nq, k),
                    "stage_ms_per_step": {s: round(v[0] / args.steps, 3) for s, v in prof.items() if v[1]}},
         "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
+    """Secondary workload: IVF-Flat on the vectors and centroids of an IVF-PQ configuration."""
+    import numpy as np
+    import torch
+    import oracle
+    import paper_2401_08281_amd as vs
+    nq, k, metric, d, nb, nprobe = cfg["nq"], cfg["k"], cfg["metric"], cfg["d"], cfg["nb"], cfg["nprobe"]
+    ix = vs.IVFFlat(d, metric, torch.from_numpy(cent).cuda())
+    t0 = time.time()
+    for s0 in range(0, nb, 10_000_000):
+        ix.add(xd[s0:s0 + 10_000_000])
+    torch.cuda.synchronize()
+    t_add = time.time() - t0
+    sizes = ix.list_sizes()
+    D = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+    for _ in range(args.warmup):
+        ix.search(qd, k, nprobe, D, I)
+    torch.cuda.synchronize()
+    vs.vs_profile_enable(True); vs.vs_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ix.search(qd, k, nprobe, D, I)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = vs.vs_profile_read(); vs.vs_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    scan_ms = prof["scan"][0] / max(prof["scan"][1], 1)
+    # algorithmic bytes of the scan: rows visited x d x 4 (probes from the same coarse quantizer)
+    ixq = vs.IVFPQ(d, metric, torch.from_numpy(cent).cuda(),
+                   torch.zeros((1, 256, d), dtype=torch.float32, device="cuda"), 8)
+    probes, _ = ixq.coarse(qd, nprobe)
+    ixq.close()
+    scanned = int(sizes[probes.long()].sum().item())
+    algo = scanned * d * 4
+    achieved = algo / (scan_ms * 1e-3) / 1e9
+    nrec = min(nq, 1000)
+    Dg, Ig = vs.vs_flat_search(xd, qd[:nrec].contiguous(), k, metric)
+    I_h, Ig_h = I.cpu().numpy(), Ig.cpu().numpy()
+    hit_k = np.mean([len(set(I_h[a].tolist()) & set(Ig_h[a].tolist())) / float(k) for a in range(nrec)])
+    cpu = None
+    if not args.no_cpu_baseline and x is not None:
+        orc = oracle.OracleIVFFlat(d, metric, cent)
+        orc.add(x)
+        n = min(nq, 500)
+        t0 = time.perf_counter(); orc.search(q[:n], k, nprobe); dt = time.perf_counter() - t0
+        cpu = {"value": n / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "first %d of %d queries, %.1f s" % (n, nq, dt)}
+    out = {
+        "metric": "IVF-Flat queries/sec at fixed nprobe", "value": nq / (ms_per_step * 1e-3),
+        "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s vectors in IVF%d,Flat %s, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
+            args.workload, cfg["nlist"], "IP" if metric else "L2", nb, d, nq, k, nprobe),
+            "recall_k_at_k": round(float(hit_k), 4), "recall_queries": int(nrec),
+            "scanned_vectors_per_query": scanned / nq, "index_build_s": round(t_add, 2),
+            "stage_ms_per_step": {s: round(v[0] / args.steps, 4) for s, v in prof.items() if v[1]}},
+        "roofline": {"bound": "hbm", "kernel": "ivfflat_scan_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": algo, "kernel_ms": scan_ms},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

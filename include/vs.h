@@ -200,6 +200,28 @@ VS_API int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stre
 VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
                     int32_t* probes, float* coarse_dist, void* hip_stream);
 
+/* ---- IVF-Flat ----------------------------------------------------------------
+ * The inverted file of Sec. 5.1 with the vectors stored as they are (no codec; App. A.3
+ * "GPU Faiss" lists it among the GPU indexes).  Coarse quantizer, list assignment, ids,
+ * probing and selection are those of the IVF-PQ index above; the scan computes the exact
+ * distance (the fp32 chain of vs_flat_search) to every vector of the probed lists, so with
+ * nprobe = nlist the result is that of vs_flat_search.  Same conventions, limits and
+ * errors as the vs_ivfpq_* calls of the same name. */
+typedef struct vs_ivfflat vs_ivfflat;
+VS_API int vs_ivfflat_create(vs_ivfflat** out, int32_t d, int32_t metric, int32_t nlist,
+                      const float* centroids /* [nlist, d], copied */, void* hip_stream);
+VS_API void vs_ivfflat_destroy(vs_ivfflat* ix);
+VS_API int64_t vs_ivfflat_ntotal(const vs_ivfflat* ix);
+VS_API int vs_ivfflat_add(vs_ivfflat* ix, const float* x, int64_t n, const int64_t* ids,
+                   void* hip_stream);
+VS_API int vs_ivfflat_search(const vs_ivfflat* ix, const float* q, int64_t nq, int32_t k,
+                      int32_t nprobe, float* out_dist, int64_t* out_ids, void* hip_stream);
+VS_API int vs_ivfflat_get_list_sizes(const vs_ivfflat* ix, int64_t* sizes, void* hip_stream);
+/* storage order: ids [ntotal], list of every entry [ntotal], stored rows [ntotal, d]
+ * (DEVICE, each may be NULL) */
+VS_API int vs_ivfflat_get_storage(const vs_ivfflat* ix, int64_t* ids, int32_t* list_of, float* rows,
+                           void* hip_stream);
+
 /* ---- stage timing (used by benchmarks) ----------------------------------- */
 
 enum {

@@ -36,6 +36,20 @@ def lib():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.vs_flat_search.restype = ctypes.c_int
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_ivfflat_create.restype = ctypes.c_int
+    L.vs_ivfflat_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, vp, vp]
+    L.vs_ivfflat_destroy.restype = None
+    L.vs_ivfflat_destroy.argtypes = [vp]
+    L.vs_ivfflat_ntotal.restype = i64
+    L.vs_ivfflat_ntotal.argtypes = [vp]
+    L.vs_ivfflat_add.restype = ctypes.c_int
+    L.vs_ivfflat_add.argtypes = [vp, vp, i64, vp, vp]
+    L.vs_ivfflat_search.restype = ctypes.c_int
+    L.vs_ivfflat_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    L.vs_ivfflat_get_list_sizes.restype = ctypes.c_int
+    L.vs_ivfflat_get_list_sizes.argtypes = [vp, vp, vp]
+    L.vs_ivfflat_get_storage.restype = ctypes.c_int
+    L.vs_ivfflat_get_storage.argtypes = [vp, vp, vp, vp, vp]
     L.vs_kmeans.restype = ctypes.c_int
     L.vs_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
     L.vs_ivfpq_train.restype = ctypes.c_int
@@ -284,6 +298,97 @@ def vs_ivfpq_coarse(h, q, nprobe, nlist):
     cdist = torch.empty((nq, npr), dtype=torch.float32, device=q.device)
     _check(lib().vs_ivfpq_coarse(h, _p(q), nq, nprobe, _p(probes), _p(cdist), _stream()))
     return probes, cdist
+
+
+def vs_ivfflat_create(d, metric, nlist, centroids):
+    centroids = _dev(centroids, torch.float32, "centroids")
+    if centroids is not None and centroids.numel() != nlist * d:
+        raise ValueError("centroids must hold nlist * d floats")
+    h = ctypes.c_void_p(0)
+    _check(lib().vs_ivfflat_create(ctypes.byref(h), d, metric, nlist, _p(centroids), _stream()))
+    return h
+
+
+def vs_ivfflat_destroy(h):
+    lib().vs_ivfflat_destroy(h)
+
+
+def vs_ivfflat_ntotal(h):
+    return int(lib().vs_ivfflat_ntotal(h))
+
+
+def vs_ivfflat_add(h, x, ids=None):
+    x = _dev(x, torch.float32, "x")
+    ids = _dev(ids, torch.int64, "ids")
+    if ids is not None and ids.numel() != x.shape[0]:
+        raise ValueError("ids must hold one id per row of x")
+    _check(lib().vs_ivfflat_add(h, _p(x), x.shape[0], _p(ids), _stream()))
+
+
+def vs_ivfflat_search(h, q, k, nprobe, out_dist=None, out_ids=None):
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_ivfflat_search(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_ivfflat_get_list_sizes(h, nlist, device):
+    sizes = torch.empty(nlist, dtype=torch.int64, device=device)
+    _check(lib().vs_ivfflat_get_list_sizes(h, _p(sizes), _stream()))
+    return sizes
+
+
+def vs_ivfflat_get_storage(h, d, device):
+    """(ids [ntotal], list of every entry [ntotal], stored rows [ntotal, d]) in storage order."""
+    n = vs_ivfflat_ntotal(h)
+    ids = torch.empty(n, dtype=torch.int64, device=device)
+    list_of = torch.empty(n, dtype=torch.int32, device=device)
+    rows = torch.empty((n, d), dtype=torch.float32, device=device)
+    _check(lib().vs_ivfflat_get_storage(h, _p(ids), _p(list_of), _p(rows), _stream()))
+    return ids, list_of, rows
+
+
+class IVFFlat:
+    """Owner of one vs_ivfflat handle (thin convenience over the functions above)."""
+
+    def __init__(self, d, metric, centroids):
+        self.d, self.metric = int(d), int(metric)
+        self.nlist = int(centroids.shape[0])
+        self.device = centroids.device
+        self.h = vs_ivfflat_create(self.d, self.metric, self.nlist, centroids)
+
+    def close(self):
+        if getattr(self, "h", None) is not None:
+            vs_ivfflat_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def ntotal(self):
+        return vs_ivfflat_ntotal(self.h)
+
+    def add(self, x, ids=None):
+        vs_ivfflat_add(self.h, x, ids)
+
+    def search(self, q, k, nprobe, out_dist=None, out_ids=None):
+        return vs_ivfflat_search(self.h, q, k, nprobe, out_dist, out_ids)
+
+    def list_sizes(self):
+        return vs_ivfflat_get_list_sizes(self.h, self.nlist, self.device)
+
+    def storage(self):
+        return vs_ivfflat_get_storage(self.h, self.d, self.device)
 
 
 class IVFPQ:

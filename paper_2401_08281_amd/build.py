@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvs.so")
 SOURCES = ["api.hip", "kernels_dist.hip", "kernels_select.hip", "kernels_ivfpq.hip", "kernels_mfma.hip",
-           "kernels_refine.hip", "kernels_train.hip"]
+           "kernels_refine.hip", "kernels_train.hip",
+           "kernels_ivfflat.hip"]
 HEADERS = ["common.hpp", "internal.hpp", os.path.join("..", "..", "include", "vs.h")]
 
 FLAGS = [

@@ -230,6 +230,11 @@ struct vs_ivfpq {
   mutable Scratch scratch;
 };
 
+// IVF-Flat shares the lists, the coarse quantizer and the bookkeeping of the IVF-PQ index
+struct vs_ivfflat {
+  vs_ivfpq core;
+};
+
 extern "C" {
 
 const char* vs_last_error(void) { return g_err; }
@@ -527,8 +532,7 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
   return VS_OK;
 }
 
-void vs_ivfpq_destroy(vs_ivfpq* ix) {
-  if (!ix) return;
+static void ivf_free_device_memory(vs_ivfpq* ix) {
   if (ix->centroids) (void)hipFree(ix->centroids);
   if (ix->codebooks) (void)hipFree(ix->codebooks);
   if (ix->list_off) (void)hipFree(ix->list_off);
@@ -536,11 +540,110 @@ void vs_ivfpq_destroy(vs_ivfpq* ix) {
   if (ix->ids) (void)hipFree(ix->ids);
   if (ix->plane_mem) (void)hipFree(ix->plane_mem);
   ix->scratch.release();
+}
+
+void vs_ivfpq_destroy(vs_ivfpq* ix) {
+  if (!ix) return;
+  ivf_free_device_memory(ix);
   delete ix;
 }
 
 int64_t vs_ivfpq_ntotal(const vs_ivfpq* ix) { return ix ? ix->ntotal : -1; }
 int32_t vs_ivfpq_code_size(const vs_ivfpq* ix) { return ix ? ix->g.code_size : -1; }
+
+namespace {
+
+// Where the n new vectors of an add go: list of every vector (device), its position in the
+// grown list-contiguous storage (device), the grown offsets (device and host), and `extra`
+// bytes of scratch for the caller.  Steps: (1) best centroid on the canon chain, ties to the
+// smaller list; (2) stable placement -- the new entries of a list follow its old ones, in the
+// order given (bookkeeping on the host: one pass over n list numbers).
+struct Placement {
+  int32_t* list_of = nullptr;
+  int64_t* dest = nullptr;
+  int64_t* new_off = nullptr;
+  char* extra = nullptr;
+  std::vector<int64_t> h_new;
+};
+
+int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, Placement* pl,
+                         hipStream_t st, const char* who) {
+  const IvfpqDims& g = ix->g;
+  // scratch: work space of the MFMA assignment (pieces of at most kAssignPiece vectors) |
+  // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets
+  constexpr int64_t kAssignPiece = 1 << 20;
+  KnnPlan plan = knn_plan(std::min(n, kAssignPiece), g.nlist, g.d, 1, ix->has_planes);
+  if (!plan.mfma) plan.bytes = 0;
+  Carver cv;
+  const size_t o_knn = cv.take(plan.bytes);
+  const size_t o_keys = cv.take((size_t)n * sizeof(u64));
+  const size_t o_list = cv.take((size_t)n * sizeof(int32_t));
+  const size_t o_extra = cv.take(extra);
+  const size_t o_dest = cv.take((size_t)n * sizeof(int64_t));
+  const size_t o_off = cv.take(((size_t)g.nlist + 1) * sizeof(int64_t));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  u64* keys = reinterpret_cast<u64*>(base + o_keys);
+  pl->list_of = reinterpret_cast<int32_t*>(base + o_list);
+  pl->extra = base + o_extra;
+  pl->dest = reinterpret_cast<int64_t*>(base + o_dest);
+  pl->new_off = reinterpret_cast<int64_t*>(base + o_off);
+
+  if (plan.mfma) {
+    for (int64_t i0 = 0; i0 < n; i0 += kAssignPiece) {
+      const int64_t ni = std::min(kAssignPiece, n - i0);
+      SelectOut o;
+      o.idx32 = pl->list_of + i0;
+      knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
+              ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1);
+    }
+  } else {
+    launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
+    launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
+    launch_keys_to_index32(keys, n, pl->list_of, st);
+  }
+
+  std::vector<int32_t> h_list((size_t)n);
+  HIP_TRY(hipMemcpyAsync(h_list.data(), pl->list_of, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  std::vector<int64_t> add_cnt((size_t)g.nlist, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t l = h_list[(size_t)i];
+    if (l < 0 || l >= g.nlist) return fail(VS_ERR_DEVICE, "%s: assignment kernel produced list %d", who, l);
+    ++add_cnt[(size_t)l];
+  }
+  pl->h_new.assign((size_t)g.nlist + 1, 0);
+  std::vector<int64_t> cursor((size_t)g.nlist);
+  for (int l = 0; l < g.nlist; ++l) {
+    const int64_t old_sz = ix->h_off[(size_t)l + 1] - ix->h_off[(size_t)l];
+    pl->h_new[(size_t)l + 1] = pl->h_new[(size_t)l] + old_sz + add_cnt[(size_t)l];
+    cursor[(size_t)l] = pl->h_new[(size_t)l] + old_sz;
+  }
+  std::vector<int64_t> h_dest((size_t)n);
+  for (int64_t i = 0; i < n; ++i) h_dest[(size_t)i] = cursor[(size_t)h_list[(size_t)i]]++;
+  HIP_TRY(hipMemcpyAsync(pl->dest, h_dest.data(), (size_t)n * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(pl->new_off, pl->h_new.data(), pl->h_new.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));   // h_dest and h_list leave scope
+  return VS_OK;
+}
+
+// Installs the grown storage (already filled on the stream) in place of the old one.
+int ivf_commit_storage(vs_ivfpq* ix, uint8_t* codes, int64_t* new_ids, int64_t total,
+                       Placement* pl, hipStream_t st, const char* who) {
+  hipError_t e = hipMemcpyAsync(ix->list_off, pl->new_off, pl->h_new.size() * sizeof(int64_t), hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) {
+    (void)hipFree(codes); (void)hipFree(new_ids);
+    return fail(VS_ERR_DEVICE, "%s: %s", who, hipGetErrorString(e));
+  }
+  if (ix->codes) (void)hipFree(ix->codes);
+  if (ix->ids) (void)hipFree(ix->ids);
+  ix->codes = codes; ix->ids = new_ids; ix->ntotal = total; ix->h_off.swap(pl->h_new);
+  return VS_OK;
+}
+
+}  // namespace
 
 int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, void* hip_stream) {
   if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_add: index is null");
@@ -550,67 +653,12 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
   if (ix->ntotal + n >= (1ll << 32)) return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_add: more than 2^32 - 1 stored vectors");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const IvfpqDims& g = ix->g;
+  Placement pl;
+  // one byte per (vector, m) for the codes before they are packed into their lists
+  if (int rc = ivf_assign_and_place(ix, x, n, (size_t)n * g.M, &pl, st, "vs_ivfpq_add")) return rc;
+  uint8_t* tmp_codes = reinterpret_cast<uint8_t*>(pl.extra);
+  launch_pq_encode(g, x, n, pl.list_of, ix->centroids, ix->codebooks, tmp_codes, st);
 
-  // scratch: best keys [n] | list_of [n] | one byte per (vector, m) [n, M] | dest [n] | new offsets
-  // | work space of the MFMA assignment, in pieces of at most kAssignPiece vectors
-  constexpr int64_t kAssignPiece = 1 << 20;
-  KnnPlan plan = knn_plan(std::min(n, kAssignPiece), g.nlist, g.d, 1, ix->has_planes);
-  if (!plan.mfma) plan.bytes = 0;
-  Carver cv;
-  const size_t o_knn = cv.take(plan.bytes);
-  const size_t o_keys = cv.take((size_t)n * sizeof(u64));
-  const size_t o_list = cv.take((size_t)n * sizeof(int32_t));
-  const size_t o_tmp = cv.take((size_t)n * g.M);
-  const size_t o_dest = cv.take((size_t)n * sizeof(int64_t));
-  const size_t o_off = cv.take(((size_t)g.nlist + 1) * sizeof(int64_t));
-  if (int rc = ix->scratch.reserve(cv.off)) return rc;
-  char* base = static_cast<char*>(ix->scratch.p);
-  u64* keys = reinterpret_cast<u64*>(base + o_keys);
-  int32_t* list_of = reinterpret_cast<int32_t*>(base + o_list);
-  uint8_t* tmp_codes = reinterpret_cast<uint8_t*>(base + o_tmp);
-  int64_t* dest = reinterpret_cast<int64_t*>(base + o_dest);
-  int64_t* new_off = reinterpret_cast<int64_t*>(base + o_off);
-
-  // 1. list assignment: best centroid on the canon chain, ties to the smaller list
-  if (plan.mfma) {
-    for (int64_t i0 = 0; i0 < n; i0 += kAssignPiece) {
-      const int64_t ni = std::min(kAssignPiece, n - i0);
-      SelectOut o;
-      o.idx32 = list_of + i0;
-      knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
-              ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1);
-    }
-  } else {
-    launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
-    launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
-    launch_keys_to_index32(keys, n, list_of, st);
-  }
-  // 2. residual PQ codes
-  launch_pq_encode(g, x, n, list_of, ix->centroids, ix->codebooks, tmp_codes, st);
-
-  // 3. stable placement: the new entries of a list follow its old ones, in the order given.
-  //    (bookkeeping on the host: one pass over n list numbers)
-  std::vector<int32_t> h_list((size_t)n);
-  HIP_TRY(hipMemcpyAsync(h_list.data(), list_of, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  std::vector<int64_t> add_cnt((size_t)g.nlist, 0);
-  for (int64_t i = 0; i < n; ++i) {
-    const int32_t l = h_list[(size_t)i];
-    if (l < 0 || l >= g.nlist) return fail(VS_ERR_DEVICE, "vs_ivfpq_add: assignment kernel produced list %d", l);
-    ++add_cnt[(size_t)l];
-  }
-  std::vector<int64_t> h_new((size_t)g.nlist + 1, 0), cursor((size_t)g.nlist);
-  for (int l = 0; l < g.nlist; ++l) {
-    const int64_t old_sz = ix->h_off[(size_t)l + 1] - ix->h_off[(size_t)l];
-    h_new[(size_t)l + 1] = h_new[(size_t)l] + old_sz + add_cnt[(size_t)l];
-    cursor[(size_t)l] = h_new[(size_t)l] + old_sz;
-  }
-  std::vector<int64_t> h_dest((size_t)n);
-  for (int64_t i = 0; i < n; ++i) h_dest[(size_t)i] = cursor[(size_t)h_list[(size_t)i]]++;
-  HIP_TRY(hipMemcpyAsync(dest, h_dest.data(), (size_t)n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(new_off, h_new.data(), h_new.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
-
-  // 4. new contiguous storage
   const int64_t total = ix->ntotal + n;
   uint8_t* codes = nullptr;
   int64_t* new_ids = nullptr;
@@ -619,19 +667,9 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
     (void)hipFree(codes);
     return fail(VS_ERR_OOM, "vs_ivfpq_add: id storage allocation failed");
   }
-  launch_relayout(g, ix->codes, ix->ids, ix->ntotal, ix->list_off, new_off, tmp_codes, ids,
-                  ix->ntotal, dest, n, codes, new_ids, st);
-  hipError_t e = hipMemcpyAsync(ix->list_off, new_off, h_new.size() * sizeof(int64_t), hipMemcpyDeviceToDevice, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);
-  if (e == hipSuccess) e = hipGetLastError();
-  if (e != hipSuccess) {
-    (void)hipFree(codes); (void)hipFree(new_ids);
-    return fail(VS_ERR_DEVICE, "vs_ivfpq_add: %s", hipGetErrorString(e));
-  }
-  if (ix->codes) (void)hipFree(ix->codes);
-  if (ix->ids) (void)hipFree(ix->ids);
-  ix->codes = codes; ix->ids = new_ids; ix->ntotal = total; ix->h_off.swap(h_new);
-  return VS_OK;
+  launch_relayout(g, ix->codes, ix->ids, ix->ntotal, ix->list_off, pl.new_off, tmp_codes, ids,
+                  ix->ntotal, pl.dest, n, codes, new_ids, st);
+  return ivf_commit_storage(ix, codes, new_ids, total, &pl, st, "vs_ivfpq_add");
 }
 
 // coarse quantizer: the npr best lists per query, best first, with their canon values
@@ -702,6 +740,145 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
     StageTimer t(VS_STAGE_MERGE, st);
     launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
   }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+// ---- IVF-Flat: the same inverted lists with the vectors stored as they are --------------
+// (core.codes holds the rows [ntotal, d] fp32, core.g.code_size = 4 d, no codebooks)
+
+int vs_ivfflat_create(vs_ivfflat** out, int32_t d, int32_t metric, int32_t nlist,
+                      const float* centroids, void* hip_stream) {
+  if (!out) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_create: out is null");
+  *out = nullptr;
+  if (!centroids) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_create: null pointer");
+  if (d < 1 || nlist < 1) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_create: d, nlist must be >= 1");
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_create: unknown metric %d", metric);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  vs_ivfflat* fx = new (std::nothrow) vs_ivfflat();
+  if (!fx) return fail(VS_ERR_OOM, "vs_ivfflat_create: host allocation failed");
+  vs_ivfpq* ix = &fx->core;
+  ix->g.d = d; ix->g.metric = metric; ix->g.nlist = nlist; ix->g.M = 0; ix->g.nbits = 0;
+  ix->g.K = 0; ix->g.dsub = 0; ix->g.code_size = d * (int)sizeof(float);
+  ix->h_off.assign((size_t)nlist + 1, 0);
+  auto cleanup = [&](int rc) { vs_ivfflat_destroy(fx); return rc; };
+#define TRY_C(expr)                                                                         \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return cleanup(fail(e_ == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "%s: %s", \
+                          #expr, hipGetErrorString(e_)));                                   \
+  } while (0)
+  TRY_C(hipGetDevice(&ix->device));
+  const size_t cb = (size_t)nlist * d * sizeof(float);
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->centroids), cb));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->list_off), ((size_t)nlist + 1) * sizeof(int64_t)));
+  TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));
+  if (mfma_knn_supported(d, 1)) {
+    TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
+    ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
+    launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
+                ix->c_planes.info, st);
+    ix->has_planes = true;
+  }
+  TRY_C(hipStreamSynchronize(st));
+#undef TRY_C
+  *out = fx;
+  return VS_OK;
+}
+
+void vs_ivfflat_destroy(vs_ivfflat* fx) {
+  if (!fx) return;
+  ivf_free_device_memory(&fx->core);
+  delete fx;
+}
+
+int64_t vs_ivfflat_ntotal(const vs_ivfflat* fx) { return fx ? fx->core.ntotal : -1; }
+
+int vs_ivfflat_add(vs_ivfflat* fx, const float* x, int64_t n, const int64_t* ids, void* hip_stream) {
+  if (!fx) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_add: index is null");
+  if (n < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_add: n < 0");
+  if (n == 0) return VS_OK;
+  if (!x) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_add: x is null");
+  vs_ivfpq* ix = &fx->core;
+  if (ix->ntotal + n >= (1ll << 32)) return fail(VS_ERR_UNSUPPORTED, "vs_ivfflat_add: more than 2^32 - 1 stored vectors");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const IvfpqDims& g = ix->g;
+  Placement pl;
+  if (int rc = ivf_assign_and_place(ix, x, n, 0, &pl, st, "vs_ivfflat_add")) return rc;
+  const int64_t total = ix->ntotal + n;
+  uint8_t* rows = nullptr;
+  int64_t* new_ids = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&rows), (size_t)total * g.code_size));
+  if (hipMalloc(reinterpret_cast<void**>(&new_ids), (size_t)total * sizeof(int64_t)) != hipSuccess) {
+    (void)hipFree(rows);
+    return fail(VS_ERR_OOM, "vs_ivfflat_add: id storage allocation failed");
+  }
+  launch_ivfflat_relayout(g.d, g.nlist, reinterpret_cast<const float*>(ix->codes), ix->ids, ix->ntotal,
+                          ix->list_off, pl.new_off, x, ids, ix->ntotal, pl.dest, n,
+                          reinterpret_cast<float*>(rows), new_ids, st);
+  return ivf_commit_storage(ix, rows, new_ids, total, &pl, st, "vs_ivfflat_add");
+}
+
+int vs_ivfflat_search(const vs_ivfflat* fx, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                      float* out_dist, int64_t* out_ids, void* hip_stream) {
+  if (!fx) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_search: index is null");
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_search: nq < 0");
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_search: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_search: nprobe = %d outside [1, %d]", nprobe, VS_MAX_K);
+  if (nq == 0) return VS_OK;
+  if (!q || !out_dist || !out_ids) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_search: null pointer");
+  const vs_ivfpq* ix = &fx->core;
+  const IvfpqDims& g = ix->g;
+  if (ivfflat_scan_lds_bytes(g.d, k) > 160 * 1024)
+    return fail(VS_ERR_UNSUPPORTED, "vs_ivfflat_search: d = %d with k = %d exceeds the LDS", g.d, k);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int npr = std::min<int>(nprobe, g.nlist);
+  // probe splits: enough workgroups to fill the chip when nq is small
+  int nsplit = (int)std::min<int64_t>(npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
+  const int ppb = (npr + nsplit - 1) / nsplit;
+  nsplit = (npr + ppb - 1) / ppb;
+  const KnnPlan plan = knn_plan(nq, g.nlist, g.d, npr, ix->has_planes);
+  Carver cv;
+  const size_t o_knn = cv.take(plan.bytes);
+  const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
+  const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
+  u64* partial = reinterpret_cast<u64*>(base + o_part);
+  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st);
+  {
+    StageTimer t(VS_STAGE_SCAN, st);
+    launch_ivfflat_scan(g.d, g.metric, q, nq, probes, npr, nsplit, ix->list_off,
+                        reinterpret_cast<const float*>(ix->codes), k, partial, ix->ids, out_dist,
+                        out_ids, st);
+  }
+  if (nsplit > 1) {
+    StageTimer t(VS_STAGE_MERGE, st);
+    launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfflat_get_list_sizes(const vs_ivfflat* fx, int64_t* sizes, void* hip_stream) {
+  if (!fx || !sizes) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_get_list_sizes: null pointer");
+  launch_list_sizes(fx->core.list_off, fx->core.g.nlist, sizes, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfflat_get_storage(const vs_ivfflat* fx, int64_t* ids, int32_t* list_of, float* rows,
+                           void* hip_stream) {
+  if (!fx) return fail(VS_ERR_INVALID_ARG, "vs_ivfflat_get_storage: index is null");
+  const vs_ivfpq* ix = &fx->core;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (ix->ntotal == 0) return VS_OK;
+  if (ids) HIP_TRY(hipMemcpyAsync(ids, ix->ids, (size_t)ix->ntotal * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+  if (list_of) launch_list_of_storage(ix->list_off, ix->g.nlist, ix->ntotal, list_of, st);
+  if (rows) HIP_TRY(hipMemcpyAsync(rows, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice, st));
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }

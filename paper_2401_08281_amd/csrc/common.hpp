@@ -273,6 +273,18 @@ static inline int select_slots_for_k(int k) {
 }
 static inline int select_regs_for_slots(int tot) { return tot <= 256 ? tot / 64 : 0; }
 
+// ---- inverted-list storage ------------------------------------------------------
+// list that owns storage position p: the l with off[l] <= p < off[l+1]
+__device__ __forceinline__ int list_of_position(const int64_t* __restrict__ off, int nlist,
+                                                int64_t p) {
+  int lo = 0, hi = nlist;  // invariant: off[lo] <= p < off[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off[mid] <= p) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
 // ---- canon distance of one pair ------------------------------------------------
 // The fp32 chain every exact decision of the library is defined in: dimension order,
 // diff = a - b rounded, acc = fma(diff, diff, acc) (inner product: acc = fma(a, b, acc)).

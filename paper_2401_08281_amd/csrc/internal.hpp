@@ -98,6 +98,20 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
                    int* fb_rows, u64* fb_partial, hipStream_t st);
 int read_fallback_total(unsigned long long* out);
 
+// ---- kernels_ivfflat.hip -------------------------------------------------------
+void launch_ivfflat_relayout(int d, int nlist, const float* old_rows, const int64_t* old_ids,
+                             int64_t old_total, const int64_t* old_off, const int64_t* new_off,
+                             const float* x, const int64_t* new_ids_or_null, int64_t id_base,
+                             const int64_t* dest, int64_t n_new, float* rows, int64_t* ids,
+                             hipStream_t st);
+size_t ivfflat_scan_lds_bytes(int d, int k);
+// canon distance of every stored vector of the probed lists, k best per (query, probe split):
+// results to out_dist / out_ids when nsplit == 1, else keys to partial [nq, nsplit, k]
+void launch_ivfflat_scan(int d, int metric, const float* q, int64_t nq, const int32_t* probes,
+                         int nprobe, int nsplit, const int64_t* list_off, const float* rows, int k,
+                         u64* partial, const int64_t* ids, float* out_dist, int64_t* out_ids,
+                         hipStream_t st);
+
 // ---- kernels_train.hip ---------------------------------------------------------
 // centroids[j] <- mean of the rows x[order[off[j] .. off[j + 1])] (float64 sum in that order);
 // a centroid with an empty range keeps its value

@@ -90,17 +90,6 @@ __global__ __launch_bounds__(256) void pq_encode_global_kernel(
 // ---------------------------------------------------------------------------
 // list storage
 // ---------------------------------------------------------------------------
-// list that owns storage position p: the l with off[l] <= p < off[l+1]
-__device__ __forceinline__ int list_of_position(const int64_t* __restrict__ off, int nlist,
-                                                int64_t p) {
-  int lo = 0, hi = nlist;  // invariant: off[lo] <= p < off[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (off[mid] <= p) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 __global__ void move_old_kernel(const uint8_t* __restrict__ old_codes,
                                 const int64_t* __restrict__ old_ids, int64_t old_total,
                                 const int64_t* __restrict__ old_off,

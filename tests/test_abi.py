@@ -80,6 +80,18 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_ivfpq_train(one, 0, 32, 0, 4, 8, 8, 1, one, one, nul, nul) == INVALID    # n < 1
     assert L.vs_ivfpq_train(one, 10, 32, 2, 4, 8, 8, 1, one, one, nul, nul) == INVALID   # metric
     assert L.vs_ivfpq_train(one, 10, 32, 0, 4, 8, 8, 1, one, nul, nul, nul) == INVALID   # null codebooks
+    hf = ctypes.c_void_p(0)
+    reff = ctypes.byref(hf)
+    assert L.vs_ivfflat_create(reff, 0, 0, 16, one, nul) == INVALID                      # d < 1
+    assert L.vs_ivfflat_create(reff, 32, 0, 0, one, nul) == INVALID                      # nlist < 1
+    assert L.vs_ivfflat_create(reff, 32, 5, 16, one, nul) == INVALID                     # metric
+    assert L.vs_ivfflat_create(reff, 32, 0, 16, nul, nul) == INVALID                     # null centroids
+    assert L.vs_ivfflat_create(None, 32, 0, 16, one, nul) == INVALID
+    assert hf.value is None
+    assert L.vs_ivfflat_add(nul, one, 5, nul, nul) == INVALID
+    assert L.vs_ivfflat_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
+    assert L.vs_ivfflat_ntotal(nul) == -1
+    L.vs_ivfflat_destroy(nul)                                                             # allowed
     h = ctypes.c_void_p(0)
     ref = ctypes.byref(h)
     assert L.vs_ivfpq_create(ref, 32, 0, 16, 5, 8, one, one, nul) == INVALID         # d % M

@@ -395,6 +395,63 @@ def test_ivfpq_search_then_refine_pipeline(vs, oracle):
     ix.close()
 
 
+# ------------------------------------------------- IVF-Flat
+
+IVFFLAT_CASES = {
+    "c1": (S.config("C1"), [(10, 4), (10, 16), (1, 1), (300, 2)]),
+    "c3_small": (S.config("C3", nb=60_000, nq=100, ncomp=100, nlist=256), [(10, 16), (100, 64)]),
+    "c4_small_ip": (S.config("C4", nb=30_000, nq=64, ncomp=50, nlist=128, metric=1), [(10, 8)]),
+    "odd_d30": (S.config("C1", nb=3_001, nq=33, d=30, nlist=7), [(10, 3), (500, 7)]),
+    "d768": (S.config("C5", nb=4_000, nq=20, ncomp=20, nlist=16), [(10, 4)]),
+}
+
+
+@pytest.mark.parametrize("name", list(IVFFLAT_CASES))
+def test_ivfflat_matches_oracle(vs, oracle, name):
+    cfg, searches = IVFFLAT_CASES[name]
+    say("ivfflat %s nb=%d d=%d nlist=%d metric=%d" % (name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["metric"]))
+    x, q = S.make_data(cfg)
+    cent = S.make_centroids(x, cfg["nlist"], cfg["seed"])
+    ix = vs.IVFFlat(cfg["d"], cfg["metric"], dev(cent))
+    orc = oracle.OracleIVFFlat(cfg["d"], cfg["metric"], cent)
+    half = cfg["nb"] // 3
+    ids = np.arange(cfg["nb"], dtype=np.int64) * 2 + 11                  # custom ids, two pieces
+    ix.add(dev(x[:half]), dev(ids[:half])); ix.add(dev(x[half:]), dev(ids[half:]))
+    orc.add(x[:half], ids[:half]); orc.add(x[half:], ids[half:])
+    assert ix.ntotal == cfg["nb"]
+    # storage: same lists, same order inside every list, the stored rows are the vectors
+    sid, slist, srows = [host(t) for t in ix.storage()]
+    np.testing.assert_array_equal(host(ix.list_sizes()), orc.list_sizes())
+    np.testing.assert_array_equal(sid, orc.ids)
+    np.testing.assert_array_equal(srows, orc.vecs)
+    np.testing.assert_array_equal(slist, np.repeat(np.arange(cfg["nlist"]), orc.list_sizes()))
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        D, I = ix.search(dev(q), k, nprobe)
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        # check_search has verified every id that differs (oracle distances within the
+        # tolerance of each other); such near-ties must stay rare
+        same = check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        assert same >= 0.97, same
+    ix.close()
+
+
+def test_ivfflat_with_all_lists_probed_equals_flat_search_bits(vs, oracle):
+    """Both scans evaluate the same fp32 chain: probing every list of an IVF-Flat index
+    returns flat search's values bit for bit (ids too, the data being integer-valued)."""
+    cfg = S.config("C3", nb=30_000, nq=50, ncomp=50, nlist=64)
+    say("ivfflat, all lists probed, vs flat search")
+    x, q = S.make_data(cfg)
+    ix = vs.IVFFlat(cfg["d"], L2, dev(S.make_centroids(x, 64, cfg["seed"])))
+    ix.add(dev(x))
+    D, I = [host(t) for t in ix.search(dev(q), 20, 64)]
+    Df, If = [host(t) for t in vs.vs_flat_search(dev(x), dev(q), 20, L2)]
+    np.testing.assert_array_equal(D, Df)
+    check_search(D, I, *oracle.flat_search(x, q, 20 + EXTRA, L2), L2)
+    ix.close()
+
+
 # ------------------------------------------------- k-means and parameter training
 
 KMEANS_CASES = [
