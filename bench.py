@@ -383,7 +383,7 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
             "recall_k_at_k": round(float(hit_k), 4), "recall_queries": int(nrec),
             "scanned_vectors_per_query": scanned / nq, "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v[0] / args.steps, 4) for s, v in prof.items() if v[1]}},
-        "roofline": {"bound": "hbm", "kernel": "ivfflat_scan_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "ivfflat_scan_tiled_kernel" if d % 32 == 0 else "ivfflat_scan_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "algorithmic_bytes_per_launch": algo, "kernel_ms": scan_ms},
         "cpu_baseline": cpu,

@@ -273,6 +273,10 @@ static inline int select_slots_for_k(int k) {
 }
 static inline int select_regs_for_slots(int tot) { return tot <= 256 ? tot / 64 : 0; }
 
+// four 32-bit words as one register tuple (HIP's own uint4 / float4 arrays are placed in
+// scratch memory by the compiler; an ext-vector type stays in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 // ---- inverted-list storage ------------------------------------------------------
 // list that owns storage position p: the l with off[l] <= p < off[l+1]
 __device__ __forceinline__ int list_of_position(const int64_t* __restrict__ off, int nlist,

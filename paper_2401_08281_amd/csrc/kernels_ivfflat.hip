@@ -5,39 +5,44 @@
 // chain as the flat search, so a vector's value here equals its value there bit for bit.
 // The lists are streamed once: rows [ntotal, d] fp32, list-contiguous; the kernel is bound
 // by that stream (d * 4 bytes per visited vector).
+#include <algorithm>
+
 #include "common.hpp"
 #include "internal.hpp"
 
 namespace {
 
 // storage of a grown index: old entries keep their order inside their list, new entries
-// follow them at dest[i]; one lane per fp32 element
+// follow them at dest[i]; one lane per fp32 element, grid-stride (a launch cannot hold more
+// than 2^32 - 1 work-items and 100M rows of 96 floats are 9.6e9 elements)
 __global__ void flat_move_old_kernel(const float* __restrict__ old_rows,
                                      const int64_t* __restrict__ old_ids, int64_t old_total, int d,
                                      const int64_t* __restrict__ old_off,
                                      const int64_t* __restrict__ new_off, int nlist,
                                      float* __restrict__ rows, int64_t* __restrict__ ids) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e >= old_total * d) return;
-  const int64_t p = e / d;
-  const int t = (int)(e - p * d);
-  const int l = list_of_position(old_off, nlist, p);
-  const int64_t np = new_off[l] + (p - old_off[l]);
-  rows[np * d + t] = old_rows[e];
-  if (t == 0) ids[np] = old_ids[p];
+  const int64_t total = old_total * d, stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += stride) {
+    const int64_t p = e / d;
+    const int t = (int)(e - p * d);
+    const int l = list_of_position(old_off, nlist, p);
+    const int64_t np = new_off[l] + (p - old_off[l]);
+    rows[np * d + t] = old_rows[e];
+    if (t == 0) ids[np] = old_ids[p];
+  }
 }
 
 __global__ void flat_scatter_new_kernel(const float* __restrict__ x,
                                         const int64_t* __restrict__ new_ids, int64_t id_base,
                                         const int64_t* __restrict__ dest, int64_t n, int d,
                                         float* __restrict__ rows, int64_t* __restrict__ ids) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e >= n * d) return;
-  const int64_t i = e / d;
-  const int t = (int)(e - i * d);
-  const int64_t p = dest[i];
-  rows[p * d + t] = x[e];
-  if (t == 0) ids[p] = new_ids ? new_ids[i] : id_base + i;
+  const int64_t total = n * d, stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += stride) {
+    const int64_t i = e / d;
+    const int t = (int)(e - i * d);
+    const int64_t p = dest[i];
+    rows[p * d + t] = x[e];
+    if (t == 0) ids[p] = new_ids ? new_ids[i] : id_base + i;
+  }
 }
 
 // One workgroup (4 wavefronts) per (query, probe split).  The query sits in LDS and is read
@@ -82,6 +87,108 @@ __global__ __launch_bounds__(256) void ivfflat_scan_kernel(
   block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
 }
 
+// The same scan with the rows staged through LDS, for d a multiple of 32.  Reading one row
+// per lane straight from memory makes every load instruction touch 64 cache lines; here a
+// tile of 256 rows x 32 dimensions is fetched with 8 lanes per row (128 consecutive bytes of
+// a row per request), written to LDS with a row stride of 36 floats (16-byte aligned and
+// conflict-free for the 16-byte reads that follow), and lane r then continues the canon
+// chain of row r over those 32 dimensions.  The next tile chunk is in flight (registers)
+// while the current one is summed; one LDS barrier per chunk.
+template <int R, int METRIC>
+__global__ __launch_bounds__(256) void ivfflat_scan_tiled_kernel(
+    const float* __restrict__ q, int d, const int32_t* __restrict__ probes, int nprobe, int ppb,
+    int nsplit, const int64_t* __restrict__ list_off, const float* __restrict__ rows, int k, int tot,
+    KeySink sink) {
+  constexpr int DC = 32, LD = 36, TR = 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
+  u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
+  float* qs = reinterpret_cast<float*>(bound + 2);              // d
+  float* tile = qs + d;                                         // 2 x TR x LD
+  const int64_t qi = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int p_end = min(nprobe, split * ppb + ppb);
+  const int r_ld = tid >> 3, c_ld = tid & 7;                    // fetch: 8 lanes per row, 32 rows per pass
+
+  for (int t = tid; t < d; t += 256) qs[t] = q[qi * d + t];
+  if (tid == 0) *bound = KEY_EMPTY;
+  WaveSelect<R> ws;
+  ws.init(slots + wave * tot, tot, k, bound);
+
+  // position in the sequence of (list, tile of 256 rows, chunk of 32 dimensions): all uniform
+  struct Pos { int p; int64_t i0, end; int c0; bool ok; };
+  auto first_row_from = [&](int p) {                            // first non-empty list at or after p
+    Pos s{p, 0, 0, 0, false};
+    for (; s.p < p_end; ++s.p) {
+      const int l = probes[qi * nprobe + s.p];
+      if (l < 0) continue;
+      s.i0 = list_off[l]; s.end = list_off[l + 1];
+      if (s.i0 < s.end) { s.ok = true; break; }
+    }
+    return s;
+  };
+  auto next_of = [&](const Pos& c) {
+    Pos n = c;
+    n.c0 += DC;
+    if (n.c0 < d) return n;
+    n.c0 = 0;
+    n.i0 += TR;
+    if (n.i0 < n.end) return n;
+    return first_row_from(c.p + 1);
+  };
+  u32x4 stg[8];   // (an ext-vector type: HIP's float4 arrays end up in scratch memory)
+#define FETCH(S)                                                                                  \
+  do {                                                                                            \
+    _Pragma("unroll") for (int j_ = 0; j_ < 8; ++j_) {                                            \
+      const int64_t row_ = min((S).i0 + j_ * 32 + r_ld, (S).end - 1);   /* rows past the end: masked later */ \
+      stg[j_] = *reinterpret_cast<const u32x4*>(rows + row_ * d + (S).c0 + c_ld * 4);            \
+    }                                                                                             \
+  } while (0)
+#define STASH(BUF)                                                                                \
+  do {                                                                                            \
+    _Pragma("unroll") for (int j_ = 0; j_ < 8; ++j_)                                              \
+      *reinterpret_cast<u32x4*>(tile + ((BUF) * TR + j_ * 32 + r_ld) * LD + c_ld * 4) = stg[j_]; \
+  } while (0)
+
+  Pos cur = first_row_from(split * ppb);
+  if (cur.ok) { FETCH(cur); STASH(0); }
+  __syncthreads();                                              // query, bound and the first chunk
+  int buf = 0;
+  float acc = 0.f;
+  while (cur.ok) {
+    const Pos nxt = next_of(cur);
+    if (nxt.ok) FETCH(nxt);                                     // in flight during the arithmetic
+    const float* __restrict__ tr = tile + (buf * TR + tid) * LD;
+    const float* __restrict__ qc = qs + cur.c0;
+#pragma unroll
+    for (int c = 0; c < DC / 4; ++c) {
+      const float4 xv = *reinterpret_cast<const float4*>(tr + c * 4);
+      const float4 qv = *reinterpret_cast<const float4*>(qc + c * 4);
+      const float xs[4] = {xv.x, xv.y, xv.z, xv.w}, qq[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (METRIC == 0) { const float diff = qq[u] - xs[u]; acc = __builtin_fmaf(diff, diff, acc); }
+        else acc = __builtin_fmaf(qq[u], xs[u], acc);
+      }
+    }
+    if (cur.c0 + DC >= d) {                                     // the row is complete
+      const int64_t i = cur.i0 + tid;
+      ws.push(i < cur.end, make_key(acc, (u32)i, METRIC), true);
+      acc = 0.f;
+    }
+    if (nxt.ok) STASH(buf ^ 1);
+    block_sync_lds();
+    cur = nxt;
+    buf ^= 1;
+  }
+#undef FETCH
+#undef STASH
+  ws.finish();
+  block_sync_lds();
+  block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
+}
+
 }  // namespace
 
 void launch_ivfflat_relayout(int d, int nlist, const float* old_rows, const int64_t* old_ids,
@@ -89,16 +196,21 @@ void launch_ivfflat_relayout(int d, int nlist, const float* old_rows, const int6
                              const float* x, const int64_t* new_ids_or_null, int64_t id_base,
                              const int64_t* dest, int64_t n_new, float* rows, int64_t* ids,
                              hipStream_t st) {
+  constexpr int64_t kMaxBlocks = 1 << 22;   // 2^30 work-items per launch; the kernels stride
   if (old_total > 0)
-    hipLaunchKernelGGL(flat_move_old_kernel, dim3((unsigned)((old_total * d + 255) / 256)), dim3(256), 0,
+    hipLaunchKernelGGL(flat_move_old_kernel,
+                       dim3((unsigned)std::min(kMaxBlocks, (old_total * d + 255) / 256)), dim3(256), 0,
                        st, old_rows, old_ids, old_total, d, old_off, new_off, nlist, rows, ids);
   if (n_new > 0)
-    hipLaunchKernelGGL(flat_scatter_new_kernel, dim3((unsigned)((n_new * d + 255) / 256)), dim3(256), 0,
+    hipLaunchKernelGGL(flat_scatter_new_kernel,
+                       dim3((unsigned)std::min(kMaxBlocks, (n_new * d + 255) / 256)), dim3(256), 0,
                        st, x, new_ids_or_null, id_base, dest, n_new, d, rows, ids);
 }
 
+// d a multiple of 32 takes the tiled kernel (two tile buffers of 256 x 36 floats on top)
 size_t ivfflat_scan_lds_bytes(int d, int k) {
-  return (size_t)(4 * select_slots_for_k(k) + 2) * sizeof(u64) + (size_t)d * sizeof(float);
+  const size_t base = (size_t)(4 * select_slots_for_k(k) + 2) * sizeof(u64) + (size_t)d * sizeof(float);
+  return d % 32 == 0 ? base + (size_t)2 * 256 * 36 * sizeof(float) : base;
 }
 
 void launch_ivfflat_scan(int d, int metric, const float* q, int64_t nq, const int32_t* probes,
@@ -117,7 +229,7 @@ void launch_ivfflat_scan(int d, int metric, const float* q, int64_t nq, const in
   const dim3 grid((unsigned)(nq * nsplit)), block(256);
 #define GO(RR, MET)                                                                              \
   do {                                                                                           \
-    auto kern = &ivfflat_scan_kernel<RR, MET>;                                                   \
+    auto kern = d % 32 == 0 ? &ivfflat_scan_tiled_kernel<RR, MET> : &ivfflat_scan_kernel<RR, MET>; \
     if (shmem > 48 * 1024)                                                                       \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);         \

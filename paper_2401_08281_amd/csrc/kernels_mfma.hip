@@ -30,7 +30,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned short bf16_rn_bits(float f) {
   u32 u = __float_as_uint(f);
@@ -648,8 +647,13 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
   if (n <= 0) return;
   const int rpb = 2048 / d;                          // d <= 128 here, d % 8 == 0
   const int64_t n_pad = mfma_padded_rows(n);
-  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((n_pad + rpb - 1) / rpb)), dim3(256), 0, st, x, n,
-                     n_pad, d, rpb, hi, lo, norm, info);
+  // in pieces of 2^24 rows (a multiple of 64): a launch holds fewer than 2^32 work-items
+  constexpr int64_t kRows = 1ll << 24;
+  for (int64_t r0 = 0; r0 < n_pad; r0 += kRows) {
+    const int64_t np = std::min(kRows, n_pad - r0), nr = std::max<int64_t>(0, std::min(np, n - r0));
+    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((np + rpb - 1) / rpb)), dim3(256), 0, st,
+                       x + r0 * d, nr, np, d, rpb, hi + r0 * d, lo + r0 * d, norm + r0, info);
+  }
 }
 
 namespace {

@@ -2,6 +2,8 @@
 // residuals"): the update step of Lloyd's iteration and the residual sub-vectors the
 // sub-quantizers are trained on.  The assignment step is the library's k-nearest-rows
 // routine with k = 1.
+#include <algorithm>
+
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -49,12 +51,13 @@ __global__ __launch_bounds__(256) void residual_slices_kernel(const float* __res
                                                               const float* __restrict__ centroids,
                                                               const int32_t* __restrict__ list_of,
                                                               float* __restrict__ out) {
-  const int64_t e = blockIdx.x * 256ll + threadIdx.x;
-  if (e >= n * d) return;
-  const int64_t i = e / d;
-  const int t = (int)(e - i * d);
-  const int m = t / dsub, u = t - m * dsub;
-  out[((int64_t)m * n + i) * dsub + u] = x[e] - centroids[(int64_t)list_of[i] * d + t];
+  const int64_t total = n * d, stride = (int64_t)gridDim.x * 256;   // grid-stride: n * d may exceed 2^32
+  for (int64_t e = blockIdx.x * 256ll + threadIdx.x; e < total; e += stride) {
+    const int64_t i = e / d;
+    const int t = (int)(e - i * d);
+    const int m = t / dsub, u = t - m * dsub;
+    out[((int64_t)m * n + i) * dsub + u] = x[e] - centroids[(int64_t)list_of[i] * d + t];
+  }
 }
 
 }  // namespace
@@ -69,6 +72,7 @@ void launch_segmented_mean(const float* x, int d, const int32_t* order, const in
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,
                             const int32_t* list_of, float* out, hipStream_t st) {
   if (n <= 0) return;
-  hipLaunchKernelGGL(residual_slices_kernel, dim3((unsigned)((n * d + 255) / 256)), dim3(256), 0, st,
+  hipLaunchKernelGGL(residual_slices_kernel,
+                     dim3((unsigned)std::min<int64_t>(1 << 22, (n * d + 255) / 256)), dim3(256), 0, st,
                      x, n, d, dsub, centroids, list_of, out);
 }

@@ -452,6 +452,33 @@ def test_ivfflat_with_all_lists_probed_equals_flat_search_bits(vs, oracle):
     ix.close()
 
 
+def test_ivfflat_storage_beyond_four_billion_elements(vs):
+    """72M x 96 floats added in three pieces: the last re-layout moves 4.6e9 elements, more
+    than one launch can hold as work-items.  Every list probed must then equal flat search
+    bit for bit, and sampled stored rows must be the vectors of their ids."""
+    import torch
+    cfg = S.config("C4", nb=72_000_000, nq=64, nlist=1024)
+    say("ivfflat large storage: nb=%d d=%d" % (cfg["nb"], cfg["d"]))
+    xd, qd = S.make_data_device(cfg)
+    cent, _ = S.make_index_params_device(cfg, xd)
+    ix = vs.IVFFlat(cfg["d"], L2, dev(cent))
+    piece = cfg["nb"] // 3
+    for s0 in range(0, cfg["nb"], piece):
+        ix.add(xd[s0:s0 + piece])
+        say("  added %d" % (s0 + piece))
+    assert ix.ntotal == cfg["nb"] and int(ix.list_sizes().sum().item()) == cfg["nb"]
+    D, I = ix.search(qd, 10, 1024)
+    Df, If = vs.vs_flat_search(xd, qd, 10, L2)
+    assert torch.equal(D, Df)
+    assert (I == If).float().mean().item() > 0.99          # equal values may swap
+    ids, list_of, rows = ix.storage()
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    pos = torch.randint(0, cfg["nb"], (200_000,), generator=g, device="cuda")
+    assert torch.equal(rows[pos], xd[ids[pos]])
+    assert torch.equal(torch.sort(ids).values, torch.arange(cfg["nb"], device="cuda"))
+    ix.close()
+
+
 # ------------------------------------------------- k-means and parameter training
 
 KMEANS_CASES = [
