@@ -311,6 +311,31 @@ void or_pq_decode(const uint8_t *codes, int64_t n, int d, const int32_t *list_of
   }
 }
 
+/* ---- stored norms (Sec. 4.3 "Compressed-domain search": with the decomposition
+ * ||q - x'||^2 = ||q||^2 + ||x'||^2 - 2 <q, x'> the term ||x'||^2 must be available at
+ * search time; it can be stored next to the code as a float32) ---------------------
+ * norm(x') for x' = c_list + concat_m T_m[c_m]: every component is one fp32 addition,
+ * the squares are accumulated by one fp32 fused-multiply-add chain in dimension order
+ * (the arithmetic is fixed so that the stored numbers can be compared bit for bit). */
+void or_pq_norms(const uint8_t *codes, int64_t n, int d, const int32_t *list_of,
+                 const float *centroids, int M, int nbits, const float *codebooks, float *norms) {
+  const int K = 1 << nbits, dsub = d / M;
+  const int code_size = M * nbits / 8;
+  for (int64_t i = 0; i < n; ++i) {
+    const float *c = centroids + (int64_t)list_of[i] * d;
+    float acc = 0.0f;
+    for (int m = 0; m < M; ++m) {
+      int j = code_at(codes + i * code_size, m, nbits);
+      const float *T = codebooks + ((int64_t)m * K + j) * dsub;
+      for (int u = 0; u < dsub; ++u) {
+        float xt = c[m * dsub + u] + T[u];
+        acc = fmaf(xt, xt, acc);
+      }
+    }
+    norms[i] = acc;
+  }
+}
+
 /* ---- O6-O8: IVF-PQ search (Sec. 5.1, Eq. 8 ADC, Eq. 12 LUT) -------------
  * The index is given as plain arrays: list l owns rows
  * [list_offsets[l], list_offsets[l+1]) of `codes` and `ids`.
@@ -322,16 +347,20 @@ void or_pq_decode(const uint8_t *codes, int64_t n, int d, const int32_t *list_of
  *   LUT_m[j] = canon_l2(r_m, T_m[j]) and the distance is sum_m LUT_m[c_m] in
  *   fp32, m ascending; for IP, LUT_m[j] = canon_ip(q_m, T_m[j]) and the
  *   score is canon_ip(q, c_l) + sum_m LUT_m[c_m].
- * form 1 exists to pin the table identity against form 0; parity tests of
- * the GPU path use form 0.
+ * form 2 (L2 only; Sec. 4.3, the decomposition ||q - x'||^2 = ||q||^2 + ||x'||^2
+ *   - 2 <q, x'> with the norm stored next to the code, norms[s] from or_pq_norms):
+ *   ((||q||^2 - 2 <q, c_l>) + norm) + sum_m (-2 <q_m, T_m[c_m]>) in fp32, m ascending,
+ *   every inner product a canon_ip chain.
+ * forms 1 and 2 exist to pin the compressed-domain identities against form 0; parity
+ * tests of the GPU path use form 0.
  *
  * nscanned[a] (may be NULL) receives the number of codes visited for query a.
  * probes_out (may be NULL) receives the probed lists, best first. */
 void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
                      const float *centroids, int M, int nbits, const float *codebooks,
                      const int64_t *list_offsets, const uint8_t *codes, const int64_t *ids,
-                     int k, int nprobe, int form, float *D, int64_t *I, int64_t *nscanned,
-                     int32_t *probes_out) {
+                     const float *norms, int k, int nprobe, int form, float *D, int64_t *I,
+                     int64_t *nscanned, int32_t *probes_out) {
   const int K = 1 << nbits, dsub = d / M;
   const int code_size = M * nbits / 8;
   if (nprobe > nlist) nprobe = nlist;
@@ -353,6 +382,12 @@ void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
       const int l = probes[a * nprobe + p];
       const float *c = centroids + (int64_t)l * d;
       float bias = 0.0f;
+      if (form == 2) {   /* L2 through stored norms: one table per query would do; rebuilt here per list for plainness */
+        bias = fmaf(-2.0f, or_canon_ip(qa, c, d), or_canon_ip(qa, qa, d));
+        for (int m = 0; m < M; ++m)
+          for (int j = 0; j < K; ++j)
+            lut[m * K + j] = -2.0f * or_canon_ip(qa + m * dsub, codebooks + ((int64_t)m * K + j) * dsub, dsub);
+      }
       if (form == 1) {
         if (metric == OR_METRIC_L2) {
           for (int t = 0; t < d; ++t) r[t] = qa[t] - c[t];
@@ -376,7 +411,7 @@ void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
           }
           dist = report_dist(qa, xd, d, metric);
         } else {
-          dist = bias;
+          dist = form == 2 ? bias + norms[s] : bias;
           for (int m = 0; m < M; ++m) dist += lut[m * K + code_at(code, m, nbits)];
         }
         topk_push(&h, dist, ids[s]);

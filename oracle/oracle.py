@@ -200,6 +200,22 @@ def pq_decode(codes, list_of, centroids, codebooks, nbits):
     return out
 
 
+def pq_norms(codes, list_of, centroids, codebooks, nbits):
+    """fp32 squared norm of every decoded vector (Sec. 4.3: the norm stored next to the code),
+    by the fixed chain of or_pq_norms."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+    codebooks = np.ascontiguousarray(codebooks, dtype=np.float32)
+    list_of = np.ascontiguousarray(list_of, dtype=np.int32)
+    n = codes.shape[0]
+    M, K, dsub = codebooks.shape
+    out = np.empty(n, dtype=np.float32)
+    _load().or_pq_norms(_ptr(codes), ctypes.c_int64(n), ctypes.c_int(M * dsub), _ptr(list_of),
+                        _ptr(centroids), ctypes.c_int(M), ctypes.c_int(nbits), _ptr(codebooks),
+                        _ptr(out))
+    return out
+
+
 def recall(I_found, I_true, n=None):
     """n-recall@k (Sec. 3.2 "Metrics for approximate nearest neighbor search"): fraction of the n ground-truth
     nearest neighbours found among the k returned ids.  n = None means n = k
@@ -296,6 +312,7 @@ class OracleIVFPQ:
         self.add_ids = np.empty(0, dtype=np.int64)
         self.add_list_of = np.empty(0, dtype=np.int32)
         self.add_codes = np.empty((0, self.code_size), dtype=np.uint8)
+        self.add_norms = np.empty(0, dtype=np.float32)
         self._relayout()
 
     @classmethod
@@ -312,6 +329,8 @@ class OracleIVFPQ:
         ix.add_ids = ix.ids
         ix.add_codes = ix.codes
         ix.add_list_of = np.repeat(np.arange(ix.nlist, dtype=np.int32), sizes)
+        ix.add_norms = pq_norms(ix.codes, ix.add_list_of, ix.centroids, ix.codebooks, ix.nbits)
+        ix.norms = ix.add_norms
         return ix
 
     @property
@@ -322,6 +341,7 @@ class OracleIVFPQ:
         order = np.argsort(self.add_list_of, kind="stable")
         self.ids = np.ascontiguousarray(self.add_ids[order])
         self.codes = np.ascontiguousarray(self.add_codes[order])
+        self.norms = np.ascontiguousarray(self.add_norms[order])
         sizes = np.bincount(self.add_list_of, minlength=self.nlist).astype(np.int64)
         self.list_offsets = np.zeros(self.nlist + 1, dtype=np.int64)
         np.cumsum(sizes, out=self.list_offsets[1:])
@@ -336,6 +356,8 @@ class OracleIVFPQ:
         self.add_ids = np.concatenate([self.add_ids, np.asarray(ids, dtype=np.int64)])
         self.add_list_of = np.concatenate([self.add_list_of, list_of])
         self.add_codes = np.concatenate([self.add_codes, codes])
+        self.add_norms = np.concatenate(
+            [self.add_norms, pq_norms(codes, list_of, self.centroids, self.codebooks, self.nbits)])
         self._relayout()
         return list_of, codes
 
@@ -354,8 +376,8 @@ class OracleIVFPQ:
             _ptr(q), ctypes.c_int64(nq), ctypes.c_int(self.d), ctypes.c_int(self.metric),
             ctypes.c_int(self.nlist), _ptr(self.centroids), ctypes.c_int(self.M),
             ctypes.c_int(self.nbits), _ptr(self.codebooks), _ptr(self.list_offsets),
-            _ptr(self.codes), _ptr(self.ids), ctypes.c_int(k), ctypes.c_int(nprobe),
-            ctypes.c_int(form), _ptr(D), _ptr(I), _ptr(nscanned), _ptr(probes))
+            _ptr(self.codes), _ptr(self.ids), _ptr(self.norms), ctypes.c_int(k),
+            ctypes.c_int(nprobe), ctypes.c_int(form), _ptr(D), _ptr(I), _ptr(nscanned), _ptr(probes))
         if return_stats:
             return D, I, nscanned, probes
         return D, I

@@ -585,3 +585,44 @@ def test_ivfflat_add_in_pieces_custom_ids_and_padding(oracle):
     for qi in range(q.shape[0]):
         n = int(nscanned[qi])
         assert (I[qi, :n] >= 0).all() and (I[qi, n:] == -1).all() and np.isposinf(D[qi, n:]).all()
+
+
+# ------------------------------------------- L2 through stored norms (Sec. 4.3)
+
+def test_stored_norm_is_the_squared_norm_of_the_decoded_vector(oracle):
+    cfg, x, q, ix = _c1_index(oracle, nb=500, nq=4)
+    xr = oracle.pq_decode(ix.codes, np.repeat(np.arange(ix.nlist, dtype=np.int32), ix.list_sizes()),
+                          ix.centroids, ix.codebooks, 8)
+    np.testing.assert_allclose(ix.norms, (xr ** 2).sum(1), rtol=2e-6)
+    # on integer-valued parameters every step is exact: the fp32 chain equals the float64 value
+    rng = np.random.default_rng(41)
+    cent = rng.integers(-9, 10, size=(4, 8)).astype(np.float32)
+    cb = rng.integers(-5, 6, size=(2, 16, 4)).astype(np.float32)
+    codes = rng.integers(0, 256, size=(50, 1)).astype(np.uint8)          # two 4-bit codes per byte
+    lo = rng.integers(0, 4, size=50).astype(np.int32)
+    nrm = oracle.pq_norms(codes, lo, cent, cb, 4)
+    dec = oracle.pq_decode(codes, lo, cent, cb, 4)
+    np.testing.assert_array_equal(nrm.astype(np.float64), (dec ** 2).sum(1))
+
+
+def test_norm_decomposition_form_agrees_with_the_definition(oracle):
+    # ||q - x'||^2 = ||q||^2 + ||x'||^2 - 2 <q, x'>: form 2 against form 0, within the
+    # rounding of the cancelling terms; identical ranking apart from near-ties
+    cfg, x, q, ix = _c1_index(oracle, nb=3000, nq=30)
+    D0, I0 = ix.search(q, 10, 4, form=0)
+    D2, I2 = ix.search(q, 10, 4, form=2)
+    scale = (q.astype(np.float64) ** 2).sum(1)[:, None] + float(ix.norms.max())
+    assert (np.abs(D2.astype(np.float64) - D0) <= 4e-7 * scale).all()
+    assert (I0 == I2).mean() > 0.98
+    # exact on integer data: same bits as the definition
+    rng = np.random.default_rng(42)
+    xi = rng.integers(0, 30, size=(400, 8)).astype(np.float32)
+    qi = rng.integers(0, 30, size=(7, 8)).astype(np.float32)
+    cent = xi[:5].copy()
+    cb = rng.integers(-4, 5, size=(4, 256, 2)).astype(np.float32)
+    ixi = oracle.OracleIVFPQ(8, L2, cent, cb, 8)
+    ixi.add(xi)
+    Da, Ia = ixi.search(qi, 6, 5, form=0)
+    Db, Ib = ixi.search(qi, 6, 5, form=2)
+    np.testing.assert_array_equal(Da, Db)
+    np.testing.assert_array_equal(Ia, Ib)
