@@ -55,6 +55,10 @@ def main():
                     help="train the coarse centroids and the PQ codebooks with NITER rounds of k-means "
                          "(vs_ivfpq_train, from the sampled parameters, on the first min(nb, 256 * nlist) "
                          "vectors) before building the index; reported under config.train")
+    ap.add_argument("--search-type", default="tables", choices=["tables", "norms"],
+                    help="tables (default, the headline form): one look-up table per (query, list) on the "
+                         "residual; norms: |q|^2 + |x'|^2 - 2<q,x'> with the norm stored next to every code "
+                         "(4 more bytes per vector, one table per query)")
     ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat"],
                     help="ivfflat: the same workload's vectors and centroids in an IVF-Flat index "
                          "(secondary line; the default ivfpq is the headline metric)")
@@ -128,6 +132,8 @@ def main():
             t_train, objs[0][0], objs[0][-1], train["pq_mse_first_last"][0], train["pq_mse_first_last"][1]))
     ix = vs.IVFPQ(cfg["d"], metric, torch.from_numpy(cent).cuda(), torch.from_numpy(cb).cuda(),
                   cfg["nbits"])
+    if args.search_type == "norms":
+        ix.set_search_type(vs.ST_STORED_NORMS)
     torch.cuda.synchronize()
     t0 = time.time()
     piece = 10_000_000
@@ -140,7 +146,7 @@ def main():
     t_add = time.time() - t0
     log("index built: ntotal=%d in %.2fs" % (ix.ntotal, t_add))
     nprobe = cfg["nprobe"]
-    code_size = cfg["M"] * cfg["nbits"] // 8
+    code_size = cfg["M"] * cfg["nbits"] // 8 + (4 if args.search_type == "norms" else 0)
 
     # algorithmic work of the scan: codes visited by the batch
     sizes = ix.list_sizes()
@@ -215,7 +221,8 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe)
 
-    traffic = load_traffic("ivfpq_scan_%s_nprobe%d" % (args.workload, nprobe))
+    traffic = load_traffic("ivfpq_scan_%s_nprobe%d%s" % (
+        args.workload, nprobe, "" if args.search_type == "tables" else "_norms"))
     out = {
         "metric": "IVF-PQ queries/sec at fixed nprobe & recall@10; ADC-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -224,6 +231,7 @@ def main():
         "config": {"workload": "%s: IVF%d,PQ%dx%d %s, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
             args.workload, cfg["nlist"], cfg["M"], cfg["nbits"], "IP" if metric else "L2", cfg["nb"],
             cfg["d"], nq, k, nprobe),
+            "search_type": args.search_type, "scan_bytes_per_code": code_size,
             "nprobe": nprobe, "k": k, "recall_k_at_k": round(float(hit_k), 4),
             "recall_1_at_k": round(float(hit_1), 4), "recall_10_at_10": round(float(hit_10), 4),
             "recall_queries": int(nrec), "scanned_codes_per_query": scanned / nq,

@@ -200,6 +200,22 @@ VS_API int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stre
 VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
                     int32_t* probes, float* coarse_dist, void* hip_stream);
 
+/*
+ * How vs_ivfpq_search evaluates distances in the compressed domain (Sec. 4.3
+ * "Compressed-domain search").  VS_ST_RESIDUAL_TABLES (default): one table of squared
+ * distances between the query's residual and the codewords per (query, probed list).
+ * VS_ST_STORED_NORMS (L2 only): the decomposition |q - x'|^2 = |q|^2 + |x'|^2 - 2 <q, x'>
+ * with |x'|^2 stored next to every code as a float32 (4 more bytes per vector): one table of
+ * inner products per QUERY, no per-list table; the result differs from the default form by
+ * the rounding of the cancelling terms, about 2^-22 (|q|^2 + |x'|^2).
+ * Set it before the first add: vs_ivfpq_add computes the norms only while it is selected
+ * (an index that already holds vectors without norms refuses VS_ST_STORED_NORMS).
+ */
+enum { VS_ST_RESIDUAL_TABLES = 0, VS_ST_STORED_NORMS = 1 };
+VS_API int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type);
+/* the stored norms, in storage order: DEVICE [ntotal] fp32 */
+VS_API int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream);
+
 /* ---- IVF-Flat ----------------------------------------------------------------
  * The inverted file of Sec. 5.1 with the vectors stored as they are (no codec; App. A.3
  * "GPU Faiss" lists it among the GPU indexes).  Coarse quantizer, list assignment, ids,

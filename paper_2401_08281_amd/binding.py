@@ -36,6 +36,10 @@ def lib():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.vs_flat_search.restype = ctypes.c_int
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_set_search_type.restype = ctypes.c_int
+    L.vs_ivfpq_set_search_type.argtypes = [vp, i32]
+    L.vs_ivfpq_get_norms.restype = ctypes.c_int
+    L.vs_ivfpq_get_norms.argtypes = [vp, vp, vp]
     L.vs_ivfflat_create.restype = ctypes.c_int
     L.vs_ivfflat_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, vp, vp]
     L.vs_ivfflat_destroy.restype = None
@@ -300,6 +304,19 @@ def vs_ivfpq_coarse(h, q, nprobe, nlist):
     return probes, cdist
 
 
+ST_RESIDUAL_TABLES, ST_STORED_NORMS = 0, 1
+
+
+def vs_ivfpq_set_search_type(h, search_type):
+    _check(lib().vs_ivfpq_set_search_type(h, int(search_type)))
+
+
+def vs_ivfpq_get_norms(h, device):
+    norms = torch.empty(vs_ivfpq_ntotal(h), dtype=torch.float32, device=device)
+    _check(lib().vs_ivfpq_get_norms(h, _p(norms), _stream()))
+    return norms
+
+
 def vs_ivfflat_create(d, metric, nlist, centroids):
     centroids = _dev(centroids, torch.float32, "centroids")
     if centroids is not None and centroids.numel() != nlist * d:
@@ -434,3 +451,9 @@ class IVFPQ:
 
     def codes(self):
         return vs_ivfpq_get_codes(self.h, self.device)
+
+    def set_search_type(self, search_type):
+        vs_ivfpq_set_search_type(self.h, search_type)
+
+    def norms(self):
+        return vs_ivfpq_get_norms(self.h, self.device)

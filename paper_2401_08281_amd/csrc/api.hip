@@ -222,6 +222,8 @@ struct vs_ivfpq {
   int64_t ntotal = 0;
   uint8_t* codes = nullptr;     // [ntotal, code_size], list-contiguous
   int64_t* ids = nullptr;       // [ntotal]
+  float* norms = nullptr;       // [ntotal] squared norms of the decoded vectors, search_type 1 only
+  int search_type = VS_ST_RESIDUAL_TABLES;
   int64_t* list_off = nullptr;  // device [nlist + 1]
   std::vector<int64_t> h_off;   // host copy
   void* plane_mem = nullptr;    // bf16 head/tail planes + norms of the centroids (MFMA route)
@@ -538,6 +540,7 @@ static void ivf_free_device_memory(vs_ivfpq* ix) {
   if (ix->list_off) (void)hipFree(ix->list_off);
   if (ix->codes) (void)hipFree(ix->codes);
   if (ix->ids) (void)hipFree(ix->ids);
+  if (ix->norms) (void)hipFree(ix->norms);
   if (ix->plane_mem) (void)hipFree(ix->plane_mem);
   ix->scratch.release();
 }
@@ -628,18 +631,21 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
 }
 
 // Installs the grown storage (already filled on the stream) in place of the old one.
-int ivf_commit_storage(vs_ivfpq* ix, uint8_t* codes, int64_t* new_ids, int64_t total,
-                       Placement* pl, hipStream_t st, const char* who) {
+int ivf_commit_storage(vs_ivfpq* ix, uint8_t* codes, int64_t* new_ids, float* new_norms,
+                       int64_t total, Placement* pl, hipStream_t st, const char* who) {
   hipError_t e = hipMemcpyAsync(ix->list_off, pl->new_off, pl->h_new.size() * sizeof(int64_t), hipMemcpyDeviceToDevice, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) {
     (void)hipFree(codes); (void)hipFree(new_ids);
+    if (new_norms) (void)hipFree(new_norms);
     return fail(VS_ERR_DEVICE, "%s: %s", who, hipGetErrorString(e));
   }
   if (ix->codes) (void)hipFree(ix->codes);
   if (ix->ids) (void)hipFree(ix->ids);
-  ix->codes = codes; ix->ids = new_ids; ix->ntotal = total; ix->h_off.swap(pl->h_new);
+  if (ix->norms) (void)hipFree(ix->norms);
+  ix->codes = codes; ix->ids = new_ids; ix->norms = new_norms; ix->ntotal = total;
+  ix->h_off.swap(pl->h_new);
   return VS_OK;
 }
 
@@ -654,22 +660,54 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const IvfpqDims& g = ix->g;
   Placement pl;
-  // one byte per (vector, m) for the codes before they are packed into their lists
-  if (int rc = ivf_assign_and_place(ix, x, n, (size_t)n * g.M, &pl, st, "vs_ivfpq_add")) return rc;
+  // one byte per (vector, m) for the codes before they are packed into their lists, and
+  // (search type "stored norms") one float per vector
+  const bool with_norms = ix->search_type == VS_ST_STORED_NORMS;
+  const size_t code_bytes = align_up((size_t)n * g.M);
+  if (int rc = ivf_assign_and_place(ix, x, n, code_bytes + (with_norms ? (size_t)n * sizeof(float) : 0),
+                                    &pl, st, "vs_ivfpq_add"))
+    return rc;
   uint8_t* tmp_codes = reinterpret_cast<uint8_t*>(pl.extra);
+  float* tmp_norms = with_norms ? reinterpret_cast<float*>(pl.extra + code_bytes) : nullptr;
   launch_pq_encode(g, x, n, pl.list_of, ix->centroids, ix->codebooks, tmp_codes, st);
+  if (with_norms)
+    launch_pq_norms(g, tmp_codes, n, pl.list_of, ix->centroids, ix->codebooks, tmp_norms, st);
 
   const int64_t total = ix->ntotal + n;
   uint8_t* codes = nullptr;
   int64_t* new_ids = nullptr;
+  float* new_norms = nullptr;
   HIP_TRY(hipMalloc(reinterpret_cast<void**>(&codes), (size_t)total * g.code_size));
-  if (hipMalloc(reinterpret_cast<void**>(&new_ids), (size_t)total * sizeof(int64_t)) != hipSuccess) {
+  if (hipMalloc(reinterpret_cast<void**>(&new_ids), (size_t)total * sizeof(int64_t)) != hipSuccess ||
+      (with_norms && hipMalloc(reinterpret_cast<void**>(&new_norms), (size_t)total * sizeof(float)) != hipSuccess)) {
     (void)hipFree(codes);
-    return fail(VS_ERR_OOM, "vs_ivfpq_add: id storage allocation failed");
+    if (new_ids) (void)hipFree(new_ids);
+    return fail(VS_ERR_OOM, "vs_ivfpq_add: id / norm storage allocation failed");
   }
-  launch_relayout(g, ix->codes, ix->ids, ix->ntotal, ix->list_off, pl.new_off, tmp_codes, ids,
-                  ix->ntotal, pl.dest, n, codes, new_ids, st);
-  return ivf_commit_storage(ix, codes, new_ids, total, &pl, st, "vs_ivfpq_add");
+  launch_relayout(g, ix->codes, ix->ids, ix->norms, ix->ntotal, ix->list_off, pl.new_off, tmp_codes,
+                  ids, ix->ntotal, tmp_norms, pl.dest, n, codes, new_ids, new_norms, st);
+  return ivf_commit_storage(ix, codes, new_ids, new_norms, total, &pl, st, "vs_ivfpq_add");
+}
+
+int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: index is null");
+  if (search_type != VS_ST_RESIDUAL_TABLES && search_type != VS_ST_STORED_NORMS)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: unknown search type %d", search_type);
+  if (search_type == VS_ST_STORED_NORMS && ix->g.metric != VS_METRIC_L2)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: stored norms serve the L2 metric only");
+  if (ix->ntotal > 0 && search_type == VS_ST_STORED_NORMS && !ix->norms)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: the index already holds vectors without norms");
+  ix->search_type = search_type;   // norms already stored are kept, so one can switch back and forth
+  return VS_OK;
+}
+
+int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
+  if (!ix || !norms) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_norms: null pointer");
+  if (ix->ntotal == 0) return VS_OK;
+  if (!ix->norms) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_norms: the index stores no norms");
+  HIP_TRY(hipMemcpyAsync(norms, ix->norms, (size_t)ix->ntotal * sizeof(float), hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(hip_stream)));
+  return VS_OK;
 }
 
 // coarse quantizer: the npr best lists per query, best first, with their canon values
@@ -729,11 +767,15 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   u64* partial = reinterpret_cast<u64*>(base + o_part);
 
   coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st);
+  // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> instead of
+  // the coarse distance, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
+  const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
   {
     StageTimer t(VS_STAGE_SCAN, st);
+    if (with_norms) launch_pair_bias(q, nq, g.d, ix->centroids, probes, npr, cdist, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
-                          ix->list_off, ix->codes, ix->ntotal, k, partial, ix->ids, out_dist,
-                          out_ids, st) != 0)
+                          ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->ntotal, k,
+                          partial, ix->ids, out_dist, out_ids, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
   }
   if (nsplit > 1) {
@@ -818,7 +860,7 @@ int vs_ivfflat_add(vs_ivfflat* fx, const float* x, int64_t n, const int64_t* ids
   launch_ivfflat_relayout(g.d, g.nlist, reinterpret_cast<const float*>(ix->codes), ix->ids, ix->ntotal,
                           ix->list_off, pl.new_off, x, ids, ix->ntotal, pl.dest, n,
                           reinterpret_cast<float*>(rows), new_ids, st);
-  return ivf_commit_storage(ix, rows, new_ids, total, &pl, st, "vs_ivfflat_add");
+  return ivf_commit_storage(ix, rows, new_ids, nullptr, total, &pl, st, "vs_ivfflat_add");
 }
 
 int vs_ivfflat_search(const vs_ivfflat* fx, const float* q, int64_t nq, int32_t k, int32_t nprobe,

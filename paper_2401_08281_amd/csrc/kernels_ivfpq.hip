@@ -90,27 +90,75 @@ __global__ __launch_bounds__(256) void pq_encode_global_kernel(
 // ---------------------------------------------------------------------------
 // list storage
 // ---------------------------------------------------------------------------
+// Squared norm of the decoded vector x' = c_list + concat_m T_m[c_m] of every new entry
+// (Sec. 4.3: the norm stored next to the code for the decomposition |q|^2 + |x'|^2 - 2<q,x'>):
+// one fp32 addition per component, squares accumulated by one fma chain in dimension order.
+// One lane per vector; tmp_codes holds one byte per (vector, m).
+__global__ void pq_norms_kernel(const uint8_t* __restrict__ tmp_codes, int64_t n, int d, int dsub,
+                                int K, int M, const int32_t* __restrict__ list_of,
+                                const float* __restrict__ centroids,
+                                const float* __restrict__ codebooks, float* __restrict__ tmp_norms) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float* __restrict__ c = centroids + (int64_t)list_of[i] * d;
+  float acc = 0.f;
+  for (int m = 0; m < M; ++m) {
+    const float* __restrict__ T = codebooks + ((int64_t)m * K + tmp_codes[i * M + m]) * dsub;
+    for (int u = 0; u < dsub; ++u) {
+      const float xt = c[m * dsub + u] + T[u];
+      acc = __builtin_fmaf(xt, xt, acc);
+    }
+  }
+  tmp_norms[i] = acc;
+}
+
+// bias[q][p] = |q|^2 - 2 <q, c_l> for the p-th probed list l of query q: both inner products
+// are fma chains in dimension order, the combination one fma.  One lane per (query, probe).
+__global__ void pair_bias_kernel(const float* __restrict__ q, int64_t nq, int d,
+                                 const float* __restrict__ centroids,
+                                 const int32_t* __restrict__ probes, int nprobe,
+                                 float* __restrict__ bias) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= nq * nprobe) return;
+  const int64_t qi = e / nprobe;
+  const int l = probes[e];
+  const float* __restrict__ qv = q + qi * d;
+  const float* __restrict__ c = centroids + (int64_t)(l >= 0 ? l : 0) * d;
+  float qq = 0.f, qc = 0.f;
+  for (int t = 0; t < d; ++t) {
+    qq = __builtin_fmaf(qv[t], qv[t], qq);
+    qc = __builtin_fmaf(qv[t], c[t], qc);
+  }
+  bias[e] = __builtin_fmaf(-2.f, qc, qq);
+}
+
 __global__ void move_old_kernel(const uint8_t* __restrict__ old_codes,
-                                const int64_t* __restrict__ old_ids, int64_t old_total,
+                                const int64_t* __restrict__ old_ids,
+                                const float* __restrict__ old_norms, int64_t old_total,
                                 const int64_t* __restrict__ old_off,
                                 const int64_t* __restrict__ new_off, int nlist, int cs,
-                                uint8_t* __restrict__ codes, int64_t* __restrict__ ids) {
+                                uint8_t* __restrict__ codes, int64_t* __restrict__ ids,
+                                float* __restrict__ norms) {
   const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (p >= old_total) return;
   const int l = list_of_position(old_off, nlist, p);
   const int64_t np = new_off[l] + (p - old_off[l]);
   ids[np] = old_ids[p];
+  if (norms) norms[np] = old_norms[p];
   for (int b = 0; b < cs; ++b) codes[np * cs + b] = old_codes[p * cs + b];
 }
 
 __global__ void scatter_new_kernel(const uint8_t* __restrict__ tmp_codes,
                                    const int64_t* __restrict__ new_ids, int64_t id_base,
+                                   const float* __restrict__ tmp_norms,
                                    const int64_t* __restrict__ dest, int64_t n, int M, int nbits,
-                                   int cs, uint8_t* __restrict__ codes, int64_t* __restrict__ ids) {
+                                   int cs, uint8_t* __restrict__ codes, int64_t* __restrict__ ids,
+                                   float* __restrict__ norms) {
   const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int64_t p = dest[i];
   ids[p] = new_ids ? new_ids[i] : id_base + i;
+  if (norms) norms[p] = tmp_norms[i];
   const uint8_t* __restrict__ t = tmp_codes + i * M;
   if (nbits == 8) {
     for (int b = 0; b < cs; ++b) codes[p * cs + b] = t[b];
@@ -167,12 +215,16 @@ __device__ __forceinline__ float adc_bytes(const float* __restrict__ lut, u32 wo
 
 template <int NBITS, int R>
 __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
-    const float* __restrict__ q, int d, int metric, int M, int dsub,
+    const float* __restrict__ q, int d, int mode, int M, int dsub,
     const float* __restrict__ centroids, const float* __restrict__ codebooks,
     const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb,
-    int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int cs,
-    int k, int tot, KeySink sink) {
+    int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
+    const float* __restrict__ norms, int cs, int k, int tot, KeySink sink) {
+  // mode 0: L2, one table of squared residual distances per (query, list); mode 1: inner
+  // product, one table per query, cdist = <q, c_l>; mode 2: L2 through stored norms (Sec. 4.3):
+  // one table -2 <q_m, T_m[j]> per query, cdist = |q|^2 - 2 <q, c_l>, norms = |x'|^2 per code
   constexpr int K = 1 << NBITS;
+  const int metric = mode == 1 ? 1 : 0;                         // ordering of the keys
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
   float* lut = reinterpret_cast<float*>(slots + 4 * tot);       // M * K
@@ -188,13 +240,13 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   WaveSelect<R> ws;
   ws.init(slots + wave * tot, tot, k);
 
-  if (metric == 1) {  // per-query tables
+  if (mode != 0) {  // per-query tables
     for (int e = threadIdx.x; e < M * K; e += 256) {
       const int m = e >> NBITS;
       const float* __restrict__ T = codebooks + (int64_t)e * dsub;
       float acc = 0.f;
       for (int u = 0; u < dsub; ++u) acc = __builtin_fmaf(qv[m * dsub + u], T[u], acc);
-      lut[e] = acc;
+      lut[e] = mode == 2 ? -2.f * acc : acc;
     }
     __syncthreads();
   }
@@ -205,7 +257,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
     const int64_t begin = list_off[l], end = list_off[l + 1];
     if (begin == end) continue;  // uniform over the workgroup
     float bias = 0.f;
-    if (metric == 0) {
+    if (mode == 0) {
       const float* __restrict__ c = centroids + (int64_t)l * d;
       __syncthreads();  // previous list's scan is done with lut
       for (int t = threadIdx.x; t < d; t += 256) rs[t] = qv[t] - c[t];
@@ -230,6 +282,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
       const bool valid = i < end;
       float dist = bias;
       if (valid) {
+        if (mode == 2) dist += norms[i];
         const uint8_t* __restrict__ cp = codes + i * cs;
         if ((cs & 15) == 0) {
           for (int w = 0; w < (cs >> 4); ++w) {
@@ -320,9 +373,12 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     const float* __restrict__ q, const float* __restrict__ centroids,
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
-    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int64_t ntotal,
-    int k, int tot, KeySink sink) {
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
+    const float* __restrict__ norms, int64_t ntotal, int k, int tot, KeySink sink) {
+  // METRIC 0: L2 with a table per (query, list); 1: inner product; 2: L2 through stored norms
+  // (one table -2 <q_m, T_m[j]> per query, cdist = |q|^2 - 2 <q, c_l>, + |x'|^2 per code)
   constexpr int K = 256, D = M * DSUB;
+  constexpr int KEY_METRIC = METRIC == 1 ? 1 : 0;
   constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
   static_assert(256 % M == 0 && M % 4 == 0, "M must divide 256 and codes are read as 32-bit words");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -370,13 +426,13 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       s_begin[p] = l >= 0 ? list_off[l] : 0;
       s_end[p] = l >= 0 ? list_off[l + 1] : 0;
     }
-    if (METRIC == 1) {  // inner product: one table per query
+    if (METRIC != 0) {  // one table per query
 #pragma unroll
       for (int i = 0; i < M; ++i) {
         float acc = 0.f;
 #pragma unroll
         for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qm[u], T[i * DSUB + u], acc);
-        lut0[m_own * K + jj + TPM * i] = acc;
+        lut0[m_own * K + jj + TPM * i] = METRIC == 2 ? -2.f * acc : acc;
       }
     }
     block_sync_lds();   // probes, bound and the IP table are visible
@@ -389,6 +445,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     // unconditional (indices clamped into range; lanes past a list's end are masked when
     // they are consumed), so the number of loads in flight is the same on every path.
     CodeWords<M> cw, cw_n;
+    float nrm = 0.f, nrm_n = 0.f;                               // METRIC 2: the code's stored norm
     int64_t i_cur = 0;
     bool v_cur = false;
     float cm[DSUB], cm_n[DSUB];
@@ -398,6 +455,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       i_cur = s_begin[0] + tid;
       v_cur = i_cur < s_end[0];
       cw.load(codes + min(i_cur, last) * M);
+      if (METRIC == 2) nrm = norms[min(i_cur, last)];
       if (METRIC == 0) {
         const int l0 = s_list[0];
 #pragma unroll
@@ -413,6 +471,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       const int64_t i_n = s_begin[pn] + tid;
       const bool v_n = (p + 1 < np) && (i_n < s_end[pn]);
       cw_n.load(codes + min(i_n, last) * M);
+      if (METRIC == 2) nrm_n = norms[min(i_n, last)];
       float bias = 0.f;
       if (METRIC == 0) {
         const int l1 = s_list[pn];
@@ -440,17 +499,21 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       }
       // scan list p; the next chunk of a long list is requested before the current one is summed
       CodeWords<M> cw2;
+      float nrm2 = 0.f;
       for (;;) {
         const int64_t i2 = i_cur + 256;
         const bool more = i2 - tid < end;      // uniform: i2 - tid is the next chunk's base
         const bool v2 = i2 < end;
-        if (more) cw2.load(codes + min(i2, last) * M);
-        const float dist = v_cur ? cw.adc(lut, bias) : 0.f;
-        ws.push(v_cur, make_key(dist, (u32)i_cur, METRIC), true);
+        if (more) {
+          cw2.load(codes + min(i2, last) * M);
+          if (METRIC == 2) nrm2 = norms[min(i2, last)];
+        }
+        const float dist = v_cur ? cw.adc(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
+        ws.push(v_cur, make_key(dist, (u32)i_cur, KEY_METRIC), true);
         if (!more) break;
-        cw = cw2; i_cur = i2; v_cur = v2;
+        cw = cw2; nrm = nrm2; i_cur = i2; v_cur = v2;
       }
-      cw = cw_n; i_cur = i_n; v_cur = v_n;
+      cw = cw_n; nrm = nrm_n; i_cur = i_n; v_cur = v_n;
 #pragma unroll
       for (int u = 0; u < DSUB; ++u) cm[u] = cm_n[u];
       TICK(4);
@@ -534,18 +597,34 @@ void launch_pq_encode(const IvfpqDims& g, const float* x, int64_t n, const int32
 }
 
 void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t* old_ids,
-                     int64_t old_total, const int64_t* old_off, const int64_t* new_off,
-                     const uint8_t* tmp_codes, const int64_t* new_ids_or_null, int64_t id_base,
-                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids,
+                     const float* old_norms, int64_t old_total, const int64_t* old_off,
+                     const int64_t* new_off, const uint8_t* tmp_codes,
+                     const int64_t* new_ids_or_null, int64_t id_base, const float* tmp_norms,
+                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids, float* norms,
                      hipStream_t st) {
   if (old_total > 0)
     hipLaunchKernelGGL(move_old_kernel, dim3((unsigned)((old_total + 255) / 256)), dim3(256), 0, st,
-                       old_codes, old_ids, old_total, old_off, new_off, g.nlist, g.code_size, codes,
-                       ids);
+                       old_codes, old_ids, old_norms, old_total, old_off, new_off, g.nlist,
+                       g.code_size, codes, ids, norms);
   if (n_new > 0)
     hipLaunchKernelGGL(scatter_new_kernel, dim3((unsigned)((n_new + 255) / 256)), dim3(256), 0, st,
-                       tmp_codes, new_ids_or_null, id_base, dest, n_new, g.M, g.nbits, g.code_size,
-                       codes, ids);
+                       tmp_codes, new_ids_or_null, id_base, tmp_norms, dest, n_new, g.M, g.nbits,
+                       g.code_size, codes, ids, norms);
+}
+
+void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
+                     const float* centroids, const float* codebooks, float* tmp_norms,
+                     hipStream_t st) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(pq_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, tmp_codes,
+                     n, g.d, g.dsub, g.K, g.M, list_of, centroids, codebooks, tmp_norms);
+}
+
+void launch_pair_bias(const float* q, int64_t nq, int d, const float* centroids,
+                      const int32_t* probes, int nprobe, float* bias, hipStream_t st) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(pair_bias_kernel, dim3((unsigned)((nq * nprobe + 255) / 256)), dim3(256), 0, st,
+                     q, nq, d, centroids, probes, nprobe, bias);
 }
 
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
@@ -564,8 +643,8 @@ template <int M, int DSUB, int METRIC, int R, int NBUF>
 static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
-                            const uint8_t* codes, int64_t ntotal, int k, int tot, KeySink sink,
-                            hipStream_t st) {
+                            const uint8_t* codes, const float* norms, int64_t ntotal, int k, int tot,
+                            KeySink sink, hipStream_t st) {
   const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * 256 * sizeof(float) +
                        (size_t)ppb * 20 + 16;
   auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
@@ -579,8 +658,8 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
     per_cu = 1;
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
-                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, ntotal, k, tot,
-                     sink);
+                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, ntotal, k,
+                     tot, sink);
 }
 
 template <int M, int DSUB>
@@ -588,15 +667,17 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                int64_t ntotal, int k, int tot, KeySink sink, hipStream_t st) {
+                                const float* norms, int mode, int64_t ntotal, int k, int tot,
+                                KeySink sink, hipStream_t st) {
 #define GO(MET, RR, NB)                                                                           \
   launch_scan_reg<M, DSUB, MET, RR, NB>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
-                                        nsplit, list_off, codes, ntotal, k, tot, sink, st)
+                                        nsplit, list_off, codes, norms, ntotal, k, tot, sink, st)
   const int r = select_regs_for_slots(tot);
   // L2 tables alternate between two buffers (one barrier per list); the single inner-product
   // table needs one.  A single L2 table with a third resident workgroup per CU measured
   // slower at 1500-code lists: the 168-register budget it needs spills the codebook.
-  if (g.metric == 1)  { if (r == 2) GO(1, 2, 1); else if (r == 4) GO(1, 4, 1); else GO(1, 0, 1); }
+  if (mode == 1)      { if (r == 2) GO(1, 2, 1); else if (r == 4) GO(1, 4, 1); else GO(1, 0, 1); }
+  else if (mode == 2) { if (r == 2) GO(2, 2, 1); else if (r == 4) GO(2, 4, 1); else GO(2, 0, 1); }
   else                { if (r == 2) GO(0, 2, 2); else if (r == 4) GO(0, 4, 2); else GO(0, 0, 2); }
 #undef GO
 }
@@ -605,23 +686,27 @@ template <int NBITS, int R>
 static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
-                                int nsplit, const int64_t* list_off, const uint8_t* codes, int k,
-                                int tot, size_t shmem, KeySink sink, hipStream_t st) {
+                                int nsplit, const int64_t* list_off, const uint8_t* codes,
+                                const float* norms, int mode, int k, int tot, size_t shmem,
+                                KeySink sink, hipStream_t st) {
   auto kern = &ivfpq_scan_kernel<NBITS, R>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, g.metric,
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, mode,
                      g.M, g.dsub, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off,
-                     codes, g.code_size, k, tot, sink);
+                     codes, norms, g.code_size, k, tot, sink);
 }
 
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      int64_t ntotal, int k, u64* partial, const int64_t* ids, float* out_dist,
-                      int64_t* out_ids, hipStream_t st) {
+                      const float* norms, int64_t ntotal, int k, u64* partial, const int64_t* ids,
+                      float* out_dist, int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return 0;
+  // table form: 1 inner product; 2 L2 through the stored norms (cdist then holds
+  // |q|^2 - 2 <q, c_l>); 0 L2 with one table of squared residual distances per (query, list)
+  const int mode = g.metric == 1 ? 1 : (norms ? 2 : 0);
   KeySink sink;
   sink.metric = g.metric;
   sink.idx32 = nullptr;
@@ -636,7 +721,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                nsplit, list_off, codes, ntotal, k, tot, sink, st);              \
+                                nsplit, list_off, codes, norms, mode, ntotal, k, tot, sink, st); \
     return 0;                                                                                    \
   }
   REG(16, 8)   // PQ16x8 on d = 128
@@ -645,7 +730,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #undef REG
 #define GEN(NB, RR)                                                                              \
   launch_scan_generic<NB, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
-                              list_off, codes, k, tot, shmem, sink, st)
+                              list_off, codes, norms, mode, k, tot, shmem, sink, st)
   const int r = select_regs_for_slots(tot);
   if (g.nbits == 8) { if (r == 2) GEN(8, 2); else if (r == 4) GEN(8, 4); else GEN(8, 0); }
   else              { if (r == 2) GEN(4, 2); else if (r == 4) GEN(4, 4); else GEN(4, 0); }

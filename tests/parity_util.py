@@ -4,7 +4,10 @@
     id -> (list, code bytes) because the order inside a list is storage detail;
   - distances: |gpu - oracle| <= 1e-4 * max(|oracle|, s) where s is the
     magnitude of the terms that cancel (inner product: ||q|| * max ||x||;
-    L2: none, the squared distance is a sum of non-negative terms);
+    L2: none, the squared distance is a sum of non-negative terms -- except for the
+    search type that evaluates |q|^2 + |x'|^2 - 2 <q, x'> (Sec. 4.3), whose terms do
+    cancel: there `cancel` = |q|^2 + max |x'|^2 per query enters with the fp32 rounding
+    that decomposition can cost, 2^-21 of it, instead of a relative share);
   - ids: identical, except that a GPU id may differ from the oracle's id at
     the same rank when the ORACLE distances of the two candidates are within
     that tolerance of each other.  To see candidates just past rank k the
@@ -16,22 +19,24 @@ REL_TOL = 1e-4
 EXTRA = 16
 
 
-def tolerance(D_or, metric, q=None, xnorm_max=None):
+def tolerance(D_or, metric, q=None, xnorm_max=None, cancel=None):
     tol = REL_TOL * np.abs(D_or.astype(np.float64))
     if metric == 1:
         qn = np.sqrt((q.astype(np.float64) ** 2).sum(1, keepdims=True))
         tol = np.maximum(tol, REL_TOL * qn * float(xnorm_max))
+    if cancel is not None:
+        tol = tol + 2.0 ** -21 * np.asarray(cancel, dtype=np.float64).reshape(-1, 1)
     return tol
 
 
-def check_search(D_gpu, I_gpu, D_or, I_or, metric, q=None, xnorm_max=None):
+def check_search(D_gpu, I_gpu, D_or, I_or, metric, q=None, xnorm_max=None, cancel=None):
     """D_or/I_or come from the oracle with k + EXTRA ranks (or more); D_gpu/I_gpu have k.
     Returns the fraction of (query, rank) slots whose id equals the oracle's."""
     D_gpu = np.asarray(D_gpu); I_gpu = np.asarray(I_gpu)
     nq, k = D_gpu.shape
     assert D_or.shape[1] >= k
     Do, Io = D_or[:, :k].astype(np.float64), I_or[:, :k]
-    tol_all = tolerance(D_or, metric, q, xnorm_max)
+    tol_all = tolerance(D_or, metric, q, xnorm_max, cancel)
     tol = tol_all[:, :k]
     # empty slots agree
     empty_o = Io < 0

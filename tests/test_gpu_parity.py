@@ -395,6 +395,82 @@ def test_ivfpq_search_then_refine_pipeline(vs, oracle):
     ix.close()
 
 
+# ------------------------------------------------- L2 through stored norms (Sec. 4.3)
+
+@pytest.mark.parametrize("name", ["c1", "c3_small", "c4_small", "pq4_l2", "odd_shapes", "c4_long_lists"])
+def test_ivfpq_stored_norm_search_matches_oracle(vs, oracle, name):
+    """Search type |q|^2 + |x'|^2 - 2 <q, x'>: the stored norms are the oracle's bit for bit,
+    the results agree with the definition (oracle form 0) within the rounding of the
+    cancelling terms, and with the default search type of the same index."""
+    cfg, searches = IVF_CASES[name]
+    say("ivfpq stored norms %s nb=%d d=%d nlist=%d M=%d nbits=%d" % (
+        name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"], cfg["nbits"]))
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), cfg["nbits"])
+    ix.set_search_type(vs.ST_STORED_NORMS)
+    orc = oracle.OracleIVFPQ(cfg["d"], L2, cent, cb, cfg["nbits"])
+    half = cfg["nb"] // 2
+    ix.add(dev(x[:half])); ix.add(dev(x[half:]))                 # two pieces: norms move with the codes
+    orc.add(x[:half]); orc.add(x[half:])
+    check_storage(ix, orc)
+    np.testing.assert_array_equal(host(ix.norms()), orc.norms)
+    cancel = (q.astype(np.float64) ** 2).sum(1) + float(orc.norms.max())
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        D, I = [host(t).copy() for t in ix.search(dev(q), k, nprobe)]
+        Do, Io = orc.search(q, k + EXTRA, nprobe)                 # the definition
+        same = check_search(D, I, Do, Io, L2, cancel=cancel)
+        assert same > 0.97, same
+        ix.set_search_type(vs.ST_RESIDUAL_TABLES)                 # the other form on the same store
+        D0, I0 = [host(t) for t in ix.search(dev(q), k, nprobe)]
+        ix.set_search_type(vs.ST_STORED_NORMS)
+        live = I0 >= 0
+        assert (np.abs(D.astype(np.float64) - D0)[live] <= (1e-4 * np.abs(D0) + 2.0 ** -21 * cancel[:, None])[live]).all()
+    ix.close()
+
+
+def test_stored_norm_search_on_integer_data_is_exact(vs, oracle):
+    """With integer-valued vectors, centroids and codebooks every term of the decomposition
+    is exact, so both search types and the oracle's definition return the same bits."""
+    say("stored norms, integer data")
+    rng = np.random.default_rng(77)
+    x = rng.integers(0, 40, size=(6000, 32)).astype(np.float32)
+    q = rng.integers(0, 40, size=(50, 32)).astype(np.float32)
+    cent = x[rng.permutation(6000)[:16]].copy()
+    cb = rng.integers(-6, 7, size=(8, 256, 4)).astype(np.float32)
+    ix = vs.IVFPQ(32, L2, dev(cent), dev(cb), 8)
+    ix.set_search_type(vs.ST_STORED_NORMS)
+    ix.add(dev(x))
+    orc = oracle.OracleIVFPQ(32, L2, cent, cb, 8)
+    orc.add(x)
+    D, I = [host(t).copy() for t in ix.search(dev(q), 10, 4)]
+    Do, Io = orc.search(q, 10, 4)
+    np.testing.assert_array_equal(D, Do)
+    ix.set_search_type(vs.ST_RESIDUAL_TABLES)
+    D0, I0 = [host(t) for t in ix.search(dev(q), 10, 4)]
+    np.testing.assert_array_equal(D, D0)
+    np.testing.assert_array_equal(I, I0)
+    ix.close()
+
+
+def test_stored_norm_search_type_rules(vs):
+    cfg = S.config("C1", nb=500)
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(32, L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x))
+    with pytest.raises(vs.VSError):
+        ix.set_search_type(vs.ST_STORED_NORMS)                    # vectors were added without norms
+    with pytest.raises(vs.VSError):
+        ix.set_search_type(7)
+    ix.close()
+    ixp = vs.IVFPQ(32, IP, dev(cent), dev(cb), 8)
+    with pytest.raises(vs.VSError):
+        ixp.set_search_type(vs.ST_STORED_NORMS)                   # L2 only
+    ixp.close()
+
+
 # ------------------------------------------------- IVF-Flat
 
 IVFFLAT_CASES = {
