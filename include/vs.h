@@ -264,7 +264,7 @@ VS_API int vs_profile_read(double* stage_ms, int64_t* launches);
 
 /* "knn_path": how exact k-nearest-row problems (coarse quantizer, list
  *   assignment, flat search) are evaluated.  0 (default): matrix-core shortlist
- *   + exact re-rank where a kernel exists (d in {32, 64, 96, 128}, k <= 150),
+ *   + exact re-rank where a kernel exists (d a multiple of 32 up to 2048, k <= 150),
  *   canon distance tiles otherwise; 1: canon tiles only; 2: same as 0.
  *   Both routes return identical results.
  * "knn_eps_scale": multiplies the error bound used to prove a shortlist

@@ -148,7 +148,7 @@ KnnPlan knn_plan(int64_t na, int64_t nb, int d, int k, bool b_prepared) {
   if (p.mfma) {
     size_t b = planes_bytes(na, d);
     if (!b_prepared) b += planes_bytes(nb, d);
-    b += align_up(mfma_knn_shortlist_bytes(na, nb, k, &p.nsplit));
+    b += align_up(mfma_knn_shortlist_bytes(na, nb, d, k, &p.nsplit));
     b += align_up(sizeof(int)) + align_up((size_t)na * sizeof(int));
     b += align_up(mfma_knn_fallback_bytes(na, nb, k));
     p.bytes = b;
@@ -169,7 +169,7 @@ void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const fl
     if (b_planes) pb = *b_planes;
     else { pb = carve_planes(ws + o, nb, d); o += planes_bytes(nb, d); }
     int ns = 1;
-    const size_t sl = align_up(mfma_knn_shortlist_bytes(na, nb, k, &ns));
+    const size_t sl = align_up(mfma_knn_shortlist_bytes(na, nb, d, k, &ns));
     u64* shortlist = reinterpret_cast<u64*>(ws + o); o += sl;
     int* fb_count = reinterpret_cast<int*>(ws + o); o += align_up(sizeof(int));
     int* fb_rows = reinterpret_cast<int*>(ws + o); o += align_up((size_t)na * sizeof(int));

@@ -95,7 +95,7 @@ int mfma_knn_kp(int k);
 void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
                  float* norm, PrepInfo* info, hipStream_t st);
 // bytes of the shortlist buffer [na, nsplit, kp] and the column split count to use
-size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out);
+size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int d, int k, int* nsplit_out);
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
                            int nsplit, u64* shortlist, hipStream_t st);
 // exact k best per row of A from the shortlists; rows that cannot be proven exact are

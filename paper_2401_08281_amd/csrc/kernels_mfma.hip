@@ -401,6 +401,243 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same two sweeps for any d that is a multiple of 32 (up to 2048), where the fragments
+// of a row block no longer fit in registers: a classic tiled contraction.  Workgroup = 8
+// wavefronts in a 4 x 2 grid over a 256 x 128 tile of (rows of A) x (rows of B); wavefront
+// (wr, wc) owns the 64 x 64 block at (64 wr, 64 wc) as 2 x 2 MFMA tiles (64 accumulators).
+// The contraction runs over chunks of 32 dimensions: each chunk of both operands is copied
+// global -> registers -> LDS (double buffered; rows padded to 80 bytes: conflict-free
+// 128-bit reads) while the previous chunk is multiplied.  One byte of either operand
+// feeds 128 or 256 rows of the other, and the selection epilogue runs once per tile, after
+// the last chunk -- MODE 0 / MODE 1 exactly as in mfma_sweep_kernel.
+// ---------------------------------------------------------------------------
+template <int METRIC, int MODE, bool THREE>
+__global__ __launch_bounds__(512, 2)
+void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
+                          const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
+                          const unsigned short* __restrict__ Bhi, const unsigned short* __restrict__ Blo,
+                          const float* __restrict__ Bnorm, const PrepInfo* __restrict__ Binfo, int64_t nb,
+                          int d, int nsplit, int64_t cols_per_split, int stride, int nphase,
+                          int64_t cols_per_phase, float* __restrict__ minima, int g_raw,
+                          const float* __restrict__ tau, int* __restrict__ cnt,
+                          u64* __restrict__ shortlist, int cap) {
+  constexpr int BM = 256, BN = 128, KC = 32, LD = 40;            // LD: LDS row stride in bf16 elements
+  constexpr int NPL = THREE ? 2 : 1;
+  constexpr int PLANE = (BM + BN) * LD;                          // one plane of one buffer, in elements
+  constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
+  constexpr float INV_S = METRIC == 0 ? 0.5f : 1.f;
+  if ((!(Ainfo->all_bf16 && Binfo->all_bf16)) != THREE) return;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned short* tiles = reinterpret_cast<unsigned short*>(smem);        // [2][NPL][BM + BN][LD]
+  float* bns = reinterpret_cast<float*>(tiles + 2 * NPL * PLANE);        // [2][BN]
+  int* cnt_s = reinterpret_cast<int*>(bns + 2 * BN);                     // [BM]
+  u64* qkey = reinterpret_cast<u64*>(cnt_s + BM) + (threadIdx.x >> 6) * 128;          // [8][128]
+  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + BM) + 8 * 128) +
+              (threadIdx.x >> 6) * 128;                                  // [8][128]
+  int qn = 0;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+  const int wr = wave >> 1, wc = wave & 1;
+  const int64_t rt = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int64_t row0 = rt * BM;
+  const int64_t c_begin = (int64_t)split * cols_per_split;
+  const int64_t c_end = min(nb, c_begin + cols_per_split);
+  const int64_t col_step = (int64_t)BN * stride;
+  const int64_t a_last = (na + 63) / 64 * 64 - 1, b_last = (nb + 63) / 64 * 64 - 1;
+  const int nkc = d / KC;
+
+  // thresholds (MODE 1) / running minima (MODE 0) of this wavefront's 64 rows
+  float mn[2][16];
+  floatx16 tr[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t r = min(row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), na - 1);
+      tr[rb][v] = MODE == 1 ? tau[r] * INV_S : 0.f;
+      mn[rb][v] = __builtin_inff();
+    }
+
+  // staging: 3 chunks of 16 bytes per lane and plane: chunk ids tid, tid + 512, tid + 1024;
+  // ids below 1024 are A (row id / 4, 8 elements at (id % 4) * 8), the rest B
+  u32x4 stg[NPL][3];
+  float stn = 0.f;
+  int s_row[3], s_col[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) { const int id = tid + 512 * i; s_row[i] = id >> 2; s_col[i] = (id & 3) * 8; }
+#define FETCH_KC(CT, KCH)                                                                         \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_) {                                            \
+      int64_t o_;                                                                                 \
+      if (s_row[i_] < BM) o_ = min(row0 + s_row[i_], a_last) * d + (KCH) * KC + s_col[i_];        \
+      else o_ = min((CT) + (int64_t)(s_row[i_] - BM) * stride, b_last) * d + (KCH) * KC + s_col[i_]; \
+      const bool isa_ = s_row[i_] < BM;                                                           \
+      stg[0][i_] = *reinterpret_cast<const u32x4*>((isa_ ? Ahi : Bhi) + o_);                      \
+      if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>((isa_ ? Alo : Blo) + o_); \
+    }                                                                                             \
+    if ((KCH) == 0 && tid < BN) stn = Bnorm[min((CT) + (int64_t)tid * stride, b_last)];           \
+  } while (0)
+#define STASH_KC(BUF, CT, KCH, TILE)                                                              \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_)                                              \
+      _Pragma("unroll") for (int pl_ = 0; pl_ < NPL; ++pl_)                                       \
+        *reinterpret_cast<u32x4*>(tiles + ((BUF) * NPL + pl_) * PLANE + s_row[i_] * LD + s_col[i_]) = stg[pl_][i_]; \
+    if ((KCH) == 0 && tid < BN)                                                                   \
+      bns[((TILE) & 1) * BN + tid] =                                                              \
+          (CT) + (int64_t)tid * stride < c_end                                                    \
+              ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();         \
+  } while (0)
+
+  if (MODE == 1) for (int i = tid; i < BM; i += 512) cnt_s[i] = 0;
+  auto drain = [&](int n) {
+    wave_lds_sync();
+    const int e = qn - n + lane;
+    if (lane < n) {
+      const int rl = qrow[e];
+      const u64 key = qkey[e];
+      const int pos = atomicAdd(&cnt_s[rl], 1);
+      const int64_t r = row0 + rl;
+      if (pos < cap) shortlist[(r * nsplit + split) * (int64_t)cap + pos] = key;
+    }
+    qn -= n;
+    wave_lds_sync();
+  };
+
+  if (c_begin < c_end) { FETCH_KC(c_begin, 0); STASH_KC(0, c_begin, 0, 0); }
+  wait_all_global_loads();
+  block_sync_lds();
+  int buf = 0, tile = 0;
+  floatx16 m[2][2];
+  for (int64_t ct = c_begin; ct < c_end; ct += col_step, ++tile) {
+    for (int kch = 0; kch < nkc; ++kch, buf ^= 1) {
+      // the stage after this one: next chunk of the same tile, or the first chunk of the next tile
+      const bool last_kc = kch + 1 == nkc;
+      const int64_t ct_n = last_kc ? ct + col_step : ct;
+      const int kch_n = last_kc ? 0 : kch + 1;
+      const bool more = ct_n < c_end;
+      if (more) FETCH_KC(ct_n, kch_n);
+      const unsigned short* __restrict__ ta = tiles + (buf * NPL) * PLANE;   // A rows, then B rows
+      if (kch == 0) {   // a new tile starts from 0 (MODE 0) / from the row thresholds (MODE 1)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) m[rb][cb] = tr[rb];
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const int oa = (wr * 64 + x * 32 + (lane & 31)) * LD + ks * 16 + 8 * (lane >> 5);
+          const int ob = (BM + wc * 64 + x * 32 + (lane & 31)) * LD + ks * 16 + 8 * (lane >> 5);
+          ah[x] = *reinterpret_cast<const bf16x8*>(ta + oa);
+          bh[x] = *reinterpret_cast<const bf16x8*>(ta + ob);
+          if constexpr (THREE) {
+            al[x] = *reinterpret_cast<const bf16x8*>(ta + PLANE + oa);
+            bl[x] = *reinterpret_cast<const bf16x8*>(ta + PLANE + ob);
+          }
+        }
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bh[cb], m[rb][cb], 0, 0, 0);
+            if constexpr (THREE) {
+              m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bl[cb], m[rb][cb], 0, 0, 0);
+              m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb], bh[cb], m[rb][cb], 0, 0, 0);
+            }
+          }
+      }
+      if (last_kc) {   // the tile is complete: selection epilogue
+        const float b0 = bns[(tile & 1) * BN + wc * 64 + (lane & 31)];
+        const float b1 = bns[(tile & 1) * BN + wc * 64 + 32 + (lane & 31)];
+        if (MODE == 0) {
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                mn[rb][v] = fminf(mn[rb][v], __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0));
+          const int ph = (int)((ct - c_begin) / cols_per_phase);
+          const int ph_next = ct + col_step < c_end ? (int)((ct + col_step - c_begin) / cols_per_phase) : nphase;
+          for (int p2 = ph; p2 < ph_next; ++p2) {
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int64_t r = row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (r < na)
+                  minima[r * g_raw + (split * nphase + p2) * 64 + wc * 32 + (lane & 31)] = mn[rb][v];
+                mn[rb][v] = __builtin_inff();
+              }
+          }
+        } else {
+          bool any[2][2];
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+              float mx = m[rb][cb][0];
+#pragma unroll
+              for (int v = 1; v < 16; ++v) mx = fmaxf(mx, m[rb][cb][v]);
+              any[rb][cb] = mx >= (cb ? b1 : b0);
+            }
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+              if (__ballot(any[rb][cb]) == 0) continue;
+              const float hb = cb ? b1 : b0;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int rl = wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const bool pass = m[rb][cb][v] >= hb && row0 + rl < na;
+                const u64 mask = __ballot(pass);
+                if (mask != 0) {
+                  if (pass) {
+                    const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
+                    const float dotv = m[rb][cb][v] - tr[rb][v];
+                    const float val = METRIC == 0 ? Anorm[row0 + rl] + 2.f * (hb - dotv) : dotv;
+                    qkey[e] = make_key(val, (u32)(ct + wc * 64 + cb * 32 + (lane & 31)), METRIC);
+                    qrow[e] = rl;
+                  }
+                  qn += __popcll(mask);
+                  if (qn >= 64) drain(64);
+                }
+              }
+            }
+        }
+      }
+      if (more) STASH_KC(buf ^ 1, ct_n, kch_n, tile + (last_kc ? 1 : 0));
+      block_sync_lds();
+    }
+  }
+#undef FETCH_KC
+#undef STASH_KC
+  if (MODE == 1) {
+    if (qn > 0) drain(qn);
+    block_sync_lds();
+    for (int i = tid; i < BM; i += 512) {
+      const int64_t r = row0 + i;
+      if (r < na) cnt[r * nsplit + split] = cnt_s[i];
+    }
+  }
+  if (MODE == 0 && c_begin >= c_end) {
+    for (int ph = 0; ph < nphase; ++ph)
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t r = row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (r < na) minima[r * g_raw + (split * nphase + ph) * 64 + wc * 32 + (lane & 31)] = __builtin_inff();
+        }
+  }
+}
+
 // tau(row) = kp-th smallest of the row's g_raw group minima (min-combined down to 64 * RG
 // values first), clamped below +inf.
 template <int RG>
@@ -632,7 +869,7 @@ __global__ void zero_int_kernel(int* p) { *p = 0; }
 int64_t mfma_padded_rows(int64_t n) { return (n + 63) / 64 * 64; }
 
 bool mfma_knn_supported(int d, int k) {
-  return (d == 32 || d == 64 || d == 96 || d == 128) && k <= 150;
+  return d >= 32 && d % 32 == 0 && d <= 2048 && k <= 150;
 }
 
 int mfma_knn_kp(int k) {
@@ -645,7 +882,7 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
                  float* norm, PrepInfo* info, hipStream_t st) {
   hipLaunchKernelGGL(prep_info_init_kernel, dim3(1), dim3(1), 0, st, info);
   if (n <= 0) return;
-  const int rpb = 2048 / d;                          // d <= 128 here, d % 8 == 0
+  const int rpb = 2048 / d;                          // d <= 2048 here, d % 8 == 0
   const int64_t n_pad = mfma_padded_rows(n);
   // in pieces of 2^24 rows (a multiple of 64): a launch holds fewer than 2^32 work-items
   constexpr int64_t kRows = 1ll << 24;
@@ -658,34 +895,45 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
 
 namespace {
 struct MfmaPlan {
+  bool kc;                                   // general-d kernel (256 x 128 tiles) instead of the
+                                             // register-stationary one (128 rows x 64 columns)
   int RB, nsplit, nphase, g_raw, rg, kp, kp_tau, stride, cap;
   int64_t cols_per_split, cols_per_phase, row_tiles;
   size_t o_minima, o_tau, o_cnt, bytes;      // offsets behind the shortlist [na][nsplit][cap]
 };
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
-MfmaPlan make_plan(int64_t na, int64_t nb, int k) {
+bool stationary_d(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
+
+MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   MfmaPlan p;
+  p.kc = !stationary_d(d);
+  const int bm = p.kc ? 256 : 128, bn = p.kc ? 128 : 64;      // tile of one workgroup step
+  const int slots = p.kc ? 256 : 512;                          // resident workgroups on the chip
   p.kp = mfma_knn_kp(k);
   p.cap = std::max(64, 3 * p.kp);
   // One 32-row block of A per wavefront: small enough in registers for two workgroups per
   // CU, whose matrix-core and vector phases then overlap (measured faster than two row
   // blocks per wavefront at half the occupancy).  Splits of B fill the 512 resident slots.
   p.RB = 1;
-  p.row_tiles = (na + 128 * p.RB - 1) / (128 * p.RB);
-  const int64_t col_steps = std::max<int64_t>(1, (nb + 63) / 64);
-  int64_t ns = std::max<int64_t>(1, 512 / p.row_tiles);
+  p.row_tiles = (na + bm - 1) / bm;
+  const int64_t col_steps = std::max<int64_t>(1, (nb + bn - 1) / bn);
+  int64_t ns = std::max<int64_t>(1, slots / p.row_tiles);
   ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
   ns = std::min<int64_t>(ns, 16);
   p.nsplit = (int)ns;
   const int64_t steps_per_split = (col_steps + ns - 1) / ns;
-  p.cols_per_split = steps_per_split * 64;
-  // The minima sweep visits every S-th tile once a split has enough of them: tau then comes
-  // from a 1/S sample of the columns.  With S = 1 the kp-th smallest group minimum guarantees
-  // kp listed columns; with S > 1 the rank is chosen so that about S * kp_tau columns are
-  // expected below tau, at least k of them except with small probability (rows that end up
-  // with fewer, or with more than their lists hold, fail the re-rank test and are recomputed).
+  p.cols_per_split = steps_per_split * bn;
+  // The minima sweep computes every S-th row of B once a split of B is long enough: tau then
+  // comes from 1/S of the columns.  With S = 1 the kp-th
+  // smallest group minimum guarantees kp listed columns; with S > 1 the rank is chosen so that
+  // about S * kp_tau columns are expected below tau, at least k of them except with small
+  // probability (rows that end up with fewer, or with more than their lists hold, fail the
+  // re-rank test and are recomputed).
   p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, steps_per_split / 32));
+  // (long rows make a sweep expensive: the tiled kernel samples from 16384 columns on)
+  if (p.kc) p.stride = (int)std::max<int64_t>(p.stride, std::min<int64_t>(4, nb / 4096));
+  p.stride = (int)std::min<int64_t>(p.stride, steps_per_split);        // at least one tile per split
   if (p.stride == 1) {
     p.kp_tau = p.kp;
   } else {
@@ -706,7 +954,7 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k) {
   int64_t nph = (p.rg + ns - 1) / ns;
   nph = std::max<int64_t>(1, std::min(nph, visited));
   p.nphase = (int)nph;
-  p.cols_per_phase = (visited + nph - 1) / nph * 64 * p.stride;
+  p.cols_per_phase = (visited + nph - 1) / nph * bn * p.stride;
   p.g_raw = 64 * p.nsplit * p.nphase;
   size_t o = up256((size_t)na * p.nsplit * p.cap * sizeof(u64));
   p.o_minima = o; o += up256((size_t)na * p.g_raw * sizeof(float));
@@ -733,8 +981,8 @@ size_t mfma_knn_fallback_bytes(int64_t na, int64_t nb, int k) {
   return f.nchunk == 1 ? 0 : (size_t)na * f.nchunk * k * sizeof(u64);
 }
 
-size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int k, int* nsplit_out) {
-  const MfmaPlan p = make_plan(na, nb, k);
+size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int d, int k, int* nsplit_out) {
+  const MfmaPlan p = make_plan(na, nb, k, d);
   *nsplit_out = p.nsplit;
   return p.bytes;
 }
@@ -766,9 +1014,36 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
 }
 
+template <int METRIC, int MODE, bool THREE>
+static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
+                              char* work, hipStream_t st) {
+  constexpr int NPL = THREE ? 2 : 1;
+  const size_t shmem = (size_t)2 * NPL * (256 + 128) * 40 * sizeof(unsigned short) + 2 * 128 * sizeof(float) +
+                       (size_t)256 * sizeof(int) + 8 * 128 * (sizeof(u64) + sizeof(int));
+  auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, THREE>;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.row_tiles * p.nsplit)), dim3(512), shmem, st, A.hi, A.lo,
+                     A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, d, p.nsplit, p.cols_per_split,
+                     MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
+                     reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
+                     reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
+                     reinterpret_cast<u64*>(work), p.cap);
+}
+
 template <int MODE>
 static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                          int metric, char* work, hipStream_t st) {
+  if (p.kc) {   // both operand-precision variants, as below
+    if (metric == 0) {
+      launch_sweep_kc_t<0, MODE, false>(p, A, B, d, work, st);
+      launch_sweep_kc_t<0, MODE, true>(p, A, B, d, work, st);
+    } else {
+      launch_sweep_kc_t<1, MODE, false>(p, A, B, d, work, st);
+      launch_sweep_kc_t<1, MODE, true>(p, A, B, d, work, st);
+    }
+    return;
+  }
 #define GO(KS)                                                                      \
   do {                                                                              \
     if (metric == 0) launch_sweep_k<KS, 0, MODE>(p, A, B, work, st);                \
@@ -786,7 +1061,7 @@ static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOper
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
                            int nsplit, u64* shortlist, hipStream_t st) {
   (void)nsplit;
-  const MfmaPlan p = make_plan(A.n, B.n, k);
+  const MfmaPlan p = make_plan(A.n, B.n, k, d);
   char* work = reinterpret_cast<char*>(shortlist);
   launch_sweep<0>(p, A, B, d, metric, work, st);
   const dim3 grid((unsigned)((A.n + 3) / 4)), block(256);
@@ -805,7 +1080,7 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
                    const u64* shortlist, float eps_scale, const SelectOut& out, int* fb_count,
                    int* fb_rows, u64* fb_partial, hipStream_t st) {
   (void)nsplit;
-  const MfmaPlan p = make_plan(A.n, B.n, k);
+  const MfmaPlan p = make_plan(A.n, B.n, k, d);
   const int kp = p.kp;
   const int* cnt = reinterpret_cast<const int*>(reinterpret_cast<const char*>(shortlist) + p.o_cnt);
   const float* tau = reinterpret_cast<const float*>(reinterpret_cast<const char*>(shortlist) + p.o_tau);

@@ -270,6 +270,12 @@ ROUTE_CASES = [
     ("unit_d96_k20", 15_000, 100, 96, 20, L2, "unit"),
     ("sift_d128_k100", 50_000, 100, 128, 100, L2, "sift"),
     ("tiny_nb_d32", 50, 10, 32, 40, L2, "gauss"),
+    # dimensions beyond 128: the tiled kernel (operands streamed in chunks of 32 dimensions)
+    ("gauss_d256_k10", 20_000, 700, 256, 10, L2, "gauss"),
+    ("gauss_d160_k100", 12_000, 130, 160, 100, L2, "gauss"),
+    ("unit_d768_k32_ip", 9_000, 300, 768, 32, IP, "unit"),
+    ("sift_d256_k20", 40_000, 64, 256, 20, L2, "sift"),
+    ("gauss_d2048_k5", 3_000, 40, 2048, 5, L2, "gauss"),
     # long database in cluster order: the threshold comes from a sample of the columns
     ("sift_sorted_d128_k100", 200_000, 64, 128, 100, L2, "sift_sorted"),
     ("unit_sorted_d96_k10", 150_000, 96, 96, 10, L2, "unit_sorted"),
