@@ -73,6 +73,14 @@ VS_API int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq
                    void* hip_stream);
 
 /*
+ * vs_flat_search, vs_kmeans and vs_ivfpq_train keep one grow-only work buffer per device
+ * (operand planes, candidate lists, ...; for a 10M x 768 database about 30 GB).  vs_trim
+ * waits for the current device to go idle and frees that buffer; the next call allocates
+ * what it needs again.  Indexes own their buffers and release them in their destroy call.
+ */
+VS_API int vs_trim(void);
+
+/*
  * Re-rank a shortlist with exact distances (Sec. 3.5 "Refining"; the "RFlat" suffix
  * of App. A.2's index factory): the second, accurate stage behind a fast first
  * search such as vs_ivfpq_search run with kc > k.

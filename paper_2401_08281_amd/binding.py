@@ -36,6 +36,8 @@ def lib():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.vs_flat_search.restype = ctypes.c_int
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_trim.restype = ctypes.c_int
+    L.vs_trim.argtypes = []
     L.vs_ivfpq_set_search_type.restype = ctypes.c_int
     L.vs_ivfpq_set_search_type.argtypes = [vp, i32]
     L.vs_ivfpq_get_norms.restype = ctypes.c_int
@@ -140,6 +142,10 @@ def vs_profile_read():
     n = (ctypes.c_int64 * len(STAGES))()
     _check(lib().vs_profile_read(ms, n))
     return {s: (float(ms[i]), int(n[i])) for i, s in enumerate(STAGES)}
+
+
+def vs_trim():
+    _check(lib().vs_trim())
 
 
 def vs_set_option(name, value):

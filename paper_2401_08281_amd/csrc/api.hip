@@ -322,6 +322,16 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   return VS_OK;
 }
 
+int vs_trim(void) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_trim: device %d", dev);
+  std::lock_guard<std::mutex> lock(g_flat_mu);
+  HIP_TRY(hipDeviceSynchronize());   // nothing may still be using the buffer
+  g_flat_scratch[dev].release();
+  return VS_OK;
+}
+
 int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d, int32_t metric,
               const int64_t* cand_ids, int32_t kc, int32_t k, float* out_dist, int64_t* out_ids,
               void* hip_stream) {

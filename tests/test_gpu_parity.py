@@ -82,6 +82,19 @@ def test_flat_sift_like_is_bit_exact(vs, oracle):
     np.testing.assert_array_equal(I, Io)
 
 
+def test_trim_releases_the_work_buffer_and_search_still_works(vs, oracle):
+    import torch
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((4000, 64), dtype=np.float32)
+    q = rng.standard_normal((30, 64), dtype=np.float32)
+    D1, I1 = [host(t).copy() for t in vs.vs_flat_search(dev(x), dev(q), 7, L2)]
+    vs.vs_trim()
+    vs.vs_trim()                                             # nothing to free: still fine
+    D2, I2 = [host(t) for t in vs.vs_flat_search(dev(x), dev(q), 7, L2)]
+    np.testing.assert_array_equal(D1, D2)
+    np.testing.assert_array_equal(I1, I2)
+
+
 def test_flat_empty_database_and_no_queries(vs):
     import torch
     say("flat nb=0 / nq=0")
@@ -138,6 +151,8 @@ IVF_CASES = {
     "c3_long_lists": (S.config("C3", nb=40_000, nq=100, ncomp=100, nlist=16), [(10, 4)]),
     "c1_long_lists": (S.config("C1", nb=20_000, nlist=8), [(10, 3), (500, 8)]),
     "odd_shapes": (S.config("C1", nb=3_001, nq=33, d=30, M=5, nlist=7), [(10, 3), (300, 7)]),
+    # the largest k and nprobe the boundary accepts, every list probed
+    "max_k_and_nprobe": (S.config("C1", nb=30_000, nq=40, nlist=1024), [(1024, 1024)]),
 }
 
 
@@ -485,6 +500,7 @@ IVFFLAT_CASES = {
     "c4_small_ip": (S.config("C4", nb=30_000, nq=64, ncomp=50, nlist=128, metric=1), [(10, 8)]),
     "odd_d30": (S.config("C1", nb=3_001, nq=33, d=30, nlist=7), [(10, 3), (500, 7)]),
     "d768": (S.config("C5", nb=4_000, nq=20, ncomp=20, nlist=16), [(10, 4)]),
+    "max_k_and_nprobe": (S.config("C1", nb=30_000, nq=40, nlist=1024), [(1024, 1024)]),
 }
 
 
