@@ -468,6 +468,71 @@ void or_ivfflat_search(const float *q, int64_t nq, int d, int metric, int nlist,
   free(probes); free(cdist);
 }
 
+/* ---- 8-bit scalar quantizer and IVF-SQ8 (Sec. 4.1 "Scalar quantizers": a uniform
+ * quantizer encodes every component on its own; a scale and an offset per dimension
+ * determine which values are reconstructed.  App. A.3 lists the IVF index with a scalar
+ * quantizer among the GPU indexes) ------------------------------------------------
+ * The paper gives no formula; the reading taken: component t is expected in
+ * [vmin_t, vmin_t + 256 step_t); that range is cut into 256 cells of width step_t; the
+ * code is the number of the cell that holds the component (components outside go to the
+ * first / last cell) and the reconstruction is the middle of the cell:
+ *     u = (x_t - vmin_t) / step_t          one fp32 subtraction, one fp32 division
+ *     code_t = 0 if u < 0, 255 if u >= 256, else the integer part of u
+ *     x'_t = fma(code_t + 0.5, step_t, vmin_t)   in fp32
+ * The fp32 operations are fixed so that codes can be compared bit for bit. */
+void or_sq8_encode(const float *x, int64_t n, int d, const float *vmin, const float *step,
+                   uint8_t *codes) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int t = 0; t < d; ++t) {
+      float u = (x[i * d + t] - vmin[t]) / step[t];
+      codes[i * d + t] = u < 0.0f ? 0 : (u >= 256.0f ? 255 : (uint8_t)(int)u);
+    }
+}
+
+void or_sq8_decode(const uint8_t *codes, int64_t n, int d, const float *vmin, const float *step,
+                   float *xdec) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int t = 0; t < d; ++t)
+      xdec[i * d + t] = fmaf((float)codes[i * d + t] + 0.5f, step[t], vmin[t]);
+}
+
+/* IVF-SQ8 search: the probes of or_coarse_probe, then for every stored code of the probed
+ * lists the distance between the query and the code's reconstruction, by the definition
+ * (float64 sum over the fp32 reconstruction, rounded once).  The vectors themselves are
+ * encoded (no residual). */
+void or_ivfsq8_search(const float *q, int64_t nq, int d, int metric, int nlist,
+                      const float *centroids, const float *vmin, const float *step,
+                      const int64_t *list_offsets, const uint8_t *codes, const int64_t *ids,
+                      int k, int nprobe, float *D, int64_t *I, int64_t *nscanned) {
+  if (nprobe > nlist) nprobe = nlist;
+  int32_t *probes = (int32_t *)malloc(sizeof(int32_t) * nq * nprobe);
+  float *cdist = (float *)malloc(sizeof(float) * nq * nprobe);
+  or_coarse_probe(q, nq, centroids, nlist, d, metric, nprobe, probes, cdist);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t a = 0; a < nq; ++a) {
+    const float *qa = q + a * d;
+    topk_t h;
+    topk_init(&h, k, metric, D + a * k, I + a * k);
+    int64_t visited = 0;
+    for (int p = 0; p < nprobe; ++p) {
+      const int l = probes[a * nprobe + p];
+      for (int64_t s = list_offsets[l]; s < list_offsets[l + 1]; ++s) {
+        const uint8_t *c = codes + s * d;
+        double acc = 0.0;
+        for (int t = 0; t < d; ++t) {
+          double xt = (double)fmaf((float)c[t] + 0.5f, step[t], vmin[t]);
+          if (metric == OR_METRIC_L2) { double diff = (double)qa[t] - xt; acc += diff * diff; }
+          else acc += (double)qa[t] * xt;
+        }
+        topk_push(&h, (float)acc, ids[s]);
+        ++visited;
+      }
+    }
+    if (nscanned) nscanned[a] = visited;
+  }
+  free(probes); free(cdist);
+}
+
 int or_num_threads(void) {
 #ifdef _OPENMP
   extern int omp_get_max_threads(void);

@@ -229,6 +229,92 @@ def recall(I_found, I_true, n=None):
     return hits / float(I_found.shape[0] * n)
 
 
+def sq8_params(x):
+    """Range of every component over the training vectors x, as (vmin [d], step [d]) fp32 with
+    256 cells of width step covering [min, max] (a constant component gets step 1)."""
+    x = np.asarray(x, dtype=np.float32)
+    lo, hi = x.min(axis=0), x.max(axis=0)
+    step = ((hi.astype(np.float64) - lo) / 256.0).astype(np.float32)
+    step[step <= 0] = 1.0
+    return np.ascontiguousarray(lo), np.ascontiguousarray(step)
+
+
+def sq8_encode(x, vmin, step):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n, d = x.shape
+    codes = np.empty((n, d), dtype=np.uint8)
+    _load().or_sq8_encode(_ptr(x), ctypes.c_int64(n), ctypes.c_int(d),
+                          _ptr(np.ascontiguousarray(vmin, dtype=np.float32)),
+                          _ptr(np.ascontiguousarray(step, dtype=np.float32)), _ptr(codes))
+    return codes
+
+
+def sq8_decode(codes, vmin, step):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    n, d = codes.shape
+    out = np.empty((n, d), dtype=np.float32)
+    _load().or_sq8_decode(_ptr(codes), ctypes.c_int64(n), ctypes.c_int(d),
+                          _ptr(np.ascontiguousarray(vmin, dtype=np.float32)),
+                          _ptr(np.ascontiguousarray(step, dtype=np.float32)), _ptr(out))
+    return out
+
+
+class OracleIVFSQ8:
+    """IVF index whose entries are 8-bit scalar-quantizer codes of the vectors (Sec. 4.1, 5.1)."""
+
+    def __init__(self, d, metric, centroids, vmin, step):
+        self.d, self.metric = int(d), int(metric)
+        self.centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+        self.vmin = np.ascontiguousarray(vmin, dtype=np.float32)
+        self.step = np.ascontiguousarray(step, dtype=np.float32)
+        self.nlist = self.centroids.shape[0]
+        self.add_ids = np.empty(0, dtype=np.int64)
+        self.add_list_of = np.empty(0, dtype=np.int32)
+        self.add_codes = np.empty((0, self.d), dtype=np.uint8)
+        self._relayout()
+
+    @property
+    def ntotal(self):
+        return self.add_ids.shape[0]
+
+    def _relayout(self):
+        order = np.argsort(self.add_list_of, kind="stable")
+        self.ids = np.ascontiguousarray(self.add_ids[order])
+        self.codes = np.ascontiguousarray(self.add_codes[order])
+        sizes = np.bincount(self.add_list_of, minlength=self.nlist).astype(np.int64)
+        self.list_offsets = np.zeros(self.nlist + 1, dtype=np.int64)
+        np.cumsum(sizes, out=self.list_offsets[1:])
+
+    def add(self, x, ids=None):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        n = x.shape[0]
+        if ids is None:
+            ids = np.arange(self.ntotal, self.ntotal + n, dtype=np.int64)
+        list_of = assign(x, self.centroids, self.metric)
+        self.add_ids = np.concatenate([self.add_ids, np.asarray(ids, dtype=np.int64)])
+        self.add_list_of = np.concatenate([self.add_list_of, list_of])
+        self.add_codes = np.concatenate([self.add_codes, sq8_encode(x, self.vmin, self.step)])
+        self._relayout()
+
+    def list_sizes(self):
+        return np.diff(self.list_offsets)
+
+    def search(self, q, k, nprobe, return_stats=False):
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        nq = q.shape[0]
+        D = np.empty((nq, k), dtype=np.float32)
+        I = np.empty((nq, k), dtype=np.int64)
+        nscanned = np.zeros(nq, dtype=np.int64)
+        _load().or_ivfsq8_search(
+            _ptr(q), ctypes.c_int64(nq), ctypes.c_int(self.d), ctypes.c_int(self.metric),
+            ctypes.c_int(self.nlist), _ptr(self.centroids), _ptr(self.vmin), _ptr(self.step),
+            _ptr(self.list_offsets), _ptr(self.codes), _ptr(self.ids), ctypes.c_int(k),
+            ctypes.c_int(nprobe), _ptr(D), _ptr(I), _ptr(nscanned))
+        if return_stats:
+            return D, I, nscanned
+        return D, I
+
+
 class OracleIVFFlat:
     """IVF index that stores the vectors themselves (Sec. 5.1), as plain numpy arrays.
     add(): assignment as in OracleIVFPQ, stable append; search(): probes, exact distances to

@@ -626,3 +626,54 @@ def test_norm_decomposition_form_agrees_with_the_definition(oracle):
     Db, Ib = ixi.search(qi, 6, 5, form=2)
     np.testing.assert_array_equal(Da, Db)
     np.testing.assert_array_equal(Ia, Ib)
+
+
+# ------------------------------------------------------------ scalar quantizer, IVF-SQ8
+
+def test_sq8_cells_codes_and_reconstruction(oracle):
+    # Sec. 4.1: a uniform quantizer per component; scale and offset decide what is reconstructed.
+    vmin = np.array([0.0, -1.0], dtype=np.float32)
+    step = np.array([1.0, 0.5], dtype=np.float32)              # cells [j, j + 1) and [-1 + j / 2, ...)
+    x = np.array([[0.0, -1.0], [0.999, -0.75], [1.0, -0.5], [255.5, 126.9], [256.0, 127.0],
+                  [-3.0, -9.0], [1e9, 1e9]], dtype=np.float32)
+    codes = oracle.sq8_encode(x, vmin, step)
+    assert codes.tolist() == [[0, 0], [0, 0], [1, 1], [255, 255], [255, 255], [0, 0], [255, 255]]
+    dec = oracle.sq8_decode(codes, vmin, step)
+    assert dec.tolist() == [[0.5, -0.75], [0.5, -0.75], [1.5, -0.25], [255.5, 126.75], [255.5, 126.75],
+                            [0.5, -0.75], [255.5, 126.75]]
+    # inside the range the reconstruction is the nearest cell middle: error at most step / 2,
+    # and re-encoding a reconstruction gives the same code (a fixed point)
+    rng = np.random.default_rng(51)
+    xr = rng.uniform(-4, 9, size=(2000, 6)).astype(np.float32)
+    lo, st = oracle.sq8_params(xr)
+    c = oracle.sq8_encode(xr, lo, st)
+    r = oracle.sq8_decode(c, lo, st)
+    assert (np.abs(r.astype(np.float64) - xr) <= st.astype(np.float64) * 0.5 * (1 + 1e-5) + 1e-6).all()
+    np.testing.assert_array_equal(oracle.sq8_encode(r, lo, st), c)
+    assert c.min() == 0 and c.max() == 255                       # the range is used from end to end
+
+
+def test_ivfsq8_is_ivfflat_over_the_reconstructions(oracle):
+    # The index only replaces every stored vector by its reconstruction.
+    cfg = S.config("C1", nb=2500, nq=25)
+    x, q = S.make_data(cfg)
+    cent = S.make_centroids(x, 16, cfg["seed"])
+    lo, st = oracle.sq8_params(x)
+    ix = oracle.OracleIVFSQ8(32, L2, cent, lo, st)
+    ix.add(x[:1000]); ix.add(x[1000:])
+    xr = oracle.sq8_decode(oracle.sq8_encode(x, lo, st), lo, st)
+    a = oracle.assign(x, cent)                                   # lists come from the ORIGINAL vectors
+    for nprobe in (3, 16):
+        D, I, nscanned = ix.search(q, 10, nprobe, return_stats=True)
+        po, _ = oracle.coarse_probe(q, cent, nprobe, L2)
+        full = np_pairwise(q, xr, L2).astype(np.float32)
+        for qi in range(q.shape[0]):
+            members = np.flatnonzero(np.isin(a, po[qi]))
+            assert nscanned[qi] == members.size
+            v = full[qi, members]
+            order = np.argsort(v, kind="stable")[:10]
+            np.testing.assert_array_equal(I[qi], members[order])
+            np.testing.assert_allclose(D[qi], v[order], rtol=1e-6)
+    # with 256 cells per component the quantization error is small: most exact neighbours survive
+    _, It = oracle.flat_search(x, q, 10, L2)
+    assert oracle.recall(ix.search(q, 10, 16)[1], It) > 0.9
