@@ -59,7 +59,7 @@ def main():
                     help="tables (default, the headline form): one look-up table per (query, list) on the "
                          "residual; norms: |q|^2 + |x'|^2 - 2<q,x'> with the norm stored next to every code "
                          "(4 more bytes per vector, one table per query)")
-    ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat"],
+    ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat", "ivfsq8"],
                     help="ivfflat: the same workload's vectors and centroids in an IVF-Flat index "
                          "(secondary line; the default ivfpq is the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -113,7 +113,7 @@ def main():
         return bench_flat(args, cfg, x, q, xd, qd)
 
     cent, cb = S.make_index_params_device(cfg, xd) if big else S.make_index_params(cfg, x)
-    if args.index == "ivfflat":
+    if args.index in ("ivfflat", "ivfsq8"):
         return bench_ivfflat(args, cfg, x, q, xd, qd, cent)
     train = None
     if args.train > 0:
@@ -340,7 +340,14 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
     import oracle
     import paper_2401_08281_amd as vs
     nq, k, metric, d, nb, nprobe = cfg["nq"], cfg["k"], cfg["metric"], cfg["d"], cfg["nb"], cfg["nprobe"]
-    ix = vs.IVFFlat(d, metric, torch.from_numpy(cent).cuda())
+    sq8 = args.index == "ivfsq8"
+    if sq8:   # ranges of the scalar quantizer from the first 1M vectors (min / max per component)
+        head = xd[: min(nb, 1_000_000)]
+        vmin = head.min(dim=0).values.contiguous()
+        step = ((head.max(dim=0).values - vmin) / 256.0).clamp_min(1e-30).contiguous()
+        ix = vs.IVFSQ8(d, metric, torch.from_numpy(cent).cuda(), vmin, step)
+    else:
+        ix = vs.IVFFlat(d, metric, torch.from_numpy(cent).cuda())
     t0 = time.time()
     for s0 in range(0, nb, 10_000_000):
         ix.add(xd[s0:s0 + 10_000_000])
@@ -367,7 +374,7 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
     probes, _ = ixq.coarse(qd, nprobe)
     ixq.close()
     scanned = int(sizes[probes.long()].sum().item())
-    algo = scanned * d * 4
+    algo = scanned * d * (1 if sq8 else 4)
     achieved = algo / (scan_ms * 1e-3) / 1e9
     nrec = min(nq, 1000)
     Dg, Ig = vs.vs_flat_search(xd, qd[:nrec].contiguous(), k, metric)
@@ -375,23 +382,26 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
     hit_k = np.mean([len(set(I_h[a].tolist()) & set(Ig_h[a].tolist())) / float(k) for a in range(nrec)])
     cpu = None
     if not args.no_cpu_baseline and x is not None:
-        orc = oracle.OracleIVFFlat(d, metric, cent)
+        orc = oracle.OracleIVFSQ8(d, metric, cent, vmin.cpu().numpy(), step.cpu().numpy()) if sq8 \
+            else oracle.OracleIVFFlat(d, metric, cent)
         orc.add(x)
         n = min(nq, 500)
         t0 = time.perf_counter(); orc.search(q[:n], k, nprobe); dt = time.perf_counter() - t0
         cpu = {"value": n / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": "first %d of %d queries, %.1f s" % (n, nq, dt)}
     out = {
-        "metric": "IVF-Flat queries/sec at fixed nprobe", "value": nq / (ms_per_step * 1e-3),
+        "metric": "%s queries/sec at fixed nprobe" % ("IVF-SQ8" if sq8 else "IVF-Flat"),
+        "value": nq / (ms_per_step * 1e-3),
         "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s vectors in IVF%d,Flat %s, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
-            args.workload, cfg["nlist"], "IP" if metric else "L2", nb, d, nq, k, nprobe),
+        "config": {"workload": "%s vectors in IVF%d,%s %s, nb=%d d=%d nq=%d k=%d nprobe=%d" % (
+            args.workload, cfg["nlist"], "SQ8" if sq8 else "Flat", "IP" if metric else "L2", nb, d, nq, k,
+            nprobe),
             "recall_k_at_k": round(float(hit_k), 4), "recall_queries": int(nrec),
             "scanned_vectors_per_query": scanned / nq, "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v[0] / args.steps, 4) for s, v in prof.items() if v[1]}},
-        "roofline": {"bound": "hbm", "kernel": "ivfflat_scan_tiled_kernel" if d % 32 == 0 else "ivfflat_scan_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("ivfsq8_scan" if sq8 else "ivfflat_scan") + ("_tiled_kernel" if d % 32 == 0 else "_kernel"), "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "algorithmic_bytes_per_launch": algo, "kernel_ms": scan_ms},
         "cpu_baseline": cpu,

@@ -246,6 +246,33 @@ VS_API int vs_ivfflat_get_list_sizes(const vs_ivfflat* ix, int64_t* sizes, void*
 VS_API int vs_ivfflat_get_storage(const vs_ivfflat* ix, int64_t* ids, int32_t* list_of, float* rows,
                            void* hip_stream);
 
+/* ---- IVF-SQ8 -----------------------------------------------------------------
+ * The inverted file of Sec. 5.1 with every vector stored as an 8-bit scalar-quantizer code
+ * (Sec. 4.1 "Scalar quantizers"; App. A.3 "GPU Faiss" lists the index): d bytes per vector.
+ * Component t is expected in [vmin[t], vmin[t] + 256 step[t]); the code is the number of the
+ * cell of width step[t] that holds it (components outside go to the first / last cell):
+ *     u = (x_t - vmin[t]) / step[t] in fp32;  code = 0 if u < 0, 255 if u >= 256, else trunc(u)
+ * and the reconstruction is the middle of the cell, fma(code + 0.5, step[t], vmin[t]).  The
+ * vectors themselves are encoded (no residual); lists come from the original vectors.  The
+ * scan evaluates the fp32 distance chain of vs_flat_search on the reconstructions.
+ *   vmin, step: DEVICE [d] fp32, copied; every step must be positive.
+ * Otherwise as the vs_ivfflat_* calls of the same name. */
+typedef struct vs_ivfsq8 vs_ivfsq8;
+VS_API int vs_ivfsq8_create(vs_ivfsq8** out, int32_t d, int32_t metric, int32_t nlist,
+                     const float* centroids, const float* vmin, const float* step,
+                     void* hip_stream);
+VS_API void vs_ivfsq8_destroy(vs_ivfsq8* ix);
+VS_API int64_t vs_ivfsq8_ntotal(const vs_ivfsq8* ix);
+VS_API int vs_ivfsq8_add(vs_ivfsq8* ix, const float* x, int64_t n, const int64_t* ids,
+                  void* hip_stream);
+VS_API int vs_ivfsq8_search(const vs_ivfsq8* ix, const float* q, int64_t nq, int32_t k,
+                     int32_t nprobe, float* out_dist, int64_t* out_ids, void* hip_stream);
+VS_API int vs_ivfsq8_get_list_sizes(const vs_ivfsq8* ix, int64_t* sizes, void* hip_stream);
+/* storage order: ids [ntotal], list of every entry [ntotal], codes [ntotal, d] bytes
+ * (DEVICE, each may be NULL) */
+VS_API int vs_ivfsq8_get_storage(const vs_ivfsq8* ix, int64_t* ids, int32_t* list_of,
+                          uint8_t* codes, void* hip_stream);
+
 /* ---- stage timing (used by benchmarks) ----------------------------------- */
 
 enum {

@@ -56,6 +56,20 @@ def lib():
     L.vs_ivfflat_get_list_sizes.argtypes = [vp, vp, vp]
     L.vs_ivfflat_get_storage.restype = ctypes.c_int
     L.vs_ivfflat_get_storage.argtypes = [vp, vp, vp, vp, vp]
+    L.vs_ivfsq8_create.restype = ctypes.c_int
+    L.vs_ivfsq8_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, vp, vp, vp, vp]
+    L.vs_ivfsq8_destroy.restype = None
+    L.vs_ivfsq8_destroy.argtypes = [vp]
+    L.vs_ivfsq8_ntotal.restype = i64
+    L.vs_ivfsq8_ntotal.argtypes = [vp]
+    L.vs_ivfsq8_add.restype = ctypes.c_int
+    L.vs_ivfsq8_add.argtypes = [vp, vp, i64, vp, vp]
+    L.vs_ivfsq8_search.restype = ctypes.c_int
+    L.vs_ivfsq8_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    L.vs_ivfsq8_get_list_sizes.restype = ctypes.c_int
+    L.vs_ivfsq8_get_list_sizes.argtypes = [vp, vp, vp]
+    L.vs_ivfsq8_get_storage.restype = ctypes.c_int
+    L.vs_ivfsq8_get_storage.argtypes = [vp, vp, vp, vp, vp]
     L.vs_kmeans.restype = ctypes.c_int
     L.vs_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
     L.vs_ivfpq_train.restype = ctypes.c_int
@@ -375,6 +389,71 @@ def vs_ivfflat_get_storage(h, d, device):
     rows = torch.empty((n, d), dtype=torch.float32, device=device)
     _check(lib().vs_ivfflat_get_storage(h, _p(ids), _p(list_of), _p(rows), _stream()))
     return ids, list_of, rows
+
+
+class IVFSQ8:
+    """Owner of one vs_ivfsq8 handle (thin convenience over the C calls)."""
+
+    def __init__(self, d, metric, centroids, vmin, step):
+        self.d, self.metric = int(d), int(metric)
+        self.nlist = int(centroids.shape[0])
+        self.device = centroids.device
+        centroids = _dev(centroids, torch.float32, "centroids")
+        vmin = _dev(vmin, torch.float32, "vmin")
+        step = _dev(step, torch.float32, "step")
+        if vmin.numel() != self.d or step.numel() != self.d or centroids.numel() != self.nlist * self.d:
+            raise ValueError("centroids must be [nlist, d], vmin and step [d]")
+        h = ctypes.c_void_p(0)
+        _check(lib().vs_ivfsq8_create(ctypes.byref(h), self.d, self.metric, self.nlist, _p(centroids),
+                                      _p(vmin), _p(step), _stream()))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None) is not None:
+            lib().vs_ivfsq8_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def ntotal(self):
+        return int(lib().vs_ivfsq8_ntotal(self.h))
+
+    def add(self, x, ids=None):
+        x = _dev(x, torch.float32, "x")
+        ids = _dev(ids, torch.int64, "ids")
+        if ids is not None and ids.numel() != x.shape[0]:
+            raise ValueError("ids must hold one id per row of x")
+        _check(lib().vs_ivfsq8_add(self.h, _p(x), x.shape[0], _p(ids), _stream()))
+
+    def search(self, q, k, nprobe, out_dist=None, out_ids=None):
+        q = _dev(q, torch.float32, "q")
+        nq = q.shape[0]
+        if out_dist is None:
+            out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+        if out_ids is None:
+            out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+        _dev(out_dist, torch.float32, "out_dist")
+        _dev(out_ids, torch.int64, "out_ids")
+        _check(lib().vs_ivfsq8_search(self.h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
+        return out_dist, out_ids
+
+    def list_sizes(self):
+        sizes = torch.empty(self.nlist, dtype=torch.int64, device=self.device)
+        _check(lib().vs_ivfsq8_get_list_sizes(self.h, _p(sizes), _stream()))
+        return sizes
+
+    def storage(self):
+        n = self.ntotal
+        ids = torch.empty(n, dtype=torch.int64, device=self.device)
+        list_of = torch.empty(n, dtype=torch.int32, device=self.device)
+        codes = torch.empty((n, self.d), dtype=torch.uint8, device=self.device)
+        _check(lib().vs_ivfsq8_get_storage(self.h, _p(ids), _p(list_of), _p(codes), _stream()))
+        return ids, list_of, codes
 
 
 class IVFFlat:

@@ -237,6 +237,13 @@ struct vs_ivfflat {
   vs_ivfpq core;
 };
 
+// IVF-SQ8 likewise; core.codes holds d bytes per vector (core.g: M = d, nbits = 8)
+struct vs_ivfsq8 {
+  vs_ivfpq core;
+  float* vmin = nullptr;   // [d] first cell's lower end per component
+  float* step = nullptr;   // [d] cell width per component
+};
+
 extern "C" {
 
 const char* vs_last_error(void) { return g_err; }
@@ -931,6 +938,150 @@ int vs_ivfflat_get_storage(const vs_ivfflat* fx, int64_t* ids, int32_t* list_of,
   if (ids) HIP_TRY(hipMemcpyAsync(ids, ix->ids, (size_t)ix->ntotal * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
   if (list_of) launch_list_of_storage(ix->list_off, ix->g.nlist, ix->ntotal, list_of, st);
   if (rows) HIP_TRY(hipMemcpyAsync(rows, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+// ---- IVF-SQ8 ---------------------------------------------------------------------------
+
+int vs_ivfsq8_create(vs_ivfsq8** out, int32_t d, int32_t metric, int32_t nlist,
+                     const float* centroids, const float* vmin, const float* step,
+                     void* hip_stream) {
+  if (!out) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_create: out is null");
+  *out = nullptr;
+  if (!centroids || !vmin || !step) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_create: null pointer");
+  if (d < 1 || nlist < 1) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_create: d, nlist must be >= 1");
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_create: unknown metric %d", metric);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  vs_ivfsq8* sx = new (std::nothrow) vs_ivfsq8();
+  if (!sx) return fail(VS_ERR_OOM, "vs_ivfsq8_create: host allocation failed");
+  vs_ivfpq* ix = &sx->core;
+  ix->g.d = d; ix->g.metric = metric; ix->g.nlist = nlist; ix->g.M = d; ix->g.nbits = 8;
+  ix->g.K = 0; ix->g.dsub = 0; ix->g.code_size = d;
+  ix->h_off.assign((size_t)nlist + 1, 0);
+  auto cleanup = [&](int rc) { vs_ivfsq8_destroy(sx); return rc; };
+#define TRY_C(expr)                                                                         \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return cleanup(fail(e_ == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "%s: %s", \
+                          #expr, hipGetErrorString(e_)));                                   \
+  } while (0)
+  TRY_C(hipGetDevice(&ix->device));
+  const size_t cb = (size_t)nlist * d * sizeof(float), pb = (size_t)d * sizeof(float);
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->centroids), cb));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->list_off), ((size_t)nlist + 1) * sizeof(int64_t)));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&sx->vmin), pb));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&sx->step), pb));
+  TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemcpyAsync(sx->vmin, vmin, pb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemcpyAsync(sx->step, step, pb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));
+  if (mfma_knn_supported(d, 1)) {
+    TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
+    ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
+    launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
+                ix->c_planes.info, st);
+    ix->has_planes = true;
+  }
+  TRY_C(hipStreamSynchronize(st));
+#undef TRY_C
+  *out = sx;
+  return VS_OK;
+}
+
+void vs_ivfsq8_destroy(vs_ivfsq8* sx) {
+  if (!sx) return;
+  ivf_free_device_memory(&sx->core);
+  if (sx->vmin) (void)hipFree(sx->vmin);
+  if (sx->step) (void)hipFree(sx->step);
+  delete sx;
+}
+
+int64_t vs_ivfsq8_ntotal(const vs_ivfsq8* sx) { return sx ? sx->core.ntotal : -1; }
+
+int vs_ivfsq8_add(vs_ivfsq8* sx, const float* x, int64_t n, const int64_t* ids, void* hip_stream) {
+  if (!sx) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_add: index is null");
+  if (n < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_add: n < 0");
+  if (n == 0) return VS_OK;
+  if (!x) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_add: x is null");
+  vs_ivfpq* ix = &sx->core;
+  if (ix->ntotal + n >= (1ll << 32)) return fail(VS_ERR_UNSUPPORTED, "vs_ivfsq8_add: more than 2^32 - 1 stored vectors");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const IvfpqDims& g = ix->g;
+  Placement pl;
+  if (int rc = ivf_assign_and_place(ix, x, n, (size_t)n * g.d, &pl, st, "vs_ivfsq8_add")) return rc;
+  uint8_t* tmp_codes = reinterpret_cast<uint8_t*>(pl.extra);
+  launch_sq8_encode(x, n, g.d, sx->vmin, sx->step, tmp_codes, st);
+  const int64_t total = ix->ntotal + n;
+  uint8_t* codes = nullptr;
+  int64_t* new_ids = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&codes), (size_t)total * g.code_size));
+  if (hipMalloc(reinterpret_cast<void**>(&new_ids), (size_t)total * sizeof(int64_t)) != hipSuccess) {
+    (void)hipFree(codes);
+    return fail(VS_ERR_OOM, "vs_ivfsq8_add: id storage allocation failed");
+  }
+  launch_relayout(g, ix->codes, ix->ids, nullptr, ix->ntotal, ix->list_off, pl.new_off, tmp_codes,
+                  ids, ix->ntotal, nullptr, pl.dest, n, codes, new_ids, nullptr, st);
+  return ivf_commit_storage(ix, codes, new_ids, nullptr, total, &pl, st, "vs_ivfsq8_add");
+}
+
+int vs_ivfsq8_search(const vs_ivfsq8* sx, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                     float* out_dist, int64_t* out_ids, void* hip_stream) {
+  if (!sx) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_search: index is null");
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_search: nq < 0");
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_search: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_search: nprobe = %d outside [1, %d]", nprobe, VS_MAX_K);
+  if (nq == 0) return VS_OK;
+  if (!q || !out_dist || !out_ids) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_search: null pointer");
+  const vs_ivfpq* ix = &sx->core;
+  const IvfpqDims& g = ix->g;
+  if (ivfsq8_scan_lds_bytes(g.d, k) > 160 * 1024)
+    return fail(VS_ERR_UNSUPPORTED, "vs_ivfsq8_search: d = %d with k = %d exceeds the LDS", g.d, k);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int npr = std::min<int>(nprobe, g.nlist);
+  int nsplit = (int)std::min<int64_t>(npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
+  const int ppb = (npr + nsplit - 1) / nsplit;
+  nsplit = (npr + ppb - 1) / ppb;
+  const KnnPlan plan = knn_plan(nq, g.nlist, g.d, npr, ix->has_planes);
+  Carver cv;
+  const size_t o_knn = cv.take(plan.bytes);
+  const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
+  const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  if (int rc = ix->scratch.reserve(cv.off)) return rc;
+  char* base = static_cast<char*>(ix->scratch.p);
+  int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
+  u64* partial = reinterpret_cast<u64*>(base + o_part);
+  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st);
+  {
+    StageTimer t(VS_STAGE_SCAN, st);
+    launch_ivfsq8_scan(g.d, g.metric, q, nq, sx->vmin, sx->step, probes, npr, nsplit, ix->list_off,
+                       ix->codes, k, partial, ix->ids, out_dist, out_ids, st);
+  }
+  if (nsplit > 1) {
+    StageTimer t(VS_STAGE_MERGE, st);
+    launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfsq8_get_list_sizes(const vs_ivfsq8* sx, int64_t* sizes, void* hip_stream) {
+  if (!sx || !sizes) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_get_list_sizes: null pointer");
+  launch_list_sizes(sx->core.list_off, sx->core.g.nlist, sizes, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_ivfsq8_get_storage(const vs_ivfsq8* sx, int64_t* ids, int32_t* list_of, uint8_t* codes,
+                          void* hip_stream) {
+  if (!sx) return fail(VS_ERR_INVALID_ARG, "vs_ivfsq8_get_storage: index is null");
+  const vs_ivfpq* ix = &sx->core;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (ix->ntotal == 0) return VS_OK;
+  if (ids) HIP_TRY(hipMemcpyAsync(ids, ix->ids, (size_t)ix->ntotal * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+  if (list_of) launch_list_of_storage(ix->list_off, ix->g.nlist, ix->ntotal, list_of, st);
+  if (codes) HIP_TRY(hipMemcpyAsync(codes, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice, st));
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }

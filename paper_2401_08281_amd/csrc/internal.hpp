@@ -121,6 +121,15 @@ void launch_ivfflat_scan(int d, int metric, const float* q, int64_t nq, const in
                          u64* partial, const int64_t* ids, float* out_dist, int64_t* out_ids,
                          hipStream_t st);
 
+// IVF-SQ8 (same file): 8-bit scalar-quantizer codes [n, d]; scan = IVF-Flat over reconstructions
+void launch_sq8_encode(const float* x, int64_t n, int d, const float* vmin, const float* step,
+                       uint8_t* codes, hipStream_t st);
+size_t ivfsq8_scan_lds_bytes(int d, int k);
+void launch_ivfsq8_scan(int d, int metric, const float* q, int64_t nq, const float* vmin,
+                        const float* step, const int32_t* probes, int nprobe, int nsplit,
+                        const int64_t* list_off, const uint8_t* codes, int k, u64* partial,
+                        const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
+
 // ---- kernels_train.hip ---------------------------------------------------------
 // centroids[j] <- mean of the rows x[order[off[j] .. off[j + 1])] (float64 sum in that order);
 // a centroid with an empty range keeps its value

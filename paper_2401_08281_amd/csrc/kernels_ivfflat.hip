@@ -189,6 +189,173 @@ __global__ __launch_bounds__(256) void ivfflat_scan_tiled_kernel(
   block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
 }
 
+// ---------------------------------------------------------------------------
+// IVF-SQ8: the entries of the lists are 8-bit scalar-quantizer codes of the vectors
+// (Sec. 4.1 "Scalar quantizers"; App. A.3 lists the index among the GPU ones).  Component t
+// of a vector falls into one of 256 cells of width step[t] starting at vmin[t]; its code is
+// the cell number, its reconstruction the middle of the cell: fma(code + 0.5, step, vmin).
+// The scan reconstructs on the fly and continues the canon chain on the reconstruction.
+// ---------------------------------------------------------------------------
+__global__ void sq8_encode_kernel(const float* __restrict__ x, int64_t n, int d,
+                                  const float* __restrict__ vmin, const float* __restrict__ step,
+                                  uint8_t* __restrict__ codes) {
+  const int64_t total = n * d, stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += stride) {
+    const int t = (int)(e % d);
+    const float u = (x[e] - vmin[t]) / step[t];
+    codes[e] = u < 0.f ? (uint8_t)0 : (u >= 256.f ? (uint8_t)255 : (uint8_t)(int)u);
+  }
+}
+
+template <int METRIC>
+__device__ __forceinline__ float sq8_step(float acc, float qt, float code, float st, float lo) {
+  const float xt = __builtin_fmaf(code + 0.5f, st, lo);
+  if (METRIC == 0) { const float diff = qt - xt; return __builtin_fmaf(diff, diff, acc); }
+  return __builtin_fmaf(qt, xt, acc);
+}
+
+// any d: one stored code per lane, read straight from memory
+template <int R, int METRIC>
+__global__ __launch_bounds__(256) void ivfsq8_scan_kernel(
+    const float* __restrict__ q, int d, const float* __restrict__ vmin, const float* __restrict__ step,
+    const int32_t* __restrict__ probes, int nprobe, int ppb, int nsplit,
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int k, int tot,
+    KeySink sink) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);
+  u64* bound = slots + 4 * tot;
+  float* qs = reinterpret_cast<float*>(bound + 2);              // q | vmin | step, d floats each
+  const int64_t qi = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int wave = threadIdx.x >> 6;
+  const int p_end = min(nprobe, split * ppb + ppb);
+  for (int t = threadIdx.x; t < d; t += 256) { qs[t] = q[qi * d + t]; qs[d + t] = vmin[t]; qs[2 * d + t] = step[t]; }
+  if (threadIdx.x == 0) *bound = KEY_EMPTY;
+  WaveSelect<R> ws;
+  ws.init(slots + wave * tot, tot, k, bound);
+  __syncthreads();
+  for (int p = split * ppb; p < p_end; ++p) {
+    const int l = probes[qi * nprobe + p];
+    if (l < 0) continue;
+    const int64_t begin = list_off[l], end = list_off[l + 1];
+    for (int64_t i0 = begin; i0 < end; i0 += 256) {
+      const int64_t i = i0 + threadIdx.x;
+      const bool valid = i < end;
+      float acc = 0.f;
+      if (valid) {
+        const uint8_t* __restrict__ c = codes + i * d;
+        for (int t = 0; t < d; ++t) acc = sq8_step<METRIC>(acc, qs[t], (float)c[t], qs[2 * d + t], qs[d + t]);
+      }
+      ws.push(valid, make_key(acc, (u32)i, METRIC), true);
+    }
+  }
+  ws.finish();
+  __syncthreads();
+  block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
+}
+
+// d a multiple of DC (64 or 32): tiles of 256 codes x DC components staged through LDS with
+// DC / 16 lanes per code (runs of DC consecutive bytes per request), rows padded by 16 bytes
+// (conflict-free 16-byte reads); structure as ivfflat_scan_tiled_kernel.
+template <int R, int METRIC, int DC>
+__global__ __launch_bounds__(256) void ivfsq8_scan_tiled_kernel(
+    const float* __restrict__ q, int d, const float* __restrict__ vmin, const float* __restrict__ step,
+    const int32_t* __restrict__ probes, int nprobe, int ppb, int nsplit,
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, int k, int tot,
+    KeySink sink) {
+  constexpr int LDB = DC + 16, TR = 256, LPR = DC / 16, NPASS = TR * LPR / 256;   // lanes per row, passes
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);
+  u64* bound = slots + 4 * tot;
+  float* qs = reinterpret_cast<float*>(bound + 2);              // q | vmin | step, d floats each
+  unsigned char* tile = reinterpret_cast<unsigned char*>(qs + 3 * d);   // 2 x TR x LDB bytes
+  const int64_t qi = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int p_end = min(nprobe, split * ppb + ppb);
+  const int r_ld = tid / LPR, c_ld = tid % LPR;
+
+  for (int t = tid; t < d; t += 256) { qs[t] = q[qi * d + t]; qs[d + t] = vmin[t]; qs[2 * d + t] = step[t]; }
+  if (tid == 0) *bound = KEY_EMPTY;
+  WaveSelect<R> ws;
+  ws.init(slots + wave * tot, tot, k, bound);
+
+  struct Pos { int p; int64_t i0, end; int c0; bool ok; };
+  auto first_row_from = [&](int p) {
+    Pos s{p, 0, 0, 0, false};
+    for (; s.p < p_end; ++s.p) {
+      const int l = probes[qi * nprobe + s.p];
+      if (l < 0) continue;
+      s.i0 = list_off[l]; s.end = list_off[l + 1];
+      if (s.i0 < s.end) { s.ok = true; break; }
+    }
+    return s;
+  };
+  auto next_of = [&](const Pos& c) {
+    Pos n = c;
+    n.c0 += DC;
+    if (n.c0 < d) return n;
+    n.c0 = 0;
+    n.i0 += TR;
+    if (n.i0 < n.end) return n;
+    return first_row_from(c.p + 1);
+  };
+  u32x4 stg[NPASS];
+#define FETCH(S)                                                                                  \
+  do {                                                                                            \
+    _Pragma("unroll") for (int j_ = 0; j_ < NPASS; ++j_) {                                        \
+      const int64_t row_ = min((S).i0 + j_ * (256 / LPR) + r_ld, (S).end - 1);                    \
+      stg[j_] = *reinterpret_cast<const u32x4*>(codes + row_ * d + (S).c0 + c_ld * 16);           \
+    }                                                                                             \
+  } while (0)
+#define STASH(BUF)                                                                                \
+  do {                                                                                            \
+    _Pragma("unroll") for (int j_ = 0; j_ < NPASS; ++j_)                                          \
+      *reinterpret_cast<u32x4*>(tile + ((BUF) * TR + j_ * (256 / LPR) + r_ld) * LDB + c_ld * 16) = stg[j_]; \
+  } while (0)
+
+  Pos cur = first_row_from(split * ppb);
+  if (cur.ok) { FETCH(cur); STASH(0); }
+  __syncthreads();
+  int buf = 0;
+  float acc = 0.f;
+  while (cur.ok) {
+    const Pos nxt = next_of(cur);
+    if (nxt.ok) FETCH(nxt);
+    const unsigned char* __restrict__ tr = tile + (buf * TR + tid) * LDB;
+    const float* __restrict__ qc = qs + cur.c0;
+#pragma unroll
+    for (int c = 0; c < DC / 16; ++c) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(tr + c * 16);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 qv = *reinterpret_cast<const float4*>(qc + c * 16 + g * 4);
+        const float4 lo = *reinterpret_cast<const float4*>(qc + d + c * 16 + g * 4);
+        const float4 st = *reinterpret_cast<const float4*>(qc + 2 * d + c * 16 + g * 4);
+        const u32 word = w[g];
+        acc = sq8_step<METRIC>(acc, qv.x, (float)(word & 0xFFu), st.x, lo.x);
+        acc = sq8_step<METRIC>(acc, qv.y, (float)((word >> 8) & 0xFFu), st.y, lo.y);
+        acc = sq8_step<METRIC>(acc, qv.z, (float)((word >> 16) & 0xFFu), st.z, lo.z);
+        acc = sq8_step<METRIC>(acc, qv.w, (float)(word >> 24), st.w, lo.w);
+      }
+    }
+    if (cur.c0 + DC >= d) {
+      const int64_t i = cur.i0 + tid;
+      ws.push(i < cur.end, make_key(acc, (u32)i, METRIC), true);
+      acc = 0.f;
+    }
+    if (nxt.ok) STASH(buf ^ 1);
+    block_sync_lds();
+    cur = nxt;
+    buf ^= 1;
+  }
+#undef FETCH
+#undef STASH
+  ws.finish();
+  block_sync_lds();
+  block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
+}
+
 }  // namespace
 
 void launch_ivfflat_relayout(int d, int nlist, const float* old_rows, const int64_t* old_ids,
@@ -235,6 +402,54 @@ void launch_ivfflat_scan(int d, int metric, const float* q, int64_t nq, const in
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);         \
     hipLaunchKernelGGL(kern, grid, block, shmem, st, q, d, probes, nprobe, ppb, nsplit, list_off, \
                        rows, k, tot, sink);                                                      \
+  } while (0)
+  switch (select_regs_for_slots(tot)) {
+    case 2: if (metric == 0) GO(2, 0); else GO(2, 1); break;
+    case 4: if (metric == 0) GO(4, 0); else GO(4, 1); break;
+    default: if (metric == 0) GO(0, 0); else GO(0, 1); break;
+  }
+#undef GO
+}
+
+void launch_sq8_encode(const float* x, int64_t n, int d, const float* vmin, const float* step,
+                       uint8_t* codes, hipStream_t st) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(sq8_encode_kernel, dim3((unsigned)std::min<int64_t>(1 << 22, (n * d + 255) / 256)),
+                     dim3(256), 0, st, x, n, d, vmin, step, codes);
+}
+
+static int sq8_chunk(int d) { return d % 64 == 0 ? 64 : (d % 32 == 0 ? 32 : 0); }
+
+size_t ivfsq8_scan_lds_bytes(int d, int k) {
+  const size_t base = (size_t)(4 * select_slots_for_k(k) + 2) * sizeof(u64) + (size_t)3 * d * sizeof(float);
+  const int dc = sq8_chunk(d);
+  return dc ? base + (size_t)2 * 256 * (dc + 16) : base;
+}
+
+void launch_ivfsq8_scan(int d, int metric, const float* q, int64_t nq, const float* vmin,
+                        const float* step, const int32_t* probes, int nprobe, int nsplit,
+                        const int64_t* list_off, const uint8_t* codes, int k, u64* partial,
+                        const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
+  if (nq <= 0) return;
+  KeySink sink;
+  sink.metric = metric;
+  sink.idx32 = nullptr;
+  if (nsplit == 1) { sink.keys = nullptr; sink.val = out_dist; sink.id64 = out_ids; sink.idmap = ids; }
+  else             { sink.keys = partial; sink.val = nullptr; sink.id64 = nullptr; sink.idmap = nullptr; }
+  const int ppb = (nprobe + nsplit - 1) / nsplit;
+  const int tot = select_slots_for_k(k);
+  const size_t shmem = ivfsq8_scan_lds_bytes(d, k);
+  const int dc = sq8_chunk(d);
+  const dim3 grid((unsigned)(nq * nsplit)), block(256);
+#define GO(RR, MET)                                                                              \
+  do {                                                                                           \
+    auto kern = dc == 64 ? &ivfsq8_scan_tiled_kernel<RR, MET, 64>                                \
+                         : (dc == 32 ? &ivfsq8_scan_tiled_kernel<RR, MET, 32> : &ivfsq8_scan_kernel<RR, MET>); \
+    if (shmem > 48 * 1024)                                                                       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);         \
+    hipLaunchKernelGGL(kern, grid, block, shmem, st, q, d, vmin, step, probes, nprobe, ppb, nsplit, \
+                       list_off, codes, k, tot, sink);                                           \
   } while (0)
   switch (select_regs_for_slots(tot)) {
     case 2: if (metric == 0) GO(2, 0); else GO(2, 1); break;

@@ -92,6 +92,16 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_ivfflat_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
     assert L.vs_ivfflat_ntotal(nul) == -1
     L.vs_ivfflat_destroy(nul)                                                             # allowed
+    hs = ctypes.c_void_p(0)
+    refs = ctypes.byref(hs)
+    assert L.vs_ivfsq8_create(refs, 0, 0, 16, one, one, one, nul) == INVALID              # d < 1
+    assert L.vs_ivfsq8_create(refs, 32, 0, 16, one, nul, one, nul) == INVALID             # null vmin
+    assert L.vs_ivfsq8_create(refs, 32, 9, 16, one, one, one, nul) == INVALID             # metric
+    assert hs.value is None
+    assert L.vs_ivfsq8_add(nul, one, 5, nul, nul) == INVALID
+    assert L.vs_ivfsq8_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
+    assert L.vs_ivfsq8_ntotal(nul) == -1
+    L.vs_ivfsq8_destroy(nul)
     h = ctypes.c_void_p(0)
     ref = ctypes.byref(h)
     assert L.vs_ivfpq_create(ref, 32, 0, 16, 5, 8, one, one, nul) == INVALID         # d % M

@@ -550,6 +550,43 @@ def test_ivfflat_with_all_lists_probed_equals_flat_search_bits(vs, oracle):
     ix.close()
 
 
+# ------------------------------------------------- IVF-SQ8
+
+IVFSQ8_CASES = {
+    "c1": (S.config("C1"), [(10, 4), (10, 16), (300, 2)]),                          # d = 32: 32-wide tiles
+    "c3_small": (S.config("C3", nb=60_000, nq=100, ncomp=100, nlist=256), [(10, 16), (100, 64)]),  # d = 128: 64-wide
+    "c4_small_ip": (S.config("C4", nb=30_000, nq=64, ncomp=50, nlist=128, metric=1), [(10, 8)]),   # d = 96
+    "odd_d30": (S.config("C1", nb=3_001, nq=33, d=30, nlist=7), [(10, 3), (500, 7)]),              # untiled kernel
+}
+
+
+@pytest.mark.parametrize("name", list(IVFSQ8_CASES))
+def test_ivfsq8_matches_oracle(vs, oracle, name):
+    cfg, searches = IVFSQ8_CASES[name]
+    say("ivfsq8 %s nb=%d d=%d nlist=%d metric=%d" % (name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["metric"]))
+    x, q = S.make_data(cfg)
+    cent = S.make_centroids(x, cfg["nlist"], cfg["seed"])
+    vmin, step = oracle.sq8_params(x[: cfg["nb"] // 2])             # trained on half: the rest may fall outside
+    ix = vs.IVFSQ8(cfg["d"], cfg["metric"], dev(cent), dev(vmin), dev(step))
+    orc = oracle.OracleIVFSQ8(cfg["d"], cfg["metric"], cent, vmin, step)
+    cut = cfg["nb"] // 3
+    ix.add(dev(x[:cut])); ix.add(dev(x[cut:]))
+    orc.add(x[:cut]); orc.add(x[cut:])
+    sid, slist, scodes = [host(t) for t in ix.storage()]
+    np.testing.assert_array_equal(host(ix.list_sizes()), orc.list_sizes())
+    np.testing.assert_array_equal(sid, orc.ids)
+    np.testing.assert_array_equal(scodes, orc.codes)                   # codes bit for bit
+    xr = oracle.sq8_decode(orc.codes, vmin, step)
+    xn = np.sqrt((xr.astype(np.float64) ** 2).sum(1).max())
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        D, I = ix.search(dev(q), k, nprobe)
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        same = check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        assert same >= 0.97, same
+    ix.close()
+
+
 def test_ivfflat_storage_beyond_four_billion_elements(vs):
     """72M x 96 floats added in three pieces: the last re-layout moves 4.6e9 elements, more
     than one launch can hold as work-items.  Every list probed must then equal flat search
