@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void ivfflat_scan_tiled_kernel(
 // (Sec. 4.1 "Scalar quantizers"; App. A.3 lists the index among the GPU ones).  Component t
 // of a vector falls into one of 256 cells of width step[t] starting at vmin[t]; its code is
 // the cell number, its reconstruction the middle of the cell: fma(code + 0.5, step, vmin).
-// The scan reconstructs on the fly and continues the canon chain on the reconstruction.
+// The scan evaluates the distance to the reconstruction from the code bytes directly.
 // ---------------------------------------------------------------------------
 __global__ void sq8_encode_kernel(const float* __restrict__ x, int64_t n, int d,
                                   const float* __restrict__ vmin, const float* __restrict__ step,
@@ -207,11 +207,37 @@ __global__ void sq8_encode_kernel(const float* __restrict__ x, int64_t n, int d,
   }
 }
 
+// Per-query terms that fold the reconstruction x'_t = vmin_t + (code + 0.5) step_t into the
+// distance chain (same value up to fp32 rounding, 3 resp. 2 vector instructions per component
+// instead of 5):  L2: q_t - x'_t = a_t - code * step_t with a_t = q_t - (vmin_t + step_t / 2);
+// IP: q_t x'_t = q_t (vmin_t + step_t / 2) + code * b_t with b_t = q_t step_t, the first terms
+// summed once per query.  qs: [0, d) a_t or b_t, [d, 2d) step_t (L2 only).
 template <int METRIC>
-__device__ __forceinline__ float sq8_step(float acc, float qt, float code, float st, float lo) {
-  const float xt = __builtin_fmaf(code + 0.5f, st, lo);
-  if (METRIC == 0) { const float diff = qt - xt; return __builtin_fmaf(diff, diff, acc); }
-  return __builtin_fmaf(qt, xt, acc);
+__device__ __forceinline__ float sq8_step(float acc, float ab, float code, float st) {
+  if (METRIC == 0) { const float diff = __builtin_fmaf(-code, st, ab); return __builtin_fmaf(diff, diff, acc); }
+  return __builtin_fmaf(code, ab, acc);
+}
+
+// fills qs for query qi and returns the constant of the inner-product form (0 for L2);
+// call with all 256 lanes, followed by a barrier
+template <int METRIC>
+__device__ __forceinline__ void sq8_query_terms(const float* __restrict__ q, int64_t qi, int d,
+                                                const float* __restrict__ vmin,
+                                                const float* __restrict__ step, float* qs,
+                                                float* ip0) {
+  for (int t = threadIdx.x; t < d; t += 256) {
+    const float mid = __builtin_fmaf(0.5f, step[t], vmin[t]);
+    if (METRIC == 0) { qs[t] = q[qi * d + t] - mid; qs[d + t] = step[t]; }
+    else { qs[t] = q[qi * d + t] * step[t]; qs[d + t] = q[qi * d + t] * mid; }
+  }
+  if (METRIC == 1) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float s0 = 0.f;
+      for (int t = 0; t < d; ++t) s0 += qs[d + t];
+      *ip0 = s0;
+    }
+  }
 }
 
 // any d: one stored code per lane, read straight from memory
@@ -224,16 +250,17 @@ __global__ __launch_bounds__(256) void ivfsq8_scan_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);
   u64* bound = slots + 4 * tot;
-  float* qs = reinterpret_cast<float*>(bound + 2);              // q | vmin | step, d floats each
+  float* qs = reinterpret_cast<float*>(bound + 2);              // per-query terms, 2 d floats (+ 1)
   const int64_t qi = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
   const int wave = threadIdx.x >> 6;
   const int p_end = min(nprobe, split * ppb + ppb);
-  for (int t = threadIdx.x; t < d; t += 256) { qs[t] = q[qi * d + t]; qs[d + t] = vmin[t]; qs[2 * d + t] = step[t]; }
+  sq8_query_terms<METRIC>(q, qi, d, vmin, step, qs, qs + 2 * d);
   if (threadIdx.x == 0) *bound = KEY_EMPTY;
   WaveSelect<R> ws;
   ws.init(slots + wave * tot, tot, k, bound);
   __syncthreads();
+  const float acc0 = METRIC == 1 ? qs[2 * d] : 0.f;
   for (int p = split * ppb; p < p_end; ++p) {
     const int l = probes[qi * nprobe + p];
     if (l < 0) continue;
@@ -241,10 +268,10 @@ __global__ __launch_bounds__(256) void ivfsq8_scan_kernel(
     for (int64_t i0 = begin; i0 < end; i0 += 256) {
       const int64_t i = i0 + threadIdx.x;
       const bool valid = i < end;
-      float acc = 0.f;
+      float acc = acc0;
       if (valid) {
         const uint8_t* __restrict__ c = codes + i * d;
-        for (int t = 0; t < d; ++t) acc = sq8_step<METRIC>(acc, qs[t], (float)c[t], qs[2 * d + t], qs[d + t]);
+        for (int t = 0; t < d; ++t) acc = sq8_step<METRIC>(acc, qs[t], (float)c[t], qs[d + t]);
       }
       ws.push(valid, make_key(acc, (u32)i, METRIC), true);
     }
@@ -267,15 +294,15 @@ __global__ __launch_bounds__(256) void ivfsq8_scan_tiled_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);
   u64* bound = slots + 4 * tot;
-  float* qs = reinterpret_cast<float*>(bound + 2);              // q | vmin | step, d floats each
-  unsigned char* tile = reinterpret_cast<unsigned char*>(qs + 3 * d);   // 2 x TR x LDB bytes
+  float* qs = reinterpret_cast<float*>(bound + 2);              // per-query terms, 2 d floats (+ 4)
+  unsigned char* tile = reinterpret_cast<unsigned char*>(qs + 2 * d + 4);   // 2 x TR x LDB bytes
   const int64_t qi = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
   const int tid = threadIdx.x, wave = tid >> 6;
   const int p_end = min(nprobe, split * ppb + ppb);
   const int r_ld = tid / LPR, c_ld = tid % LPR;
 
-  for (int t = tid; t < d; t += 256) { qs[t] = q[qi * d + t]; qs[d + t] = vmin[t]; qs[2 * d + t] = step[t]; }
+  sq8_query_terms<METRIC>(q, qi, d, vmin, step, qs, qs + 2 * d);
   if (tid == 0) *bound = KEY_EMPTY;
   WaveSelect<R> ws;
   ws.init(slots + wave * tot, tot, k, bound);
@@ -317,8 +344,9 @@ __global__ __launch_bounds__(256) void ivfsq8_scan_tiled_kernel(
   Pos cur = first_row_from(split * ppb);
   if (cur.ok) { FETCH(cur); STASH(0); }
   __syncthreads();
+  const float acc0 = METRIC == 1 ? qs[2 * d] : 0.f;
   int buf = 0;
-  float acc = 0.f;
+  float acc = acc0;
   while (cur.ok) {
     const Pos nxt = next_of(cur);
     if (nxt.ok) FETCH(nxt);
@@ -329,20 +357,20 @@ __global__ __launch_bounds__(256) void ivfsq8_scan_tiled_kernel(
       const u32x4 w = *reinterpret_cast<const u32x4*>(tr + c * 16);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 qv = *reinterpret_cast<const float4*>(qc + c * 16 + g * 4);
-        const float4 lo = *reinterpret_cast<const float4*>(qc + d + c * 16 + g * 4);
-        const float4 st = *reinterpret_cast<const float4*>(qc + 2 * d + c * 16 + g * 4);
+        const float4 ab = *reinterpret_cast<const float4*>(qc + c * 16 + g * 4);
+        float4 st = ab;
+        if (METRIC == 0) st = *reinterpret_cast<const float4*>(qc + d + c * 16 + g * 4);
         const u32 word = w[g];
-        acc = sq8_step<METRIC>(acc, qv.x, (float)(word & 0xFFu), st.x, lo.x);
-        acc = sq8_step<METRIC>(acc, qv.y, (float)((word >> 8) & 0xFFu), st.y, lo.y);
-        acc = sq8_step<METRIC>(acc, qv.z, (float)((word >> 16) & 0xFFu), st.z, lo.z);
-        acc = sq8_step<METRIC>(acc, qv.w, (float)(word >> 24), st.w, lo.w);
+        acc = sq8_step<METRIC>(acc, ab.x, (float)(word & 0xFFu), st.x);
+        acc = sq8_step<METRIC>(acc, ab.y, (float)((word >> 8) & 0xFFu), st.y);
+        acc = sq8_step<METRIC>(acc, ab.z, (float)((word >> 16) & 0xFFu), st.z);
+        acc = sq8_step<METRIC>(acc, ab.w, (float)(word >> 24), st.w);
       }
     }
     if (cur.c0 + DC >= d) {
       const int64_t i = cur.i0 + tid;
       ws.push(i < cur.end, make_key(acc, (u32)i, METRIC), true);
-      acc = 0.f;
+      acc = acc0;
     }
     if (nxt.ok) STASH(buf ^ 1);
     block_sync_lds();
@@ -421,7 +449,7 @@ void launch_sq8_encode(const float* x, int64_t n, int d, const float* vmin, cons
 static int sq8_chunk(int d) { return d % 64 == 0 ? 64 : (d % 32 == 0 ? 32 : 0); }
 
 size_t ivfsq8_scan_lds_bytes(int d, int k) {
-  const size_t base = (size_t)(4 * select_slots_for_k(k) + 2) * sizeof(u64) + (size_t)3 * d * sizeof(float);
+  const size_t base = (size_t)(4 * select_slots_for_k(k) + 2) * sizeof(u64) + ((size_t)2 * d + 4) * sizeof(float);
   const int dc = sq8_chunk(d);
   return dc ? base + (size_t)2 * 256 * (dc + 16) : base;
 }
