@@ -223,6 +223,7 @@ struct vs_ivfpq {
   uint8_t* codes = nullptr;     // [ntotal, code_size], list-contiguous
   int64_t* ids = nullptr;       // [ntotal]
   float* norms = nullptr;       // [ntotal] squared norms of the decoded vectors, search_type 1 only
+  float* cnorm = nullptr;       // [nlist] squared norms of the centroids (IVF-PQ only)
   int search_type = VS_ST_RESIDUAL_TABLES;
   int64_t* list_off = nullptr;  // device [nlist + 1]
   std::vector<int64_t> h_off;   // host copy
@@ -537,6 +538,8 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
   TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->list_off), ((size_t)nlist + 1) * sizeof(int64_t)));
   TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
   TRY_C(hipMemcpyAsync(ix->codebooks, codebooks, tb, hipMemcpyDeviceToDevice, st));
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->cnorm), (size_t)nlist * sizeof(float)));
+  launch_row_norms(ix->centroids, nlist, d, ix->cnorm, st);
   TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));
   if (mfma_knn_supported(d, 1)) {
     TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
@@ -558,6 +561,7 @@ static void ivf_free_device_memory(vs_ivfpq* ix) {
   if (ix->codes) (void)hipFree(ix->codes);
   if (ix->ids) (void)hipFree(ix->ids);
   if (ix->norms) (void)hipFree(ix->norms);
+  if (ix->cnorm) (void)hipFree(ix->cnorm);
   if (ix->plane_mem) (void)hipFree(ix->plane_mem);
   ix->scratch.release();
 }
@@ -784,15 +788,14 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   u64* partial = reinterpret_cast<u64*>(base + o_part);
 
   coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st);
-  // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> instead of
-  // the coarse distance, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
+  // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
+  // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
   {
     StageTimer t(VS_STAGE_SCAN, st);
-    if (with_norms) launch_pair_bias(q, nq, g.d, ix->centroids, probes, npr, cdist, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
-                          ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->ntotal, k,
-                          partial, ix->ids, out_dist, out_ids, st) != 0)
+                          ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->cnorm,
+                          ix->ntotal, k, partial, ix->ids, out_dist, out_ids, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
   }
   if (nsplit > 1) {

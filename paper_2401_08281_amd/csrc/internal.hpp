@@ -56,9 +56,8 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
 void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
                      const float* centroids, const float* codebooks, float* tmp_norms,
                      hipStream_t st);
-// bias[q][p] = |q|^2 - 2 <q, centroid of probes[q][p]>
-void launch_pair_bias(const float* q, int64_t nq, int d, const float* centroids,
-                      const int32_t* probes, int nprobe, float* bias, hipStream_t st);
+// norms[i] = |row i|^2 (fma chain in dimension order)
+void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_t st);
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
                             hipStream_t st);
 void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_t st);
@@ -67,8 +66,8 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      const float* norms, int64_t ntotal, int k, u64* partial, const int64_t* ids,
-                      float* out_dist, int64_t* out_ids, hipStream_t st);
+                      const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
+                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 

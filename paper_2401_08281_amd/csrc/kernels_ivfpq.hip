@@ -112,24 +112,14 @@ __global__ void pq_norms_kernel(const uint8_t* __restrict__ tmp_codes, int64_t n
   tmp_norms[i] = acc;
 }
 
-// bias[q][p] = |q|^2 - 2 <q, c_l> for the p-th probed list l of query q: both inner products
-// are fma chains in dimension order, the combination one fma.  One lane per (query, probe).
-__global__ void pair_bias_kernel(const float* __restrict__ q, int64_t nq, int d,
-                                 const float* __restrict__ centroids,
-                                 const int32_t* __restrict__ probes, int nprobe,
-                                 float* __restrict__ bias) {
-  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (e >= nq * nprobe) return;
-  const int64_t qi = e / nprobe;
-  const int l = probes[e];
-  const float* __restrict__ qv = q + qi * d;
-  const float* __restrict__ c = centroids + (int64_t)(l >= 0 ? l : 0) * d;
-  float qq = 0.f, qc = 0.f;
-  for (int t = 0; t < d; ++t) {
-    qq = __builtin_fmaf(qv[t], qv[t], qq);
-    qc = __builtin_fmaf(qv[t], c[t], qc);
-  }
-  bias[e] = __builtin_fmaf(-2.f, qc, qq);
+// norms[i] = |row i|^2 as one fma chain in dimension order.  One lane per row.
+__global__ void row_norms_kernel(const float* __restrict__ x, int64_t n, int d,
+                                 float* __restrict__ norms) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int t = 0; t < d; ++t) acc = __builtin_fmaf(x[i * d + t], x[i * d + t], acc);
+  norms[i] = acc;
 }
 
 __global__ void move_old_kernel(const uint8_t* __restrict__ old_codes,
@@ -219,10 +209,12 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
     const float* __restrict__ centroids, const float* __restrict__ codebooks,
     const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb,
     int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
-    const float* __restrict__ norms, int cs, int k, int tot, KeySink sink) {
+    const float* __restrict__ norms, const float* __restrict__ cnorm, int cs, int k, int tot,
+    KeySink sink) {
   // mode 0: L2, one table of squared residual distances per (query, list); mode 1: inner
   // product, one table per query, cdist = <q, c_l>; mode 2: L2 through stored norms (Sec. 4.3):
-  // one table -2 <q_m, T_m[j]> per query, cdist = |q|^2 - 2 <q, c_l>, norms = |x'|^2 per code
+  // one table -2 <q_m, T_m[j]> per query; per list |q|^2 - 2 <q, c_l> = |q - c_l|^2 - |c_l|^2,
+  // the coarse distance minus the centroid's norm; norms = |x'|^2 per code
   constexpr int K = 1 << NBITS;
   const int metric = mode == 1 ? 1 : 0;                         // ordering of the keys
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -276,6 +268,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
       __syncthreads();
     } else {
       bias = cdist[qi * nprobe + p];
+      if (mode == 2) bias -= cnorm[l];
     }
     for (int64_t i0 = begin + wave * VS_WAVE; i0 < end; i0 += 4 * VS_WAVE) {
       const int64_t i = i0 + lane;
@@ -374,9 +367,11 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
-    const float* __restrict__ norms, int64_t ntotal, int k, int tot, KeySink sink) {
+    const float* __restrict__ norms, const float* __restrict__ cnorm, int64_t ntotal, int k, int tot,
+    KeySink sink) {
   // METRIC 0: L2 with a table per (query, list); 1: inner product; 2: L2 through stored norms
-  // (one table -2 <q_m, T_m[j]> per query, cdist = |q|^2 - 2 <q, c_l>, + |x'|^2 per code)
+  // (one table -2 <q_m, T_m[j]> per query; per list cdist - |c_l|^2 = |q|^2 - 2 <q, c_l>;
+  // + |x'|^2 per code)
   constexpr int K = 256, D = M * DSUB;
   constexpr int KEY_METRIC = METRIC == 1 ? 1 : 0;
   constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
@@ -496,6 +491,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
         TICK(3);
       } else {
         bias = cdist[qi * nprobe + p_begin + p];
+        if (METRIC == 2) bias -= cnorm[s_list[p]];
       }
       // scan list p; the next chunk of a long list is requested before the current one is summed
       CodeWords<M> cw2;
@@ -620,11 +616,9 @@ void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, co
                      n, g.d, g.dsub, g.K, g.M, list_of, centroids, codebooks, tmp_norms);
 }
 
-void launch_pair_bias(const float* q, int64_t nq, int d, const float* centroids,
-                      const int32_t* probes, int nprobe, float* bias, hipStream_t st) {
-  if (nq <= 0) return;
-  hipLaunchKernelGGL(pair_bias_kernel, dim3((unsigned)((nq * nprobe + 255) / 256)), dim3(256), 0, st,
-                     q, nq, d, centroids, probes, nprobe, bias);
+void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_t st) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, d, norms);
 }
 
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
@@ -643,8 +637,8 @@ template <int M, int DSUB, int METRIC, int R, int NBUF>
 static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
-                            const uint8_t* codes, const float* norms, int64_t ntotal, int k, int tot,
-                            KeySink sink, hipStream_t st) {
+                            const uint8_t* codes, const float* norms, const float* cnorm,
+                            int64_t ntotal, int k, int tot, KeySink sink, hipStream_t st) {
   const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * 256 * sizeof(float) +
                        (size_t)ppb * 20 + 16;
   auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
@@ -658,8 +652,8 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
     per_cu = 1;
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
-                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, ntotal, k,
-                     tot, sink);
+                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, ntotal,
+                     k, tot, sink);
 }
 
 template <int M, int DSUB>
@@ -667,11 +661,11 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                const float* norms, int mode, int64_t ntotal, int k, int tot,
-                                KeySink sink, hipStream_t st) {
+                                const float* norms, const float* cnorm, int mode, int64_t ntotal,
+                                int k, int tot, KeySink sink, hipStream_t st) {
 #define GO(MET, RR, NB)                                                                           \
   launch_scan_reg<M, DSUB, MET, RR, NB>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
-                                        nsplit, list_off, codes, norms, ntotal, k, tot, sink, st)
+                                        nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, st)
   const int r = select_regs_for_slots(tot);
   // L2 tables alternate between two buffers (one barrier per list); the single inner-product
   // table needs one.  A single L2 table with a third resident workgroup per CU measured
@@ -687,25 +681,25 @@ static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                const float* norms, int mode, int k, int tot, size_t shmem,
-                                KeySink sink, hipStream_t st) {
+                                const float* norms, const float* cnorm, int mode, int k, int tot,
+                                size_t shmem, KeySink sink, hipStream_t st) {
   auto kern = &ivfpq_scan_kernel<NBITS, R>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, mode,
                      g.M, g.dsub, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off,
-                     codes, norms, g.code_size, k, tot, sink);
+                     codes, norms, cnorm, g.code_size, k, tot, sink);
 }
 
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      const float* norms, int64_t ntotal, int k, u64* partial, const int64_t* ids,
-                      float* out_dist, int64_t* out_ids, hipStream_t st) {
+                      const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
+                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return 0;
-  // table form: 1 inner product; 2 L2 through the stored norms (cdist then holds
-  // |q|^2 - 2 <q, c_l>); 0 L2 with one table of squared residual distances per (query, list)
+  // table form: 1 inner product; 2 L2 through the stored norms (norms non-null; cnorm = the
+  // centroids' squared norms); 0 L2 with one table of squared residual distances per (query, list)
   const int mode = g.metric == 1 ? 1 : (norms ? 2 : 0);
   KeySink sink;
   sink.metric = g.metric;
@@ -721,7 +715,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                nsplit, list_off, codes, norms, mode, ntotal, k, tot, sink, st); \
+                                nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, tot, sink, st); \
     return 0;                                                                                    \
   }
   REG(16, 8)   // PQ16x8 on d = 128
@@ -730,7 +724,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #undef REG
 #define GEN(NB, RR)                                                                              \
   launch_scan_generic<NB, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
-                              list_off, codes, norms, mode, k, tot, shmem, sink, st)
+                              list_off, codes, norms, cnorm, mode, k, tot, shmem, sink, st)
   const int r = select_regs_for_slots(tot);
   if (g.nbits == 8) { if (r == 2) GEN(8, 2); else if (r == 4) GEN(8, 4); else GEN(8, 0); }
   else              { if (r == 2) GEN(4, 2); else if (r == 4) GEN(4, 4); else GEN(4, 0); }
