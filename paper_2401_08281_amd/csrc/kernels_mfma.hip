@@ -44,72 +44,83 @@ __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
 // Operand preparation: bf16 head / tail planes, fp32 squared norms, and the
 // facts needed to bound the approximation error (PrepInfo).
 // One lane per 8 consecutive elements (d % 8 == 0), 256 lanes per workgroup,
-// RB = 2048 / d ... rows per workgroup; row sums are added in a fixed order.
+// 2048 / d rows per group; a workgroup walks over groups and reports its flags
+// and largest norm once at the end.  Row sums are added in a fixed order.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, int64_t n,
-                                                   int64_t n_pad, int d, int rows_per_block,
+                                                   int64_t n_pad, int d, int rows_per_group,
                                                    unsigned short* __restrict__ hi,
                                                    unsigned short* __restrict__ lo,
                                                    float* __restrict__ norm,
                                                    PrepInfo* __restrict__ info) {
-  __shared__ float part[256];
-  __shared__ u32 flags[3];
+  __shared__ float part[2][256];                       // two buffers: one barrier per group
+  __shared__ u32 flags[4];                             // all_int, all_bf16, all_nonneg, largest norm
   const int cpr = d / 8;                               // chunks per row
-  const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
   const int tid = threadIdx.x;
   if (tid < 3) flags[tid] = 1u;
-  __syncthreads();
+  if (tid == 3) flags[3] = 0u;
   const int r = tid / cpr, c = tid - r * cpr;
-  float ss = 0.f;
   bool is_int = true, is_bf16 = true, is_nonneg = true;
-  if (r < rows_per_block && row0 + r < n) {
-    const int64_t off = (row0 + r) * d + c * 8;
-    float v[8];
-    const float4 a = *reinterpret_cast<const float4*>(x + off);
-    const float4 b = *reinterpret_cast<const float4*>(x + off + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    unsigned short h[8], l[8];
+  u32 max_bits = 0u;
+  const int64_t ngroups = (n_pad + rows_per_group - 1) / rows_per_group;
+  int pb = 0;
+  for (int64_t g = blockIdx.x; g < ngroups; g += gridDim.x, pb ^= 1) {
+    const int64_t row0 = g * rows_per_group;
+    float ss = 0.f;
+    if (r < rows_per_group && row0 + r < n) {
+      const int64_t off = (row0 + r) * d + c * 8;
+      float v[8];
+      const float4 a = *reinterpret_cast<const float4*>(x + off);
+      const float4 b = *reinterpret_cast<const float4*>(x + off + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      unsigned short h[8], l[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      h[t] = bf16_rn_bits(v[t]);
-      const float rem = v[t] - bf16_bits_to_f32(h[t]);      // exact in fp32
-      l[t] = bf16_rn_bits(rem);
-      is_bf16 = is_bf16 && rem == 0.f;
-      is_int = is_int && v[t] == __builtin_rintf(v[t]);
-      is_nonneg = is_nonneg && v[t] >= 0.f;
-      ss = __builtin_fmaf(v[t], v[t], ss);
+      for (int t = 0; t < 8; ++t) {
+        h[t] = bf16_rn_bits(v[t]);
+        const float rem = v[t] - bf16_bits_to_f32(h[t]);      // exact in fp32
+        l[t] = bf16_rn_bits(rem);
+        is_bf16 = is_bf16 && rem == 0.f;
+        is_int = is_int && v[t] == __builtin_rintf(v[t]);
+        is_nonneg = is_nonneg && v[t] >= 0.f;
+        ss = __builtin_fmaf(v[t], v[t], ss);
+      }
+      uint4 hv, lv;
+      hv.x = h[0] | ((u32)h[1] << 16); hv.y = h[2] | ((u32)h[3] << 16);
+      hv.z = h[4] | ((u32)h[5] << 16); hv.w = h[6] | ((u32)h[7] << 16);
+      lv.x = l[0] | ((u32)l[1] << 16); lv.y = l[2] | ((u32)l[3] << 16);
+      lv.z = l[4] | ((u32)l[5] << 16); lv.w = l[6] | ((u32)l[7] << 16);
+      *reinterpret_cast<uint4*>(hi + off) = hv;
+      *reinterpret_cast<uint4*>(lo + off) = lv;
+    } else if (r < rows_per_group && row0 + r < n_pad) {   // padding rows: zeros (never selected)
+      const int64_t off = (row0 + r) * d + c * 8;
+      const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+      *reinterpret_cast<uint4*>(hi + off) = z;
+      *reinterpret_cast<uint4*>(lo + off) = z;
     }
-    uint4 hv, lv;
-    hv.x = h[0] | ((u32)h[1] << 16); hv.y = h[2] | ((u32)h[3] << 16);
-    hv.z = h[4] | ((u32)h[5] << 16); hv.w = h[6] | ((u32)h[7] << 16);
-    lv.x = l[0] | ((u32)l[1] << 16); lv.y = l[2] | ((u32)l[3] << 16);
-    lv.z = l[4] | ((u32)l[5] << 16); lv.w = l[6] | ((u32)l[7] << 16);
-    *reinterpret_cast<uint4*>(hi + off) = hv;
-    *reinterpret_cast<uint4*>(lo + off) = lv;
+    part[pb][tid] = ss;
+    // (the buffer written two groups later is safe: every lane passes the next group's
+    // barrier only after its reads below)
+    __syncthreads();
+    if (tid < rows_per_group && row0 + tid < n) {
+      float sum = 0.f;
+      for (int j = 0; j < cpr; ++j) sum += part[pb][tid * cpr + j];
+      norm[row0 + tid] = sum;
+      max_bits = max(max_bits, __float_as_uint(sum));        // sum >= 0: bit order = value order
+    } else if (tid < rows_per_group && row0 + tid < n_pad) {
+      norm[row0 + tid] = 0.f;
+    }
   }
-  else if (r < rows_per_block && row0 + r < n_pad) {   // padding rows: zeros (never selected)
-    const int64_t off = (row0 + r) * d + c * 8;
-    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-    *reinterpret_cast<uint4*>(hi + off) = z;
-    *reinterpret_cast<uint4*>(lo + off) = z;
-  }
-  part[tid] = ss;
+  __syncthreads();
   if (!is_int) flags[0] = 0u;
   if (!is_bf16) flags[1] = 0u;
   if (!is_nonneg) flags[2] = 0u;
+  if (max_bits) atomicMax(&flags[3], max_bits);
   __syncthreads();
-  if (tid < rows_per_block && row0 + tid < n) {
-    float s = 0.f;
-    for (int j = 0; j < cpr; ++j) s += part[tid * cpr + j];
-    norm[row0 + tid] = s;
-    atomicMax(&info->max_norm_bits, __float_as_uint(s));    // s >= 0: bit order = value order
-  } else if (tid < rows_per_block && row0 + tid < n_pad) {
-    norm[row0 + tid] = 0.f;
-  }
   if (tid == 0) {
     if (!flags[0]) atomicAnd(&info->all_int, 0u);
     if (!flags[1]) atomicAnd(&info->all_bf16, 0u);
     if (!flags[2]) atomicAnd(&info->all_nonneg, 0u);
+    if (flags[3]) atomicMax(&info->max_norm_bits, flags[3]);
   }
 }
 
@@ -173,6 +184,10 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   u64* qkey = reinterpret_cast<u64*>(cnt_s + 128 * RB) + (threadIdx.x >> 6) * 128;   // [4][128]
   int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + 128 * RB) + 4 * 128) +
               (threadIdx.x >> 6) * 128;                           // [4][128]
+  // |q|^2 of the workgroup's rows (L2 values of listed columns are formed from LDS only: a
+  // read from memory there would wait behind the tile loads in flight)
+  float* an_s = reinterpret_cast<float*>(reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + 128 * RB) +
+                                                               4 * 128) + 4 * 128);   // [128 * RB]
   int qn = 0;                                                     // queue fill (wave-uniform)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
@@ -210,8 +225,9 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int64_t r = min(row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), na - 1);
-      tr[rb][v] = MODE == 1 ? tau[r] * INV_S : 0.f;
+      const int64_t r = row0 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      // (rows past the end of A start from -inf: nothing of them passes the collect test)
+      tr[rb][v] = MODE == 1 ? (r < na ? tau[r] * INV_S : -__builtin_inff()) : 0.f;
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) mn[rb][cb][v] = __builtin_inff();
     }
@@ -262,7 +278,11 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   } while (0)
   static_assert(CHUNKS % 256 == 0, "every lane stages the same number of chunks");
 
-  if (MODE == 1) for (int i = tid; i < 128 * RB; i += 256) cnt_s[i] = 0;
+  if (MODE == 1)
+    for (int i = tid; i < 128 * RB; i += 256) {
+      cnt_s[i] = 0;
+      an_s[i] = METRIC == 0 ? Anorm[min(rt * (128 * RB) + i, na - 1)] : 0.f;
+    }
   // Takes n <= 64 queued candidates (the newest ones) and appends each to its row's list:
   // one LDS atomic per candidate for the position, all lanes in parallel.
   auto drain = [&](int n) {
@@ -287,27 +307,43 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
     if (more) FETCH_TILE(ct + col_step);                          // in flight during the MFMAs
     floatx16 m[RB][2];
     const unsigned short* __restrict__ bth = bt + (buf * NPL) * BN * LDB;
+    // B fragments go through a ring of registers and are requested PF fragments ahead of
+    // their use; the scheduling groups below pin that order (one LDS read per product group)
+    constexpr int NF = KSTEPS * 2, PF = 4;
+    static_assert(NF >= PF, "ring deeper than the tile");
+    bf16x8 rh[PF], rl[THREE ? PF : 1];
+#define FRAG_OFF(F) ((((F) & 1) * 32 + (lane & 31)) * LDB + ((F) >> 1) * 16 + 8 * (lane >> 5))
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-      bf16x8 bh[2], bl[2];
+    for (int f = 0; f < PF; ++f) {
+      rh[f] = *reinterpret_cast<const bf16x8*>(bth + FRAG_OFF(f));
+      if constexpr (THREE) rl[f] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f));
+    }
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const int o = (cb * 32 + (lane & 31)) * LDB + kk * 16 + 8 * (lane >> 5);
-        bh[cb] = *reinterpret_cast<const bf16x8*>(bth + o);
-        if constexpr (THREE) bl[cb] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + o);
-      }
+    for (int f = 0; f < NF; ++f) {
+      const int kk = f >> 1, cb = f & 1;
+      const bf16x8 ch = rh[f % PF];
+      bf16x8 cl;
+      if constexpr (THREE) cl = rl[f % PF];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          // the first product starts from 0 (MODE 0) or from the row thresholds (MODE 1)
-          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bh[cb],
-                                                              kk == 0 ? tr[rb] : m[rb][cb], 0, 0, 0);
-          if constexpr (THREE) {
-            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], bl[cb], m[rb][cb], 0, 0, 0);
-            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], bh[cb], m[rb][cb], 0, 0, 0);
-          }
+      for (int rb = 0; rb < RB; ++rb) {
+        // the first product starts from 0 (MODE 0) or from the row thresholds (MODE 1)
+        m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], ch, kk == 0 ? tr[rb] : m[rb][cb], 0, 0, 0);
+        if constexpr (THREE) {
+          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], cl, m[rb][cb], 0, 0, 0);
+          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], ch, m[rb][cb], 0, 0, 0);
         }
+      }
+      if (f + PF < NF) {
+        rh[f % PF] = *reinterpret_cast<const bf16x8*>(bth + FRAG_OFF(f + PF));
+        if constexpr (THREE) rl[f % PF] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f + PF));
+      }
+    }
+#undef FRAG_OFF
+    __builtin_amdgcn_sched_group_barrier(0x100, PF * NPL, 0);                       // LDS reads
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      __builtin_amdgcn_sched_group_barrier(0x008, RB * (THREE ? 3 : 1), 0);         // matrix products
+      if (f + PF < NF) __builtin_amdgcn_sched_group_barrier(0x100, NPL, 0);
     }
     const float b0 = bns[buf * BN + (lane & 31)], b1 = bns[buf * BN + 32 + (lane & 31)];
     if (MODE == 0) {
@@ -351,25 +387,33 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-          if (__ballot(any[rb][cb]) == 0) continue;               // nothing of this 32 x 32 block passes
+          if (__builtin_amdgcn_ballot_w64(any[rb][cb]) == 0) continue;   // nothing of this 32 x 32 block passes
           const float hb = cb ? b1 : b0;
+          // rare path: narrow down by groups of four accumulators, then by element
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int rl = wave * (32 * RB) + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const bool pass = m[rb][cb][v] >= hb && rt * (128 * RB) + rl < na;
-            const u64 mask = __ballot(pass);
-            if (mask != 0) {
-              if (pass) {
-                const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
-                // approximate value from the accumulator a = tau / s + <q,x>:
-                // L2: |q|^2 + |x|^2 - 2 <q,x> = |q|^2 + 2 (b / s - (a - tau / s));  IP: <q,x>
-                const float dotv = m[rb][cb][v] - tr[rb][v];
-                const float val = METRIC == 0 ? Anorm[rt * (128 * RB) + rl] + 2.f * (hb - dotv) : dotv;
-                qkey[e] = make_key(val, (u32)(ct + cb * 32 + (lane & 31)), METRIC);
-                qrow[e] = rl;
+          for (int g = 0; g < 4; ++g) {
+            const float gm = fmaxf(fmaxf(m[rb][cb][4 * g], m[rb][cb][4 * g + 1]),
+                                   fmaxf(m[rb][cb][4 * g + 2], m[rb][cb][4 * g + 3]));
+            if (__builtin_amdgcn_ballot_w64(gm >= hb) == 0) continue;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int v = 4 * g + u;
+              const int rl = wave * (32 * RB) + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              const bool pass = m[rb][cb][v] >= hb;
+              const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+              if (mask != 0) {
+                if (pass) {
+                  const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
+                  // approximate value from the accumulator a = tau / s + <q,x>:
+                  // L2: |q|^2 + |x|^2 - 2 <q,x> = |q|^2 + 2 (b / s - (a - tau / s));  IP: <q,x>
+                  const float dotv = m[rb][cb][v] - tr[rb][v];
+                  const float val = METRIC == 0 ? an_s[rl] + 2.f * (hb - dotv) : dotv;
+                  qkey[e] = make_key(val, (u32)(ct + cb * 32 + (lane & 31)), METRIC);
+                  qrow[e] = rl;
+                }
+                qn += __popcll(mask);
+                if (qn >= 64) drain(64);
               }
-              qn += __popcll(mask);
-              if (qn >= 64) drain(64);
             }
           }
         }
@@ -436,6 +480,8 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   u64* qkey = reinterpret_cast<u64*>(cnt_s + BM) + (threadIdx.x >> 6) * 128;          // [8][128]
   int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + BM) + 8 * 128) +
               (threadIdx.x >> 6) * 128;                                  // [8][128]
+  float* an_s = reinterpret_cast<float*>(reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + BM) + 8 * 128) +
+                                         8 * 128);                       // [BM] |q|^2 of the rows
   int qn = 0;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
@@ -456,8 +502,8 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int64_t r = min(row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), na - 1);
-      tr[rb][v] = MODE == 1 ? tau[r] * INV_S : 0.f;
+      const int64_t r = row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      tr[rb][v] = MODE == 1 ? (r < na ? tau[r] * INV_S : -__builtin_inff()) : 0.f;
       mn[rb][v] = __builtin_inff();
     }
 
@@ -491,7 +537,11 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
               ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();         \
   } while (0)
 
-  if (MODE == 1) for (int i = tid; i < BM; i += 512) cnt_s[i] = 0;
+  if (MODE == 1)
+    for (int i = tid; i < BM; i += 512) {
+      cnt_s[i] = 0;
+      an_s[i] = METRIC == 0 ? Anorm[min(row0 + i, na - 1)] : 0.f;
+    }
   auto drain = [&](int n) {
     wave_lds_sync();
     const int e = qn - n + lane;
@@ -590,23 +640,30 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
           for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
-              if (__ballot(any[rb][cb]) == 0) continue;
+              if (__builtin_amdgcn_ballot_w64(any[rb][cb]) == 0) continue;
               const float hb = cb ? b1 : b0;
 #pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int rl = wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const bool pass = m[rb][cb][v] >= hb && row0 + rl < na;
-                const u64 mask = __ballot(pass);
-                if (mask != 0) {
-                  if (pass) {
-                    const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
-                    const float dotv = m[rb][cb][v] - tr[rb][v];
-                    const float val = METRIC == 0 ? Anorm[row0 + rl] + 2.f * (hb - dotv) : dotv;
-                    qkey[e] = make_key(val, (u32)(ct + wc * 64 + cb * 32 + (lane & 31)), METRIC);
-                    qrow[e] = rl;
+              for (int g = 0; g < 4; ++g) {   // rare path: by groups of four, then by element
+                const float gm = fmaxf(fmaxf(m[rb][cb][4 * g], m[rb][cb][4 * g + 1]),
+                                       fmaxf(m[rb][cb][4 * g + 2], m[rb][cb][4 * g + 3]));
+                if (__builtin_amdgcn_ballot_w64(gm >= hb) == 0) continue;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const int v = 4 * g + u;
+                  const int rl = wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                  const bool pass = m[rb][cb][v] >= hb;
+                  const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+                  if (mask != 0) {
+                    if (pass) {
+                      const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
+                      const float dotv = m[rb][cb][v] - tr[rb][v];
+                      const float val = METRIC == 0 ? an_s[rl] + 2.f * (hb - dotv) : dotv;
+                      qkey[e] = make_key(val, (u32)(ct + wc * 64 + cb * 32 + (lane & 31)), METRIC);
+                      qrow[e] = rl;
+                    }
+                    qn += __popcll(mask);
+                    if (qn >= 64) drain(64);
                   }
-                  qn += __popcll(mask);
-                  if (qn >= 64) drain(64);
                 }
               }
             }
@@ -884,13 +941,9 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
   if (n <= 0) return;
   const int rpb = 2048 / d;                          // d <= 2048 here, d % 8 == 0
   const int64_t n_pad = mfma_padded_rows(n);
-  // in pieces of 2^24 rows (a multiple of 64): a launch holds fewer than 2^32 work-items
-  constexpr int64_t kRows = 1ll << 24;
-  for (int64_t r0 = 0; r0 < n_pad; r0 += kRows) {
-    const int64_t np = std::min(kRows, n_pad - r0), nr = std::max<int64_t>(0, std::min(np, n - r0));
-    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((np + rpb - 1) / rpb)), dim3(256), 0, st,
-                       x + r0 * d, nr, np, d, rpb, hi + r0 * d, lo + r0 * d, norm + r0, info);
-  }
+  const int64_t ngroups = (n_pad + rpb - 1) / rpb;
+  hipLaunchKernelGGL(prep_kernel, dim3((unsigned)std::min<int64_t>(ngroups, 4096)), dim3(256), 0, st, x, n,
+                     n_pad, d, rpb, hi, lo, norm, info);
 }
 
 namespace {
@@ -910,18 +963,34 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   MfmaPlan p;
   p.kc = !stationary_d(d);
   const int bm = p.kc ? 256 : 128, bn = p.kc ? 128 : 64;      // tile of one workgroup step
-  const int slots = p.kc ? 256 : 512;                          // resident workgroups on the chip
   p.kp = mfma_knn_kp(k);
   p.cap = std::max(64, 3 * p.kp);
-  // One 32-row block of A per wavefront: small enough in registers for two workgroups per
-  // CU, whose matrix-core and vector phases then overlap (measured faster than two row
-  // blocks per wavefront at half the occupancy).  Splits of B fill the 512 resident slots.
+  // One 32-row block of A per wavefront: small enough in registers for two (operands split
+  // in head and tail) or three (operands exactly bf16) workgroups per CU, whose matrix-core
+  // and vector phases then overlap (measured faster than two row blocks per wavefront at
+  // half the occupancy).
   p.RB = 1;
   p.row_tiles = (na + bm - 1) / bm;
   const int64_t col_steps = std::max<int64_t>(1, (nb + bn - 1) / bn);
-  int64_t ns = std::max<int64_t>(1, slots / p.row_tiles);
-  ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
-  ns = std::min<int64_t>(ns, 16);
+  int64_t ns;
+  if (p.kc) {   // 256 resident workgroups
+    ns = std::max<int64_t>(1, 256 / p.row_tiles);
+    ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
+    ns = std::min<int64_t>(ns, 16);
+  } else {
+    // Splits of B so that the workgroups come in full rounds at both occupancies (512 and
+    // 768 resident workgroups on the chip): which variant runs is decided on the device.
+    ns = 1;
+    double best = -1.0;
+    const int64_t ns_max = std::min<int64_t>(24, std::max<int64_t>(1, col_steps / 8));
+    for (int64_t c = 1; c <= ns_max; ++c) {
+      const double g = (double)(p.row_tiles * c);
+      const double e2 = g / (std::ceil(g / 512.0) * 512.0), e3 = g / (std::ceil(g / 768.0) * 768.0);
+      const double score = std::min(e2, e3);
+      if (score > best + 0.02) { best = score; ns = c; }
+      if (best >= 0.9) break;                                   // good enough: no more splits
+    }
+  }
   p.nsplit = (int)ns;
   const int64_t steps_per_split = (col_steps + ns - 1) / ns;
   p.cols_per_split = steps_per_split * bn;
@@ -931,9 +1000,14 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   // about S * kp_tau columns are expected below tau, at least k of them except with small
   // probability (rows that end up with fewer, or with more than their lists hold, fail the
   // re-rank test and are recomputed).
-  p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, steps_per_split / 32));
-  // (long rows make a sweep expensive: the tiled kernel samples from 16384 columns on)
-  if (p.kc) p.stride = (int)std::max<int64_t>(p.stride, std::min<int64_t>(4, nb / 4096));
+  if (p.kc) {
+    p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, steps_per_split / 32));
+    // (long rows make a sweep expensive: the tiled kernel samples from 16384 columns on)
+    p.stride = (int)std::max<int64_t>(p.stride, std::min<int64_t>(4, nb / 4096));
+  } else {
+    // (independent of the number of splits; measured flat between half and twice this)
+    p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, col_steps / 192));
+  }
   p.stride = (int)std::min<int64_t>(p.stride, steps_per_split);        // at least one tile per split
   if (p.stride == 1) {
     p.kp_tau = p.kp;
@@ -993,7 +1067,8 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                            hipStream_t st) {
   constexpr int D = KSTEPS * 16, NPL = THREE ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * 64 * (D + 8) * sizeof(unsigned short) + 2 * 64 * sizeof(float) +
-                       (size_t)128 * RB * sizeof(int) + 4 * 128 * (sizeof(u64) + sizeof(int));
+                       (size_t)128 * RB * (sizeof(int) + sizeof(float)) +
+                       4 * 128 * (sizeof(u64) + sizeof(int));
   auto kern = &mfma_sweep_kernel<KSTEPS, RB, METRIC, MODE, THREE>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1020,7 +1095,7 @@ static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const Mfm
                               char* work, hipStream_t st) {
   constexpr int NPL = THREE ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * (256 + 128) * 40 * sizeof(unsigned short) + 2 * 128 * sizeof(float) +
-                       (size_t)256 * sizeof(int) + 8 * 128 * (sizeof(u64) + sizeof(int));
+                       (size_t)256 * (sizeof(int) + sizeof(float)) + 8 * 128 * (sizeof(u64) + sizeof(int));
   auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, THREE>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
