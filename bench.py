@@ -40,6 +40,13 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+def scan_kernel_name(cfg, code_size):
+    """The scan kernel the library picks for this shape (same rule as its launcher)."""
+    if cfg["nbits"] == 8 and (cfg["M"], cfg["d"] // cfg["M"]) in ((16, 8), (32, 3), (8, 4)):
+        return "ivfpq_scan_reg_kernel"
+    return "ivfpq_scan_pipe_kernel" if code_size in (16, 32, 64) else "ivfpq_scan_kernel"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,7 +249,7 @@ def main():
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v},
             **({"refine": refine} if refine else {}), **({"train": train} if train else {})},
-        "roofline": {"bound": "hbm", "kernel": "ivfpq_scan_reg_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(cfg, code_size), "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "peak_measured_read_stream": HBM_READ_MEASURED_GBS,
                      "frac_of_measured": achieved / HBM_READ_MEASURED_GBS,

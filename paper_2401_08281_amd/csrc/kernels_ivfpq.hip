@@ -307,6 +307,139 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// The same scan for codes of 16, 32 or 64 bytes (W16 = code size / 16), software
+// pipelined: the workgroup walks over the chunks of 256 codes of all its lists as one
+// sequence, and the codes of the next chunk -- of the same list or of the next
+// non-empty one -- are requested before the current chunk is summed, so a short list
+// costs no exposed memory latency beyond the first one of the item.  Requests are
+// clamped into the code array; lanes past the end of a list are masked when consumed.
+// ---------------------------------------------------------------------------
+template <int NBITS, int R, int W16>
+__global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
+    const float* __restrict__ q, int d, int mode, int M, int dsub,
+    const float* __restrict__ centroids, const float* __restrict__ codebooks,
+    const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb,
+    int nsplit, const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
+    const float* __restrict__ norms, const float* __restrict__ cnorm, int64_t ntotal, int k, int tot,
+    KeySink sink) {
+  constexpr int K = 1 << NBITS;
+  constexpr int MPW = NBITS == 8 ? 16 : 32;                      // sub-quantizers per 16 code bytes
+  const int metric = mode == 1 ? 1 : 0;                         // ordering of the keys
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
+  float* lut = reinterpret_cast<float*>(slots + 4 * tot);       // M * K
+  float* rs = lut + M * K;                                      // d (+ 1 to keep what follows aligned)
+  int64_t* s_begin = reinterpret_cast<int64_t*>(rs + ((d + 1) & ~1));   // ppb
+  int64_t* s_end = s_begin + ppb;                               // ppb
+  int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
+
+  const int64_t qi = blockIdx.x / nsplit;
+  const int split = blockIdx.x % nsplit;
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const float* __restrict__ qv = q + qi * d;
+  const int p_begin = split * ppb;
+  const int np = ntotal > 0 ? max(0, min(nprobe, p_begin + ppb) - p_begin) : 0;
+  const int64_t last = ntotal > 0 ? ntotal - 1 : 0;
+  const int cs = 16 * W16;
+
+  WaveSelect<R> ws;
+  ws.init(slots + wave * tot, tot, k);
+  for (int p = tid; p < np; p += 256) {
+    const int l = probes[qi * nprobe + p_begin + p];
+    s_list[p] = l >= 0 ? l : 0;
+    s_begin[p] = l >= 0 ? list_off[l] : 0;
+    s_end[p] = l >= 0 ? list_off[l + 1] : 0;
+  }
+  if (mode != 0) {  // per-query tables
+    for (int e = tid; e < M * K; e += 256) {
+      const int m = e >> NBITS;
+      const float* __restrict__ T = codebooks + (int64_t)e * dsub;
+      float acc = 0.f;
+      for (int u = 0; u < dsub; ++u) acc = __builtin_fmaf(qv[m * dsub + u], T[u], acc);
+      lut[e] = mode == 2 ? -2.f * acc : acc;
+    }
+  }
+  __syncthreads();
+
+  int p = 0;
+  while (p < np && s_begin[p] == s_end[p]) ++p;                 // first non-empty list (uniform)
+  int64_t base = p < np ? s_begin[p] : 0;                       // first code of the current chunk
+  u32x4 cw[W16], cwn[W16];
+  float nrm = 0.f, nrmn = 0.f;
+  if (p < np) {
+    const int64_t i = min(base + tid, last);
+#pragma unroll
+    for (int w = 0; w < W16; ++w) cw[w] = reinterpret_cast<const u32x4*>(codes + i * cs)[w];
+    if (mode == 2) nrm = norms[i];
+  }
+  bool first = true;                                            // first chunk of its list
+  float bias = 0.f;
+  while (p < np) {
+    const int64_t end = s_end[p];
+    int pn = p;
+    int64_t base_n = base + 256;
+    if (base_n >= end) {
+      pn = p + 1;
+      while (pn < np && s_begin[pn] == s_end[pn]) ++pn;
+      base_n = pn < np ? s_begin[pn] : 0;
+    }
+    if (pn < np) {
+      const int64_t i = min(base_n + tid, last);
+#pragma unroll
+      for (int w = 0; w < W16; ++w) cwn[w] = reinterpret_cast<const u32x4*>(codes + i * cs)[w];
+      if (mode == 2) nrmn = norms[i];
+    }
+    if (first) {
+      const int l = s_list[p];
+      if (mode == 0) {
+        const float* __restrict__ c = centroids + (int64_t)l * d;
+        __syncthreads();  // the previous list's scan is done with lut
+        for (int t = tid; t < d; t += 256) rs[t] = qv[t] - c[t];
+        __syncthreads();
+        for (int e = tid; e < M * K; e += 256) {
+          const int m = e >> NBITS;
+          const float* __restrict__ T = codebooks + (int64_t)e * dsub;
+          const float* r = rs + m * dsub;
+          float acc = 0.f;
+          for (int u = 0; u < dsub; ++u) {
+            const float diff = r[u] - T[u];
+            acc = __builtin_fmaf(diff, diff, acc);
+          }
+          lut[e] = acc;
+        }
+        __syncthreads();
+        bias = 0.f;
+      } else {
+        bias = cdist[qi * nprobe + p_begin + p];
+        if (mode == 2) bias -= cnorm[l];
+      }
+    }
+    const int64_t i = base + tid;
+    const bool valid = i < end;
+    float dist = mode == 2 ? bias + nrm : bias;
+    if (valid) {
+#pragma unroll
+      for (int w = 0; w < W16; ++w) {
+        dist = adc_bytes<NBITS>(lut, cw[w].x, w * MPW, dist);
+        dist = adc_bytes<NBITS>(lut, cw[w].y, w * MPW + MPW / 4, dist);
+        dist = adc_bytes<NBITS>(lut, cw[w].z, w * MPW + MPW / 2, dist);
+        dist = adc_bytes<NBITS>(lut, cw[w].w, w * MPW + 3 * (MPW / 4), dist);
+      }
+    }
+    ws.push(valid, make_key(dist, (u32)i, metric));
+    first = pn != p;
+    p = pn;
+    base = base_n;
+#pragma unroll
+    for (int w = 0; w < W16; ++w) cw[w] = cwn[w];
+    nrm = nrmn;
+  }
+  ws.finish();
+  __syncthreads();
+  block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
+}
+
+// ---------------------------------------------------------------------------
 // Register-resident-codebook variant for 8-bit codes (K = 256) and shapes known
 // at compile time.  Lane j of the workgroup owns codeword j of EVERY
 // sub-quantizer: M * DSUB floats in registers, loaded once per workgroup.  The
@@ -676,6 +809,22 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
 #undef GO
 }
 
+template <int NBITS, int R, int W16>
+static void launch_scan_pipe(const IvfpqDims& g, const float* q, int64_t nq,
+                             const float* centroids, const float* codebooks,
+                             const int32_t* probes, const float* cdist, int nprobe, int ppb,
+                             int nsplit, const int64_t* list_off, const uint8_t* codes,
+                             const float* norms, const float* cnorm, int mode, int64_t ntotal, int k,
+                             int tot, size_t shmem, KeySink sink, hipStream_t st) {
+  auto kern = &ivfpq_scan_pipe_kernel<NBITS, R, W16>;
+  if (shmem > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nq * nsplit)), dim3(256), shmem, st, q, g.d, mode,
+                     g.M, g.dsub, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, list_off,
+                     codes, norms, cnorm, ntotal, k, tot, sink);
+}
+
 template <int NBITS, int R>
 static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
                                 const float* centroids, const float* codebooks,
@@ -722,10 +871,28 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   REG(32, 3)   // PQ32x8 on d = 96
   REG(8, 4)    // PQ8x8 on d = 32
 #undef REG
+  const int r = select_regs_for_slots(tot);
+  // codes of 16, 32 or 64 bytes: the software-pipelined kernel
+  const size_t pipe_shmem = shmem + sizeof(float) + (size_t)ppb * 20 + 16;
+  if ((g.code_size == 16 || g.code_size == 32 || g.code_size == 64) && pipe_shmem + 64 <= 160 * 1024) {
+#define PIPE3(NB, RR, WW)                                                                        \
+  launch_scan_pipe<NB, RR, WW>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
+                               list_off, codes, norms, cnorm, mode, ntotal, k, tot, pipe_shmem, sink, st)
+#define PIPE2(NB, RR)                                                                            \
+  do {                                                                                           \
+    if (g.code_size == 16) PIPE3(NB, RR, 1);                                                     \
+    else if (g.code_size == 32) PIPE3(NB, RR, 2);                                                \
+    else PIPE3(NB, RR, 4);                                                                       \
+  } while (0)
+    if (g.nbits == 8) { if (r == 2) PIPE2(8, 2); else if (r == 4) PIPE2(8, 4); else PIPE2(8, 0); }
+    else              { if (r == 2) PIPE2(4, 2); else if (r == 4) PIPE2(4, 4); else PIPE2(4, 0); }
+#undef PIPE2
+#undef PIPE3
+    return 0;
+  }
 #define GEN(NB, RR)                                                                              \
   launch_scan_generic<NB, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
                               list_off, codes, norms, cnorm, mode, k, tot, shmem, sink, st)
-  const int r = select_regs_for_slots(tot);
   if (g.nbits == 8) { if (r == 2) GEN(8, 2); else if (r == 4) GEN(8, 4); else GEN(8, 0); }
   else              { if (r == 2) GEN(4, 2); else if (r == 4) GEN(4, 4); else GEN(4, 0); }
 #undef GEN
