@@ -151,6 +151,11 @@ IVF_CASES = {
     "c3_long_lists": (S.config("C3", nb=40_000, nq=100, ncomp=100, nlist=16), [(10, 4)]),
     "c1_long_lists": (S.config("C1", nb=20_000, nlist=8), [(10, 3), (500, 8)]),
     "odd_shapes": (S.config("C1", nb=3_001, nq=33, d=30, M=5, nlist=7), [(10, 3), (300, 7)]),
+    # generic shapes with 16-, 32- and 64-byte codes: the software-pipelined scan kernel
+    "pq16x8_d64": (S.config("C1", nb=30_000, nq=64, d=64, M=16, nlist=64), [(10, 8), (100, 64)]),
+    "pq32x4_d64": (S.config("C1", nb=30_000, nq=64, d=64, M=32, nbits=4, nlist=64), [(10, 8)]),
+    "pq64x8_ip": (S.config("C4", nb=30_000, nq=64, ncomp=40, nlist=64, metric=1, d=128, M=64), [(10, 8), (100, 3)]),
+    "pq64x4_l2_empty_lists": (S.config("C5", nb=3_000, nq=50, ncomp=10, nlist=256, metric=0), [(10, 32)]),
     # the largest k and nprobe the boundary accepts, every list probed
     "max_k_and_nprobe": (S.config("C1", nb=30_000, nq=40, nlist=1024), [(1024, 1024)]),
 }
@@ -418,7 +423,8 @@ def test_ivfpq_search_then_refine_pipeline(vs, oracle):
 
 # ------------------------------------------------- L2 through stored norms (Sec. 4.3)
 
-@pytest.mark.parametrize("name", ["c1", "c3_small", "c4_small", "pq4_l2", "odd_shapes", "c4_long_lists"])
+@pytest.mark.parametrize("name", ["c1", "c3_small", "c4_small", "pq4_l2", "odd_shapes", "c4_long_lists",
+                                  "pq16x8_d64", "pq32x4_d64"])
 def test_ivfpq_stored_norm_search_matches_oracle(vs, oracle, name):
     """Search type |q|^2 + |x'|^2 - 2 <q, x'>: the stored norms are the oracle's bit for bit,
     the results agree with the definition (oracle form 0) within the rounding of the
