@@ -159,9 +159,29 @@ KnnPlan knn_plan(int64_t na, int64_t nb, int d, int k, bool b_prepared) {
   return p;
 }
 
-void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const float* B, int64_t nb,
-             int d, int metric, int k, const Planes* b_planes, const SelectOut& out, hipStream_t st,
-             int stage_dist, int stage_select) {
+// Plan for n rows of A processed in pieces of at most `piece` rows: the work space covers the
+// full pieces and the shorter last one (a shorter piece may be laid out with more splits of B,
+// so its work space is not bounded by that of a longer one).
+KnnPlan knn_plan_pieces(int64_t n, int64_t piece, int64_t nb, int d, int k, bool b_prepared) {
+  KnnPlan p = knn_plan(std::min(n, piece), nb, d, k, b_prepared);
+  if (n > piece && n % piece != 0) {
+    const KnnPlan last = knn_plan(n % piece, nb, d, k, b_prepared);
+    p.bytes = std::max(p.bytes, last.bytes);
+  }
+  return p;
+}
+
+// `plan` must come from knn_plan / knn_plan_pieces for these shapes: a work space smaller than
+// what na rows need is refused here, before any kernel is launched on it.
+int knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const float* B, int64_t nb,
+            int d, int metric, int k, const Planes* b_planes, const SelectOut& out, hipStream_t st,
+            int stage_dist, int stage_select) {
+  {
+    const KnnPlan need = knn_plan(na, nb, d, k, b_planes != nullptr);
+    if (need.mfma != plan.mfma || (plan.mfma && need.bytes > plan.bytes))
+      return fail(VS_ERR_DEVICE, "k-nearest-rows: work space of %zu bytes planned, %zu needed for %lld rows",
+                  plan.bytes, need.bytes, (long long)na);
+  }
   if (plan.mfma) {
     size_t o = 0;
     Planes pa = carve_planes(ws + o, na, d); o += planes_bytes(na, d);
@@ -187,7 +207,7 @@ void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const fl
                     fb_count, fb_rows, fb_partial, st);
     }
     g_knn_mfma_rows += na;
-    return;
+    return VS_OK;
   }
   float* mat = reinterpret_cast<float*>(ws);
   u64* keys = reinterpret_cast<u64*>(ws + align_up((size_t)plan.rows * plan.cols * sizeof(float)));
@@ -210,6 +230,7 @@ void knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const fl
       }
     }
   }
+  return VS_OK;
 }
 
 }  // namespace
@@ -323,8 +344,9 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
     launch_fill_u64(keys, nq * k, 0xFFFFFFFFFFFFFFFFull, st);
     launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
   } else {
-    knn_run(plan, base, q, nq, x, nb, d, metric, k, nullptr, out, st, VS_STAGE_FLAT_DIST,
-            VS_STAGE_FLAT_SELECT);
+    if (int rc = knn_run(plan, base, q, nq, x, nb, d, metric, k, nullptr, out, st, VS_STAGE_FLAT_DIST,
+                         VS_STAGE_FLAT_SELECT))
+      return rc;
   }
   HIP_TRY(hipGetLastError());
   return VS_OK;
@@ -370,14 +392,16 @@ namespace {
 int nearest_rows(const float* A, int64_t n, const float* B, int64_t nb, int d, int metric,
                  int32_t* idx, float* val, Scratch& sc, hipStream_t st) {
   constexpr int64_t kPiece = 1 << 20;
-  const KnnPlan plan = knn_plan(std::min(n, kPiece), nb, d, 1, false);
+  const KnnPlan plan = knn_plan_pieces(n, kPiece, nb, d, 1, false);
   if (int rc = sc.reserve(plan.bytes)) return rc;
   for (int64_t i0 = 0; i0 < n; i0 += kPiece) {
     const int64_t ni = std::min(kPiece, n - i0);
     SelectOut o;
     o.idx32 = idx + i0;
     o.val = val ? val + i0 : nullptr;
-    knn_run(plan, static_cast<char*>(sc.p), A + i0 * d, ni, B, nb, d, metric, 1, nullptr, o, st, -1, -1);
+    if (int rc = knn_run(plan, static_cast<char*>(sc.p), A + i0 * d, ni, B, nb, d, metric, 1, nullptr, o,
+                         st, -1, -1))
+      return rc;
   }
   return VS_OK;
 }
@@ -596,7 +620,7 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
   // scratch: work space of the MFMA assignment (pieces of at most kAssignPiece vectors) |
   // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets
   constexpr int64_t kAssignPiece = 1 << 20;
-  KnnPlan plan = knn_plan(std::min(n, kAssignPiece), g.nlist, g.d, 1, ix->has_planes);
+  KnnPlan plan = knn_plan_pieces(n, kAssignPiece, g.nlist, g.d, 1, ix->has_planes);
   if (!plan.mfma) plan.bytes = 0;
   Carver cv;
   const size_t o_knn = cv.take(plan.bytes);
@@ -618,8 +642,9 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
       const int64_t ni = std::min(kAssignPiece, n - i0);
       SelectOut o;
       o.idx32 = pl->list_of + i0;
-      knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
-              ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1);
+      if (int rc = knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
+                           ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1))
+        return rc;
     }
   } else {
     launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
@@ -732,14 +757,14 @@ int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
 }
 
 // coarse quantizer: the npr best lists per query, best first, with their canon values
-static void coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
-                          int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st) {
+static int coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
+                         int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st) {
   SelectOut out;
   out.val = cdist;
   out.idx32 = probes;
-  knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
-          ix->has_planes ? &ix->c_planes : nullptr, out, st, VS_STAGE_COARSE_DIST,
-          VS_STAGE_COARSE_SELECT);
+  return knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
+                 ix->has_planes ? &ix->c_planes : nullptr, out, st, VS_STAGE_COARSE_DIST,
+                 VS_STAGE_COARSE_SELECT);
 }
 
 int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
@@ -753,7 +778,7 @@ int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t npro
   const int npr = std::min<int>(nprobe, ix->g.nlist);
   const KnnPlan plan = knn_plan(nq, ix->g.nlist, ix->g.d, npr, ix->has_planes);
   if (int rc = ix->scratch.reserve(plan.bytes)) return rc;
-  coarse_select(ix, plan, static_cast<char*>(ix->scratch.p), q, nq, npr, probes, coarse_dist, st);
+  if (int rc = coarse_select(ix, plan, static_cast<char*>(ix->scratch.p), q, nq, npr, probes, coarse_dist, st)) return rc;
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
@@ -787,7 +812,7 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   float* cdist = reinterpret_cast<float*>(base + o_cd);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
 
-  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st);
+  if (int rc = coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st)) return rc;
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
   // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
@@ -910,7 +935,7 @@ int vs_ivfflat_search(const vs_ivfflat* fx, const float* q, int64_t nq, int32_t 
   char* base = static_cast<char*>(ix->scratch.p);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
-  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st);
+  if (int rc = coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st)) return rc;
   {
     StageTimer t(VS_STAGE_SCAN, st);
     launch_ivfflat_scan(g.d, g.metric, q, nq, probes, npr, nsplit, ix->list_off,
@@ -1055,7 +1080,7 @@ int vs_ivfsq8_search(const vs_ivfsq8* sx, const float* q, int64_t nq, int32_t k,
   char* base = static_cast<char*>(ix->scratch.p);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
-  coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st);
+  if (int rc = coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, nullptr, st)) return rc;
   {
     StageTimer t(VS_STAGE_SCAN, st);
     launch_ivfsq8_scan(g.d, g.metric, q, nq, sx->vmin, sx->step, probes, npr, nsplit, ix->list_off,

@@ -965,11 +965,13 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   const int bm = p.kc ? 256 : 128, bn = p.kc ? 128 : 64;      // tile of one workgroup step
   p.kp = mfma_knn_kp(k);
   p.cap = std::max(64, 3 * p.kp);
-  // One 32-row block of A per wavefront: small enough in registers for two (operands split
-  // in head and tail) or three (operands exactly bf16) workgroups per CU, whose matrix-core
-  // and vector phases then overlap (measured faster than two row blocks per wavefront at
-  // half the occupancy).
-  p.RB = 1;
+  // Row blocks of A per wavefront.  Operands split in head and tail: one 32-row block (two
+  // workgroups per CU).  Operands exactly bf16: the fragments are half as many, and the
+  // collect sweep takes two row blocks per wavefront (still two workgroups per CU; half
+  // the tile traffic, LDS reads and barriers per product; measured 7-10 % faster than
+  // three workgroups per CU with one block) unless A is so short that the second block
+  // would be mostly padding.
+  p.RB = na >= 1024 ? 2 : 1;
   p.row_tiles = (na + bm - 1) / bm;
   const int64_t col_steps = std::max<int64_t>(1, (nb + bn - 1) / bn);
   int64_t ns;
@@ -978,15 +980,18 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
     ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
     ns = std::min<int64_t>(ns, 16);
   } else {
-    // Splits of B so that the workgroups come in full rounds at both occupancies (512 and
-    // 768 resident workgroups on the chip): which variant runs is decided on the device.
+    // Splits of B so that the workgroups come in full rounds for both variants of the
+    // collect sweep (which one runs is decided on the device): 128-row tiles on 512
+    // resident workgroups, and 256-row tiles on 512 or 128-row tiles on 768.
+    const int64_t tiles_b = p.RB == 2 ? (na + 255) / 256 : p.row_tiles;
+    const double slots_b = p.RB == 2 ? 512.0 : 768.0;
     ns = 1;
     double best = -1.0;
     const int64_t ns_max = std::min<int64_t>(24, std::max<int64_t>(1, col_steps / 8));
     for (int64_t c = 1; c <= ns_max; ++c) {
-      const double g = (double)(p.row_tiles * c);
-      const double e2 = g / (std::ceil(g / 512.0) * 512.0), e3 = g / (std::ceil(g / 768.0) * 768.0);
-      const double score = std::min(e2, e3);
+      const double ga = (double)(p.row_tiles * c), gb = (double)(tiles_b * c);
+      const double ea = ga / (std::ceil(ga / 512.0) * 512.0), eb = gb / (std::ceil(gb / slots_b) * slots_b);
+      const double score = std::min(ea, eb);
       if (score > best + 0.02) { best = score; ns = c; }
       if (best >= 0.9) break;                                   // good enough: no more splits
     }
@@ -1073,7 +1078,8 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(p.row_tiles * p.nsplit)), dim3(256), shmem, st, A.hi, A.lo,
+  const int64_t row_tiles = (A.n + 128 * RB - 1) / (128 * RB);   // (the lists are per row: any RB fits)
+  hipLaunchKernelGGL(kern, dim3((unsigned)(row_tiles * p.nsplit)), dim3(256), shmem, st, A.hi, A.lo,
                      A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
@@ -1086,7 +1092,8 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                            hipStream_t st) {
   // both operand-precision variants are enqueued; the kernel that does not match the flags
   // written by operand preparation returns immediately (the flags live in device memory)
-  launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
+  if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, false>(p, A, B, work, st);
+  else launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
   launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
 }
 

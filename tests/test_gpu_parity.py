@@ -620,6 +620,25 @@ def test_ivfflat_storage_beyond_four_billion_elements(vs):
     ix.close()
 
 
+def test_add_whose_last_piece_is_shorter_than_the_others(vs):
+    """One add of 2^20 + 931,328 vectors: the assignment runs in pieces of 2^20 rows and the
+    shorter last piece is laid out with more splits of the centroids than a full one, so its
+    work space is the larger of the two.  Every list probed must equal flat search."""
+    import torch
+    cfg = S.config("C4", nb=(1 << 20) + 931_328, nq=64, nlist=1024, d=32, M=8)
+    say("ivfflat add with a shorter last piece: nb=%d d=%d" % (cfg["nb"], cfg["d"]))
+    xd, qd = S.make_data_device(cfg)
+    cent, _ = S.make_index_params_device(cfg, xd)
+    ix = vs.IVFFlat(cfg["d"], L2, dev(cent))
+    ix.add(xd)
+    assert ix.ntotal == cfg["nb"] and int(ix.list_sizes().sum().item()) == cfg["nb"]
+    D, I = ix.search(qd, 10, 1024)
+    Df, If = vs.vs_flat_search(xd, qd, 10, L2)
+    assert torch.equal(D, Df)
+    assert (I == If).float().mean().item() > 0.99          # equal values may swap
+    ix.close()
+
+
 # ------------------------------------------------- k-means and parameter training
 
 KMEANS_CASES = [
