@@ -290,6 +290,12 @@ ROUTE_CASES = [
     ("unit_d96_k20", 15_000, 100, 96, 20, L2, "unit"),
     ("sift_d128_k100", 50_000, 100, 128, 100, L2, "sift"),
     ("tiny_nb_d32", 50, 10, 32, 40, L2, "gauss"),
+    # exactly-bf16 data and >= 1024 rows of A: the one-pass collect sweep with two row blocks per
+    # wavefront, at every d it is built for, with row counts that leave ragged 256-row tiles
+    ("sift_d32_k10_many_rows", 20_000, 1500, 32, 10, L2, "sift"),
+    ("sift_d64_k5_ip_many_rows", 12_000, 1111, 64, 5, IP, "sift"),
+    ("sift_d96_k30_many_rows", 15_000, 1025, 96, 30, L2, "sift"),
+    ("sift_d128_k100_many_rows", 25_000, 1300, 128, 100, L2, "sift"),
     # dimensions beyond 128: the tiled kernel (operands streamed in chunks of 32 dimensions)
     ("gauss_d256_k10", 20_000, 700, 256, 10, L2, "gauss"),
     ("gauss_d160_k100", 12_000, 130, 160, 100, L2, "gauss"),
