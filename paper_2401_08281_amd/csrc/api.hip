@@ -806,11 +806,13 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
   const size_t o_cd = cv.take((size_t)nq * npr * sizeof(float));
   const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  const size_t o_cnt = cv.take(sizeof(u64));
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
   float* cdist = reinterpret_cast<float*>(base + o_cd);
   u64* partial = reinterpret_cast<u64*>(base + o_part);
+  u64* counter = reinterpret_cast<u64*>(base + o_cnt);
 
   if (int rc = coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st)) return rc;
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
@@ -820,7 +822,7 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
     StageTimer t(VS_STAGE_SCAN, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
                           ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->cnorm,
-                          ix->ntotal, k, partial, ix->ids, out_dist, out_ids, st) != 0)
+                          ix->ntotal, k, partial, counter, ix->ids, out_dist, out_ids, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
   }
   if (nsplit > 1) {

@@ -63,11 +63,12 @@ void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_
 void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_t st);
 // nsplit > 1: partial[q][s][0..k) = k best keys (value, storage position) of the probes handled by
 // split s.  nsplit == 1: final results go straight to out_dist / out_ids (ids[position]).
+// counter: one 64-bit word of device memory the scan may use to hand out its work items.
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
                       const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
-                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
+                      u64* counter, const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 

@@ -501,7 +501,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
     const float* __restrict__ norms, const float* __restrict__ cnorm, int64_t ntotal, int k, int tot,
-    KeySink sink) {
+    KeySink sink, unsigned long long* __restrict__ next_item) {
   // METRIC 0: L2 with a table per (query, list); 1: inner product; 2: L2 through stored norms
   // (one table -2 <q_m, T_m[j]> per query; per list cdist - |c_l|^2 = |q|^2 - 2 <q, c_l>;
   // + |x'|^2 per code)
@@ -516,6 +516,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
   int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + NBUF * M * K);  // ppb
   int64_t* s_end = s_begin + ppb;                               // ppb
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
+  unsigned long long* s_item = reinterpret_cast<unsigned long long*>(bound + 1);   // the item in hand
 
   const int tid = threadIdx.x, wave = tid >> 6;
   const int m_own = tid / TPM, jj = tid % TPM;
@@ -535,7 +536,14 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jj + TPM * i) * DSUB + u];
   wait_all_global_loads();   // the codebook is in registers from here on
 
-  for (int64_t item = blockIdx.x; item < nitems; item += gridDim.x) {
+  // Items are handed out through a counter in memory (*next_item starts at 0), one at a time: the
+  // items of a batch differ in length (the sum of their lists), and with a fixed share per
+  // workgroup the launch would end with the unluckiest share.
+  for (;;) {
+    if (tid == 0) *s_item = atomicAdd(next_item, 1ull);
+    block_sync_lds();
+    const int64_t item = (int64_t)*s_item;
+    if (item >= nitems) break;
     const int64_t qi = item / nsplit;
     const int split = (int)(item % nsplit);
     const int p_begin = split * ppb;
@@ -771,7 +779,7 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
                             const float* codebooks, const int32_t* probes, const float* cdist,
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
                             const uint8_t* codes, const float* norms, const float* cnorm,
-                            int64_t ntotal, int k, int tot, KeySink sink, hipStream_t st) {
+                            int64_t ntotal, int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
   const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * 256 * sizeof(float) +
                        (size_t)ppb * 20 + 16;
   auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
@@ -784,9 +792,10 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, shmem) != hipSuccess || per_cu < 1)
     per_cu = 1;
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
+  launch_fill_u64(counter, 1, 0ull, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
                      probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, ntotal,
-                     k, tot, sink);
+                     k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
 }
 
 template <int M, int DSUB>
@@ -795,10 +804,10 @@ static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
                                 const float* norms, const float* cnorm, int mode, int64_t ntotal,
-                                int k, int tot, KeySink sink, hipStream_t st) {
+                                int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
 #define GO(MET, RR, NB)                                                                           \
   launch_scan_reg<M, DSUB, MET, RR, NB>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
-                                        nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, st)
+                                        nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, counter, st)
   const int r = select_regs_for_slots(tot);
   // L2 tables alternate between two buffers (one barrier per list); the single inner-product
   // table needs one.  A single L2 table with a third resident workgroup per CU measured
@@ -845,7 +854,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
                       const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
-                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
+                      u64* counter, const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return 0;
   // table form: 1 inner product; 2 L2 through the stored norms (norms non-null; cnorm = the
   // centroids' squared norms); 0 L2 with one table of squared residual distances per (query, list)
@@ -864,7 +873,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, tot, sink, st); \
+                                nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, tot, sink, counter, st); \
     return 0;                                                                                    \
   }
   REG(16, 8)   // PQ16x8 on d = 128
