@@ -161,6 +161,65 @@ IVF_CASES = {
 }
 
 
+def random_ivf_shapes(n_cases, seed):
+    """Seeded draws of small valid index shapes: every combination the launcher tells apart
+    (metric, code width, code size, sub-vector length, list length against the chunk size,
+    k against the selection's register variants) turns up among them."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for c in range(n_cases):
+        nbits = int(rng.choice([8, 8, 4]))
+        M = int(rng.choice([1, 2, 4, 8, 16, 32, 64] if nbits == 8 else [2, 4, 8, 16, 32, 64, 128]))
+        dsub = int(rng.choice([1, 2, 3, 4, 8, 12]))
+        while M * dsub > 768:
+            dsub = max(1, dsub // 2)
+        kind = str(rng.choice(["C1", "C3", "C4"]))             # gaussian / integer / unit-norm data
+        nlist = int(rng.choice([1, 3, 16, 50, 200]))
+        nb = int(rng.choice([300, 2_000, 9_000]))
+        cfg = S.config(kind, nb=nb, nq=int(rng.choice([1, 7, 40])), d=M * dsub, M=M, nbits=nbits, nlist=nlist,
+                       metric=int(rng.choice([L2, L2, IP])), ncomp=min(20, nb), seed=1000 + c)
+        k = int(rng.choice([1, 10, 100, 300]))
+        nprobe = int(min(nlist, rng.choice([1, 2, 8, 64])))
+        out.append((cfg, k, nprobe))
+    return out
+
+
+def test_random_shapes_match_oracle(vs, oracle):
+    """Forty seeded small indexes of mixed shapes: storage bit-exact, coarse stage bit-exact,
+    search results within the distance tolerance, for both L2 search types."""
+    for n, (cfg, k, nprobe) in enumerate(random_ivf_shapes(40, 20240127)):
+        say("random shape %d: %s nb=%d nq=%d d=%d M=%d nbits=%d nlist=%d metric=%d k=%d nprobe=%d" % (
+            n, cfg["kind"], cfg["nb"], cfg["nq"], cfg["d"], cfg["M"], cfg["nbits"], cfg["nlist"], cfg["metric"],
+            k, nprobe))
+        x, q = S.make_data(cfg)
+        cent, cb = S.make_index_params(cfg, x)
+        ix = vs.IVFPQ(cfg["d"], cfg["metric"], dev(cent), dev(cb), cfg["nbits"])
+        if cfg["metric"] == L2:
+            ix.set_search_type(vs.ST_STORED_NORMS)             # norms are stored by every add
+        orc = oracle.OracleIVFPQ(cfg["d"], cfg["metric"], cent, cb, cfg["nbits"])
+        bounds = np.linspace(0, x.shape[0], 2 + n % 3).astype(int)
+        for s0, e0 in zip(bounds[:-1], bounds[1:]):
+            ix.add(dev(x[s0:e0]))
+            orc.add(x[s0:e0])
+        check_storage(ix, orc)
+        xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
+        probes, cdist = ix.coarse(dev(q), nprobe)
+        po, co = oracle.coarse_probe(q, orc.centroids, nprobe, cfg["metric"])
+        np.testing.assert_array_equal(host(probes), po)
+        np.testing.assert_array_equal(host(cdist), co)
+        ix.set_search_type(vs.ST_RESIDUAL_TABLES)
+        D, I = ix.search(dev(q), k, nprobe)
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        if cfg["metric"] == L2:
+            ix.set_search_type(vs.ST_STORED_NORMS)
+            np.testing.assert_array_equal(host(ix.norms()), orc.norms)
+            cancel = (q.astype(np.float64) ** 2).sum(1) + float(orc.norms.max())
+            D, I = ix.search(dev(q), k, nprobe)
+            check_search(host(D).copy(), host(I).copy(), Do, Io, L2, cancel=cancel)
+        ix.close()
+
+
 @pytest.mark.parametrize("name", list(IVF_CASES))
 def test_ivfpq_matches_oracle(vs, oracle, name):
     cfg, searches = IVF_CASES[name]
