@@ -704,6 +704,51 @@ def test_add_whose_last_piece_is_shorter_than_the_others(vs):
     ix.close()
 
 
+def test_random_shapes_flat_ivfflat_ivfsq8_match_oracle(vs, oracle):
+    """Thirty seeded small problems of mixed shapes (d from 1 to 288, both routes of the distance
+    stage, tiled and untiled list scans, k from 1 to 1024): flat search, IVF-Flat and IVF-SQ8
+    against their oracles."""
+    rng = np.random.default_rng(20240128)
+    for n in range(30):
+        d = int(rng.choice([1, 3, 8, 30, 32, 64, 96, 100, 128, 160, 288]))
+        kind = str(rng.choice(["C1", "C3", "C4"]))
+        nb = int(rng.choice([1, 60, 3_000, 12_000]))
+        nq = int(rng.choice([1, 9, 130, 1_100]))
+        metric = int(rng.choice([L2, L2, IP]))
+        k = int(rng.choice([1, 10, 100, 1024]))
+        nlist = int(min(nb, rng.choice([1, 5, 40])))
+        nprobe = int(min(nlist, rng.choice([1, 4, 40])))
+        cfg = S.config(kind, nb=nb, nq=nq, d=d, nlist=nlist, metric=metric, ncomp=min(20, nb), seed=2000 + n,
+                       M=1, nbits=8)
+        say("random problem %d: %s nb=%d nq=%d d=%d metric=%d k=%d nlist=%d nprobe=%d" % (
+            n, kind, nb, nq, d, metric, k, nlist, nprobe))
+        x, q = S.make_data(cfg)
+        xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+        kk = min(k + EXTRA, max(nb, k))
+        D, I = vs.vs_flat_search(dev(x), dev(q), k, metric)
+        Do, Io = oracle.flat_search(x, q, kk, metric)
+        check_search(host(D), host(I), Do, Io, metric, q, xn)
+        cent = S.make_centroids(x, nlist, cfg["seed"])
+        fx = vs.IVFFlat(d, metric, dev(cent))
+        fo = oracle.OracleIVFFlat(d, metric, cent)
+        fx.add(dev(x)); fo.add(x)
+        D, I = fx.search(dev(q), k, nprobe)
+        Do, Io = fo.search(q, k + EXTRA, nprobe)
+        check_search(host(D), host(I), Do, Io, metric, q, xn)
+        fx.close()
+        vmin, step = oracle.sq8_params(x)
+        sx = vs.IVFSQ8(d, metric, dev(cent), dev(vmin), dev(step))
+        so = oracle.OracleIVFSQ8(d, metric, cent, vmin, step)
+        sx.add(dev(x)); so.add(x)
+        np.testing.assert_array_equal(host(sx.storage()[2]), so.codes)
+        xr = oracle.sq8_decode(so.codes, vmin, step)
+        xrn = np.sqrt((xr.astype(np.float64) ** 2).sum(1).max())
+        D, I = sx.search(dev(q), k, nprobe)
+        Do, Io = so.search(q, k + EXTRA, nprobe)
+        check_search(host(D), host(I), Do, Io, metric, q, xrn)
+        sx.close()
+
+
 # ------------------------------------------------- k-means and parameter training
 
 KMEANS_CASES = [
