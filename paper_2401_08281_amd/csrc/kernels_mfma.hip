@@ -974,11 +974,25 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   p.RB = na >= 1024 ? 2 : 1;
   p.row_tiles = (na + bm - 1) / bm;
   const int64_t col_steps = std::max<int64_t>(1, (nb + bn - 1) / bn);
+  // Most splits of B a plan may use: 16 resp. 24, and more when A is so short that those
+  // would leave most of the chip idle (a handful of queries against a long B) -- as long as
+  // the per-(row, split) lists stay within 256 MB.
+  const int64_t stride0 = p.kc ? 16 : std::max<int64_t>(1, std::min<int64_t>(16, col_steps / 192));
+  const double r0 = stride0 == 1 ? 0.0 : std::ceil((double)k / stride0 + 4.0 * std::sqrt((double)k / stride0) + 2.0);
+  const int64_t cap0 = stride0 == 1 ? p.cap
+                                    : std::max<int64_t>(64, (int64_t)std::ceil(1.15 * stride0 * (r0 + 5.5 * std::sqrt(r0) + 8.0)) + 16);
+  const int64_t slots = p.kc ? 256 : 512, ns_usual = p.kc ? 16 : 24;
+  int64_t ns_cap = ns_usual;
+  if (p.row_tiles * ns_usual < slots) {
+    ns_cap = (slots + p.row_tiles - 1) / p.row_tiles;
+    const int64_t by_memory = (int64_t)((256ull << 20) / ((size_t)na * cap0 * sizeof(u64)));
+    ns_cap = std::max(ns_usual, std::min(ns_cap, by_memory));
+  }
   int64_t ns;
   if (p.kc) {   // 256 resident workgroups
     ns = std::max<int64_t>(1, 256 / p.row_tiles);
     ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
-    ns = std::min<int64_t>(ns, 16);
+    ns = std::min<int64_t>(ns, ns_cap);
   } else {
     // Splits of B so that the workgroups come in full rounds for both variants of the
     // collect sweep (which one runs is decided on the device): 128-row tiles on 512
@@ -987,7 +1001,7 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
     const double slots_b = p.RB == 2 ? 512.0 : 768.0;
     ns = 1;
     double best = -1.0;
-    const int64_t ns_max = std::min<int64_t>(24, std::max<int64_t>(1, col_steps / 8));
+    const int64_t ns_max = std::min<int64_t>(ns_cap, std::max<int64_t>(1, col_steps / 8));
     for (int64_t c = 1; c <= ns_max; ++c) {
       const double ga = (double)(p.row_tiles * c), gb = (double)(tiles_b * c);
       const double ea = ga / (std::ceil(ga / 512.0) * 512.0), eb = gb / (std::ceil(gb / slots_b) * slots_b);
