@@ -988,10 +988,13 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
     const int64_t by_memory = (int64_t)((256ull << 20) / ((size_t)na * cap0 * sizeof(u64)));
     ns_cap = std::max(ns_usual, std::min(ns_cap, by_memory));
   }
+  // ... and at least 8 tiles of B per split, unless that leaves fewer than 128 workgroups
+  int64_t by_length = std::max<int64_t>(1, col_steps / 8);
+  if (p.row_tiles * by_length < 128) by_length = std::max(by_length, std::min<int64_t>(col_steps, 128 / p.row_tiles));
   int64_t ns;
   if (p.kc) {   // 256 resident workgroups
     ns = std::max<int64_t>(1, 256 / p.row_tiles);
-    ns = std::min(ns, std::max<int64_t>(1, col_steps / 8));
+    ns = std::min(ns, by_length);
     ns = std::min<int64_t>(ns, ns_cap);
   } else {
     // Splits of B so that the workgroups come in full rounds for both variants of the
@@ -1001,7 +1004,7 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
     const double slots_b = p.RB == 2 ? 512.0 : 768.0;
     ns = 1;
     double best = -1.0;
-    const int64_t ns_max = std::min<int64_t>(ns_cap, std::max<int64_t>(1, col_steps / 8));
+    const int64_t ns_max = std::min<int64_t>(ns_cap, by_length);
     for (int64_t c = 1; c <= ns_max; ++c) {
       const double ga = (double)(p.row_tiles * c), gb = (double)(tiles_b * c);
       const double ea = ga / (std::ceil(ga / 512.0) * 512.0), eb = gb / (std::ceil(gb / slots_b) * slots_b);
