@@ -79,9 +79,9 @@ def main():
                          "--pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (every box here has one); "
-              "--gpus %d is not supported. See DESIGN.md for how the path would shard." % args.gpus,
-              file=sys.stderr)
+        print("bench.py: this library runs on ONE GPU; --gpus %d is not supported (to use several, "
+              "shard the stored vectors by id over one process per GPU and merge the k best of each)."
+              % args.gpus, file=sys.stderr)
         return 2
 
     import numpy as np
