@@ -161,6 +161,42 @@ IVF_CASES = {
 }
 
 
+def test_search_can_be_captured_in_a_hip_graph(vs):
+    """The search entry points only enqueue kernels on the caller's stream (after a warm-up has
+    grown the scratch buffers): captured in a graph, every replay on new queries must return
+    what the eager call returns, with eager work and synchronisations between the replays."""
+    import torch
+    cfg = S.config("C3", nb=100_000, nq=512, ncomp=100, nlist=512)
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x))
+    qd = dev(q)
+    for nq in (1, 128):
+        say("graph capture of ivfpq search, nq=%d" % nq)
+        qs = qd[:nq].contiguous().clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                ix.search(qs, 10, 16)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            Dg, Ig = ix.search(qs, 10, 16)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            qs.copy_(qd[rep * nq:(rep + 1) * nq])
+            g.replay()
+            torch.cuda.synchronize()
+            De, Ie = ix.search(qs, 10, 16)
+            Df, If = vs.vs_flat_search(dev(x[:1000]), qs, 5, L2)     # unrelated eager work in between
+            torch.cuda.synchronize()
+            assert torch.equal(Dg, De) and torch.equal(Ig, Ie), "replay %d differs from the eager search" % rep
+    ix.close()
+
+
 def random_ivf_shapes(n_cases, seed):
     """Seeded draws of small valid index shapes: every combination the launcher tells apart
     (metric, code width, code size, sub-vector length, list length against the chunk size,
