@@ -1023,9 +1023,9 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   // probability (rows that end up with fewer, or with more than their lists hold, fail the
   // re-rank test and are recomputed).
   if (p.kc) {
-    p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, steps_per_split / 32));
-    // (long rows make a sweep expensive: the tiled kernel samples from 16384 columns on)
-    p.stride = (int)std::max<int64_t>(p.stride, std::min<int64_t>(4, nb / 4096));
+    // (long rows make a sweep expensive: the tiled kernel samples as soon as 1024 columns
+    // remain in the sample; measured on 16384 and 200000 columns: S = 16 beats 8, 4 and 2)
+    p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, nb / 1024));
   } else {
     // (independent of the number of splits; measured flat between half and twice this)
     p.stride = (int)std::max<int64_t>(1, std::min<int64_t>(16, col_steps / 192));
