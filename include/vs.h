@@ -312,6 +312,19 @@ VS_API int vs_set_option(const char* name, double value);
  * pointer to 2 int64).  Synchronises the device. */
 VS_API int vs_counters_read(int64_t* counters);
 
+/* Bytes of device scratch that one exact k-nearest-rows problem takes inside the
+ * library (Sec. 3.1: brute-force search; the same routine serves the coarse
+ * quantizer of Sec. 5.1 and the list assignment of add): na rows against nb rows
+ * of dimension d, k results per row, processed in pieces of at most `piece` rows
+ * (piece <= 0: one piece).  b_prepared != 0: the nb rows are an index's centroids,
+ * prepared once at creation.  Host arithmetic only -- no device call, usable
+ * without a GPU -- so a caller can budget memory before a search or an add.
+ * The figure covers every piece, also a shorter last one (which may be laid out
+ * with more splits of the nb rows than a full piece).  Returns -1 on invalid
+ * arguments (na < 0, nb < 0, d < 1, k < 1). */
+VS_API int64_t vs_knn_workspace_bytes(int64_t na, int64_t nb, int32_t d, int32_t k, int64_t piece,
+                                      int32_t b_prepared);
+
 /* Message of the calling thread's most recent error ("" if none). */
 VS_API const char* vs_last_error(void);
 

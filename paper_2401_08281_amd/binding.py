@@ -38,6 +38,8 @@ def lib():
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
     L.vs_trim.restype = ctypes.c_int
     L.vs_trim.argtypes = []
+    L.vs_knn_workspace_bytes.restype = i64
+    L.vs_knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i64, i32]
     L.vs_ivfpq_set_search_type.restype = ctypes.c_int
     L.vs_ivfpq_set_search_type.argtypes = [vp, i32]
     L.vs_ivfpq_get_norms.restype = ctypes.c_int
@@ -164,6 +166,14 @@ def vs_trim():
 
 def vs_set_option(name, value):
     _check(lib().vs_set_option(name.encode(), float(value)))
+
+
+def vs_knn_workspace_bytes(na, nb, d, k, piece=0, b_prepared=False):
+    """Device scratch of one k-nearest-rows problem, in bytes (host arithmetic only)."""
+    r = int(lib().vs_knn_workspace_bytes(int(na), int(nb), int(d), int(k), int(piece), int(bool(b_prepared))))
+    if r < 0:
+        raise VSError(-1, lib().vs_last_error().decode())
+    return r
 
 
 def vs_counters_read():

@@ -306,6 +306,19 @@ int vs_set_option(const char* name, double value) {
   return fail(VS_ERR_INVALID_ARG, "vs_set_option: unknown option '%s'", name);
 }
 
+int64_t vs_knn_workspace_bytes(int64_t na, int64_t nb, int32_t d, int32_t k, int64_t piece,
+                               int32_t b_prepared) {
+  if (na < 0 || nb < 0 || d < 1 || k < 1) {
+    fail(VS_ERR_INVALID_ARG, "vs_knn_workspace_bytes: na = %lld, nb = %lld, d = %d, k = %d", (long long)na,
+         (long long)nb, d, k);
+    return -1;
+  }
+  if (na == 0) return 0;
+  const KnnPlan p = piece > 0 ? knn_plan_pieces(na, piece, nb, d, k, b_prepared != 0)
+                              : knn_plan(na, nb, d, k, b_prepared != 0);
+  return (int64_t)p.bytes;
+}
+
 int vs_counters_read(int64_t* counters) {
   if (!counters) return fail(VS_ERR_INVALID_ARG, "vs_counters_read: null pointer");
   HIP_TRY(hipDeviceSynchronize());

@@ -123,3 +123,32 @@ def test_binding_rejects_host_tensors():
     import paper_2401_08281_amd as vs
     with pytest.raises(TypeError):
         vs.vs_flat_search(torch.zeros(4, 2), torch.zeros(1, 2), 1)
+
+
+def test_knn_workspace_covers_every_piece_size():
+    """The scratch planned for n rows in pieces must hold every piece that will run -- the full
+    ones and the shorter last one, which may be laid out with more splits than a full piece
+    (host arithmetic only: no GPU).  Checked over seeded random shapes and on the shape that
+    once wrote past a buffer planned from the full piece alone."""
+    import numpy as np
+    import paper_2401_08281_amd as vs
+    rng = np.random.default_rng(5)
+    cases = [((1 << 20) + 931_328, 1 << 20, 1024, 96, 1, True)]
+    for _ in range(300):
+        piece = int(rng.choice([1 << 10, 1 << 14, 1 << 17, 1 << 20]))
+        n = int(rng.integers(1, 5 * piece))
+        nb = int(rng.choice([1, 7, 256, 1024, 4096, 65536, 1_000_000]))
+        d = int(rng.choice([4, 30, 32, 64, 96, 128, 160, 768]))
+        k = int(rng.choice([1, 10, 64, 100, 150, 151, 1024]))
+        cases.append((n, piece, nb, d, k, bool(rng.integers(0, 2))))
+    for n, piece, nb, d, k, prepared in cases:
+        planned = vs.vs_knn_workspace_bytes(n, nb, d, k, piece, prepared)
+        sizes = {min(n, piece)}
+        if n > piece and n % piece:
+            sizes.add(n % piece)
+        for m in sizes:
+            need = vs.vs_knn_workspace_bytes(m, nb, d, k, 0, prepared)
+            assert planned >= need, (n, piece, nb, d, k, prepared, m, planned, need)
+    assert vs.vs_knn_workspace_bytes(0, 10, 8, 1) == 0
+    with pytest.raises(vs.VSError):
+        vs.vs_knn_workspace_bytes(10, 10, 0, 1)
