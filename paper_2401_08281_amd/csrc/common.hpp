@@ -316,6 +316,58 @@ __device__ __forceinline__ float canon_row(const float* __restrict__ qs, const f
   return acc;
 }
 
+// The same value for 64 rows at once, one per lane of a wavefront, with memory read in runs of
+// 128 bytes (d a multiple of 32): per chunk of 32 dimensions eight lanes fetch the 128 bytes
+// of one row (8 rows per load instruction), the chunk goes through a wavefront-private LDS
+// tile (row stride 36 floats: aligned, conflict-free) and lane r continues the chain of row
+// `row` of lane r in dimension order; the next chunk is in flight in registers meanwhile.
+// row: any valid row of B in every lane (lanes without a row pass 0 and drop the result).
+// ids_s: 64 int64 and tile: 64 * 36 floats of LDS owned by this wavefront.
+template <int METRIC>
+__device__ __forceinline__ float wave_canon_rows_tiled(const float* __restrict__ qs,
+                                                       const float* __restrict__ B, int d, int64_t row,
+                                                       int64_t* __restrict__ ids_s,
+                                                       float* __restrict__ tile) {
+  constexpr int DC = 32, LD = 36;
+  const int lane = lane_id(), r_ld = lane >> 3, c_ld = lane & 7;
+  wave_lds_sync();                                   // earlier users of ids_s and the tile are done
+  ids_s[lane] = row;
+  wave_lds_sync();
+  const float* rp[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) rp[i] = B + ids_s[r_ld + 8 * i] * d + c_ld * 4;
+  u32x4 stg[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(rp[i]);
+  float acc = 0.f;
+  const int nch = d / DC;
+  for (int ch = 0; ch < nch; ++ch) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<u32x4*>(tile + (r_ld + 8 * i) * LD + c_ld * 4) = stg[i];
+    wave_lds_sync();
+    if (ch + 1 < nch) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(rp[i] + (ch + 1) * DC);
+    }
+    const float* __restrict__ tr = tile + lane * LD;
+    const float* __restrict__ qc = qs + ch * DC;
+#pragma unroll
+    for (int cc = 0; cc < DC / 4; ++cc) {
+      const float4 xv = *reinterpret_cast<const float4*>(tr + cc * 4);
+      const float4 qv = *reinterpret_cast<const float4*>(qc + cc * 4);
+      const float xs[4] = {xv.x, xv.y, xv.z, xv.w}, qq[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (METRIC == 0) { const float diff = qq[u] - xs[u]; acc = __builtin_fmaf(diff, diff, acc); }
+        else acc = __builtin_fmaf(qq[u], xs[u], acc);
+      }
+    }
+    wave_lds_sync();                                 // the tile is free for the next chunk
+  }
+  return acc;
+}
+
 // ---- merge of sorted key lists by ranking -----------------------------------
 // `nl` ascending lists of k keys each (padded with KEY_EMPTY) sit at
 // base + w * stride.  Keys are unique, so the number of keys smaller than x over

@@ -764,6 +764,8 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   const u64 tkey = ws.s[kp - 1];                                // kp-th best approximate key
 
   // canon value of every shortlisted row, then an exact sort
+  // (one row per lane, R rows in flight per lane: staging 64 rows at a time through an LDS
+  // tile, as the refinement kernel does, measured slower here)
   u64 v[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {

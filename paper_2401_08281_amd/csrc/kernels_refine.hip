@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void refine_tiled_kernel(const float* __restri
                                                            const int64_t* __restrict__ cand, int kc, int k,
                                                            int tot, float* __restrict__ out_dist,
                                                            int64_t* __restrict__ out_ids) {
-  constexpr int DC = 32, LD = 36;
+  constexpr int LD = 36;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int64_t qi = blockIdx.x * 4ll + wave;
@@ -72,47 +72,12 @@ __global__ __launch_bounds__(256) void refine_tiled_kernel(const float* __restri
   for (int t = lane; t < d; t += VS_WAVE) qs[t] = q[qi * d + t];
   WaveSelect<R> ws;
   ws.init(slots, tot, k);
-  const int r_ld = lane >> 3, c_ld = lane & 7;                  // fetch: 8 lanes per row, 8 rows per pass
-  const int nch = d / DC;
   const int64_t* __restrict__ c = cand + qi * (int64_t)kc;
   for (int j0 = 0; j0 < kc; j0 += VS_WAVE) {
     const int j = j0 + lane;
     const int64_t id = j < kc ? c[j] : -1;
     const bool valid = id >= 0 && id < nb;          // empty slots of the first stage are skipped
-    wave_lds_sync();                                 // the previous group is done with ids_s and the tile
-    ids_s[lane] = valid ? id : 0;
-    wave_lds_sync();
-    const float* rp[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) rp[i] = x + ids_s[r_ld + 8 * i] * d + c_ld * 4;
-    u32x4 stg[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(rp[i]);
-    float acc = 0.f;
-    for (int ch = 0; ch < nch; ++ch) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4*>(tile + (r_ld + 8 * i) * LD + c_ld * 4) = stg[i];
-      wave_lds_sync();
-      if (ch + 1 < nch) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(rp[i] + (ch + 1) * DC);
-      }
-      const float* __restrict__ tr = tile + lane * LD;
-      const float* __restrict__ qc = qs + ch * DC;
-#pragma unroll
-      for (int cc = 0; cc < DC / 4; ++cc) {
-        const float4 xv = *reinterpret_cast<const float4*>(tr + cc * 4);
-        const float4 qv = *reinterpret_cast<const float4*>(qc + cc * 4);
-        const float xs[4] = {xv.x, xv.y, xv.z, xv.w}, qq[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (METRIC == 0) { const float diff = qq[u] - xs[u]; acc = __builtin_fmaf(diff, diff, acc); }
-          else acc = __builtin_fmaf(qq[u], xs[u], acc);
-        }
-      }
-      wave_lds_sync();                               // the tile is free for the next chunk
-    }
+    const float acc = wave_canon_rows_tiled<METRIC>(qs, x, d, valid ? id : 0, ids_s, tile);
     ws.push(valid, make_key(acc, (u32)id, METRIC));
   }
   ws.finish();
