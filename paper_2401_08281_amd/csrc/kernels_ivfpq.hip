@@ -477,6 +477,15 @@ struct CodeWords {           // one PQ code of M bytes held in registers
     for (int i = 0; i < W; ++i) dist = adc_bytes<8>(lut, w[i], 4 * i, dist);
     return dist;
   }
+  // the same for tables whose rows are KP floats apart
+  template <int KP>
+  __device__ __forceinline__ float adc_rows(const float* __restrict__ lut, float dist) const {
+#pragma unroll
+    for (int i = 0; i < W; ++i)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) dist += lut[(4 * i + b) * KP + ((w[i] >> (8 * b)) & 0xFFu)];
+    return dist;
+  }
 };
 
 #ifdef VS_SCAN_TIMING
@@ -508,12 +517,16 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
   constexpr int K = 256, D = M * DSUB;
   constexpr int KEY_METRIC = METRIC == 1 ? 1 : 0;
   constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
+  // Rows of a table are K + TPM floats apart: the lanes of a wavefront store entries of 64 / TPM
+  // consecutive sub-quantizers at the same column, and with rows a multiple of 256 bytes apart
+  // those stores would all fall into the same TPM banks.
+  constexpr int KP = K + TPM;
   static_assert(256 % M == 0 && M % 4 == 0, "M must divide 256 and codes are read as 32-bit words");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
   u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
-  float* lut0 = reinterpret_cast<float*>(bound + 2);            // NBUF x M * K
-  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + NBUF * M * K);  // ppb
+  float* lut0 = reinterpret_cast<float*>(bound + 2);            // NBUF x M * KP
+  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + NBUF * M * KP);  // ppb
   int64_t* s_end = s_begin + ppb;                               // ppb
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
   unsigned long long* s_item = reinterpret_cast<unsigned long long*>(bound + 1);   // the item in hand
@@ -568,7 +581,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
         float acc = 0.f;
 #pragma unroll
         for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qm[u], T[i * DSUB + u], acc);
-        lut0[m_own * K + jj + TPM * i] = METRIC == 2 ? -2.f * acc : acc;
+        lut0[m_own * KP + jj + TPM * i] = METRIC == 2 ? -2.f * acc : acc;
       }
     }
     block_sync_lds();   // probes, bound and the IP table are visible
@@ -600,7 +613,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     }
     TICK(1);
     for (int p = 0; p < np; ++p) {
-      float* __restrict__ lut = (METRIC == 0 && NBUF == 2) ? lut0 + (p & 1) * (M * K) : lut0;
+      float* __restrict__ lut = (METRIC == 0 && NBUF == 2) ? lut0 + (p & 1) * (M * KP) : lut0;
       const int64_t end = s_end[p];
       // requests for the next iteration (the last iteration re-requests its own list)
       const int pn = min(p + 1, np - 1);
@@ -625,7 +638,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
             const float diff = r[u] - T[i * DSUB + u];
             acc = __builtin_fmaf(diff, diff, acc);
           }
-          lut[m_own * K + jj + TPM * i] = acc;
+          lut[m_own * KP + jj + TPM * i] = acc;
         }
         TICK(2);
         block_sync_lds();   // table p visible; scan p - 1 (on the other buffer) finished everywhere
@@ -645,7 +658,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
           cw2.load(codes + min(i2, last) * M);
           if (METRIC == 2) nrm2 = norms[min(i2, last)];
         }
-        const float dist = v_cur ? cw.adc(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
+        const float dist = v_cur ? cw.template adc_rows<KP>(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
         ws.push(v_cur, make_key(dist, (u32)i_cur, KEY_METRIC), true);
         if (!more) break;
         cw = cw2; nrm = nrm2; i_cur = i2; v_cur = v2;
@@ -780,7 +793,7 @@ static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, cons
                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
                             const uint8_t* codes, const float* norms, const float* cnorm,
                             int64_t ntotal, int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
-  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * 256 * sizeof(float) +
+  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * (256 + 256 / M) * sizeof(float) +
                        (size_t)ppb * 20 + 16;
   auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
   if (shmem > 48 * 1024)
@@ -869,7 +882,8 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)g.d * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
-  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + (size_t)ppb * 20 + 32;  // two tables
+  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + 2 * 256 * sizeof(float) +
+                           (size_t)ppb * 20 + 32;   // two tables, their rows padded
 #define REG(MM, DS)                                                                              \
   if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
     launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
