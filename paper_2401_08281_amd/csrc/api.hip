@@ -406,6 +406,16 @@ int nearest_rows(const float* A, int64_t n, const float* B, int64_t nb, int d, i
                  int32_t* idx, float* val, Scratch& sc, hipStream_t st) {
   constexpr int64_t kPiece = 1 << 20;
   const KnnPlan plan = knn_plan_pieces(n, kPiece, nb, d, 1, false);
+  if (!plan.mfma) {
+    // shapes the matrix-core kernels do not cover (sub-vectors of a few dimensions): fused canon
+    // distance + arg-best tiles, one 64-bit key (value, row of B) per row of A
+    if (int rc = sc.reserve((size_t)n * sizeof(u64))) return rc;
+    u64* keys = static_cast<u64*>(sc.p);
+    launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
+    launch_canon_argbest(A, n, B, nb, d, metric, keys, st);
+    launch_keys_to_probes(keys, n, metric, idx, val, st);
+    return VS_OK;
+  }
   if (int rc = sc.reserve(plan.bytes)) return rc;
   for (int64_t i0 = 0; i0 < n; i0 += kPiece) {
     const int64_t ni = std::min(kPiece, n - i0);

@@ -13,34 +13,102 @@ namespace {
 // it in ascending order; lane t adds up dimensions t, t + 64, ... of those vectors in
 // float64, in that order -- a fixed order, so the sum has one value however the kernel is
 // scheduled -- and stores sum / count rounded to fp32.  A centroid without vectors is left
-// as it is.  Dimensions are taken 256 at a time.
+// as it is.  Dimensions are taken 64 * NC at a time (NC = 1, 2 or 4).
+// The chain of a large cluster is long (it sets the kernel's time), so the memory latency
+// is taken off it: 64 / NC vectors at a time, their numbers come in with one load, their
+// rows are all requested before the first is added, and the additions then run in the
+// list's order.
+template <int NC>
 __global__ __launch_bounds__(256) void segmented_mean_kernel(const float* __restrict__ x, int d,
                                                              const int32_t* __restrict__ order,
                                                              const int64_t* __restrict__ off, int K,
                                                              float* __restrict__ centroids) {
+  constexpr int NB = 64 / NC;
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int64_t j = blockIdx.x * 4ll + wave;
   if (j >= K) return;
   const int64_t b = off[j], e = off[j + 1];
   if (b == e) return;
   const double count = (double)(e - b);
-  for (int t0 = 0; t0 < d; t0 += 256) {
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-    for (int64_t i = b; i < e; ++i) {
+  for (int t0 = 0; t0 < d; t0 += 64 * NC) {
+    double acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] = 0.0;
+    int64_t i = b;
+    for (; i + NB <= e; i += NB) {
+      const int32_t mine = order[i + (lane & (NB - 1))];
+      float v[NB][NC];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const float* __restrict__ row = x + (int64_t)__shfl(mine, u) * d + t0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          const int t = lane + 64 * c;
+          v[u][c] = t0 + t < d ? row[t] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] += (double)v[u][c];
+    }
+    for (; i < e; ++i) {
       const float* __restrict__ row = x + (int64_t)order[i] * d + t0;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < NC; ++c) {
         const int t = lane + 64 * c;
         if (t0 + t < d) acc[c] += (double)row[t];
       }
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const int t = t0 + lane + 64 * c;
       if (t < d) centroids[j * d + t] = (float)(acc[c] / count);
     }
   }
+}
+
+// The same for rows of at most 32 floats (the sub-vectors of a product quantizer), where one
+// row per load instruction would leave most lanes idle: lane (s, t) = (lane / DP, lane % DP)
+// reads dimension t of every (64 / DP)-th vector, so one load instruction fetches 64 / DP
+// rows and a batch of 16 instructions 16 * 64 / DP vectors; the chain of dimension t then
+// takes the values in the list's order through cross-lane reads (it is kept in every group
+// s alike).  DP: d rounded up to 8, 16 or 32.
+template <int DP>
+__global__ __launch_bounds__(256) void segmented_mean_small_kernel(const float* __restrict__ x, int d,
+                                                                   const int32_t* __restrict__ order,
+                                                                   const int64_t* __restrict__ off, int K,
+                                                                   float* __restrict__ centroids) {
+  constexpr int VPL = 64 / DP, NU = 16, NBV = NU * VPL;          // vectors per load, loads and vectors per batch
+  constexpr int NO = (NBV + 63) / 64;                            // registers of vector numbers per batch
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int s = lane / DP, t = lane % DP;
+  const int64_t j = blockIdx.x * 4ll + wave;
+  if (j >= K) return;
+  const int64_t b = off[j], e = off[j + 1];
+  if (b == e) return;
+  const double count = (double)(e - b);
+  double acc = 0.0;
+  int64_t i = b;
+  for (; i + NBV <= e; i += NBV) {
+    int32_t mine[NO];
+#pragma unroll
+    for (int o = 0; o < NO; ++o) mine[o] = (64 * o + lane) < NBV ? order[i + 64 * o + lane] : 0;
+    float v[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int w = u * VPL + s;                                 // this lane's vector of load u: number w of the batch
+      const int32_t r = __shfl(mine[(u * VPL) / 64], w & 63);    // (a load's vectors sit in one register of numbers)
+      v[u] = t < d ? x[(int64_t)r * d + t] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+#pragma unroll
+      for (int s2 = 0; s2 < VPL; ++s2) acc += (double)__shfl(v[u], s2 * DP + t);
+  }
+  for (; i < e; ++i)                                             // the rest, one vector at a time
+    if (t < d) acc += (double)x[(int64_t)order[i] * d + t];
+  if (s == 0 && t < d) centroids[j * d + t] = (float)(acc / count);
 }
 
 // out[m][i][u] = x[i][m * dsub + u] - centroids[list_of[i]][m * dsub + u]: the residual of
@@ -65,8 +133,13 @@ __global__ __launch_bounds__(256) void residual_slices_kernel(const float* __res
 void launch_segmented_mean(const float* x, int d, const int32_t* order, const int64_t* off, int K,
                            float* centroids, hipStream_t st) {
   if (K <= 0) return;
-  hipLaunchKernelGGL(segmented_mean_kernel, dim3((unsigned)((K + 3) / 4)), dim3(256), 0, st, x, d,
-                     order, off, K, centroids);
+  const dim3 grid((unsigned)((K + 3) / 4)), block(256);
+  if (d <= 8) hipLaunchKernelGGL((segmented_mean_small_kernel<8>), grid, block, 0, st, x, d, order, off, K, centroids);
+  else if (d <= 16) hipLaunchKernelGGL((segmented_mean_small_kernel<16>), grid, block, 0, st, x, d, order, off, K, centroids);
+  else if (d <= 32) hipLaunchKernelGGL((segmented_mean_small_kernel<32>), grid, block, 0, st, x, d, order, off, K, centroids);
+  else if (d <= 64) hipLaunchKernelGGL((segmented_mean_kernel<1>), grid, block, 0, st, x, d, order, off, K, centroids);
+  else if (d <= 128) hipLaunchKernelGGL((segmented_mean_kernel<2>), grid, block, 0, st, x, d, order, off, K, centroids);
+  else hipLaunchKernelGGL((segmented_mean_kernel<4>), grid, block, 0, st, x, d, order, off, K, centroids);
 }
 
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,

@@ -794,6 +794,10 @@ KMEANS_CASES = [
     ("unit_d96_k300", 30_000, 96, 300, 3, "unit"),
     ("subvectors_d4_k256", 20_000, 4, 256, 4, "gauss"),       # a sub-quantizer's shape: canon tiles
     ("odd_d30_k7", 3_001, 30, 7, 6, "gauss"),
+    # large clusters of short rows: the update kernel that reads several rows per load
+    ("subvectors_d8_k16", 30_000, 8, 16, 3, "gauss"),
+    ("subvectors_d12_k20", 20_000, 12, 20, 3, "gauss"),
+    ("subvectors_d3_k8", 9_000, 3, 8, 3, "gauss"),
     ("more_centroids_than_vectors", 40, 8, 64, 2, "gauss"),
 ]
 
