@@ -46,6 +46,7 @@ __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
 // One lane per 8 consecutive elements (d % 8 == 0), 256 lanes per workgroup,
 // 2048 / d rows per group; a workgroup walks over groups and reports its flags
 // and largest norm once at the end.  Row sums are added in a fixed order.
+// The planes are [n_pad][d] row-major.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, int64_t n,
                                                    int64_t n_pad, int d, int rows_per_group,
@@ -108,6 +109,94 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
       max_bits = max(max_bits, __float_as_uint(sum));        // sum >= 0: bit order = value order
     } else if (tid < rows_per_group && row0 + tid < n_pad) {
       norm[row0 + tid] = 0.f;
+    }
+  }
+  __syncthreads();
+  if (!is_int) flags[0] = 0u;
+  if (!is_bf16) flags[1] = 0u;
+  if (!is_nonneg) flags[2] = 0u;
+  if (max_bits) atomicMax(&flags[3], max_bits);
+  __syncthreads();
+  if (tid == 0) {
+    if (!flags[0]) atomicAnd(&info->all_int, 0u);
+    if (!flags[1]) atomicAnd(&info->all_bf16, 0u);
+    if (!flags[2]) atomicAnd(&info->all_nonneg, 0u);
+    if (flags[3]) atomicMax(&info->max_norm_bits, flags[3]);
+  }
+}
+
+// The same preparation for the tiled kernel, which wants the planes as d / 16 panels of
+// [n_pad][16]: elements k0 .. k0 + 15 of all rows lie together, so that a block of 32 rows x
+// 16 elements -- one MFMA operand -- is 1 KB of consecutive memory.  A workgroup takes 32
+// rows at a time: lane (r, s) = (tid % 32, tid / 32) converts chunks s, s + 8, ... of row r,
+// so a wavefront writes one whole block (32 rows x 32 bytes, consecutive) per store and
+// reads 64-byte runs of 32 rows; the eight partial sums of a row are added in a fixed order.
+__global__ __launch_bounds__(256) void prep_panel_kernel(const float* __restrict__ x, int64_t n,
+                                                         int64_t n_pad, int d,
+                                                         unsigned short* __restrict__ hi,
+                                                         unsigned short* __restrict__ lo,
+                                                         float* __restrict__ norm,
+                                                         PrepInfo* __restrict__ info) {
+  __shared__ float part[2][8][32];
+  __shared__ u32 flags[4];
+  const int cpr = d / 8;
+  const int tid = threadIdx.x, r = tid & 31, s = tid >> 5;
+  if (tid < 3) flags[tid] = 1u;
+  if (tid == 3) flags[3] = 0u;
+  bool is_int = true, is_bf16 = true, is_nonneg = true;
+  u32 max_bits = 0u;
+  const int64_t nblocks = n_pad / 32;
+  int pb = 0;
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x, pb ^= 1) {
+    const int64_t row = b * 32 + r;
+    float ss = 0.f;
+    if (row < n) {
+#pragma unroll 4
+      for (int c = s; c < cpr; c += 8) {
+        const int64_t off = row * d + c * 8;
+        float v[8];
+        const float4 a = *reinterpret_cast<const float4*>(x + off);
+        const float4 bq = *reinterpret_cast<const float4*>(x + off + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = bq.x; v[5] = bq.y; v[6] = bq.z; v[7] = bq.w;
+        unsigned short h[8], l[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          h[t] = bf16_rn_bits(v[t]);
+          const float rem = v[t] - bf16_bits_to_f32(h[t]);      // exact in fp32
+          l[t] = bf16_rn_bits(rem);
+          is_bf16 = is_bf16 && rem == 0.f;
+          is_int = is_int && v[t] == __builtin_rintf(v[t]);
+          is_nonneg = is_nonneg && v[t] >= 0.f;
+          ss = __builtin_fmaf(v[t], v[t], ss);
+        }
+        uint4 hv, lv;
+        hv.x = h[0] | ((u32)h[1] << 16); hv.y = h[2] | ((u32)h[3] << 16);
+        hv.z = h[4] | ((u32)h[5] << 16); hv.w = h[6] | ((u32)h[7] << 16);
+        lv.x = l[0] | ((u32)l[1] << 16); lv.y = l[2] | ((u32)l[3] << 16);
+        lv.z = l[4] | ((u32)l[5] << 16); lv.w = l[6] | ((u32)l[7] << 16);
+        const int64_t out = ((int64_t)(c >> 1) * n_pad + row) * 16 + (c & 1) * 8;
+        *reinterpret_cast<uint4*>(hi + out) = hv;
+        *reinterpret_cast<uint4*>(lo + out) = lv;
+      }
+    } else {                                               // padding rows: zeros (never selected)
+      const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+      for (int c = s; c < cpr; c += 8) {
+        const int64_t out = ((int64_t)(c >> 1) * n_pad + row) * 16 + (c & 1) * 8;
+        *reinterpret_cast<uint4*>(hi + out) = z;
+        *reinterpret_cast<uint4*>(lo + out) = z;
+      }
+    }
+    part[pb][s][r] = ss;
+    // (the buffer written two blocks later is safe: every lane passes the next block's
+    // barrier only after its reads below)
+    __syncthreads();
+    if (tid < 32) {
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += part[pb][j][tid];
+      const int64_t rr = b * 32 + tid;
+      norm[rr] = rr < n ? sum : 0.f;
+      if (rr < n) max_bits = max(max_bits, __float_as_uint(sum));   // sum >= 0: bit order = value order
     }
   }
   __syncthreads();
@@ -447,17 +536,26 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
 
 // ---------------------------------------------------------------------------
 // The same two sweeps for any d that is a multiple of 32 (up to 2048), where the fragments
-// of a row block no longer fit in registers: a classic tiled contraction.  Workgroup = 8
-// wavefronts in a 4 x 2 grid over a 256 x 128 tile of (rows of A) x (rows of B); wavefront
-// (wr, wc) owns the 64 x 64 block at (64 wr, 64 wc) as 2 x 2 MFMA tiles (64 accumulators).
-// The contraction runs over chunks of 32 dimensions: each chunk of both operands is copied
-// global -> registers -> LDS (double buffered; rows padded to 80 bytes: conflict-free
-// 128-bit reads) while the previous chunk is multiplied.  One byte of either operand
-// feeds 128 or 256 rows of the other, and the selection epilogue runs once per tile, after
-// the last chunk -- MODE 0 / MODE 1 exactly as in mfma_sweep_kernel.
+// of a row block no longer fit in registers: a tiled contraction.  Workgroup = 8 wavefronts
+// in a 4 x 2 grid over a 256 x 256 tile of (rows of A) x (rows of B); wavefront (wr, wc) owns
+// rows 64 wr .. + 63 of the tile and the four 32-column blocks wc, wc + 2, wc + 4, wc + 6
+// (interleaved, so that a short B still reaches all 64 group minima of a row) as 2 x 4 MFMA
+// tiles (128 accumulators): one fragment read from LDS feeds 4 resp. 2 products.
+// The operands come in the panel layout of prep_kernel: a block of 32 rows x 16 elements is
+// 1 KB of consecutive memory.  The contraction runs over stages of 32 dimensions (two
+// panels); the 16 row blocks of a stage are copied global -> LDS directly
+// (global_load_lds_dwordx4: no staging registers, no LDS stores), one stage ahead of the
+// products (two buffers).  A copy instruction moves one block: lane l fetches the 16 bytes
+// of row (l & 31), elements 8 (l >> 5) .. + 7, and the hardware stores them at l * 16 of the
+// block -- exactly the order in which the MFMA operand is read back, so fragment reads are
+// 1 KB of consecutive LDS (conflict-free without padding).  The copies are not tracked by
+// the compiler: every stage ends with an explicit wait for this wavefront's copies and a
+// workgroup barrier, which is also what frees the other buffer for the next copies.
+// The selection epilogue runs once per tile, after the last stage -- MODE 0 / MODE 1 exactly
+// as in mfma_sweep_kernel.
 // ---------------------------------------------------------------------------
 template <int METRIC, int MODE, bool THREE>
-__global__ __launch_bounds__(512, 2)
+__global__ __launch_bounds__(512)
 void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
                           const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
                           const unsigned short* __restrict__ Bhi, const unsigned short* __restrict__ Blo,
@@ -466,22 +564,21 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
                           int64_t cols_per_phase, float* __restrict__ minima, int g_raw,
                           const float* __restrict__ tau, int* __restrict__ cnt,
                           u64* __restrict__ shortlist, int cap) {
-  constexpr int BM = 256, BN = 128, KC = 32, LD = 40;            // LD: LDS row stride in bf16 elements
+  constexpr int BM = 256, BN = 256, BLK = 1024;                  // BLK: bytes of a 32-row x 16-element block
   constexpr int NPL = THREE ? 2 : 1;
-  constexpr int PLANE = (BM + BN) * LD;                          // one plane of one buffer, in elements
+  constexpr int STAGE = NPL * 2 * 16 * BLK;                      // [plane][panel][8 A + 8 B blocks][BLK]
   constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
   constexpr float INV_S = METRIC == 0 ? 0.5f : 1.f;
   if ((!(Ainfo->all_bf16 && Binfo->all_bf16)) != THREE) return;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned short* tiles = reinterpret_cast<unsigned short*>(smem);        // [2][NPL][BM + BN][LD]
-  float* bns = reinterpret_cast<float*>(tiles + 2 * NPL * PLANE);        // [2][BN]
+  unsigned char* tiles = smem;                                           // [2][STAGE]
+  float* bns = reinterpret_cast<float*>(tiles + 2 * STAGE);              // [2][BN]
   int* cnt_s = reinterpret_cast<int*>(bns + 2 * BN);                     // [BM]
-  u64* qkey = reinterpret_cast<u64*>(cnt_s + BM) + (threadIdx.x >> 6) * 128;          // [8][128]
-  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + BM) + 8 * 128) +
+  float* an_s = reinterpret_cast<float*>(cnt_s + BM);                    // [BM] |q|^2 of the rows
+  u64* qkey = reinterpret_cast<u64*>(an_s + BM) + (threadIdx.x >> 6) * 128;           // [8][128]
+  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(an_s + BM) + 8 * 128) +
               (threadIdx.x >> 6) * 128;                                  // [8][128]
-  float* an_s = reinterpret_cast<float*>(reinterpret_cast<int*>(reinterpret_cast<u64*>(cnt_s + BM) + 8 * 128) +
-                                         8 * 128);                       // [BM] |q|^2 of the rows
   int qn = 0;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
@@ -492,8 +589,8 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   const int64_t c_begin = (int64_t)split * cols_per_split;
   const int64_t c_end = min(nb, c_begin + cols_per_split);
   const int64_t col_step = (int64_t)BN * stride;
-  const int64_t a_last = (na + 63) / 64 * 64 - 1, b_last = (nb + 63) / 64 * 64 - 1;
-  const int nkc = d / KC;
+  const int64_t na_pad = (na + 63) / 64 * 64, nb_pad = (nb + 63) / 64 * 64;
+  const int nst = d / 32;
 
   // thresholds (MODE 1) / running minima (MODE 0) of this wavefront's 64 rows
   float mn[2][16];
@@ -507,35 +604,34 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
       mn[rb][v] = __builtin_inff();
     }
 
-  // staging: 3 chunks of 16 bytes per lane and plane: chunk ids tid, tid + 512, tid + 1024;
-  // ids below 1024 are A (row id / 4, 8 elements at (id % 4) * 8), the rest B
-  u32x4 stg[NPL][3];
-  float stn = 0.f;
-  int s_row[3], s_col[3];
+  // Copies: wavefront w moves row blocks 2w and 2w + 1 of every (plane, panel) of a stage;
+  // blocks 0..7 are the 256 rows of A (wavefronts 0..3), 8..15 the 256 rows of B.
+  const bool copies_a = wave < 4;
+  const unsigned short* __restrict__ src_hi = copies_a ? Ahi : Bhi;
+  const unsigned short* __restrict__ src_lo = copies_a ? Alo : Blo;
+  const int64_t panel_elems = (copies_a ? na_pad : nb_pad) * 16;
+  int64_t goff[2];                         // element offset of this lane's 16 bytes inside a panel
+  auto set_rows = [&](int64_t ct) {
 #pragma unroll
-  for (int i = 0; i < 3; ++i) { const int id = tid + 512 * i; s_row[i] = id >> 2; s_col[i] = (id & 3) * 8; }
-#define FETCH_KC(CT, KCH)                                                                         \
-  do {                                                                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_) {                                            \
-      int64_t o_;                                                                                 \
-      if (s_row[i_] < BM) o_ = min(row0 + s_row[i_], a_last) * d + (KCH) * KC + s_col[i_];        \
-      else o_ = min((CT) + (int64_t)(s_row[i_] - BM) * stride, b_last) * d + (KCH) * KC + s_col[i_]; \
-      const bool isa_ = s_row[i_] < BM;                                                           \
-      stg[0][i_] = *reinterpret_cast<const u32x4*>((isa_ ? Ahi : Bhi) + o_);                      \
-      if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>((isa_ ? Alo : Blo) + o_); \
-    }                                                                                             \
-    if ((KCH) == 0 && tid < BN) stn = Bnorm[min((CT) + (int64_t)tid * stride, b_last)];           \
-  } while (0)
-#define STASH_KC(BUF, CT, KCH, TILE)                                                              \
-  do {                                                                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_)                                              \
-      _Pragma("unroll") for (int pl_ = 0; pl_ < NPL; ++pl_)                                       \
-        *reinterpret_cast<u32x4*>(tiles + ((BUF) * NPL + pl_) * PLANE + s_row[i_] * LD + s_col[i_]) = stg[pl_][i_]; \
-    if ((KCH) == 0 && tid < BN)                                                                   \
-      bns[((TILE) & 1) * BN + tid] =                                                              \
-          (CT) + (int64_t)tid * stride < c_end                                                    \
-              ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();         \
-  } while (0)
+    for (int i = 0; i < 2; ++i) {
+      const int rl = ((wave & 3) * 2 + i) * 32 + (lane & 31);            // row of the tile, 0..255
+      const int64_t g = copies_a ? min(row0 + rl, na_pad - 1) : min(ct + (int64_t)rl * stride, nb_pad - 1);
+      goff[i] = g * 16 + 8 * (lane >> 5);
+    }
+  };
+  auto copy_stage = [&](int buf, int st) {
+#pragma unroll
+    for (int pl = 0; pl < NPL; ++pl)
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const unsigned short* g = (pl ? src_lo : src_hi) + (int64_t)(st * 2 + pp) * panel_elems + goff[i];
+          unsigned char* l = tiles + buf * STAGE + ((pl * 2 + pp) * 16 + wave * 2 + i) * BLK;
+          __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
+        }
+  };
+  float stn = 0.f;
 
   if (MODE == 1)
     for (int i = tid; i < BM; i += 512) {
@@ -556,44 +652,56 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
     wave_lds_sync();
   };
 
-  if (c_begin < c_end) { FETCH_KC(c_begin, 0); STASH_KC(0, c_begin, 0, 0); }
+  if (c_begin < c_end) {
+    set_rows(c_begin);
+    copy_stage(0, 0);
+    if (tid < BN) {
+      const int64_t c = c_begin + (int64_t)tid * stride;
+      stn = Bnorm[min(c, nb_pad - 1)];
+      bns[tid] = c < c_end ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();
+    }
+  }
   wait_all_global_loads();
   block_sync_lds();
   int buf = 0, tile = 0;
-  floatx16 m[2][2];
+  floatx16 m[2][4];
   for (int64_t ct = c_begin; ct < c_end; ct += col_step, ++tile) {
-    for (int kch = 0; kch < nkc; ++kch, buf ^= 1) {
-      // the stage after this one: next chunk of the same tile, or the first chunk of the next tile
-      const bool last_kc = kch + 1 == nkc;
-      const int64_t ct_n = last_kc ? ct + col_step : ct;
-      const int kch_n = last_kc ? 0 : kch + 1;
+    for (int st = 0; st < nst; ++st, buf ^= 1) {
+      // the stage after this one: next stage of the same tile, or the first of the next tile
+      const bool last_st = st + 1 == nst;
+      const int64_t ct_n = last_st ? ct + col_step : ct;
       const bool more = ct_n < c_end;
-      if (more) FETCH_KC(ct_n, kch_n);
-      const unsigned short* __restrict__ ta = tiles + (buf * NPL) * PLANE;   // A rows, then B rows
-      if (kch == 0) {   // a new tile starts from 0 (MODE 0) / from the row thresholds (MODE 1)
+      if (more) {
+        if (last_st && !copies_a) set_rows(ct_n);
+        copy_stage(buf ^ 1, last_st ? 0 : st + 1);
+        if (last_st && tid < BN) stn = Bnorm[min(ct_n + (int64_t)tid * stride, nb_pad - 1)];
+      }
+      const unsigned char* __restrict__ tb = tiles + buf * STAGE;
+      if (st == 0) {   // a new tile starts from 0 (MODE 0) / from the row thresholds (MODE 1)
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int cb = 0; cb < 2; ++cb) m[rb][cb] = tr[rb];
+          for (int cb = 0; cb < 4; ++cb) m[rb][cb] = tr[rb];
       }
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        bf16x8 ah[2], al[2], bh[2], bl[2];
+      for (int pp = 0; pp < 2; ++pp) {
+        bf16x8 ah[2], al[2], bh[4], bl[4];
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
-          const int oa = (wr * 64 + x * 32 + (lane & 31)) * LD + ks * 16 + 8 * (lane >> 5);
-          const int ob = (BM + wc * 64 + x * 32 + (lane & 31)) * LD + ks * 16 + 8 * (lane >> 5);
-          ah[x] = *reinterpret_cast<const bf16x8*>(ta + oa);
-          bh[x] = *reinterpret_cast<const bf16x8*>(ta + ob);
-          if constexpr (THREE) {
-            al[x] = *reinterpret_cast<const bf16x8*>(ta + PLANE + oa);
-            bl[x] = *reinterpret_cast<const bf16x8*>(ta + PLANE + ob);
-          }
+          ah[x] = *reinterpret_cast<const bf16x8*>(tb + (pp * 16 + wr * 2 + x) * BLK + lane * 16);
+          if constexpr (THREE)
+            al[x] = *reinterpret_cast<const bf16x8*>(tb + ((2 + pp) * 16 + wr * 2 + x) * BLK + lane * 16);
+        }
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          bh[y] = *reinterpret_cast<const bf16x8*>(tb + (pp * 16 + 8 + 2 * y + wc) * BLK + lane * 16);
+          if constexpr (THREE)
+            bl[y] = *reinterpret_cast<const bf16x8*>(tb + ((2 + pp) * 16 + 8 + 2 * y + wc) * BLK + lane * 16);
         }
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
+          for (int cb = 0; cb < 4; ++cb) {
             m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bh[cb], m[rb][cb], 0, 0, 0);
             if constexpr (THREE) {
               m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bl[cb], m[rb][cb], 0, 0, 0);
@@ -601,17 +709,18 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
             }
           }
       }
-      if (last_kc) {   // the tile is complete: selection epilogue
-        const float b0 = bns[(tile & 1) * BN + wc * 64 + (lane & 31)];
-        const float b1 = bns[(tile & 1) * BN + wc * 64 + 32 + (lane & 31)];
+      if (last_st) {   // the tile is complete: selection epilogue
+        float bt[4];
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) bt[cb] = bns[(tile & 1) * BN + (2 * cb + wc) * 32 + (lane & 31)];
         if (MODE == 0) {
 #pragma unroll
           for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
+            for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
               for (int v = 0; v < 16; ++v)
-                mn[rb][v] = fminf(mn[rb][v], __builtin_fmaf(SCALE, m[rb][cb][v], cb ? b1 : b0));
+                mn[rb][v] = fminf(mn[rb][v], __builtin_fmaf(SCALE, m[rb][cb][v], bt[cb]));
           const int ph = (int)((ct - c_begin) / cols_per_phase);
           const int ph_next = ct + col_step < c_end ? (int)((ct + col_step - c_begin) / cols_per_phase) : nphase;
           for (int p2 = ph; p2 < ph_next; ++p2) {
@@ -626,22 +735,22 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
               }
           }
         } else {
-          bool any[2][2];
+          bool any[2][4];
 #pragma unroll
           for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
+            for (int cb = 0; cb < 4; ++cb) {
               float mx = m[rb][cb][0];
 #pragma unroll
               for (int v = 1; v < 16; ++v) mx = fmaxf(mx, m[rb][cb][v]);
-              any[rb][cb] = mx >= (cb ? b1 : b0);
+              any[rb][cb] = mx >= bt[cb];
             }
 #pragma unroll
           for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
+            for (int cb = 0; cb < 4; ++cb) {
               if (__builtin_amdgcn_ballot_w64(any[rb][cb]) == 0) continue;
-              const float hb = cb ? b1 : b0;
+              const float hb = bt[cb];
 #pragma unroll
               for (int g = 0; g < 4; ++g) {   // rare path: by groups of four, then by element
                 const float gm = fmaxf(fmaxf(m[rb][cb][4 * g], m[rb][cb][4 * g + 1]),
@@ -658,7 +767,7 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
                       const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
                       const float dotv = m[rb][cb][v] - tr[rb][v];
                       const float val = METRIC == 0 ? an_s[rl] + 2.f * (hb - dotv) : dotv;
-                      qkey[e] = make_key(val, (u32)(ct + wc * 64 + cb * 32 + (lane & 31)), METRIC);
+                      qkey[e] = make_key(val, (u32)(ct + (2 * cb + wc) * 32 + (lane & 31)), METRIC);
                       qrow[e] = rl;
                     }
                     qn += __popcll(mask);
@@ -668,13 +777,15 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
               }
             }
         }
+        if (more && tid < BN)   // column terms of the next tile (the other half of bns)
+          bns[((tile + 1) & 1) * BN + tid] =
+              ct_n + (int64_t)tid * stride < c_end
+                  ? (METRIC == 0 ? (MODE == 1 ? stn * INV_S : stn) : 0.f) : __builtin_inff();
       }
-      if (more) STASH_KC(buf ^ 1, ct_n, kch_n, tile + (last_kc ? 1 : 0));
-      block_sync_lds();
+      wait_all_global_loads();   // this wavefront's copies of the next stage have landed
+      block_sync_lds();          // ... everyone's have, and everyone is done reading this stage
     }
   }
-#undef FETCH_KC
-#undef STASH_KC
   if (MODE == 1) {
     if (qn > 0) drain(qn);
     block_sync_lds();
@@ -696,7 +807,7 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
 }
 
 // tau(row) = kp-th smallest of the row's g_raw group minima (min-combined down to 64 * RG
-// values first), clamped below +inf.
+// values first), or the largest finite one if fewer than kp are finite.
 template <int RG>
 __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ minima, int g_raw,
                                                   int64_t na, int kp, float* __restrict__ tau) {
@@ -716,13 +827,26 @@ __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ mini
     }
   }
   wave_sort_regs(v);
+  // With fewer than kp finite minima (a short B) the threshold is the largest finite one: any
+  // threshold is valid for the re-rank test, and a finite one keeps the collect sweep's
+  // accumulators (which start at the threshold) in a range where the products still register.
+  int nfin = 0;
+#pragma unroll
+  for (int r = 0; r < RG; ++r) nfin += v[r] < order_f32(__builtin_inff()) ? 1 : 0;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) nfin += __shfl_xor(nfin, off);
+  const int rank = max(min(kp, nfin), 1) - 1;
   u32 pick = 0;
 #pragma unroll
   for (int r = 0; r < RG; ++r)
-    if (lane * RG + r == kp - 1) pick = v[r];
+    if (lane * RG + r == rank) pick = v[r];
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) pick |= (u32)__shfl_xor((int)pick, off);
-  if (lane == 0) tau[row] = fminf(unorder_f32(pick), 3.4028234e38f);
+  if (lane == 0) {
+    float t = unorder_f32(pick);
+    if (nfin < kp) t += __builtin_fabsf(t) * 1e-3f;    // (the two sweeps round differently: keep the largest listed)
+    tau[row] = fminf(t, 3.4028234e38f);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -937,12 +1061,22 @@ int mfma_knn_kp(int k) {
   return std::min(kp, 192);
 }
 
+namespace {
+// (the register-stationary kernel measured 1.3 - 1.45x faster than the tiled one at these d)
+bool stationary_d(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
+}  // namespace
+
 void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
                  float* norm, PrepInfo* info, hipStream_t st) {
   hipLaunchKernelGGL(prep_info_init_kernel, dim3(1), dim3(1), 0, st, info);
   if (n <= 0) return;
-  const int rpb = 2048 / d;                          // d <= 2048 here, d % 8 == 0
   const int64_t n_pad = mfma_padded_rows(n);
+  if (!stationary_d(d)) {                            // the tiled kernel reads panels
+    hipLaunchKernelGGL(prep_panel_kernel, dim3((unsigned)std::min<int64_t>(n_pad / 32, 4096)), dim3(256), 0,
+                       st, x, n, n_pad, d, hi, lo, norm, info);
+    return;
+  }
+  const int rpb = 2048 / d;                          // d % 8 == 0
   const int64_t ngroups = (n_pad + rpb - 1) / rpb;
   hipLaunchKernelGGL(prep_kernel, dim3((unsigned)std::min<int64_t>(ngroups, 4096)), dim3(256), 0, st, x, n,
                      n_pad, d, rpb, hi, lo, norm, info);
@@ -950,7 +1084,7 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
 
 namespace {
 struct MfmaPlan {
-  bool kc;                                   // general-d kernel (256 x 128 tiles) instead of the
+  bool kc;                                   // general-d kernel (256 x 256 tiles) instead of the
                                              // register-stationary one (128 rows x 64 columns)
   int RB, nsplit, nphase, g_raw, rg, kp, kp_tau, stride, cap;
   int64_t cols_per_split, cols_per_phase, row_tiles;
@@ -958,13 +1092,10 @@ struct MfmaPlan {
 };
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
-// (the register-stationary kernel measured 1.3 - 1.45x faster than the tiled one at these d)
-bool stationary_d(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
-
 MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   MfmaPlan p;
   p.kc = !stationary_d(d);
-  const int bm = p.kc ? 256 : 128, bn = p.kc ? 128 : 64;      // tile of one workgroup step
+  const int bm = p.kc ? 256 : 128, bn = p.kc ? 256 : 64;      // tile of one workgroup step
   p.kp = mfma_knn_kp(k);
   p.cap = std::max(64, 3 * p.kp);
   // Row blocks of A per wavefront.  Operands split in head and tail: one 32-row block (two
@@ -1120,7 +1251,7 @@ template <int METRIC, int MODE, bool THREE>
 static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                               char* work, hipStream_t st) {
   constexpr int NPL = THREE ? 2 : 1;
-  const size_t shmem = (size_t)2 * NPL * (256 + 128) * 40 * sizeof(unsigned short) + 2 * 128 * sizeof(float) +
+  const size_t shmem = (size_t)2 * NPL * 2 * 16 * 1024 + 2 * 256 * sizeof(float) +
                        (size_t)256 * (sizeof(int) + sizeof(float)) + 8 * 128 * (sizeof(u64) + sizeof(int));
   auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, THREE>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
