@@ -576,15 +576,23 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   float* bns = reinterpret_cast<float*>(tiles + 2 * STAGE);              // [2][BN]
   int* cnt_s = reinterpret_cast<int*>(bns + 2 * BN);                     // [BM]
   float* an_s = reinterpret_cast<float*>(cnt_s + BM);                    // [BM] |q|^2 of the rows
-  u64* qkey = reinterpret_cast<u64*>(an_s + BM) + (threadIdx.x >> 6) * 128;           // [8][128]
-  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(an_s + BM) + 8 * 128) +
+  float* tr_s = an_s + BM;                                               // [BM] row thresholds (MODE 1)
+  u64* qkey = reinterpret_cast<u64*>(tr_s + BM) + (threadIdx.x >> 6) * 128;           // [8][128]
+  int* qrow = reinterpret_cast<int*>(reinterpret_cast<u64*>(tr_s + BM) + 8 * 128) +
               (threadIdx.x >> 6) * 128;                                  // [8][128]
   int qn = 0;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
   const int wr = wave >> 1, wc = wave & 1;
-  const int64_t rt = blockIdx.x / nsplit;
-  const int split = blockIdx.x % nsplit;
+  // Work item = (row tile, split of B), numbered row tile first.  Workgroup ids go round the
+  // eight XCDs, each with an L2 of its own: XCD x takes a run of consecutive items, i.e. a few
+  // row tiles with all their splits, so that its workgroups share their A and B tiles in L2
+  // (with ids taken in order, no two workgroups of an XCD shared an A tile: 56 % L2 misses).
+  const int64_t items = (na + BM - 1) / BM * nsplit, per_xcd = (items + 7) / 8;
+  const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if ((int64_t)(blockIdx.x >> 3) >= per_xcd || item >= items) return;
+  const int64_t rt = item / nsplit;
+  const int split = (int)(item % nsplit);
   const int64_t row0 = rt * BM;
   const int64_t c_begin = (int64_t)split * cols_per_split;
   const int64_t c_end = min(nb, c_begin + cols_per_split);
@@ -592,17 +600,12 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   const int64_t na_pad = (na + 63) / 64 * 64, nb_pad = (nb + 63) / 64 * 64;
   const int nst = d / 32;
 
-  // thresholds (MODE 1) / running minima (MODE 0) of this wavefront's 64 rows
+  // running minima (MODE 0) of this wavefront's 64 rows; the row thresholds (MODE 1) sit in LDS
   float mn[2][16];
-  floatx16 tr[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int64_t r = row0 + wr * 64 + rb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      tr[rb][v] = MODE == 1 ? (r < na ? tau[r] * INV_S : -__builtin_inff()) : 0.f;
-      mn[rb][v] = __builtin_inff();
-    }
+    for (int v = 0; v < 16; ++v) mn[rb][v] = __builtin_inff();
 
   // Copies: wavefront w moves row blocks 2w and 2w + 1 of every (plane, panel) of a stage;
   // blocks 0..7 are the 256 rows of A (wavefronts 0..3), 8..15 the 256 rows of B.
@@ -619,17 +622,16 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
       goff[i] = g * 16 + 8 * (lane >> 5);
     }
   };
+  // copy number c of a stage, c < 4 NPL: (plane, panel, row block) = (c / 4, (c / 2) % 2, c % 2)
+  auto copy_one = [&](int buf, int st, int c) {
+    const int pl = c >> 2, pp = (c >> 1) & 1, i = c & 1;
+    const unsigned short* g = (pl ? src_lo : src_hi) + (int64_t)(st * 2 + pp) * panel_elems + goff[i];
+    unsigned char* l = tiles + buf * STAGE + ((pl * 2 + pp) * 16 + wave * 2 + i) * BLK;
+    __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
+  };
   auto copy_stage = [&](int buf, int st) {
 #pragma unroll
-    for (int pl = 0; pl < NPL; ++pl)
-#pragma unroll
-      for (int pp = 0; pp < 2; ++pp)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const unsigned short* g = (pl ? src_lo : src_hi) + (int64_t)(st * 2 + pp) * panel_elems + goff[i];
-          unsigned char* l = tiles + buf * STAGE + ((pl * 2 + pp) * 16 + wave * 2 + i) * BLK;
-          __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
-        }
+    for (int c = 0; c < 4 * NPL; ++c) copy_one(buf, st, c);
   };
   float stn = 0.f;
 
@@ -637,6 +639,7 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
     for (int i = tid; i < BM; i += 512) {
       cnt_s[i] = 0;
       an_s[i] = METRIC == 0 ? Anorm[min(row0 + i, na - 1)] : 0.f;
+      tr_s[i] = row0 + i < na ? tau[row0 + i] * INV_S : -__builtin_inff();
     }
   auto drain = [&](int n) {
     wave_lds_sync();
@@ -663,25 +666,36 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
   }
   wait_all_global_loads();
   block_sync_lds();
-  int buf = 0, tile = 0;
+  int buf = 0;
   floatx16 m[2][4];
-  for (int64_t ct = c_begin; ct < c_end; ct += col_step, ++tile) {
+  const int ntiles = c_begin < c_end ? (int)((c_end - c_begin + col_step - 1) / col_step) : 0;
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int64_t ct = c_begin + tile * col_step;
     for (int st = 0; st < nst; ++st, buf ^= 1) {
       // the stage after this one: next stage of the same tile, or the first of the next tile
       const bool last_st = st + 1 == nst;
       const int64_t ct_n = last_st ? ct + col_step : ct;
-      const bool more = ct_n < c_end;
+      const bool more = !last_st || tile + 1 < ntiles;
+      const int st_n = last_st ? 0 : st + 1;
       if (more) {
         if (last_st && !copies_a) set_rows(ct_n);
-        copy_stage(buf ^ 1, last_st ? 0 : st + 1);
+        copy_stage(buf ^ 1, st_n);
         if (last_st && tid < BN) stn = Bnorm[min(ct_n + (int64_t)tid * stride, nb_pad - 1)];
       }
       const unsigned char* __restrict__ tb = tiles + buf * STAGE;
       if (st == 0) {   // a new tile starts from 0 (MODE 0) / from the row thresholds (MODE 1)
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < 2; ++rb) {
+          floatx16 t0;
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) m[rb][cb] = tr[rb];
+          for (int g = 0; g < 4; ++g) {
+            float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (MODE == 1) t4 = *reinterpret_cast<const float4*>(tr_s + wr * 64 + rb * 32 + 8 * g + 4 * (lane >> 5));
+            t0[4 * g] = t4.x; t0[4 * g + 1] = t4.y; t0[4 * g + 2] = t4.z; t0[4 * g + 3] = t4.w;
+          }
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) m[rb][cb] = t0;
+        }
       }
 #pragma unroll
       for (int pp = 0; pp < 2; ++pp) {
@@ -722,7 +736,7 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
               for (int v = 0; v < 16; ++v)
                 mn[rb][v] = fminf(mn[rb][v], __builtin_fmaf(SCALE, m[rb][cb][v], bt[cb]));
           const int ph = (int)((ct - c_begin) / cols_per_phase);
-          const int ph_next = ct + col_step < c_end ? (int)((ct + col_step - c_begin) / cols_per_phase) : nphase;
+          const int ph_next = tile + 1 < ntiles ? (int)((ct + col_step - c_begin) / cols_per_phase) : nphase;
           for (int p2 = ph; p2 < ph_next; ++p2) {
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
@@ -765,7 +779,7 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
                   if (mask != 0) {
                     if (pass) {
                       const int e = qn + __popcll(mask & ((1ull << lane) - 1ull));
-                      const float dotv = m[rb][cb][v] - tr[rb][v];
+                      const float dotv = m[rb][cb][v] - tr_s[rl];
                       const float val = METRIC == 0 ? an_s[rl] + 2.f * (hb - dotv) : dotv;
                       qkey[e] = make_key(val, (u32)(ct + (2 * cb + wc) * 32 + (lane & 31)), METRIC);
                       qrow[e] = rl;
@@ -1252,11 +1266,12 @@ static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const Mfm
                               char* work, hipStream_t st) {
   constexpr int NPL = THREE ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * 2 * 16 * 1024 + 2 * 256 * sizeof(float) +
-                       (size_t)256 * (sizeof(int) + sizeof(float)) + 8 * 128 * (sizeof(u64) + sizeof(int));
+                       (size_t)256 * (sizeof(int) + 2 * sizeof(float)) + 8 * 128 * (sizeof(u64) + sizeof(int));
   auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, THREE>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(p.row_tiles * p.nsplit)), dim3(512), shmem, st, A.hi, A.lo,
+  const int64_t per_xcd = (p.row_tiles * p.nsplit + 7) / 8;       // the kernel deals the items out by XCD
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(512), shmem, st, A.hi, A.lo,
                      A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, d, p.nsplit, p.cols_per_split,
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,

@@ -397,6 +397,11 @@ ROUTE_CASES = [
     ("unit_d768_k32_ip", 9_000, 300, 768, 32, IP, "unit"),
     ("sift_d256_k20", 40_000, 64, 256, 20, L2, "sift"),
     ("gauss_d2048_k5", 3_000, 40, 2048, 5, L2, "gauss"),
+    # B barely longer than the shortlist: fewer finite group minima than the wanted rank
+    ("gauss_d256_k100_short_b", 190, 70, 256, 100, L2, "gauss"),
+    ("gauss_d160_k150_ip_short_b", 300, 33, 160, 150, IP, "gauss"),
+    ("gauss_d768_k32_ip_short_b", 128, 300, 768, 32, IP, "gauss"),
+    ("gauss_d128_k100_short_b", 130, 40, 128, 100, L2, "gauss"),
     # long database in cluster order: the threshold comes from a sample of the columns
     ("sift_sorted_d128_k100", 200_000, 64, 128, 100, L2, "sift_sorted"),
     ("unit_sorted_d96_k10", 150_000, 96, 96, 10, L2, "unit_sorted"),
