@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat", "ivfsq8"],
                     help="ivfflat: the same workload's vectors and centroids in an IVF-Flat index "
                          "(secondary line; the default ivfpq is the headline metric)")
+    ap.add_argument("--flat-stateless", action="store_true",
+                    help="workload C2: time vs_flat_search (database prepared in every call) instead of a "
+                         "flat index (prepared once, at add)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
@@ -297,13 +300,19 @@ def bench_flat(args, cfg, x, q, xd, qd):
     D = torch.empty((nq, k), dtype=torch.float32, device="cuda")
     I = torch.empty((nq, k), dtype=torch.int64, device="cuda")
     vs.vs_counters_read()
+    if args.flat_stateless:      # the stateless entry point: prepares the database in every call
+        search = lambda: vs.vs_flat_search(xd, qd, k, metric, D, I)
+    else:                        # a flat index: the database is prepared when it is added
+        ix = vs.Flat(d, metric)
+        ix.add(xd)
+        search = lambda: ix.search(qd, k, D, I)
     for _ in range(args.warmup):
-        vs.vs_flat_search(xd, qd, k, metric, D, I)
+        search()
     torch.cuda.synchronize()
     vs.vs_profile_enable(True); vs.vs_profile_read()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        vs.vs_flat_search(xd, qd, k, metric, D, I)
+        search()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = vs.vs_profile_read(); vs.vs_profile_enable(False)
@@ -316,7 +325,7 @@ def bench_flat(args, cfg, x, q, xd, qd):
         # the whole stage's time is charged to it, so the fraction is a lower bound for the kernel.
         flops = 2.0 * nq * nb * d
         achieved = flops / (dist_ms_total * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "mfma_sweep_kernel (stage: prep + minima sweep + collect sweep)",
+        roof = {"bound": "mfma", "kernel": "mfma_sweep_kernel (stage: operand preparation + minima sweep + collect sweep)",
                 "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "peak_measured_mfma_loop": BF16_MFMA_MEASURED_TFLOPS,
                 "frac_of_measured": achieved / BF16_MFMA_MEASURED_TFLOPS, "traffic": None,
@@ -339,6 +348,7 @@ def bench_flat(args, cfg, x, q, xd, qd):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C2: flat L2, nb=%d d=%d nq=%d k=%d" % (nb, d, nq, k),
+                   "entry_point": "vs_flat_search" if args.flat_stateless else "vs_flat_index_search",
                    "stage_ms_per_step": {s: round(v[0] / args.steps, 3) for s, v in prof.items() if v[1]}},
         "roofline": roof,
         "cpu_baseline": cpu,

@@ -73,6 +73,30 @@ VS_API int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq
                    void* hip_stream);
 
 /*
+ * Flat index (Sec. 3.1; the "Flat" index of App. A.2, which stores the vectors as they
+ * are): the database of vs_flat_search kept by the library, so that what a search needs of
+ * it besides the rows -- squared norms and the bf16 operand planes of the matrix-core
+ * route -- is computed when vectors are added instead of in every search.
+ *   vs_flat_create   empty index for d-dimensional vectors and one metric.
+ *   vs_flat_add      appends n rows x [n, d] (copied; row j of the call gets id ntotal + j,
+ *                    Sec. "Adding vectors": sequential ids) and prepares the whole
+ *                    database again: its cost grows with ntotal, add in large pieces.
+ *                    Synchronises the stream.  ntotal stays below 2^31.
+ *   vs_flat_index_search  same results as vs_flat_search(stored rows, ...), bit for bit.
+ *   vs_flat_ntotal   number of stored rows (-1 for a null handle).
+ *   vs_flat_destroy  frees the index (null is a no-op); the caller makes sure that no
+ *                    search on it is still running.
+ * Errors: as vs_flat_search; VS_ERR_OOM when storage cannot grow (the index is unchanged).
+ */
+typedef struct vs_flat vs_flat;
+VS_API int vs_flat_create(vs_flat** out, int32_t d, int32_t metric);
+VS_API void vs_flat_destroy(vs_flat* ix);
+VS_API int64_t vs_flat_ntotal(const vs_flat* ix);
+VS_API int vs_flat_add(vs_flat* ix, const float* x, int64_t n, void* hip_stream);
+VS_API int vs_flat_index_search(const vs_flat* ix, const float* q, int64_t nq, int32_t k,
+                                float* out_dist, int64_t* out_ids, void* hip_stream);
+
+/*
  * vs_flat_search, vs_kmeans and vs_ivfpq_train keep one grow-only work buffer per device
  * (operand planes, candidate lists, ...; for a 10M x 768 database about 30 GB).  vs_trim
  * waits for the current device to go idle and frees that buffer; the next call allocates

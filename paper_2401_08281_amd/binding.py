@@ -38,6 +38,16 @@ def lib():
     L.vs_flat_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
     L.vs_trim.restype = ctypes.c_int
     L.vs_trim.argtypes = []
+    L.vs_flat_create.restype = ctypes.c_int
+    L.vs_flat_create.argtypes = [ctypes.POINTER(vp), i32, i32]
+    L.vs_flat_destroy.restype = None
+    L.vs_flat_destroy.argtypes = [vp]
+    L.vs_flat_ntotal.restype = i64
+    L.vs_flat_ntotal.argtypes = [vp]
+    L.vs_flat_add.restype = ctypes.c_int
+    L.vs_flat_add.argtypes = [vp, vp, i64, vp]
+    L.vs_flat_index_search.restype = ctypes.c_int
+    L.vs_flat_index_search.argtypes = [vp, vp, i64, i32, vp, vp, vp]
     L.vs_knn_workspace_bytes.restype = i64
     L.vs_knn_workspace_bytes.argtypes = [i64, i64, i32, i32, i64, i32]
     L.vs_ivfpq_set_search_type.restype = ctypes.c_int
@@ -197,6 +207,38 @@ def vs_flat_search(x, q, k, metric=METRIC_L2, out_dist=None, out_ids=None):
     _dev(out_dist, torch.float32, "out_dist")
     _dev(out_ids, torch.int64, "out_ids")
     _check(lib().vs_flat_search(_p(x), nb, _p(q), nq, d, metric, k, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_flat_create(d, metric=METRIC_L2):
+    h = ctypes.c_void_p()
+    _check(lib().vs_flat_create(ctypes.byref(h), int(d), int(metric)))
+    return h
+
+
+def vs_flat_destroy(h):
+    lib().vs_flat_destroy(h)
+
+
+def vs_flat_ntotal(h):
+    return int(lib().vs_flat_ntotal(h))
+
+
+def vs_flat_add(h, x):
+    x = _dev(x, torch.float32, "x")
+    _check(lib().vs_flat_add(h, _p(x), x.shape[0], _stream()))
+
+
+def vs_flat_index_search(h, q, k, out_dist=None, out_ids=None):
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_flat_index_search(h, _p(q), nq, k, _p(out_dist), _p(out_ids), _stream()))
     return out_dist, out_ids
 
 
@@ -464,6 +506,39 @@ class IVFSQ8:
         codes = torch.empty((n, self.d), dtype=torch.uint8, device=self.device)
         _check(lib().vs_ivfsq8_get_storage(self.h, _p(ids), _p(list_of), _p(codes), _stream()))
         return ids, list_of, codes
+
+
+class Flat:
+    """Owner of one vs_flat handle (thin convenience over the functions above)."""
+
+    def __init__(self, d, metric=METRIC_L2):
+        self.d, self.metric = int(d), int(metric)
+        self.h = vs_flat_create(self.d, self.metric)
+
+    def close(self):
+        if getattr(self, "h", None) is not None:
+            vs_flat_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def ntotal(self):
+        return vs_flat_ntotal(self.h)
+
+    def add(self, x):
+        if x.shape[1] != self.d:
+            raise ValueError("x has dimension %d, the index %d" % (x.shape[1], self.d))
+        vs_flat_add(self.h, x)
+
+    def search(self, q, k, out_dist=None, out_ids=None):
+        if q.shape[1] != self.d:
+            raise ValueError("q has dimension %d, the index %d" % (q.shape[1], self.d))
+        return vs_flat_index_search(self.h, q, k, out_dist, out_ids)
 
 
 class IVFFlat:

@@ -259,6 +259,16 @@ struct vs_ivfflat {
   vs_ivfpq core;
 };
 
+// Flat index: the rows as given, plus the prepared operand of the matrix-core route
+struct vs_flat {
+  int d = 0, metric = 0, device = 0;
+  int64_t ntotal = 0, cap = 0;  // rows stored / rows the buffers hold
+  float* x = nullptr;           // [cap, d]
+  void* plane_mem = nullptr;    // planes_bytes(cap, d), laid out for ntotal rows
+  Planes planes;
+  bool has_planes = false;
+};
+
 // IVF-SQ8 likewise; core.codes holds d bytes per vector (core.g: M = d, nbits = 8)
 struct vs_ivfsq8 {
   vs_ivfpq core;
@@ -358,6 +368,106 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
     launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
   } else {
     if (int rc = knn_run(plan, base, q, nq, x, nb, d, metric, k, nullptr, out, st, VS_STAGE_FLAT_DIST,
+                         VS_STAGE_FLAT_SELECT))
+      return rc;
+  }
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_flat_create(vs_flat** out, int32_t d, int32_t metric) {
+  if (!out) return fail(VS_ERR_INVALID_ARG, "vs_flat_create: out is null");
+  *out = nullptr;
+  if (d < 1) return fail(VS_ERR_INVALID_ARG, "vs_flat_create: d = %d < 1", d);
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP) return fail(VS_ERR_INVALID_ARG, "vs_flat_create: unknown metric %d", metric);
+  vs_flat* ix = new (std::nothrow) vs_flat();
+  if (!ix) return fail(VS_ERR_OOM, "vs_flat_create: host allocation failed");
+  ix->d = d; ix->metric = metric;
+  if (hipError_t e = hipGetDevice(&ix->device); e != hipSuccess) {
+    delete ix;
+    return fail(VS_ERR_DEVICE, "vs_flat_create: %s", hipGetErrorString(e));
+  }
+  *out = ix;
+  return VS_OK;
+}
+
+void vs_flat_destroy(vs_flat* ix) {
+  if (!ix) return;
+  if (ix->x) (void)hipFree(ix->x);
+  if (ix->plane_mem) (void)hipFree(ix->plane_mem);
+  delete ix;
+}
+
+int64_t vs_flat_ntotal(const vs_flat* ix) { return ix ? ix->ntotal : -1; }
+
+int vs_flat_add(vs_flat* ix, const float* x, int64_t n, void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_flat_add: index is null");
+  if (n < 0) return fail(VS_ERR_INVALID_ARG, "vs_flat_add: negative size");
+  if (n == 0) return VS_OK;
+  if (!x) return fail(VS_ERR_INVALID_ARG, "vs_flat_add: null pointer");
+  if (ix->ntotal + n >= (1ll << 31)) return fail(VS_ERR_INVALID_ARG, "vs_flat_add: ntotal must stay below 2^31");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int d = ix->d;
+  const bool planes = mfma_knn_supported(d, 1);
+  const int64_t total = ix->ntotal + n;
+  if (total > ix->cap) {   // grow both buffers (at least doubling), keep the stored rows
+    const int64_t cap = std::max(total, 2 * ix->cap);
+    float* nx = nullptr;
+    void* np = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&nx), (size_t)cap * d * sizeof(float));
+    if (e == hipSuccess && planes) e = hipMalloc(&np, planes_bytes(cap, d));
+    if (e == hipSuccess && ix->ntotal > 0)
+      e = hipMemcpyAsync(nx, ix->x, (size_t)ix->ntotal * d * sizeof(float), hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+      if (nx) (void)hipFree(nx);
+      if (np) (void)hipFree(np);
+      (void)hipGetLastError();
+      return fail(e == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "vs_flat_add: %s", hipGetErrorString(e));
+    }
+    if (ix->x) (void)hipFree(ix->x);
+    if (ix->plane_mem) (void)hipFree(ix->plane_mem);
+    ix->x = nx; ix->plane_mem = np; ix->cap = cap;
+  }
+  HIP_TRY(hipMemcpyAsync(ix->x + ix->ntotal * d, x, (size_t)n * d * sizeof(float), hipMemcpyDeviceToDevice, st));
+  ix->ntotal = total;
+  if (planes) {   // (the panel layout of the planes depends on the row count: prepared anew)
+    ix->planes = carve_planes(static_cast<char*>(ix->plane_mem), total, d);
+    launch_prep(ix->x, total, d, ix->planes.hi, ix->planes.lo, ix->planes.norm, ix->planes.info, st);
+    ix->has_planes = true;
+  }
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipGetLastError());
+  return VS_OK;
+}
+
+int vs_flat_index_search(const vs_flat* ix, const float* q, int64_t nq, int32_t k, float* out_dist,
+                         int64_t* out_ids, void* hip_stream) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_flat_index_search: index is null");
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_flat_index_search: negative size");
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_flat_index_search: k = %d outside [1, %d]", k, VS_MAX_K);
+  if (nq == 0) return VS_OK;
+  if (!q || !out_dist || !out_ids) return fail(VS_ERR_INVALID_ARG, "vs_flat_index_search: null pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int dev = ix->device;
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_flat_index_search: device %d", dev);
+  const int64_t nb = ix->ntotal;
+  const int d = ix->d, metric = ix->metric;
+  const Planes* bp = ix->has_planes ? &ix->planes : nullptr;
+  const KnnPlan plan = knn_plan(nq, nb, d, k, bp != nullptr);
+  std::lock_guard<std::mutex> lock(g_flat_mu);
+  Scratch& sc = g_flat_scratch[dev];
+  if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
+  char* base = static_cast<char*>(sc.p);
+  SelectOut out;
+  out.val = out_dist;
+  out.id64 = out_ids;
+  if (nb == 0) {   // nothing to select from: all slots empty
+    u64* keys = reinterpret_cast<u64*>(base);
+    launch_fill_u64(keys, nq * k, 0xFFFFFFFFFFFFFFFFull, st);
+    launch_keys_to_results(keys, nq * k, metric, out_dist, out_ids, nullptr, st);
+  } else {
+    if (int rc = knn_run(plan, base, q, nq, ix->x, nb, d, metric, k, bp, out, st, VS_STAGE_FLAT_DIST,
                          VS_STAGE_FLAT_SELECT))
       return rc;
   }

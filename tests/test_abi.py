@@ -56,7 +56,16 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_flat_search(one, 10, nul, 1, 4, 0, 1, one, one, nul) == INVALID      # null q
     assert L.vs_flat_search(one, -1, one, 1, 4, 0, 1, one, one, nul) == INVALID
     assert L.vs_flat_search(nul, 10, nul, 0, 4, 0, 1, nul, nul, nul) == 0            # nq == 0: no-op
-    # vs_refine(x, nb, q, nq, d, metric, cand, kc, k, out_dist, out_ids, stream)
+    # flat index: vs_flat_create(out, d, metric), vs_flat_add(ix, x, n, stream),
+    # vs_flat_index_search(ix, q, nq, k, out_dist, out_ids, stream)
+    h = ctypes.c_void_p()
+    assert L.vs_flat_create(None, 4, 0) == INVALID
+    assert L.vs_flat_create(ctypes.byref(h), 0, 0) == INVALID and not h.value       # d < 1
+    assert L.vs_flat_create(ctypes.byref(h), 4, 5) == INVALID and not h.value       # metric
+    assert L.vs_flat_add(nul, one, 3, nul) == INVALID                                # null index
+    assert L.vs_flat_index_search(nul, one, 1, 1, one, one, nul) == INVALID
+    assert L.vs_flat_ntotal(nul) == -1
+    L.vs_flat_destroy(nul)                                                           # no-op
     assert L.vs_refine(one, 10, one, 1, 0, 0, one, 5, 1, one, one, nul) == INVALID       # d < 1
     assert L.vs_refine(one, 10, one, 1, 4, 0, one, 0, 1, one, one, nul) == INVALID       # kc < 1
     assert b"kc = 0" in L.vs_last_error()

@@ -450,6 +450,59 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
     check_search(Dm, Im, Do, Io, metric, q, xn)
 
 
+# ------------------------------------------------- flat index (prepared database)
+
+FLAT_INDEX_CASES = [
+    # name, nb, nq, d, k, metric, kind
+    ("sift_d128_k100", 30_000, 200, 128, 100, L2, "sift"),      # one matrix-core pass, row-major planes
+    ("gauss_d768_k10_ip", 5_000, 64, 768, 10, IP, "gauss"),     # tiled kernel, panel planes
+    ("gauss_d256_k30", 9_000, 70, 256, 30, L2, "gauss"),
+    ("gauss_d100_k20", 4_000, 50, 100, 20, L2, "gauss"),        # d the matrix-core route does not cover
+]
+
+
+@pytest.mark.parametrize("name,nb,nq,d,k,metric,kind", FLAT_INDEX_CASES, ids=[c[0] for c in FLAT_INDEX_CASES])
+def test_flat_index_equals_flat_search(vs, oracle, name, nb, nq, d, k, metric, kind):
+    """The flat index returns, after every add, exactly what the stateless flat search returns
+    on the rows stored so far (the prepared operand is laid out anew when the index grows),
+    and the final state agrees with the oracle."""
+    say("flat index %s nb=%d nq=%d d=%d k=%d metric=%d" % (name, nb, nq, d, k, metric))
+    if kind == "gauss":
+        rng = np.random.default_rng(zlib.crc32(name.encode()))
+        x = rng.standard_normal((nb, d), dtype=np.float32)
+        q = rng.standard_normal((nq, d), dtype=np.float32)
+    else:
+        x, q = S.make_data(S.config("C2", nb=nb, nq=nq, d=d, ncomp=30))
+    xd, qd = dev(x), dev(q)
+    ix = vs.Flat(d, metric)
+    assert ix.ntotal == 0
+    D0, I0 = ix.search(qd, k)                                   # empty index: empty slots
+    assert (host(I0) == -1).all()
+    assert np.isinf(host(D0)).all()
+    n = 0
+    for piece in (1000, 1, nb // 2, nb):                        # grows twice; a one-row add
+        m = min(piece, nb - n)
+        if m <= 0:
+            break
+        say("  add %d rows at %d" % (m, n))
+        ix.add(xd[n:n + m])
+        n += m
+        assert ix.ntotal == n
+        Di, Ii = ix.search(qd, k)
+        Ds, Is = vs.vs_flat_search(xd[:n], qd, k, metric)
+        np.testing.assert_array_equal(host(Ii), host(Is))
+        np.testing.assert_array_equal(host(Di), host(Ds))
+    assert n == nb
+    Do, Io = oracle.flat_search(x, q, min(k + EXTRA, nb), metric)
+    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max())
+    check_search(host(Di), host(Ii), Do, Io, metric, q, xn)
+    with pytest.raises(vs.VSError):
+        ix.search(qd, vs.VS_MAX_K + 1)
+    with pytest.raises(ValueError):
+        ix.add(xd[:3, : d - 1].contiguous())
+    ix.close()
+
+
 # ------------------------------------------------- refinement of a shortlist
 
 REFINE_CASES = [
