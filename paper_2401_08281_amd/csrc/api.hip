@@ -108,6 +108,7 @@ struct Planes {
   unsigned short* lo = nullptr;
   float* norm = nullptr;
   PrepInfo* info = nullptr;
+  int known_bf16 = -1;          // info->all_bf16 once the host has read it back, else -1
 };
 size_t planes_bytes(int64_t n, int d) {
   n = mfma_padded_rows(n);
@@ -127,7 +128,16 @@ Planes carve_planes(char* base, int64_t n, int d) {
 MfmaOperand operand(const float* x, int64_t n, const Planes& p) {
   MfmaOperand m;
   m.x = x; m.hi = p.hi; m.lo = p.lo; m.norm = p.norm; m.info = p.info; m.n = n;
+  m.known_bf16 = p.known_bf16;
   return m;
+}
+// After the preparation of an index's own operand has completed: tell the host whether the
+// rows are exactly bf16, so that searches enqueue only the sweep variant that will run.
+hipError_t learn_planes(Planes* p) {
+  PrepInfo h;
+  const hipError_t e = hipMemcpy(&h, p->info, sizeof(PrepInfo), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) p->known_bf16 = h.all_bf16 ? 1 : 0;
+  return e;
 }
 
 // Exact k best rows of B for every row of A (canon values, ties to the smaller index),
@@ -437,6 +447,7 @@ int vs_flat_add(vs_flat* ix, const float* x, int64_t n, void* hip_stream) {
     ix->has_planes = true;
   }
   HIP_TRY(hipStreamSynchronize(st));
+  if (planes) HIP_TRY(learn_planes(&ix->planes));
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
@@ -706,6 +717,7 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));
+  if (ix->has_planes) TRY_C(learn_planes(&ix->c_planes));
 #undef TRY_C
   *out = ix;
   return VS_OK;
@@ -1005,6 +1017,7 @@ int vs_ivfflat_create(vs_ivfflat** out, int32_t d, int32_t metric, int32_t nlist
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));
+  if (ix->has_planes) TRY_C(learn_planes(&ix->c_planes));
 #undef TRY_C
   *out = fx;
   return VS_OK;
@@ -1148,6 +1161,7 @@ int vs_ivfsq8_create(vs_ivfsq8** out, int32_t d, int32_t metric, int32_t nlist,
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));
+  if (ix->has_planes) TRY_C(learn_planes(&ix->c_planes));
 #undef TRY_C
   *out = sx;
   return VS_OK;

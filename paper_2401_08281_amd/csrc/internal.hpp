@@ -87,6 +87,7 @@ struct MfmaOperand {
   const float* norm;          // [n] squared norms
   const PrepInfo* info;
   int64_t n;
+  int known_bf16;             // info->all_bf16 where the host has read it back (0 / 1), else -1
 };
 bool mfma_knn_supported(int d, int k);
 // operand planes hold this many rows (the tail is zero padding)

@@ -833,6 +833,7 @@ __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ mini
 #pragma unroll
   for (int r = 0; r < RG; ++r) v[r] = order_f32(__builtin_inff());
   // value j goes to slot j % (64 * RG): lane (j / RG) % 64, register j % RG
+#pragma unroll 8
   for (int j0 = 0; j0 < g_raw; j0 += 64 * RG) {
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
@@ -886,16 +887,31 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   ws.init(slots, 64 * R, kp);
   bool truncated = false;
   int64_t total = 0;                                            // columns with m <= tau
-  for (int sp = 0; sp < nsplit; ++sp) {
-    const u64* __restrict__ src = shortlist + (row * nsplit + sp) * (int64_t)cap;
-    const int listed = cnt[row * nsplit + sp];
-    truncated = truncated || listed > cap;
-    total += listed;
-    const int n = min(listed, cap);
-    for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
-      const int j = j0 + lane;
-      const u64 key = j < n ? src[j] : KEY_EMPTY;
-      ws.push(j < n && key != KEY_EMPTY, key);
+  // (eight splits at a time: their counts and the first 64 slots of their lists -- cap >= 64,
+  // the slots exist whether filled or not -- are requested together, one round trip instead
+  // of sixteen; a handful of rows against many splits is bound by exactly these)
+  for (int sp0 = 0; sp0 < nsplit; sp0 += 8) {
+    int listed[8];
+    u64 first[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int sp = min(sp0 + u, nsplit - 1);
+      listed[u] = sp0 + u < nsplit ? cnt[row * nsplit + sp] : 0;
+      first[u] = shortlist[(row * nsplit + sp) * (int64_t)cap + lane];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (sp0 + u >= nsplit) break;
+      const u64* __restrict__ src = shortlist + (row * nsplit + sp0 + u) * (int64_t)cap;
+      truncated = truncated || listed[u] > cap;
+      total += listed[u];
+      const int n = min(listed[u], cap);
+      if (n > 0) ws.push(lane < n && first[u] != KEY_EMPTY, first[u]);
+      for (int j0 = VS_WAVE; j0 < n; j0 += VS_WAVE) {
+        const int j = j0 + lane;
+        const u64 key = j < n ? src[j] : KEY_EMPTY;
+        ws.push(j < n && key != KEY_EMPTY, key);
+      }
     }
   }
   ws.finish();
@@ -1231,6 +1247,14 @@ size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int d, int k, int* nspli
   return p.bytes;
 }
 
+// which operand-precision variant is ruled out by what the host knows of the operands
+static bool certainly_three(const MfmaOperand& A, const MfmaOperand& B) {
+  return A.known_bf16 == 0 || B.known_bf16 == 0;
+}
+static bool certainly_one(const MfmaOperand& A, const MfmaOperand& B) {
+  return A.known_bf16 == 1 && B.known_bf16 == 1;
+}
+
 template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
 static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
                            hipStream_t st) {
@@ -1255,10 +1279,13 @@ template <int KSTEPS, int METRIC, int MODE>
 static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
                            hipStream_t st) {
   // both operand-precision variants are enqueued; the kernel that does not match the flags
-  // written by operand preparation returns immediately (the flags live in device memory)
-  if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, false>(p, A, B, work, st);
-  else launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
-  launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
+  // written by operand preparation returns immediately (the flags live in device memory) --
+  // unless the host already knows an operand's flag and with it which variant cannot run
+  if (!certainly_three(A, B)) {
+    if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, false>(p, A, B, work, st);
+    else launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
+  }
+  if (!certainly_one(A, B)) launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
 }
 
 template <int METRIC, int MODE, bool THREE>
@@ -1283,12 +1310,13 @@ template <int MODE>
 static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                          int metric, char* work, hipStream_t st) {
   if (p.kc) {   // both operand-precision variants, as below
+    const bool one = !certainly_three(A, B), three = !certainly_one(A, B);
     if (metric == 0) {
-      launch_sweep_kc_t<0, MODE, false>(p, A, B, d, work, st);
-      launch_sweep_kc_t<0, MODE, true>(p, A, B, d, work, st);
+      if (one) launch_sweep_kc_t<0, MODE, false>(p, A, B, d, work, st);
+      if (three) launch_sweep_kc_t<0, MODE, true>(p, A, B, d, work, st);
     } else {
-      launch_sweep_kc_t<1, MODE, false>(p, A, B, d, work, st);
-      launch_sweep_kc_t<1, MODE, true>(p, A, B, d, work, st);
+      if (one) launch_sweep_kc_t<1, MODE, false>(p, A, B, d, work, st);
+      if (three) launch_sweep_kc_t<1, MODE, true>(p, A, B, d, work, st);
     }
     return;
   }
