@@ -246,7 +246,7 @@ __global__ void prep_info_init_kernel(PrepInfo* info) {
 // Every column that is NOT listed has m > tau, which is what the re-rank kernel's
 // sufficiency test needs.
 // ---------------------------------------------------------------------------
-template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
+template <int KSTEPS, int RB, int METRIC, int MODE, int PREC>
 __global__ __launch_bounds__(256, 2)
 void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
                        const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
@@ -256,14 +256,24 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
                        int64_t cols_per_phase,
                        float* __restrict__ minima, int g_raw,       // MODE 0 out: [na][g_raw]
                        const float* __restrict__ tau,               // MODE 1 in:  [na]
-                       int* __restrict__ cnt, u64* __restrict__ shortlist, int cap) {  // MODE 1 out
+                       int* __restrict__ cnt, u64* __restrict__ shortlist, int cap,    // MODE 1 out
+                       int allow_two) {
+  // PREC: which products the operands need.  0: both are exactly bf16 -- heads only.  1: A is
+  // exact, B is not -- A's tails are zero, so head x head + head x tail (two passes; A's tail
+  // plane is never read).  2: head x head + head x tail + tail x head (three passes).
+  constexpr bool THREE = PREC == 2, LOB = PREC >= 1;
   constexpr int D = KSTEPS * 16, BN = 64, LDB = D + 8;            // LDS row stride in bf16 elements
-  constexpr int NPL = THREE ? 2 : 1;                              // planes of B in LDS
+  constexpr int NPL = LOB ? 2 : 1;                                // planes of B in LDS
   constexpr int CHUNKS = BN * (D / 8);                            // 16-byte chunks per plane per step
   constexpr int CPT = (CHUNKS + 255) / 256;                       // chunks per lane
   constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
-  // both variants are launched; the one that does not match the operands' flags leaves at once
-  if ((!(Ainfo->all_bf16 && Binfo->all_bf16)) != THREE) return;
+  // the variants that may be needed are all launched; those that do not match the operands'
+  // flags leave at once (the two-pass variant is only enqueued for long A: allow_two)
+  {
+    const bool ea = Ainfo->all_bf16 != 0, eb = Binfo->all_bf16 != 0;
+    const int want = ea && eb ? 0 : (ea && allow_two ? 1 : 2);
+    if (want != PREC) return;
+  }
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short* bt = reinterpret_cast<unsigned short*>(smem);   // [2 buffers][NPL][BN][LDB]
@@ -342,14 +352,14 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
       const unsigned short* __restrict__ tl_ = Blo + (CT) * D;                                   \
       _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                       \
         stg[0][i_] = *reinterpret_cast<const u32x4*>(th_ + g_lin[i_]);                           \
-        if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(tl_ + g_lin[i_]); \
+        if constexpr (LOB) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(tl_ + g_lin[i_]);   \
       }                                                                                          \
       stn = Bnorm[(CT) + (tid & 63)];                                                            \
     } else {                                                                                     \
       _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                       \
         const int64_t o_ = min((CT) + g_row[i_], b_last) * D + g_col[i_];                        \
         stg[0][i_] = *reinterpret_cast<const u32x4*>(Bhi + o_);                                  \
-        if constexpr (THREE) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(Blo + o_);       \
+        if constexpr (LOB) stg[NPL - 1][i_] = *reinterpret_cast<const u32x4*>(Blo + o_);         \
       }                                                                                          \
       stn = Bnorm[min((CT) + (int64_t)(tid & 63) * stride, b_last)];                             \
     }                                             /* stn is consumed only at the stash */        \
@@ -400,38 +410,36 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
     // their use; the scheduling groups below pin that order (one LDS read per product group)
     constexpr int NF = KSTEPS * 2, PF = 4;
     static_assert(NF >= PF, "ring deeper than the tile");
-    bf16x8 rh[PF], rl[THREE ? PF : 1];
+    bf16x8 rh[PF], rl[LOB ? PF : 1];
 #define FRAG_OFF(F) ((((F) & 1) * 32 + (lane & 31)) * LDB + ((F) >> 1) * 16 + 8 * (lane >> 5))
 #pragma unroll
     for (int f = 0; f < PF; ++f) {
       rh[f] = *reinterpret_cast<const bf16x8*>(bth + FRAG_OFF(f));
-      if constexpr (THREE) rl[f] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f));
+      if constexpr (LOB) rl[f] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f));
     }
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
       const int kk = f >> 1, cb = f & 1;
       const bf16x8 ch = rh[f % PF];
       bf16x8 cl;
-      if constexpr (THREE) cl = rl[f % PF];
+      if constexpr (LOB) cl = rl[f % PF];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         // the first product starts from 0 (MODE 0) or from the row thresholds (MODE 1)
         m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], ch, kk == 0 ? tr[rb] : m[rb][cb], 0, 0, 0);
-        if constexpr (THREE) {
-          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], cl, m[rb][cb], 0, 0, 0);
-          m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], ch, m[rb][cb], 0, 0, 0);
-        }
+        if constexpr (LOB) m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], cl, m[rb][cb], 0, 0, 0);
+        if constexpr (THREE) m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], ch, m[rb][cb], 0, 0, 0);
       }
       if (f + PF < NF) {
         rh[f % PF] = *reinterpret_cast<const bf16x8*>(bth + FRAG_OFF(f + PF));
-        if constexpr (THREE) rl[f % PF] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f + PF));
+        if constexpr (LOB) rl[f % PF] = *reinterpret_cast<const bf16x8*>(bth + BN * LDB + FRAG_OFF(f + PF));
       }
     }
 #undef FRAG_OFF
     __builtin_amdgcn_sched_group_barrier(0x100, PF * NPL, 0);                       // LDS reads
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-      __builtin_amdgcn_sched_group_barrier(0x008, RB * (THREE ? 3 : 1), 0);         // matrix products
+      __builtin_amdgcn_sched_group_barrier(0x008, RB * (PREC + 1), 0);              // matrix products
       if (f + PF < NF) __builtin_amdgcn_sched_group_barrier(0x100, NPL, 0);
     }
     const float b0 = bns[buf * BN + (lane & 31)], b1 = bns[buf * BN + 32 + (lane & 31)];
@@ -1254,15 +1262,19 @@ static bool certainly_three(const MfmaOperand& A, const MfmaOperand& B) {
 static bool certainly_one(const MfmaOperand& A, const MfmaOperand& B) {
   return A.known_bf16 == 1 && B.known_bf16 == 1;
 }
+// The two-pass variant is one more (possibly empty) launch: only for an A long enough that
+// the sweeps, not the launches, are what a call costs.  The kernels get the same answer as
+// a flag, so that exactly one variant takes the work.
+static bool two_pass_allowed(const MfmaOperand& A) { return A.n >= 256; }
 
-template <int KSTEPS, int RB, int METRIC, int MODE, bool THREE>
+template <int KSTEPS, int RB, int METRIC, int MODE, int PREC>
 static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
                            hipStream_t st) {
-  constexpr int D = KSTEPS * 16, NPL = THREE ? 2 : 1;
+  constexpr int D = KSTEPS * 16, NPL = PREC >= 1 ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * 64 * (D + 8) * sizeof(unsigned short) + 2 * 64 * sizeof(float) +
                        (size_t)128 * RB * (sizeof(int) + sizeof(float)) +
                        4 * 128 * (sizeof(u64) + sizeof(int));
-  auto kern = &mfma_sweep_kernel<KSTEPS, RB, METRIC, MODE, THREE>;
+  auto kern = &mfma_sweep_kernel<KSTEPS, RB, METRIC, MODE, PREC>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -1272,7 +1284,7 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
-                     reinterpret_cast<u64*>(work), p.cap);
+                     reinterpret_cast<u64*>(work), p.cap, two_pass_allowed(A) ? 1 : 0);
 }
 
 template <int KSTEPS, int METRIC, int MODE>
@@ -1282,10 +1294,15 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   // written by operand preparation returns immediately (the flags live in device memory) --
   // unless the host already knows an operand's flag and with it which variant cannot run
   if (!certainly_three(A, B)) {
-    if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, false>(p, A, B, work, st);
-    else launch_sweep_t<KSTEPS, 1, METRIC, MODE, false>(p, A, B, work, st);
+    if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, 0>(p, A, B, work, st);
+    else launch_sweep_t<KSTEPS, 1, METRIC, MODE, 0>(p, A, B, work, st);
   }
-  if (!certainly_one(A, B)) launch_sweep_t<KSTEPS, 1, METRIC, MODE, true>(p, A, B, work, st);
+  if (!certainly_one(A, B)) {
+    // A exact and B not (integer vectors against trained centroids): two passes instead of three
+    if (two_pass_allowed(A) && A.known_bf16 != 0 && B.known_bf16 != 1)
+      launch_sweep_t<KSTEPS, 1, METRIC, MODE, 1>(p, A, B, work, st);
+    launch_sweep_t<KSTEPS, 1, METRIC, MODE, 2>(p, A, B, work, st);
+  }
 }
 
 template <int METRIC, int MODE, bool THREE>

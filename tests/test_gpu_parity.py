@@ -397,6 +397,10 @@ ROUTE_CASES = [
     ("unit_d768_k32_ip", 9_000, 300, 768, 32, IP, "unit"),
     ("sift_d256_k20", 40_000, 64, 256, 20, L2, "sift"),
     ("gauss_d2048_k5", 3_000, 40, 2048, 5, L2, "gauss"),
+    # integer queries (exactly bf16) against a general database: the two-pass variant (nq >= 256)
+    ("int_q_float_x_d128_k20", 30_000, 700, 128, 20, L2, "int_q"),
+    ("int_q_float_x_d64_k5_ip", 8_000, 300, 64, 5, IP, "int_q"),
+    ("int_q_float_x_d96_few_rows", 8_000, 40, 96, 10, L2, "int_q"),    # short A: three passes
     # B barely longer than the shortlist: fewer finite group minima than the wanted rank
     ("gauss_d256_k100_short_b", 190, 70, 256, 100, L2, "gauss"),
     ("gauss_d160_k150_ip_short_b", 300, 33, 160, 150, IP, "gauss"),
@@ -418,6 +422,10 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
         rng = np.random.default_rng(zlib.crc32(name.encode()))
         x = rng.standard_normal((nb, d), dtype=np.float32)
         q = rng.standard_normal((nq, d), dtype=np.float32)
+    elif kind == "int_q":
+        rng = np.random.default_rng(zlib.crc32(name.encode()))
+        x = (30.0 * rng.standard_normal((nb, d))).astype(np.float32)
+        q = np.rint(30.0 * rng.standard_normal((nq, d))).astype(np.float32)
     elif kind.startswith("unit"):
         x, q = S.make_data(S.config("C4", nb=nb, nq=nq, d=d, ncomp=30))
     else:
