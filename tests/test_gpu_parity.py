@@ -466,6 +466,7 @@ FLAT_INDEX_CASES = [
     ("gauss_d768_k10_ip", 5_000, 64, 768, 10, IP, "gauss"),     # tiled kernel, panel planes
     ("gauss_d256_k30", 9_000, 70, 256, 30, L2, "gauss"),
     ("gauss_d100_k20", 4_000, 50, 100, 20, L2, "gauss"),        # d the matrix-core route does not cover
+    ("sift_d128_k300", 6_000, 33, 128, 300, L2, "sift"),        # k beyond the matrix-core route: planes unused
 ]
 
 
