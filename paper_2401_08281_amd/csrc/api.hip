@@ -575,12 +575,16 @@ int kmeans_rounds(const float* x, int64_t n, int d, int K, int niter, float* cen
       ++h_off[(size_t)j + 1];
     }
     if (objective) objective[r] = n > 0 ? obj / (double)n : 0.0;
+    int64_t largest = 0;
+    for (int j = 0; j < K; ++j) largest = std::max(largest, h_off[(size_t)j + 1]);
     for (int j = 0; j < K; ++j) { h_off[(size_t)j + 1] += h_off[(size_t)j]; cursor[(size_t)j] = h_off[(size_t)j]; }
     for (int64_t i = 0; i < n; ++i) h_order[(size_t)cursor[(size_t)h_idx[(size_t)i]]++] = (int32_t)i;
     HIP_TRY(hipMemcpyAsync(order, h_order.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(off, h_off.data(), h_off.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    // (2) every centroid moves to the mean of its vectors
-    launch_segmented_mean(x, d, order, off, K, centroids, st);
+    // (2) every centroid moves to the mean of its vectors (the assignment's scratch is free
+    // again: it holds the block sums of clusters longer than one summation block)
+    if (int rc = sc.reserve(segmented_mean_partial_bytes(n, d, K, largest))) return rc;
+    launch_segmented_mean(x, d, order, off, K, largest, centroids, static_cast<double*>(sc.p), st);
     HIP_TRY(hipStreamSynchronize(st));   // the host arrays are reused by the next round
   }
   HIP_TRY(hipGetLastError());

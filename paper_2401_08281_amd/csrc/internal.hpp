@@ -132,10 +132,13 @@ void launch_ivfsq8_scan(int d, int metric, const float* q, int64_t nq, const flo
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 
 // ---- kernels_train.hip ---------------------------------------------------------
-// centroids[j] <- mean of the rows x[order[off[j] .. off[j + 1])] (float64 sum in that order);
-// a centroid with an empty range keeps its value
+// centroids[j] <- mean of the rows x[order[off[j] .. off[j + 1])] (float64 sum in that order, in
+// blocks of 4096 rows whose sums are added in block order); a centroid with an empty range keeps
+// its value.  `largest` = the largest range's length; `partial` = work space of
+// segmented_mean_partial_bytes (may be null when that is 0)
+size_t segmented_mean_partial_bytes(int64_t n, int d, int K, int64_t largest);
 void launch_segmented_mean(const float* x, int d, const int32_t* order, const int64_t* off, int K,
-                           float* centroids, hipStream_t st);
+                           int64_t largest, float* centroids, double* partial, hipStream_t st);
 // out[m][i][:] = (x[i] - centroids[list_of[i]])[m * dsub : (m + 1) * dsub], out is [d / dsub][n][dsub]
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,
                             const int32_t* list_of, float* out, hipStream_t st);

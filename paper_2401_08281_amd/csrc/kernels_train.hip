@@ -9,11 +9,19 @@
 
 namespace {
 
-// One wavefront per centroid j.  order[off[j] .. off[j + 1]) lists the vectors assigned to
-// it in ascending order; lane t adds up dimensions t, t + 64, ... of those vectors in
-// float64, in that order -- a fixed order, so the sum has one value however the kernel is
-// scheduled -- and stores sum / count rounded to fp32.  A centroid without vectors is left
-// as it is.  Dimensions are taken 64 * NC at a time (NC = 1, 2 or 4).
+constexpr int64_t kBlock = 4096;   // vectors per summation block (a multiple of every batch below)
+
+// One wavefront per (centroid j, block of kBlock vectors).  order[off[j] .. off[j + 1])
+// lists the vectors assigned to centroid j in ascending order; they are summed in float64 in
+// blocks of kBlock: a block from 0 in the list's order, the block sums in block order -- a
+// fixed order, so the sum has one value however the kernels are scheduled, and the blocks of
+// a large cluster run side by side (sixteen centroids over millions of sub-vectors would
+// otherwise be sixteen chains).  A centroid of one block stores sum / count rounded to fp32
+// directly; the others store their block sums to `partial` (block bk of centroid j at slot
+// off[j] / kBlock + j + bk: the slots of different centroids never overlap) and
+// segmented_mean_finish_kernel adds them up.  A centroid without vectors is left as it is.
+// Lane t adds up dimensions t, t + 64, ...; dimensions are taken 64 * NC at a time (NC = 1,
+// 2 or 4).
 // The chain of a large cluster is long (it sets the kernel's time), so the memory latency
 // is taken off it: 64 / NC vectors at a time, their numbers come in with one load, their
 // rows are all requested before the first is added, and the additions then run in the
@@ -22,15 +30,19 @@ template <int NC>
 __global__ __launch_bounds__(256) void segmented_mean_kernel(const float* __restrict__ x, int d,
                                                              const int32_t* __restrict__ order,
                                                              const int64_t* __restrict__ off, int K,
-                                                             float* __restrict__ centroids) {
+                                                             float* __restrict__ centroids,
+                                                             double* __restrict__ partial) {
   constexpr int NB = 64 / NC;
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int64_t j = blockIdx.x * 4ll + wave;
   if (j >= K) return;
-  const int64_t b = off[j], e = off[j + 1];
-  if (b == e) return;
-  const double count = (double)(e - b);
+  const int64_t b0 = off[j], e0 = off[j + 1];
+  if (b0 == e0) return;
+  const double count = (double)(e0 - b0);
+  const int64_t nblk = (e0 - b0 + kBlock - 1) / kBlock;
+  for (int64_t bk = blockIdx.y; bk < nblk; bk += gridDim.y)
   for (int t0 = 0; t0 < d; t0 += 64 * NC) {
+    const int64_t b = b0 + bk * kBlock, e = min(e0, b + kBlock);
     double acc[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) acc[c] = 0.0;
@@ -63,7 +75,10 @@ __global__ __launch_bounds__(256) void segmented_mean_kernel(const float* __rest
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int t = t0 + lane + 64 * c;
-      if (t < d) centroids[j * d + t] = (float)(acc[c] / count);
+      if (t < d) {
+        if (nblk == 1) centroids[j * d + t] = (float)(acc[c] / count);
+        else partial[(b0 / kBlock + j + bk) * d + t] = acc[c];
+      }
     }
   }
 }
@@ -78,16 +93,21 @@ template <int DP>
 __global__ __launch_bounds__(256) void segmented_mean_small_kernel(const float* __restrict__ x, int d,
                                                                    const int32_t* __restrict__ order,
                                                                    const int64_t* __restrict__ off, int K,
-                                                                   float* __restrict__ centroids) {
+                                                                   float* __restrict__ centroids,
+                                                                   double* __restrict__ partial) {
   constexpr int VPL = 64 / DP, NU = 16, NBV = NU * VPL;          // vectors per load, loads and vectors per batch
   constexpr int NO = (NBV + 63) / 64;                            // registers of vector numbers per batch
+  static_assert(kBlock % NBV == 0, "whole batches per block");
   const int wave = threadIdx.x >> 6, lane = lane_id();
   const int s = lane / DP, t = lane % DP;
   const int64_t j = blockIdx.x * 4ll + wave;
   if (j >= K) return;
-  const int64_t b = off[j], e = off[j + 1];
-  if (b == e) return;
-  const double count = (double)(e - b);
+  const int64_t b0 = off[j], e0 = off[j + 1];
+  if (b0 == e0) return;
+  const double count = (double)(e0 - b0);
+  const int64_t nblk = (e0 - b0 + kBlock - 1) / kBlock;
+  for (int64_t bk = blockIdx.y; bk < nblk; bk += gridDim.y) {
+  const int64_t b = b0 + bk * kBlock, e = min(e0, b + kBlock);
   double acc = 0.0;
   int64_t i = b;
   for (; i + NBV <= e; i += NBV) {
@@ -108,7 +128,31 @@ __global__ __launch_bounds__(256) void segmented_mean_small_kernel(const float* 
   }
   for (; i < e; ++i)                                             // the rest, one vector at a time
     if (t < d) acc += (double)x[(int64_t)order[i] * d + t];
-  if (s == 0 && t < d) centroids[j * d + t] = (float)(acc / count);
+  if (s == 0 && t < d) {
+    if (nblk == 1) centroids[j * d + t] = (float)(acc / count);
+    else partial[(b0 / kBlock + j + bk) * d + t] = acc;
+  }
+  }
+}
+
+// Centroids of more than one block: the block sums in block order, then the mean.
+__global__ __launch_bounds__(256) void segmented_mean_finish_kernel(const double* __restrict__ partial,
+                                                                    int d,
+                                                                    const int64_t* __restrict__ off, int K,
+                                                                    float* __restrict__ centroids) {
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int64_t j = blockIdx.x * 4ll + wave;
+  if (j >= K) return;
+  const int64_t b0 = off[j], e0 = off[j + 1];
+  const int64_t nblk = (e0 - b0 + kBlock - 1) / kBlock;
+  if (nblk <= 1) return;
+  const double count = (double)(e0 - b0);
+  const double* __restrict__ src = partial + (b0 / kBlock + j) * d;
+  for (int t = lane; t < d; t += VS_WAVE) {
+    double total = 0.0;
+    for (int64_t bk = 0; bk < nblk; ++bk) total += src[bk * d + t];
+    centroids[j * d + t] = (float)(total / count);
+  }
 }
 
 // out[m][i][u] = x[i][m * dsub + u] - centroids[list_of[i]][m * dsub + u]: the residual of
@@ -130,16 +174,26 @@ __global__ __launch_bounds__(256) void residual_slices_kernel(const float* __res
 
 }  // namespace
 
+size_t segmented_mean_partial_bytes(int64_t n, int d, int K, int64_t largest) {
+  if (largest <= kBlock) return 0;
+  return (size_t)(n / kBlock + K + 1) * d * sizeof(double);
+}
+
 void launch_segmented_mean(const float* x, int d, const int32_t* order, const int64_t* off, int K,
-                           float* centroids, hipStream_t st) {
+                           int64_t largest, float* centroids, double* partial, hipStream_t st) {
   if (K <= 0) return;
-  const dim3 grid((unsigned)((K + 3) / 4)), block(256);
-  if (d <= 8) hipLaunchKernelGGL((segmented_mean_small_kernel<8>), grid, block, 0, st, x, d, order, off, K, centroids);
-  else if (d <= 16) hipLaunchKernelGGL((segmented_mean_small_kernel<16>), grid, block, 0, st, x, d, order, off, K, centroids);
-  else if (d <= 32) hipLaunchKernelGGL((segmented_mean_small_kernel<32>), grid, block, 0, st, x, d, order, off, K, centroids);
-  else if (d <= 64) hipLaunchKernelGGL((segmented_mean_kernel<1>), grid, block, 0, st, x, d, order, off, K, centroids);
-  else if (d <= 128) hipLaunchKernelGGL((segmented_mean_kernel<2>), grid, block, 0, st, x, d, order, off, K, centroids);
-  else hipLaunchKernelGGL((segmented_mean_kernel<4>), grid, block, 0, st, x, d, order, off, K, centroids);
+  // `largest` = size of the largest cluster (the host counted): its number of blocks is the grid's second dimension
+  const int64_t nblk = std::max<int64_t>(1, (largest + kBlock - 1) / kBlock);
+  const dim3 grid((unsigned)((K + 3) / 4), (unsigned)std::min<int64_t>(nblk, 65535)), block(256);
+  if (d <= 8) hipLaunchKernelGGL((segmented_mean_small_kernel<8>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  else if (d <= 16) hipLaunchKernelGGL((segmented_mean_small_kernel<16>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  else if (d <= 32) hipLaunchKernelGGL((segmented_mean_small_kernel<32>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  else if (d <= 64) hipLaunchKernelGGL((segmented_mean_kernel<1>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  else if (d <= 128) hipLaunchKernelGGL((segmented_mean_kernel<2>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  else hipLaunchKernelGGL((segmented_mean_kernel<4>), grid, block, 0, st, x, d, order, off, K, centroids, partial);
+  if (nblk > 1)
+    hipLaunchKernelGGL(segmented_mean_finish_kernel, dim3((unsigned)((K + 3) / 4)), block, 0, st, partial, d, off, K,
+                       centroids);
 }
 
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,

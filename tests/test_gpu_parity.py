@@ -866,6 +866,13 @@ KMEANS_CASES = [
     ("subvectors_d12_k20", 20_000, 12, 20, 3, "gauss"),
     ("subvectors_d3_k8", 9_000, 3, 8, 3, "gauss"),
     ("more_centroids_than_vectors", 40, 8, 64, 2, "gauss"),
+    # clusters longer than one summation block (4096 vectors): block sums, then their sum
+    ("long_clusters_d8_k4", 40_000, 8, 4, 3, "gauss"),
+    ("long_clusters_d12_k3", 30_001, 12, 3, 2, "gauss"),
+    ("long_clusters_d32_k5", 33_000, 32, 5, 2, "gauss"),
+    ("long_clusters_d96_k3", 20_000, 96, 3, 2, "unit"),
+    ("long_clusters_d200_k2", 13_000, 200, 2, 2, "gauss"),
+    ("long_and_short_clusters_d64", 25_000, 64, 40, 2, "sift"),
 ]
 
 

@@ -458,6 +458,25 @@ def test_kmeans_round_is_assign_then_mean(oracle):
     np.testing.assert_allclose(oracle.kmeans(x, c0, 1)[0], first.astype(np.float32), rtol=1e-6)
 
 
+def test_kmeans_mean_of_a_cluster_longer_than_one_summation_block(oracle):
+    """The update sums a centroid's vectors in float64 in blocks of 4096; whatever the order, a
+    float64 sum of 10,000 fp32 values of comparable size is within 1e-12 relative of the exact
+    sum, so the fp32 mean equals the correctly rounded mean of exact rational arithmetic in all
+    but a vanishing share of components -- checked here against Python's exact fractions, and
+    against numpy's pairwise float64 sum to the last fp32 bit but one."""
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((10_000, 3)).astype(np.float32) + np.float32(5.0)   # one cluster, far from 0
+    c0 = np.array([[5.0, 5.0, 5.0], [-50.0, -50.0, -50.0]], np.float32)          # the second gets nothing
+    c, _ = oracle.kmeans(x, c0, 1)
+    np.testing.assert_array_equal(c[1], c0[1])
+    for t in range(3):
+        exact = sum((Fraction(float(v)) for v in x[:, t]), Fraction(0)) / x.shape[0]
+        assert c[0, t] == np.float32(float(exact)), (t, c[0, t], float(exact))
+    ref = (x.astype(np.float64).sum(0) / x.shape[0]).astype(np.float32)
+    assert np.all(np.abs(c[0].view(np.int32) - ref.view(np.int32)) <= 1)
+
+
 def test_kmeans_objective_never_increases(oracle):
     # Both of Lloyd's steps can only lower the mean squared error.
     rng = np.random.default_rng(32)
