@@ -550,17 +550,45 @@ int nearest_rows(const float* A, int64_t n, const float* B, int64_t nb, int d, i
   return VS_OK;
 }
 
+struct DeviceBuf {   // a plain allocation released on scope exit
+  void* p = nullptr;
+  ~DeviceBuf() { if (p) (void)hipFree(p); }
+  int alloc(size_t bytes) { HIP_TRY(hipMalloc(&p, std::max<size_t>(bytes, 256))); return VS_OK; }
+};
+
 // niter rounds of Lloyd's iteration on device data.  dev_buf: idx [n] int32 | val [n] fp32 |
 // order [n] int32 | off [K + 1] int64, carved by the caller; sc: scratch of the assignment.
 int kmeans_rounds(const float* x, int64_t n, int d, int K, int niter, float* centroids,
                   double* objective, int32_t* idx, float* val, int32_t* order, int64_t* off,
                   Scratch& sc, hipStream_t st) {
-  std::vector<int32_t> h_idx((size_t)n), h_order((size_t)n);
-  std::vector<float> h_val((size_t)n);
+  // Up to 16384 centroids the bookkeeping of a round (the objective, and every centroid's
+  // vectors in ascending order) stays on the device; beyond, the host does it.
+  const bool on_device = K <= 16384 && n > 0;
+  DeviceBuf sortbuf;
+  if (on_device) { if (int rc = sortbuf.alloc(kmeans_sort_bytes(n, K))) return rc; }
+  std::vector<int32_t> h_idx(on_device ? 0 : (size_t)n), h_order(on_device ? 0 : (size_t)n);
+  std::vector<float> h_val(on_device ? 0 : (size_t)n);
   std::vector<int64_t> h_off((size_t)K + 1), cursor((size_t)K);
   for (int r = 0; r < niter; ++r) {
     // (1) nearest centroid of every vector: canon L2, ties to the smaller centroid number
     if (int rc = nearest_rows(x, n, centroids, K, d, VS_METRIC_L2, idx, val, sc, st)) return rc;
+    if (on_device) {
+      int64_t* scal = nullptr;
+      double* partial = nullptr;
+      launch_kmeans_sort(idx, val, n, K, static_cast<char*>(sortbuf.p), order, off, &scal, &partial, st);
+      int64_t h_scal[2];
+      double h_part[256];
+      HIP_TRY(hipMemcpyAsync(h_scal, scal, sizeof(h_scal), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipMemcpyAsync(h_part, partial, sizeof(h_part), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      if (h_scal[1] != 0) return fail(VS_ERR_DEVICE, "k-means: assignment produced a centroid outside [0, %d)", K);
+      double obj = 0.0;
+      for (int t = 0; t < 256; ++t) obj += h_part[t];
+      if (objective) objective[r] = obj / (double)n;
+      if (int rc = sc.reserve(segmented_mean_partial_bytes(n, d, K, h_scal[0]))) return rc;
+      launch_segmented_mean(x, d, order, off, K, h_scal[0], centroids, static_cast<double*>(sc.p), st);
+      continue;
+    }
     HIP_TRY(hipMemcpyAsync(h_idx.data(), idx, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipMemcpyAsync(h_val.data(), val, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -587,15 +615,10 @@ int kmeans_rounds(const float* x, int64_t n, int d, int K, int niter, float* cen
     launch_segmented_mean(x, d, order, off, K, largest, centroids, static_cast<double*>(sc.p), st);
     HIP_TRY(hipStreamSynchronize(st));   // the host arrays are reused by the next round
   }
+  HIP_TRY(hipStreamSynchronize(st));     // the centroids are final when the call returns
   HIP_TRY(hipGetLastError());
   return VS_OK;
 }
-
-struct DeviceBuf {   // a plain allocation released on scope exit
-  void* p = nullptr;
-  ~DeviceBuf() { if (p) (void)hipFree(p); }
-  int alloc(size_t bytes) { HIP_TRY(hipMalloc(&p, std::max<size_t>(bytes, 256))); return VS_OK; }
-};
 
 }  // namespace
 

@@ -139,6 +139,12 @@ void launch_ivfsq8_scan(int d, int metric, const float* q, int64_t nq, const flo
 size_t segmented_mean_partial_bytes(int64_t n, int d, int K, int64_t largest);
 void launch_segmented_mean(const float* x, int d, const int32_t* order, const int64_t* off, int K,
                            int64_t largest, float* centroids, double* partial, hipStream_t st);
+// stable counting sort of the assignment idx [n] by centroid (K <= 16384) and the float64 sum
+// of val [n]: order [n], off [K + 1]; scal[0] = largest cluster, scal[1] != 0 if an
+// assignment was outside [0, K); partial [256] sums to the sum of val
+size_t kmeans_sort_bytes(int64_t n, int K);
+void launch_kmeans_sort(const int32_t* idx, const float* val, int64_t n, int K, char* work, int32_t* order,
+                        int64_t* off, int64_t** scal_out, double** partial_out, hipStream_t st);
 // out[m][i][:] = (x[i] - centroids[list_of[i]])[m * dsub : (m + 1) * dsub], out is [d / dsub][n][dsub]
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,
                             const int32_t* list_of, float* out, hipStream_t st);

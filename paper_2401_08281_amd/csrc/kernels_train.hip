@@ -155,6 +155,117 @@ __global__ __launch_bounds__(256) void segmented_mean_finish_kernel(const double
   }
 }
 
+// ---- bookkeeping of a k-means round on the device -----------------------------------
+// The update needs, for every centroid, the numbers of its vectors in ascending order: a
+// stable counting sort of the assignment idx [n] by centroid.  The vectors are cut into at
+// most 256 chunks of consecutive vectors:
+//   km_hist_kernel     per chunk, how many vectors go to each centroid        mat [nchunk][K]
+//   km_colscan_kernel  per centroid, exclusive running sum down the chunks (in place) and the total
+//   km_offsets_kernel  exclusive sum of the totals = first slot of each centroid, off [K + 1];
+//                      the largest total
+//   km_scatter_kernel  one wavefront per chunk walks over its vectors in order, 64 at a time:
+//                      lanes with the same centroid are ranked by lane number (ballot), so
+//                      every vector gets slot off[j] + (vectors of j in earlier chunks) +
+//                      (earlier vectors of j in this chunk): the stable order.
+// K <= 16384 (one counter per centroid in LDS); the host does the same sort otherwise.
+__global__ __launch_bounds__(256) void km_hist_kernel(const int32_t* __restrict__ idx, int64_t n, int K,
+                                                      int64_t chunk, int32_t* __restrict__ mat,
+                                                      int* __restrict__ bad) {
+  extern __shared__ int km_lds[];
+  for (int j = threadIdx.x; j < K; j += 256) km_lds[j] = 0;
+  __syncthreads();
+  const int64_t i0 = blockIdx.x * chunk, i1 = min(n, i0 + chunk);
+  for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) {
+    const int32_t j = idx[i];
+    if (j < 0 || j >= K) *bad = 1;
+    else atomicAdd(&km_lds[j], 1);
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < K; j += 256) mat[(int64_t)blockIdx.x * K + j] = km_lds[j];
+}
+
+__global__ __launch_bounds__(256) void km_colscan_kernel(int32_t* __restrict__ mat, int nchunk, int K,
+                                                         int64_t* __restrict__ cnt) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= K) return;
+  int32_t run = 0;
+  for (int c = 0; c < nchunk; ++c) {
+    const int32_t v = mat[(int64_t)c * K + j];
+    mat[(int64_t)c * K + j] = run;
+    run += v;
+  }
+  cnt[j] = run;
+}
+
+// one workgroup: lane t owns centroids [t * per, (t + 1) * per)
+__global__ __launch_bounds__(256) void km_offsets_kernel(const int64_t* __restrict__ cnt, int K,
+                                                         int64_t* __restrict__ off,
+                                                         int64_t* __restrict__ largest) {
+  __shared__ int64_t part[256], big[256];
+  const int t = threadIdx.x, per = (K + 255) / 256;
+  const int j0 = min(K, t * per), j1 = min(K, j0 + per);
+  int64_t sum = 0, mx = 0;
+  for (int j = j0; j < j1; ++j) { sum += cnt[j]; mx = max(mx, cnt[j]); }
+  part[t] = sum; big[t] = mx;
+  __syncthreads();
+  int64_t base = 0;
+  for (int u = 0; u < t; ++u) base += part[u];
+  for (int j = j0; j < j1; ++j) { off[j] = base; base += cnt[j]; }
+  if (t == 255) {
+    int64_t total = 0, m = 0;
+    for (int u = 0; u < 256; ++u) { total += part[u]; m = max(m, big[u]); }
+    off[K] = total;
+    *largest = m;
+  }
+}
+
+__global__ __launch_bounds__(64) void km_scatter_kernel(const int32_t* __restrict__ idx, int64_t n, int K,
+                                                        int64_t chunk, const int32_t* __restrict__ mat,
+                                                        const int64_t* __restrict__ off,
+                                                        int32_t* __restrict__ order) {
+  extern __shared__ int km_lds[];                       // next slot of every centroid for this chunk
+  const int lane = lane_id();
+  for (int j = lane; j < K; j += VS_WAVE) km_lds[j] = (int)(off[j] + mat[(int64_t)blockIdx.x * K + j]);
+  wave_lds_sync();
+  const int64_t i0 = blockIdx.x * chunk, i1 = min(n, i0 + chunk);
+  for (int64_t g = i0; g < i1; g += VS_WAVE) {
+    const int64_t i = g + lane;
+    const bool valid = i < i1;
+    int32_t key = valid ? idx[i] : -1;
+    if (key >= K) key = -1;                             // (flagged by km_hist_kernel; never stored)
+    u64 todo = __builtin_amdgcn_ballot_w64(key >= 0);
+    while (todo != 0) {                                 // one round per distinct centroid among the 64
+      const int leader = __builtin_ctzll(todo);
+      const int32_t k = __shfl(key, leader);
+      const u64 same = __builtin_amdgcn_ballot_w64(key == k);
+      const int base = km_lds[k];
+      if (key == k) order[base + __popcll(same & ((1ull << lane) - 1ull))] = (int32_t)i;
+      wave_lds_sync();                                  // everyone has read the slot before it moves
+      if (lane == leader) km_lds[k] = base + __popcll(same);
+      wave_lds_sync();
+      todo &= ~same;
+    }
+  }
+}
+
+// Sum of val [n] in float64 in a fixed order: workgroup w sums a contiguous slice (lane-strided,
+// then a fixed tree), the host adds the 256 partial sums in order.
+__global__ __launch_bounds__(256) void km_objective_kernel(const float* __restrict__ val, int64_t n,
+                                                           double* __restrict__ partial) {
+  __shared__ double red[256];
+  const int64_t per = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t i0 = blockIdx.x * per, i1 = min(n, i0 + per);
+  double acc = 0.0;
+  for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) acc += (double)val[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
 // out[m][i][u] = x[i][m * dsub + u] - centroids[list_of[i]][m * dsub + u]: the residual of
 // every vector (one fp32 subtraction per component), regrouped into M contiguous matrices
 // of sub-vectors.
@@ -194,6 +305,37 @@ void launch_segmented_mean(const float* x, int d, const int32_t* order, const in
   if (nblk > 1)
     hipLaunchKernelGGL(segmented_mean_finish_kernel, dim3((unsigned)((K + 3) / 4)), block, 0, st, partial, d, off, K,
                        centroids);
+}
+
+size_t kmeans_sort_bytes(int64_t n, int K) {
+  (void)n;
+  return (size_t)256 * K * sizeof(int32_t) + (size_t)K * sizeof(int64_t) + 256 * sizeof(double) + 64;
+}
+
+// work: kmeans_sort_bytes(n, K); out: order [n], off [K + 1]; in the work space afterwards:
+// scal[0] = the largest cluster (int64), scal[1] = 1 if an assignment was out of range,
+// partial [256] doubles whose sum is the sum of val.
+void launch_kmeans_sort(const int32_t* idx, const float* val, int64_t n, int K, char* work, int32_t* order,
+                        int64_t* off, int64_t** scal_out, double** partial_out, hipStream_t st) {
+  int32_t* mat = reinterpret_cast<int32_t*>(work);
+  int64_t* cnt = reinterpret_cast<int64_t*>(work + (size_t)256 * K * sizeof(int32_t));
+  double* partial = reinterpret_cast<double*>(cnt + K);
+  int64_t* scal = reinterpret_cast<int64_t*>(partial + 256);
+  *scal_out = scal; *partial_out = partial;
+  const int64_t chunk = std::max<int64_t>(2048, ((n + 255) / 256 + 63) / 64 * 64);
+  const int nchunk = (int)((n + chunk - 1) / chunk);
+  const size_t lds = (size_t)K * sizeof(int);
+  if (lds > 48 * 1024) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&km_hist_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&km_scatter_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  }
+  launch_fill_u64(reinterpret_cast<u64*>(scal), 2, 0ull, st);
+  hipLaunchKernelGGL(km_hist_kernel, dim3((unsigned)nchunk), dim3(256), lds, st, idx, n, K, chunk, mat,
+                     reinterpret_cast<int*>(scal + 1));
+  hipLaunchKernelGGL(km_colscan_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, mat, nchunk, K, cnt);
+  hipLaunchKernelGGL(km_offsets_kernel, dim3(1), dim3(256), 0, st, cnt, K, off, scal);
+  hipLaunchKernelGGL(km_scatter_kernel, dim3((unsigned)nchunk), dim3(64), lds, st, idx, n, K, chunk, mat, off, order);
+  hipLaunchKernelGGL(km_objective_kernel, dim3(256), dim3(256), 0, st, val, n, partial);
 }
 
 void launch_residual_slices(const float* x, int64_t n, int d, int dsub, const float* centroids,

@@ -873,6 +873,9 @@ KMEANS_CASES = [
     ("long_clusters_d96_k3", 20_000, 96, 3, 2, "unit"),
     ("long_clusters_d200_k2", 13_000, 200, 2, 2, "gauss"),
     ("long_and_short_clusters_d64", 25_000, 64, 40, 2, "sift"),
+    # more centroids than the device-side bookkeeping takes (16384): the host sorts the assignment
+    ("host_bookkeeping_k20000", 25_000, 4, 20_000, 2, "gauss"),
+    ("device_bookkeeping_k16384", 40_000, 8, 16_384, 2, "gauss"),
 ]
 
 
