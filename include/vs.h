@@ -129,14 +129,16 @@ VS_API int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int
  * Lloyd's k-means (Sec. 4.1 "The k-means vector quantizer"): niter rounds of
  *   (1) every training vector goes to its nearest centroid (squared L2 on the fp32 chain
  *       of vs_flat_search, ties to the smaller centroid number);
- *   (2) every centroid moves to the mean of its vectors (float64 sum in the order of the
- *       vectors, divided by their number, rounded to fp32); a centroid that received no
- *       vector stays where it is.
+ *   (2) every centroid moves to the mean of its vectors (float64 sum of its vectors in
+ *       ascending order, taken in blocks of 4096 -- each block summed from 0, the block sums
+ *       added in block order -- divided by their number, rounded to fp32: one value whatever
+ *       the schedule); a centroid that received no vector stays where it is.
  *   x          [n, d] fp32 training vectors, n < 2^31.
  *   centroids  [K, d] fp32: in, the initial centroids; out, the trained ones.
  *   objective  HOST pointer to niter doubles, or NULL: the mean squared distance of the
  *              training vectors to their centroid at step (1) of every round.
- * Synchronises the stream every round (the assignment is read back to order the vectors).
+ * Synchronises the stream every round (the size of the largest cluster and the objective
+ * are read back; beyond 16384 centroids the whole assignment is, to be ordered on the host).
  * Errors: null pointers, d < 1, K < 1, niter < 0, n outside [0, 2^31).
  */
 VS_API int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter,
