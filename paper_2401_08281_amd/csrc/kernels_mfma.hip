@@ -1094,7 +1094,10 @@ bool mfma_knn_supported(int d, int k) {
 }
 
 int mfma_knn_kp(int k) {
-  int kp = k + std::max(16, k / 4);
+  // (k = 1, the assignment of the add path and of k-means: 8 candidates are re-ranked instead
+  // of 24 -- the re-rank's gathers are 7 % of an assignment -- and a row whose best is not
+  // provably among them takes the exact fallback as always)
+  int kp = k + (k == 1 ? 7 : std::max(16, k / 4));
   kp = (kp + 7) / 8 * 8;
   return std::min(kp, 192);
 }
