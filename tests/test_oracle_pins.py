@@ -458,6 +458,45 @@ def test_kmeans_round_is_assign_then_mean(oracle):
     np.testing.assert_allclose(oracle.kmeans(x, c0, 1)[0], first.astype(np.float32), rtol=1e-6)
 
 
+def test_code_sizes_the_paper_states(oracle):
+    """tests/golden/code_sizes.txt holds the code sizes the paper gives as numbers.  The oracle's
+    encoders must produce codes of those sizes (for the parameters they support, 4 and 8 bits: the
+    paper's rule M * ceil(log2 K) bits, checked on its own PQ6x10 example first), and a code must use
+    all of its bytes: vectors built from the last codeword of every sub-quantizer fill every byte."""
+    import math, os
+    recs = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "code_sizes.txt")):
+        if line.strip() and not line.startswith("#"):
+            f = line.split()
+            recs.append((f[0], dict(kv.split("=") for kv in f[1:] if "=" in kv and not kv.startswith("(")), line))
+    kinds = {r[0] for r in recs}
+    assert kinds == {"pq", "sq8", "kmeans", "ids"}
+    rule = lambda M, K: M * math.ceil(math.log2(K))                  # Sec. 4.1, in bits
+    for kind, kv, line in recs:
+        if kind == "pq":
+            assert rule(int(kv["M"]), 1 << int(kv["nbits"])) == int(kv["bits"]), line
+        elif kind == "kmeans":
+            assert rule(1, int(kv["K"])) == 8 * int(kv["bytes"]), line
+        elif kind == "ids":
+            assert math.ceil(math.log2(int(kv["N"]))) == int(kv["bits"]), line
+        elif kind == "sq8":
+            d = int(kv["d"])
+            x = np.linspace(-1, 1, 2 * d, dtype=np.float32).reshape(2, d)
+            vmin, step = oracle.sq8_params(x)
+            codes = oracle.sq8_encode(x, vmin, step)
+            assert codes.dtype == np.uint8 and codes.shape == (2, int(kv["bytes"])), line
+    # the same rule for the product quantizers the oracle supports, on its encoder's output
+    rng = np.random.default_rng(5)
+    for M, nbits, dsub in ((6, 8, 2), (16, 8, 1), (8, 4, 3), (64, 4, 1)):
+        K, d = 1 << nbits, M * dsub
+        cb = rng.standard_normal((M, K, dsub)).astype(np.float32)
+        cent = np.zeros((1, d), np.float32)
+        x = np.stack([cb[:, 0, :].reshape(d), cb[:, K - 1, :].reshape(d)])   # first / last codeword everywhere
+        codes = oracle.pq_encode(x, np.zeros(2, np.int32), cent, cb, nbits)
+        assert codes.shape[1] * 8 == rule(M, K)
+        assert (codes[0] == 0).all() and (codes[1] == 0xFF).all()            # every bit of every byte is used
+
+
 def test_kmeans_mean_of_a_cluster_longer_than_one_summation_block(oracle):
     """The update sums a centroid's vectors in float64 in blocks of 4096; whatever the order, a
     float64 sum of 10,000 fp32 values of comparable size is within 1e-12 relative of the exact
