@@ -306,6 +306,40 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
 }
 
+// Look-ups of one 32-bit word of 4-bit codes (8 sub-quantizers from m_base on) in tables that
+// start at the beginning of the workgroup's LDS.  The byte offset of an entry, nibble * 4, is
+// one instruction per nibble: with lo = word << 2 and hi = word >> 2 the scaled low / high
+// nibble of code byte b sits in bits 2..5 of byte b of lo / hi, and a byte-selecting AND with
+// 0x3C (v_and_b32_sdwa) isolates it; the table's own offset is the load's immediate.  The
+// scan of 4-bit codes is bound by its vector instructions: this form has 2.25 per look-up
+// (with the addition) where shift-and-mask extraction and address arithmetic have 3.
+template <int B>
+__device__ __forceinline__ u32 byte_and(u32 x, u32 mask) {
+  u32 r;
+  if constexpr (B == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 3) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  return r;
+}
+// (the tables are addressed as LDS address 0 + offset: the caller has checked that they start there)
+typedef __attribute__((address_space(3))) const float* lds_cfloat_ptr;
+template <int B>
+__device__ __forceinline__ float adc_nibble_pair(u32 lo, u32 hi, u32 mask, int m_base, float dist) {
+  const u32 o0 = byte_and<B>(lo, mask), o1 = byte_and<B>(hi, mask);
+  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o0 + (u32)((m_base + 2 * B) * 64)));
+  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o1 + (u32)((m_base + 2 * B + 1) * 64)));
+  return dist;
+}
+__device__ __forceinline__ float adc_word4(u32 word, int m_base, float dist) {
+  const u32 lo = word << 2, hi = word >> 2, mask = 0x3Cu;
+  dist = adc_nibble_pair<0>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<1>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<2>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<3>(lo, hi, mask, m_base, dist);
+  return dist;
+}
+
 // ---------------------------------------------------------------------------
 // The same scan for codes of 16, 32 or 64 bytes (W16 = code size / 16), software
 // pipelined: the workgroup walks over the chunks of 256 codes of all its lists as one
@@ -326,12 +360,18 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
   constexpr int MPW = NBITS == 8 ? 16 : 32;                      // sub-quantizers per 16 code bytes
   const int metric = mode == 1 ? 1 : 0;                         // ordering of the keys
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
-  float* lut = reinterpret_cast<float*>(slots + 4 * tot);       // M * K
+  // (the tables come first: with no static LDS in this kernel they start at LDS address 0, and
+  // the 4-bit look-ups then carry a table's offset as an immediate; checked, not assumed)
+  float* lut = reinterpret_cast<float*>(smem);                  // M * K
+  const bool lut_at_zero =
+      (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u &&
+      M * K * (int)sizeof(float) <= 65536;
   float* rs = lut + M * K;                                      // d (+ 1 to keep what follows aligned)
   int64_t* s_begin = reinterpret_cast<int64_t*>(rs + ((d + 1) & ~1));   // ppb
   int64_t* s_end = s_begin + ppb;                               // ppb
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
+  u64* slots = reinterpret_cast<u64*>(                          // 4 * tot
+      (reinterpret_cast<uintptr_t>(s_list + ppb) + 7) & ~(uintptr_t)7);
 
   const int64_t qi = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
@@ -420,10 +460,17 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
     if (valid) {
 #pragma unroll
       for (int w = 0; w < W16; ++w) {
-        dist = adc_bytes<NBITS>(lut, cw[w].x, w * MPW, dist);
-        dist = adc_bytes<NBITS>(lut, cw[w].y, w * MPW + MPW / 4, dist);
-        dist = adc_bytes<NBITS>(lut, cw[w].z, w * MPW + MPW / 2, dist);
-        dist = adc_bytes<NBITS>(lut, cw[w].w, w * MPW + 3 * (MPW / 4), dist);
+        if (NBITS == 4 && lut_at_zero) {
+          dist = adc_word4(cw[w].x, w * MPW, dist);
+          dist = adc_word4(cw[w].y, w * MPW + MPW / 4, dist);
+          dist = adc_word4(cw[w].z, w * MPW + MPW / 2, dist);
+          dist = adc_word4(cw[w].w, w * MPW + 3 * (MPW / 4), dist);
+        } else {
+          dist = adc_bytes<NBITS>(lut, cw[w].x, w * MPW, dist);
+          dist = adc_bytes<NBITS>(lut, cw[w].y, w * MPW + MPW / 4, dist);
+          dist = adc_bytes<NBITS>(lut, cw[w].z, w * MPW + MPW / 2, dist);
+          dist = adc_bytes<NBITS>(lut, cw[w].w, w * MPW + 3 * (MPW / 4), dist);
+        }
       }
     }
     ws.push(valid, make_key(dist, (u32)i, metric));
@@ -914,7 +961,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 #undef REG
   const int r = select_regs_for_slots(tot);
   // codes of 16, 32 or 64 bytes: the software-pipelined kernel
-  const size_t pipe_shmem = shmem + sizeof(float) + (size_t)ppb * 20 + 16;
+  const size_t pipe_shmem = shmem + sizeof(float) + (size_t)ppb * 20 + 24;
   if ((g.code_size == 16 || g.code_size == 32 || g.code_size == 64) && pipe_shmem + 64 <= 160 * 1024) {
 #define PIPE3(NB, RR, WW)                                                                        \
   launch_scan_pipe<NB, RR, WW>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, nsplit, \
