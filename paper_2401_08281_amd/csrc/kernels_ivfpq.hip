@@ -203,6 +203,40 @@ __device__ __forceinline__ float adc_bytes(const float* __restrict__ lut, u32 wo
   return dist;
 }
 
+// Look-ups of one 32-bit word of 4-bit codes (8 sub-quantizers from m_base on) in tables that
+// start at the beginning of the workgroup's LDS.  The byte offset of an entry, nibble * 4, is
+// one instruction per nibble: with lo = word << 2 and hi = word >> 2 the scaled low / high
+// nibble of code byte b sits in bits 2..5 of byte b of lo / hi, and a byte-selecting AND with
+// 0x3C (v_and_b32_sdwa) isolates it; the table's own offset is the load's immediate.  The
+// scan of 4-bit codes is bound by its vector instructions: this form has 2.25 per look-up
+// (with the addition) where shift-and-mask extraction and address arithmetic have 3.
+template <int B>
+__device__ __forceinline__ u32 byte_and(u32 x, u32 mask) {
+  u32 r;
+  if constexpr (B == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  if constexpr (B == 3) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
+  return r;
+}
+// (the tables are addressed as LDS address 0 + offset: the caller has checked that they start there)
+typedef __attribute__((address_space(3))) const float* lds_cfloat_ptr;
+template <int B>
+__device__ __forceinline__ float adc_nibble_pair(u32 lo, u32 hi, u32 mask, int m_base, float dist) {
+  const u32 o0 = byte_and<B>(lo, mask), o1 = byte_and<B>(hi, mask);
+  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o0 + (u32)((m_base + 2 * B) * 64)));
+  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o1 + (u32)((m_base + 2 * B + 1) * 64)));
+  return dist;
+}
+__device__ __forceinline__ float adc_word4(u32 word, int m_base, float dist) {
+  const u32 lo = word << 2, hi = word >> 2, mask = 0x3Cu;
+  dist = adc_nibble_pair<0>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<1>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<2>(lo, hi, mask, m_base, dist);
+  dist = adc_nibble_pair<3>(lo, hi, mask, m_base, dist);
+  return dist;
+}
+
 template <int NBITS, int R>
 __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
     const float* __restrict__ q, int d, int mode, int M, int dsub,
@@ -218,9 +252,13 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   constexpr int K = 1 << NBITS;
   const int metric = mode == 1 ? 1 : 0;                         // ordering of the keys
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
-  float* lut = reinterpret_cast<float*>(slots + 4 * tot);       // M * K
+  // (the tables come first, see adc_word4)
+  float* lut = reinterpret_cast<float*>(smem);                  // M * K
   float* rs = lut + M * K;                                      // d
+  u64* slots = reinterpret_cast<u64*>(rs + ((d + 1) & ~1));     // 4 * tot
+  const bool lut_at_zero =
+      (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u &&
+      M * K * (int)sizeof(float) <= 65536;
 
   const int64_t qi = blockIdx.x / nsplit;
   const int split = blockIdx.x % nsplit;
@@ -281,15 +319,23 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
           for (int w = 0; w < (cs >> 4); ++w) {
             const uint4 v = reinterpret_cast<const uint4*>(cp)[w];
             const int mb = w * (NBITS == 8 ? 16 : 32);
-            dist = adc_bytes<NBITS>(lut, v.x, mb, dist);
-            dist = adc_bytes<NBITS>(lut, v.y, mb + (NBITS == 8 ? 4 : 8), dist);
-            dist = adc_bytes<NBITS>(lut, v.z, mb + (NBITS == 8 ? 8 : 16), dist);
-            dist = adc_bytes<NBITS>(lut, v.w, mb + (NBITS == 8 ? 12 : 24), dist);
+            if (NBITS == 4 && lut_at_zero) {
+              dist = adc_word4(v.x, mb, dist);
+              dist = adc_word4(v.y, mb + 8, dist);
+              dist = adc_word4(v.z, mb + 16, dist);
+              dist = adc_word4(v.w, mb + 24, dist);
+            } else {
+              dist = adc_bytes<NBITS>(lut, v.x, mb, dist);
+              dist = adc_bytes<NBITS>(lut, v.y, mb + (NBITS == 8 ? 4 : 8), dist);
+              dist = adc_bytes<NBITS>(lut, v.z, mb + (NBITS == 8 ? 8 : 16), dist);
+              dist = adc_bytes<NBITS>(lut, v.w, mb + (NBITS == 8 ? 12 : 24), dist);
+            }
           }
         } else if ((cs & 3) == 0) {
-          for (int w = 0; w < (cs >> 2); ++w)
-            dist = adc_bytes<NBITS>(lut, reinterpret_cast<const u32*>(cp)[w],
-                                    w * (NBITS == 8 ? 4 : 8), dist);
+          for (int w = 0; w < (cs >> 2); ++w) {
+            if (NBITS == 4 && lut_at_zero) dist = adc_word4(reinterpret_cast<const u32*>(cp)[w], w * 8, dist);
+            else dist = adc_bytes<NBITS>(lut, reinterpret_cast<const u32*>(cp)[w], w * (NBITS == 8 ? 4 : 8), dist);
+          }
         } else {
           for (int b = 0; b < cs; ++b) {
             const u32 byte = cp[b];
@@ -304,40 +350,6 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
   ws.finish();
   __syncthreads();
   block_rank_merge(slots, tot, 4, k, sink, ((int64_t)qi * nsplit + split) * k);
-}
-
-// Look-ups of one 32-bit word of 4-bit codes (8 sub-quantizers from m_base on) in tables that
-// start at the beginning of the workgroup's LDS.  The byte offset of an entry, nibble * 4, is
-// one instruction per nibble: with lo = word << 2 and hi = word >> 2 the scaled low / high
-// nibble of code byte b sits in bits 2..5 of byte b of lo / hi, and a byte-selecting AND with
-// 0x3C (v_and_b32_sdwa) isolates it; the table's own offset is the load's immediate.  The
-// scan of 4-bit codes is bound by its vector instructions: this form has 2.25 per look-up
-// (with the addition) where shift-and-mask extraction and address arithmetic have 3.
-template <int B>
-__device__ __forceinline__ u32 byte_and(u32 x, u32 mask) {
-  u32 r;
-  if constexpr (B == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
-  if constexpr (B == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
-  if constexpr (B == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
-  if constexpr (B == 3) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(mask));
-  return r;
-}
-// (the tables are addressed as LDS address 0 + offset: the caller has checked that they start there)
-typedef __attribute__((address_space(3))) const float* lds_cfloat_ptr;
-template <int B>
-__device__ __forceinline__ float adc_nibble_pair(u32 lo, u32 hi, u32 mask, int m_base, float dist) {
-  const u32 o0 = byte_and<B>(lo, mask), o1 = byte_and<B>(hi, mask);
-  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o0 + (u32)((m_base + 2 * B) * 64)));
-  dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)(o1 + (u32)((m_base + 2 * B + 1) * 64)));
-  return dist;
-}
-__device__ __forceinline__ float adc_word4(u32 word, int m_base, float dist) {
-  const u32 lo = word << 2, hi = word >> 2, mask = 0x3Cu;
-  dist = adc_nibble_pair<0>(lo, hi, mask, m_base, dist);
-  dist = adc_nibble_pair<1>(lo, hi, mask, m_base, dist);
-  dist = adc_nibble_pair<2>(lo, hi, mask, m_base, dist);
-  dist = adc_nibble_pair<3>(lo, hi, mask, m_base, dist);
-  return dist;
 }
 
 // ---------------------------------------------------------------------------
@@ -945,7 +957,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const int ppb = (nprobe + nsplit - 1) / nsplit;
   const int tot = select_slots_for_k(k);
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
-                       (size_t)g.d * sizeof(float);
+                       (size_t)(g.d + 2) * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
   const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + 2 * 256 * sizeof(float) +
                            (size_t)ppb * 20 + 32;   // two tables, their rows padded
