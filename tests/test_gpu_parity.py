@@ -458,6 +458,46 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
     check_search(Dm, Im, Do, Io, metric, q, xn)
 
 
+def test_random_route_shapes_agree(vs):
+    """Forty seeded shapes over every d class of the matrix-core kernels (register-stationary and
+    tiled, up to 2048), ragged and tiny B, k from 1 to 150, the three operand-precision variants
+    and data with a large common offset: the matrix-core route returns what the canon tiles
+    return, bit for bit (the canon route itself is checked against the oracle above)."""
+    import torch
+    rng = np.random.default_rng(20241127)
+    try:
+        for n in range(40):
+            d = int(rng.choice([32, 64, 96, 128, 160, 192, 256, 320, 512, 768, 1024, 2048]))
+            nb = int(rng.choice([1, 5, 63, 64, 65, 127, 129, 190, 255, 257, 300, 1000, 2047, 2049, 5000, 20000]))
+            nq = int(rng.choice([1, 2, 31, 64, 100, 255, 256, 257, 600]))
+            if nb * nq * d > 2e10:
+                nq = max(1, int(2e10 / (nb * d)))
+            k = int(rng.choice([1, 2, 10, 32, 64, 100, 128, 150]))
+            metric = int(rng.choice([L2, L2, IP]))
+            kind = int(rng.choice([0, 1, 2, 3]))
+            say("route shape %d: d=%d nb=%d nq=%d k=%d metric=%d kind=%d" % (n, d, nb, nq, k, metric, kind))
+            g = torch.Generator(device="cuda"); g.manual_seed(1000 + n)
+            x = torch.randn((nb, d), generator=g, device="cuda")
+            q = torch.randn((nq, d), generator=g, device="cuda")
+            if kind == 1:                       # integers on both sides: one pass
+                x, q = (x * 20).round(), (q * 20).round()
+            elif kind == 2:                     # exact queries, general database: two passes from 256 queries on
+                x, q = x * 20, (q * 20).round()
+            elif kind == 3:                     # a common offset: large norms, small gaps
+                x, q = x + 3.0, q + 3.0
+            vs.vs_set_option("knn_path", 1)
+            Dc, Ic = vs.vs_flat_search(x, q, k, metric)
+            vs.vs_set_option("knn_path", 0)
+            vs.vs_counters_read()
+            Dm, Im = vs.vs_flat_search(x, q, k, metric)
+            rows, _ = vs.vs_counters_read()
+            assert rows == nq
+            np.testing.assert_array_equal(host(Im), host(Ic))
+            np.testing.assert_array_equal(host(Dm), host(Dc))
+    finally:
+        vs.vs_set_option("knn_path", 0)
+
+
 # ------------------------------------------------- flat index (prepared database)
 
 FLAT_INDEX_CASES = [
