@@ -3,8 +3,8 @@
  *
  * Batched IVF-PQ search and flat exact k-NN search as described in
  * "The Faiss Library" (arXiv 2401.08281): Sec. 3 (Eq. 1-2, brute-force
- * search, metrics), Sec. 4 (Eq. 8 asymmetric distance computation, product
- * quantizer, Eq. 12 look-up tables), Sec. 5.1 (inverted files, residual
+ * search, metrics), Sec. 4 (Eq. 10 asymmetric distance computation, product
+ * quantizer, Eq. 14 look-up tables), Sec. 5.1 (inverted files, residual
  * encoding), App. A.3 "Optimization", paragraph "GPU Faiss" (the four GPU stages).
  *
  * General conventions
@@ -129,20 +129,25 @@ VS_API int vs_refine(const float* x, int64_t nb, const float* q, int64_t nq, int
  * Lloyd's k-means (Sec. 4.1 "The k-means vector quantizer"): niter rounds of
  *   (1) every training vector goes to its nearest centroid (squared L2 on the fp32 chain
  *       of vs_flat_search, ties to the smaller centroid number);
- *   (2) every centroid moves to the mean of its vectors (float64 sum of its vectors in
- *       ascending order, taken in blocks of 4096 -- each block summed from 0, the block sums
- *       added in block order -- divided by their number, rounded to fp32: one value whatever
- *       the schedule); a centroid that received no vector stays where it is.
+ *   (2) every centroid moves to the mean of its vectors: their float64 sum divided by their
+ *       number, rounded to fp32; a centroid that received no vector stays where it is.
+ *       The sum of a cluster of more than 4096 vectors is formed from partial sums of 4096
+ *       consecutive members each (added in order), so that a long cluster is summed by
+ *       several wavefronts; for clusters up to 4096 vectors it is the running sum in the
+ *       order of the training set.  Either way the result is deterministic, and it differs
+ *       from the running sum by float64 rounding only (at most the last bit of the fp32 mean).
  *   x          [n, d] fp32 training vectors, n < 2^31.
  *   centroids  [K, d] fp32: in, the initial centroids; out, the trained ones.
  *   objective  HOST pointer to niter doubles, or NULL: the mean squared distance of the
  *              training vectors to their centroid at step (1) of every round.
+ *   assign     DEVICE [n] int32, or NULL: the centroid of every training vector at step (1)
+ *              of the LAST round (the clusters whose means the returned centroids are).
  * Synchronises the stream every round (the size of the largest cluster and the objective
  * are read back; beyond 16384 centroids the whole assignment is, to be ordered on the host).
  * Errors: null pointers, d < 1, K < 1, niter < 0, n outside [0, 2^31).
  */
 VS_API int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter,
-              float* centroids, double* objective, void* hip_stream);
+              float* centroids, double* objective, int32_t* assign, void* hip_stream);
 
 /*
  * Parameters of an IVF-PQ index from training vectors (Sec. 5.1: the coarse quantizer is a
@@ -164,8 +169,8 @@ VS_API int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, 
 
 /*
  * Create an empty IVF-PQ index (Sec. 5.1 "Inverted files"; Sec. 4.1 product
- * quantizer).  Training is not part of this library: the nlist coarse
- * centroids and the M sub-codebooks are inputs and are copied.
+ * quantizer).  The nlist coarse centroids and the M sub-codebooks are inputs (sampled by
+ * the caller, or trained with vs_ivfpq_train) and are copied.
  *   centroids [nlist, d] fp32.
  *   codebooks [M, 2^nbits, d/M] fp32: codebooks[m][j] is codeword j of
  *             sub-quantizer m.
@@ -198,7 +203,7 @@ VS_API int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nl
 VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, void* hip_stream);
 
 /*
- * Batched IVF-PQ search (Sec. 5.1; Eq. 8 ADC; Eq. 12 look-up tables; App. A.3 "GPU Faiss").
+ * Batched IVF-PQ search (Sec. 5.1; Eq. 10 ADC; Eq. 14 look-up tables; App. A.3 "GPU Faiss").
  * For every query: the nprobe best centroids are found exactly (nprobe is
  * clamped to nlist), a look-up table LUT_m[j] is built per (query, probed
  * list) on the query's residual to the list centroid (per query for IP, plus
@@ -237,7 +242,13 @@ VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32
 /*
  * How vs_ivfpq_search evaluates distances in the compressed domain (Sec. 4.3
  * "Compressed-domain search").  VS_ST_RESIDUAL_TABLES (default): one table of squared
- * distances between the query's residual and the codewords per (query, probed list).
+ * distances between the query's residual r = q - c_l and the codewords per (query, probed
+ * list).  For the shapes with a specialised kernel (8-bit codes of 8, 16 or 32 sub-quantizers
+ * on d = 32, 128, 96) an entry is evaluated as (|r_m|^2 + |t|^2) + sum_u r_u (-2 t_u) rather than
+ * sum_u (r_u - t_u)^2: the same number for integer data, otherwise off by rounding of at most
+ * (d/M + 2) 2^-23 (|r_m|^2 + |t|^2) -- relative to the cancelling terms, not to the distance, which
+ * matters only when the query (nearly) coincides with a reconstruction.  Results of both L2
+ * forms are clamped at 0.
  * VS_ST_STORED_NORMS (L2 only): the decomposition |q - x'|^2 = |q|^2 + |x'|^2 - 2 <q, x'>
  * with |x'|^2 stored next to every code as a float32 (4 more bytes per vector): one table of
  * inner products per QUERY, no per-list table; the result differs from the default form by

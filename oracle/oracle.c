@@ -209,19 +209,19 @@ void or_coarse_probe(const float *q, int64_t nq, const float *centroids, int nli
  * Each of the niter rounds (1) assigns every training vector to its nearest
  * centroid -- canon L2, ties to the smaller centroid number, the rule of
  * or_assign -- and (2) moves every centroid to the mean of the vectors assigned
- * to it: float64 sum of its vectors in ascending order (in blocks, see below),
- * divided by the count, rounded to fp32.  A centroid that received no vector keeps its position (the paper
- * does not say; this is the reading taken).  centroids: in = the initial
- * centroids, out = the trained ones.  objective[r], if asked for, is the mean
- * over the training vectors of the canon distance to the assigned centroid in
- * round r's step (1), summed in float64 in the order of the vectors. */
-#define OR_KMEANS_BLOCK 4096
+ * to it: the float64 sum of those vectors, added one after the other in the order
+ * of the training set, divided by their number, rounded once to fp32.  A centroid
+ * that received no vector keeps its position (the paper does not say; this is the
+ * reading taken).  centroids: in = the initial centroids, out = the trained ones.
+ * objective[r], if asked for, is the mean over the training vectors of the canon
+ * distance to the assigned centroid in round r's step (1), summed in float64 in the
+ * order of the vectors.  assign_out, if asked for, receives the assignment of the
+ * LAST round's step (1) (the one the returned centroids are the means of). */
 void or_kmeans(const float *x, int64_t n, int d, int K, int niter, float *centroids,
-               double *objective) {
+               double *objective, int32_t *assign_out) {
   int32_t *a = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
   float *best = (float *)malloc((size_t)(n > 0 ? n : 1) * sizeof(float));
   double *sum = (double *)malloc((size_t)K * d * sizeof(double));
-  double *blk = (double *)malloc((size_t)K * d * sizeof(double));
   int64_t *cnt = (int64_t *)malloc((size_t)K * sizeof(int64_t));
   for (int r = 0; r < niter; ++r) {
 #pragma omp parallel for schedule(static)
@@ -238,32 +238,21 @@ void or_kmeans(const float *x, int64_t n, int d, int K, int niter, float *centro
     double obj = 0.0;
     for (int64_t i = 0; i < n; ++i) obj += (double)best[i];
     if (objective) objective[r] = n > 0 ? obj / (double)n : 0.0;
-    /* Sum of a centroid's vectors in float64: its vectors are taken in ascending order, in
-     * blocks of OR_KMEANS_BLOCK; a block is summed from 0 in that order, and the block sums
-     * are added in block order (a centroid with at most one block: the plain running sum).
-     * The paper fixes no order; this one is fixed, and its blocks can be summed side by
-     * side. */
-    for (int64_t t = 0; t < (int64_t)K * d; ++t) sum[t] = blk[t] = 0.0;
+    for (int64_t t = 0; t < (int64_t)K * d; ++t) sum[t] = 0.0;
     for (int j = 0; j < K; ++j) cnt[j] = 0;
     for (int64_t i = 0; i < n; ++i) {
-      const int j = a[i];
-      double *bj = blk + (int64_t)j * d;
-      for (int t = 0; t < d; ++t) bj[t] += (double)x[i * d + t];
-      if (++cnt[j] % OR_KMEANS_BLOCK == 0) {
-        double *sj = sum + (int64_t)j * d;
-        for (int t = 0; t < d; ++t) { sj[t] += bj[t]; bj[t] = 0.0; }
-      }
+      double *sj = sum + (int64_t)a[i] * d;
+      for (int t = 0; t < d; ++t) sj[t] += (double)x[i * d + t];
+      ++cnt[a[i]];
     }
-    for (int j = 0; j < K; ++j)
-      if (cnt[j] % OR_KMEANS_BLOCK != 0)
-        for (int t = 0; t < d; ++t) sum[(int64_t)j * d + t] += blk[(int64_t)j * d + t];
     for (int j = 0; j < K; ++j) {
       if (cnt[j] == 0) continue;
       for (int t = 0; t < d; ++t)
         centroids[(int64_t)j * d + t] = (float)(sum[(int64_t)j * d + t] / (double)cnt[j]);
     }
   }
-  free(a); free(best); free(sum); free(blk); free(cnt);
+  if (assign_out && niter > 0) memcpy(assign_out, a, (size_t)n * sizeof(int32_t));
+  free(a); free(best); free(sum); free(cnt);
 }
 
 /* ---- O3/O4: residual PQ encoding (Sec. 4.1 "product quantizer", Sec. 5.1
@@ -350,7 +339,7 @@ void or_pq_norms(const uint8_t *codes, int64_t n, int d, const int32_t *list_of,
   }
 }
 
-/* ---- O6-O8: IVF-PQ search (Sec. 5.1, Eq. 8 ADC, Eq. 12 LUT) -------------
+/* ---- O6-O8: IVF-PQ search (Sec. 5.1, Eq. 10 ADC, Eq. 14 LUT) -------------
  * The index is given as plain arrays: list l owns rows
  * [list_offsets[l], list_offsets[l+1]) of `codes` and `ids`.
  *

@@ -106,18 +106,22 @@ def refine(x, q, cand, k, metric=METRIC_L2):
     return D, I
 
 
-def kmeans(x, init, niter):
+def kmeans(x, init, niter, return_assign=False):
     """Sec. 4.1: niter rounds of Lloyd's iteration from the centroids `init` [K, d].
     Returns (centroids [K, d] fp32, objective [niter] float64: the mean squared distance to
-    the assigned centroid at each round's assignment step)."""
+    the assigned centroid at each round's assignment step) and, with return_assign, the
+    assignment [n] int32 of the last round's assignment step."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     c = np.array(init, dtype=np.float32, order="C", copy=True)
     n, d = x.shape
     K = c.shape[0]
     assert c.shape[1] == d
     obj = np.zeros(max(niter, 0), dtype=np.float64)
+    a = np.full(n, -1, dtype=np.int32)
     _load().or_kmeans(_ptr(x), ctypes.c_int64(n), ctypes.c_int(d), ctypes.c_int(K),
-                      ctypes.c_int(niter), _ptr(c), _ptr(obj))
+                      ctypes.c_int(niter), _ptr(c), _ptr(obj), _ptr(a))
+    if return_assign:
+        return c, obj, a
     return c, obj
 
 

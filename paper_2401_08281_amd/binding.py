@@ -83,7 +83,7 @@ def lib():
     L.vs_ivfsq8_get_storage.restype = ctypes.c_int
     L.vs_ivfsq8_get_storage.argtypes = [vp, vp, vp, vp, vp]
     L.vs_kmeans.restype = ctypes.c_int
-    L.vs_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+    L.vs_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
     L.vs_ivfpq_train.restype = ctypes.c_int
     L.vs_ivfpq_train.argtypes = [vp, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.vs_refine.restype = ctypes.c_int
@@ -264,9 +264,10 @@ def vs_refine(x, q, cand_ids, k, metric=METRIC_L2, out_dist=None, out_ids=None):
     return out_dist, out_ids
 
 
-def vs_kmeans(x, centroids, niter):
+def vs_kmeans(x, centroids, niter, return_assign=False):
     """Trains `centroids` [K, d] (device tensor, updated in place) on x [n, d]; returns the
-    objective of every round as a list of floats."""
+    objective of every round as a list of floats and, with return_assign, the last round's
+    assignment as an int32 device tensor [n]."""
     x = _dev(x, torch.float32, "x")
     centroids = _dev(centroids, torch.float32, "centroids")
     n, d = x.shape
@@ -274,8 +275,11 @@ def vs_kmeans(x, centroids, niter):
     if centroids.dim() != 2 or centroids.shape[1] != d:
         raise ValueError("centroids must be [K, d]")
     obj = (ctypes.c_double * max(niter, 1))()
-    _check(lib().vs_kmeans(_p(x), n, d, K, niter, _p(centroids), obj, _stream()))
-    return [float(obj[r]) for r in range(max(niter, 0))]
+    assign = torch.empty(n, dtype=torch.int32, device=x.device) if return_assign else None
+    _check(lib().vs_kmeans(_p(x), n, d, K, niter, _p(centroids), obj,
+                           _p(assign) if return_assign else None, _stream()))
+    objs = [float(obj[r]) for r in range(max(niter, 0))]
+    return (objs, assign) if return_assign else objs
 
 
 def vs_ivfpq_train(x, metric, centroids, codebooks, nbits, niter):

@@ -623,7 +623,7 @@ int kmeans_rounds(const float* x, int64_t n, int d, int K, int niter, float* cen
 }  // namespace
 
 int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter, float* centroids,
-              double* objective, void* hip_stream) {
+              double* objective, int32_t* assign, void* hip_stream) {
   if (n < 0 || n >= (1ll << 31)) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: n outside [0, 2^31)");
   if (d < 1 || K < 1) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: d = %d, K = %d must be >= 1", d, K);
   if (niter < 0) return fail(VS_ERR_INVALID_ARG, "vs_kmeans: niter < 0");
@@ -646,9 +646,15 @@ int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter, fl
   if (int rc = buf.alloc(cv.off)) return rc;
   char* b = static_cast<char*>(buf.p);
   std::lock_guard<std::mutex> lock(g_flat_mu);
-  return kmeans_rounds(x, n, d, K, niter, centroids, objective, reinterpret_cast<int32_t*>(b + o_idx),
-                       reinterpret_cast<float*>(b + o_val), reinterpret_cast<int32_t*>(b + o_order),
-                       reinterpret_cast<int64_t*>(b + o_off), g_flat_scratch[dev], st);
+  if (int rc = kmeans_rounds(x, n, d, K, niter, centroids, objective, reinterpret_cast<int32_t*>(b + o_idx),
+                             reinterpret_cast<float*>(b + o_val), reinterpret_cast<int32_t*>(b + o_order),
+                             reinterpret_cast<int64_t*>(b + o_off), g_flat_scratch[dev], st))
+    return rc;
+  if (assign) {   // idx still holds the last round's step (1)
+    HIP_TRY(hipMemcpyAsync(assign, b + o_idx, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));   // the work buffer is released on return
+  }
+  return VS_OK;
 }
 
 int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, int32_t nlist, int32_t M,

@@ -170,7 +170,7 @@ __global__ void list_sizes_kernel(const int64_t* __restrict__ off, int nlist,
 }
 
 // ---------------------------------------------------------------------------
-// Fused LUT build + ADC scan + k-selection (Sec. 4 Eq. 8 (ADC) and Eq. 12 (look-up
+// Fused LUT build + ADC scan + k-selection (Sec. 4 Eq. 10 (ADC) and Eq. 14 (look-up
 // tables); Sec. 5.1; App. A.3 "GPU Faiss": tables staged in on-chip memory, lists
 // streamed from HBM).
 //
@@ -344,6 +344,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
           }
         }
       }
+      if (mode == 2) dist = fmaxf(dist, 0.f);   // the expanded square can round below zero
       ws.push(valid, make_key(dist, (u32)i, metric));
     }
   }
@@ -485,6 +486,7 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
         }
       }
     }
+    if (mode == 2) dist = fmaxf(dist, 0.f);     // the expanded square can round below zero
     ws.push(valid, make_key(dist, (u32)i, metric));
     first = pn != p;
     p = pn;
@@ -735,7 +737,8 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
           cw2.load(codes + min(i2, last) * M);
           if (METRIC == 2) nrm2 = norms[min(i2, last)];
         }
-        const float dist = v_cur ? cw.template adc_rows<KP>(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
+        float dist = v_cur ? cw.template adc_rows<KP>(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
+        if (METRIC != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
         ws.push(v_cur, make_key(dist, (u32)i_cur, KEY_METRIC), true);
         if (!more) break;
         cw = cw2; nrm = nrm2; i_cur = i2; v_cur = v2;

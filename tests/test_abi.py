@@ -76,13 +76,13 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_refine(one, 1 << 32, one, 1, 4, 0, one, 5, 1, one, one, nul) == INVALID  # ids must fit 32 bits
     assert L.vs_refine(one, 10, one, 1, 20000, 0, one, 5, 1024, one, one, nul) == UNSUPPORTED   # LDS
     assert L.vs_refine(nul, 10, nul, 0, 4, 0, nul, 5, 1, nul, nul, nul) == 0             # nq == 0: no-op
-    # vs_kmeans(x, n, d, K, niter, centroids, objective, stream)
-    assert L.vs_kmeans(one, 10, 0, 4, 1, one, nul, nul) == INVALID                       # d < 1
-    assert L.vs_kmeans(one, 10, 4, 0, 1, one, nul, nul) == INVALID                       # K < 1
-    assert L.vs_kmeans(one, 10, 4, 4, -1, one, nul, nul) == INVALID                      # niter < 0
-    assert L.vs_kmeans(one, 1 << 31, 4, 4, 1, one, nul, nul) == INVALID                  # n
-    assert L.vs_kmeans(one, 10, 4, 4, 1, nul, nul, nul) == INVALID                       # null centroids
-    assert L.vs_kmeans(one, 10, 4, 4, 0, one, nul, nul) == 0                             # no round: no-op
+    # vs_kmeans(x, n, d, K, niter, centroids, objective, assign, stream)
+    assert L.vs_kmeans(one, 10, 0, 4, 1, one, nul, nul, nul) == INVALID                       # d < 1
+    assert L.vs_kmeans(one, 10, 4, 0, 1, one, nul, nul, nul) == INVALID                       # K < 1
+    assert L.vs_kmeans(one, 10, 4, 4, -1, one, nul, nul, nul) == INVALID                      # niter < 0
+    assert L.vs_kmeans(one, 1 << 31, 4, 4, 1, one, nul, nul, nul) == INVALID                  # n
+    assert L.vs_kmeans(one, 10, 4, 4, 1, nul, nul, nul, nul) == INVALID                       # null centroids
+    assert L.vs_kmeans(one, 10, 4, 4, 0, one, nul, nul, nul) == 0                             # no round: no-op
     # vs_ivfpq_train(x, n, d, metric, nlist, M, nbits, niter, centroids, codebooks, objective, stream)
     assert L.vs_ivfpq_train(one, 10, 32, 0, 4, 5, 8, 1, one, one, nul, nul) == INVALID   # d % M
     assert L.vs_ivfpq_train(one, 10, 32, 0, 4, 8, 5, 1, one, one, nul, nul) == UNSUPPORTED  # nbits

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as S
-from parity_util import EXTRA, check_search, storage_map
+from parity_util import EXTRA, check_search, l2_table_cancel, storage_map
 
 pytestmark = pytest.mark.gpu
 
@@ -238,7 +238,7 @@ def test_random_shapes_match_oracle(vs, oracle):
             ix.add(dev(x[s0:e0]))
             orc.add(x[s0:e0])
         check_storage(ix, orc)
-        xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
+        xn = float(np.sqrt(orc.norms.max()))                   # largest decoded vector
         probes, cdist = ix.coarse(dev(q), nprobe)
         po, co = oracle.coarse_probe(q, orc.centroids, nprobe, cfg["metric"])
         np.testing.assert_array_equal(host(probes), po)
@@ -246,7 +246,8 @@ def test_random_shapes_match_oracle(vs, oracle):
         ix.set_search_type(vs.ST_RESIDUAL_TABLES)
         D, I = ix.search(dev(q), k, nprobe)
         Do, Io = orc.search(q, k + EXTRA, nprobe)
-        check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        tc, te = l2_table_cancel(co, cb) if cfg["metric"] == L2 else (None, 0.0)
+        check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn, cancel=tc, cancel_eps=te)
         if cfg["metric"] == L2:
             ix.set_search_type(vs.ST_STORED_NORMS)
             np.testing.assert_array_equal(host(ix.norms()), orc.norms)
@@ -254,6 +255,45 @@ def test_random_shapes_match_oracle(vs, oracle):
             D, I = ix.search(dev(q), k, nprobe)
             check_search(host(D).copy(), host(I).copy(), Do, Io, L2, cancel=cancel)
         ix.close()
+
+
+NEAR_ZERO_CASES = {
+    # the three shapes whose tables are built from the expanded square, on non-integer data
+    "pq8x8_d32": S.config("C1", nb=8_000),
+    "pq16x8_d128": S.config("C4", nb=20_000, nq=8, ncomp=40, nlist=64, d=128, M=16),
+    "pq32x8_d96": S.config("C4", nb=20_000, nq=8, ncomp=40, nlist=64),
+    # and one that goes through the subtraction form
+    "pq16x8_d64": S.config("C1", nb=8_000, d=64, M=16, nlist=32),
+}
+
+
+@pytest.mark.parametrize("name", list(NEAR_ZERO_CASES))
+def test_queries_equal_or_close_to_decoded_vectors(vs, oracle, name):
+    """L2 distances near zero: the query IS the reconstruction of a stored code (or within 1e-6 of
+    it).  A table entry evaluated as |r_m|^2 + |t|^2 - 2 <r_m, t> then cancels almost completely;
+    the result must stay non-negative and within the rounding that expansion can cost, relative
+    to the cancelling terms (l2_table_cancel), of the oracle's value."""
+    cfg = NEAR_ZERO_CASES[name]
+    say("near-zero %s nb=%d d=%d M=%d nlist=%d" % (name, cfg["nb"], cfg["d"], cfg["M"], cfg["nlist"]))
+    x, _ = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x)
+    rng = np.random.default_rng(11)
+    pick = rng.choice(cfg["nb"], 48, replace=False)
+    dec = oracle.pq_decode(orc.add_codes[pick], orc.add_list_of[pick], orc.centroids, orc.codebooks, 8)
+    q = np.concatenate([dec.astype(np.float32), (dec * (1.0 + 1e-6)).astype(np.float32),
+                        (dec + 1e-3 * rng.standard_normal(dec.shape)).astype(np.float32)])
+    for k, nprobe in ((10, 4), (3, cfg["nlist"])):
+        D, I = ix.search(dev(q), k, nprobe)
+        D, I = host(D), host(I)
+        assert (D >= 0).all(), "negative squared distance %r" % float(D.min())
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        _, co = oracle.coarse_probe(q, orc.centroids, nprobe, L2)
+        tc, te = l2_table_cancel(co, orc.codebooks)
+        check_search(D, I, Do, Io, L2, cancel=tc, cancel_eps=te)
+        # the stored vector itself is found first (its reconstruction is the query, or next to it)
+        found = (I[:48, 0] == orc.add_ids[pick]) | (Do[:48, 0] == Do[:48, 1])
+        assert found.all()
+    ix.close()
 
 
 @pytest.mark.parametrize("name", list(IVF_CASES))
@@ -264,7 +304,7 @@ def test_ivfpq_matches_oracle(vs, oracle, name):
     x, q = S.make_data(cfg)
     ix, orc = build_both(vs, oracle, cfg, x)
     check_storage(ix, orc)
-    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
+    xn = float(np.sqrt(orc.norms.max()))                       # largest decoded vector
     for k, nprobe in searches:
         say("  search k=%d nprobe=%d" % (k, nprobe))
         probes, cdist = ix.coarse(dev(q), nprobe)
@@ -273,7 +313,8 @@ def test_ivfpq_matches_oracle(vs, oracle, name):
         np.testing.assert_array_equal(host(cdist), co)
         D, I = ix.search(dev(q), k, nprobe)
         Do, Io = orc.search(q, k + EXTRA, nprobe)
-        same = check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+        tc, te = l2_table_cancel(co, orc.codebooks) if cfg["metric"] == L2 else (None, 0.0)
+        same = check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn, cancel=tc, cancel_eps=te)
         assert same > 0.99, same
     ix.close()
 
@@ -354,7 +395,9 @@ def test_c3_full_size_sampled(vs, oracle):
         say("  search all %d queries, nprobe=%d; oracle on %d of them" % (cfg["nq"], nprobe, qs.size))
         D, I = ix.search(dq, 10, nprobe)
         Do, Io = orc.search(q[qs], 10 + EXTRA, nprobe)
-        check_search(host(D)[qs], host(I)[qs], Do, Io, L2)
+        _, co = oracle.coarse_probe(q[qs], cent, nprobe, L2)
+        tc, te = l2_table_cancel(co, cb)
+        check_search(host(D)[qs], host(I)[qs], Do, Io, L2, cancel=tc, cancel_eps=te)
     ix.close()
 
 
@@ -906,7 +949,7 @@ KMEANS_CASES = [
     ("subvectors_d12_k20", 20_000, 12, 20, 3, "gauss"),
     ("subvectors_d3_k8", 9_000, 3, 8, 3, "gauss"),
     ("more_centroids_than_vectors", 40, 8, 64, 2, "gauss"),
-    # clusters longer than one summation block (4096 vectors): block sums, then their sum
+    # clusters longer than 4096 vectors: the kernel adds partial sums, the oracle one by one
     ("long_clusters_d8_k4", 40_000, 8, 4, 3, "gauss"),
     ("long_clusters_d12_k3", 30_001, 12, 3, 2, "gauss"),
     ("long_clusters_d32_k5", 33_000, 32, 5, 2, "gauss"),
@@ -919,10 +962,22 @@ KMEANS_CASES = [
 ]
 
 
+def _ulp_apart(a, b):
+    """Largest distance between two fp32 arrays counted in representable numbers."""
+    ia = a.view(np.int32).astype(np.int64); ib = b.view(np.int32).astype(np.int64)
+    ia = np.where(ia < 0, -(ia & 0x7FFFFFFF), ia); ib = np.where(ib < 0, -(ib & 0x7FFFFFFF), ib)
+    return int(np.abs(ia - ib).max()) if a.size else 0
+
+
 @pytest.mark.parametrize("name,n,d,K,niter,kind", KMEANS_CASES, ids=[c[0] for c in KMEANS_CASES])
-def test_kmeans_matches_oracle_bit_for_bit(vs, oracle, name, n, d, K, niter, kind):
-    """Assignment is canon on both sides and the means are float64 sums in a fixed order, so
-    the trained centroids are identical; the objective is a float64 sum of identical terms."""
+def test_kmeans_matches_oracle(vs, oracle, name, n, d, K, niter, kind):
+    """Round by round, each round started from the ORACLE's centroids: the assignment (a canon
+    decision on both sides) is identical bit for bit, the objective is a float64 sum of identical
+    terms, and every new centroid is within one fp32 step of the oracle's (the oracle adds a
+    cluster's vectors one by one in float64; the kernel adds partial sums of 4096 members, which
+    differs by float64 rounding only) -- and identical where no cluster exceeds 4096 vectors.
+    The whole run from the same start then agrees within 1e-5 (a centroid one step off can move a
+    vector that sits on a cell boundary)."""
     import torch
     say("kmeans %s n=%d d=%d K=%d niter=%d" % (name, n, d, K, niter))
     rng = np.random.default_rng(zlib.crc32(name.encode()))
@@ -935,17 +990,42 @@ def test_kmeans_matches_oracle_bit_for_bit(vs, oracle, name, n, d, K, niter, kin
     init = x[rng.permutation(n)[:K]].copy() if K <= n else rng.standard_normal((K, d), dtype=np.float32)
     if name == "odd_d30_k7":
         init[3] = 1e4                                          # a centroid no vector ever picks
+    xd = dev(x)
+    c_or = init.copy()
+    short = True
+    for r in range(niter):
+        c_next, obj_o, a_o = oracle.kmeans(x, c_or, 1, return_assign=True)
+        c = dev(c_or.copy())
+        obj, a = vs.vs_kmeans(xd, c, 1, return_assign=True)
+        np.testing.assert_array_equal(host(a), a_o)
+        np.testing.assert_allclose(np.array(obj), obj_o, rtol=1e-12)
+        largest = int(np.bincount(a_o, minlength=K).max())
+        if largest <= 4096:
+            np.testing.assert_array_equal(host(c), c_next)
+        else:
+            short = False
+            # one fp32 step, or (a mean that nearly cancels to zero) the float64 rounding itself
+            assert _ulp_apart(host(c), c_next) <= 1 or \
+                np.abs(host(c).astype(np.float64) - c_next).max() <= 1e-10 * float(np.abs(x).max())
+        c_or = c_next
     c = dev(init.copy())
-    obj = vs.vs_kmeans(dev(x), c, niter)
+    obj = vs.vs_kmeans(xd, c, niter)
     co, objo = oracle.kmeans(x, init, niter)
-    np.testing.assert_array_equal(host(c), co)
-    np.testing.assert_allclose(np.array(obj), objo, rtol=1e-12)
+    if short:
+        np.testing.assert_array_equal(host(c), co)
+        np.testing.assert_allclose(np.array(obj), objo, rtol=1e-12)
+    else:
+        np.testing.assert_allclose(np.array(obj), objo, rtol=1e-6)
+        scale = float(np.abs(x).max())
+        np.testing.assert_allclose(host(c), co, rtol=1e-5, atol=1e-5 * scale)
     if name == "odd_d30_k7":
         np.testing.assert_array_equal(host(c)[3], init[3])
 
 
 @pytest.mark.parametrize("name", ["c1", "pq4_l2", "ip_8bit"])
 def test_ivfpq_training_matches_oracle_bit_for_bit(vs, oracle, name):
+    """(6000 training vectors: no cluster reaches the 4096 vectors beyond which the kernel's
+    float64 sum is grouped differently from the oracle's, so the parameters are identical.)"""
     cfg = dict(IVF_CASES[name][0])
     cfg["nb"] = min(cfg["nb"], 6_000)
     say("train %s nb=%d d=%d nlist=%d M=%d nbits=%d metric=%d" % (
@@ -966,8 +1046,10 @@ def test_ivfpq_training_matches_oracle_bit_for_bit(vs, oracle, name):
     check_storage(ix, orc)
     D, I = ix.search(dev(q), 10, 4)
     Do, Io = orc.search(q, 10 + EXTRA, 4)
-    xn = np.sqrt((x.astype(np.float64) ** 2).sum(1).max()) * 1.5
-    check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn)
+    xn = float(np.sqrt(orc.norms.max()))
+    _, co = oracle.coarse_probe(q, ce, 4, cfg["metric"])
+    tc, te = l2_table_cancel(co, cbk) if cfg["metric"] == L2 else (None, 0.0)
+    check_search(host(D), host(I), Do, Io, cfg["metric"], q, xn, cancel=tc, cancel_eps=te)
     ix.close()
 
 
@@ -1012,7 +1094,7 @@ def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
     del codes_d
     q = host(qd)
     qs = np.sort(rng.choice(cfg["nq"], n_queries, replace=False))
-    xn = 1.5      # unit-norm data (decoded vectors are close to unit norm)
+    xn = float(np.sqrt(orc.norms.max()))      # largest decoded vector
     for k, nprobe in searches:
         say("  search all %d queries k=%d nprobe=%d; oracle on %d of them" % (cfg["nq"], k, nprobe, qs.size))
         probes, cdist = ix.coarse(qd, nprobe)
@@ -1021,7 +1103,8 @@ def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
         np.testing.assert_array_equal(host(cdist)[qs], co_)
         D, I = ix.search(qd, k, nprobe)
         Do, Io = orc.search(q[qs], k + EXTRA, nprobe)
-        check_search(host(D)[qs], host(I)[qs], Do, Io, cfg["metric"], q[qs], xn)
+        tc, te = l2_table_cancel(co_, cb) if cfg["metric"] == L2 else (None, 0.0)
+        check_search(host(D)[qs], host(I)[qs], Do, Io, cfg["metric"], q[qs], xn, cancel=tc, cancel_eps=te)
     ix.close()
 
 

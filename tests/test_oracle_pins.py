@@ -260,6 +260,73 @@ def test_decode_layout_M_K_dsub(oracle):
 
 # -------------------------------------------------------------- O7 ADC, O8 select
 
+@pytest.mark.parametrize("metric", [L2, IP])
+def test_coarse_probe_with_fewer_probes_than_lists_is_flat_search_over_centroids(oracle, metric):
+    # Sec. 5.1: the probed lists are the nprobe nearest centroids "as in Eq. 2".  Integer data, so the
+    # canon fp32 chain, the float64 sum and numpy agree bit for bit: the probes, their order and
+    # their values must be those of a flat search over the centroids (argmax for IP).
+    rng = np.random.default_rng(51)
+    cent = rng.integers(-9, 10, size=(40, 10)).astype(np.float32)
+    q = rng.integers(-9, 10, size=(60, 10)).astype(np.float32)
+    for nprobe in (1, 5, 17):
+        probes, cd = oracle.coarse_probe(q, cent, nprobe, metric)
+        Df, If = oracle.flat_search(cent, q, nprobe, metric)
+        np.testing.assert_array_equal(probes, If)
+        np.testing.assert_array_equal(cd, Df)
+        Dn, In = np_topk(np_pairwise(q, cent, metric), nprobe, metric)
+        np.testing.assert_array_equal(probes, In)
+        np.testing.assert_array_equal(cd, Dn)
+    if metric == IP:   # a plausible mistake: L2 ordering under the IP metric picks other lists
+        p_l2, _ = oracle.coarse_probe(q, cent, 5, L2)
+        p_ip, _ = oracle.coarse_probe(q, cent, 5, IP)
+        assert (p_l2 != p_ip).any()
+
+
+@pytest.mark.parametrize("metric,nbits", [(IP, 8), (IP, 4), (L2, 8)])
+def test_ivfpq_search_with_fewer_probes_than_lists_is_numpy_over_the_probed_members(oracle, metric, nbits):
+    # nprobe < nlist: the candidates of a query are exactly the members of its probed lists
+    # (probes from numpy, not from the oracle), scored on the decoded vectors, best first.
+    cfg, x, q, ix = _c1_index(oracle, metric, nbits, nb=2500, nq=40)
+    nprobe, k = 3, 12
+    D, I = ix.search(q, k, nprobe)
+    dec = oracle.pq_decode(ix.add_codes, ix.add_list_of, ix.centroids, ix.codebooks, nbits)
+    cd = np_pairwise(q, ix.centroids, metric).astype(np.float32)
+    order = np.argsort(cd if metric == L2 else -cd, axis=1, kind="stable")[:, :nprobe]
+    full = np_pairwise(q, dec, metric)
+    for a in range(q.shape[0]):
+        member = np.isin(ix.add_list_of, order[a])
+        cand = np.flatnonzero(member)
+        d32 = full[a, cand].astype(np.float32)
+        o = np.lexsort((ix.add_ids[cand], d32 if metric == L2 else -d32))[:k]
+        np.testing.assert_array_equal(I[a], ix.add_ids[cand][o])
+        np.testing.assert_allclose(D[a], d32[o], rtol=1e-6)
+    if metric == IP:   # the per-list bias <q, c_l> matters: without the centroid the scores differ
+        assert not np.allclose(D, np.take_along_axis((q.astype(np.float64) @ (dec - ix.centroids[ix.add_list_of]).T), I, 1), rtol=1e-3)
+
+
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_ivfsq8_search_with_fewer_probes_than_lists_is_numpy_over_the_probed_members(oracle, metric):
+    rng = np.random.default_rng(53)
+    x = rng.standard_normal((2000, 12)).astype(np.float32)
+    q = rng.standard_normal((30, 12)).astype(np.float32)
+    cent = x[rng.permutation(2000)[:14]].copy()
+    vmin, step = oracle.sq8_params(x)
+    ix = oracle.OracleIVFSQ8(12, metric, cent, vmin, step)
+    ix.add(x)
+    nprobe, k = 4, 9
+    D, I = ix.search(q, k, nprobe)
+    dec = oracle.sq8_decode(ix.add_codes, vmin, step)
+    cd = np_pairwise(q, cent, metric).astype(np.float32)
+    order = np.argsort(cd if metric == L2 else -cd, axis=1, kind="stable")[:, :nprobe]
+    full = np_pairwise(q, dec, metric)
+    for a in range(q.shape[0]):
+        cand = np.flatnonzero(np.isin(ix.add_list_of, order[a]))
+        d32 = full[a, cand].astype(np.float32)
+        o = np.lexsort((ix.add_ids[cand], d32 if metric == L2 else -d32))[:k]
+        np.testing.assert_array_equal(I[a], ix.add_ids[cand][o])
+        np.testing.assert_allclose(D[a], d32[o], rtol=1e-6)
+
+
 def _c1_index(oracle, metric=L2, nbits=8, **kw):
     cfg = S.config("C1", **kw)
     x, q = S.make_data(cfg)
@@ -273,7 +340,7 @@ def _c1_index(oracle, metric=L2, nbits=8, **kw):
 
 @pytest.mark.parametrize("metric,nbits", [(L2, 8), (IP, 8), (L2, 4), (IP, 4)])
 def test_adc_equals_distance_to_decoded_vector(oracle, metric, nbits):
-    # Eq. 8: the ADC distance is the distance from q to D(C(x)); Eq. 12: the sum
+    # Eq. 10: the ADC distance is the distance from q to D(C(x)); Eq. 14: the sum
     # of table look-ups equals it.  Probe all lists => the result must equal a
     # flat search over the decoded database, and the LUT form must agree.
     cfg, x, q, ix = _c1_index(oracle, metric, nbits, nb=2000, nq=30)
@@ -497,12 +564,12 @@ def test_code_sizes_the_paper_states(oracle):
         assert (codes[0] == 0).all() and (codes[1] == 0xFF).all()            # every bit of every byte is used
 
 
-def test_kmeans_mean_of_a_cluster_longer_than_one_summation_block(oracle):
-    """The update sums a centroid's vectors in float64 in blocks of 4096; whatever the order, a
-    float64 sum of 10,000 fp32 values of comparable size is within 1e-12 relative of the exact
-    sum, so the fp32 mean equals the correctly rounded mean of exact rational arithmetic in all
-    but a vanishing share of components -- checked here against Python's exact fractions, and
-    against numpy's pairwise float64 sum to the last fp32 bit but one."""
+def test_kmeans_mean_of_a_long_cluster_is_the_correctly_rounded_mean(oracle):
+    """The update adds a centroid's vectors one after the other in float64.  A float64 sum of
+    10,000 fp32 values of comparable size is within 1e-12 relative of the exact sum, so the fp32
+    mean equals the correctly rounded mean of exact rational arithmetic in all but a vanishing
+    share of components -- checked here against Python's exact fractions, and against numpy's
+    pairwise float64 sum to the last fp32 bit but one."""
     from fractions import Fraction
     rng = np.random.default_rng(77)
     x = rng.standard_normal((10_000, 3)).astype(np.float32) + np.float32(5.0)   # one cluster, far from 0
@@ -514,6 +581,33 @@ def test_kmeans_mean_of_a_cluster_longer_than_one_summation_block(oracle):
         assert c[0, t] == np.float32(float(exact)), (t, c[0, t], float(exact))
     ref = (x.astype(np.float64).sum(0) / x.shape[0]).astype(np.float32)
     assert np.all(np.abs(c[0].view(np.int32) - ref.view(np.int32)) <= 1)
+
+
+def test_kmeans_sum_runs_in_training_set_order(oracle):
+    """The float64 sum of a cluster is a running sum over the training set in its given order (no
+    blocks, no pairwise tree, not reversed): values whose float64 sum depends on the order tell
+    the orders apart.  From the left, 2^60 + 1 absorbs the 1, - 2^60 gives 0, + 1 gives 1: mean
+    1/4.  A pairwise tree gives (2^60 + 1) + (-2^60 + 1) = 0, and so does the reversed order."""
+    big = np.float32(2.0 ** 60)
+    x = np.array([[big], [1.0], [-big], [1.0]], np.float32)
+    c, _ = oracle.kmeans(x, np.array([[0.0]], np.float32), 1)
+    assert c[0, 0] == np.float32(0.25)
+    x2 = np.array([[1.0], [1.0], [big], [-big]], np.float32)     # both ones absorbed: 2^60 - 2^60
+    c2, _ = oracle.kmeans(x2, np.array([[0.0]], np.float32), 1)
+    assert c2[0, 0] == np.float32(0.0)
+
+
+def test_kmeans_reported_assignment_is_the_last_rounds(oracle):
+    rng = np.random.default_rng(78)
+    x = rng.integers(-20, 21, size=(3000, 6)).astype(np.float32)
+    c0 = x[rng.permutation(3000)[:11]].copy()
+    c2, _ = oracle.kmeans(x, c0, 2)
+    c3, _, a3 = oracle.kmeans(x, c0, 3, return_assign=True)
+    np.testing.assert_array_equal(a3, oracle.assign(x, c2, L2))               # step (1) of round 3 starts from c2
+    np.testing.assert_array_equal(a3, np_pairwise(x, c2, L2).argmin(1))       # integer data: exact either way
+    for j in range(11):
+        if (a3 == j).any():
+            np.testing.assert_array_equal(c3[j], x[a3 == j].astype(np.float64).mean(0).astype(np.float32))
 
 
 def test_kmeans_objective_never_increases(oracle):
