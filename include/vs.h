@@ -216,6 +216,27 @@ VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* 
 VS_API int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
                     float* out_dist, int64_t* out_ids, void* hip_stream);
 
+/*
+ * vs_ivfpq_search for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * bit for bit, but the work space of the search (operand planes and candidate lists of the
+ * coarse quantizer, probes, per-split partial results, the work counter of the scan) is a
+ * file-scope device array of VS_STATIC_SCRATCH_BYTES that every GPU the library runs on holds
+ * until the process ends, instead of the index's grow-only buffer.  The call allocates and
+ * frees nothing (no hipMalloc / hipFree, no events) and only enqueues kernels on hip_stream.
+ * The array's device address is looked up once per device (in vs_ivfpq_create, else in the
+ * first call on that device).
+ * Limits: the work space grows with nq (and nlist, d, nprobe, k): a call whose work space
+ * exceeds VS_STATIC_SCRATCH_BYTES is refused with VS_ERR_INVALID_ARG and a message that states
+ * both sizes (32 MiB serve e.g. 64 queries at nlist = 65536, d = 96, nprobe = 64, k = 100, or
+ * 256 queries at nlist = 4096, d = 128, nprobe = 64).  Profiling stages are not recorded.
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU race
+ * (also calls on different indexes or streams); the caller serialises them.
+ */
+#define VS_STATIC_SCRATCH_BYTES (32u << 20)
+VS_API int vs_ivfpq_search_static(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k,
+                           int32_t nprobe, float* out_dist, int64_t* out_ids, void* hip_stream);
+
 /* Frees the index and all device memory it owns.  NULL is allowed. */
 VS_API void vs_ivfpq_destroy(vs_ivfpq* ix);
 

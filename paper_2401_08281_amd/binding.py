@@ -94,6 +94,8 @@ def lib():
     L.vs_ivfpq_add.argtypes = [vp, vp, i64, vp, vp]
     L.vs_ivfpq_search.restype = ctypes.c_int
     L.vs_ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_search_static.restype = ctypes.c_int
+    L.vs_ivfpq_search_static.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     L.vs_ivfpq_destroy.restype = None
     L.vs_ivfpq_destroy.argtypes = [vp]
     L.vs_ivfpq_ntotal.restype = i64
@@ -337,6 +339,19 @@ def vs_ivfpq_search(h, q, k, nprobe, out_dist=None, out_ids=None):
     _dev(out_dist, torch.float32, "out_dist")
     _dev(out_ids, torch.int64, "out_ids")
     _check(lib().vs_ivfpq_search(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_ivfpq_search_static(h, q, k, nprobe, out_dist, out_ids):
+    """vs_ivfpq_search on the library's static work space: no device allocation inside the
+    call, so the outputs are the caller's (tensors [nq, k], fp32 and int64)."""
+    q = _dev(q, torch.float32, "q")
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    nq = q.shape[0]
+    if tuple(out_dist.shape) != (nq, k) or tuple(out_ids.shape) != (nq, k):
+        raise ValueError("out_dist and out_ids must be [nq, k]")
+    _check(lib().vs_ivfpq_search_static(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
     return out_dist, out_ids
 
 
@@ -613,6 +628,9 @@ class IVFPQ:
 
     def search(self, q, k, nprobe, out_dist=None, out_ids=None):
         return vs_ivfpq_search(self.h, q, k, nprobe, out_dist, out_ids)
+
+    def search_static(self, q, k, nprobe, out_dist, out_ids):
+        return vs_ivfpq_search_static(self.h, q, k, nprobe, out_dist, out_ids)
 
     def coarse(self, q, nprobe):
         return vs_ivfpq_coarse(self.h, q, nprobe, self.nlist)

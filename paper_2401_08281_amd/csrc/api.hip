@@ -56,6 +56,32 @@ struct Carver {
   size_t take(size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; }
 };
 
+// The file-scope device array behind vs_ivfpq_search_static.  Its name is a host-side stand-in,
+// not a device address: host code uses the per-device pointer that hipGetSymbolAddress returns
+// (every GPU holds its own copy of the array at its own address).
+constexpr size_t kStaticScratchBytes = VS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_static_mu;
+void* g_static_ptr[16] = {nullptr};
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device
+// current); null + error on failure.
+int static_scratch(char** out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "static scratch: device %d", dev);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(VS_ERR_DEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_static_ptr[dev] = ptr;
+  }
+  *out = static_cast<char*>(g_static_ptr[dev]);
+  return VS_OK;
+}
+
 // scratch of vs_flat_search, one per device
 std::mutex g_flat_mu;
 Scratch g_flat_scratch[16];
@@ -752,6 +778,10 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
   TRY_C(hipStreamSynchronize(st));
   if (ix->has_planes) TRY_C(learn_planes(&ix->c_planes));
 #undef TRY_C
+  {   // set-up for vs_ivfpq_search_static: this device's address of the static work space
+    char* unused = nullptr;
+    if (int rc = static_scratch(&unused)) return cleanup(rc);
+  }
   *out = ix;
   return VS_OK;
 }
@@ -936,13 +966,14 @@ int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
 
 // coarse quantizer: the npr best lists per query, best first, with their canon values
 static int coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
-                         int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st) {
+                         int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st,
+                         bool timed = true) {
   SelectOut out;
   out.val = cdist;
   out.idx32 = probes;
   return knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
-                 ix->has_planes ? &ix->c_planes : nullptr, out, st, VS_STAGE_COARSE_DIST,
-                 VS_STAGE_COARSE_SELECT);
+                 ix->has_planes ? &ix->c_planes : nullptr, out, st, timed ? VS_STAGE_COARSE_DIST : -1,
+                 timed ? VS_STAGE_COARSE_SELECT : -1);
 }
 
 int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
@@ -961,54 +992,97 @@ int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t npro
   return VS_OK;
 }
 
-int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
-                    float* out_dist, int64_t* out_ids, void* hip_stream) {
-  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: index is null");
-  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: nq < 0");
-  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: k = %d outside [1, %d]", k, VS_MAX_K);
-  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: nprobe = %d outside [1, %d]", nprobe, VS_MAX_K);
-  if (nq == 0) return VS_OK;
-  if (!q || !out_dist || !out_ids) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_search: null pointer");
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+namespace {
+
+// Work space of one search, carved from one buffer.
+struct SearchLayout {
+  int npr = 0, nsplit = 1;
+  KnnPlan plan;
+  size_t o_knn = 0, o_pr = 0, o_cd = 0, o_part = 0, o_cnt = 0, bytes = 0;
+};
+void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayout* out) {
+  SearchLayout& L = *out;
   const IvfpqDims& g = ix->g;
-  const int npr = std::min<int>(nprobe, g.nlist);
-
+  L.npr = std::min<int>(nprobe, g.nlist);
   // probe splits: enough workgroups to fill the chip when nq is small
-  int nsplit = (int)std::min<int64_t>(npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
-  const int ppb = (npr + nsplit - 1) / nsplit;
-  nsplit = (npr + ppb - 1) / ppb;
-
-  const KnnPlan plan = knn_plan(nq, g.nlist, g.d, npr, ix->has_planes);
+  L.nsplit = (int)std::min<int64_t>(L.npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
+  const int ppb = (L.npr + L.nsplit - 1) / L.nsplit;
+  L.nsplit = (L.npr + ppb - 1) / ppb;
+  L.plan = knn_plan(nq, g.nlist, g.d, L.npr, ix->has_planes);
   Carver cv;
-  const size_t o_knn = cv.take(plan.bytes);
-  const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
-  const size_t o_cd = cv.take((size_t)nq * npr * sizeof(float));
-  const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
-  const size_t o_cnt = cv.take(sizeof(u64));
-  if (int rc = ix->scratch.reserve(cv.off)) return rc;
-  char* base = static_cast<char*>(ix->scratch.p);
-  int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
-  float* cdist = reinterpret_cast<float*>(base + o_cd);
-  u64* partial = reinterpret_cast<u64*>(base + o_part);
-  u64* counter = reinterpret_cast<u64*>(base + o_cnt);
+  L.o_knn = cv.take(L.plan.bytes);
+  L.o_pr = cv.take((size_t)nq * L.npr * sizeof(int32_t));
+  L.o_cd = cv.take((size_t)nq * L.npr * sizeof(float));
+  L.o_part = cv.take((size_t)nq * L.nsplit * k * sizeof(u64));
+  L.o_cnt = cv.take(sizeof(u64));
+  L.bytes = cv.off;
+}
 
-  if (int rc = coarse_select(ix, plan, base + o_knn, q, nq, npr, probes, cdist, st)) return rc;
+int search_check_args(const char* who, const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k,
+                      int32_t nprobe, const float* out_dist, const int64_t* out_ids) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "%s: index is null", who);
+  if (nq < 0) return fail(VS_ERR_INVALID_ARG, "%s: nq < 0", who);
+  if (k < 1 || k > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "%s: k = %d outside [1, %d]", who, k, VS_MAX_K);
+  if (nprobe < 1 || nprobe > VS_MAX_K) return fail(VS_ERR_INVALID_ARG, "%s: nprobe = %d outside [1, %d]", who, nprobe, VS_MAX_K);
+  if (nq > 0 && (!q || !out_dist || !out_ids)) return fail(VS_ERR_INVALID_ARG, "%s: null pointer", who);
+  return VS_OK;
+}
+
+// The search itself on a work space of L.bytes at `base`: kernel launches only.
+int search_run(const char* who, const vs_ivfpq* ix, const SearchLayout& L, char* base, const float* q,
+               int64_t nq, int k, float* out_dist, int64_t* out_ids, hipStream_t st, bool timed) {
+  const IvfpqDims& g = ix->g;
+  int32_t* probes = reinterpret_cast<int32_t*>(base + L.o_pr);
+  float* cdist = reinterpret_cast<float*>(base + L.o_cd);
+  u64* partial = reinterpret_cast<u64*>(base + L.o_part);
+  u64* counter = reinterpret_cast<u64*>(base + L.o_cnt);
+  if (int rc = coarse_select(ix, L.plan, base + L.o_knn, q, nq, L.npr, probes, cdist, st, timed)) return rc;
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
   // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
   {
-    StageTimer t(VS_STAGE_SCAN, st);
-    if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, npr, nsplit,
+    StageTimer t(timed ? VS_STAGE_SCAN : -1, st);
+    if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, L.npr, L.nsplit,
                           ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->cnorm,
                           ix->ntotal, k, partial, counter, ix->ids, out_dist, out_ids, st) != 0)
-      return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_search: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", g.M * g.K, k);
+      return fail(VS_ERR_UNSUPPORTED, "%s: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", who, g.M * g.K, k);
   }
-  if (nsplit > 1) {
-    StageTimer t(VS_STAGE_MERGE, st);
-    launch_ivfpq_merge(partial, nq, nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
+  if (L.nsplit > 1) {
+    StageTimer t(timed ? VS_STAGE_MERGE : -1, st);
+    launch_ivfpq_merge(partial, nq, L.nsplit, k, g.metric, ix->ids, out_dist, out_ids, st);
   }
   HIP_TRY(hipGetLastError());
   return VS_OK;
+}
+
+}  // namespace
+
+int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                    float* out_dist, int64_t* out_ids, void* hip_stream) {
+  if (int rc = search_check_args("vs_ivfpq_search", ix, q, nq, k, nprobe, out_dist, out_ids)) return rc;
+  if (nq == 0) return VS_OK;
+  SearchLayout L;
+  search_layout(ix, nq, k, nprobe, &L);
+  if (int rc = ix->scratch.reserve(L.bytes)) return rc;
+  return search_run("vs_ivfpq_search", ix, L, static_cast<char*>(ix->scratch.p), q, nq, k, out_dist, out_ids,
+                    static_cast<hipStream_t>(hip_stream), true);
+}
+
+int vs_ivfpq_search_static(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                           float* out_dist, int64_t* out_ids, void* hip_stream) {
+  if (int rc = search_check_args("vs_ivfpq_search_static", ix, q, nq, k, nprobe, out_dist, out_ids)) return rc;
+  if (nq == 0) return VS_OK;
+  SearchLayout L;
+  search_layout(ix, nq, k, nprobe, &L);
+  if (L.bytes > kStaticScratchBytes)
+    return fail(VS_ERR_INVALID_ARG,
+                "vs_ivfpq_search_static: %lld queries with k = %d, nprobe = %d need %zu bytes of work space, "
+                "the static buffer holds %zu; search fewer queries per call or use vs_ivfpq_search",
+                (long long)nq, k, nprobe, L.bytes, kStaticScratchBytes);
+  char* base = nullptr;
+  if (int rc = static_scratch(&base)) return rc;
+  return search_run("vs_ivfpq_search_static", ix, L, base, q, nq, k, out_dist, out_ids,
+                    static_cast<hipStream_t>(hip_stream), false);
 }
 
 // ---- IVF-Flat: the same inverted lists with the vectors stored as they are --------------
