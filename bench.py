@@ -44,7 +44,7 @@ def log(msg):
 def scan_kernel_name(cfg, code_size):
     """The scan kernel the library picks for this shape (same rule as its launcher)."""
     if cfg["nbits"] == 8 and (cfg["M"], cfg["d"] // cfg["M"]) in ((16, 8), (32, 3), (8, 4)):
-        return "ivfpq_scan_reg_kernel"
+        return "ivfpq_scan_bank_kernel"
     return "ivfpq_scan_pipe_kernel" if code_size in (16, 32, 64) else "ivfpq_scan_kernel"
 
 

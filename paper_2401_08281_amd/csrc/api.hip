@@ -939,7 +939,7 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
     return fail(VS_ERR_OOM, "vs_ivfpq_add: id / norm storage allocation failed");
   }
   launch_relayout(g, ix->codes, ix->ids, ix->norms, ix->ntotal, ix->list_off, pl.new_off, tmp_codes,
-                  ids, ix->ntotal, tmp_norms, pl.dest, n, codes, new_ids, new_norms, st);
+                  ids, ix->ntotal, tmp_norms, pl.dest, pl.list_of, n, codes, new_ids, new_norms, st);
   return ivf_commit_storage(ix, codes, new_ids, new_norms, total, &pl, st, "vs_ivfpq_add");
 }
 
@@ -1306,7 +1306,7 @@ int vs_ivfsq8_add(vs_ivfsq8* sx, const float* x, int64_t n, const int64_t* ids, 
     return fail(VS_ERR_OOM, "vs_ivfsq8_add: id storage allocation failed");
   }
   launch_relayout(g, ix->codes, ix->ids, nullptr, ix->ntotal, ix->list_off, pl.new_off, tmp_codes,
-                  ids, ix->ntotal, nullptr, pl.dest, n, codes, new_ids, nullptr, st);
+                  ids, ix->ntotal, nullptr, pl.dest, pl.list_of, n, codes, new_ids, nullptr, st);
   return ivf_commit_storage(ix, codes, new_ids, nullptr, total, &pl, st, "vs_ivfsq8_add");
 }
 
@@ -1391,8 +1391,13 @@ int vs_ivfpq_get_assignments(const vs_ivfpq* ix, int64_t* ids, int32_t* list_of,
 int vs_ivfpq_get_codes(const vs_ivfpq* ix, uint8_t* codes, void* hip_stream) {
   if (!ix || !codes) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_codes: null pointer");
   if (ix->ntotal == 0) return VS_OK;
-  HIP_TRY(hipMemcpyAsync(codes, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice,
-                         static_cast<hipStream_t>(hip_stream)));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (ivfpq_codes_rotated(ix->g)) {   // the store keeps these shapes' codes rotated for the scan
+    launch_codes_canonical(ix->g, ix->codes, ix->list_off, ix->ntotal, codes, st);
+    HIP_TRY(hipGetLastError());
+    return VS_OK;
+  }
+  HIP_TRY(hipMemcpyAsync(codes, ix->codes, (size_t)ix->ntotal * ix->g.code_size, hipMemcpyDeviceToDevice, st));
   return VS_OK;
 }
 

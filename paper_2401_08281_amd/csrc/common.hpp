@@ -156,8 +156,8 @@ __device__ __forceinline__ void wave_sort_regs(T (&v)[R]) {
 // once the threshold has tightened almost every candidate costs one compare.
 // When the reservoir cannot take another full wavefront of candidates, the
 // live slots are sorted and the reservoir is emptied.  TOT is a power of two
-// >= k + 64.  R > 0: TOT == 64 * R and the sort runs in registers (R keys per
-// lane, DPP exchanges); R == 0: any TOT, bitonic network through LDS.
+// >= k + 64.  R > 0: TOT <= 64 * R (any size >= k + 64) and the sort runs in registers (R keys
+// per lane, DPP exchanges); R == 0: TOT a power of two, bitonic network through LDS.
 // LDS pointers carry their address space in the type, so that every access below is
 // a ds_* instruction (not a flat access that has to discover its aperture at run time).
 typedef __attribute__((address_space(3))) volatile u64* lds_u64_ptr;
@@ -170,20 +170,18 @@ struct WaveSelect {
   bool has_shared;
   int tot, k, cnt;       // cnt: reservoir fill (wave-uniform)
   u64 thresh;            // k-th best key this wavefront holds (wave-uniform)
-#ifdef VS_SCAN_TIMING
-  unsigned long long trim_cycles = 0;
-#endif
+  u64 seen;              // the workgroup bound as last read by refresh_shared() (wave-uniform)
 
   // attach to existing state (slots hold k sorted keys plus cnt_ reservoir entries)
   __device__ __forceinline__ void attach(u64* slots, int tot_, int k_, int cnt_, u64 thresh_) {
     s = to_lds(slots); shared = (lds_u64_ptr)0; has_shared = false;
-    tot = tot_; k = k_; cnt = cnt_; thresh = thresh_;
+    tot = tot_; k = k_; cnt = cnt_; thresh = thresh_; seen = KEY_EMPTY;
   }
 
   __device__ __forceinline__ void init(u64* slots, int tot_, int k_, u64* shared_ = nullptr) {
     s = to_lds(slots); has_shared = shared_ != nullptr;
     shared = has_shared ? to_lds(shared_) : (lds_u64_ptr)0;
-    tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY;
+    tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY; seen = KEY_EMPTY;
     for (int i = lane_id(); i < k; i += VS_WAVE) s[i] = KEY_EMPTY;
     wave_lds_sync();
   }
@@ -227,9 +225,6 @@ struct WaveSelect {
 
   // Sorts the live slots, keeps the best k, empties the reservoir.
   __device__ __forceinline__ void trim() {
-#ifdef VS_SCAN_TIMING
-    const unsigned long long t0_ = clock64();
-#endif
     if constexpr (R > 0) sort_regs(); else sort_lds();
     cnt = 0;
     thresh = s[k - 1];
@@ -238,9 +233,6 @@ struct WaveSelect {
     if (has_shared && lane_id() == 0 && thresh != KEY_EMPTY)
       __hip_atomic_fetch_min((__attribute__((address_space(3))) u64*)shared, thresh,
                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-#ifdef VS_SCAN_TIMING
-    trim_cycles += clock64() - t0_;
-#endif
   }
 
   // Every lane of the wavefront must call this together.  use_shared: also
@@ -255,6 +247,23 @@ struct WaveSelect {
     if (pass) s[pos] = key;
     cnt += __popcll(mask);
     if (k + cnt + VS_WAVE > tot) trim();
+  }
+
+  // The same with the workgroup bound taken from the copy that refresh_shared() made: a bound only
+  // ever tightens, so an old copy is still a valid (weaker) bound, and reading it once per list
+  // instead of once per push takes an LDS round trip off every push.
+  __device__ __forceinline__ void refresh_shared() {
+    if (has_shared) { const u64 sh = *shared; seen = sh < seen ? sh : seen; }
+  }
+  __device__ __forceinline__ void push_cached(bool valid, u64 key) {
+    const u64 th = seen < thresh ? seen : thresh;
+    bool pass = valid && key < th;
+    u64 mask = __ballot(pass);
+    if (mask == 0) return;
+    int pos = k + cnt + __popcll(mask & ((1ull << lane_id()) - 1ull));
+    if (pass) s[pos] = key;
+    cnt += __popcll(mask);
+    if (k + cnt + VS_WAVE > tot) { trim(); refresh_shared(); }
   }
 
   // After finish(), slots [0, k) hold the k best keys in ascending order.

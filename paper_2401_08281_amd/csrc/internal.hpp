@@ -50,8 +50,14 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
                      const float* old_norms, int64_t old_total, const int64_t* old_off,
                      const int64_t* new_off, const uint8_t* tmp_codes,
                      const int64_t* new_ids_or_null, int64_t id_base, const float* tmp_norms,
-                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids, float* norms,
-                     hipStream_t st);
+                     const int64_t* dest, const int32_t* new_list_of, int64_t n_new, uint8_t* codes,
+                     int64_t* ids, float* norms, hipStream_t st);
+// Indexes of the shapes that the bank-private-table scan kernel serves keep the code at position
+// p of its list rotated by p bytes (stored byte b = c_{(b + p) mod M}); launch_relayout writes
+// that layout, launch_codes_canonical turns a copy back into byte m = c_m.
+bool ivfpq_codes_rotated(const IvfpqDims& g);
+void launch_codes_canonical(const IvfpqDims& g, const uint8_t* stored, const int64_t* off,
+                            int64_t total, uint8_t* out, hipStream_t st);
 // tmp_norms[i] = |c_list(i) + decoded code i|^2 (tmp_codes: one byte per (vector, m))
 void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
                      const float* centroids, const float* codebooks, float* tmp_norms,

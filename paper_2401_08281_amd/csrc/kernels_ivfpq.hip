@@ -138,23 +138,39 @@ __global__ void move_old_kernel(const uint8_t* __restrict__ old_codes,
   for (int b = 0; b < cs; ++b) codes[np * cs + b] = old_codes[p * cs + b];
 }
 
+// rot > 0 (= M, 8-bit codes): the code at position p of its list is stored rotated by p bytes,
+// stored byte b = c_{(b + p) mod M} (the layout ivfpq_scan_bank_kernel reads); rot == 0: as is.
 __global__ void scatter_new_kernel(const uint8_t* __restrict__ tmp_codes,
                                    const int64_t* __restrict__ new_ids, int64_t id_base,
                                    const float* __restrict__ tmp_norms,
                                    const int64_t* __restrict__ dest, int64_t n, int M, int nbits,
-                                   int cs, uint8_t* __restrict__ codes, int64_t* __restrict__ ids,
-                                   float* __restrict__ norms) {
+                                   int cs, int rot, const int32_t* __restrict__ list_of,
+                                   const int64_t* __restrict__ new_off, uint8_t* __restrict__ codes,
+                                   int64_t* __restrict__ ids, float* __restrict__ norms) {
   const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int64_t p = dest[i];
   ids[p] = new_ids ? new_ids[i] : id_base + i;
   if (norms) norms[p] = tmp_norms[i];
   const uint8_t* __restrict__ t = tmp_codes + i * M;
-  if (nbits == 8) {
+  if (rot > 0) {
+    const int shift = (int)((p - new_off[list_of[i]]) & (int64_t)(rot - 1));   // rot is a power of two
+    for (int b = 0; b < cs; ++b) codes[p * cs + b] = t[(b + shift) & (rot - 1)];
+  } else if (nbits == 8) {
     for (int b = 0; b < cs; ++b) codes[p * cs + b] = t[b];
   } else {  // two 4-bit codes per byte, even m in the low nibble
     for (int b = 0; b < cs; ++b) codes[p * cs + b] = (uint8_t)(t[2 * b] | (t[2 * b + 1] << 4));
   }
+}
+
+// The stored codes as the header defines them (byte m = c_m): undoes the rotation above.
+__global__ void unrotate_codes_kernel(const uint8_t* __restrict__ stored, const int64_t* __restrict__ off,
+                                      int nlist, int64_t total, int M, uint8_t* __restrict__ out) {
+  const int64_t s = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (s >= total) return;
+  const int l = list_of_position(off, nlist, s);
+  const int shift = (int)((s - off[l]) & (int64_t)(M - 1));
+  for (int b = 0; b < M; ++b) out[s * M + ((b + shift) & (M - 1))] = stored[s * M + b];
 }
 
 __global__ void list_of_storage_kernel(const int64_t* __restrict__ off, int nlist, int64_t total,
@@ -501,71 +517,114 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Register-resident-codebook variant for 8-bit codes (K = 256) and shapes known
-// at compile time.  Lane j of the workgroup owns codeword j of EVERY
-// sub-quantizer: M * DSUB floats in registers, loaded once per workgroup.  The
-// workgroups are persistent: each walks over (query, probe split) items, so
-// the codebook is read from memory once per workgroup, not once per list.
-// Building a table then costs, per lane, M * DSUB (sub, fma) pairs against the
-// residual, which every lane reads from LDS as broadcasts, and M conflict-free
-// LDS stores.  The first 256 codes of a list are requested from memory before
-// the table is built, so their latency hides under the arithmetic.
+// Register-resident codebook + bank-private look-up tables, for 8-bit codes (K = 256) of
+// M = 8, 16 or 32 sub-quantizers and shapes known at compile time.
+//
+// Look-ups.  A wavefront's LDS read of one dword per lane is served 32 lanes at a time by 64
+// banks; 32 random addresses collide in some bank almost always (measured: 5.9 - 7.9 clk per
+// wavefront read against 3.0 - 3.7 when the 32 lanes hit 32 different banks).  So the tables
+// are laid out [j][column] with rows of 64 floats = one pass over all banks: entry j of
+// sub-quantizer m sits at float j * 64 + column, its bank is its column, and at every step the
+// 32 lanes of a pass read 32 DIFFERENT columns: lane l looks up sub-quantizer (t + l) mod M at
+// step t, in copy (l / M) mod (32 / M) of that table (every table exists 32 / M times).  Columns
+// 0 .. 31 hold one set of tables, columns 32 .. 63 the other one of the double buffer (L2: the
+// next list's tables are built while this one is scanned, in banks the scan never touches).
+// For the lanes to find byte t of their code to be c_{(t + l) mod M}, the index stores the code
+// at position p of its list rotated by p bytes (see rotate_code): a chunk starts at a multiple
+// of 256 codes from the list's start, so l = p mod 64.
+// The address of an entry is then ONE instruction: v_perm_b32 puts the code byte into byte 1
+// (j * 256) and the lane's column byte (4 * column, a per-lane constant of the step) into byte 0;
+// the tables start at LDS address 0 (checked at run time, with a plain fallback).
+//
+// Tables.  Lane (m, jg) of the workgroup owns codewords jg * M .. jg * M + M - 1 of sub-quantizer
+// m = lane mod M: M * DSUB floats in registers, loaded once per (persistent) workgroup.  The 32
+// lanes of a pass then store one row segment of 32 consecutive columns: conflict-free as well.
 // ---------------------------------------------------------------------------
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x3 __attribute__((ext_vector_type(3)));
+
+// One PQ code of M bytes (8, 16 or 32) per lane, fetched by hand-issued loads.  The compiler
+// tracks the loads it issues itself register by register, but at the joins of a loop it merges
+// that knowledge conservatively and then waits for EVERY load in flight (vmcnt(0)) where one old
+// load is needed -- which ends a prefetch of more than one chunk.  So the scan issues its code
+// loads in asm and waits for them by count: vector memory loads return in order, and
+// wait_newer<N>() returns once at most N younger load INSTRUCTIONS are outstanding, i.e. once
+// this code (and everything older) has arrived.  The registers are operands of the wait, so no
+// use can be scheduled ahead of it.
 template <int M>
-struct CodeWords {           // one PQ code of M bytes held in registers
+struct CodeWords {
   static constexpr int W = M / 4;
-  u32 w[W];
-  __device__ __forceinline__ void load(const uint8_t* __restrict__ p) {
-    if constexpr (M % 16 == 0) {
+  static constexpr int NLOAD = M == 32 ? 2 : 1;       // load instructions per code
+  u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};    // M == 32: a, b; M == 16: a; M == 8: a.xy as a2
+  u32x2 a2 = {0u, 0u};
+  __device__ __forceinline__ u32 word(int i) const {
+    if constexpr (M == 8) return a2[i & 1];
+    else return i < 4 ? a[i & 3] : b[i & 3];
+  }
+  // (the destination registers are asm outputs and nothing else touches them before the wait:
+  // a copy issued in between would read them before the data has arrived)
+  __device__ __forceinline__ void load_async(const uint8_t* p) {
+    if constexpr (M == 32)
+      asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
+                   : "=&v"(a), "=&v"(b) : "v"(p) : "memory");
+    else if constexpr (M == 16)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(a) : "v"(p) : "memory");
+    else
+      asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(a2) : "v"(p) : "memory");
+  }
+  template <int N>
+  __device__ __forceinline__ void wait_newer() {
+    if constexpr (M == 32) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+    else if constexpr (M == 16) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a2) : "n"(N) : "memory");
+  }
+  // all loads issued so far have landed in this set's registers
+  __device__ __forceinline__ void drain() {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(a2) : : "memory");
+  }
+  // sum of the M table entries; col[w] holds the lane's four column bytes of steps 4w .. 4w + 3.
+  // Look-ups go in groups of at most 16: the addresses of a group, its reads back to back (LDS
+  // returns in order, so each addition then waits for its own value only), its additions.  Left to
+  // itself the scheduler issues five reads and drains them all before the next five.
+  template <bool AT_ZERO>
+  __device__ __forceinline__ float adc_banked(const unsigned char* __restrict__ lut, const u32 (&col)[W],
+                                              float dist) const {
+    constexpr int G = M < 16 ? M : 16;          // look-ups per group
 #pragma unroll
-      for (int i = 0; i < M / 16; ++i) {
-        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
-        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+    for (int g0 = 0; g0 < M; g0 += G) {
+      u32 a[G];
+#pragma unroll
+      for (int i = 0; i < G / 4; ++i) {
+        const u32 cwd = word(g0 / 4 + i), cl = col[g0 / 4 + i];
+        // byte 0 <- column byte b of cl, byte 1 <- code byte b of cwd, bytes 2 and 3 <- 0
+        a[4 * i] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0400u);
+        a[4 * i + 1] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0501u);
+        a[4 * i + 2] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0602u);
+        a[4 * i + 3] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0703u);
       }
-    } else if constexpr (M % 8 == 0) {
+      float v[G];
 #pragma unroll
-      for (int i = 0; i < M / 8; ++i) {
-        const uint2 v = reinterpret_cast<const uint2*>(p)[i];
-        w[2 * i] = v.x; w[2 * i + 1] = v.y;
+      for (int t = 0; t < G; ++t) {
+        if constexpr (AT_ZERO) v[t] = *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)a[t]);
+        else v[t] = *reinterpret_cast<const float*>(lut + a[t]);
       }
-    } else {
 #pragma unroll
-      for (int i = 0; i < W; ++i) w[i] = reinterpret_cast<const u32*>(p)[i];
+      for (int t = 0; t < G; ++t) dist += v[t];
+      if constexpr (AT_ZERO) {
+        __builtin_amdgcn_sched_group_barrier(0x002, G, 0);     // the group's address instructions
+        __builtin_amdgcn_sched_group_barrier(0x100, G, 0);     // its reads, back to back
+        __builtin_amdgcn_sched_group_barrier(0x002, G, 0);     // its additions
+      }
     }
-  }
-  __device__ __forceinline__ float adc(const float* __restrict__ lut, float dist) const {
-#pragma unroll
-    for (int i = 0; i < W; ++i) dist = adc_bytes<8>(lut, w[i], 4 * i, dist);
-    return dist;
-  }
-  // the same for tables whose rows are KP floats apart
-  template <int KP>
-  __device__ __forceinline__ float adc_rows(const float* __restrict__ lut, float dist) const {
-#pragma unroll
-    for (int i = 0; i < W; ++i)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) dist += lut[(4 * i + b) * KP + ((w[i] >> (8 * b)) & 0xFFu)];
     return dist;
   }
 };
 
-#ifdef VS_SCAN_TIMING
-// debug builds only: cycles spent per phase, summed over wavefront 0 of every workgroup
-__device__ unsigned long long g_scan_cycles[8];
-#define TICK(slot)                                                        \
-  do {                                                                    \
-    if (tid == 0) {                                                       \
-      const unsigned long long now_ = clock64();                     \
-      tacc[slot] += now_ - tprev;                                         \
-      tprev = now_;                                                       \
-    }                                                                     \
-  } while (0)
-#else
-#define TICK(slot) do {} while (0)
-#endif
+constexpr int kBankTableBytes = 256 * 64 * (int)sizeof(float);   // 256 rows of 64 floats
 
-template <int M, int DSUB, int METRIC, int R, int NBUF>
-__global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
+template <int M, int DSUB, int METRIC, int R, int NT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 128, NT / 128)))
+void ivfpq_scan_bank_kernel(
     const float* __restrict__ q, const float* __restrict__ centroids,
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
@@ -577,47 +636,49 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
   // + |x'|^2 per code)
   constexpr int K = 256, D = M * DSUB;
   constexpr int KEY_METRIC = METRIC == 1 ? 1 : 0;
-  constexpr int TPM = 256 / M;    // lanes that share one sub-quantizer
-  // Rows of a table are K + TPM floats apart: the lanes of a wavefront store entries of 64 / TPM
-  // consecutive sub-quantizers at the same column, and with rows a multiple of 256 bytes apart
-  // those stores would all fall into the same TPM banks.
-  constexpr int KP = K + TPM;
-  static_assert(256 % M == 0 && M % 4 == 0, "M must divide 256 and codes are read as 32-bit words");
+  constexpr int REP = 32 / M;     // copies of every table
+  constexpr int NW = NT / 64;     // wavefronts of the workgroup (two workgroups share a CU)
+  constexpr int EPL = K * M / NT; // table entries a lane builds = codewords it keeps
+  // EXPAND: L2 table entries as |r|^2 + |t|^2 - 2 <r, t> (|t|^2 in registers, DSUB + 1 instructions
+  // per entry) rather than as sum (r - t)^2 (2 DSUB instructions)
+  constexpr bool EXPAND = METRIC == 0;
+  static_assert(NT == 256 || NT == 512, "two workgroups per CU");
+  static_assert(M == 8 || M == 16 || M == 32, "tables of M sub-quantizers fill 32 banks in 32 / M copies");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
-  u64* bound = slots + 4 * tot;                                 // workgroup bound (+ pad)
-  float* lut0 = reinterpret_cast<float*>(bound + 2);            // NBUF x M * KP
-  int64_t* s_begin = reinterpret_cast<int64_t*>(lut0 + NBUF * M * KP);  // ppb
-  int64_t* s_end = s_begin + ppb;                               // ppb
+  // (the tables come first: with no static LDS in this kernel they start at LDS address 0)
+  float* lut0 = reinterpret_cast<float*>(smem);                 // [256][64]
+  u64* slots = reinterpret_cast<u64*>(smem + kBankTableBytes);  // NW * tot
+  u64* bound = slots + NW * tot;                                 // workgroup bound (+ the item in hand)
+  // the item's NON-EMPTY probed lists, compacted: first and one-past-last storage position
+  // (positions fit 32 bits: an index holds fewer than 2^32 vectors), list number, per-list term
+  u32* s_begin = reinterpret_cast<u32*>(bound + 3);             // ppb
+  u32* s_end = s_begin + ppb;                                   // ppb
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);    // ppb
-  unsigned long long* s_item = reinterpret_cast<unsigned long long*>(bound + 1);   // the item in hand
+  float* s_bias = reinterpret_cast<float*>(s_list + ppb);       // ppb (inner product / stored norms)
+  int* s_nl = reinterpret_cast<int*>(bound + 2);                // how many of them
+  unsigned long long* s_item = reinterpret_cast<unsigned long long*>(bound + 1);
+  const bool lut_at_zero = (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u;
 
   const int tid = threadIdx.x, wave = tid >> 6;
-  const int m_own = tid / TPM, jj = tid % TPM;
-  const int64_t last = ntotal > 0 ? ntotal - 1 : 0;             // clamp for speculative code loads
-#ifdef VS_SCAN_TIMING
-  unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  unsigned long long tprev = clock64();
-#endif
+  const int m_own = tid & (M - 1), jg = tid / M;                // table build: codewords jg * EPL + i of m_own
+  const int rep0 = jg & (REP - 1);                              // this lane's copy (build: the first it stores)
+  const u32 last = ntotal > 0 ? (u32)(ntotal - 1) : 0u;         // clamp for speculative code loads
 
-  // Lane (m_own, jj) owns codewords jj, jj + TPM, ... of sub-quantizer m_own: M codewords
-  // of DSUB floats = D registers, loaded once per workgroup.
-  float T[M * DSUB];
+  float T[EPL * DSUB];
 #pragma unroll
-  for (int i = 0; i < M; ++i)
+  for (int i = 0; i < EPL; ++i)
 #pragma unroll
     for (int u = 0; u < DSUB; ++u)
-      T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jj + TPM * i) * DSUB + u];
+      T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jg * EPL + i) * DSUB + u];
   wait_all_global_loads();   // the codebook is in registers from here on
-  // L2 tables are built as |r|^2 + |t|^2 - 2 <r, t> (Sec. 4.3's decomposition applied to one
-  // sub-vector): per entry DSUB fused multiply-adds on -2 t and one addition, against DSUB
-  // subtractions and DSUB fused multiply-adds for sum (r - t)^2 -- the table build is vector
-  // arithmetic only, and a third to 45 % of it goes away.  Exact for integer data; otherwise the
-  // entry differs from the subtraction form by rounding of the order 1e-7 (|r|^2 + |t|^2).
-  float TN[METRIC == 0 ? M : 1];
-  if (METRIC == 0) {
+  // EXPAND: L2 tables are built as |r|^2 + |t|^2 - 2 <r, t> (Sec. 4.3's expansion applied to one
+  // sub-vector): per entry DSUB fused multiply-adds on -2 t and one addition.  Exact for integer
+  // data; otherwise the entry differs from the subtraction form by rounding of at most
+  // (DSUB + 2) 2^-23 (|r|^2 + |t|^2).
+  float TN[EXPAND ? EPL : 1];
+  if (EXPAND) {
 #pragma unroll
-    for (int i = 0; i < M; ++i) {
+    for (int i = 0; i < EPL; ++i) {
       float tn = 0.f;
 #pragma unroll
       for (int u = 0; u < DSUB; ++u) {
@@ -626,6 +687,16 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
       }
       TN[i] = tn;
     }
+  }
+  // scan role: column byte (4 * column) of every step, four steps per register
+  u32 col[M / 4];
+#pragma unroll
+  for (int w = 0; w < M / 4; ++w) {
+    u32 v = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      v |= (u32)(4 * (((4 * w + b + tid) & (M - 1)) + M * rep0)) << (8 * b);
+    col[w] = v;
   }
 
   // Items are handed out through a counter in memory (*next_item starts at 0), one at a time: the
@@ -647,121 +718,198 @@ __global__ __launch_bounds__(256) void ivfpq_scan_reg_kernel(
     WaveSelect<R> ws;
     ws.init(slots + wave * tot, tot, k, bound);
     if (tid == 0) *bound = KEY_EMPTY;
-    // the item's probes and list extents, fetched in one parallel round
-    for (int p = tid; p < np; p += 256) {
-      const int l = probes[qi * nprobe + p_begin + p];
-      s_list[p] = l >= 0 ? l : 0;
-      s_begin[p] = l >= 0 ? list_off[l] : 0;
-      s_end[p] = l >= 0 ? list_off[l + 1] : 0;
+    // the item's probes and list extents: wavefront 0 fetches them 64 at a time and keeps the
+    // non-empty lists, in probe order
+    if (wave == 0) {
+      int cnt = 0;
+      for (int p0 = 0; p0 < np; p0 += VS_WAVE) {
+        const int p = p0 + tid;
+        const int l = p < np ? probes[qi * nprobe + p_begin + p] : -1;
+        const int64_t b = l >= 0 ? list_off[l] : 0, e = l >= 0 ? list_off[l + 1] : 0;
+        const bool keep = e > b;
+        const u64 mask = __ballot(keep);
+        const int pos = cnt + __popcll(mask & ((1ull << tid) - 1ull));
+        if (keep) {
+          s_list[pos] = l;
+          s_begin[pos] = (u32)b;
+          s_end[pos] = (u32)e;
+          if (METRIC != 0) {
+            float bs = cdist[qi * nprobe + p_begin + p];
+            if (METRIC == 2) bs -= cnorm[l];
+            s_bias[pos] = bs;
+          }
+        }
+        cnt += __popcll(mask);
+      }
+      if (tid == 0) *s_nl = cnt;
     }
-    if (METRIC != 0) {  // one table per query
+    // (the query slice is in registers before the scan's hand-counted loads start: a use here makes
+    // the compiler wait for it now rather than, for everything in flight, inside the scan)
 #pragma unroll
-      for (int i = 0; i < M; ++i) {
+    for (int u = 0; u < DSUB; ++u) asm volatile("" : "+v"(qm[u]));
+    if (METRIC != 0) {  // one table per query, in the first set of columns
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
         float acc = 0.f;
 #pragma unroll
         for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qm[u], T[i * DSUB + u], acc);
-        lut0[m_own * KP + jj + TPM * i] = METRIC == 2 ? -2.f * acc : acc;
+        const float e = METRIC == 2 ? -2.f * acc : acc;
+#pragma unroll
+        for (int c = 0; c < REP; ++c)
+          lut0[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = e;
       }
     }
-    block_sync_lds();   // probes, bound and the IP table are visible
-    TICK(0);
+    block_sync_lds();   // probes, bound and the per-query table are visible
 
-    // Software pipeline over the item's lists (L2 metric): iteration p builds table p into
-    // lut[p & 1] from registers only (query slice, centroid slice, codewords), then -- after
-    // ONE barrier -- scans list p.  The first 256 codes and the centroid slice of list p + 1
-    // are requested at the top of iteration p, a full iteration ahead.  These requests are
-    // unconditional (indices clamped into range; lanes past a list's end are masked when
-    // they are consumed), so the number of loads in flight is the same on every path.
-    CodeWords<M> cw, cw_n;
-    float nrm = 0.f, nrm_n = 0.f;                               // METRIC 2: the code's stored norm
-    int64_t i_cur = 0;
-    bool v_cur = false;
-    float cm[DSUB], cm_n[DSUB];
-#pragma unroll
-    for (int u = 0; u < DSUB; ++u) cm[u] = cm_n[u] = 0.f;
-    if (np > 0) {
-      i_cur = s_begin[0] + tid;
-      v_cur = i_cur < s_end[0];
-      cw.load(codes + min(i_cur, last) * M);
-      if (METRIC == 2) nrm = norms[min(i_cur, last)];
-      if (METRIC == 0) {
-        const int l0 = s_list[0];
-#pragma unroll
-        for (int u = 0; u < DSUB; ++u) cm[u] = centroids[(int64_t)l0 * D + m_own * DSUB + u];
-      }
+    // The chunks of NT codes of the item's non-empty lists form ONE sequence, and the scan is a
+    // stream from HBM whose rate is bounded by what is in flight (bytes in flight = rate x
+    // latency; one chunk ahead per wavefront is 16 KB per CU, about 4 TB/s chip-wide at the
+    // latency measured under load).  So the codes of chunk c + 2 are requested before chunk c is
+    // summed, across list boundaries, into one of three register sets that take turns -- the loop
+    // is unrolled three times so that no set is ever copied (a copy would wait for the load just
+    // issued).  Requests are clamped into the code array; lanes past a list's end are masked when
+    // consumed.  At the first chunk of a list (L2 metric) its table is built into column set
+    // `parity` from registers only (query slice, centroid slice requested one list ahead,
+    // codewords), then ONE barrier, then the list is scanned while the other set's table may
+    // still be in use by a slower wavefront.
+    // Control state is wave-uniform and kept in scalar registers (readfirstlane of the LDS
+    // arrays, touched once per list, not once per chunk): consumer / producer list, the extents
+    // of that list, the first code of the current chunk.
+    const int nl = __builtin_amdgcn_readfirstlane(*s_nl);
+    int pc = 0, pp = 0;
+    u32 cb = 0, ce = 0, pe = 0;
+    if (nl > 0) {
+      cb = __builtin_amdgcn_readfirstlane(s_begin[0]);
+      ce = pe = __builtin_amdgcn_readfirstlane(s_end[0]);
     }
-    TICK(1);
-    for (int p = 0; p < np; ++p) {
-      float* __restrict__ lut = (METRIC == 0 && NBUF == 2) ? lut0 + (p & 1) * (M * KP) : lut0;
-      const int64_t end = s_end[p];
-      // requests for the next iteration (the last iteration re-requests its own list)
-      const int pn = min(p + 1, np - 1);
-      const int64_t i_n = s_begin[pn] + tid;
-      const bool v_n = (p + 1 < np) && (i_n < s_end[pn]);
-      cw_n.load(codes + min(i_n, last) * M);
-      if (METRIC == 2) nrm_n = norms[min(i_n, last)];
-      float bias = 0.f;
-      if (METRIC == 0) {
-        const int l1 = s_list[pn];
-#pragma unroll
-        for (int u = 0; u < DSUB; ++u) cm_n[u] = centroids[(int64_t)l1 * D + m_own * DSUB + u];
-        float r[DSUB];
-#pragma unroll
-        for (int u = 0; u < DSUB; ++u) r[u] = qm[u] - cm[u];
-        if (NBUF == 1 && p > 0) block_sync_lds();   // single table: scan p - 1 finished everywhere
-        float rn = 0.f;
-#pragma unroll
-        for (int u = 0; u < DSUB; ++u) rn = __builtin_fmaf(r[u], r[u], rn);
-#pragma unroll
-        for (int i = 0; i < M; ++i) {
-          float acc = rn + TN[i];
-#pragma unroll
-          for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
-          lut[m_own * KP + jj + TPM * i] = acc;
+    u32 base_c = cb, base_p = cb;
+    // load instructions per request: the code, and its stored norm (METRIC 2)
+    constexpr int NLT = CodeWords<M>::NLOAD + (METRIC == 2 ? 1 : 0);
+    // Always issues exactly NLT loads (past the item's last chunk: of code 0 .. NT - 1, unused),
+    // so that "2 * NLT younger loads" below means the same on every path.
+    auto request = [&](CodeWords<M>& dst, float& nrm_dst) {
+      const u32 i = min(base_p + (u32)tid, last);
+      dst.load_async(codes + (u64)i * M);
+      if (METRIC == 2) asm volatile("global_load_dword %0, %1, off" : "=&v"(nrm_dst) : "v"(norms + i) : "memory");
+      if (pp < nl) {
+        base_p += NT;
+        if (base_p >= pe) {
+          ++pp;
+          base_p = pp < nl ? __builtin_amdgcn_readfirstlane(s_begin[pp]) : 0u;
+          pe = pp < nl ? __builtin_amdgcn_readfirstlane(s_end[pp]) : 0u;
         }
-        TICK(2);
-        block_sync_lds();   // table p visible; scan p - 1 (on the other buffer) finished everywhere
-        TICK(3);
-      } else {
-        bias = cdist[qi * nprobe + p_begin + p];
-        if (METRIC == 2) bias -= cnorm[s_list[p]];
       }
-      // scan list p; the next chunk of a long list is requested before the current one is summed
-      CodeWords<M> cw2;
-      float nrm2 = 0.f;
+    };
+    // centroid slice of the next list to build (L2 tables), hand-issued like the codes: one dword
+    // load per component into a register of its own, so that the wait and the first use (the
+    // residual q - c) are ONE asm statement and nothing can read a component before it has arrived
+    float cn[DSUB];
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) cn[u] = 0.f;
+    auto request_centroid = [&](int pl) {
+      if (METRIC == 0 && pl < nl) {
+        const float* src = centroids + (int64_t)__builtin_amdgcn_readfirstlane(s_list[pl]) * D + m_own * DSUB;
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u)
+          asm volatile("global_load_dword %0, %1, off" : "=&v"(cn[u]) : "v"(src + u) : "memory");
+      }
+    };
+    CodeWords<M> S0, S1, S2;
+    float n0 = 0.f, n1 = 0.f, n2 = 0.f;                         // METRIC 2: the codes' stored norms
+    int parity = 0;
+    float bias = 0.f;
+    auto consume = [&](CodeWords<M>& cw, float& nrm) {
+      // this chunk's code was requested two requests ago: everything but the 2 * NLT youngest
+      // loads has arrived once this returns
+      cw.template wait_newer<2 * NLT>();
+      if (METRIC == 2) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(nrm) : "n"(2 * NLT) : "memory");
+      if (base_c == cb) {                                       // (uniform) first chunk of list pc
+        ws.refresh_shared();
+        if (METRIC == 0) {
+          // the slice was requested at the first chunk of the list before (or in the prologue):
+          // only this step's request is younger.  r = q - c, one fp32 subtraction per component.
+          float r[DSUB];
+          asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NLT) : "memory");
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u)
+            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qm[u]), "v"(cn[u]), "n"(NLT) : "memory");
+          request_centroid(pc + 1);                             // one list ahead
+          float rn = 0.f;
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u) rn = __builtin_fmaf(r[u], r[u], rn);
+#pragma unroll
+          for (int w = 0; w < M / 4; ++w)   // this list's column set: + 32 floats = bit 7 of every column byte
+            col[w] = (col[w] & 0x7f7f7f7fu) | (parity ? 0x80808080u : 0u);
+          float* __restrict__ lutp = lut0 + 32 * parity;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) {
+            float acc;
+            if (EXPAND) {
+              acc = rn + TN[i];
+#pragma unroll
+              for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
+            } else {
+              acc = 0.f;
+#pragma unroll
+              for (int u = 0; u < DSUB; ++u) {
+                const float diff = r[u] - T[i * DSUB + u];
+                acc = __builtin_fmaf(diff, diff, acc);
+              }
+            }
+#pragma unroll
+            for (int c = 0; c < REP; ++c)
+              lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = acc;
+          }
+          parity ^= 1;
+          block_sync_lds();   // this table is visible; the scan on the other column set has finished everywhere
+        } else {
+          bias = s_bias[pc];
+        }
+      }
+      const u32 i = base_c + (u32)tid;
+      const bool valid = i < ce;
+      float dist = 0.f;
+      if (valid) {
+        const float d0 = METRIC == 2 ? bias + nrm : bias;
+        dist = lut_at_zero ? cw.template adc_banked<true>(smem, col, d0)
+                           : cw.template adc_banked<false>(smem, col, d0);
+      }
+      if (METRIC != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
+      ws.push_cached(valid, make_key(dist, i, KEY_METRIC));
+      base_c += NT;
+      if (base_c >= ce) {
+        ++pc;
+        if (pc < nl) {
+          cb = base_c = __builtin_amdgcn_readfirstlane(s_begin[pc]);
+          ce = __builtin_amdgcn_readfirstlane(s_end[pc]);
+        }
+      }
+    };
+    if (nl > 0) {   // (uniform; ntotal > 0 here)
+      request_centroid(pc);
+      request(S0, n0);
+      request(S1, n1);
       for (;;) {
-        const int64_t i2 = i_cur + 256;
-        const bool more = i2 - tid < end;      // uniform: i2 - tid is the next chunk's base
-        const bool v2 = i2 < end;
-        if (more) {
-          cw2.load(codes + min(i2, last) * M);
-          if (METRIC == 2) nrm2 = norms[min(i2, last)];
-        }
-        float dist = v_cur ? cw.template adc_rows<KP>(lut, METRIC == 2 ? bias + nrm : bias) : 0.f;
-        if (METRIC != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
-        ws.push(v_cur, make_key(dist, (u32)i_cur, KEY_METRIC), true);
-        if (!more) break;
-        cw = cw2; nrm = nrm2; i_cur = i2; v_cur = v2;
+        request(S2, n2); consume(S0, n0);
+        if (pc >= nl) break;
+        request(S0, n0); consume(S1, n1);
+        if (pc >= nl) break;
+        request(S1, n1); consume(S2, n2);
+        if (pc >= nl) break;
       }
-      cw = cw_n; nrm = nrm_n; i_cur = i_n; v_cur = v_n;
+      // The last two requests are still in flight.  They must land while their registers still
+      // belong to them: once the sets are dead the compiler hands the registers to other values
+      // (addresses of the result stores below), and a load arriving then would overwrite those.
+      S0.drain(); S1.drain(); S2.drain();
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(n0), "+v"(n1), "+v"(n2) : : "memory");
 #pragma unroll
-      for (int u = 0; u < DSUB; ++u) cm[u] = cm_n[u];
-      TICK(4);
+      for (int u = 0; u < DSUB; ++u) asm volatile("s_waitcnt vmcnt(0)" : "+v"(cn[u]) : : "memory");
     }
     ws.finish();
     block_sync_lds();
-    TICK(5);
-    block_rank_merge(slots, tot, 4, k, sink, item * k);
+    block_rank_merge(slots, tot, NW, k, sink, item * k);
     block_sync_lds();   // the slots have been read; the next item may reset them
-    TICK(6);
-#ifdef VS_SCAN_TIMING
-    if (tid == 0) { tacc[7] += ws.trim_cycles; }
-#endif
   }
-#ifdef VS_SCAN_TIMING
-  if (tid == 0)
-    for (int t = 0; t < 8; ++t) atomicAdd(&g_scan_cycles[t], tacc[t]);
-#endif
 }
 
 // One wavefront per query: k best of the nsplit partial lists, then
@@ -800,6 +948,25 @@ __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__
 
 // ------------------------------------------------------------------ launchers
 
+// Shapes served by ivfpq_scan_bank_kernel; an index of such a shape stores its codes rotated.
+bool ivfpq_codes_rotated(const IvfpqDims& g) {
+  return g.nbits == 8 && ((g.M == 16 && g.dsub == 8) || (g.M == 32 && g.dsub == 3) || (g.M == 8 && g.dsub == 4));
+}
+constexpr int kBankThreads = 256;   // 4 wavefronts per workgroup, two workgroups per CU
+static size_t bank_scan_lds_bytes(int tot, int ppb) {
+  return (size_t)kBankTableBytes + (size_t)((kBankThreads / 64) * tot + 2) * sizeof(u64) + (size_t)ppb * 16 + 24;
+}
+// Selection slots per wavefront for the bank kernel: as for the other kernels (a power of two >=
+// k + 64) unless a multiple of 32 between k + 64 and that lets two workgroups share a CU's LDS.
+static int bank_slots_for_k(int k, int ppb) {
+  const int tot = select_slots_for_k(k);
+  if (tot > 256) return tot;                               // sorted through LDS: powers of two only
+  if (2 * bank_scan_lds_bytes(tot, ppb) <= 160 * 1024) return tot;
+  for (int t = tot - 32; t >= k + 64; t -= 32)
+    if (2 * bank_scan_lds_bytes(t, ppb) <= 160 * 1024) return t;
+  return tot;
+}
+
 void launch_pq_encode(const IvfpqDims& g, const float* x, int64_t n, const int32_t* list_of,
                       const float* centroids, const float* codebooks, uint8_t* tmp_codes,
                       hipStream_t st) {
@@ -830,8 +997,9 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
                      const float* old_norms, int64_t old_total, const int64_t* old_off,
                      const int64_t* new_off, const uint8_t* tmp_codes,
                      const int64_t* new_ids_or_null, int64_t id_base, const float* tmp_norms,
-                     const int64_t* dest, int64_t n_new, uint8_t* codes, int64_t* ids, float* norms,
-                     hipStream_t st) {
+                     const int64_t* dest, const int32_t* new_list_of, int64_t n_new, uint8_t* codes,
+                     int64_t* ids, float* norms, hipStream_t st) {
+  // (old entries keep their position inside their list, hence their rotation)
   if (old_total > 0)
     hipLaunchKernelGGL(move_old_kernel, dim3((unsigned)((old_total + 255) / 256)), dim3(256), 0, st,
                        old_codes, old_ids, old_norms, old_total, old_off, new_off, g.nlist,
@@ -839,7 +1007,15 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
   if (n_new > 0)
     hipLaunchKernelGGL(scatter_new_kernel, dim3((unsigned)((n_new + 255) / 256)), dim3(256), 0, st,
                        tmp_codes, new_ids_or_null, id_base, tmp_norms, dest, n_new, g.M, g.nbits,
-                       g.code_size, codes, ids, norms);
+                       g.code_size, ivfpq_codes_rotated(g) ? g.M : 0, new_list_of, new_off, codes, ids,
+                       norms);
+}
+
+void launch_codes_canonical(const IvfpqDims& g, const uint8_t* stored, const int64_t* off,
+                            int64_t total, uint8_t* out, hipStream_t st) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(unrotate_codes_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     stored, off, g.nlist, total, g.M, out);
 }
 
 void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
@@ -867,47 +1043,44 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
                      nlist, sizes);
 }
 
-template <int M, int DSUB, int METRIC, int R, int NBUF>
-static void launch_scan_reg(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
-                            const float* codebooks, const int32_t* probes, const float* cdist,
-                            int nprobe, int ppb, int nsplit, const int64_t* list_off,
-                            const uint8_t* codes, const float* norms, const float* cnorm,
-                            int64_t ntotal, int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
-  const size_t shmem = (size_t)(4 * tot + 2) * sizeof(u64) + (size_t)NBUF * M * (256 + 256 / M) * sizeof(float) +
-                       (size_t)ppb * 20 + 16;
-  auto kern = &ivfpq_scan_reg_kernel<M, DSUB, METRIC, R, NBUF>;
+template <int M, int DSUB, int METRIC, int R>
+static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                             const float* codebooks, const int32_t* probes, const float* cdist,
+                             int nprobe, int ppb, int nsplit, const int64_t* list_off,
+                             const uint8_t* codes, const float* norms, const float* cnorm,
+                             int64_t ntotal, int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
+  const size_t shmem = bank_scan_lds_bytes(tot, ppb);
+  constexpr int NT = kBankThreads;
+  auto kern = &ivfpq_scan_bank_kernel<M, DSUB, METRIC, R, NT>;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   const int64_t nitems = nq * nsplit;
   // persistent workgroups: as many as are resident at once on the 256 CUs, each walks over items
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, shmem) != hipSuccess || per_cu < 1)
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NT, shmem) != hipSuccess || per_cu < 1)
     per_cu = 1;
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
   launch_fill_u64(counter, 1, 0ull, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), shmem, st, q, centroids, codebooks,
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), shmem, st, q, centroids, codebooks,
                      probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, ntotal,
                      k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
 }
 
 template <int M, int DSUB>
-static void launch_scan_reg_any(const IvfpqDims& g, const float* q, int64_t nq,
-                                const float* centroids, const float* codebooks,
-                                const int32_t* probes, const float* cdist, int nprobe, int ppb,
-                                int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                const float* norms, const float* cnorm, int mode, int64_t ntotal,
-                                int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
-#define GO(MET, RR, NB)                                                                           \
-  launch_scan_reg<M, DSUB, MET, RR, NB>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
-                                        nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, counter, st)
-  const int r = select_regs_for_slots(tot);
-  // L2 tables alternate between two buffers (one barrier per list); the single inner-product
-  // table needs one.  A single L2 table with a third resident workgroup per CU measured
-  // slower at 1500-code lists: the 168-register budget it needs spills the codebook.
-  if (mode == 1)      { if (r == 2) GO(1, 2, 1); else if (r == 4) GO(1, 4, 1); else GO(1, 0, 1); }
-  else if (mode == 2) { if (r == 2) GO(2, 2, 1); else if (r == 4) GO(2, 4, 1); else GO(2, 0, 1); }
-  else                { if (r == 2) GO(0, 2, 2); else if (r == 4) GO(0, 4, 2); else GO(0, 0, 2); }
+static void launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
+                                 const float* centroids, const float* codebooks,
+                                 const int32_t* probes, const float* cdist, int nprobe, int ppb,
+                                 int nsplit, const int64_t* list_off, const uint8_t* codes,
+                                 const float* norms, const float* cnorm, int mode, int64_t ntotal,
+                                 int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
+#define GO(MET, RR)                                                                               \
+  launch_scan_bank<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,  \
+                                     nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, counter, st)
+  const int r = tot <= 128 ? 2 : (tot <= 256 ? 4 : 0);   // register-sort width covering the slots
+  if (mode == 1)      { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
+  else if (mode == 2) { if (r == 2) GO(2, 2); else if (r == 4) GO(2, 4); else GO(2, 0); }
+  else                { if (r == 2) GO(0, 2); else if (r == 4) GO(0, 4); else GO(0, 0); }
 #undef GO
 }
 
@@ -962,18 +1135,21 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)(g.d + 2) * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
-  const size_t reg_shmem = shmem + (size_t)g.M * g.K * sizeof(float) + 2 * 256 * sizeof(float) +
-                           (size_t)ppb * 20 + 32;   // two tables, their rows padded
-#define REG(MM, DS)                                                                              \
-  if (g.nbits == 8 && g.M == MM && g.dsub == DS && reg_shmem <= 160 * 1024) {                    \
-    launch_scan_reg_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, tot, sink, counter, st); \
-    return 0;                                                                                    \
+  if (ivfpq_codes_rotated(g)) {   // (the stored codes are rotated: no other kernel reads them)
+    const int btot = bank_slots_for_k(k, ppb);
+    if (bank_scan_lds_bytes(btot, ppb) > 160 * 1024) return -1;
+#define BANK(MM, DS)                                                                              \
+  if (g.M == MM && g.dsub == DS) {                                                                \
+    launch_scan_bank_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
+                                 nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, btot, sink, counter, st); \
+    return 0;                                                                                     \
   }
-  REG(16, 8)   // PQ16x8 on d = 128
-  REG(32, 3)   // PQ32x8 on d = 96
-  REG(8, 4)    // PQ8x8 on d = 32
-#undef REG
+    BANK(16, 8)   // PQ16x8 on d = 128
+    BANK(32, 3)   // PQ32x8 on d = 96
+    BANK(8, 4)    // PQ8x8 on d = 32
+#undef BANK
+    return -1;
+  }
   const int r = select_regs_for_slots(tot);
   // codes of 16, 32 or 64 bytes: the software-pipelined kernel
   const size_t pipe_shmem = shmem + sizeof(float) + (size_t)ppb * 20 + 24;
@@ -1002,14 +1178,6 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   return 0;
 }
 
-#ifdef VS_SCAN_TIMING
-extern "C" __attribute__((visibility("default"))) int vs_debug_scan_cycles(unsigned long long* out8) {
-  unsigned long long zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_scan_cycles), sizeof(zero)) != hipSuccess) return -1;
-  if (hipMemcpyToSymbol(HIP_SYMBOL(g_scan_cycles), zero, sizeof(zero)) != hipSuccess) return -1;
-  return 0;
-}
-#endif
 
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {

@@ -286,7 +286,10 @@ def test_queries_equal_or_close_to_decoded_vectors(vs, oracle, name):
         D, I = ix.search(dev(q), k, nprobe)
         D, I = host(D), host(I)
         assert (D >= 0).all(), "negative squared distance %r" % float(D.min())
-        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        # (this synthetic set holds runs of vectors with one and the same code: they tie exactly in
+        # the oracle and within rounding on the GPU, whose summation order depends on the position
+        # in the list -- enough oracle ranks are asked for to hold every such run)
+        Do, Io = orc.search(q, k + 400, nprobe)
         _, co = oracle.coarse_probe(q, orc.centroids, nprobe, L2)
         tc, te = l2_table_cancel(co, orc.codebooks)
         check_search(D, I, Do, Io, L2, cancel=tc, cancel_eps=te)
