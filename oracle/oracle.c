@@ -354,7 +354,14 @@ void or_pq_norms(const uint8_t *codes, int64_t n, int d, const int32_t *list_of,
  *   - 2 <q, x'> with the norm stored next to the code, norms[s] from or_pq_norms):
  *   ((||q||^2 - 2 <q, c_l>) + norm) + sum_m (-2 <q_m, T_m[c_m]>) in fp32, m ascending,
  *   every inner product a canon_ip chain.
- * forms 1 and 2 exist to pin the compressed-domain identities against form 0; parity
+ * form 3 (L2 only; Sec. 4.3 "Compressed-domain search": the table of a (query, list) pair
+ *   split into a term that depends on the query alone and one that depends on the list alone,
+ *   the latter computed once when the index is built):
+ *   |q_m - c_m - t|^2 = |q_m - c_m|^2 + (-2 <q_m, t>) + (|t|^2 + 2 <c_m, t>), hence
+ *   LUT_m[j] = A_m[j] + B_{l,m}[j] with A_m[j] = -2 canon_ip(q_m, T_m[j]) (per query) and
+ *   B_{l,m}[j] = fma(2, canon_ip(c_{l,m}, T_m[j]), canon_ip(T_m[j], T_m[j])) (per list), and the
+ *   distance is canon_l2(q, c_l) + sum_m LUT_m[c_m] in fp32, m ascending.
+ * forms 1 to 3 exist to pin the compressed-domain identities against form 0; parity
  * tests of the GPU path use form 0.
  *
  * nscanned[a] (may be NULL) receives the number of codes visited for query a.
@@ -390,6 +397,16 @@ void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
         for (int m = 0; m < M; ++m)
           for (int j = 0; j < K; ++j)
             lut[m * K + j] = -2.0f * or_canon_ip(qa + m * dsub, codebooks + ((int64_t)m * K + j) * dsub, dsub);
+      }
+      if (form == 3) {   /* per-query term + per-list term; both rebuilt here per pair for plainness */
+        bias = or_canon_l2(qa, c, d);
+        for (int m = 0; m < M; ++m)
+          for (int j = 0; j < K; ++j) {
+            const float *T = codebooks + ((int64_t)m * K + j) * dsub;
+            const float a_mj = -2.0f * or_canon_ip(qa + m * dsub, T, dsub);
+            const float b_mj = fmaf(2.0f, or_canon_ip(c + m * dsub, T, dsub), or_canon_ip(T, T, dsub));
+            lut[m * K + j] = a_mj + b_mj;
+          }
       }
       if (form == 1) {
         if (metric == OR_METRIC_L2) {

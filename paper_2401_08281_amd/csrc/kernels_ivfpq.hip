@@ -639,8 +639,9 @@ void ivfpq_scan_bank_kernel(
   constexpr int REP = 32 / M;     // copies of every table
   constexpr int NW = NT / 64;     // wavefronts of the workgroup (two workgroups share a CU)
   constexpr int EPL = K * M / NT; // table entries a lane builds = codewords it keeps
-  // EXPAND: L2 table entries as |r|^2 + |t|^2 - 2 <r, t> (|t|^2 in registers, DSUB + 1 instructions
-  // per entry) rather than as sum (r - t)^2 (2 DSUB instructions)
+  // EXPAND: an L2 table entry holds |t|^2 - 2 <r_m, t> (|t|^2 in registers, DSUB instructions per
+  // entry) rather than sum (r_m - t)^2 (2 DSUB instructions); the missing sum_m |r_m|^2 = |q - c_l|^2
+  // is the coarse distance of the probe, which starts every code's sum
   constexpr bool EXPAND = METRIC == 0;
   static_assert(NT == 256 || NT == 512, "two workgroups per CU");
   static_assert(M == 8 || M == 16 || M == 32, "tables of M sub-quantizers fill 32 banks in 32 / M copies");
@@ -662,7 +663,6 @@ void ivfpq_scan_bank_kernel(
   const int tid = threadIdx.x, wave = tid >> 6;
   const int m_own = tid & (M - 1), jg = tid / M;                // table build: codewords jg * EPL + i of m_own
   const int rep0 = jg & (REP - 1);                              // this lane's copy (build: the first it stores)
-  const u32 last = ntotal > 0 ? (u32)(ntotal - 1) : 0u;         // clamp for speculative code loads
 
   float T[EPL * DSUB];
 #pragma unroll
@@ -671,9 +671,9 @@ void ivfpq_scan_bank_kernel(
     for (int u = 0; u < DSUB; ++u)
       T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jg * EPL + i) * DSUB + u];
   wait_all_global_loads();   // the codebook is in registers from here on
-  // EXPAND: L2 tables are built as |r|^2 + |t|^2 - 2 <r, t> (Sec. 4.3's expansion applied to one
-  // sub-vector): per entry DSUB fused multiply-adds on -2 t and one addition.  Exact for integer
-  // data; otherwise the entry differs from the subtraction form by rounding of at most
+  // EXPAND: |r - t|^2 = |r|^2 + |t|^2 - 2 <r, t> (Sec. 4.3's expansion applied to one sub-vector):
+  // per entry DSUB fused multiply-adds on -2 t starting from |t|^2.  Exact for integer data;
+  // otherwise a distance differs from the subtraction form by rounding of at most
   // (DSUB + 2) 2^-23 (|r|^2 + |t|^2).
   float TN[EXPAND ? EPL : 1];
   if (EXPAND) {
@@ -733,11 +733,9 @@ void ivfpq_scan_bank_kernel(
           s_list[pos] = l;
           s_begin[pos] = (u32)b;
           s_end[pos] = (u32)e;
-          if (METRIC != 0) {
-            float bs = cdist[qi * nprobe + p_begin + p];
-            if (METRIC == 2) bs -= cnorm[l];
-            s_bias[pos] = bs;
-          }
+          float bs = cdist[qi * nprobe + p_begin + p];   // L2 tables: |q - c_l|^2 = sum_m |r_m|^2, see EXPAND
+          if (METRIC == 2) bs -= cnorm[l];
+          s_bias[pos] = bs;
         }
         cnt += __popcll(mask);
       }
@@ -785,10 +783,13 @@ void ivfpq_scan_bank_kernel(
     u32 base_c = cb, base_p = cb;
     // load instructions per request: the code, and its stored norm (METRIC 2)
     constexpr int NLT = CodeWords<M>::NLOAD + (METRIC == 2 ? 1 : 0);
-    // Always issues exactly NLT loads (past the item's last chunk: of code 0 .. NT - 1, unused),
+    // Always issues exactly NLT loads (past the item's last chunk: of code 0, unused),
     // so that "2 * NLT younger loads" below means the same on every path.
     auto request = [&](CodeWords<M>& dst, float& nrm_dst) {
-      const u32 i = min(base_p + (u32)tid, last);
+      // lanes past the list's end fetch the chunk's first code again (one cache line the wavefront
+      // reads anyway) instead of the next list's codes: a list's last chunk is half empty on average
+      const u32 iv = base_p + (u32)tid;
+      const u32 i = iv < pe ? iv : base_p;
       dst.load_async(codes + (u64)i * M);
       if (METRIC == 2) asm volatile("global_load_dword %0, %1, off" : "=&v"(nrm_dst) : "v"(norms + i) : "memory");
       if (pp < nl) {
@@ -834,9 +835,6 @@ void ivfpq_scan_bank_kernel(
           for (int u = 0; u < DSUB; ++u)
             asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qm[u]), "v"(cn[u]), "n"(NLT) : "memory");
           request_centroid(pc + 1);                             // one list ahead
-          float rn = 0.f;
-#pragma unroll
-          for (int u = 0; u < DSUB; ++u) rn = __builtin_fmaf(r[u], r[u], rn);
 #pragma unroll
           for (int w = 0; w < M / 4; ++w)   // this list's column set: + 32 floats = bit 7 of every column byte
             col[w] = (col[w] & 0x7f7f7f7fu) | (parity ? 0x80808080u : 0u);
@@ -845,7 +843,7 @@ void ivfpq_scan_bank_kernel(
           for (int i = 0; i < EPL; ++i) {
             float acc;
             if (EXPAND) {
-              acc = rn + TN[i];
+              acc = TN[i];
 #pragma unroll
               for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
             } else {
@@ -862,9 +860,8 @@ void ivfpq_scan_bank_kernel(
           }
           parity ^= 1;
           block_sync_lds();   // this table is visible; the scan on the other column set has finished everywhere
-        } else {
-          bias = s_bias[pc];
         }
+        bias = s_bias[pc];
       }
       const u32 i = base_c + (u32)tid;
       const bool valid = i < ce;

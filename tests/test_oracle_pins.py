@@ -355,6 +355,30 @@ def test_adc_equals_distance_to_decoded_vector(oracle, metric, nbits):
     assert (I1 == I0).mean() > 0.98
 
 
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_split_tables_form_equals_the_definition(oracle, nbits):
+    # Sec. 4.3: the (query, list) table is the sum of a per-query and a per-list term plus the
+    # coarse distance.  Against form 0 (distance to the decoded vector in float64) within the
+    # rounding of the cancelling terms |q|^2 + |c|^2 + |t|^2, and exactly on integer data.
+    cfg, x, q, ix = _c1_index(oracle, L2, nbits, nb=2000, nq=30)
+    D0, I0 = ix.search(q, 10, 5, form=0)
+    D3, I3 = ix.search(q, 10, 5, form=3)
+    scale = (q.astype(np.float64) ** 2).sum(1, keepdims=True) + float((ix.centroids.astype(np.float64) ** 2).sum(1).max()) + 10.0
+    assert (np.abs(D3.astype(np.float64) - D0) <= 1e-6 * scale).all()
+    assert (I3 == I0).mean() > 0.98
+    rng = np.random.default_rng(31)
+    xi = rng.integers(-12, 13, size=(1500, 8)).astype(np.float32)
+    qi = rng.integers(-12, 13, size=(20, 8)).astype(np.float32)
+    cent = xi[:6].copy()
+    cb = rng.integers(-6, 7, size=(4, 1 << nbits, 2)).astype(np.float32)
+    io = oracle.OracleIVFPQ(8, L2, cent, cb, nbits)
+    io.add(xi)
+    Da, Ia = io.search(qi, 7, 3, form=0)
+    Db, Ib = io.search(qi, 7, 3, form=3)
+    np.testing.assert_array_equal(Da, Db)          # integers: every term is exact in fp32
+    np.testing.assert_array_equal(Ia, Ib)
+
+
 def test_exact_codes_and_all_probes_reproduce_flat_search(oracle):
     rng = np.random.default_rng(17)
     cent, cb, lists, codes, x = _exact_code_case(rng, 9, 6, 256, 3, 1500)
