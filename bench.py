@@ -67,10 +67,12 @@ def main():
                     help="train the coarse centroids and the PQ codebooks with NITER rounds of k-means "
                          "(vs_ivfpq_train, from the sampled parameters, on the first min(nb, 256 * nlist) "
                          "vectors) before building the index; reported under config.train")
-    ap.add_argument("--search-type", default="tables", choices=["tables", "norms"],
+    ap.add_argument("--search-type", default="tables", choices=["tables", "norms", "precomputed"],
                     help="tables (default, the headline form): one look-up table per (query, list) on the "
                          "residual; norms: |q|^2 + |x'|^2 - 2<q,x'> with the norm stored next to every code "
-                         "(4 more bytes per vector, one table per query)")
+                         "(4 more bytes per vector, one table per query); precomputed: the table of a "
+                         "(query, list) pair as a per-query term plus a per-list term computed at set-up "
+                         "(nlist * M * 2^nbits floats), one addition per entry instead of d / M multiply-adds")
     ap.add_argument("--index", default="ivfpq", choices=["ivfpq", "ivfflat", "ivfsq8"],
                     help="ivfflat: the same workload's vectors and centroids in an IVF-Flat index "
                          "(secondary line; the default ivfpq is the headline metric)")
@@ -149,6 +151,8 @@ def main():
                   cfg["nbits"])
     if args.search_type == "norms":
         ix.set_search_type(vs.ST_STORED_NORMS)
+    if args.search_type == "precomputed":
+        ix.set_search_type(vs.ST_PRECOMPUTED_TABLES)
     torch.cuda.synchronize()
     t0 = time.time()
     piece = 10_000_000
@@ -237,7 +241,7 @@ def main():
         cpu = cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe)
 
     traffic = load_traffic("ivfpq_scan_%s_nprobe%d%s" % (
-        args.workload, nprobe, "" if args.search_type == "tables" else "_norms"))
+        args.workload, nprobe, "" if args.search_type == "tables" else "_" + args.search_type))
     out = {
         "metric": "IVF-PQ queries/sec at fixed nprobe & recall@10; ADC-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

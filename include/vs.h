@@ -276,8 +276,18 @@ VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32
  * the rounding of the cancelling terms, about 2^-22 (|q|^2 + |x'|^2).
  * Set it before the first add: vs_ivfpq_add computes the norms only while it is selected
  * (an index that already holds vectors without norms refuses VS_ST_STORED_NORMS).
+ * VS_ST_PRECOMPUTED_TABLES (L2 only): the same table per (query, probed list) as the default,
+ * but formed as the sum of a term that depends on the query alone, -2 <q_m, T_m[j]> (computed
+ * once per query), and a term that depends on the list alone, |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>
+ * (computed once, when this type is first selected: nlist * M * 2^nbits floats of device memory,
+ * 64 MB for nlist = 4096, M = 16), plus the probe's coarse distance |q - c_l|^2: one addition per
+ * table entry and list instead of d / M multiply-adds, which is what pays when lists hold a few
+ * hundred codes and the tables cost more than the scan.  Results differ from the default form by
+ * rounding of the cancelling terms, at most about 2^-21 (|q|^2 + |c_l|^2 + |x' - c_l|^2).  Can be
+ * selected at any time.  VS_ERR_UNSUPPORTED for shapes without a specialised scan kernel (other
+ * than 8-bit codes with M x d/M = 8 x 4, 16 x 8, 32 x 3), VS_ERR_OOM if the tables do not fit.
  */
-enum { VS_ST_RESIDUAL_TABLES = 0, VS_ST_STORED_NORMS = 1 };
+enum { VS_ST_RESIDUAL_TABLES = 0, VS_ST_STORED_NORMS = 1, VS_ST_PRECOMPUTED_TABLES = 2 };
 VS_API int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type);
 /* the stored norms, in storage order: DEVICE [ntotal] fp32 */
 VS_API int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream);

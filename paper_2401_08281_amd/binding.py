@@ -395,7 +395,7 @@ def vs_ivfpq_coarse(h, q, nprobe, nlist):
     return probes, cdist
 
 
-ST_RESIDUAL_TABLES, ST_STORED_NORMS = 0, 1
+ST_RESIDUAL_TABLES, ST_STORED_NORMS, ST_PRECOMPUTED_TABLES = 0, 1, 2
 
 
 def vs_ivfpq_set_search_type(h, search_type):

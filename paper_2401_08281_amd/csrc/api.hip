@@ -281,6 +281,7 @@ struct vs_ivfpq {
   int64_t* ids = nullptr;       // [ntotal]
   float* norms = nullptr;       // [ntotal] squared norms of the decoded vectors, search_type 1 only
   float* cnorm = nullptr;       // [nlist] squared norms of the centroids (IVF-PQ only)
+  float* list_tables = nullptr; // [nlist, K, M] per-list terms of the split tables (search type 2, once computed)
   int search_type = VS_ST_RESIDUAL_TABLES;
   int64_t* list_off = nullptr;  // device [nlist + 1]
   std::vector<int64_t> h_off;   // host copy
@@ -794,6 +795,7 @@ static void ivf_free_device_memory(vs_ivfpq* ix) {
   if (ix->ids) (void)hipFree(ix->ids);
   if (ix->norms) (void)hipFree(ix->norms);
   if (ix->cnorm) (void)hipFree(ix->cnorm);
+  if (ix->list_tables) (void)hipFree(ix->list_tables);
   if (ix->plane_mem) (void)hipFree(ix->plane_mem);
   ix->scratch.release();
 }
@@ -945,13 +947,28 @@ int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* ids, vo
 
 int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type) {
   if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: index is null");
-  if (search_type != VS_ST_RESIDUAL_TABLES && search_type != VS_ST_STORED_NORMS)
+  if (search_type != VS_ST_RESIDUAL_TABLES && search_type != VS_ST_STORED_NORMS &&
+      search_type != VS_ST_PRECOMPUTED_TABLES)
     return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: unknown search type %d", search_type);
-  if (search_type == VS_ST_STORED_NORMS && ix->g.metric != VS_METRIC_L2)
-    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: stored norms serve the L2 metric only");
+  if (search_type != VS_ST_RESIDUAL_TABLES && ix->g.metric != VS_METRIC_L2)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: stored norms and precomputed tables serve the L2 metric only");
   if (ix->ntotal > 0 && search_type == VS_ST_STORED_NORMS && !ix->norms)
     return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: the index already holds vectors without norms");
-  ix->search_type = search_type;   // norms already stored are kept, so one can switch back and forth
+  if (search_type == VS_ST_PRECOMPUTED_TABLES && !ix->list_tables) {
+    const IvfpqDims& g = ix->g;
+    if (!ivfpq_codes_rotated(g))
+      return fail(VS_ERR_UNSUPPORTED, "vs_ivfpq_set_search_type: precomputed tables exist for 8-bit codes of "
+                  "8 x 4, 16 x 8 and 32 x 3 dimensions only (M = %d, d / M = %d, nbits = %d)", g.M, g.dsub, g.nbits);
+    // one table of M * K floats per list (the centroids and codebooks never change after create)
+    float* t = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&t), (size_t)g.nlist * g.K * g.M * sizeof(float)));
+    launch_pq_list_tables(g, ix->centroids, ix->codebooks, t, nullptr);
+    hipError_t e = hipStreamSynchronize(nullptr);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) { (void)hipFree(t); return fail(VS_ERR_DEVICE, "vs_ivfpq_set_search_type: %s", hipGetErrorString(e)); }
+    ix->list_tables = t;
+  }
+  ix->search_type = search_type;   // norms and tables already stored are kept, so one can switch back and forth
   return VS_OK;
 }
 
@@ -998,7 +1015,8 @@ namespace {
 struct SearchLayout {
   int npr = 0, nsplit = 1;
   KnnPlan plan;
-  size_t o_knn = 0, o_pr = 0, o_cd = 0, o_part = 0, o_cnt = 0, bytes = 0;
+  size_t o_knn = 0, o_pr = 0, o_cd = 0, o_part = 0, o_cnt = 0, o_qt = 0, bytes = 0;
+  bool query_tables = false;
 };
 void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayout* out) {
   SearchLayout& L = *out;
@@ -1015,6 +1033,11 @@ void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayo
   L.o_cd = cv.take((size_t)nq * L.npr * sizeof(float));
   L.o_part = cv.take((size_t)nq * L.nsplit * k * sizeof(u64));
   L.o_cnt = cv.take(sizeof(u64));
+  // (every table form but the residual tables: inner product, stored norms, precomputed tables)
+  L.query_tables = ivfpq_wave_scan_applies(g, ix->ntotal) &&
+                   (g.metric == VS_METRIC_IP || (ix->search_type == VS_ST_STORED_NORMS && ix->norms) ||
+                    (ix->search_type == VS_ST_PRECOMPUTED_TABLES && ix->list_tables));
+  if (L.query_tables) L.o_qt = cv.take(ivfpq_query_table_bytes(g, nq));
   L.bytes = cv.off;
 }
 
@@ -1040,11 +1063,15 @@ int search_run(const char* who, const vs_ivfpq* ix, const SearchLayout& L, char*
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
   // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
+  const bool split = ix->search_type == VS_ST_PRECOMPUTED_TABLES && ix->list_tables;
   {
     StageTimer t(timed ? VS_STAGE_SCAN : -1, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, L.npr, L.nsplit,
                           ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->cnorm,
-                          ix->ntotal, k, partial, counter, ix->ids, out_dist, out_ids, st) != 0)
+                          split ? ix->list_tables : nullptr,
+                          L.query_tables ? reinterpret_cast<float*>(base + L.o_qt) : nullptr, ix->ntotal, k,
+                          partial, counter, ix->ids,
+                          out_dist, out_ids, st) != 0)
       return fail(VS_ERR_UNSUPPORTED, "%s: look-up tables of M * 2^nbits = %d floats plus selection state for k = %d exceed the LDS", who, g.M * g.K, k);
   }
   if (L.nsplit > 1) {

@@ -73,8 +73,18 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
-                      u64* counter, const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
+                      const float* norms, const float* cnorm, const float* list_tables,
+                      float* query_tables, int64_t ntotal, int k, u64* partial, u64* counter,
+                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
+// The wavefront-private scan (one wavefront per (query, probe split); every table form but the
+// residual tables) is used while the mean list is at most this long; it needs query_tables:
+// ivfpq_query_table_bytes() of device work space.
+constexpr int kWaveScanMaxMeanList = 1024;
+bool ivfpq_wave_scan_applies(const IvfpqDims& g, int64_t ntotal);
+size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq);
+// out [nlist][K][M]: |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>, the per-list term of the split look-up tables
+void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
+                           hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 

@@ -173,6 +173,23 @@ __global__ void unrotate_codes_kernel(const uint8_t* __restrict__ stored, const 
   for (int b = 0; b < M; ++b) out[s * M + ((b + shift) & (M - 1))] = stored[s * M + b];
 }
 
+// Per-list term of the split look-up tables (Sec. 4.3 "Compressed-domain search"):
+// B[l][j][m] = |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>, inner products as fma chains in dimension order.
+// One lane per entry; layout [nlist][K][M] (the M entries of a codeword number are adjacent, as
+// the scan kernel's table rows are).
+__global__ void pq_list_tables_kernel(const float* __restrict__ centroids, const float* __restrict__ codebooks,
+                                      int nlist, int d, int M, int K, int dsub, float* __restrict__ out) {
+  const int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (e >= (int64_t)nlist * K * M) return;
+  const int m = (int)(e % M), j = (int)((e / M) % K);
+  const int64_t l = e / ((int64_t)M * K);
+  const float* __restrict__ T = codebooks + ((int64_t)m * K + j) * dsub;
+  const float* __restrict__ c = centroids + l * d + m * dsub;
+  float ct = 0.f, tt = 0.f;
+  for (int u = 0; u < dsub; ++u) { ct = __builtin_fmaf(c[u], T[u], ct); tt = __builtin_fmaf(T[u], T[u], tt); }
+  out[e] = __builtin_fmaf(2.f, ct, tt);
+}
+
 __global__ void list_of_storage_kernel(const int64_t* __restrict__ off, int nlist, int64_t total,
                                        int32_t* __restrict__ list_of) {
   const int64_t p = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
@@ -629,13 +646,18 @@ void ivfpq_scan_bank_kernel(
     const float* __restrict__ codebooks, const int32_t* __restrict__ probes,
     const float* __restrict__ cdist, int nprobe, int ppb, int nsplit, int64_t nitems,
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
-    const float* __restrict__ norms, const float* __restrict__ cnorm, int64_t ntotal, int k, int tot,
+    const float* __restrict__ norms, const float* __restrict__ cnorm,
+    const float* __restrict__ list_tables, int64_t ntotal, int k, int tot,
     KeySink sink, unsigned long long* __restrict__ next_item) {
   // METRIC 0: L2 with a table per (query, list); 1: inner product; 2: L2 through stored norms
   // (one table -2 <q_m, T_m[j]> per query; per list cdist - |c_l|^2 = |q|^2 - 2 <q, c_l>;
-  // + |x'|^2 per code)
+  // + |x'|^2 per code); 3: L2 with the table of a (query, list) pair formed as a per-query term
+  // A_m[j] = -2 <q_m, T_m[j]>, kept in registers, plus a per-list term B_l[j][m] = |T_m[j]|^2 +
+  // 2 <c_{l,m}, T_m[j]> read from list_tables [nlist][256][M] (Sec. 4.3): one addition per entry
+  // instead of DSUB multiply-adds, for indexes whose lists are too short to amortise a table
   constexpr int K = 256, D = M * DSUB;
   constexpr int KEY_METRIC = METRIC == 1 ? 1 : 0;
+  constexpr bool PER_LIST = METRIC == 0 || METRIC == 3;   // a table per (query, list), double buffered
   constexpr int REP = 32 / M;     // copies of every table
   constexpr int NW = NT / 64;     // wavefronts of the workgroup (two workgroups share a CU)
   constexpr int EPL = K * M / NT; // table entries a lane builds = codewords it keeps
@@ -745,7 +767,17 @@ void ivfpq_scan_bank_kernel(
     // the compiler wait for it now rather than, for everything in flight, inside the scan)
 #pragma unroll
     for (int u = 0; u < DSUB; ++u) asm volatile("" : "+v"(qm[u]));
-    if (METRIC != 0) {  // one table per query, in the first set of columns
+    float tq[METRIC == 3 ? EPL : 1];                            // METRIC 3: the per-query term of this lane's entries
+    if (METRIC == 3) {
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        float acc = 0.f;
+#pragma unroll
+        for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qm[u], T[i * DSUB + u], acc);
+        tq[i] = -2.f * acc;
+      }
+    }
+    if (METRIC == 1 || METRIC == 2) {  // one table per query, in the first set of columns
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
         float acc = 0.f;
@@ -774,11 +806,25 @@ void ivfpq_scan_bank_kernel(
     // arrays, touched once per list, not once per chunk): consumer / producer list, the extents
     // of that list, the first code of the current chunk.
     const int nl = __builtin_amdgcn_readfirstlane(*s_nl);
+    // (the first 64 lists' entries also sit one per lane in registers: a cross-lane read costs a
+    // few cycles where an LDS read costs a round trip, and short lists switch every chunk)
+    const int lane = tid & (VS_WAVE - 1);
+    const u32 xb = lane < nl ? s_begin[lane] : 0u, xe = lane < nl ? s_end[lane] : 0u;
+    const int xl = lane < nl ? s_list[lane] : 0;
+    auto list_begin = [&](int pl) -> u32 {
+      return pl < VS_WAVE ? (u32)__builtin_amdgcn_readlane((int)xb, pl) : (u32)__builtin_amdgcn_readfirstlane(s_begin[pl]);
+    };
+    auto list_end = [&](int pl) -> u32 {
+      return pl < VS_WAVE ? (u32)__builtin_amdgcn_readlane((int)xe, pl) : (u32)__builtin_amdgcn_readfirstlane(s_end[pl]);
+    };
+    auto list_number = [&](int pl) -> int {
+      return pl < VS_WAVE ? __builtin_amdgcn_readlane(xl, pl) : __builtin_amdgcn_readfirstlane(s_list[pl]);
+    };
     int pc = 0, pp = 0;
     u32 cb = 0, ce = 0, pe = 0;
     if (nl > 0) {
-      cb = __builtin_amdgcn_readfirstlane(s_begin[0]);
-      ce = pe = __builtin_amdgcn_readfirstlane(s_end[0]);
+      cb = list_begin(0);
+      ce = pe = list_end(0);
     }
     u32 base_c = cb, base_p = cb;
     // load instructions per request: the code, and its stored norm (METRIC 2)
@@ -796,8 +842,8 @@ void ivfpq_scan_bank_kernel(
         base_p += NT;
         if (base_p >= pe) {
           ++pp;
-          base_p = pp < nl ? __builtin_amdgcn_readfirstlane(s_begin[pp]) : 0u;
-          pe = pp < nl ? __builtin_amdgcn_readfirstlane(s_end[pp]) : 0u;
+          base_p = pp < nl ? list_begin(pp) : 0u;
+          pe = pp < nl ? list_end(pp) : 0u;
         }
       }
     };
@@ -809,10 +855,22 @@ void ivfpq_scan_bank_kernel(
     for (int u = 0; u < DSUB; ++u) cn[u] = 0.f;
     auto request_centroid = [&](int pl) {
       if (METRIC == 0 && pl < nl) {
-        const float* src = centroids + (int64_t)__builtin_amdgcn_readfirstlane(s_list[pl]) * D + m_own * DSUB;
+        const float* src = centroids + (int64_t)list_number(pl) * D + m_own * DSUB;
 #pragma unroll
         for (int u = 0; u < DSUB; ++u)
           asm volatile("global_load_dword %0, %1, off" : "=&v"(cn[u]) : "v"(src + u) : "memory");
+      }
+    };
+    // METRIC 3: the per-list term of this lane's entries of the next list to build, likewise
+    float tl[METRIC == 3 ? EPL : 1];
+#pragma unroll
+    for (int i = 0; i < (METRIC == 3 ? EPL : 1); ++i) tl[i] = 0.f;
+    auto request_list_table = [&](int pl) {
+      if (METRIC == 3 && pl < nl) {
+        const float* src = list_tables + ((int64_t)list_number(pl) * K + jg * EPL) * M + m_own;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i)
+          asm volatile("global_load_dword %0, %1, off" : "=&v"(tl[i]) : "v"(src + i * M) : "memory");
       }
     };
     CodeWords<M> S0, S1, S2;
@@ -825,38 +883,52 @@ void ivfpq_scan_bank_kernel(
       cw.template wait_newer<2 * NLT>();
       if (METRIC == 2) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(nrm) : "n"(2 * NLT) : "memory");
       if (base_c == cb) {                                       // (uniform) first chunk of list pc
-        ws.refresh_shared();
-        if (METRIC == 0) {
-          // the slice was requested at the first chunk of the list before (or in the prologue):
-          // only this step's request is younger.  r = q - c, one fp32 subtraction per component.
-          float r[DSUB];
-          asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NLT) : "memory");
-#pragma unroll
-          for (int u = 0; u < DSUB; ++u)
-            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qm[u]), "v"(cn[u]), "n"(NLT) : "memory");
-          request_centroid(pc + 1);                             // one list ahead
+        if ((pc & 3) == 0) ws.refresh_shared();
+        if (PER_LIST) {
 #pragma unroll
           for (int w = 0; w < M / 4; ++w)   // this list's column set: + 32 floats = bit 7 of every column byte
             col[w] = (col[w] & 0x7f7f7f7fu) | (parity ? 0x80808080u : 0u);
           float* __restrict__ lutp = lut0 + 32 * parity;
+          if (METRIC == 0) {
+            // the slice was requested at the first chunk of the list before (or in the prologue):
+            // only this step's request is younger.  r = q - c, one fp32 subtraction per component.
+            float r[DSUB];
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NLT) : "memory");
 #pragma unroll
-          for (int i = 0; i < EPL; ++i) {
-            float acc;
-            if (EXPAND) {
-              acc = TN[i];
+            for (int u = 0; u < DSUB; ++u)
+              asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qm[u]), "v"(cn[u]), "n"(NLT) : "memory");
+            request_centroid(pc + 1);                             // one list ahead
 #pragma unroll
-              for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
-            } else {
-              acc = 0.f;
+            for (int i = 0; i < EPL; ++i) {
+              float acc;
+              if (EXPAND) {
+                acc = TN[i];
 #pragma unroll
-              for (int u = 0; u < DSUB; ++u) {
-                const float diff = r[u] - T[i * DSUB + u];
-                acc = __builtin_fmaf(diff, diff, acc);
+                for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
+              } else {
+                acc = 0.f;
+#pragma unroll
+                for (int u = 0; u < DSUB; ++u) {
+                  const float diff = r[u] - T[i * DSUB + u];
+                  acc = __builtin_fmaf(diff, diff, acc);
+                }
               }
-            }
 #pragma unroll
-            for (int c = 0; c < REP; ++c)
-              lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = acc;
+              for (int c = 0; c < REP; ++c)
+                lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = acc;
+            }
+          } else {
+            // entry = per-query term + per-list term; the wait and the addition are one statement
+            float e[EPL];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+              asm volatile("s_waitcnt vmcnt(%3)\n\tv_add_f32 %0, %1, %2" : "=v"(e[i]) : "v"(tq[i]), "v"(tl[i]), "n"(NLT) : "memory");
+            request_list_table(pc + 1);                           // one list ahead
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+#pragma unroll
+              for (int c = 0; c < REP; ++c)
+                lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = e[i];
           }
           parity ^= 1;
           block_sync_lds();   // this table is visible; the scan on the other column set has finished everywhere
@@ -877,13 +949,14 @@ void ivfpq_scan_bank_kernel(
       if (base_c >= ce) {
         ++pc;
         if (pc < nl) {
-          cb = base_c = __builtin_amdgcn_readfirstlane(s_begin[pc]);
-          ce = __builtin_amdgcn_readfirstlane(s_end[pc]);
+          cb = base_c = list_begin(pc);
+          ce = list_end(pc);
         }
       }
     };
     if (nl > 0) {   // (uniform; ntotal > 0 here)
       request_centroid(pc);
+      request_list_table(pc);
       request(S0, n0);
       request(S1, n1);
       for (;;) {
@@ -901,12 +974,214 @@ void ivfpq_scan_bank_kernel(
       asm volatile("s_waitcnt vmcnt(0)" : "+v"(n0), "+v"(n1), "+v"(n2) : : "memory");
 #pragma unroll
       for (int u = 0; u < DSUB; ++u) asm volatile("s_waitcnt vmcnt(0)" : "+v"(cn[u]) : : "memory");
+#pragma unroll
+      for (int i = 0; i < (METRIC == 3 ? EPL : 1); ++i) asm volatile("s_waitcnt vmcnt(0)" : "+v"(tl[i]) : : "memory");
     }
     ws.finish();
     block_sync_lds();
     block_rank_merge(slots, tot, NW, k, sink, item * k);
     block_sync_lds();   // the slots have been read; the next item may reset them
   }
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront-private scan (Sec. 4.3 "Compressed-domain search") for 8-bit codes of M = 8 or 16
+// sub-quantizers and the table forms whose per-(query, list) work is small: ONE WAVEFRONT per
+// (query, probe split), nothing shared between wavefronts, so a CU runs nine independent streams
+// and the latencies of one (its probes, the first codes of a list) are covered by the others --
+// which is what lists of a few hundred codes need: there a (query, list) pair is one or two rounds
+// of look-ups, and a workgroup that works through them together spends its time at barriers and on
+// per-query set-up.
+// MODE 1 (inner product) and MODE 2 (L2 through the stored norms): one table per query,
+// A_q[j][m] = s <q_m, T_m[j]> with s = 1 or -2 (query_tables, written by pq_query_tables_kernel
+// before this launch), copied to LDS once per work item; a list contributes one number (<q, c_l>,
+// or |q - c_l|^2 - |c_l|^2) and, for MODE 2, every code its stored |x'|^2.
+// MODE 3 (precomputed tables): the table of a pair is A_q + B_l with
+// B_l[j][m] = |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]> (list_tables, computed once per index); this lane's
+// 4 * NI entries of A_q stay in registers for the whole item, and a list costs NI 16-byte loads,
+// four additions and one 16-byte LDS store per lane each.  The distance of a code is the probe's
+// coarse distance |q - c_l|^2 plus its M table entries.
+// All of these are laid out [j][m], and so is the wavefront's table in LDS: rows of M floats.  The
+// codes are stored rotated by their position in the list (rotate_code), so lane l finds
+// sub-quantizer (t + l) mod M in byte t of its code.
+// ---------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// One workgroup: the tables of kQtQueries queries.  A thread keeps one codebook entry T_m[j] in
+// registers and takes the queries' sub-vectors from LDS.
+constexpr int kQtQueries = 8;
+template <int DSUB>
+__global__ __launch_bounds__(256) void pq_query_tables_kernel(const float* __restrict__ q, int64_t nq,
+                                                              const float* __restrict__ codebooks, int d, int M,
+                                                              int K, float scale, float* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* qs = reinterpret_cast<float*>(smem);          // [kQtQueries][d]
+  const int64_t q0 = (int64_t)blockIdx.x * kQtQueries;
+  const int nqb = (int)min((int64_t)kQtQueries, nq - q0);
+  for (int i = threadIdx.x; i < nqb * d; i += blockDim.x) qs[i] = q[q0 * d + i];
+  __syncthreads();
+  for (int e = threadIdx.x; e < K * M; e += blockDim.x) {   // e = j * M + m
+    const int m = e % M, j = e / M;
+    float T[DSUB];
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) T[u] = codebooks[((int64_t)m * K + j) * DSUB + u];
+    for (int a = 0; a < nqb; ++a) {
+      float acc = 0.f;
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qs[a * d + m * DSUB + u], T[u], acc);
+      out[(q0 + a) * K * M + e] = scale * acc;
+    }
+  }
+}
+
+template <int M, int MODE, int R>
+__global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
+    const float* __restrict__ query_tables, const float* __restrict__ list_tables,
+    const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb, int nsplit,
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, const float* __restrict__ norms,
+    const float* __restrict__ cnorm, int64_t ntotal, int k, int tot, KeySink sink) {
+  constexpr int K = 256;
+  constexpr int KEY_METRIC = MODE == 1 ? 1 : 0;
+  constexpr int QPR = M / 4;          // 16-byte pieces per table row
+  constexpr int RPI = 64 / QPR;       // rows one load instruction of the wavefront covers
+  constexpr int NI = K / RPI;         // load instructions per table = 16-byte pieces per lane
+  static_assert(M == 8 || M == 16, "rows of 8 or 16 floats");
+  static_assert(MODE >= 1 && MODE <= 3, "table form");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* lut = reinterpret_cast<float*>(smem);                              // [256][M]
+  u64* slots = reinterpret_cast<u64*>(smem + K * M * sizeof(float));        // tot
+  u32* s_begin = reinterpret_cast<u32*>(slots + tot);                       // ppb: the non-empty lists
+  u32* s_end = s_begin + ppb;
+  int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);
+  float* s_bias = reinterpret_cast<float*>(s_list + ppb);
+
+  const bool lut_at_zero = (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u;
+  const int lane = threadIdx.x;
+  const int64_t item = blockIdx.x;
+  const int64_t qi = item / nsplit;
+  const int split = (int)(item % nsplit);
+  const int p_begin = split * ppb;
+  const int np = ntotal > 0 ? min(nprobe, p_begin + ppb) - p_begin : 0;
+
+  // this lane's pieces of the per-query term: piece i covers row (lane / QPR) + RPI * i, floats
+  // 4 * (lane % QPR) .. + 3
+  const int row0 = lane / QPR, quad = lane % QPR;
+  f32x4 tq[MODE == 3 ? NI : 1];
+  {
+    const f32x4* __restrict__ src = reinterpret_cast<const f32x4*>(query_tables + qi * K * M) + lane;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const f32x4 v = src[i * 64];
+      if constexpr (MODE == 3) tq[i] = v;
+      else *reinterpret_cast<f32x4*>(lut + (row0 + RPI * i) * M + 4 * quad) = v;
+    }
+  }
+  WaveSelect<R> ws;
+  ws.init(slots, tot, k);
+  int nl = 0;
+  for (int p0 = 0; p0 < np; p0 += VS_WAVE) {   // the item's non-empty lists, in probe order
+    const int p = p0 + lane;
+    const int l = p < np ? probes[qi * nprobe + p_begin + p] : -1;
+    const int64_t b = l >= 0 ? list_off[l] : 0, e = l >= 0 ? list_off[l + 1] : 0;
+    const bool keep = e > b;
+    const u64 mask = __ballot(keep);
+    const int pos = nl + __popcll(mask & ((1ull << lane) - 1ull));
+    if (keep) {
+      s_list[pos] = l;
+      s_begin[pos] = (u32)b;
+      s_end[pos] = (u32)e;
+      float bs = cdist[qi * nprobe + p_begin + p];
+      if (MODE == 2) bs -= cnorm[l];
+      s_bias[pos] = bs;
+    }
+    nl += __popcll(mask);
+  }
+  wave_lds_sync();
+  // byte offset of this lane's column in a row for every step, four steps per register, in units
+  // that leave room for it in one byte: v_perm_b32 puts the code byte j into byte 1 and this into
+  // byte 0, and one shift turns (j << 8 | unit * column) into the byte offset j * 4 M + 4 * column
+  constexpr int kShift = M == 16 ? 2 : 3;
+  u32 col[M / 4];
+#pragma unroll
+  for (int w = 0; w < M / 4; ++w) {
+    u32 v = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) v |= (u32)(((4 * w + b + lane) & (M - 1)) << (2 + kShift)) << (8 * b);
+    col[w] = v;
+  }
+  auto load_codes = [&](CodeWords<M>& w, u32 i) {
+    const uint8_t* cp = codes + (u64)i * M;
+    if constexpr (M == 16) w.a = *reinterpret_cast<const u32x4*>(cp);
+    else w.a2 = *reinterpret_cast<const u32x2*>(cp);
+  };
+  // The chunks of 64 codes of all the item's lists form one sequence; the codes of the chunk after
+  // the current one -- the next of this list or the first of the next list -- are requested before
+  // the current chunk's look-ups (lanes past a list's end read the chunk's first code).
+  auto list_at = [&](int pl, u32& begin, u32& end) {
+    begin = __builtin_amdgcn_readfirstlane(s_begin[pl]);
+    end = __builtin_amdgcn_readfirstlane(s_end[pl]);
+  };
+  int pl = 0;
+  u32 base = 0, end = 0;
+  bool first = true;     // the current chunk is the first of its list (uniform)
+  CodeWords<M> cw;
+  float nrm = 0.f, bias = 0.f;
+  if (nl > 0) {
+    list_at(0, base, end);
+    const u32 i = base + (u32)lane;
+    const u32 at = i < end ? i : base;
+    load_codes(cw, at);
+    if (MODE == 2) nrm = norms[at];
+  }
+  while (pl < nl) {
+    int npl = pl;
+    u32 nbase = base + VS_WAVE, nend = end;
+    if (nbase >= end) {
+      ++npl;
+      if (npl < nl) list_at(npl, nbase, nend);
+    }
+    CodeWords<M> nx;
+    float nrm_nx = 0.f;
+    if (npl < nl) {
+      const u32 i2 = nbase + (u32)lane;
+      const u32 at = i2 < nend ? i2 : nbase;
+      load_codes(nx, at);
+      if (MODE == 2) nrm_nx = norms[at];
+    }
+    if (first) {
+      bias = s_bias[pl];
+      if constexpr (MODE == 3) {
+        const int l = __builtin_amdgcn_readfirstlane(s_list[pl]);
+        const f32x4* __restrict__ tls = reinterpret_cast<const f32x4*>(list_tables + (int64_t)l * K * M) + lane;
+        f32x4 tl[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) tl[i] = tls[i * 64];
+        wave_lds_sync();     // the look-ups of the list before are done with the table
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          *reinterpret_cast<f32x4*>(lut + (row0 + RPI * i) * M + 4 * quad) = tq[i] + tl[i];
+        wave_lds_sync();
+      }
+    }
+    const u32 i = base + (u32)lane;
+    const bool valid = i < end;
+    float dist = MODE == 2 ? bias + nrm : bias;
+#pragma unroll
+    for (int t = 0; t < M; ++t) {
+      constexpr u32 sel0 = 0x0c0c0400u;   // byte 1 = byte (t & 3) of the code word, byte 0 = of col
+      const u32 a = __builtin_amdgcn_perm(cw.word(t >> 2), col[t >> 2], sel0 + 0x101u * (t & 3)) >> kShift;
+      // (the table sits at LDS address 0 when the kernel has no static LDS: then the offset is the address)
+      if (lut_at_zero) dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)a);
+      else dist += *reinterpret_cast<const float*>(smem + a);
+    }
+    if (MODE != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
+    ws.push(valid, make_key(dist, i, KEY_METRIC));
+    first = npl != pl;
+    pl = npl; base = nbase; end = nend;
+    if (pl < nl) { cw = nx; nrm = nrm_nx; }
+  }
+  ws.finish();
+  for (int j = lane; j < k; j += VS_WAVE) sink.put(item * k + j, ws.s[j]);
 }
 
 // One wavefront per query: k best of the nsplit partial lists, then
@@ -948,6 +1223,12 @@ __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__
 // Shapes served by ivfpq_scan_bank_kernel; an index of such a shape stores its codes rotated.
 bool ivfpq_codes_rotated(const IvfpqDims& g) {
   return g.nbits == 8 && ((g.M == 16 && g.dsub == 8) || (g.M == 32 && g.dsub == 3) || (g.M == 8 && g.dsub == 4));
+}
+// The wavefront-private kernel (one wavefront per (query, probe split), rows of M floats) serves the
+// rotated shapes with M = 8 or 16 while the lists are short: with long lists the workgroup-wide
+// kernel streams better.
+bool ivfpq_wave_scan_applies(const IvfpqDims& g, int64_t ntotal) {
+  return ivfpq_codes_rotated(g) && (g.M == 8 || g.M == 16) && ntotal <= (int64_t)g.nlist * kWaveScanMaxMeanList;
 }
 constexpr int kBankThreads = 256;   // 4 wavefronts per workgroup, two workgroups per CU
 static size_t bank_scan_lds_bytes(int tot, int ppb) {
@@ -1028,6 +1309,13 @@ void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_
   hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, d, norms);
 }
 
+void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
+                           hipStream_t st) {
+  const int64_t n = (int64_t)g.nlist * g.K * g.M;
+  hipLaunchKernelGGL(pq_list_tables_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, centroids,
+                     codebooks, g.nlist, g.d, g.M, g.K, g.dsub, out);
+}
+
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,
                             hipStream_t st) {
   if (total <= 0) return;
@@ -1045,7 +1333,8 @@ static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, con
                              const float* codebooks, const int32_t* probes, const float* cdist,
                              int nprobe, int ppb, int nsplit, const int64_t* list_off,
                              const uint8_t* codes, const float* norms, const float* cnorm,
-                             int64_t ntotal, int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
+                             const float* list_tables, int64_t ntotal, int k, int tot, KeySink sink,
+                             u64* counter, hipStream_t st) {
   const size_t shmem = bank_scan_lds_bytes(tot, ppb);
   constexpr int NT = kBankThreads;
   auto kern = &ivfpq_scan_bank_kernel<M, DSUB, METRIC, R, NT>;
@@ -1060,8 +1349,8 @@ static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, con
   const int64_t grid = std::min<int64_t>(nitems, 256ll * per_cu);
   launch_fill_u64(counter, 1, 0ull, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), shmem, st, q, centroids, codebooks,
-                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, ntotal,
-                     k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
+                     probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, list_tables,
+                     ntotal, k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
 }
 
 template <int M, int DSUB>
@@ -1069,15 +1358,50 @@ static void launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
                                  const float* centroids, const float* codebooks,
                                  const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                  int nsplit, const int64_t* list_off, const uint8_t* codes,
-                                 const float* norms, const float* cnorm, int mode, int64_t ntotal,
-                                 int k, int tot, KeySink sink, u64* counter, hipStream_t st) {
+                                 const float* norms, const float* cnorm, const float* list_tables,
+                                 int mode, int64_t ntotal, int k, int tot, KeySink sink, u64* counter,
+                                 hipStream_t st) {
 #define GO(MET, RR)                                                                               \
   launch_scan_bank<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,  \
-                                     nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink, counter, st)
+                                     nsplit, list_off, codes, norms, cnorm, list_tables, ntotal, k, tot, sink, counter, st)
   const int r = tot <= 128 ? 2 : (tot <= 256 ? 4 : 0);   // register-sort width covering the slots
   if (mode == 1)      { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
   else if (mode == 2) { if (r == 2) GO(2, 2); else if (r == 4) GO(2, 4); else GO(2, 0); }
+  else if (mode == 3) { if (r == 2) GO(3, 2); else if (r == 4) GO(3, 4); else GO(3, 0); }
   else                { if (r == 2) GO(0, 2); else if (r == 4) GO(0, 4); else GO(0, 0); }
+#undef GO
+}
+
+// Work space the wavefront-private kernel needs: one table per query, [nq][K][M] floats.
+size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq) {
+  return (size_t)nq * g.K * g.M * sizeof(float);
+}
+static size_t wave_scan_lds_bytes(const IvfpqDims& g, int tot, int ppb) {
+  return (size_t)g.K * g.M * sizeof(float) + (size_t)tot * sizeof(u64) + (size_t)ppb * 16;
+}
+template <int M, int DSUB, int MODE>
+static void launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, const float* codebooks,
+                             float* query_tables, const float* list_tables, const int32_t* probes,
+                             const float* cdist, int nprobe, int ppb, int nsplit, const int64_t* list_off,
+                             const uint8_t* codes, const float* norms, const float* cnorm, int64_t ntotal,
+                             int k, KeySink sink, hipStream_t st) {
+  hipLaunchKernelGGL((pq_query_tables_kernel<DSUB>), dim3((unsigned)((nq + kQtQueries - 1) / kQtQueries)),
+                     dim3(256), (size_t)kQtQueries * g.d * sizeof(float), st, q, nq, codebooks, g.d, g.M, g.K,
+                     MODE == 1 ? 1.f : -2.f, query_tables);
+  const int tot = select_slots_for_k(k);
+  const size_t shmem = wave_scan_lds_bytes(g, tot, ppb);
+  const dim3 grid((unsigned)(nq * nsplit)), block(64);
+#define GO(RR)                                                                                        \
+  do {                                                                                                \
+    auto kern = &ivfpq_scan_wave_kernel<M, MODE, RR>;                                                 \
+    if (shmem > 48 * 1024)                                                                            \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);              \
+    hipLaunchKernelGGL(kern, grid, block, shmem, st, query_tables, list_tables, probes, cdist, nprobe, \
+                       ppb, nsplit, list_off, codes, norms, cnorm, ntotal, k, tot, sink);             \
+  } while (0)
+  const int r = select_regs_for_slots(tot);
+  if (r == 2) GO(2); else if (r == 4) GO(4); else GO(0);
 #undef GO
 }
 
@@ -1116,12 +1440,14 @@ static void launch_scan_generic(const IvfpqDims& g, const float* q, int64_t nq,
 int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                       const float* codebooks, const int32_t* probes, const float* cdist,
                       int nprobe, int nsplit, const int64_t* list_off, const uint8_t* codes,
-                      const float* norms, const float* cnorm, int64_t ntotal, int k, u64* partial,
-                      u64* counter, const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
+                      const float* norms, const float* cnorm, const float* list_tables,
+                      float* query_tables, int64_t ntotal, int k, u64* partial, u64* counter,
+                      const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {
   if (nq <= 0) return 0;
   // table form: 1 inner product; 2 L2 through the stored norms (norms non-null; cnorm = the
   // centroids' squared norms); 0 L2 with one table of squared residual distances per (query, list)
-  const int mode = g.metric == 1 ? 1 : (norms ? 2 : 0);
+  // 3: L2 with per-list terms of the tables precomputed (list_tables non-null; bank kernel shapes only)
+  const int mode = g.metric == 1 ? 1 : (norms ? 2 : (list_tables && ivfpq_codes_rotated(g) ? 3 : 0));
   KeySink sink;
   sink.metric = g.metric;
   sink.idx32 = nullptr;
@@ -1132,13 +1458,23 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   const size_t shmem = (size_t)4 * tot * sizeof(u64) + (size_t)g.M * g.K * sizeof(float) +
                        (size_t)(g.d + 2) * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
+  if (mode != 0 && query_tables && ivfpq_wave_scan_applies(g, ntotal)) {
+    if (wave_scan_lds_bytes(g, select_slots_for_k(k), ppb) > 160 * 1024) return -1;
+#define WAVE(MM, DS, MODE)                                                                             \
+  launch_scan_wave<MM, DS, MODE>(g, q, nq, codebooks, query_tables, list_tables, probes, cdist, nprobe, \
+                                 ppb, nsplit, list_off, codes, norms, cnorm, ntotal, k, sink, st)
+    if (g.M == 16) { if (mode == 1) WAVE(16, 8, 1); else if (mode == 2) WAVE(16, 8, 2); else WAVE(16, 8, 3); }
+    else           { if (mode == 1) WAVE(8, 4, 1); else if (mode == 2) WAVE(8, 4, 2); else WAVE(8, 4, 3); }
+#undef WAVE
+    return 0;
+  }
   if (ivfpq_codes_rotated(g)) {   // (the stored codes are rotated: no other kernel reads them)
     const int btot = bank_slots_for_k(k, ppb);
     if (bank_scan_lds_bytes(btot, ppb) > 160 * 1024) return -1;
 #define BANK(MM, DS)                                                                              \
   if (g.M == MM && g.dsub == DS) {                                                                \
     launch_scan_bank_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                 nsplit, list_off, codes, norms, cnorm, mode, ntotal, k, btot, sink, counter, st); \
+                                 nsplit, list_off, codes, norms, cnorm, list_tables, mode, ntotal, k, btot, sink, counter, st); \
     return 0;                                                                                     \
   }
     BANK(16, 8)   // PQ16x8 on d = 128

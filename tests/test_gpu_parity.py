@@ -146,6 +146,11 @@ IVF_CASES = {
     "c5_small": (S.config("C5", nb=20_000, nq=100, ncomp=50, nlist=128), [(10, 32), (100, 128)]),
     "pq4_l2": (S.config("C1", nb=5_000, M=16, nbits=4), [(10, 4)]),
     "ip_8bit": (S.config("C4", nb=20_000, nq=64, ncomp=40, nlist=64, metric=1, M=8), [(10, 8)]),
+    # inner product on the shapes whose codes are stored rotated: short lists (one wavefront per
+    # (query, probe split)) and long ones (one workgroup)
+    "c1_ip": (S.config("C1", metric=1), [(10, 4), (100, 8), (300, 99)]),
+    "c3_small_ip": (S.config("C3", nb=60_000, nq=100, ncomp=100, nlist=256, metric=1), [(10, 16), (100, 64)]),
+    "c3_long_lists_ip": (S.config("C3", nb=40_000, nq=100, ncomp=100, nlist=16, metric=1), [(10, 4)]),
     # long lists (>= 1024 codes per list on average): the single-table scan variant
     "c4_long_lists": (S.config("C4", nb=40_000, nq=100, ncomp=100, nlist=32), [(100, 8), (10, 32)]),
     "c3_long_lists": (S.config("C3", nb=40_000, nq=100, ncomp=100, nlist=16), [(10, 4)]),
@@ -678,7 +683,8 @@ def test_ivfpq_search_then_refine_pipeline(vs, oracle):
 # ------------------------------------------------- L2 through stored norms (Sec. 4.3)
 
 @pytest.mark.parametrize("name", ["c1", "c3_small", "c4_small", "pq4_l2", "odd_shapes", "c4_long_lists",
-                                  "pq16x8_d64", "pq32x4_d64"])
+                                  "c3_long_lists", "c1_long_lists", "pq16x8_d64", "pq32x4_d64",
+                                  "max_k_and_nprobe"])
 def test_ivfpq_stored_norm_search_matches_oracle(vs, oracle, name):
     """Search type |q|^2 + |x'|^2 - 2 <q, x'>: the stored norms are the oracle's bit for bit,
     the results agree with the definition (oracle form 0) within the rounding of the
@@ -708,6 +714,63 @@ def test_ivfpq_stored_norm_search_matches_oracle(vs, oracle, name):
         ix.set_search_type(vs.ST_STORED_NORMS)
         live = I0 >= 0
         assert (np.abs(D.astype(np.float64) - D0)[live] <= (1e-4 * np.abs(D0) + 2.0 ** -21 * cancel[:, None])[live]).all()
+    ix.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c3_small", "c4_small", "c4_long_lists", "c3_long_lists", "c1_long_lists",
+                                  "max_k_and_nprobe"])
+def test_ivfpq_precomputed_table_search_matches_oracle(vs, oracle, name):
+    """Search type "per-query term + per-list term" (Sec. 4.3): against the definition (oracle form
+    0) within the rounding of the cancelling terms |q|^2 + |c_l|^2 + |x' - c_l|^2, and against the
+    default search type of the same index; switching back and forth leaves both unchanged."""
+    cfg, searches = IVF_CASES[name]
+    say("ivfpq precomputed tables %s nb=%d d=%d nlist=%d M=%d" % (name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"]))
+    x, q = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x, pieces=2)
+    check_storage(ix, orc)
+    tmax = float((orc.codebooks.astype(np.float64) ** 2).sum(2).max(1).sum())
+    cancel = (q.astype(np.float64) ** 2).sum(1) + float((orc.centroids.astype(np.float64) ** 2).sum(1).max()) + tmax
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        D0, I0 = [host(t).copy() for t in ix.search(dev(q), k, nprobe)]
+        ix.set_search_type(vs.ST_PRECOMPUTED_TABLES)
+        D, I = [host(t).copy() for t in ix.search(dev(q), k, nprobe)]
+        ix.set_search_type(vs.ST_RESIDUAL_TABLES)
+        D1, I1 = [host(t).copy() for t in ix.search(dev(q), k, nprobe)]
+        np.testing.assert_array_equal(D1, D0); np.testing.assert_array_equal(I1, I0)
+        assert (D[I >= 0] >= 0).all()
+        Do, Io = orc.search(q, k + EXTRA, nprobe)                 # the definition
+        same = check_search(D, I, Do, Io, L2, cancel=cancel)
+        assert same > 0.97, same
+        live = I0 >= 0
+        assert (np.abs(D.astype(np.float64) - D0)[live] <= (1e-4 * np.abs(D0) + 2.0 ** -21 * cancel[:, None])[live]).all()
+    ix.close()
+
+
+def test_precomputed_table_search_type_rules(vs):
+    import torch
+    say("precomputed tables: rules")
+    cfg = S.config("C1", nb=2000)
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ip = vs.IVFPQ(cfg["d"], IP, dev(cent), dev(cb), 8)
+    with pytest.raises(vs.VSError):
+        ip.set_search_type(vs.ST_PRECOMPUTED_TABLES)            # L2 only
+    ip.close()
+    cfg2 = S.config("C1", nb=2000, M=16, nbits=4)
+    cent2, cb2 = S.make_index_params(cfg2, x)
+    g = vs.IVFPQ(cfg2["d"], L2, dev(cent2), dev(cb2), 4)
+    with pytest.raises(vs.VSError) as e:
+        g.set_search_type(vs.ST_PRECOMPUTED_TABLES)             # no specialised kernel for this shape
+    assert e.value.code == -2
+    g.close()
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.set_search_type(vs.ST_PRECOMPUTED_TABLES)                # before any add: fine, the tables depend on the parameters only
+    ix.add(dev(x))
+    D, I = ix.search(dev(q), 5, 3)
+    ix.set_search_type(vs.ST_RESIDUAL_TABLES)
+    D0, I0 = ix.search(dev(q), 5, 3)
+    assert (host(I) == host(I0)).mean() > 0.98
     ix.close()
 
 

@@ -64,8 +64,8 @@ def kernels(tmp_path_factory):
 
 
 def test_every_instantiation_is_present(kernels):
-    # three shapes x three table forms x three selection widths
-    assert len(kernels) == 27, sorted(kernels)
+    # three shapes x four table forms x three selection widths
+    assert len(kernels) == 36, sorted(kernels)
 
 
 def test_no_compiler_instruction_touches_a_register_in_flight(kernels):
