@@ -30,22 +30,153 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix cores, published
-# What a read-only streaming kernel (16-byte loads, 64 KB in flight per CU, over a 512 MB span)
-# reached on the MI355X boxes used here, and an MFMA-only loop of v_mfma_f32_32x32x16_bf16:
-# reported next to the published peaks.
-HBM_READ_MEASURED_GBS = 6640.0
-BF16_MFMA_MEASURED_TFLOPS = 2150.0
+# Next to the published peaks the JSON line carries what THIS GPU reached in THIS run on a
+# read-only stream over 2 GiB and on a register-only loop of v_mfma_f32_32x32x16_bf16
+# (libvs_calibrate.so; --no-calibrate-peaks leaves them null).
+SCAN_SOURCES = ("kernels_ivfpq.hip", "common.hpp")   # what the scan kernels are compiled from
 
 
 def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def scan_kernel_name(cfg, code_size):
+def scan_kernel_name(cfg, search_type):
     """The scan kernel the library picks for this shape (same rule as its launcher)."""
+    code_size = cfg["M"] * cfg["nbits"] // 8
     if cfg["nbits"] == 8 and (cfg["M"], cfg["d"] // cfg["M"]) in ((16, 8), (32, 3), (8, 4)):
+        short = cfg["M"] in (8, 16) and cfg["nb"] <= cfg["nlist"] * 1024
+        if short and (cfg["metric"] == 1 or search_type != "tables"):
+            return "ivfpq_scan_wave_kernel"
         return "ivfpq_scan_bank_kernel"
     return "ivfpq_scan_pipe_kernel" if code_size in (16, 32, 64) else "ivfpq_scan_kernel"
+
+
+def calibrate_lib():
+    import ctypes
+    from paper_2401_08281_amd import build
+    path = build.calibrate_lib_path()
+    if not os.path.exists(path):
+        build.build_calibrate_lib()
+    L = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    L.vsc_copy.restype = ctypes.c_int
+    L.vsc_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.vsc_read_stream.restype = ctypes.c_int
+    L.vsc_read_stream.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.vsc_mfma_loop.restype = ctypes.c_int
+    L.vsc_mfma_loop.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+    return L
+
+
+def calibrate_peaks(torch):
+    """{"read_stream_GBps", "mfma_loop_TFLOPs"} measured now on this GPU, on torch's current stream."""
+    import ctypes
+    L = calibrate_lib()
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    buf = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_()      # 2 GiB: beyond every cache
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gbs = ctypes.c_double(0.0)
+    rc = L.vsc_read_stream(ctypes.c_void_p(buf.data_ptr()), buf.numel() * 4, 5, ctypes.c_void_p(sink.data_ptr()),
+                           ctypes.byref(gbs), st)
+    assert rc == 0, "vsc_read_stream failed: %d" % rc
+    del buf
+    out = torch.empty(256 * 2 * 256, dtype=torch.float32, device="cuda")
+    tf = ctypes.c_double(0.0)
+    rc = L.vsc_mfma_loop(20000, ctypes.c_void_p(out.data_ptr()), ctypes.byref(tf), st)
+    assert rc == 0, "vsc_mfma_loop failed: %d" % rc
+    torch.cuda.synchronize()
+    return {"read_stream_GBps": round(gbs.value, 1), "mfma_loop_TFLOPs": round(tf.value, 1)}
+
+
+def calibrate_copy(torch):
+    """Three 1 GiB device-to-device copies by vs_calibrate_copy_kernel: the known-size reference
+    for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE."""
+    import ctypes
+    L = calibrate_lib()
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        assert L.vsc_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), src.numel() * 4, st) == 0
+    torch.cuda.synchronize()
+    del src, dst
+
+
+def source_stamp():
+    """Identifies the scan kernels' source text: traffic figures measured on another text are not
+    this build's."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in SCAN_SOURCES:
+        with open(os.path.join(ROOT, "paper_2401_08281_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_key(args, nprobe):
+    return "ivfpq_scan_%s_nprobe%d%s" % (args.workload, nprobe,
+                                         "" if args.search_type == "tables" else "_" + args.search_type)
+
+
+def record_traffic(args):
+    """--record-traffic FETCH_DIR WRITE_DIR: reads the counter_collection.csv files that two
+    `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE ... -- python3 bench.py --calibrate-copy ...` runs of the
+    same workload left in the two folders, scales the scan kernel's counters by what the same
+    counters show for the 1 GiB copies of vs_calibrate_copy_kernel, and stores the result, stamped
+    with the scan kernels' source text and the commit, in profiles/traffic.json.  No GPU needed."""
+    import csv
+    import glob
+    import subprocess
+    import synth_inputs as S
+    cfg = S.config(args.workload)
+    nprobe = args.nprobe or cfg["nprobe"]
+    kernel = scan_kernel_name(cfg, args.search_type)
+    GIB_KIB = float(1 << 20)
+    got = {}
+    for counter, folder in zip(("FETCH_SIZE", "WRITE_SIZE"), args.record_traffic):
+        vals = {"scan": [], "copy": []}
+        files = glob.glob(os.path.join(folder, "**", "*counter_collection.csv"), recursive=True)
+        assert files, "no counter_collection.csv under " + folder
+        for path in files:
+            with open(path) as f:
+                for r in csv.DictReader(f):
+                    if r["Counter_Name"] != counter:
+                        continue
+                    if kernel in r["Kernel_Name"]:
+                        vals["scan"].append(float(r["Counter_Value"]))
+                    elif "vs_calibrate_copy_kernel" in r["Kernel_Name"]:
+                        vals["copy"].append(float(r["Counter_Value"]))
+        assert vals["scan"] and vals["copy"], "%s: %d scan and %d copy dispatches in %s" % (
+            counter, len(vals["scan"]), len(vals["copy"]), folder)
+        scan = sum(vals["scan"]) / len(vals["scan"])
+        copy = sum(vals["copy"]) / len(vals["copy"])
+        scale = GIB_KIB / copy                       # actual KiB per counted KiB
+        got[counter] = (scan, copy, scale, len(vals["scan"]))
+        print("%s %s: n=%d avg=%.1f KiB per dispatch; 1 GiB copy reads as %.1f KiB -> scale %.3f -> %.3f GB" % (
+            kernel, counter, len(vals["scan"]), scan, copy, scale, scan * 1024 * scale / 1e9))
+    try:
+        commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True,
+                                text=True).stdout.strip() or "unknown"
+    except OSError:
+        commit = "unknown"
+    fetch = got["FETCH_SIZE"][0] * 1024 * got["FETCH_SIZE"][2]
+    write = got["WRITE_SIZE"][0] * 1024 * got["WRITE_SIZE"][2]
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        table = {}
+    table[traffic_key(args, nprobe)] = {
+        "hbm_bytes_per_launch": int(fetch + write), "fetch_bytes": int(fetch), "write_bytes": int(write),
+        "fetch_scale": round(got["FETCH_SIZE"][2], 3), "write_scale": round(got["WRITE_SIZE"][2], 3),
+        "kernel": kernel, "scan_source_sha256_16": source_stamp(), "measured_after_commit": commit,
+    }
+    with open(path, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print("wrote %s [%s]" % (path, traffic_key(args, nprobe)))
+    return 0
 
 
 def main():
@@ -81,9 +212,19 @@ def main():
                          "flat index (prepared once, at add)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a 1 GiB device-to-device copy kernel (reference for rocprofv3 "
-                         "--pmc FETCH_SIZE / WRITE_SIZE runs)")
+                    help="also run three 1 GiB device-to-device copies by vs_calibrate_copy_kernel "
+                         "(the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
+    ap.add_argument("--calibrate-peaks", dest="calibrate_peaks", action="store_true", default=True,
+                    help="measure this GPU's read-stream rate and bf16 matrix-core loop rate in this run and "
+                         "report them next to the published peaks (default)")
+    ap.add_argument("--no-calibrate-peaks", dest="calibrate_peaks", action="store_false")
+    ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no benchmark: turn the output folders of two rocprofv3 --pmc runs of this workload "
+                         "(FETCH_SIZE, then WRITE_SIZE, both with --calibrate-copy) into the workload's entry "
+                         "of profiles/traffic.json")
     args = ap.parse_args()
+    if args.record_traffic:
+        return record_traffic(args)
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU; --gpus %d is not supported (to use several, "
               "shard the stored vectors by id over one process per GPU and merge the k best of each)."
@@ -101,12 +242,11 @@ def main():
     vs.lib()
 
     if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch)
+    args.peaks = calibrate_peaks(torch) if args.calibrate_peaks else None
+    if args.peaks:
+        log("this GPU now: read stream %.0f GB/s, bf16 matrix-core loop %.0f TFLOP/s" % (
+            args.peaks["read_stream_GBps"], args.peaks["mfma_loop_TFLOPs"]))
 
     over = {}
     if args.nb:
@@ -167,11 +307,12 @@ def main():
     nprobe = cfg["nprobe"]
     code_size = cfg["M"] * cfg["nbits"] // 8 + (4 if args.search_type == "norms" else 0)
 
-    # algorithmic work of the scan: codes visited by the batch
+    # algorithmic work of the scan: codes visited by the batch, counted by the library in the
+    # same call that searches (vs_ivfpq_search_stats)
     sizes = ix.list_sizes()
-    probes, _ = ix.coarse(qd, nprobe)
-    scanned = int(sizes[probes.long()].sum().item())
-    pairs = int(probes.numel())
+    _, _, stats = ix.search_stats(qd, k, nprobe)
+    scanned = stats["scanned_codes"]
+    pairs = nq * min(nprobe, cfg["nlist"])
     imbalance = float((sizes.double() ** 2).sum().item() * cfg["nlist"] / float(cfg["nb"]) ** 2)
 
     D = torch.empty((nq, k), dtype=torch.float32, device="cuda")
@@ -240,8 +381,25 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_ivfpq(cfg, cent, cb, ix, q, k, nprobe)
 
-    traffic = load_traffic("ivfpq_scan_%s_nprobe%d%s" % (
-        args.workload, nprobe, "" if args.search_type == "tables" else "_" + args.search_type))
+    traffic = load_traffic(traffic_key(args, nprobe))
+    peaks = args.peaks or {}
+    read_now = peaks.get("read_stream_GBps")
+    # the coarse quantizer's distance stage: algorithmic flop of one nq x nlist x d contraction
+    # over the stage's time (operand preparation and every sweep and pass included)
+    coarse_ms = stage_ms.get("coarse_dist", 0.0)
+    coarse_flop = 2.0 * nq * cfg["nlist"] * cfg["d"]
+    on_mfma = stats["coarse_rows_matrix_core"] > 0
+    coarse_tf = coarse_flop / (coarse_ms * 1e-3) / 1e12 if coarse_ms > 0 else 0.0
+    coarse_peak = BF16_MFMA_PEAK_TFLOPS if on_mfma else FP32_VECTOR_PEAK_TFLOPS
+    roofline_coarse = {
+        "bound": "mfma" if on_mfma else "alu",
+        "kernel": "mfma_sweep_kernel (stage: operand preparation + minima sweep + collect sweep)" if on_mfma
+                  else "canon_matrix_kernel",
+        "achieved": coarse_tf, "peak": coarse_peak, "unit": "TFLOP/s", "frac": coarse_tf / coarse_peak,
+        "algorithmic_flop_per_step": coarse_flop, "stage_ms": coarse_ms,
+        "peak_measured_mfma_loop": peaks.get("mfma_loop_TFLOPs") if on_mfma else None,
+        "rows_matrix_core": stats["coarse_rows_matrix_core"],
+        "rows_exact_fallback": stats["coarse_rows_fallback"], "traffic": None}
     out = {
         "metric": "IVF-PQ queries/sec at fixed nprobe & recall@10; ADC-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -257,12 +415,14 @@ def main():
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v},
             **({"refine": refine} if refine else {}), **({"train": train} if train else {})},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(cfg, code_size), "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(cfg, args.search_type), "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "peak_measured_read_stream": HBM_READ_MEASURED_GBS,
-                     "frac_of_measured": achieved / HBM_READ_MEASURED_GBS,
+                     "peak_measured_read_stream": read_now,
+                     "frac_of_measured": achieved / read_now if read_now else None,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
-                     "kernel_ms": scan_ms, "pairs_per_launch": pairs},
+                     "kernel_ms": scan_ms, "pairs_per_launch": pairs,
+                     "probed_nonempty_lists_per_launch": stats["probed_lists"]},
+        "roofline_coarse": roofline_coarse,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
@@ -332,8 +492,10 @@ def bench_flat(args, cfg, x, q, xd, qd):
         achieved = flops / (dist_ms_total * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": "mfma_sweep_kernel (stage: operand preparation + minima sweep + collect sweep)",
                 "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "peak_measured_mfma_loop": BF16_MFMA_MEASURED_TFLOPS,
-                "frac_of_measured": achieved / BF16_MFMA_MEASURED_TFLOPS, "traffic": None,
+                "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                "peak_measured_mfma_loop": (args.peaks or {}).get("mfma_loop_TFLOPs"),
+                "frac_of_measured": achieved / args.peaks["mfma_loop_TFLOPs"] if args.peaks else None,
+                "algorithmic_flop_per_step": flops, "traffic": None,
                 "exact_fallback_rows_per_step": fallback_rows / (args.warmup + args.steps)}
     else:
         flops = 3.0 * nq * nb * d      # sub + fma per pair and dimension
@@ -432,8 +594,8 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
             "stage_ms_per_step": {s: round(v[0] / args.steps, 4) for s, v in prof.items() if v[1]}},
         "roofline": {"bound": "hbm", "kernel": ("ivfsq8_scan" if sq8 else "ivfflat_scan") + ("_tiled_kernel" if d % 32 == 0 else "_kernel"), "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "peak_measured_read_stream": HBM_READ_MEASURED_GBS,
-                     "frac_of_measured": achieved / HBM_READ_MEASURED_GBS,
+                     "peak_measured_read_stream": (args.peaks or {}).get("read_stream_GBps"),
+                     "frac_of_measured": achieved / args.peaks["read_stream_GBps"] if args.peaks else None,
                      "traffic": None, "algorithmic_bytes_per_launch": algo, "kernel_ms": scan_ms},
         "cpu_baseline": cpu,
     }
@@ -442,13 +604,16 @@ def bench_ivfflat(args, cfg, x, q, xd, qd, cent):
 
 
 def load_traffic(key):
-    """HBM bytes per launch measured with rocprofv3 --pmc in separate runs, if recorded."""
+    """HBM bytes per launch measured with rocprofv3 --pmc in separate runs (--record-traffic), if
+    recorded for the scan kernels' present source text; None otherwise."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
             rec = json.load(f).get(key)
-            return rec["hbm_bytes_per_launch"] if rec else None
-    except (OSError, ValueError):
+        if not rec or rec.get("scan_source_sha256_16") != source_stamp():
+            return None
+        return rec["hbm_bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
         return None
 
 

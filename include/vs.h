@@ -217,6 +217,25 @@ VS_API int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32
                     float* out_dist, int64_t* out_ids, void* hip_stream);
 
 /*
+ * vs_ivfpq_search that also reports what the call did (App. A.3 "GPU Faiss": the scan of the
+ * probed lists is the stage to price).  stats: DEVICE pointer to one vs_search_stats, written in
+ * stream order by a small kernel of the same call (no synchronisation), or NULL for none:
+ *   scanned_codes   sum over the (query, probe) pairs of the probed list's size = codes the scan read
+ *   probed_lists    (query, probe) pairs whose list is not empty
+ *   coarse_rows_matrix_core  queries whose probes were found through the matrix-core shortlist
+ *   coarse_rows_fallback     ... of which failed the sufficiency test and were redone exactly
+ * Results, errors and work space are those of vs_ivfpq_search.  nq == 0 zeroes the block.
+ */
+typedef struct vs_search_stats {
+  int64_t scanned_codes;
+  int64_t probed_lists;
+  int64_t coarse_rows_matrix_core;
+  int64_t coarse_rows_fallback;
+} vs_search_stats;
+VS_API int vs_ivfpq_search_stats(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                          float* out_dist, int64_t* out_ids, vs_search_stats* stats, void* hip_stream);
+
+/*
  * vs_ivfpq_search for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
  * bit for bit, but the work space of the search (operand planes and candidate lists of the

@@ -25,12 +25,13 @@ class VSError(RuntimeError):
 
 
 def lib():
-    """Loads libvs.so (building it first only if it is not there at all)."""
+    """Loads libvs.so, building it first if it is missing or older than one of its sources
+    (VS_NO_REBUILD=1 in the environment loads a stale library as it is)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from . import build
+    from . import build
+    if not os.path.exists(_LIB_PATH) or (build.is_stale() and os.environ.get("VS_NO_REBUILD") != "1"):
         build.build_lib()
     L = ctypes.CDLL(_LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
@@ -94,6 +95,8 @@ def lib():
     L.vs_ivfpq_add.argtypes = [vp, vp, i64, vp, vp]
     L.vs_ivfpq_search.restype = ctypes.c_int
     L.vs_ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    L.vs_ivfpq_search_stats.restype = ctypes.c_int
+    L.vs_ivfpq_search_stats.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
     L.vs_ivfpq_search_static.restype = ctypes.c_int
     L.vs_ivfpq_search_static.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     L.vs_ivfpq_destroy.restype = None
@@ -342,6 +345,22 @@ def vs_ivfpq_search(h, q, k, nprobe, out_dist=None, out_ids=None):
     return out_dist, out_ids
 
 
+SEARCH_STATS_FIELDS = ("scanned_codes", "probed_lists", "coarse_rows_matrix_core", "coarse_rows_fallback")
+
+
+def vs_ivfpq_search_stats(h, q, k, nprobe):
+    """vs_ivfpq_search plus the call's vs_search_stats block: (dist, ids, stats) with stats an
+    int64 device tensor of the struct's fields in SEARCH_STATS_FIELDS order, written in stream
+    order (reading it on the host synchronises)."""
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    out_dist = torch.empty((nq, k), dtype=torch.float32, device=q.device)
+    out_ids = torch.empty((nq, k), dtype=torch.int64, device=q.device)
+    stats = torch.empty(len(SEARCH_STATS_FIELDS), dtype=torch.int64, device=q.device)
+    _check(lib().vs_ivfpq_search_stats(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _p(stats), _stream()))
+    return out_dist, out_ids, stats
+
+
 def vs_ivfpq_search_static(h, q, k, nprobe, out_dist, out_ids):
     """vs_ivfpq_search on the library's static work space: no device allocation inside the
     call, so the outputs are the caller's (tensors [nq, k], fp32 and int64)."""
@@ -462,26 +481,72 @@ def vs_ivfflat_get_storage(h, d, device):
     return ids, list_of, rows
 
 
+def vs_ivfsq8_create(d, metric, nlist, centroids, vmin, step):
+    centroids = _dev(centroids, torch.float32, "centroids")
+    vmin = _dev(vmin, torch.float32, "vmin")
+    step = _dev(step, torch.float32, "step")
+    if vmin.numel() != d or step.numel() != d or centroids.numel() != nlist * d:
+        raise ValueError("centroids must be [nlist, d], vmin and step [d]")
+    h = ctypes.c_void_p(0)
+    _check(lib().vs_ivfsq8_create(ctypes.byref(h), d, metric, nlist, _p(centroids), _p(vmin), _p(step), _stream()))
+    return h
+
+
+def vs_ivfsq8_destroy(h):
+    lib().vs_ivfsq8_destroy(h)
+
+
+def vs_ivfsq8_ntotal(h):
+    return int(lib().vs_ivfsq8_ntotal(h))
+
+
+def vs_ivfsq8_add(h, x, ids=None):
+    x = _dev(x, torch.float32, "x")
+    ids = _dev(ids, torch.int64, "ids")
+    if ids is not None and ids.numel() != x.shape[0]:
+        raise ValueError("ids must hold one id per row of x")
+    _check(lib().vs_ivfsq8_add(h, _p(x), x.shape[0], _p(ids), _stream()))
+
+
+def vs_ivfsq8_search(h, q, k, nprobe, out_dist=None, out_ids=None):
+    q = _dev(q, torch.float32, "q")
+    nq = q.shape[0]
+    if out_dist is None:
+        out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
+    if out_ids is None:
+        out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
+    _dev(out_dist, torch.float32, "out_dist")
+    _dev(out_ids, torch.int64, "out_ids")
+    _check(lib().vs_ivfsq8_search(h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
+    return out_dist, out_ids
+
+
+def vs_ivfsq8_get_list_sizes(h, nlist, device):
+    sizes = torch.empty(nlist, dtype=torch.int64, device=device)
+    _check(lib().vs_ivfsq8_get_list_sizes(h, _p(sizes), _stream()))
+    return sizes
+
+
+def vs_ivfsq8_get_storage(h, n, d, device):
+    ids = torch.empty(n, dtype=torch.int64, device=device)
+    list_of = torch.empty(n, dtype=torch.int32, device=device)
+    codes = torch.empty((n, d), dtype=torch.uint8, device=device)
+    _check(lib().vs_ivfsq8_get_storage(h, _p(ids), _p(list_of), _p(codes), _stream()))
+    return ids, list_of, codes
+
+
 class IVFSQ8:
-    """Owner of one vs_ivfsq8 handle (thin convenience over the C calls)."""
+    """Owner of one vs_ivfsq8 handle (thin convenience over the functions above)."""
 
     def __init__(self, d, metric, centroids, vmin, step):
         self.d, self.metric = int(d), int(metric)
         self.nlist = int(centroids.shape[0])
         self.device = centroids.device
-        centroids = _dev(centroids, torch.float32, "centroids")
-        vmin = _dev(vmin, torch.float32, "vmin")
-        step = _dev(step, torch.float32, "step")
-        if vmin.numel() != self.d or step.numel() != self.d or centroids.numel() != self.nlist * self.d:
-            raise ValueError("centroids must be [nlist, d], vmin and step [d]")
-        h = ctypes.c_void_p(0)
-        _check(lib().vs_ivfsq8_create(ctypes.byref(h), self.d, self.metric, self.nlist, _p(centroids),
-                                      _p(vmin), _p(step), _stream()))
-        self.h = h
+        self.h = vs_ivfsq8_create(self.d, self.metric, self.nlist, centroids, vmin, step)
 
     def close(self):
         if getattr(self, "h", None) is not None:
-            lib().vs_ivfsq8_destroy(self.h)
+            vs_ivfsq8_destroy(self.h)
             self.h = None
 
     def __del__(self):
@@ -492,39 +557,19 @@ class IVFSQ8:
 
     @property
     def ntotal(self):
-        return int(lib().vs_ivfsq8_ntotal(self.h))
+        return vs_ivfsq8_ntotal(self.h)
 
     def add(self, x, ids=None):
-        x = _dev(x, torch.float32, "x")
-        ids = _dev(ids, torch.int64, "ids")
-        if ids is not None and ids.numel() != x.shape[0]:
-            raise ValueError("ids must hold one id per row of x")
-        _check(lib().vs_ivfsq8_add(self.h, _p(x), x.shape[0], _p(ids), _stream()))
+        vs_ivfsq8_add(self.h, x, ids)
 
     def search(self, q, k, nprobe, out_dist=None, out_ids=None):
-        q = _dev(q, torch.float32, "q")
-        nq = q.shape[0]
-        if out_dist is None:
-            out_dist = torch.empty((nq, max(k, 0)), dtype=torch.float32, device=q.device)
-        if out_ids is None:
-            out_ids = torch.empty((nq, max(k, 0)), dtype=torch.int64, device=q.device)
-        _dev(out_dist, torch.float32, "out_dist")
-        _dev(out_ids, torch.int64, "out_ids")
-        _check(lib().vs_ivfsq8_search(self.h, _p(q), nq, k, nprobe, _p(out_dist), _p(out_ids), _stream()))
-        return out_dist, out_ids
+        return vs_ivfsq8_search(self.h, q, k, nprobe, out_dist, out_ids)
 
     def list_sizes(self):
-        sizes = torch.empty(self.nlist, dtype=torch.int64, device=self.device)
-        _check(lib().vs_ivfsq8_get_list_sizes(self.h, _p(sizes), _stream()))
-        return sizes
+        return vs_ivfsq8_get_list_sizes(self.h, self.nlist, self.device)
 
     def storage(self):
-        n = self.ntotal
-        ids = torch.empty(n, dtype=torch.int64, device=self.device)
-        list_of = torch.empty(n, dtype=torch.int32, device=self.device)
-        codes = torch.empty((n, self.d), dtype=torch.uint8, device=self.device)
-        _check(lib().vs_ivfsq8_get_storage(self.h, _p(ids), _p(list_of), _p(codes), _stream()))
-        return ids, list_of, codes
+        return vs_ivfsq8_get_storage(self.h, self.ntotal, self.d, self.device)
 
 
 class Flat:
@@ -628,6 +673,11 @@ class IVFPQ:
 
     def search(self, q, k, nprobe, out_dist=None, out_ids=None):
         return vs_ivfpq_search(self.h, q, k, nprobe, out_dist, out_ids)
+
+    def search_stats(self, q, k, nprobe):
+        """(dist, ids, stats): stats is a dict of the call's vs_search_stats (synchronises)."""
+        D, I, st = vs_ivfpq_search_stats(self.h, q, k, nprobe)
+        return D, I, dict(zip(SEARCH_STATS_FIELDS, (int(v) for v in st.tolist())))
 
     def search_static(self, q, k, nprobe, out_dist, out_ids):
         return vs_ivfpq_search_static(self.h, q, k, nprobe, out_dist, out_ids)

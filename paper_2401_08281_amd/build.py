@@ -5,6 +5,10 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvs.so")
+# the benchmark's calibration kernels (read stream, matrix-core loop, named copy): a library of
+# their own, so that libvs.so exports the search boundary and nothing else
+CALIBRATE_LIB = os.path.join(HERE, "libvs_calibrate.so")
+CALIBRATE_SOURCE = "calibrate.hip"
 SOURCES = ["api.hip", "kernels_dist.hip", "kernels_select.hip", "kernels_ivfpq.hip", "kernels_mfma.hip",
            "kernels_refine.hip", "kernels_train.hip",
            "kernels_ivfflat.hip"]
@@ -22,12 +26,26 @@ def lib_path():
     return LIB
 
 
+def calibrate_lib_path():
+    return CALIBRATE_LIB
+
+
 def is_stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS] + [os.path.abspath(__file__)]
     return any(os.path.getmtime(p) > t for p in deps)
+
+
+def build_calibrate_lib(verbose=False):
+    """Compiles and links libvs_calibrate.so (one translation unit)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + ["-shared", os.path.join(CSRC, CALIBRATE_SOURCE), "-o", CALIBRATE_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    _drain([(cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT))])
+    return CALIBRATE_LIB
 
 
 def build_lib(verbose=False, jobs=4, extra_flags=(), out=None, tag=""):
@@ -50,6 +68,8 @@ def build_lib(verbose=False, jobs=4, extra_flags=(), out=None, tag=""):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    if out is None and not tag:
+        build_calibrate_lib(verbose)
     return target
 
 

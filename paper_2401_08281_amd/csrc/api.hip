@@ -211,7 +211,10 @@ KnnPlan knn_plan_pieces(int64_t n, int64_t piece, int64_t nb, int d, int k, bool
 // what na rows need is refused here, before any kernel is launched on it.
 int knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const float* B, int64_t nb,
             int d, int metric, int k, const Planes* b_planes, const SelectOut& out, hipStream_t st,
-            int stage_dist, int stage_select) {
+            int stage_dist, int stage_select, const int** fallback_count = nullptr) {
+  // fallback_count: receives the device address of this call's count of rows that took the exact
+  // fallback (valid once the call's kernels have run), or null when the canon tiles served the call
+  if (fallback_count) *fallback_count = nullptr;
   {
     const KnnPlan need = knn_plan(na, nb, d, k, b_planes != nullptr);
     if (need.mfma != plan.mfma || (plan.mfma && need.bytes > plan.bytes))
@@ -243,6 +246,7 @@ int knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const flo
                     fb_count, fb_rows, fb_partial, st);
     }
     g_knn_mfma_rows += na;
+    if (fallback_count) *fallback_count = fb_count;
     return VS_OK;
   }
   float* mat = reinterpret_cast<float*>(ws);
@@ -984,13 +988,13 @@ int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
 // coarse quantizer: the npr best lists per query, best first, with their canon values
 static int coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
                          int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st,
-                         bool timed = true) {
+                         bool timed = true, const int** fallback_count = nullptr) {
   SelectOut out;
   out.val = cdist;
   out.idx32 = probes;
   return knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
                  ix->has_planes ? &ix->c_planes : nullptr, out, st, timed ? VS_STAGE_COARSE_DIST : -1,
-                 timed ? VS_STAGE_COARSE_SELECT : -1);
+                 timed ? VS_STAGE_COARSE_SELECT : -1, fallback_count);
 }
 
 int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t nprobe,
@@ -1053,13 +1057,19 @@ int search_check_args(const char* who, const vs_ivfpq* ix, const float* q, int64
 
 // The search itself on a work space of L.bytes at `base`: kernel launches only.
 int search_run(const char* who, const vs_ivfpq* ix, const SearchLayout& L, char* base, const float* q,
-               int64_t nq, int k, float* out_dist, int64_t* out_ids, hipStream_t st, bool timed) {
+               int64_t nq, int k, float* out_dist, int64_t* out_ids, hipStream_t st, bool timed,
+               vs_search_stats* stats = nullptr) {
   const IvfpqDims& g = ix->g;
   int32_t* probes = reinterpret_cast<int32_t*>(base + L.o_pr);
   float* cdist = reinterpret_cast<float*>(base + L.o_cd);
   u64* partial = reinterpret_cast<u64*>(base + L.o_part);
   u64* counter = reinterpret_cast<u64*>(base + L.o_cnt);
-  if (int rc = coarse_select(ix, L.plan, base + L.o_knn, q, nq, L.npr, probes, cdist, st, timed)) return rc;
+  const int* fallback_count = nullptr;
+  if (int rc = coarse_select(ix, L.plan, base + L.o_knn, q, nq, L.npr, probes, cdist, st, timed, &fallback_count))
+    return rc;
+  if (stats)
+    launch_search_stats(probes, nq * L.npr, ix->list_off, fallback_count, L.plan.mfma ? nq : 0,
+                        reinterpret_cast<long long*>(stats), st);
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
   // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
@@ -1093,6 +1103,21 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   if (int rc = ix->scratch.reserve(L.bytes)) return rc;
   return search_run("vs_ivfpq_search", ix, L, static_cast<char*>(ix->scratch.p), q, nq, k, out_dist, out_ids,
                     static_cast<hipStream_t>(hip_stream), true);
+}
+
+int vs_ivfpq_search_stats(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
+                          float* out_dist, int64_t* out_ids, vs_search_stats* stats, void* hip_stream) {
+  if (int rc = search_check_args("vs_ivfpq_search_stats", ix, q, nq, k, nprobe, out_dist, out_ids)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (nq == 0) {
+    if (stats) launch_fill_u64(reinterpret_cast<u64*>(stats), sizeof(vs_search_stats) / sizeof(u64), 0ull, st);
+    return VS_OK;
+  }
+  SearchLayout L;
+  search_layout(ix, nq, k, nprobe, &L);
+  if (int rc = ix->scratch.reserve(L.bytes)) return rc;
+  return search_run("vs_ivfpq_search_stats", ix, L, static_cast<char*>(ix->scratch.p), q, nq, k, out_dist, out_ids,
+                    st, true, stats);
 }
 
 int vs_ivfpq_search_static(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,

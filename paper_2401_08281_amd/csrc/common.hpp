@@ -171,19 +171,33 @@ struct WaveSelect {
   int tot, k, cnt;       // cnt: reservoir fill (wave-uniform)
   u64 thresh;            // k-th best key this wavefront holds (wave-uniform)
   u64 seen;              // the workgroup bound as last read by refresh_shared() (wave-uniform)
+  u64 bound;             // min(thresh, seen): what push_cached() and push_value() test against
+  float bound_f;         // the value in `bound`, in a scalar register (NaN while nothing bounds)
+  int metric;            // how push_value() orders values: 0 smaller is better, 1 larger is better
 
   // attach to existing state (slots hold k sorted keys plus cnt_ reservoir entries)
   __device__ __forceinline__ void attach(u64* slots, int tot_, int k_, int cnt_, u64 thresh_) {
     s = to_lds(slots); shared = (lds_u64_ptr)0; has_shared = false;
-    tot = tot_; k = k_; cnt = cnt_; thresh = thresh_; seen = KEY_EMPTY;
+    tot = tot_; k = k_; cnt = cnt_; thresh = thresh_; seen = KEY_EMPTY; metric = 0;
+    rebound();
   }
 
   __device__ __forceinline__ void init(u64* slots, int tot_, int k_, u64* shared_ = nullptr) {
     s = to_lds(slots); has_shared = shared_ != nullptr;
     shared = has_shared ? to_lds(shared_) : (lds_u64_ptr)0;
-    tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY; seen = KEY_EMPTY;
+    tot = tot_; k = k_; cnt = 0; thresh = KEY_EMPTY; seen = KEY_EMPTY; metric = 0;
+    rebound();
     for (int i = lane_id(); i < k; i += VS_WAVE) s[i] = KEY_EMPTY;
     wave_lds_sync();
+  }
+  // values are ordered as make_key(v, i, metric_) orders them (call right after init / attach)
+  __device__ __forceinline__ void set_metric(int metric_) { metric = metric_; rebound(); }
+  // bound and bound_f follow thresh and seen.  The value of the all-ones key is a NaN under both
+  // metrics, and no value compares greater or smaller than a NaN: nothing is rejected by it.
+  __device__ __forceinline__ void rebound() {
+    bound = seen < thresh ? seen : thresh;
+    bound_f = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+                                            __builtin_bit_cast(int, key_value(bound, metric))));
   }
 
   __device__ __forceinline__ void sort_lds() {
@@ -228,6 +242,7 @@ struct WaveSelect {
     if constexpr (R > 0) sort_regs(); else sort_lds();
     cnt = 0;
     thresh = s[k - 1];
+    rebound();
     // The k-th best key of ANY subset bounds the k-th best of the whole: publish it so
     // that sibling wavefronts reject candidates that cannot make the workgroup's top k.
     if (has_shared && lane_id() == 0 && thresh != KEY_EMPTY)
@@ -253,17 +268,24 @@ struct WaveSelect {
   // ever tightens, so an old copy is still a valid (weaker) bound, and reading it once per list
   // instead of once per push takes an LDS round trip off every push.
   __device__ __forceinline__ void refresh_shared() {
-    if (has_shared) { const u64 sh = *shared; seen = sh < seen ? sh : seen; }
+    if (has_shared) { const u64 sh = *shared; seen = sh < seen ? sh : seen; rebound(); }
   }
   __device__ __forceinline__ void push_cached(bool valid, u64 key) {
-    const u64 th = seen < thresh ? seen : thresh;
-    bool pass = valid && key < th;
+    bool pass = valid && key < bound;
     u64 mask = __ballot(pass);
     if (mask == 0) return;
     int pos = k + cnt + __popcll(mask & ((1ull << lane_id()) - 1ull));
     if (pass) s[pos] = key;
     cnt += __popcll(mask);
     if (k + cnt + VS_WAVE > tot) { trim(); refresh_shared(); }
+  }
+  // push_cached(valid, make_key(v, idx, metric)) with a cheaper way out for the usual case that no
+  // lane holds a candidate: a key below the bound has a value that is not worse than the bound's,
+  // so one float compare against a scalar rejects a whole wavefront before any key is formed.
+  __device__ __forceinline__ void push_value(bool valid, float v, u32 idx) {
+    const bool maybe = valid && (metric ? !(v < bound_f) : !(v > bound_f));
+    if (__ballot(maybe) == 0) return;
+    push_cached(valid, make_key(v, idx, metric));
   }
 
   // After finish(), slots [0, k) hold the k best keys in ascending order.

@@ -82,6 +82,11 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 constexpr int kWaveScanMaxMeanList = 1024;
 bool ivfpq_wave_scan_applies(const IvfpqDims& g, int64_t ntotal);
 size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq);
+// stats[0] = sum over the n (query, probe) pairs of the probed list's size, stats[1] = pairs whose
+// list is not empty, stats[2] = mfma_rows, stats[3] = *fallback_count (0 if null); device memory,
+// written in stream order.
+void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
+                         int64_t mfma_rows, long long* stats, hipStream_t st);
 // out [nlist][K][M]: |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>, the per-list term of the split look-up tables
 void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
                            hipStream_t st);

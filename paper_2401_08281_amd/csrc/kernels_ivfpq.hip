@@ -680,8 +680,8 @@ void ivfpq_scan_bank_kernel(
   float* s_bias = reinterpret_cast<float*>(s_list + ppb);       // ppb (inner product / stored norms)
   int* s_nl = reinterpret_cast<int*>(bound + 2);                // how many of them
   unsigned long long* s_item = reinterpret_cast<unsigned long long*>(bound + 1);
-  const bool lut_at_zero = (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u;
-
+  // (the kernel has no static LDS, so its dynamic LDS -- the tables first -- starts at LDS address
+  // 0 and a table offset is an LDS address: the launcher checks this)
   const int tid = threadIdx.x, wave = tid >> 6;
   const int m_own = tid & (M - 1), jg = tid / M;                // table build: codewords jg * EPL + i of m_own
   const int rep0 = jg & (REP - 1);                              // this lane's copy (build: the first it stores)
@@ -739,6 +739,7 @@ void ivfpq_scan_bank_kernel(
 
     WaveSelect<R> ws;
     ws.init(slots + wave * tot, tot, k, bound);
+    ws.set_metric(KEY_METRIC);
     if (tid == 0) *bound = KEY_EMPTY;
     // the item's probes and list extents: wavefront 0 fetches them 64 at a time and keeps the
     // non-empty lists, in probe order
@@ -940,11 +941,10 @@ void ivfpq_scan_bank_kernel(
       float dist = 0.f;
       if (valid) {
         const float d0 = METRIC == 2 ? bias + nrm : bias;
-        dist = lut_at_zero ? cw.template adc_banked<true>(smem, col, d0)
-                           : cw.template adc_banked<false>(smem, col, d0);
+        dist = cw.template adc_banked<true>(smem, col, d0);
       }
       if (METRIC != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
-      ws.push_cached(valid, make_key(dist, i, KEY_METRIC));
+      ws.push_value(valid, dist, i);
       base_c += NT;
       if (base_c >= ce) {
         ++pc;
@@ -1055,7 +1055,8 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);
   float* s_bias = reinterpret_cast<float*>(s_list + ppb);
 
-  const bool lut_at_zero = (u32)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem) == 0u;
+  // (no static LDS: the table starts at LDS address 0 and a table offset is an LDS address; the
+  // launcher checks this)
   const int lane = threadIdx.x;
   const int64_t item = blockIdx.x;
   const int64_t qi = item / nsplit;
@@ -1078,6 +1079,7 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
   }
   WaveSelect<R> ws;
   ws.init(slots, tot, k);
+  ws.set_metric(KEY_METRIC);
   int nl = 0;
   for (int p0 = 0; p0 < np; p0 += VS_WAVE) {   // the item's non-empty lists, in probe order
     const int p = p0 + lane;
@@ -1170,12 +1172,10 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
     for (int t = 0; t < M; ++t) {
       constexpr u32 sel0 = 0x0c0c0400u;   // byte 1 = byte (t & 3) of the code word, byte 0 = of col
       const u32 a = __builtin_amdgcn_perm(cw.word(t >> 2), col[t >> 2], sel0 + 0x101u * (t & 3)) >> kShift;
-      // (the table sits at LDS address 0 when the kernel has no static LDS: then the offset is the address)
-      if (lut_at_zero) dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)a);
-      else dist += *reinterpret_cast<const float*>(smem + a);
+      dist += *reinterpret_cast<lds_cfloat_ptr>((uintptr_t)a);
     }
     if (MODE != 1) dist = fmaxf(dist, 0.f);   // a squared distance: the expanded square can round below zero
-    ws.push(valid, make_key(dist, i, KEY_METRIC));
+    ws.push_value(valid, dist, i);
     first = npl != pl;
     pl = npl; base = nbase; end = nend;
     if (pl < nl) { cw = nx; nrm = nrm_nx; }
@@ -1217,6 +1217,34 @@ __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__
 }
 
 }  // namespace
+
+// What one search scanned: list sizes summed over its (query, probe) pairs.  stats was zeroed in
+// stream order before this launch.
+__global__ __launch_bounds__(256) void search_stats_kernel(const int32_t* __restrict__ probes, int64_t n,
+                                                           const int64_t* __restrict__ list_off,
+                                                           const int* __restrict__ fallback_count,
+                                                           int64_t mfma_rows, unsigned long long* __restrict__ stats) {
+  unsigned long long codes = 0, lists = 0;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int l = probes[i];
+    if (l < 0) continue;
+    const unsigned long long sz = (unsigned long long)(list_off[l + 1] - list_off[l]);
+    codes += sz;
+    lists += sz > 0 ? 1ull : 0ull;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    codes += __shfl_down(codes, o, 64);
+    lists += __shfl_down(lists, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (codes) atomicAdd(&stats[0], codes);
+    if (lists) atomicAdd(&stats[1], lists);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    stats[2] = (unsigned long long)mfma_rows;
+    stats[3] = fallback_count ? (unsigned long long)*fallback_count : 0ull;
+  }
+}
 
 // ------------------------------------------------------------------ launchers
 
@@ -1309,6 +1337,14 @@ void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_
   hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, d, norms);
 }
 
+void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
+                         int64_t mfma_rows, long long* stats, hipStream_t st) {
+  launch_fill_u64(reinterpret_cast<u64*>(stats), 4, 0ull, st);
+  const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(1024, (n + 255) / 256));
+  hipLaunchKernelGGL(search_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, st, probes, n, list_off,
+                     fallback_count, mfma_rows, reinterpret_cast<unsigned long long*>(stats));
+}
+
 void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
                            hipStream_t st) {
   const int64_t n = (int64_t)g.nlist * g.K * g.M;
@@ -1328,8 +1364,15 @@ void launch_list_sizes(const int64_t* off, int nlist, int64_t* sizes, hipStream_
                      nlist, sizes);
 }
 
+// A kernel without static LDS has its dynamic LDS at LDS address 0, which the bank-private and the
+// wavefront-private scans rely on (a table offset is used as an LDS address).
+static bool dynamic_lds_starts_at_zero(const void* kernel) {
+  hipFuncAttributes attr;
+  return hipFuncGetAttributes(&attr, kernel) == hipSuccess && attr.sharedSizeBytes == 0;
+}
+
 template <int M, int DSUB, int METRIC, int R>
-static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+static int launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
                              const float* codebooks, const int32_t* probes, const float* cdist,
                              int nprobe, int ppb, int nsplit, const int64_t* list_off,
                              const uint8_t* codes, const float* norms, const float* cnorm,
@@ -1338,6 +1381,8 @@ static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, con
   const size_t shmem = bank_scan_lds_bytes(tot, ppb);
   constexpr int NT = kBankThreads;
   auto kern = &ivfpq_scan_bank_kernel<M, DSUB, METRIC, R, NT>;
+  static const bool at_zero = dynamic_lds_starts_at_zero(reinterpret_cast<const void*>(kern));
+  if (!at_zero) return -1;
   if (shmem > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -1351,10 +1396,11 @@ static void launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, con
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), shmem, st, q, centroids, codebooks,
                      probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, list_tables,
                      ntotal, k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
+  return 0;
 }
 
 template <int M, int DSUB>
-static void launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
+static int launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
                                  const float* centroids, const float* codebooks,
                                  const int32_t* probes, const float* cdist, int nprobe, int ppb,
                                  int nsplit, const int64_t* list_off, const uint8_t* codes,
@@ -1362,8 +1408,8 @@ static void launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
                                  int mode, int64_t ntotal, int k, int tot, KeySink sink, u64* counter,
                                  hipStream_t st) {
 #define GO(MET, RR)                                                                               \
-  launch_scan_bank<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,  \
-                                     nsplit, list_off, codes, norms, cnorm, list_tables, ntotal, k, tot, sink, counter, st)
+  return launch_scan_bank<M, DSUB, MET, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,  \
+                                            nsplit, list_off, codes, norms, cnorm, list_tables, ntotal, k, tot, sink, counter, st)
   const int r = tot <= 128 ? 2 : (tot <= 256 ? 4 : 0);   // register-sort width covering the slots
   if (mode == 1)      { if (r == 2) GO(1, 2); else if (r == 4) GO(1, 4); else GO(1, 0); }
   else if (mode == 2) { if (r == 2) GO(2, 2); else if (r == 4) GO(2, 4); else GO(2, 0); }
@@ -1380,7 +1426,7 @@ static size_t wave_scan_lds_bytes(const IvfpqDims& g, int tot, int ppb) {
   return (size_t)g.K * g.M * sizeof(float) + (size_t)tot * sizeof(u64) + (size_t)ppb * 16;
 }
 template <int M, int DSUB, int MODE>
-static void launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, const float* codebooks,
+static int launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, const float* codebooks,
                              float* query_tables, const float* list_tables, const int32_t* probes,
                              const float* cdist, int nprobe, int ppb, int nsplit, const int64_t* list_off,
                              const uint8_t* codes, const float* norms, const float* cnorm, int64_t ntotal,
@@ -1394,6 +1440,8 @@ static void launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, con
 #define GO(RR)                                                                                        \
   do {                                                                                                \
     auto kern = &ivfpq_scan_wave_kernel<M, MODE, RR>;                                                 \
+    static const bool at_zero = dynamic_lds_starts_at_zero(reinterpret_cast<const void*>(kern));      \
+    if (!at_zero) return -1;                                                                          \
     if (shmem > 48 * 1024)                                                                            \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);              \
@@ -1403,6 +1451,7 @@ static void launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, con
   const int r = select_regs_for_slots(tot);
   if (r == 2) GO(2); else if (r == 4) GO(4); else GO(0);
 #undef GO
+  return 0;
 }
 
 template <int NBITS, int R, int W16>
@@ -1461,21 +1510,19 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   if (mode != 0 && query_tables && ivfpq_wave_scan_applies(g, ntotal)) {
     if (wave_scan_lds_bytes(g, select_slots_for_k(k), ppb) > 160 * 1024) return -1;
 #define WAVE(MM, DS, MODE)                                                                             \
-  launch_scan_wave<MM, DS, MODE>(g, q, nq, codebooks, query_tables, list_tables, probes, cdist, nprobe, \
+  return launch_scan_wave<MM, DS, MODE>(g, q, nq, codebooks, query_tables, list_tables, probes, cdist, nprobe, \
                                  ppb, nsplit, list_off, codes, norms, cnorm, ntotal, k, sink, st)
     if (g.M == 16) { if (mode == 1) WAVE(16, 8, 1); else if (mode == 2) WAVE(16, 8, 2); else WAVE(16, 8, 3); }
     else           { if (mode == 1) WAVE(8, 4, 1); else if (mode == 2) WAVE(8, 4, 2); else WAVE(8, 4, 3); }
 #undef WAVE
-    return 0;
   }
   if (ivfpq_codes_rotated(g)) {   // (the stored codes are rotated: no other kernel reads them)
     const int btot = bank_slots_for_k(k, ppb);
     if (bank_scan_lds_bytes(btot, ppb) > 160 * 1024) return -1;
 #define BANK(MM, DS)                                                                              \
   if (g.M == MM && g.dsub == DS) {                                                                \
-    launch_scan_bank_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb,      \
-                                 nsplit, list_off, codes, norms, cnorm, list_tables, mode, ntotal, k, btot, sink, counter, st); \
-    return 0;                                                                                     \
+    return launch_scan_bank_any<MM, DS>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, ppb, \
+                                        nsplit, list_off, codes, norms, cnorm, list_tables, mode, ntotal, k, btot, sink, counter, st); \
   }
     BANK(16, 8)   // PQ16x8 on d = 128
     BANK(32, 3)   // PQ32x8 on d = 96

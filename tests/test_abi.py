@@ -22,12 +22,34 @@ def declared_symbols():
     return re.findall(r"VS_API\s+[\w\s\*]+?\b(vs_\w+)\s*\(", text)
 
 
+# The boundary, name by name.  The paper's interface (App. A.1 "add / search", Sec. 5.1 inverted
+# lists, Sec. 4.1 / 4.3 training, Sec. 3.2 refinement) as this library exports it.
+BOUNDARY = """
+vs_flat_search vs_flat_create vs_flat_destroy vs_flat_ntotal vs_flat_add vs_flat_index_search
+vs_trim vs_refine vs_kmeans vs_ivfpq_train
+vs_ivfpq_create vs_ivfpq_add vs_ivfpq_search vs_ivfpq_search_stats vs_ivfpq_search_static vs_ivfpq_destroy
+vs_ivfpq_ntotal vs_ivfpq_code_size vs_ivfpq_get_list_sizes vs_ivfpq_get_assignments vs_ivfpq_get_codes
+vs_ivfpq_coarse vs_ivfpq_set_search_type vs_ivfpq_get_norms
+vs_ivfflat_create vs_ivfflat_destroy vs_ivfflat_ntotal vs_ivfflat_add vs_ivfflat_search
+vs_ivfflat_get_list_sizes vs_ivfflat_get_storage
+vs_ivfsq8_create vs_ivfsq8_destroy vs_ivfsq8_ntotal vs_ivfsq8_add vs_ivfsq8_search
+vs_ivfsq8_get_list_sizes vs_ivfsq8_get_storage
+vs_profile_enable vs_profile_read vs_set_option vs_counters_read vs_knn_workspace_bytes
+vs_last_error vs_version
+""".split()
+
+
 def test_header_declares_the_boundary():
+    """The header declares exactly the boundary: nothing missing, nothing extra, nothing twice."""
     names = declared_symbols()
-    for must in ("vs_flat_search", "vs_ivfpq_create", "vs_ivfpq_add", "vs_ivfpq_search",
-                 "vs_ivfpq_destroy", "vs_last_error"):
-        assert must in names
-    assert len(names) == len(set(names)) >= 13
+    assert len(names) == len(set(names))
+    assert sorted(names) == sorted(BOUNDARY)
+
+
+def test_binding_has_a_function_of_the_same_name_for_every_entry_point():
+    import paper_2401_08281_amd as vs
+    for name in BOUNDARY:
+        assert callable(getattr(vs, name, None)), name
 
 
 def test_library_exports_every_declared_symbol(L):
@@ -123,6 +145,8 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert h.value is None
     assert L.vs_ivfpq_add(nul, one, 5, nul, nul) == INVALID
     assert L.vs_ivfpq_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
+    assert L.vs_ivfpq_search_stats(nul, one, 5, 10, 4, one, one, one, nul) == INVALID
+    assert L.vs_ivfpq_search_static(nul, one, 5, 10, 4, one, one, nul) == INVALID
     assert L.vs_ivfpq_ntotal(nul) == -1 and L.vs_ivfpq_code_size(nul) == -1
     L.vs_ivfpq_destroy(nul)                                                           # allowed
 
