@@ -293,8 +293,10 @@ VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32
  * with |x'|^2 stored next to every code as a float32 (4 more bytes per vector): one table of
  * inner products per QUERY, no per-list table; the result differs from the default form by
  * the rounding of the cancelling terms, about 2^-22 (|q|^2 + |x'|^2).
- * Set it before the first add: vs_ivfpq_add computes the norms only while it is selected
- * (an index that already holds vectors without norms refuses VS_ST_STORED_NORMS).
+ * vs_ivfpq_add computes the norms of what it adds only while this type is selected (adding
+ * under another type drops the stored norms); selecting it on an index that holds vectors
+ * without norms computes them from the stored codes (ntotal * (code_size + 8) bytes of
+ * temporary device memory; VS_ERR_OOM if that does not fit) and synchronises.
  * VS_ST_PRECOMPUTED_TABLES (L2 only): the same table per (query, probed list) as the default,
  * but formed as the sum of a term that depends on the query alone, -2 <q_m, T_m[j]> (computed
  * once per query), and a term that depends on the list alone, |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>

@@ -956,8 +956,38 @@ int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type) {
     return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: unknown search type %d", search_type);
   if (search_type != VS_ST_RESIDUAL_TABLES && ix->g.metric != VS_METRIC_L2)
     return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: stored norms and precomputed tables serve the L2 metric only");
-  if (ix->ntotal > 0 && search_type == VS_ST_STORED_NORMS && !ix->norms)
-    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_search_type: the index already holds vectors without norms");
+  if (ix->ntotal > 0 && search_type == VS_ST_STORED_NORMS && !ix->norms) {
+    // the index holds vectors without norms: compute them from the stored codes, with the kernel
+    // that vs_ivfpq_add uses (it takes codes in their canonical byte order and the list of each)
+    const IvfpqDims& g = ix->g;
+    const int64_t n = ix->ntotal;
+    const bool rotated = ivfpq_codes_rotated(g);
+    float* norms = nullptr;
+    int32_t* list_of = nullptr;
+    uint8_t* canon = nullptr;
+    auto release = [&] {
+      if (list_of) (void)hipFree(list_of);
+      if (canon) (void)hipFree(canon);
+    };
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&norms), (size_t)n * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&list_of), (size_t)n * sizeof(int32_t));
+    if (e == hipSuccess && rotated) e = hipMalloc(reinterpret_cast<void**>(&canon), (size_t)n * g.code_size);
+    if (e == hipSuccess) {
+      launch_list_of_storage(ix->list_off, g.nlist, n, list_of, nullptr);
+      if (rotated) launch_codes_canonical(g, ix->codes, ix->list_off, n, canon, nullptr);
+      launch_pq_norms(g, rotated ? canon : ix->codes, n, list_of, ix->centroids, ix->codebooks, norms, nullptr,
+                      true);
+      e = hipStreamSynchronize(nullptr);
+      if (e == hipSuccess) e = hipGetLastError();
+    }
+    release();
+    if (e != hipSuccess) {
+      if (norms) (void)hipFree(norms);
+      return fail(e == hipErrorOutOfMemory ? VS_ERR_OOM : VS_ERR_DEVICE, "vs_ivfpq_set_search_type: %s",
+                  hipGetErrorString(e));
+    }
+    ix->norms = norms;
+  }
   if (search_type == VS_ST_PRECOMPUTED_TABLES && !ix->list_tables) {
     const IvfpqDims& g = ix->g;
     if (!ivfpq_codes_rotated(g))

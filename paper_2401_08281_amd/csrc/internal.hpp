@@ -58,10 +58,12 @@ void launch_relayout(const IvfpqDims& g, const uint8_t* old_codes, const int64_t
 bool ivfpq_codes_rotated(const IvfpqDims& g);
 void launch_codes_canonical(const IvfpqDims& g, const uint8_t* stored, const int64_t* off,
                             int64_t total, uint8_t* out, hipStream_t st);
-// tmp_norms[i] = |c_list(i) + decoded code i|^2 (tmp_codes: one byte per (vector, m))
+// tmp_norms[i] = |c_list(i) + decoded code i|^2.  tmp_codes: one byte per (vector, m) as the encoder
+// writes them; stored_form: code_size bytes per vector as the lists hold them (4-bit codes packed
+// two per byte; byte order canonical, not rotated)
 void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
                      const float* centroids, const float* codebooks, float* tmp_norms,
-                     hipStream_t st);
+                     hipStream_t st, bool stored_form = false);
 // norms[i] = |row i|^2 (fma chain in dimension order)
 void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_t st);
 void launch_list_of_storage(const int64_t* off, int nlist, int64_t total, int32_t* list_of,

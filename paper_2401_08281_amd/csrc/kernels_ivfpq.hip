@@ -93,9 +93,10 @@ __global__ __launch_bounds__(256) void pq_encode_global_kernel(
 // Squared norm of the decoded vector x' = c_list + concat_m T_m[c_m] of every new entry
 // (Sec. 4.3: the norm stored next to the code for the decomposition |q|^2 + |x'|^2 - 2<q,x'>):
 // one fp32 addition per component, squares accumulated by one fma chain in dimension order.
-// One lane per vector; tmp_codes holds one byte per (vector, m).
+// One lane per vector; tmp_codes holds one byte per (vector, m), or -- packed4 -- the stored form of
+// 4-bit codes, two per byte (byte i = c_{2i} | c_{2i+1} << 4).
 __global__ void pq_norms_kernel(const uint8_t* __restrict__ tmp_codes, int64_t n, int d, int dsub,
-                                int K, int M, const int32_t* __restrict__ list_of,
+                                int K, int M, bool packed4, const int32_t* __restrict__ list_of,
                                 const float* __restrict__ centroids,
                                 const float* __restrict__ codebooks, float* __restrict__ tmp_norms) {
   const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
@@ -103,7 +104,8 @@ __global__ void pq_norms_kernel(const uint8_t* __restrict__ tmp_codes, int64_t n
   const float* __restrict__ c = centroids + (int64_t)list_of[i] * d;
   float acc = 0.f;
   for (int m = 0; m < M; ++m) {
-    const float* __restrict__ T = codebooks + ((int64_t)m * K + tmp_codes[i * M + m]) * dsub;
+    const int cm = packed4 ? (tmp_codes[i * (M / 2) + (m >> 1)] >> (4 * (m & 1))) & 15 : tmp_codes[i * M + m];
+    const float* __restrict__ T = codebooks + ((int64_t)m * K + cm) * dsub;
     for (int u = 0; u < dsub; ++u) {
       const float xt = c[m * dsub + u] + T[u];
       acc = __builtin_fmaf(xt, xt, acc);
@@ -1326,10 +1328,11 @@ void launch_codes_canonical(const IvfpqDims& g, const uint8_t* stored, const int
 
 void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, const int32_t* list_of,
                      const float* centroids, const float* codebooks, float* tmp_norms,
-                     hipStream_t st) {
+                     hipStream_t st, bool stored_form) {
   if (n <= 0) return;
   hipLaunchKernelGGL(pq_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, tmp_codes,
-                     n, g.d, g.dsub, g.K, g.M, list_of, centroids, codebooks, tmp_norms);
+                     n, g.d, g.dsub, g.K, g.M, stored_form && g.nbits == 4, list_of, centroids, codebooks,
+                     tmp_norms);
 }
 
 void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_t st) {

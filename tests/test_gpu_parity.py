@@ -1,5 +1,6 @@
 """Parity of the HIP path (through the C ABI) against the CPU oracle, on the
 same seeded inputs.  Needs a real MI355X."""
+import os
 import sys
 import zlib
 
@@ -14,9 +15,20 @@ pytestmark = pytest.mark.gpu
 L2, IP = 0, 1
 
 
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "progress.log")
+
+
 def say(msg):
+    """Names the case before it runs: on stdout (shown for a failing test) and, because pytest holds
+    stdout back while a test runs, also in a log file that grows with the work done."""
     print("[case] " + msg, flush=True)
     sys.stdout.flush()
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS), exist_ok=True)
+        with open(_PROGRESS, "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
 
 
 @pytest.fixture(scope="module")
@@ -372,6 +384,32 @@ def test_search_is_deterministic(vs):
 
 # ------------------------------------------------- full-size configurations
 
+def test_search_stats_count_what_the_search_read(vs):
+    """vs_ivfpq_search_stats: same results as vs_ivfpq_search, and a block that adds up the sizes
+    of the probed lists (from the library's own probes and list sizes)."""
+    cfg = S.config("C3", nb=60_000, nq=333, ncomp=100, nlist=300)      # some lists stay empty
+    say("ivfpq search stats nb=%d nlist=%d" % (cfg["nb"], cfg["nlist"]))
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x[:30_000]))
+    sizes = host(ix.list_sizes())
+    for k, nprobe in ((10, 1), (10, 17), (100, 300), (10, 1000)):
+        D, I = ix.search(dev(q), k, nprobe)
+        D2, I2, st = ix.search_stats(dev(q), k, nprobe)
+        np.testing.assert_array_equal(host(D2), host(D)); np.testing.assert_array_equal(host(I2), host(I))
+        probes, _ = ix.coarse(dev(q), nprobe)
+        sz = sizes[host(probes)]
+        assert st["scanned_codes"] == int(sz.sum()) and st["probed_lists"] == int((sz > 0).sum())
+        assert st["coarse_rows_matrix_core"] in (0, cfg["nq"])
+        assert 0 <= st["coarse_rows_fallback"] <= st["coarse_rows_matrix_core"]
+    import torch
+    empty = torch.empty((0, cfg["d"]), dtype=torch.float32, device="cuda")
+    _, _, st = ix.search_stats(empty, 10, 4)
+    assert all(v == 0 for v in st.values())
+    ix.close()
+
+
 def test_c3_full_size_sampled(vs, oracle):
     """IVF4096,PQ16x8 on 1M vectors in the launch configuration the bench times.
     The oracle cannot add 1M vectors in seconds, so assignments and codes are checked
@@ -388,7 +426,7 @@ def test_c3_full_size_sampled(vs, oracle):
     sizes = host(ix.list_sizes())
     assert sizes.sum() == cfg["nb"] and (np.sort(ids) == np.arange(cfg["nb"])).all()
     rng = np.random.default_rng(5)
-    sample = np.sort(rng.choice(cfg["nb"], 4000, replace=False))
+    sample = np.sort(rng.choice(cfg["nb"], 20_000, replace=False))
     say("  oracle assign + encode on %d sampled vectors" % sample.size)
     lo = oracle.assign(x[sample], cent, L2)
     co = oracle.pq_encode(x[sample], lo, cent, cb, 8)
@@ -399,13 +437,22 @@ def test_c3_full_size_sampled(vs, oracle):
     orc = oracle.OracleIVFPQ.from_storage(cfg["d"], L2, cent, cb, 8, offsets, codes, ids)
     qs = np.sort(rng.choice(cfg["nq"], 200, replace=False))
     dq = dev(q)
-    for nprobe in (1, 16, 64):
-        say("  search all %d queries, nprobe=%d; oracle on %d of them" % (cfg["nq"], nprobe, qs.size))
-        D, I = ix.search(dq, 10, nprobe)
-        Do, Io = orc.search(q[qs], 10 + EXTRA, nprobe)
+    for k, nprobe in ((10, 1), (10, 16), (10, 64), (100, 64)):
+        say("  search all %d queries, k=%d nprobe=%d; oracle on %d of them" % (cfg["nq"], k, nprobe, qs.size))
+        D, I = ix.search(dq, k, nprobe)
+        Do, Io = orc.search(q[qs], k + EXTRA, nprobe)
         _, co = oracle.coarse_probe(q[qs], cent, nprobe, L2)
         tc, te = l2_table_cancel(co, cb)
         check_search(host(D)[qs], host(I)[qs], Do, Io, L2, cancel=tc, cancel_eps=te)
+    # the other two search types on the same store, at the widest setting (Sec. 4.3)
+    cancel = (q[qs].astype(np.float64) ** 2).sum(1) + float((cent.astype(np.float64) ** 2).sum(1).max()) + \
+        float((cb.astype(np.float64) ** 2).sum(2).max(1).sum())
+    Do, Io = orc.search(q[qs], 100 + EXTRA, 64)
+    for st in (vs.ST_STORED_NORMS, vs.ST_PRECOMPUTED_TABLES):
+        say("  search type %d, k=100 nprobe=64" % st)
+        ix.set_search_type(st)
+        D, I = ix.search(dq, 100, 64)
+        check_search(host(D)[qs], host(I)[qs], Do, Io, L2, cancel=cancel)
     ix.close()
 
 
@@ -509,11 +556,12 @@ def test_matrix_core_route_equals_canon_route(vs, oracle, name, nb, nq, d, k, me
     check_search(Dm, Im, Do, Io, metric, q, xn)
 
 
-def test_random_route_shapes_agree(vs):
+def test_random_route_shapes_agree(vs, oracle):
     """Forty seeded shapes over every d class of the matrix-core kernels (register-stationary and
     tiled, up to 2048), ragged and tiny B, k from 1 to 150, the three operand-precision variants
     and data with a large common offset: the matrix-core route returns what the canon tiles
-    return, bit for bit (the canon route itself is checked against the oracle above)."""
+    return, bit for bit, and both agree with the oracle on the shape's queries (on a seeded
+    sub-sample of them where nb * nq * d is large)."""
     import torch
     rng = np.random.default_rng(20241127)
     try:
@@ -545,6 +593,12 @@ def test_random_route_shapes_agree(vs):
             assert rows == nq
             np.testing.assert_array_equal(host(Im), host(Ic))
             np.testing.assert_array_equal(host(Dm), host(Dc))
+            nqs = int(max(1, min(nq, 4e8 // (nb * d))))
+            qs = np.sort(rng.choice(nq, nqs, replace=False))
+            xh, qh = host(x), host(q)[qs]
+            Do, Io = oracle.flat_search(xh, qh, min(k + EXTRA, max(nb, k)), metric)
+            xn = np.sqrt((xh.astype(np.float64) ** 2).sum(1).max())
+            check_search(host(Dm)[qs], host(Im)[qs], Do, Io, metric, qh, xn)
     finally:
         vs.vs_set_option("knn_path", 0)
 
@@ -798,14 +852,44 @@ def test_stored_norm_search_on_integer_data_is_exact(vs, oracle):
     ix.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "pq4_l2", "c4_small", "odd_shapes"])
+def test_stored_norms_of_an_index_filled_under_another_search_type(vs, oracle, name):
+    """Selecting the stored-norm search on an index that holds vectors without norms computes them
+    from the stored codes (rotated or not): bit for bit the oracle's norms, and they survive
+    switching back and forth; an add under another search type drops them and a new selection
+    brings all of them back."""
+    cfg, searches = IVF_CASES[name]
+    say("norms of a filled index: %s" % name)
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), cfg["nbits"])
+    orc = oracle.OracleIVFPQ(cfg["d"], L2, cent, cb, cfg["nbits"])
+    half = cfg["nb"] // 2
+    ix.add(dev(x[:half])); orc.add(x[:half])
+    ix.set_search_type(vs.ST_STORED_NORMS)                        # vectors were added without norms
+    np.testing.assert_array_equal(host(ix.norms()), orc.norms)
+    k, nprobe = searches[0]
+    D1, I1 = [host(t).copy() for t in ix.search(dev(q), k, nprobe)]
+    ix.set_search_type(vs.ST_RESIDUAL_TABLES)
+    ix.add(dev(x[half:])); orc.add(x[half:])                      # drops the norms
+    with pytest.raises(vs.VSError):
+        ix.norms()
+    ix.set_search_type(vs.ST_STORED_NORMS)
+    check_storage(ix, orc)
+    np.testing.assert_array_equal(host(ix.norms()), orc.norms)
+    cancel = (q.astype(np.float64) ** 2).sum(1) + float(orc.norms.max())
+    D, I = [host(t) for t in ix.search(dev(q), k, nprobe)]
+    Do, Io = orc.search(q, k + EXTRA, nprobe)
+    check_search(D, I, Do, Io, L2, cancel=cancel)
+    ix.close()
+
+
 def test_stored_norm_search_type_rules(vs):
     cfg = S.config("C1", nb=500)
     x, q = S.make_data(cfg)
     cent, cb = S.make_index_params(cfg, x)
     ix = vs.IVFPQ(32, L2, dev(cent), dev(cb), 8)
     ix.add(dev(x))
-    with pytest.raises(vs.VSError):
-        ix.set_search_type(vs.ST_STORED_NORMS)                    # vectors were added without norms
     with pytest.raises(vs.VSError):
         ix.set_search_type(7)
     ix.close()
@@ -1175,8 +1259,8 @@ def _large_config_sampled(vs, oracle, name, n_sample, n_queries, searches):
 
 
 def test_c4_full_size_sampled(vs, oracle):
-    _large_config_sampled(vs, oracle, "C4", 1500, 100, [(100, 64)])
+    _large_config_sampled(vs, oracle, "C4", 20_000, 1000, [(100, 64)])
 
 
 def test_c5_full_size_sampled(vs, oracle):
-    _large_config_sampled(vs, oracle, "C5", 500, 100, [(10, 32)])
+    _large_config_sampled(vs, oracle, "C5", 20_000, 1000, [(10, 32)])
