@@ -11,7 +11,7 @@ CALIBRATE_LIB = os.path.join(HERE, "libvs_calibrate.so")
 CALIBRATE_SOURCE = "calibrate.hip"
 SOURCES = ["api.hip", "kernels_dist.hip", "kernels_select.hip", "kernels_ivfpq.hip", "kernels_mfma.hip",
            "kernels_refine.hip", "kernels_train.hip",
-           "kernels_ivfflat.hip"]
+           "kernels_ivfflat.hip", "kernels_place.hip"]
 HEADERS = ["common.hpp", "internal.hpp", os.path.join("..", "..", "include", "vs.h")]
 
 FLAGS = [

@@ -819,7 +819,7 @@ namespace {
 // grown list-contiguous storage (device), the grown offsets (device and host), and `extra`
 // bytes of scratch for the caller.  Steps: (1) best centroid on the canon chain, ties to the
 // smaller list; (2) stable placement -- the new entries of a list follow its old ones, in the
-// order given (bookkeeping on the host: one pass over n list numbers).
+// order given (a stable sort of the batch by list on the device: launch_ivf_place).
 struct Placement {
   int32_t* list_of = nullptr;
   int64_t* dest = nullptr;
@@ -831,8 +831,9 @@ struct Placement {
 int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, Placement* pl,
                          hipStream_t st, const char* who) {
   const IvfpqDims& g = ix->g;
+  if (n >= (1ll << 31)) return fail(VS_ERR_UNSUPPORTED, "%s: at most 2^31 - 1 vectors per call", who);
   // scratch: work space of the MFMA assignment (pieces of at most kAssignPiece vectors) |
-  // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets
+  // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets | work space of the placement
   constexpr int64_t kAssignPiece = 1 << 20;
   KnnPlan plan = knn_plan_pieces(n, kAssignPiece, g.nlist, g.d, 1, ix->has_planes);
   if (!plan.mfma) plan.bytes = 0;
@@ -843,6 +844,7 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
   const size_t o_extra = cv.take(extra);
   const size_t o_dest = cv.take((size_t)n * sizeof(int64_t));
   const size_t o_off = cv.take(((size_t)g.nlist + 1) * sizeof(int64_t));
+  const size_t o_place = cv.take(ivf_place_work_bytes(n, g.nlist));
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
   u64* keys = reinterpret_cast<u64*>(base + o_keys);
@@ -866,27 +868,19 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
     launch_keys_to_index32(keys, n, pl->list_of, st);
   }
 
-  std::vector<int32_t> h_list((size_t)n);
-  HIP_TRY(hipMemcpyAsync(h_list.data(), pl->list_of, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  std::vector<int64_t> add_cnt((size_t)g.nlist, 0);
-  for (int64_t i = 0; i < n; ++i) {
-    const int32_t l = h_list[(size_t)i];
-    if (l < 0 || l >= g.nlist) return fail(VS_ERR_DEVICE, "%s: assignment kernel produced list %d", who, l);
-    ++add_cnt[(size_t)l];
-  }
+  // slots in the grown lists: a stable sort of the batch by list, on the device; only the new
+  // offsets (nlist + 1 numbers) and one flag come back to the host
+  int* bad = launch_ivf_place(pl->list_of, n, g.nlist, ix->list_off, base + o_place, pl->dest, pl->new_off, st);
   pl->h_new.assign((size_t)g.nlist + 1, 0);
-  std::vector<int64_t> cursor((size_t)g.nlist);
-  for (int l = 0; l < g.nlist; ++l) {
-    const int64_t old_sz = ix->h_off[(size_t)l + 1] - ix->h_off[(size_t)l];
-    pl->h_new[(size_t)l + 1] = pl->h_new[(size_t)l] + old_sz + add_cnt[(size_t)l];
-    cursor[(size_t)l] = pl->h_new[(size_t)l] + old_sz;
-  }
-  std::vector<int64_t> h_dest((size_t)n);
-  for (int64_t i = 0; i < n; ++i) h_dest[(size_t)i] = cursor[(size_t)h_list[(size_t)i]]++;
-  HIP_TRY(hipMemcpyAsync(pl->dest, h_dest.data(), (size_t)n * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(pl->new_off, pl->h_new.data(), pl->h_new.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipStreamSynchronize(st));   // h_dest and h_list leave scope
+  int h_bad = 0;
+  HIP_TRY(hipMemcpyAsync(pl->h_new.data(), pl->new_off, pl->h_new.size() * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(&h_bad, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipGetLastError());
+  if (h_bad) return fail(VS_ERR_DEVICE, "%s: the assignment kernel produced a list outside [0, %d)", who, g.nlist);
+  if (pl->h_new[(size_t)g.nlist] != ix->ntotal + n)
+    return fail(VS_ERR_DEVICE, "%s: %lld slots placed for %lld stored + %lld new vectors", who,
+                (long long)pl->h_new[(size_t)g.nlist], (long long)ix->ntotal, (long long)n);
   return VS_OK;
 }
 

@@ -84,6 +84,14 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
 constexpr int kWaveScanMaxMeanList = 1024;
 bool ivfpq_wave_scan_applies(const IvfpqDims& g, int64_t ntotal);
 size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq);
+// Slots of n newly assigned vectors in the grown inverted lists, computed on the device:
+// dest[i] = slot of vector i (behind its list's old entries, new vectors of a list in batch order),
+// new_off [nlist + 1] = offsets of the grown lists.  list_of [n] (n < 2^31), old_off [nlist + 1],
+// work: ivf_place_work_bytes(n, nlist) bytes, all device memory.  Returns the device address of a
+// flag that is non-zero once the kernels have run if some list_of[i] is outside [0, nlist).
+size_t ivf_place_work_bytes(int64_t n, int nlist);
+int* launch_ivf_place(const int32_t* list_of, int64_t n, int nlist, const int64_t* old_off, char* work,
+                      int64_t* dest, int64_t* new_off, hipStream_t st);
 // stats[0] = sum over the n (query, probe) pairs of the probed list's size, stats[1] = pairs whose
 // list is not empty, stats[2] = mfma_rows, stats[3] = *fallback_count (0 if null); device memory,
 // written in stream order.
