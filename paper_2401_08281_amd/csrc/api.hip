@@ -135,6 +135,7 @@ struct Planes {
   float* norm = nullptr;
   PrepInfo* info = nullptr;
   int known_bf16 = -1;          // info->all_bf16 once the host has read it back, else -1
+  bool try_heads_only = false;  // prepared with PrepInfo::heads_only set (an index's own operand)
 };
 size_t planes_bytes(int64_t n, int d) {
   n = mfma_padded_rows(n);
@@ -155,6 +156,7 @@ MfmaOperand operand(const float* x, int64_t n, const Planes& p) {
   MfmaOperand m;
   m.x = x; m.hi = p.hi; m.lo = p.lo; m.norm = p.norm; m.info = p.info; m.n = n;
   m.known_bf16 = p.known_bf16;
+  m.try_heads_only = p.try_heads_only;
   return m;
 }
 // After the preparation of an index's own operand has completed: tell the host whether the
@@ -292,6 +294,7 @@ struct vs_ivfpq {
   void* plane_mem = nullptr;    // bf16 head/tail planes + norms of the centroids (MFMA route)
   Planes c_planes;
   bool has_planes = false;
+  bool assign_probed = false;   // an add has run its assignment through the matrix-core route
   mutable Scratch scratch;
 };
 
@@ -474,7 +477,8 @@ int vs_flat_add(vs_flat* ix, const float* x, int64_t n, void* hip_stream) {
   ix->ntotal = total;
   if (planes) {   // (the panel layout of the planes depends on the row count: prepared anew)
     ix->planes = carve_planes(static_cast<char*>(ix->plane_mem), total, d);
-    launch_prep(ix->x, total, d, ix->planes.hi, ix->planes.lo, ix->planes.norm, ix->planes.info, st);
+    launch_prep(ix->x, total, d, ix->planes.hi, ix->planes.lo, ix->planes.norm, ix->planes.info, st, true);
+    ix->planes.try_heads_only = true;
     ix->has_planes = true;
   }
   HIP_TRY(hipStreamSynchronize(st));
@@ -777,7 +781,8 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
     TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
     ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
     launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
-                ix->c_planes.info, st);
+                ix->c_planes.info, st, true);
+    ix->c_planes.try_heads_only = true;
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));
@@ -835,7 +840,16 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
   // scratch: work space of the MFMA assignment (pieces of at most kAssignPiece vectors) |
   // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets | work space of the placement
   constexpr int64_t kAssignPiece = 1 << 20;
-  KnnPlan plan = knn_plan_pieces(n, kAssignPiece, g.nlist, g.d, 1, ix->has_planes);
+  // The first piece of an index's first large add is a short one: the sweeps start out on the
+  // bf16 heads alone and learn from a call's fallback count whether that does for this data; a
+  // short first call keeps the price of finding out small.
+  constexpr int64_t kProbePiece = 8192;
+  const int64_t first_piece = !ix->assign_probed && n > 4 * kProbePiece ? kProbePiece : 0;
+  KnnPlan plan = knn_plan_pieces(n - first_piece, kAssignPiece, g.nlist, g.d, 1, ix->has_planes);
+  if (first_piece > 0) {
+    const KnnPlan probe = knn_plan(first_piece, g.nlist, g.d, 1, ix->has_planes);
+    plan.bytes = std::max(plan.bytes, probe.bytes);
+  }
   if (!plan.mfma) plan.bytes = 0;
   Carver cv;
   const size_t o_knn = cv.take(plan.bytes);
@@ -854,14 +868,16 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
   pl->new_off = reinterpret_cast<int64_t*>(base + o_off);
 
   if (plan.mfma) {
-    for (int64_t i0 = 0; i0 < n; i0 += kAssignPiece) {
-      const int64_t ni = std::min(kAssignPiece, n - i0);
+    for (int64_t i0 = 0; i0 < n;) {
+      const int64_t ni = i0 == 0 && first_piece > 0 ? first_piece : std::min(kAssignPiece, n - i0);
       SelectOut o;
       o.idx32 = pl->list_of + i0;
       if (int rc = knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
                            ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1))
         return rc;
+      i0 += ni;
     }
+    ix->assign_probed = true;
   } else {
     launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
     launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
@@ -1196,7 +1212,8 @@ int vs_ivfflat_create(vs_ivfflat** out, int32_t d, int32_t metric, int32_t nlist
     TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
     ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
     launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
-                ix->c_planes.info, st);
+                ix->c_planes.info, st, true);
+    ix->c_planes.try_heads_only = true;
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));
@@ -1340,7 +1357,8 @@ int vs_ivfsq8_create(vs_ivfsq8** out, int32_t d, int32_t metric, int32_t nlist,
     TRY_C(hipMalloc(&ix->plane_mem, planes_bytes(nlist, d)));
     ix->c_planes = carve_planes(static_cast<char*>(ix->plane_mem), nlist, d);
     launch_prep(ix->centroids, nlist, d, ix->c_planes.hi, ix->c_planes.lo, ix->c_planes.norm,
-                ix->c_planes.info, st);
+                ix->c_planes.info, st, true);
+    ix->c_planes.try_heads_only = true;
     ix->has_planes = true;
   }
   TRY_C(hipStreamSynchronize(st));

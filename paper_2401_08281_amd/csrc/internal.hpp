@@ -110,6 +110,13 @@ struct PrepInfo {
   u32 all_bf16;       // every value is exactly representable in bf16
   u32 max_norm_bits;  // bits of the largest squared row norm (non-negative float)
   u32 all_nonneg;     // no value is negative
+  // Of the column operand of a k-nearest-rows call only, and only where that operand outlives the
+  // call (an index's centroids or vectors): bit 0 (calls with k = 1) and bit 1 (k > 1) are set
+  // while the sweeps of such calls may use the bf16 heads alone on operands that are not exactly
+  // bf16 (one matrix product instead of three, with the wider error bound that goes with it).  A
+  // bit is cleared for good by the exact fallback once more than one row in 512 of a call failed
+  // the sufficiency test under that bound.
+  u32 heads_only;
 };
 struct MfmaOperand {
   const float* x;             // [n, d] original fp32 rows
@@ -119,13 +126,14 @@ struct MfmaOperand {
   const PrepInfo* info;
   int64_t n;
   int known_bf16;             // info->all_bf16 where the host has read it back (0 / 1), else -1
+  bool try_heads_only;        // info->heads_only was set when the operand was prepared (it may have been cleared since)
 };
 bool mfma_knn_supported(int d, int k);
 // operand planes hold this many rows (the tail is zero padding)
 int64_t mfma_padded_rows(int64_t n);
 int mfma_knn_kp(int k);
 void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
-                 float* norm, PrepInfo* info, hipStream_t st);
+                 float* norm, PrepInfo* info, hipStream_t st, bool try_heads_only = false);
 // bytes of the shortlist buffer [na, nsplit, kp] and the column split count to use
 size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int d, int k, int* nsplit_out);
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,

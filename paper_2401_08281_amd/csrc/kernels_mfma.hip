@@ -213,8 +213,9 @@ __global__ __launch_bounds__(256) void prep_panel_kernel(const float* __restrict
   }
 }
 
-__global__ void prep_info_init_kernel(PrepInfo* info) {
+__global__ void prep_info_init_kernel(PrepInfo* info, u32 heads_only) {
   info->all_int = 1u; info->all_bf16 = 1u; info->max_norm_bits = 0u; info->all_nonneg = 1u;
+  info->heads_only = heads_only ? 3u : 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -271,7 +272,8 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   // flags leave at once (the two-pass variant is only enqueued for long A: allow_two)
   {
     const bool ea = Ainfo->all_bf16 != 0, eb = Binfo->all_bf16 != 0;
-    const int want = ea && eb ? 0 : (ea && allow_two ? 1 : 2);
+    // allow_two: bit 0 = the two-pass variant was enqueued; bits 1.. = this call's bit of heads_only
+    const int want = (ea && eb) || (Binfo->heads_only & (u32)(allow_two >> 1)) ? 0 : (ea && (allow_two & 1) ? 1 : 2);
     if (want != PREC) return;
   }
 
@@ -571,13 +573,13 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
                           int d, int nsplit, int64_t cols_per_split, int stride, int nphase,
                           int64_t cols_per_phase, float* __restrict__ minima, int g_raw,
                           const float* __restrict__ tau, int* __restrict__ cnt,
-                          u64* __restrict__ shortlist, int cap) {
+                          u64* __restrict__ shortlist, int cap, int hbit) {
   constexpr int BM = 256, BN = 256, BLK = 1024;                  // BLK: bytes of a 32-row x 16-element block
   constexpr int NPL = THREE ? 2 : 1;
   constexpr int STAGE = NPL * 2 * 16 * BLK;                      // [plane][panel][8 A + 8 B blocks][BLK]
   constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
   constexpr float INV_S = METRIC == 0 ? 0.5f : 1.f;
-  if ((!(Ainfo->all_bf16 && Binfo->all_bf16)) != THREE) return;
+  if ((!((Ainfo->all_bf16 && Binfo->all_bf16) || (Binfo->heads_only & (u32)hbit))) != THREE) return;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* tiles = smem;                                           // [2][STAGE]
@@ -962,11 +964,15 @@ __global__ __launch_bounds__(64) void rerank_kernel(
     const bool exact = Ainfo->all_int && Binfo->all_int && Ainfo->all_bf16 && Binfo->all_bf16 &&
                        (nonneg ? nsum < 8388608.f : nsum < 5592405.f);
     if (!exact) {   // (exact: approximate = canon bit for bit, so the k best listed keys are the answer)
-      const bool three = !(Ainfo->all_bf16 && Binfo->all_bf16);
+      const bool inexact = !(Ainfo->all_bf16 && Binfo->all_bf16);
       // |approx - canon| <= eps: bf16 head/tail split drops terms below 2^-15 |q||x| per product;
       // fp32 accumulation and the canon chain each stay below d 2^-22 (|q|^2 + |x|^2); the
-      // collect sweep's own rounding (a few ulps of |tau| / 2 + |<q,x>|) is the last term
-      const float coef = (three ? 6.2e-5f : 0.f) + (float)d * 4.8e-7f + 2e-6f;
+      // collect sweep's own rounding (a few ulps of |tau| / 2 + |<q,x>|) is the last term.
+      // Heads alone on inexact operands: q = qh + ql with |ql_i| <= 2^-9 |q_i|, likewise x, so
+      // |<q,x> - <qh,xh>| <= 2^-8 (1 + 2^-10) |q||x| <= 2^-9 (1 + 2^-10) (|q|^2 + |x|^2), twice
+      // that on the distance: 3.92e-3 (|q|^2 + |x|^2).
+      const float split_term = !inexact ? 0.f : ((Binfo->heads_only & (u32)(k == 1 ? 1 : 2)) ? 3.92e-3f : 6.2e-5f);
+      const float coef = split_term + (float)d * 4.8e-7f + 2e-6f;
       const float eps = eps_scale * coef * (na2 + nb2);
       const float tau_v = tau[row];
       const float ub = METRIC == 0 ? na2 + tau_v : -tau_v;
@@ -1006,15 +1012,22 @@ __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict
                                                          int nchunk, u64* __restrict__ partial,
                                                          SelectOut out,
                                                          const int* __restrict__ fb_count,
-                                                         const int* __restrict__ fb_rows) {
+                                                         const int* __restrict__ fb_rows,
+                                                         PrepInfo* __restrict__ adapt, int64_t na) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
   float* qs = reinterpret_cast<float*>(slots + 4 * tot);        // d
   const int wave = threadIdx.x >> 6;
   const bool vec = (d & 3) == 0;
   const int count = *fb_count;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && count > 0)
+  if (blockIdx.x == 0 && threadIdx.x == 0 && count > 0) {
     atomicAdd(&g_fallback_total, (unsigned long long)count);
+    // heads alone did not do for calls of this kind on this operand: so many rows had to be redone
+    // here (more than one in 512) that it cost more than the two matrix products saved: a redone row
+    // costs some hundred times its share of a sweep -- from the next call on the sweeps use all three
+    const u32 bit = k == 1 ? 1u : 2u;
+    if (adapt && (adapt->heads_only & bit) && count >= 8 && (int64_t)count * 512 > na) atomicAnd(&adapt->heads_only, ~bit);
+  }
   const int64_t tasks = (int64_t)count * nchunk;
   for (int64_t task = blockIdx.x; task < tasks; task += gridDim.x) {
     const int64_t f = task / nchunk;
@@ -1108,8 +1121,8 @@ bool stationary_d(int d) { return d == 32 || d == 64 || d == 96 || d == 128; }
 }  // namespace
 
 void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned short* lo,
-                 float* norm, PrepInfo* info, hipStream_t st) {
-  hipLaunchKernelGGL(prep_info_init_kernel, dim3(1), dim3(1), 0, st, info);
+                 float* norm, PrepInfo* info, hipStream_t st, bool try_heads_only) {
+  hipLaunchKernelGGL(prep_info_init_kernel, dim3(1), dim3(1), 0, st, info, try_heads_only ? 1u : 0u);
   if (n <= 0) return;
   const int64_t n_pad = mfma_padded_rows(n);
   if (!stationary_d(d)) {                            // the tiled kernel reads panels
@@ -1128,16 +1141,21 @@ struct MfmaPlan {
   bool kc;                                   // general-d kernel (256 x 256 tiles) instead of the
                                              // register-stationary one (128 rows x 64 columns)
   int RB, nsplit, nphase, g_raw, rg, kp, kp_tau, stride, cap;
+  int hbit;                                  // the bit of PrepInfo::heads_only that calls with this k go by
   int64_t cols_per_split, cols_per_phase, row_tiles;
   size_t o_minima, o_tau, o_cnt, bytes;      // offsets behind the shortlist [na][nsplit][cap]
 };
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+// Calls for the single nearest row (list assignment) and calls for the k > 1 nearest (probes, flat
+// search) learn separately whether the heads alone do: their margins differ.
+__host__ __device__ inline int heads_only_bit(int k) { return k == 1 ? 1 : 2; }
 
 MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
   MfmaPlan p;
   p.kc = !stationary_d(d);
   const int bm = p.kc ? 256 : 128, bn = p.kc ? 256 : 64;      // tile of one workgroup step
   p.kp = mfma_knn_kp(k);
+  p.hbit = heads_only_bit(k);
   p.cap = std::max(64, 3 * p.kp);
   // Row blocks of A per wavefront.  Operands split in head and tail: one 32-row block (two
   // workgroups per CU).  Operands exactly bf16: the fragments are half as many, and the
@@ -1287,7 +1305,7 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
-                     reinterpret_cast<u64*>(work), p.cap, two_pass_allowed(A) ? 1 : 0);
+                     reinterpret_cast<u64*>(work), p.cap, (two_pass_allowed(A) ? 1 : 0) | (p.hbit << 1));
 }
 
 template <int KSTEPS, int METRIC, int MODE>
@@ -1296,7 +1314,8 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   // both operand-precision variants are enqueued; the kernel that does not match the flags
   // written by operand preparation returns immediately (the flags live in device memory) --
   // unless the host already knows an operand's flag and with it which variant cannot run
-  if (!certainly_three(A, B)) {
+  // (an operand that may be swept by its heads alone needs the one-product variant enqueued too)
+  if (!certainly_three(A, B) || B.try_heads_only) {
     if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, 0>(p, A, B, work, st);
     else launch_sweep_t<KSTEPS, 1, METRIC, MODE, 0>(p, A, B, work, st);
   }
@@ -1323,14 +1342,14 @@ static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const Mfm
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
-                     reinterpret_cast<u64*>(work), p.cap);
+                     reinterpret_cast<u64*>(work), p.cap, p.hbit);
 }
 
 template <int MODE>
 static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                          int metric, char* work, hipStream_t st) {
   if (p.kc) {   // both operand-precision variants, as below
-    const bool one = !certainly_three(A, B), three = !certainly_one(A, B);
+    const bool one = !certainly_three(A, B) || B.try_heads_only, three = !certainly_one(A, B);
     if (metric == 0) {
       if (one) launch_sweep_kc_t<0, MODE, false>(p, A, B, d, work, st);
       if (three) launch_sweep_kc_t<0, MODE, true>(p, A, B, d, work, st);
@@ -1398,7 +1417,8 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
 #define CR(RV, MET)                                                                              \
   do {                                                                                           \
     hipLaunchKernelGGL((canon_rows_kernel<RV, MET>), dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d, \
-                       k, tot, fp.chunk_cols, fp.nchunk, fb_partial, out, fb_count, fb_rows);    \
+                       k, tot, fp.chunk_cols, fp.nchunk, fb_partial, out, fb_count, fb_rows,     \
+                       eps_scale < 0.f ? nullptr : const_cast<PrepInfo*>(B.info), A.n);          \
     if (fp.nchunk > 1)                                                                           \
       hipLaunchKernelGGL((canon_rows_merge_kernel<RV, MET>), dim3((unsigned)std::min<int64_t>(A.n, 1024)), \
                          dim3(64), (size_t)tot * sizeof(u64), st, fb_partial, fp.nchunk, k, tot, out, \
