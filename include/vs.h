@@ -293,6 +293,8 @@ VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32
  * with |x'|^2 stored next to every code as a float32 (4 more bytes per vector): one table of
  * inner products per QUERY, no per-list table; the result differs from the default form by
  * the rounding of the cancelling terms, about 2^-22 (|q|^2 + |x'|^2).
+ * With lists of a few hundred codes this is the fastest of the three forms (no per-list table
+ * at all: for the 8 x 4 and 16 x 8 shapes one wavefront scans a (query, probe split) on its own).
  * vs_ivfpq_add computes the norms of what it adds only while this type is selected (adding
  * under another type drops the stored norms); selecting it on an index that holds vectors
  * without norms computes them from the stored codes (ntotal * (code_size + 8) bytes of
