@@ -67,6 +67,10 @@ enum {
  * (query, row) pair in dimension order; ties go to the smaller id.
  * nq == 0 is a no-op.  nb == 0 fills the outputs with empty slots.
  * Errors: null pointers (with nq > 0), d < 1, k < 1 or k > VS_MAX_K, unknown metric.
+ * Work space: one grow-only buffer per device, shared by vs_flat_search, vs_flat_index_search,
+ * vs_kmeans and vs_ivfpq_train.  Calls from several host threads or on several streams are
+ * serialised on it: a call on another stream than the previous user's first waits (on the
+ * device, through an event) for that user's kernels.
  */
 VS_API int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32_t d,
                    int32_t metric, int32_t k, float* out_dist, int64_t* out_ids,
@@ -192,7 +196,9 @@ VS_API int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nl
  * in the order given.
  *   x   [n, d] fp32.
  *   ids [n] int64 >= 0, or NULL for sequential ids starting at the current
- *       ntotal.
+ *       ntotal.  The ids are not inspected: a negative id is stored and returned as
+ *       given, where it cannot be told from the -1 of an empty result slot (Sec. 6.1:
+ *       the sign bit marks an invalid id) -- the caller keeps ids non-negative.
  * Both decisions are taken on the fp32 fused-multiply-add chain described
  * for vs_flat_search, so they are reproducible bit for bit on any IEEE
  * machine.  Code bytes: nbits == 8: byte m = c_m; nbits == 4: byte i =

@@ -82,9 +82,36 @@ int static_scratch(char** out) {
   return VS_OK;
 }
 
-// scratch of vs_flat_search, one per device
+// scratch of vs_flat_search, vs_flat_index_search, vs_kmeans and vs_ivfpq_train, one per device
 std::mutex g_flat_mu;
 Scratch g_flat_scratch[16];
+hipEvent_t g_flat_done[16] = {};      // recorded behind the last launches that use the scratch
+hipStream_t g_flat_last[16] = {};     // ... on this stream
+
+// One user of a device's scratch at a time, also on the device: holds the mutex while a call
+// enqueues its work, makes a call on ANOTHER stream wait for the event that the previous user
+// recorded behind its last launch, and records its own when it leaves.  (Calls on one stream are
+// ordered by the stream.  A stream under graph capture neither waits nor records: a captured call
+// must not be mixed with calls on other streams that use the same scratch.)
+struct FlatScratchGuard {
+  std::unique_lock<std::mutex> lock;
+  int dev;
+  hipStream_t st;
+  bool live;
+  FlatScratchGuard(int dev_, hipStream_t st_) : lock(g_flat_mu), dev(dev_), st(st_), live(true) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { live = false; return; }
+    if (g_flat_done[dev] && g_flat_last[dev] != st) (void)hipStreamWaitEvent(st, g_flat_done[dev], 0);
+  }
+  ~FlatScratchGuard() {
+    if (!live) return;
+    if (!g_flat_done[dev] && hipEventCreateWithFlags(&g_flat_done[dev], hipEventDisableTiming) != hipSuccess) {
+      g_flat_done[dev] = nullptr;
+      return;
+    }
+    if (hipEventRecord(g_flat_done[dev], st) == hipSuccess) g_flat_last[dev] = st;
+  }
+};
 
 // ---- optional stage timing ---------------------------------------------------
 struct ProfRec { int stage; hipEvent_t a, b; };
@@ -399,7 +426,7 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_flat_search: device %d", dev);
 
   const KnnPlan plan = knn_plan(nq, nb, d, k, false);
-  std::lock_guard<std::mutex> lock(g_flat_mu);
+  FlatScratchGuard guard(dev, st);
   Scratch& sc = g_flat_scratch[dev];
   if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
   char* base = static_cast<char*>(sc.p);
@@ -501,7 +528,7 @@ int vs_flat_index_search(const vs_flat* ix, const float* q, int64_t nq, int32_t 
   const int d = ix->d, metric = ix->metric;
   const Planes* bp = ix->has_planes ? &ix->planes : nullptr;
   const KnnPlan plan = knn_plan(nq, nb, d, k, bp != nullptr);
-  std::lock_guard<std::mutex> lock(g_flat_mu);
+  FlatScratchGuard guard(dev, st);
   Scratch& sc = g_flat_scratch[dev];
   if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
   char* base = static_cast<char*>(sc.p);
@@ -680,7 +707,7 @@ int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter, fl
   DeviceBuf buf;
   if (int rc = buf.alloc(cv.off)) return rc;
   char* b = static_cast<char*>(buf.p);
-  std::lock_guard<std::mutex> lock(g_flat_mu);
+  FlatScratchGuard guard(dev, st);
   if (int rc = kmeans_rounds(x, n, d, K, niter, centroids, objective, reinterpret_cast<int32_t*>(b + o_idx),
                              reinterpret_cast<float*>(b + o_val), reinterpret_cast<int32_t*>(b + o_order),
                              reinterpret_cast<int64_t*>(b + o_off), g_flat_scratch[dev], st))
@@ -721,7 +748,7 @@ int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, int32_t
   int32_t* order = reinterpret_cast<int32_t*>(b + o_order);
   int64_t* off = reinterpret_cast<int64_t*>(b + o_off);
   float* res = reinterpret_cast<float*>(b + o_res);
-  std::lock_guard<std::mutex> lock(g_flat_mu);
+  FlatScratchGuard guard(dev, st);
   Scratch& sc = g_flat_scratch[dev];
   // 1. coarse quantizer: k-means on the training vectors
   if (int rc = kmeans_rounds(x, n, d, nlist, niter, centroids, objective, idx, val, order, off, sc, st)) return rc;

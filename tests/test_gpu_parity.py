@@ -107,6 +107,29 @@ def test_trim_releases_the_work_buffer_and_search_still_works(vs, oracle):
     np.testing.assert_array_equal(I1, I2)
 
 
+def test_flat_searches_on_two_streams_share_the_work_space_safely(vs):
+    """vs_flat_search keeps one work buffer per device.  Calls issued on two streams without any
+    synchronisation between them must not see each other's candidate lists: the later call waits
+    on the device for the earlier one's kernels."""
+    import torch
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    xs = [torch.randn((40_000, 64), generator=g, device="cuda") for _ in range(2)]
+    qs = [torch.randn((500, 64), generator=g, device="cuda") for _ in range(2)]
+    ref = [[host(t).copy() for t in vs.vs_flat_search(xs[i], qs[i], 10, L2)] for i in range(2)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(6):
+        say("two streams, round %d" % rep)
+        outs = []
+        for i in (0, 1, 0, 1):
+            with torch.cuda.stream(streams[i]):
+                outs.append((i, vs.vs_flat_search(xs[i], qs[i], 10, L2)))
+        torch.cuda.synchronize()
+        for i, (D, I) in outs:
+            np.testing.assert_array_equal(host(I), ref[i][1])
+            np.testing.assert_array_equal(host(D), ref[i][0])
+
+
 def test_flat_empty_database_and_no_queries(vs):
     import torch
     say("flat nb=0 / nq=0")
