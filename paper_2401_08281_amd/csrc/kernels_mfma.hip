@@ -1059,6 +1059,110 @@ __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict
   }
 }
 
+// The same fallback for d a multiple of 32 (every shape the matrix-core route serves), with the
+// columns staged through LDS: one row of B per lane read straight from memory makes every load
+// instruction touch 64 cache lines and the chain wait for each of them (6 us per redone row at
+// 65536 x 96).  Here a tile of 256 rows of B x 32 dimensions is fetched with 8 lanes per row (128
+// consecutive bytes per request), written to LDS with a row stride of 36 floats (16-byte aligned,
+// conflict-free for the 16-byte reads that follow), and lane r continues the canon chain of row r
+// over those 32 dimensions -- the same values in the same order as canon_row, hence the same bits.
+// The next tile chunk is in flight (registers) while the current one is summed.
+template <int R, int METRIC>
+__global__ __launch_bounds__(256) void canon_rows_tiled_kernel(const float* __restrict__ A,
+                                                               const float* __restrict__ B, int64_t nb,
+                                                               int d, int k, int tot, int64_t chunk_cols,
+                                                               int nchunk, u64* __restrict__ partial,
+                                                               SelectOut out,
+                                                               const int* __restrict__ fb_count,
+                                                               const int* __restrict__ fb_rows,
+                                                               PrepInfo* __restrict__ adapt, int64_t na) {
+  constexpr int DC = 32, LD = 36, TR = 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u64* slots = reinterpret_cast<u64*>(smem);                    // 4 * tot
+  float* qs = reinterpret_cast<float*>(slots + 4 * tot);        // d
+  float* tile = qs + d;                                         // 2 x TR x LD
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int r_ld = tid >> 3, c_ld = tid & 7;                    // fetch: 8 lanes per row, 32 rows per pass
+  const int count = *fb_count;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && count > 0) {
+    atomicAdd(&g_fallback_total, (unsigned long long)count);
+    // heads alone did not do for calls of this kind on this operand: so many rows had to be redone
+    // here (more than one in 512) that it cost more than the two matrix products saved -- from the
+    // next call on the sweeps use all three
+    const u32 bit = k == 1 ? 1u : 2u;
+    if (adapt && (adapt->heads_only & bit) && count >= 8 && (int64_t)count * 512 > na) atomicAnd(&adapt->heads_only, ~bit);
+  }
+  const int64_t tasks = (int64_t)count * nchunk;
+  for (int64_t task = blockIdx.x; task < tasks; task += gridDim.x) {
+    const int64_t f = task / nchunk;
+    const int ch = (int)(task - f * nchunk);
+    const int64_t row = fb_rows[f];
+    const int64_t c_begin = ch * chunk_cols, c_end = min(nb, c_begin + chunk_cols);
+    __syncthreads();                                            // the task before is done with qs, tile and slots
+    for (int t = tid; t < d; t += 256) qs[t] = A[row * d + t];
+    WaveSelect<R> ws;
+    ws.init(slots + wave * tot, tot, k);
+    u32x4 stg[8];
+    auto fetch = [&](int64_t i0, int c0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int64_t r = min(i0 + j * 32 + r_ld, c_end - 1);   // rows past the end: masked at the push
+        stg[j] = *reinterpret_cast<const u32x4*>(B + r * d + c0 + c_ld * 4);
+      }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        *reinterpret_cast<u32x4*>(tile + (buf * TR + j * 32 + r_ld) * LD + c_ld * 4) = stg[j];
+    };
+    int64_t i0 = c_begin;
+    int c0 = 0, buf = 0;
+    bool ok = i0 < c_end;                                        // (uniform)
+    if (ok) { fetch(i0, c0); stash(0); }
+    __syncthreads();                                            // query and the first chunk
+    float acc = 0.f;
+    while (ok) {
+      int64_t ni0 = i0;
+      int nc0 = c0 + DC;
+      if (nc0 >= d) { nc0 = 0; ni0 += TR; }
+      const bool nok = ni0 < c_end;
+      if (nok) fetch(ni0, nc0);                                 // in flight during the arithmetic
+      const float* __restrict__ tr = tile + (buf * TR + tid) * LD;
+      const float* __restrict__ qc = qs + c0;
+#pragma unroll
+      for (int c = 0; c < DC / 4; ++c) {
+        const float4 xv = *reinterpret_cast<const float4*>(tr + c * 4);
+        const float4 qv = *reinterpret_cast<const float4*>(qc + c * 4);
+        const float xs[4] = {xv.x, xv.y, xv.z, xv.w}, qq[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (METRIC == 0) { const float diff = qq[u] - xs[u]; acc = __builtin_fmaf(diff, diff, acc); }
+          else acc = __builtin_fmaf(qq[u], xs[u], acc);
+        }
+      }
+      if (c0 + DC >= d) {                                       // the row is complete
+        const int64_t i = i0 + tid;
+        ws.push(i < c_end, make_key(acc, (u32)i, METRIC));
+        acc = 0.f;
+      }
+      if (nok) stash(buf ^ 1);
+      block_sync_lds();
+      i0 = ni0; c0 = nc0; ok = nok; buf ^= 1;
+    }
+    ws.finish();
+    __syncthreads();
+    KeySink sink;
+    sink.idmap = nullptr; sink.metric = METRIC;
+    if (nchunk == 1) {
+      sink.keys = nullptr; sink.val = out.val; sink.id64 = out.id64; sink.idx32 = out.idx32;
+      block_rank_merge(slots, tot, 4, k, sink, row * (int64_t)k);
+    } else {
+      sink.keys = partial; sink.val = nullptr; sink.id64 = nullptr; sink.idx32 = nullptr;
+      block_rank_merge(slots, tot, 4, k, sink, task * (int64_t)k);
+    }
+  }
+}
+
 // One wavefront per listed row: k best of its nchunk * k partial keys.
 template <int R, int METRIC>
 __global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restrict__ partial,
@@ -1256,10 +1360,11 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
 
 namespace {
 struct FallbackPlan { int64_t chunk_cols; int nchunk; };
-// column chunks of the exact fallback: at least 32768 columns each, at most 64 chunks
+// column chunks of the exact fallback: at least 8192 columns each (a few hundred redone rows
+// still make a few thousand tasks), at most 64 chunks
 FallbackPlan fallback_plan(int64_t nb) {
   FallbackPlan f;
-  f.chunk_cols = std::max<int64_t>(32768, ((nb + 63) / 64 + 255) / 256 * 256);
+  f.chunk_cols = std::max<int64_t>(8192, ((nb + 63) / 64 + 255) / 256 * 256);
   f.nchunk = (int)std::max<int64_t>(1, (nb + f.chunk_cols - 1) / f.chunk_cols);
   return f;
 }
@@ -1411,12 +1516,18 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
 #undef RR
   // rows whose shortlist could not be proven sufficient: canon over all columns
   const int tot = select_slots_for_k(k);
-  const size_t sh2 = (size_t)4 * tot * sizeof(u64) + (size_t)d * sizeof(float);
+  const bool tiled = d % 32 == 0;
+  const size_t sh2 = (size_t)4 * tot * sizeof(u64) + (size_t)d * sizeof(float) +
+                     (tiled ? (size_t)2 * 256 * 36 * sizeof(float) : 0);
   const FallbackPlan fp = fallback_plan(B.n);
   const int grid = (int)std::min<int64_t>(A.n * fp.nchunk, 2048);
 #define CR(RV, MET)                                                                              \
   do {                                                                                           \
-    hipLaunchKernelGGL((canon_rows_kernel<RV, MET>), dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d, \
+    auto kern = tiled ? &canon_rows_tiled_kernel<RV, MET> : &canon_rows_kernel<RV, MET>;         \
+    if (sh2 > 48 * 1024)                                                                         \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);           \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d,                   \
                        k, tot, fp.chunk_cols, fp.nchunk, fb_partial, out, fb_count, fb_rows,     \
                        eps_scale < 0.f ? nullptr : const_cast<PrepInfo*>(B.info), A.n);          \
     if (fp.nchunk > 1)                                                                           \
