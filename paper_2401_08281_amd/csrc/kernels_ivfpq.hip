@@ -1008,6 +1008,7 @@ void ivfpq_scan_bank_kernel(
 // sub-quantizer (t + l) mod M in byte t of its code.
 // ---------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kWaveScanShare = 2;   // wavefronts that share a per-query table (inner product, stored norms)
 
 // One workgroup: the tables of kQtQueries queries.  A thread keeps one codebook entry T_m[j] in
 // registers and takes the queries' sub-vectors from LDS.
@@ -1037,7 +1038,7 @@ __global__ __launch_bounds__(256) void pq_query_tables_kernel(const float* __res
 }
 
 template <int M, int MODE, int R>
-__global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
+__global__ __launch_bounds__(MODE == 3 ? 64 : 64 * kWaveScanShare) void ivfpq_scan_wave_kernel(
     const float* __restrict__ query_tables, const float* __restrict__ list_tables,
     const int32_t* __restrict__ probes, const float* __restrict__ cdist, int nprobe, int ppb, int nsplit,
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes, const float* __restrict__ norms,
@@ -1049,17 +1050,23 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
   constexpr int NI = K / RPI;         // load instructions per table = 16-byte pieces per lane
   static_assert(M == 8 || M == 16, "rows of 8 or 16 floats");
   static_assert(MODE >= 1 && MODE <= 3, "table form");
+  // MODE 1, 2: the table depends on the query alone, so NW wavefronts of one work item share it
+  // (each scans every NW-th list of the item and selects on its own; the results are merged by
+  // rank at the end): the LDS per wavefront shrinks and more wavefronts fit a CU, which is what
+  // hides the latency of the per-list chain (extent -> first codes -> look-ups).
+  constexpr int NW = MODE == 3 ? 1 : kWaveScanShare;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* lut = reinterpret_cast<float*>(smem);                              // [256][M]
-  u64* slots = reinterpret_cast<u64*>(smem + K * M * sizeof(float));        // tot
-  u32* s_begin = reinterpret_cast<u32*>(slots + tot);                       // ppb: the non-empty lists
+  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  u64* slots0 = reinterpret_cast<u64*>(smem + K * M * sizeof(float));       // NW x tot
+  u64* slots = slots0 + wave * tot;
+  u32* s_begin = reinterpret_cast<u32*>(slots0 + NW * tot) + wave * 4 * ppb; // ppb: this wavefront's non-empty lists
   u32* s_end = s_begin + ppb;
   int32_t* s_list = reinterpret_cast<int32_t*>(s_end + ppb);
   float* s_bias = reinterpret_cast<float*>(s_list + ppb);
 
   // (no static LDS: the table starts at LDS address 0 and a table offset is an LDS address; the
   // launcher checks this)
-  const int lane = threadIdx.x;
   const int64_t item = blockIdx.x;
   const int64_t qi = item / nsplit;
   const int split = (int)(item % nsplit);
@@ -1072,19 +1079,23 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
   f32x4 tq[MODE == 3 ? NI : 1];
   {
     const f32x4* __restrict__ src = reinterpret_cast<const f32x4*>(query_tables + qi * K * M) + lane;
+    if constexpr (MODE == 3) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const f32x4 v = src[i * 64];
-      if constexpr (MODE == 3) tq[i] = v;
-      else *reinterpret_cast<f32x4*>(lut + (row0 + RPI * i) * M + 4 * quad) = v;
+      for (int i = 0; i < NI; ++i) tq[i] = src[i * 64];
+    } else {   // wavefront w copies pieces w, w + NW, ...
+#pragma unroll
+      for (int i = 0; i < NI / NW; ++i) {
+        const int ii = i * NW + wave;
+        *reinterpret_cast<f32x4*>(lut + (row0 + RPI * ii) * M + 4 * quad) = src[ii * 64];
+      }
     }
   }
   WaveSelect<R> ws;
   ws.init(slots, tot, k);
   ws.set_metric(KEY_METRIC);
   int nl = 0;
-  for (int p0 = 0; p0 < np; p0 += VS_WAVE) {   // the item's non-empty lists, in probe order
-    const int p = p0 + lane;
+  for (int p0 = 0; p0 < np; p0 += VS_WAVE * NW) {   // this wavefront's non-empty lists, in probe order
+    const int p = p0 + lane * NW + wave;            // (dealt out in turn: the probes come sorted by distance)
     const int l = p < np ? probes[qi * nprobe + p_begin + p] : -1;
     const int64_t b = l >= 0 ? list_off[l] : 0, e = l >= 0 ? list_off[l + 1] : 0;
     const bool keep = e > b;
@@ -1100,7 +1111,8 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
     }
     nl += __popcll(mask);
   }
-  wave_lds_sync();
+  if constexpr (NW == 1) wave_lds_sync();
+  else block_sync_lds();                            // the shared table is complete
   // byte offset of this lane's column in a row for every step, four steps per register, in units
   // that leave room for it in one byte: v_perm_b32 puts the code byte j into byte 1 and this into
   // byte 0, and one shift turns (j << 8 | unit * column) into the byte offset j * 4 M + 4 * column
@@ -1183,7 +1195,12 @@ __global__ __launch_bounds__(64) void ivfpq_scan_wave_kernel(
     if (pl < nl) { cw = nx; nrm = nrm_nx; }
   }
   ws.finish();
-  for (int j = lane; j < k; j += VS_WAVE) sink.put(item * k + j, ws.s[j]);
+  if constexpr (NW == 1) {
+    for (int j = lane; j < k; j += VS_WAVE) sink.put(item * k + j, ws.s[j]);
+  } else {
+    block_sync_lds();
+    block_rank_merge(slots0, tot, NW, k, sink, item * k);
+  }
 }
 
 // One wavefront per query: k best of the nsplit partial lists, then
@@ -1425,8 +1442,9 @@ static int launch_scan_bank_any(const IvfpqDims& g, const float* q, int64_t nq,
 size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq) {
   return (size_t)nq * g.K * g.M * sizeof(float);
 }
-static size_t wave_scan_lds_bytes(const IvfpqDims& g, int tot, int ppb) {
-  return (size_t)g.K * g.M * sizeof(float) + (size_t)tot * sizeof(u64) + (size_t)ppb * 16;
+static size_t wave_scan_lds_bytes(const IvfpqDims& g, int mode, int tot, int ppb) {
+  const int nw = mode == 3 ? 1 : kWaveScanShare;
+  return (size_t)g.K * g.M * sizeof(float) + (size_t)nw * ((size_t)tot * sizeof(u64) + (size_t)ppb * 16);
 }
 template <int M, int DSUB, int MODE>
 static int launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, const float* codebooks,
@@ -1438,8 +1456,8 @@ static int launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, cons
                      dim3(256), (size_t)kQtQueries * g.d * sizeof(float), st, q, nq, codebooks, g.d, g.M, g.K,
                      MODE == 1 ? 1.f : -2.f, query_tables);
   const int tot = select_slots_for_k(k);
-  const size_t shmem = wave_scan_lds_bytes(g, tot, ppb);
-  const dim3 grid((unsigned)(nq * nsplit)), block(64);
+  const size_t shmem = wave_scan_lds_bytes(g, MODE, tot, ppb);
+  const dim3 grid((unsigned)(nq * nsplit)), block(MODE == 3 ? 64 : 64 * kWaveScanShare);
 #define GO(RR)                                                                                        \
   do {                                                                                                \
     auto kern = &ivfpq_scan_wave_kernel<M, MODE, RR>;                                                 \
@@ -1511,7 +1529,7 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
                        (size_t)(g.d + 2) * sizeof(float);
   if (shmem + 64 > 160 * 1024) return -1;
   if (mode != 0 && query_tables && ivfpq_wave_scan_applies(g, ntotal)) {
-    if (wave_scan_lds_bytes(g, select_slots_for_k(k), ppb) > 160 * 1024) return -1;
+    if (wave_scan_lds_bytes(g, mode, select_slots_for_k(k), ppb) > 160 * 1024) return -1;
 #define WAVE(MM, DS, MODE)                                                                             \
   return launch_scan_wave<MM, DS, MODE>(g, q, nq, codebooks, query_tables, list_tables, probes, cdist, nprobe, \
                                  ppb, nsplit, list_off, codes, norms, cnorm, ntotal, k, sink, st)
