@@ -797,10 +797,13 @@ int vs_ivfpq_create(vs_ivfpq** out, int32_t d, int32_t metric, int32_t nlist, in
   const size_t cb = (size_t)nlist * d * sizeof(float);
   const size_t tb = (size_t)M * ix->g.K * ix->g.dsub * sizeof(float);
   TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->centroids), cb));
-  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->codebooks), tb));
+  // (the codebooks twice: [M, K, dsub] as given, and behind it [K, M, dsub], the order in which the
+  // per-query tables of the wavefront-private scan are computed)
+  TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->codebooks), 2 * tb));
   TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->list_off), ((size_t)nlist + 1) * sizeof(int64_t)));
   TRY_C(hipMemcpyAsync(ix->centroids, centroids, cb, hipMemcpyDeviceToDevice, st));
   TRY_C(hipMemcpyAsync(ix->codebooks, codebooks, tb, hipMemcpyDeviceToDevice, st));
+  launch_pq_codebooks_by_entry(ix->g, ix->codebooks, ix->codebooks + tb / sizeof(float), st);
   TRY_C(hipMalloc(reinterpret_cast<void**>(&ix->cnorm), (size_t)nlist * sizeof(float)));
   launch_row_norms(ix->centroids, nlist, d, ix->cnorm, st);
   TRY_C(hipMemsetAsync(ix->list_off, 0, ((size_t)nlist + 1) * sizeof(int64_t), st));

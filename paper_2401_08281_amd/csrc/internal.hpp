@@ -97,6 +97,9 @@ int* launch_ivf_place(const int32_t* list_of, int64_t n, int nlist, const int64_
 // written in stream order.
 void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
                          int64_t mfma_rows, long long* stats, hipStream_t st);
+// out [K][M][dsub] = codebooks [M][K][dsub] with the first two axes exchanged.  launch_ivfpq_scan
+// expects it directly behind the codebooks it is given (codebooks + M * K * dsub).
+void launch_pq_codebooks_by_entry(const IvfpqDims& g, const float* codebooks, float* out, hipStream_t st);
 // out [nlist][K][M]: |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>, the per-list term of the split look-up tables
 void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
                            hipStream_t st);

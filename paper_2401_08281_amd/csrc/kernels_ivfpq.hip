@@ -1015,7 +1015,7 @@ constexpr int kWaveScanShare = 2;   // wavefronts that share a per-query table (
 constexpr int kQtQueries = 8;
 template <int DSUB>
 __global__ __launch_bounds__(256) void pq_query_tables_kernel(const float* __restrict__ q, int64_t nq,
-                                                              const float* __restrict__ codebooks, int d, int M,
+                                                              const float* __restrict__ codebooks_by_entry, int d, int M,
                                                               int K, float scale, float* __restrict__ out) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* qs = reinterpret_cast<float*>(smem);          // [kQtQueries][d]
@@ -1023,16 +1023,34 @@ __global__ __launch_bounds__(256) void pq_query_tables_kernel(const float* __res
   const int nqb = (int)min((int64_t)kQtQueries, nq - q0);
   for (int i = threadIdx.x; i < nqb * d; i += blockDim.x) qs[i] = q[q0 * d + i];
   __syncthreads();
-  for (int e = threadIdx.x; e < K * M; e += blockDim.x) {   // e = j * M + m
-    const int m = e % M, j = e / M;
-    float T[DSUB];
+  // a thread takes four consecutive entries e = j * M + m (one j, four m; M is a multiple of 4):
+  // 4 * DSUB consecutive floats of codebooks_by_entry [K][M][DSUB], one 16-byte store per query
+  for (int e4 = threadIdx.x; e4 < K * M / 4; e4 += blockDim.x) {
+    const int m0 = (e4 * 4) % M;
+    float T[4][DSUB];
 #pragma unroll
-    for (int u = 0; u < DSUB; ++u) T[u] = codebooks[((int64_t)m * K + j) * DSUB + u];
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) T[i][u] = codebooks_by_entry[((int64_t)e4 * 4 + i) * DSUB + u];
     for (int a = 0; a < nqb; ++a) {
-      float acc = 0.f;
+      f32x4 r;
 #pragma unroll
-      for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qs[a * d + m * DSUB + u], T[u], acc);
-      out[(q0 + a) * K * M + e] = scale * acc;
+      for (int i = 0; i < 4; ++i) {
+        float acc = 0.f;
+        if constexpr (DSUB % 4 == 0) {   // the query's sub-vector in 16-byte LDS reads
+#pragma unroll
+          for (int u4 = 0; u4 < DSUB / 4; ++u4) {
+            const f32x4 qv = *reinterpret_cast<const f32x4*>(qs + a * d + (m0 + i) * DSUB + 4 * u4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = __builtin_fmaf(qv[u], T[i][4 * u4 + u], acc);
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(qs[a * d + (m0 + i) * DSUB + u], T[i][u], acc);
+        }
+        r[i] = scale * acc;
+      }
+      *reinterpret_cast<f32x4*>(out + (q0 + a) * K * M + (int64_t)e4 * 4) = r;
     }
   }
 }
@@ -1237,6 +1255,14 @@ __global__ __launch_bounds__(64) void ivfpq_merge_kernel(const u64* __restrict__
 
 }  // namespace
 
+__global__ void pq_codebooks_by_entry_kernel(const float* __restrict__ codebooks, int M, int K, int dsub,
+                                             float* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;      // index into out: (j, m, u)
+  if (i >= M * K * dsub) return;
+  const int u = i % dsub, m = (i / dsub) % M, j = i / (dsub * M);
+  out[i] = codebooks[((int64_t)m * K + j) * dsub + u];
+}
+
 // What one search scanned: list sizes summed over its (query, probe) pairs.  stats was zeroed in
 // stream order before this launch.
 __global__ __launch_bounds__(256) void search_stats_kernel(const int32_t* __restrict__ probes, int64_t n,
@@ -1365,6 +1391,12 @@ void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_o
                      fallback_count, mfma_rows, reinterpret_cast<unsigned long long*>(stats));
 }
 
+void launch_pq_codebooks_by_entry(const IvfpqDims& g, const float* codebooks, float* out, hipStream_t st) {
+  const int n = g.M * g.K * g.dsub;
+  hipLaunchKernelGGL(pq_codebooks_by_entry_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, codebooks,
+                     g.M, g.K, g.dsub, out);
+}
+
 void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
                            hipStream_t st) {
   const int64_t n = (int64_t)g.nlist * g.K * g.M;
@@ -1453,8 +1485,8 @@ static int launch_scan_wave(const IvfpqDims& g, const float* q, int64_t nq, cons
                              const uint8_t* codes, const float* norms, const float* cnorm, int64_t ntotal,
                              int k, KeySink sink, hipStream_t st) {
   hipLaunchKernelGGL((pq_query_tables_kernel<DSUB>), dim3((unsigned)((nq + kQtQueries - 1) / kQtQueries)),
-                     dim3(256), (size_t)kQtQueries * g.d * sizeof(float), st, q, nq, codebooks, g.d, g.M, g.K,
-                     MODE == 1 ? 1.f : -2.f, query_tables);
+                     dim3(256), (size_t)kQtQueries * g.d * sizeof(float), st, q, nq,
+                     codebooks + (size_t)g.M * g.K * g.dsub, g.d, g.M, g.K, MODE == 1 ? 1.f : -2.f, query_tables);
   const int tot = select_slots_for_k(k);
   const size_t shmem = wave_scan_lds_bytes(g, MODE, tot, ppb);
   const dim3 grid((unsigned)(nq * nsplit)), block(MODE == 3 ? 64 : 64 * kWaveScanShare);
