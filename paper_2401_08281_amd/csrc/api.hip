@@ -267,7 +267,7 @@ int knn_run(const KnnPlan& plan, char* ws, const float* A, int64_t na, const flo
       StageTimer t(stage_dist, st);
       launch_prep(A, na, d, pa.hi, pa.lo, pa.norm, pa.info, st);
       if (!b_planes) launch_prep(B, nb, d, pb.hi, pb.lo, pb.norm, pb.info, st);
-      launch_mfma_shortlist(oa, ob, d, metric, k, plan.nsplit, shortlist, st);
+      launch_mfma_shortlist(oa, ob, d, metric, k, plan.nsplit, shortlist, fb_count, st);
     }
     {
       StageTimer t(stage_select, st);

@@ -139,8 +139,9 @@ void launch_prep(const float* x, int64_t n, int d, unsigned short* hi, unsigned 
                  float* norm, PrepInfo* info, hipStream_t st, bool try_heads_only = false);
 // bytes of the shortlist buffer [na, nsplit, kp] and the column split count to use
 size_t mfma_knn_shortlist_bytes(int64_t na, int64_t nb, int d, int k, int* nsplit_out);
+// (also clears *fb_count, the counter that launch_rerank of the same call adds to)
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
-                           int nsplit, u64* shortlist, hipStream_t st);
+                           int nsplit, u64* shortlist, int* fb_count, hipStream_t st);
 // exact k best per row of A from the shortlists; rows that cannot be proven exact are
 // recomputed over all of B.  fb_count: 1 int, fb_rows: A.n ints, fb_partial:
 // mfma_knn_fallback_bytes(...) bytes (device scratch; may be null when that is 0).

@@ -1281,7 +1281,14 @@ __global__ __launch_bounds__(256) void search_stats_kernel(const int32_t* __rest
     codes += __shfl_down(codes, o, 64);
     lists += __shfl_down(lists, o, 64);
   }
-  if ((threadIdx.x & 63) == 0) {
+  // one pair of atomics per workgroup (thousands of wavefronts adding to the same two words
+  // serialise: 63 us for 160k pairs)
+  __shared__ unsigned long long part[2][4];
+  if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = codes; part[1][threadIdx.x >> 6] = lists; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    codes = part[0][0] + part[0][1] + part[0][2] + part[0][3];
+    lists = part[1][0] + part[1][1] + part[1][2] + part[1][3];
     if (codes) atomicAdd(&stats[0], codes);
     if (lists) atomicAdd(&stats[1], lists);
   }
@@ -1386,7 +1393,7 @@ void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_
 void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
                          int64_t mfma_rows, long long* stats, hipStream_t st) {
   launch_fill_u64(reinterpret_cast<u64*>(stats), 4, 0ull, st);
-  const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(1024, (n + 255) / 256));
+  const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(256, (n + 255) / 256));
   hipLaunchKernelGGL(search_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, st, probes, n, list_off,
                      fallback_count, mfma_rows, reinterpret_cast<unsigned long long*>(stats));
 }

@@ -834,7 +834,11 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
 // values first), or the largest finite one if fewer than kp are finite.
 template <int RG>
 __global__ __launch_bounds__(256) void tau_kernel(const float* __restrict__ minima, int g_raw,
-                                                  int64_t na, int kp, float* __restrict__ tau) {
+                                                  int64_t na, int kp, float* __restrict__ tau,
+                                                  int* __restrict__ zero_this) {
+  // (also clears the count of rows that the re-rank, which runs later on the same stream, will
+  // send to the exact fallback: one launch less per call)
+  if (zero_this && blockIdx.x == 0 && threadIdx.x == 0) *zero_this = 0;
   const int64_t row = blockIdx.x * 4ll + (threadIdx.x >> 6);
   if (row >= na) return;
   const int lane = lane_id();
@@ -1198,7 +1202,6 @@ __global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restr
   }
 }
 
-__global__ void zero_int_kernel(int* p) { *p = 0; }
 
 }  // namespace
 
@@ -1479,7 +1482,7 @@ static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOper
 }
 
 void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, int metric, int k,
-                           int nsplit, u64* shortlist, hipStream_t st) {
+                           int nsplit, u64* shortlist, int* fb_count, hipStream_t st) {
   (void)nsplit;
   const MfmaPlan p = make_plan(A.n, B.n, k, d);
   char* work = reinterpret_cast<char*>(shortlist);
@@ -1488,10 +1491,10 @@ void launch_mfma_shortlist(const MfmaOperand& A, const MfmaOperand& B, int d, in
   float* tau = reinterpret_cast<float*>(work + p.o_tau);
   const float* minima = reinterpret_cast<const float*>(work + p.o_minima);
   switch (p.rg) {
-    case 1: hipLaunchKernelGGL((tau_kernel<1>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
-    case 2: hipLaunchKernelGGL((tau_kernel<2>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
-    case 4: hipLaunchKernelGGL((tau_kernel<4>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
-    default: hipLaunchKernelGGL((tau_kernel<8>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau); break;
+    case 1: hipLaunchKernelGGL((tau_kernel<1>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau, fb_count); break;
+    case 2: hipLaunchKernelGGL((tau_kernel<2>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau, fb_count); break;
+    case 4: hipLaunchKernelGGL((tau_kernel<4>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau, fb_count); break;
+    default: hipLaunchKernelGGL((tau_kernel<8>), grid, block, 0, st, minima, p.g_raw, A.n, p.kp_tau, tau, fb_count); break;
   }
   launch_sweep<1>(p, A, B, d, metric, work, st);
 }
@@ -1504,8 +1507,7 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
   const int kp = p.kp;
   const int* cnt = reinterpret_cast<const int*>(reinterpret_cast<const char*>(shortlist) + p.o_cnt);
   const float* tau = reinterpret_cast<const float*>(reinterpret_cast<const char*>(shortlist) + p.o_tau);
-  hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, fb_count);
-  const int R = kp <= 64 ? 2 : 4;
+  const int R = kp <= 64 ? 2 : 4;   // (fb_count was cleared by launch_mfma_shortlist's threshold kernel)
   const size_t sh = (size_t)64 * R * sizeof(u64) + (size_t)d * sizeof(float);
 #define RR(RV, MET)                                                                               \
   hipLaunchKernelGGL((rerank_kernel<RV, MET>), dim3((unsigned)A.n), dim3(64), sh, st, shortlist,  \
