@@ -218,6 +218,11 @@ VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* 
  * are returned best first with their stored ids.
  *   q [nq, d] fp32; out_dist [nq, k] fp32; out_ids [nq, k] int64.
  * Errors: null pointers (with nq > 0), k or nprobe < 1 or > VS_MAX_K.
+ * Work space: one grow-only buffer per index (the first call of a size allocates it; later
+ * calls only enqueue kernels).  Searches of one index from several host threads or on several
+ * streams are serialised on it: a call on another stream than the previous search's first waits,
+ * on the device, for that search's kernels.  Searching while the same index is being added to
+ * is not supported.
  */
 VS_API int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
                     float* out_dist, int64_t* out_ids, void* hip_stream);

@@ -36,18 +36,52 @@ int fail(int code, const char* fmt, ...) {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-// Grow-only device scratch buffer.
+// Grow-only device scratch buffer, with what it takes to hand it from one user to the next:
+// a mutex for the host side and an event recorded behind the last user's launches.
 struct Scratch {
   void* p = nullptr;
   size_t bytes = 0;
+  std::mutex mu;
+  hipEvent_t done = nullptr;     // recorded behind the last launches that use the buffer
+  hipStream_t last = nullptr;    // ... on this stream
   int reserve(size_t need) {
     if (need <= bytes) return VS_OK;
-    if (p) { HIP_TRY(hipFree(p)); p = nullptr; bytes = 0; }
+    if (p) { HIP_TRY(hipFree(p)); p = nullptr; bytes = 0; }   // (hipFree waits for the device)
     HIP_TRY(hipMalloc(&p, need));
     bytes = need;
     return VS_OK;
   }
-  void release() { if (p) (void)hipFree(p); p = nullptr; bytes = 0; }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr; bytes = 0;
+    if (done) (void)hipEventDestroy(done);
+    done = nullptr; last = nullptr;
+  }
+};
+
+// One user of a scratch buffer at a time, also on the device: holds the mutex while a call
+// enqueues its work, makes a call on ANOTHER stream wait for the event that the previous user
+// recorded behind its last launch, and records its own when it leaves.  (Calls on one stream are
+// ordered by the stream.  A stream under graph capture neither waits nor records: a captured call
+// must not be mixed with calls on other streams that use the same buffer.)
+struct ScratchUse {
+  Scratch& sc;
+  std::unique_lock<std::mutex> lock;
+  hipStream_t st;
+  bool live;
+  ScratchUse(Scratch& sc_, hipStream_t st_) : sc(sc_), lock(sc_.mu), st(st_), live(true) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { live = false; return; }
+    if (sc.done && sc.last != st) (void)hipStreamWaitEvent(st, sc.done, 0);
+  }
+  ~ScratchUse() {
+    if (!live) return;
+    if (!sc.done && hipEventCreateWithFlags(&sc.done, hipEventDisableTiming) != hipSuccess) {
+      sc.done = nullptr;
+      return;
+    }
+    if (hipEventRecord(sc.done, st) == hipSuccess) sc.last = st;
+  }
 };
 
 // Carves aligned sub-buffers out of one allocation.
@@ -83,35 +117,7 @@ int static_scratch(char** out) {
 }
 
 // scratch of vs_flat_search, vs_flat_index_search, vs_kmeans and vs_ivfpq_train, one per device
-std::mutex g_flat_mu;
 Scratch g_flat_scratch[16];
-hipEvent_t g_flat_done[16] = {};      // recorded behind the last launches that use the scratch
-hipStream_t g_flat_last[16] = {};     // ... on this stream
-
-// One user of a device's scratch at a time, also on the device: holds the mutex while a call
-// enqueues its work, makes a call on ANOTHER stream wait for the event that the previous user
-// recorded behind its last launch, and records its own when it leaves.  (Calls on one stream are
-// ordered by the stream.  A stream under graph capture neither waits nor records: a captured call
-// must not be mixed with calls on other streams that use the same scratch.)
-struct FlatScratchGuard {
-  std::unique_lock<std::mutex> lock;
-  int dev;
-  hipStream_t st;
-  bool live;
-  FlatScratchGuard(int dev_, hipStream_t st_) : lock(g_flat_mu), dev(dev_), st(st_), live(true) {
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { live = false; return; }
-    if (g_flat_done[dev] && g_flat_last[dev] != st) (void)hipStreamWaitEvent(st, g_flat_done[dev], 0);
-  }
-  ~FlatScratchGuard() {
-    if (!live) return;
-    if (!g_flat_done[dev] && hipEventCreateWithFlags(&g_flat_done[dev], hipEventDisableTiming) != hipSuccess) {
-      g_flat_done[dev] = nullptr;
-      return;
-    }
-    if (hipEventRecord(g_flat_done[dev], st) == hipSuccess) g_flat_last[dev] = st;
-  }
-};
 
 // ---- optional stage timing ---------------------------------------------------
 struct ProfRec { int stage; hipEvent_t a, b; };
@@ -426,7 +432,7 @@ int vs_flat_search(const float* x, int64_t nb, const float* q, int64_t nq, int32
   if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_flat_search: device %d", dev);
 
   const KnnPlan plan = knn_plan(nq, nb, d, k, false);
-  FlatScratchGuard guard(dev, st);
+  ScratchUse guard(g_flat_scratch[dev], st);
   Scratch& sc = g_flat_scratch[dev];
   if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
   char* base = static_cast<char*>(sc.p);
@@ -528,7 +534,7 @@ int vs_flat_index_search(const vs_flat* ix, const float* q, int64_t nq, int32_t 
   const int d = ix->d, metric = ix->metric;
   const Planes* bp = ix->has_planes ? &ix->planes : nullptr;
   const KnnPlan plan = knn_plan(nq, nb, d, k, bp != nullptr);
-  FlatScratchGuard guard(dev, st);
+  ScratchUse guard(g_flat_scratch[dev], st);
   Scratch& sc = g_flat_scratch[dev];
   if (int rc = sc.reserve(plan.bytes + (size_t)nq * k * sizeof(u64))) return rc;
   char* base = static_cast<char*>(sc.p);
@@ -552,7 +558,7 @@ int vs_trim(void) {
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 16) return fail(VS_ERR_UNSUPPORTED, "vs_trim: device %d", dev);
-  std::lock_guard<std::mutex> lock(g_flat_mu);
+  std::lock_guard<std::mutex> lock(g_flat_scratch[dev].mu);
   HIP_TRY(hipDeviceSynchronize());   // nothing may still be using the buffer
   g_flat_scratch[dev].release();
   return VS_OK;
@@ -707,7 +713,7 @@ int vs_kmeans(const float* x, int64_t n, int32_t d, int32_t K, int32_t niter, fl
   DeviceBuf buf;
   if (int rc = buf.alloc(cv.off)) return rc;
   char* b = static_cast<char*>(buf.p);
-  FlatScratchGuard guard(dev, st);
+  ScratchUse guard(g_flat_scratch[dev], st);
   if (int rc = kmeans_rounds(x, n, d, K, niter, centroids, objective, reinterpret_cast<int32_t*>(b + o_idx),
                              reinterpret_cast<float*>(b + o_val), reinterpret_cast<int32_t*>(b + o_order),
                              reinterpret_cast<int64_t*>(b + o_off), g_flat_scratch[dev], st))
@@ -748,7 +754,7 @@ int vs_ivfpq_train(const float* x, int64_t n, int32_t d, int32_t metric, int32_t
   int32_t* order = reinterpret_cast<int32_t*>(b + o_order);
   int64_t* off = reinterpret_cast<int64_t*>(b + o_off);
   float* res = reinterpret_cast<float*>(b + o_res);
-  FlatScratchGuard guard(dev, st);
+  ScratchUse guard(g_flat_scratch[dev], st);
   Scratch& sc = g_flat_scratch[dev];
   // 1. coarse quantizer: k-means on the training vectors
   if (int rc = kmeans_rounds(x, n, d, nlist, niter, centroids, objective, idx, val, order, off, sc, st)) return rc;
@@ -1077,6 +1083,7 @@ int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t npro
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int npr = std::min<int>(nprobe, ix->g.nlist);
   const KnnPlan plan = knn_plan(nq, ix->g.nlist, ix->g.d, npr, ix->has_planes);
+  ScratchUse use(ix->scratch, st);
   if (int rc = ix->scratch.reserve(plan.bytes)) return rc;
   if (int rc = coarse_select(ix, plan, static_cast<char*>(ix->scratch.p), q, nq, npr, probes, coarse_dist, st)) return rc;
   HIP_TRY(hipGetLastError());
@@ -1170,6 +1177,7 @@ int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, i
   if (nq == 0) return VS_OK;
   SearchLayout L;
   search_layout(ix, nq, k, nprobe, &L);
+  ScratchUse use(ix->scratch, static_cast<hipStream_t>(hip_stream));
   if (int rc = ix->scratch.reserve(L.bytes)) return rc;
   return search_run("vs_ivfpq_search", ix, L, static_cast<char*>(ix->scratch.p), q, nq, k, out_dist, out_ids,
                     static_cast<hipStream_t>(hip_stream), true);
@@ -1185,6 +1193,7 @@ int vs_ivfpq_search_stats(const vs_ivfpq* ix, const float* q, int64_t nq, int32_
   }
   SearchLayout L;
   search_layout(ix, nq, k, nprobe, &L);
+  ScratchUse use(ix->scratch, st);
   if (int rc = ix->scratch.reserve(L.bytes)) return rc;
   return search_run("vs_ivfpq_search_stats", ix, L, static_cast<char*>(ix->scratch.p), q, nq, k, out_dist, out_ids,
                     st, true, stats);
@@ -1309,6 +1318,7 @@ int vs_ivfflat_search(const vs_ivfflat* fx, const float* q, int64_t nq, int32_t 
   const size_t o_knn = cv.take(plan.bytes);
   const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
   const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  ScratchUse use(ix->scratch, st);
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);
@@ -1456,6 +1466,7 @@ int vs_ivfsq8_search(const vs_ivfsq8* sx, const float* q, int64_t nq, int32_t k,
   const size_t o_knn = cv.take(plan.bytes);
   const size_t o_pr = cv.take((size_t)nq * npr * sizeof(int32_t));
   const size_t o_part = cv.take((size_t)nq * nsplit * k * sizeof(u64));
+  ScratchUse use(ix->scratch, st);
   if (int rc = ix->scratch.reserve(cv.off)) return rc;
   char* base = static_cast<char*>(ix->scratch.p);
   int32_t* probes = reinterpret_cast<int32_t*>(base + o_pr);

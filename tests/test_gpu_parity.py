@@ -130,6 +130,32 @@ def test_flat_searches_on_two_streams_share_the_work_space_safely(vs):
             np.testing.assert_array_equal(host(D), ref[i][0])
 
 
+def test_index_searches_on_two_streams_share_the_work_space_safely(vs):
+    """The same for the per-index work buffer of vs_ivfpq_search: two query batches searched on
+    two streams, back to back without synchronisation, equal the searches done one at a time."""
+    import torch
+    cfg = S.config("C3", nb=60_000, nq=400, ncomp=100, nlist=256)
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    ix = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), 8)
+    ix.add(dev(x))
+    qs = [dev(q[:200]), dev(q[200:])]
+    ref = [[host(t).copy() for t in ix.search(qs[i], 10, 16)] for i in range(2)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(6):
+        say("index, two streams, round %d" % rep)
+        outs = []
+        for i in (0, 1, 0, 1):
+            with torch.cuda.stream(streams[i]):
+                outs.append((i, ix.search(qs[i], 10, 16)))
+        torch.cuda.synchronize()
+        for i, (D, I) in outs:
+            np.testing.assert_array_equal(host(I), ref[i][1])
+            np.testing.assert_array_equal(host(D), ref[i][0])
+    ix.close()
+
+
 def test_flat_empty_database_and_no_queries(vs):
     import torch
     say("flat nb=0 / nq=0")
