@@ -366,7 +366,7 @@ void or_pq_norms(const uint8_t *codes, int64_t n, int d, const int32_t *list_of,
  *
  * nscanned[a] (may be NULL) receives the number of codes visited for query a.
  * probes_out (may be NULL) receives the probed lists, best first. */
-void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
+void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int coarse_metric, int nlist,
                      const float *centroids, int M, int nbits, const float *codebooks,
                      const int64_t *list_offsets, const uint8_t *codes, const int64_t *ids,
                      const float *norms, int k, int nprobe, int form, float *D, int64_t *I,
@@ -376,7 +376,10 @@ void or_ivfpq_search(const float *q, int64_t nq, int d, int metric, int nlist,
   if (nprobe > nlist) nprobe = nlist;
   int32_t *probes = (int32_t *)malloc(sizeof(int32_t) * nq * nprobe);
   float *cdist = (float *)malloc(sizeof(float) * nq * nprobe);
-  or_coarse_probe(q, nq, centroids, nlist, d, metric, nprobe, probes, cdist);
+  /* the lists to visit are the nprobe best under the COARSE metric (Sec. 5.1, the figure on
+   * maximum inner product search: an inner-product index may assign and probe by L2, the
+   * default there, or by inner product); the scores below are under the index metric */
+  or_coarse_probe(q, nq, centroids, nlist, d, coarse_metric, nprobe, probes, cdist);
   if (probes_out) memcpy(probes_out, probes, sizeof(int32_t) * nq * nprobe);
 
 #pragma omp parallel for schedule(dynamic, 1)

@@ -385,11 +385,14 @@ class OracleIVFPQ:
 
     add():    O2 assignment, O3/O4 residual encoding, O5 stable append.
     search(): O6 probes, O7 ADC on the decoded vector, O8 selection.
+    coarse_metric: the metric of list assignment and probing; the index metric unless given
+    (Sec. 5.1, maximum inner product search: an inner-product index may assign by L2).
     """
 
-    def __init__(self, d, metric, centroids, codebooks, nbits):
+    def __init__(self, d, metric, centroids, codebooks, nbits, coarse_metric=None):
         self.d = int(d)
         self.metric = int(metric)
+        self.coarse_metric = self.metric if coarse_metric is None else int(coarse_metric)
         self.centroids = np.ascontiguousarray(centroids, dtype=np.float32)
         self.codebooks = np.ascontiguousarray(codebooks, dtype=np.float32)
         self.nbits = int(nbits)
@@ -406,10 +409,10 @@ class OracleIVFPQ:
         self._relayout()
 
     @classmethod
-    def from_storage(cls, d, metric, centroids, codebooks, nbits, list_offsets, codes, ids):
+    def from_storage(cls, d, metric, centroids, codebooks, nbits, list_offsets, codes, ids, coarse_metric=None):
         """Wraps an already laid-out store (list l owns rows list_offsets[l] ..
         list_offsets[l+1] of codes / ids) so that search() can run on it."""
-        ix = cls(d, metric, centroids, codebooks, nbits)
+        ix = cls(d, metric, centroids, codebooks, nbits, coarse_metric)
         ix.list_offsets = np.ascontiguousarray(list_offsets, dtype=np.int64)
         ix.codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1, ix.code_size)
         ix.ids = np.ascontiguousarray(ids, dtype=np.int64)
@@ -441,7 +444,7 @@ class OracleIVFPQ:
         n = x.shape[0]
         if ids is None:  # sequential ids continue from ntotal (Sec. 6.1)
             ids = np.arange(self.ntotal, self.ntotal + n, dtype=np.int64)
-        list_of = assign(x, self.centroids, self.metric)
+        list_of = assign(x, self.centroids, self.coarse_metric)
         codes = pq_encode(x, list_of, self.centroids, self.codebooks, self.nbits)
         self.add_ids = np.concatenate([self.add_ids, np.asarray(ids, dtype=np.int64)])
         self.add_list_of = np.concatenate([self.add_list_of, list_of])
@@ -464,7 +467,7 @@ class OracleIVFPQ:
         probes = np.empty((nq, npr), dtype=np.int32)
         _load().or_ivfpq_search(
             _ptr(q), ctypes.c_int64(nq), ctypes.c_int(self.d), ctypes.c_int(self.metric),
-            ctypes.c_int(self.nlist), _ptr(self.centroids), ctypes.c_int(self.M),
+            ctypes.c_int(self.coarse_metric), ctypes.c_int(self.nlist), _ptr(self.centroids), ctypes.c_int(self.M),
             ctypes.c_int(self.nbits), _ptr(self.codebooks), _ptr(self.list_offsets),
             _ptr(self.codes), _ptr(self.ids), _ptr(self.norms), ctypes.c_int(k),
             ctypes.c_int(nprobe), ctypes.c_int(form), _ptr(D), _ptr(I), _ptr(nscanned), _ptr(probes))

@@ -304,6 +304,43 @@ def test_ivfpq_search_with_fewer_probes_than_lists_is_numpy_over_the_probed_memb
         assert not np.allclose(D, np.take_along_axis((q.astype(np.float64) @ (dec - ix.centroids[ix.add_list_of]).T), I, 1), rtol=1e-3)
 
 
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_inner_product_index_with_l2_assignment_is_numpy_with_l2_lists_and_ip_scores(oracle, nbits):
+    # Sec. 5.1, maximum inner product search: lists chosen by L2 (at add and at search), scores by
+    # inner product on the decoded vectors.  Everything from numpy: the L2-nearest centroid of every
+    # vector, the nprobe L2-nearest lists of every query, inner products with the reconstructions.
+    # The centroids get very different norms, so that L2 and inner-product assignment disagree.
+    cfg = S.config("C1", nb=2500, nq=40)
+    x, q = S.make_data(cfg)
+    M = cfg["M"] if nbits == 8 else 16
+    cent = S.make_centroids(x, cfg["nlist"], cfg["seed"]) * np.linspace(0.3, 3.0, cfg["nlist"], dtype=np.float32)[:, None]
+    cb = S.make_codebooks(x, cent, M, nbits, cfg["seed"])
+    ix = oracle.OracleIVFPQ(cfg["d"], IP, cent, cb, nbits, coarse_metric=L2)
+    ix.add(x)
+    by_l2 = np.argmin(np_pairwise(x, cent, L2), axis=1)
+    by_ip = np.argmax(np_pairwise(x, cent, IP), axis=1)
+    np.testing.assert_array_equal(ix.add_list_of, by_l2)
+    assert (by_l2 != by_ip).mean() > 0.3                      # the option changes the index
+    nprobe, k = 3, 12
+    D, I = ix.search(q, k, nprobe)
+    dec = oracle.pq_decode(ix.add_codes, ix.add_list_of, ix.centroids, ix.codebooks, nbits)
+    order = np.argsort(np_pairwise(q, cent, L2).astype(np.float32), axis=1, kind="stable")[:, :nprobe]
+    full = np_pairwise(q, dec, IP)
+    for a in range(q.shape[0]):
+        cand = np.flatnonzero(np.isin(ix.add_list_of, order[a]))
+        s32 = full[a, cand].astype(np.float32)
+        o = np.lexsort((ix.add_ids[cand], -s32))[:k]
+        np.testing.assert_array_equal(I[a], ix.add_ids[cand][o])
+        np.testing.assert_allclose(D[a], s32[o], rtol=1e-6)
+    # the table form (form 1: bias <q, c_l> + sum of per-query table entries) agrees with it
+    D1, I1 = ix.search(q, k, nprobe, form=1)
+    np.testing.assert_allclose(D1, D, rtol=1e-4, atol=1e-4)
+    # and the default (coarse metric = index metric) is a different index
+    ix2 = oracle.OracleIVFPQ(cfg["d"], IP, cent, cb, nbits)
+    ix2.add(x)
+    np.testing.assert_array_equal(ix2.add_list_of, by_ip)
+
+
 @pytest.mark.parametrize("metric", [IP, L2])
 def test_ivfsq8_search_with_fewer_probes_than_lists_is_numpy_over_the_probed_members(oracle, metric):
     rng = np.random.default_rng(53)
