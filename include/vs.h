@@ -323,6 +323,19 @@ VS_API int vs_ivfpq_coarse(const vs_ivfpq* ix, const float* q, int64_t nq, int32
  */
 enum { VS_ST_RESIDUAL_TABLES = 0, VS_ST_STORED_NORMS = 1, VS_ST_PRECOMPUTED_TABLES = 2 };
 VS_API int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type);
+/*
+ * The metric under which vectors are assigned to lists and lists are probed, when it is not the
+ * index metric (Sec. 5.1, the figure on maximum inner product search: an inner-product index
+ * may assign by L2 -- the paper's default -- or by inner product).  Here the default is the index
+ * metric for both; vs_ivfpq_set_coarse_metric(ix, VS_METRIC_L2) on a VS_METRIC_IP index makes
+ * vs_ivfpq_add take the L2-nearest centroid and searches probe the nprobe L2-nearest lists, while
+ * scores stay inner products <q, c_l> + sum_m <q_m, T_m[c_m]> (the <q, c_l> of the probed lists is
+ * then computed after the coarse quantizer, one fused-multiply-add chain each).
+ * vs_ivfpq_coarse returns the values of the coarse metric.  To be called while the index is
+ * empty.  Errors: unknown metric; VS_METRIC_IP on an L2 index; an index that already holds
+ * vectors assigned under the other metric.
+ */
+VS_API int vs_ivfpq_set_coarse_metric(vs_ivfpq* ix, int32_t metric);
 /* the stored norms, in storage order: DEVICE [ntotal] fp32 */
 VS_API int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream);
 

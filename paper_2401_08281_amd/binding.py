@@ -421,6 +421,10 @@ def vs_ivfpq_set_search_type(h, search_type):
     _check(lib().vs_ivfpq_set_search_type(h, int(search_type)))
 
 
+def vs_ivfpq_set_coarse_metric(h, metric):
+    _check(lib().vs_ivfpq_set_coarse_metric(h, int(metric)))
+
+
 def vs_ivfpq_get_norms(h, device):
     norms = torch.empty(vs_ivfpq_ntotal(h), dtype=torch.float32, device=device)
     _check(lib().vs_ivfpq_get_norms(h, _p(norms), _stream()))
@@ -696,6 +700,9 @@ class IVFPQ:
 
     def set_search_type(self, search_type):
         vs_ivfpq_set_search_type(self.h, search_type)
+
+    def set_coarse_metric(self, metric):
+        vs_ivfpq_set_coarse_metric(self.h, metric)
 
     def norms(self):
         return vs_ivfpq_get_norms(self.h, self.device)

@@ -328,6 +328,7 @@ struct vs_ivfpq {
   Planes c_planes;
   bool has_planes = false;
   bool assign_probed = false;   // an add has run its assignment through the matrix-core route
+  int coarse_metric = -1;       // metric of list assignment and probing; -1: the index metric (g.metric)
   mutable Scratch scratch;
 };
 
@@ -345,6 +346,8 @@ struct vs_flat {
   Planes planes;
   bool has_planes = false;
 };
+
+inline int coarse_metric_of(const vs_ivfpq* ix) { return ix->coarse_metric < 0 ? ix->g.metric : ix->coarse_metric; }
 
 // IVF-SQ8 likewise; core.codes holds d bytes per vector (core.g: M = d, nbits = 8)
 struct vs_ivfsq8 {
@@ -872,6 +875,7 @@ struct Placement {
 int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, Placement* pl,
                          hipStream_t st, const char* who) {
   const IvfpqDims& g = ix->g;
+  const int cmetric = ix->coarse_metric < 0 ? g.metric : ix->coarse_metric;   // lists are chosen under the coarse metric
   if (n >= (1ll << 31)) return fail(VS_ERR_UNSUPPORTED, "%s: at most 2^31 - 1 vectors per call", who);
   // scratch: work space of the MFMA assignment (pieces of at most kAssignPiece vectors) |
   // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets | work space of the placement
@@ -908,7 +912,7 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
       const int64_t ni = i0 == 0 && first_piece > 0 ? first_piece : std::min(kAssignPiece, n - i0);
       SelectOut o;
       o.idx32 = pl->list_of + i0;
-      if (int rc = knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, g.metric, 1,
+      if (int rc = knn_run(plan, base + o_knn, x + i0 * g.d, ni, ix->centroids, g.nlist, g.d, cmetric, 1,
                            ix->has_planes ? &ix->c_planes : nullptr, o, st, -1, -1))
         return rc;
       i0 += ni;
@@ -916,7 +920,7 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
     ix->assign_probed = true;
   } else {
     launch_fill_u64(keys, n, 0xFFFFFFFFFFFFFFFFull, st);
-    launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, g.metric, keys, st);
+    launch_canon_argbest(x, n, ix->centroids, g.nlist, g.d, cmetric, keys, st);
     launch_keys_to_index32(keys, n, pl->list_of, st);
   }
 
@@ -1052,6 +1056,18 @@ int vs_ivfpq_set_search_type(vs_ivfpq* ix, int32_t search_type) {
   return VS_OK;
 }
 
+int vs_ivfpq_set_coarse_metric(vs_ivfpq* ix, int32_t metric) {
+  if (!ix) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_coarse_metric: index is null");
+  if (metric != VS_METRIC_L2 && metric != VS_METRIC_IP)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_coarse_metric: unknown metric %d", metric);
+  if (ix->g.metric == VS_METRIC_L2 && metric != VS_METRIC_L2)
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_coarse_metric: an L2 index chooses its lists by L2");
+  if (ix->ntotal > 0 && metric != coarse_metric_of(ix))
+    return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_set_coarse_metric: the index already holds vectors assigned under the other metric");
+  ix->coarse_metric = metric;
+  return VS_OK;
+}
+
 int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
   if (!ix || !norms) return fail(VS_ERR_INVALID_ARG, "vs_ivfpq_get_norms: null pointer");
   if (ix->ntotal == 0) return VS_OK;
@@ -1061,14 +1077,15 @@ int vs_ivfpq_get_norms(const vs_ivfpq* ix, float* norms, void* hip_stream) {
   return VS_OK;
 }
 
-// coarse quantizer: the npr best lists per query, best first, with their canon values
+// coarse quantizer: the npr best lists per query, best first, with their canon values (under the
+// coarse metric)
 static int coarse_select(const vs_ivfpq* ix, const KnnPlan& plan, char* ws, const float* q,
                          int64_t nq, int npr, int32_t* probes, float* cdist, hipStream_t st,
                          bool timed = true, const int** fallback_count = nullptr) {
   SelectOut out;
   out.val = cdist;
   out.idx32 = probes;
-  return knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, ix->g.metric, npr,
+  return knn_run(plan, ws, q, nq, ix->centroids, ix->g.nlist, ix->g.d, coarse_metric_of(ix), npr,
                  ix->has_planes ? &ix->c_planes : nullptr, out, st, timed ? VS_STAGE_COARSE_DIST : -1,
                  timed ? VS_STAGE_COARSE_SELECT : -1, fallback_count);
 }
@@ -1144,6 +1161,10 @@ int search_run(const char* who, const vs_ivfpq* ix, const SearchLayout& L, char*
   const int* fallback_count = nullptr;
   if (int rc = coarse_select(ix, L.plan, base + L.o_knn, q, nq, L.npr, probes, cdist, st, timed, &fallback_count))
     return rc;
+  // an inner-product index that chooses its lists by L2: the scan's per-list term is <q, c_l>,
+  // not the L2 distance the coarse quantizer returned
+  if (g.metric == VS_METRIC_IP && coarse_metric_of(ix) == VS_METRIC_L2)
+    launch_probe_inner_products(q, nq, g.d, ix->centroids, probes, L.npr, cdist, st);
   if (stats)
     launch_search_stats(probes, nq * L.npr, ix->list_off, fallback_count, L.plan.mfma ? nq : 0,
                         reinterpret_cast<long long*>(stats), st);

@@ -92,6 +92,10 @@ size_t ivfpq_query_table_bytes(const IvfpqDims& g, int64_t nq);
 size_t ivf_place_work_bytes(int64_t n, int nlist);
 int* launch_ivf_place(const int32_t* list_of, int64_t n, int nlist, const int64_t* old_off, char* work,
                       int64_t* dest, int64_t* new_off, hipStream_t st);
+// cdist[a][p] = <q_a, c_{probes[a][p]}> as one fp32 fused-multiply-add chain in dimension order
+// (the value the coarse quantizer itself returns under the inner-product metric); probes < 0 are left alone
+void launch_probe_inner_products(const float* q, int64_t nq, int d, const float* centroids,
+                                 const int32_t* probes, int nprobe, float* cdist, hipStream_t st);
 // stats[0] = sum over the n (query, probe) pairs of the probed list's size, stats[1] = pairs whose
 // list is not empty, stats[2] = mfma_rows, stats[3] = *fallback_count (0 if null); device memory,
 // written in stream order.

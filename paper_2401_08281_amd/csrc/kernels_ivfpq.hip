@@ -1263,6 +1263,22 @@ __global__ void pq_codebooks_by_entry_kernel(const float* __restrict__ codebooks
   out[i] = codebooks[((int64_t)m * K + j) * dsub + u];
 }
 
+// One lane per (query, probe): the inner product of the query with the probed centroid, canon chain.
+__global__ __launch_bounds__(256) void probe_inner_products_kernel(const float* __restrict__ q, int64_t nq, int d,
+                                                                   const float* __restrict__ centroids,
+                                                                   const int32_t* __restrict__ probes, int nprobe,
+                                                                   float* __restrict__ cdist) {
+  const int64_t e = blockIdx.x * 256ll + threadIdx.x;
+  if (e >= nq * nprobe) return;
+  const int l = probes[e];
+  if (l < 0) return;
+  const float* __restrict__ qa = q + (e / nprobe) * d;
+  const float* __restrict__ c = centroids + (int64_t)l * d;
+  float acc = 0.f;
+  for (int t = 0; t < d; ++t) acc = __builtin_fmaf(qa[t], c[t], acc);
+  cdist[e] = acc;
+}
+
 // What one search scanned: list sizes summed over its (query, probe) pairs.  stats was zeroed in
 // stream order before this launch.
 __global__ __launch_bounds__(256) void search_stats_kernel(const int32_t* __restrict__ probes, int64_t n,
@@ -1388,6 +1404,14 @@ void launch_pq_norms(const IvfpqDims& g, const uint8_t* tmp_codes, int64_t n, co
 void launch_row_norms(const float* x, int64_t n, int d, float* norms, hipStream_t st) {
   if (n <= 0) return;
   hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, n, d, norms);
+}
+
+void launch_probe_inner_products(const float* q, int64_t nq, int d, const float* centroids,
+                                 const int32_t* probes, int nprobe, float* cdist, hipStream_t st) {
+  const int64_t n = nq * nprobe;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(probe_inner_products_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, q, nq, d,
+                     centroids, probes, nprobe, cdist);
 }
 
 void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,

@@ -29,7 +29,7 @@ vs_flat_search vs_flat_create vs_flat_destroy vs_flat_ntotal vs_flat_add vs_flat
 vs_trim vs_refine vs_kmeans vs_ivfpq_train
 vs_ivfpq_create vs_ivfpq_add vs_ivfpq_search vs_ivfpq_search_stats vs_ivfpq_search_static vs_ivfpq_destroy
 vs_ivfpq_ntotal vs_ivfpq_code_size vs_ivfpq_get_list_sizes vs_ivfpq_get_assignments vs_ivfpq_get_codes
-vs_ivfpq_coarse vs_ivfpq_set_search_type vs_ivfpq_get_norms
+vs_ivfpq_coarse vs_ivfpq_set_search_type vs_ivfpq_set_coarse_metric vs_ivfpq_get_norms
 vs_ivfflat_create vs_ivfflat_destroy vs_ivfflat_ntotal vs_ivfflat_add vs_ivfflat_search
 vs_ivfflat_get_list_sizes vs_ivfflat_get_storage
 vs_ivfsq8_create vs_ivfsq8_destroy vs_ivfsq8_ntotal vs_ivfsq8_add vs_ivfsq8_search
@@ -147,6 +147,7 @@ def test_argument_errors_are_reported_without_a_device(L):
     assert L.vs_ivfpq_search(nul, one, 5, 10, 4, one, one, nul) == INVALID
     assert L.vs_ivfpq_search_stats(nul, one, 5, 10, 4, one, one, one, nul) == INVALID
     assert L.vs_ivfpq_search_static(nul, one, 5, 10, 4, one, one, nul) == INVALID
+    assert L.vs_ivfpq_set_coarse_metric(nul, 0) == INVALID
     assert L.vs_ivfpq_ntotal(nul) == -1 and L.vs_ivfpq_code_size(nul) == -1
     L.vs_ivfpq_destroy(nul)                                                           # allowed
 

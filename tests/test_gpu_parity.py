@@ -388,6 +388,46 @@ def test_ivfpq_matches_oracle(vs, oracle, name):
     ix.close()
 
 
+@pytest.mark.parametrize("name", ["c1_ip", "c3_small_ip", "ip_8bit", "pq64x8_ip", "c5_small"])
+def test_inner_product_index_with_l2_assignment_matches_oracle(vs, oracle, name):
+    """Sec. 5.1, maximum inner product search: lists chosen by L2 at add and at search, scores by
+    inner product.  The centroids are scaled to very different norms so that L2 and inner-product
+    assignment disagree; storage is bit-exact, probes are the L2 probes, results match the oracle."""
+    cfg, searches = IVF_CASES[name]
+    assert cfg["metric"] == IP
+    say("ip index, l2 assignment: %s nb=%d d=%d nlist=%d M=%d nbits=%d" % (
+        name, cfg["nb"], cfg["d"], cfg["nlist"], cfg["M"], cfg["nbits"]))
+    x, q = S.make_data(cfg)
+    cent, cb = S.make_index_params(cfg, x)
+    cent = (cent * np.linspace(0.5, 2.0, cfg["nlist"], dtype=np.float32)[:, None]).astype(np.float32)
+    ix = vs.IVFPQ(cfg["d"], IP, dev(cent), dev(cb), cfg["nbits"])
+    ix.set_coarse_metric(L2)
+    orc = oracle.OracleIVFPQ(cfg["d"], IP, cent, cb, cfg["nbits"], coarse_metric=L2)
+    half = cfg["nb"] // 2
+    ix.add(dev(x[:half])); ix.add(dev(x[half:]))
+    orc.add(x[:half]); orc.add(x[half:])
+    check_storage(ix, orc)
+    assert (orc.add_list_of != oracle.assign(x, cent, IP)).mean() > 0.05     # the option changes the index
+    with pytest.raises(vs.VSError):
+        ix.set_coarse_metric(IP)                                   # not once vectors are stored
+    xn = float(np.sqrt(orc.norms.max()))
+    for k, nprobe in searches:
+        say("  search k=%d nprobe=%d" % (k, nprobe))
+        probes, cdist = ix.coarse(dev(q), nprobe)
+        po, co = oracle.coarse_probe(q, cent, nprobe, L2)
+        np.testing.assert_array_equal(host(probes), po)
+        np.testing.assert_array_equal(host(cdist), co)
+        D, I = ix.search(dev(q), k, nprobe)
+        Do, Io = orc.search(q, k + EXTRA, nprobe)
+        same = check_search(host(D), host(I), Do, Io, IP, q, xn)
+        assert same > 0.99, same
+    ix.close()
+    l2 = vs.IVFPQ(cfg["d"], L2, dev(cent), dev(cb), cfg["nbits"])
+    with pytest.raises(vs.VSError):
+        l2.set_coarse_metric(IP)
+    l2.close()
+
+
 def test_ivfpq_add_in_pieces_with_custom_ids(vs, oracle):
     cfg = S.config("C1", nb=6_000)
     say("ivfpq pieces + custom ids")
