@@ -186,3 +186,45 @@ def test_knn_workspace_covers_every_piece_size():
     assert vs.vs_knn_workspace_bytes(0, 10, 8, 1) == 0
     with pytest.raises(vs.VSError):
         vs.vs_knn_workspace_bytes(10, 10, 0, 1)
+
+
+def test_bench_traffic_record_is_stamped_and_ignored_when_the_kernels_change(tmp_path, monkeypatch):
+    """bench.py --record-traffic (host only): two counter files of a profiler run become one entry
+    of profiles/traffic.json, scaled by the named 1 GiB copy kernel and stamped with the scan
+    kernels' source text; load_traffic returns it for that text only."""
+    import csv
+    import importlib
+    import json
+    import sys
+    sys.path.insert(0, ROOT)
+    bench = importlib.import_module("bench")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    (tmp_path / "profiles").mkdir()
+    src = tmp_path / "paper_2401_08281_amd" / "csrc"
+    src.mkdir(parents=True)
+    for name in bench.SCAN_SOURCES:
+        (src / name).write_text("// " + name)
+    def counters(folder, counter, scan_kib, copy_kib):
+        d = tmp_path / folder
+        d.mkdir()
+        with open(d / "x_counter_collection.csv", "w", newline="") as f:
+            w = csv.DictWriter(f, fieldnames=["Kernel_Name", "Counter_Name", "Counter_Value"])
+            w.writeheader()
+            for v in (scan_kib, scan_kib + 2.0):
+                w.writerow({"Kernel_Name": "void ivfpq_scan_bank_kernel<32, 3, 0, 4, 256>(float const*)",
+                            "Counter_Name": counter, "Counter_Value": v})
+            w.writerow({"Kernel_Name": "vs_calibrate_copy_kernel(uint4 const*, uint4*, unsigned long)",
+                        "Counter_Name": counter, "Counter_Value": copy_kib})
+            w.writerow({"Kernel_Name": "other_kernel", "Counter_Name": counter, "Counter_Value": 1e9})
+        return str(d)
+    class Args:
+        workload, nprobe, search_type = "C4", None, "tables"
+    Args.record_traffic = [counters("f", "FETCH_SIZE", 1000.0, 524288.0), counters("w", "WRITE_SIZE", 10.0, 1048576.0)]
+    assert bench.record_traffic(Args) == 0
+    rec = json.load(open(tmp_path / "profiles" / "traffic.json"))["ivfpq_scan_C4_nprobe64"]
+    assert rec["fetch_scale"] == 2.0 and rec["write_scale"] == 1.0
+    assert rec["fetch_bytes"] == int(1001.0 * 1024 * 2.0) and rec["write_bytes"] == int(11.0 * 1024)
+    assert bench.load_traffic("ivfpq_scan_C4_nprobe64") == rec["hbm_bytes_per_launch"]
+    (src / bench.SCAN_SOURCES[0]).write_text("// changed")
+    assert bench.load_traffic("ivfpq_scan_C4_nprobe64") is None
+    assert bench.load_traffic("no_such_key") is None
