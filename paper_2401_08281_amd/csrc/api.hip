@@ -165,6 +165,7 @@ void tile_shape(int64_t na, int64_t nb, int64_t* rows, int64_t* cols) {
 struct Planes {
   unsigned short* hi = nullptr;
   unsigned short* lo = nullptr;
+  unsigned short* h16 = nullptr;   // fp16 heads, at lo + (padded rows) * d
   float* norm = nullptr;
   PrepInfo* info = nullptr;
   int known_bf16 = -1;          // info->all_bf16 once the host has read it back, else -1
@@ -172,22 +173,24 @@ struct Planes {
 };
 size_t planes_bytes(int64_t n, int d) {
   n = mfma_padded_rows(n);
-  return 2 * align_up((size_t)n * d * sizeof(unsigned short)) + align_up((size_t)n * sizeof(float)) +
-         align_up(sizeof(PrepInfo));
+  return align_up((size_t)n * d * sizeof(unsigned short)) + align_up((size_t)2 * n * d * sizeof(unsigned short)) +
+         align_up((size_t)n * sizeof(float)) + align_up(sizeof(PrepInfo));
 }
 Planes carve_planes(char* base, int64_t n, int d) {
   Planes p;
   n = mfma_padded_rows(n);
   size_t o = 0;
   p.hi = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));
-  p.lo = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)n * d * sizeof(unsigned short));
+  // (operand preparation writes the fp16 heads right behind the bf16 tails: one block of two planes)
+  p.lo = reinterpret_cast<unsigned short*>(base + o); o += align_up((size_t)2 * n * d * sizeof(unsigned short));
+  p.h16 = p.lo + (size_t)n * d;
   p.norm = reinterpret_cast<float*>(base + o); o += align_up((size_t)n * sizeof(float));
   p.info = reinterpret_cast<PrepInfo*>(base + o);
   return p;
 }
 MfmaOperand operand(const float* x, int64_t n, const Planes& p) {
   MfmaOperand m;
-  m.x = x; m.hi = p.hi; m.lo = p.lo; m.norm = p.norm; m.info = p.info; m.n = n;
+  m.x = x; m.hi = p.hi; m.lo = p.lo; m.h16 = p.h16; m.norm = p.norm; m.info = p.info; m.n = n;
   m.known_bf16 = p.known_bf16;
   m.try_heads_only = p.try_heads_only;
   return m;

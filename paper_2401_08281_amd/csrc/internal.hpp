@@ -129,6 +129,7 @@ struct MfmaOperand {
   const float* x;             // [n, d] original fp32 rows
   const unsigned short* hi;   // [n, d] bf16 heads
   const unsigned short* lo;   // [n, d] bf16 tails
+  const unsigned short* h16;  // [n, d] fp16 heads (written by operand preparation right behind the tails)
   const float* norm;          // [n] squared norms
   const PrepInfo* info;
   int64_t n;

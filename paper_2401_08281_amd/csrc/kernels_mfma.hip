@@ -39,6 +39,34 @@ __device__ __forceinline__ unsigned short bf16_rn_bits(float f) {
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) {
   return __uint_as_float(((u32)b) << 16);
 }
+// fp16 image of a float, round to nearest even, subnormals kept (the matrix cores take them as
+// they are)
+__device__ __forceinline__ unsigned short f16_rn_bits(float f) {
+  return __builtin_bit_cast(unsigned short, (_Float16)f);
+}
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+// One matrix product on 16-byte operand fragments that hold eight bf16 or (F16) eight fp16 values.
+template <bool F16>
+__device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+// Operands whose values fit fp16 (|v| <= sqrt(max |row|^2) <= 2^15): their fp16 heads exist.
+__device__ __forceinline__ bool f16_heads_ok(const PrepInfo* a, const PrepInfo* b) {
+  return a->max_norm_bits <= 0x4E800000u && b->max_norm_bits <= 0x4E800000u;   // 2^30 as float bits
+}
+// Which operand-precision variant a call runs (every kernel of the call evaluates this on the
+// same flags): 0 one product on the bf16 heads (both operands exactly bf16), 3 one product on the
+// fp16 heads (the attempt on an index's own operand, see PrepInfo::heads_only), 1 two products
+// (A exactly bf16, long A), 2 three products.
+__device__ __forceinline__ int precision_variant(const PrepInfo* a, const PrepInfo* b, int hbit, bool allow_two) {
+  const bool ea = a->all_bf16 != 0, eb = b->all_bf16 != 0;
+  if (ea && eb) return 0;
+  if ((b->heads_only & (u32)hbit) && f16_heads_ok(a, b)) return 3;
+  return ea && allow_two ? 1 : 2;
+}
 
 // ---------------------------------------------------------------------------
 // Operand preparation: bf16 head / tail planes, fp32 squared norms, and the
@@ -74,29 +102,34 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
       const float4 a = *reinterpret_cast<const float4*>(x + off);
       const float4 b = *reinterpret_cast<const float4*>(x + off + 4);
       v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-      unsigned short h[8], l[8];
+      unsigned short h[8], l[8], f[8];
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         h[t] = bf16_rn_bits(v[t]);
         const float rem = v[t] - bf16_bits_to_f32(h[t]);      // exact in fp32
         l[t] = bf16_rn_bits(rem);
+        f[t] = f16_rn_bits(v[t]);
         is_bf16 = is_bf16 && rem == 0.f;
         is_int = is_int && v[t] == __builtin_rintf(v[t]);
         is_nonneg = is_nonneg && v[t] >= 0.f;
         ss = __builtin_fmaf(v[t], v[t], ss);
       }
-      uint4 hv, lv;
+      uint4 hv, lv, fv;
       hv.x = h[0] | ((u32)h[1] << 16); hv.y = h[2] | ((u32)h[3] << 16);
       hv.z = h[4] | ((u32)h[5] << 16); hv.w = h[6] | ((u32)h[7] << 16);
       lv.x = l[0] | ((u32)l[1] << 16); lv.y = l[2] | ((u32)l[3] << 16);
       lv.z = l[4] | ((u32)l[5] << 16); lv.w = l[6] | ((u32)l[7] << 16);
+      fv.x = f[0] | ((u32)f[1] << 16); fv.y = f[2] | ((u32)f[3] << 16);
+      fv.z = f[4] | ((u32)f[5] << 16); fv.w = f[6] | ((u32)f[7] << 16);
       *reinterpret_cast<uint4*>(hi + off) = hv;
       *reinterpret_cast<uint4*>(lo + off) = lv;
+      *reinterpret_cast<uint4*>(lo + n_pad * d + off) = fv;   // the fp16 heads: a third plane behind the tails
     } else if (r < rows_per_group && row0 + r < n_pad) {   // padding rows: zeros (never selected)
       const int64_t off = (row0 + r) * d + c * 8;
       const uint4 z = make_uint4(0u, 0u, 0u, 0u);
       *reinterpret_cast<uint4*>(hi + off) = z;
       *reinterpret_cast<uint4*>(lo + off) = z;
+      *reinterpret_cast<uint4*>(lo + n_pad * d + off) = z;
     }
     part[pb][tid] = ss;
     // (the buffer written two groups later is safe: every lane passes the next group's
@@ -158,25 +191,29 @@ __global__ __launch_bounds__(256) void prep_panel_kernel(const float* __restrict
         const float4 a = *reinterpret_cast<const float4*>(x + off);
         const float4 bq = *reinterpret_cast<const float4*>(x + off + 4);
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = bq.x; v[5] = bq.y; v[6] = bq.z; v[7] = bq.w;
-        unsigned short h[8], l[8];
+        unsigned short h[8], l[8], f[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
           h[t] = bf16_rn_bits(v[t]);
           const float rem = v[t] - bf16_bits_to_f32(h[t]);      // exact in fp32
           l[t] = bf16_rn_bits(rem);
+          f[t] = f16_rn_bits(v[t]);
           is_bf16 = is_bf16 && rem == 0.f;
           is_int = is_int && v[t] == __builtin_rintf(v[t]);
           is_nonneg = is_nonneg && v[t] >= 0.f;
           ss = __builtin_fmaf(v[t], v[t], ss);
         }
-        uint4 hv, lv;
+        uint4 hv, lv, fv;
         hv.x = h[0] | ((u32)h[1] << 16); hv.y = h[2] | ((u32)h[3] << 16);
         hv.z = h[4] | ((u32)h[5] << 16); hv.w = h[6] | ((u32)h[7] << 16);
         lv.x = l[0] | ((u32)l[1] << 16); lv.y = l[2] | ((u32)l[3] << 16);
         lv.z = l[4] | ((u32)l[5] << 16); lv.w = l[6] | ((u32)l[7] << 16);
+        fv.x = f[0] | ((u32)f[1] << 16); fv.y = f[2] | ((u32)f[3] << 16);
+        fv.z = f[4] | ((u32)f[5] << 16); fv.w = f[6] | ((u32)f[7] << 16);
         const int64_t out = ((int64_t)(c >> 1) * n_pad + row) * 16 + (c & 1) * 8;
         *reinterpret_cast<uint4*>(hi + out) = hv;
         *reinterpret_cast<uint4*>(lo + out) = lv;
+        *reinterpret_cast<uint4*>(lo + n_pad * d + out) = fv;   // the fp16 heads: a third plane, same panels
       }
     } else {                                               // padding rows: zeros (never selected)
       const uint4 z = make_uint4(0u, 0u, 0u, 0u);
@@ -184,6 +221,7 @@ __global__ __launch_bounds__(256) void prep_panel_kernel(const float* __restrict
         const int64_t out = ((int64_t)(c >> 1) * n_pad + row) * 16 + (c & 1) * 8;
         *reinterpret_cast<uint4*>(hi + out) = z;
         *reinterpret_cast<uint4*>(lo + out) = z;
+        *reinterpret_cast<uint4*>(lo + n_pad * d + out) = z;
       }
     }
     part[pb][s][r] = ss;
@@ -261,8 +299,9 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
                        int allow_two) {
   // PREC: which products the operands need.  0: both are exactly bf16 -- heads only.  1: A is
   // exact, B is not -- A's tails are zero, so head x head + head x tail (two passes; A's tail
-  // plane is never read).  2: head x head + head x tail + tail x head (three passes).
-  constexpr bool THREE = PREC == 2, LOB = PREC >= 1;
+  // plane is never read).  2: head x head + head x tail + tail x head (three passes).  3: one
+  // product on the fp16 heads, which the host passes in place of the bf16 heads (Ahi, Bhi).
+  constexpr bool THREE = PREC == 2, LOB = PREC == 1 || PREC == 2, F16 = PREC == 3;
   constexpr int D = KSTEPS * 16, BN = 64, LDB = D + 8;            // LDS row stride in bf16 elements
   constexpr int NPL = LOB ? 2 : 1;                                // planes of B in LDS
   constexpr int CHUNKS = BN * (D / 8);                            // 16-byte chunks per plane per step
@@ -270,12 +309,8 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
   // the variants that may be needed are all launched; those that do not match the operands'
   // flags leave at once (the two-pass variant is only enqueued for long A: allow_two)
-  {
-    const bool ea = Ainfo->all_bf16 != 0, eb = Binfo->all_bf16 != 0;
-    // allow_two: bit 0 = the two-pass variant was enqueued; bits 1.. = this call's bit of heads_only
-    const int want = (ea && eb) || (Binfo->heads_only & (u32)(allow_two >> 1)) ? 0 : (ea && (allow_two & 1) ? 1 : 2);
-    if (want != PREC) return;
-  }
+  // allow_two: bit 0 = the two-pass variant was enqueued; bits 1.. = this call's bit of heads_only
+  if (precision_variant(Ainfo, Binfo, allow_two >> 1, (allow_two & 1) != 0) != PREC) return;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned short* bt = reinterpret_cast<unsigned short*>(smem);   // [2 buffers][NPL][BN][LDB]
@@ -428,9 +463,9 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         // the first product starts from 0 (MODE 0) or from the row thresholds (MODE 1)
-        m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], ch, kk == 0 ? tr[rb] : m[rb][cb], 0, 0, 0);
-        if constexpr (LOB) m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb][kk], cl, m[rb][cb], 0, 0, 0);
-        if constexpr (THREE) m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb][kk], ch, m[rb][cb], 0, 0, 0);
+        m[rb][cb] = mfma_32x32x16<F16>(ah[rb][kk], ch, kk == 0 ? tr[rb] : m[rb][cb]);
+        if constexpr (LOB) m[rb][cb] = mfma_32x32x16<false>(ah[rb][kk], cl, m[rb][cb]);
+        if constexpr (THREE) m[rb][cb] = mfma_32x32x16<false>(al[rb][kk], ch, m[rb][cb]);
       }
       if (f + PF < NF) {
         rh[f % PF] = *reinterpret_cast<const bf16x8*>(bth + FRAG_OFF(f + PF));
@@ -441,7 +476,7 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
     __builtin_amdgcn_sched_group_barrier(0x100, PF * NPL, 0);                       // LDS reads
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-      __builtin_amdgcn_sched_group_barrier(0x008, RB * (PREC + 1), 0);              // matrix products
+      __builtin_amdgcn_sched_group_barrier(0x008, RB * (1 + (LOB ? 1 : 0) + (THREE ? 1 : 0)), 0);   // matrix products
       if (f + PF < NF) __builtin_amdgcn_sched_group_barrier(0x100, NPL, 0);
     }
     const float b0 = bns[buf * BN + (lane & 31)], b1 = bns[buf * BN + 32 + (lane & 31)];
@@ -564,7 +599,7 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
 // The selection epilogue runs once per tile, after the last stage -- MODE 0 / MODE 1 exactly
 // as in mfma_sweep_kernel.
 // ---------------------------------------------------------------------------
-template <int METRIC, int MODE, bool THREE>
+template <int METRIC, int MODE, int PREC>   // PREC: 0, 2 or 3 as in mfma_sweep_kernel
 __global__ __launch_bounds__(512)
 void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned short* __restrict__ Alo,
                           const float* __restrict__ Anorm, const PrepInfo* __restrict__ Ainfo, int64_t na,
@@ -575,11 +610,12 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
                           const float* __restrict__ tau, int* __restrict__ cnt,
                           u64* __restrict__ shortlist, int cap, int hbit) {
   constexpr int BM = 256, BN = 256, BLK = 1024;                  // BLK: bytes of a 32-row x 16-element block
+  constexpr bool THREE = PREC == 2, F16 = PREC == 3;
   constexpr int NPL = THREE ? 2 : 1;
   constexpr int STAGE = NPL * 2 * 16 * BLK;                      // [plane][panel][8 A + 8 B blocks][BLK]
   constexpr float SCALE = METRIC == 0 ? -2.f : -1.f;
   constexpr float INV_S = METRIC == 0 ? 0.5f : 1.f;
-  if ((!((Ainfo->all_bf16 && Binfo->all_bf16) || (Binfo->heads_only & (u32)hbit))) != THREE) return;
+  if (precision_variant(Ainfo, Binfo, hbit, false) != PREC) return;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* tiles = smem;                                           // [2][STAGE]
@@ -726,10 +762,10 @@ void mfma_sweep_kc_kernel(const unsigned short* __restrict__ Ahi, const unsigned
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb) {
-            m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bh[cb], m[rb][cb], 0, 0, 0);
+            m[rb][cb] = mfma_32x32x16<F16>(ah[rb], bh[cb], m[rb][cb]);
             if constexpr (THREE) {
-              m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bl[cb], m[rb][cb], 0, 0, 0);
-              m[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rb], bh[cb], m[rb][cb], 0, 0, 0);
+              m[rb][cb] = mfma_32x32x16<false>(ah[rb], bl[cb], m[rb][cb]);
+              m[rb][cb] = mfma_32x32x16<false>(al[rb], bh[cb], m[rb][cb]);
             }
           }
       }
@@ -972,12 +1008,19 @@ __global__ __launch_bounds__(64) void rerank_kernel(
       // |approx - canon| <= eps: bf16 head/tail split drops terms below 2^-15 |q||x| per product;
       // fp32 accumulation and the canon chain each stay below d 2^-22 (|q|^2 + |x|^2); the
       // collect sweep's own rounding (a few ulps of |tau| / 2 + |<q,x>|) is the last term.
-      // Heads alone on inexact operands: q = qh + ql with |ql_i| <= 2^-9 |q_i|, likewise x, so
-      // |<q,x> - <qh,xh>| <= 2^-8 (1 + 2^-10) |q||x| <= 2^-9 (1 + 2^-10) (|q|^2 + |x|^2), twice
-      // that on the distance: 3.92e-3 (|q|^2 + |x|^2).
-      const float split_term = !inexact ? 0.f : ((Binfo->heads_only & (u32)(k == 1 ? 1 : 2)) ? 3.92e-3f : 6.2e-5f);
+      // fp16 heads alone: qh_i = q_i + a_i with |a_i| <= u |q_i| + s, u = 2^-11 (rounding to 11
+      // significant bits) and s = 2^-25 (half the spacing of fp16 subnormals), likewise x, so
+      // |<q,x> - <qh,xh>| <= (2u + u^2) |q||x| + s (1 + u) sqrt(d) (|q| + |x|) + d s^2; with
+      // |q||x| <= N / 2 and |q| + |x| <= sqrt(2 N), N = |q|^2 + |x|^2, twice that on the distance:
+      // 9.78e-4 N + 6.0e-8 sqrt(2 d N) + 1.8e-15 d (inner product: the value is the product itself,
+      // half of each).
+      const bool f16 = precision_variant(Ainfo, Binfo, k == 1 ? 1 : 2, false) == 3;
+      const float nn = na2 + nb2;
+      constexpr float F16_S = METRIC == 0 ? 1.f : 0.5f;
+      const float split_term = !inexact ? 0.f : (f16 ? F16_S * 9.78e-4f : 6.2e-5f);
       const float coef = split_term + (float)d * 4.8e-7f + 2e-6f;
-      const float eps = eps_scale * coef * (na2 + nb2);
+      const float abs_term = f16 ? F16_S * (6.0e-8f * sqrtf(2.f * (float)d * nn) + 1.8e-15f * (float)d) : 0.f;
+      const float eps = eps_scale * (coef * nn + abs_term);
       const float tau_v = tau[row];
       const float ub = METRIC == 0 ? na2 + tau_v : -tau_v;
       const float kv = key_value(vk, METRIC);
@@ -1005,6 +1048,27 @@ __global__ __launch_bounds__(64) void rerank_kernel(
   }
 }
 
+// How the exact fallback cuts the columns of B into chunks.  The host plans chunks for the worst
+// case (every row redone); with few redone rows those would leave most of the chip idle (5 rows x
+// 2 chunks of 8192 columns x 768 dimensions: 0.8 ms on ten workgroups), so the kernels cut finer
+// -- about three tasks per compute unit, at most 64 chunks of at least 256 columns -- as far as
+// the buffer of partial results (cap_keys keys; 0: keep the host's plan) holds count * nchunk * k.
+struct FallbackSplit { int64_t chunk_cols; int nchunk; };
+__device__ __forceinline__ FallbackSplit fallback_split(int count, int64_t nb, int k, int64_t chunk_cols,
+                                                        int nchunk, int64_t cap_keys) {
+  FallbackSplit f;
+  f.chunk_cols = chunk_cols; f.nchunk = nchunk;
+  if (cap_keys > 0 && count > 0) {
+    int64_t want = (768 + count - 1) / count;
+    want = min(min(want, (int64_t)64), min((nb + 255) / 256, cap_keys / ((int64_t)count * k)));
+    if (want > nchunk) {
+      f.chunk_cols = ((nb + want - 1) / want + 255) / 256 * 256;
+      f.nchunk = (int)((nb + f.chunk_cols - 1) / f.chunk_cols);
+    }
+  }
+  return f;
+}
+
 // Canon over ALL columns for the rows listed in fb_rows.  Persistent workgroups walk over
 // (listed row, column chunk) tasks, so that even a single listed row is spread over the
 // chip; with more than one chunk the k best of each chunk go to `partial` as keys and
@@ -1012,9 +1076,9 @@ __global__ __launch_bounds__(64) void rerank_kernel(
 template <int R, int METRIC>
 __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict__ A,
                                                          const float* __restrict__ B, int64_t nb,
-                                                         int d, int k, int tot, int64_t chunk_cols,
-                                                         int nchunk, u64* __restrict__ partial,
-                                                         SelectOut out,
+                                                         int d, int k, int tot, int64_t chunk_cols0,
+                                                         int nchunk0, int64_t cap_keys,
+                                                         u64* __restrict__ partial, SelectOut out,
                                                          const int* __restrict__ fb_count,
                                                          const int* __restrict__ fb_rows,
                                                          PrepInfo* __restrict__ adapt, int64_t na) {
@@ -1032,6 +1096,9 @@ __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict
     const u32 bit = k == 1 ? 1u : 2u;
     if (adapt && (adapt->heads_only & bit) && count >= 8 && (int64_t)count * 512 > na) atomicAnd(&adapt->heads_only, ~bit);
   }
+  const FallbackSplit fs = fallback_split(count, nb, k, chunk_cols0, nchunk0, cap_keys);
+  const int64_t chunk_cols = fs.chunk_cols;
+  const int nchunk = fs.nchunk;
   const int64_t tasks = (int64_t)count * nchunk;
   for (int64_t task = blockIdx.x; task < tasks; task += gridDim.x) {
     const int64_t f = task / nchunk;
@@ -1074,9 +1141,9 @@ __global__ __launch_bounds__(256) void canon_rows_kernel(const float* __restrict
 template <int R, int METRIC>
 __global__ __launch_bounds__(256) void canon_rows_tiled_kernel(const float* __restrict__ A,
                                                                const float* __restrict__ B, int64_t nb,
-                                                               int d, int k, int tot, int64_t chunk_cols,
-                                                               int nchunk, u64* __restrict__ partial,
-                                                               SelectOut out,
+                                                               int d, int k, int tot, int64_t chunk_cols0,
+                                                               int nchunk0, int64_t cap_keys,
+                                                               u64* __restrict__ partial, SelectOut out,
                                                                const int* __restrict__ fb_count,
                                                                const int* __restrict__ fb_rows,
                                                                PrepInfo* __restrict__ adapt, int64_t na) {
@@ -1096,6 +1163,9 @@ __global__ __launch_bounds__(256) void canon_rows_tiled_kernel(const float* __re
     const u32 bit = k == 1 ? 1u : 2u;
     if (adapt && (adapt->heads_only & bit) && count >= 8 && (int64_t)count * 512 > na) atomicAnd(&adapt->heads_only, ~bit);
   }
+  const FallbackSplit fs = fallback_split(count, nb, k, chunk_cols0, nchunk0, cap_keys);
+  const int64_t chunk_cols = fs.chunk_cols;
+  const int nchunk = fs.nchunk;
   const int64_t tasks = (int64_t)count * nchunk;
   for (int64_t task = blockIdx.x; task < tasks; task += gridDim.x) {
     const int64_t f = task / nchunk;
@@ -1169,8 +1239,9 @@ __global__ __launch_bounds__(256) void canon_rows_tiled_kernel(const float* __re
 
 // One wavefront per listed row: k best of its nchunk * k partial keys.
 template <int R, int METRIC>
-__global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restrict__ partial,
-                                                              int nchunk, int k, int tot,
+__global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restrict__ partial, int64_t nb,
+                                                              int64_t chunk_cols0, int nchunk0,
+                                                              int64_t cap_keys, int k, int tot,
                                                               SelectOut out,
                                                               const int* __restrict__ fb_count,
                                                               const int* __restrict__ fb_rows) {
@@ -1178,6 +1249,8 @@ __global__ __launch_bounds__(64) void canon_rows_merge_kernel(const u64* __restr
   u64* slots = reinterpret_cast<u64*>(smem);                    // tot
   const int lane = lane_id();
   const int count = *fb_count;
+  const int nchunk = fallback_split(count, nb, k, chunk_cols0, nchunk0, cap_keys).nchunk;
+  if (nchunk == 1) return;                                      // the rows were written directly
   for (int f = blockIdx.x; f < count; f += gridDim.x) {
     const int64_t row = fb_rows[f];
     WaveSelect<R> ws;
@@ -1362,19 +1435,25 @@ MfmaPlan make_plan(int64_t na, int64_t nb, int k, int d) {
 }  // namespace
 
 namespace {
-struct FallbackPlan { int64_t chunk_cols; int nchunk; };
-// column chunks of the exact fallback: at least 8192 columns each (a few hundred redone rows
-// still make a few thousand tasks), at most 64 chunks
-FallbackPlan fallback_plan(int64_t nb) {
+struct FallbackPlan { int64_t chunk_cols; int nchunk; int64_t cap_keys; };
+// Column chunks of the exact fallback for the case that every row is redone: at least 8192 columns
+// each (a few hundred redone rows still make a few thousand tasks), at most 64 chunks.  From 8192
+// columns on, the kernels cut finer when few rows are redone (fallback_split): cap_keys > 0 is the
+// size of the buffer of partial results, which then also holds 64 rows x 64 chunks.
+FallbackPlan fallback_plan(int64_t na, int64_t nb, int k) {
   FallbackPlan f;
   f.chunk_cols = std::max<int64_t>(8192, ((nb + 63) / 64 + 255) / 256 * 256);
   f.nchunk = (int)std::max<int64_t>(1, (nb + f.chunk_cols - 1) / f.chunk_cols);
+  f.cap_keys = 0;
+  if (nb >= 8192)
+    f.cap_keys = std::max<int64_t>(f.nchunk == 1 ? 0 : na * f.nchunk * k, std::min<int64_t>(na, 64) * 64 * k);
   return f;
 }
 }  // namespace
 
 size_t mfma_knn_fallback_bytes(int64_t na, int64_t nb, int k) {
-  const FallbackPlan f = fallback_plan(nb);
+  const FallbackPlan f = fallback_plan(na, nb, k);
+  if (f.cap_keys > 0) return (size_t)f.cap_keys * sizeof(u64);
   return f.nchunk == 1 ? 0 : (size_t)na * f.nchunk * k * sizeof(u64);
 }
 
@@ -1399,7 +1478,7 @@ static bool two_pass_allowed(const MfmaOperand& A) { return A.n >= 256; }
 template <int KSTEPS, int RB, int METRIC, int MODE, int PREC>
 static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
                            hipStream_t st) {
-  constexpr int D = KSTEPS * 16, NPL = PREC >= 1 ? 2 : 1;
+  constexpr int D = KSTEPS * 16, NPL = PREC == 1 || PREC == 2 ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * 64 * (D + 8) * sizeof(unsigned short) + 2 * 64 * sizeof(float) +
                        (size_t)128 * RB * (sizeof(int) + sizeof(float)) +
                        4 * 128 * (sizeof(u64) + sizeof(int));
@@ -1408,8 +1487,9 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   const int64_t row_tiles = (A.n + 128 * RB - 1) / (128 * RB);   // (the lists are per row: any RB fits)
-  hipLaunchKernelGGL(kern, dim3((unsigned)(row_tiles * p.nsplit)), dim3(256), shmem, st, A.hi, A.lo,
-                     A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
+  hipLaunchKernelGGL(kern, dim3((unsigned)(row_tiles * p.nsplit)), dim3(256), shmem, st,
+                     PREC == 3 ? A.h16 : A.hi, A.lo, A.norm, A.info, A.n,
+                     PREC == 3 ? B.h16 : B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
@@ -1422,8 +1502,12 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   // both operand-precision variants are enqueued; the kernel that does not match the flags
   // written by operand preparation returns immediately (the flags live in device memory) --
   // unless the host already knows an operand's flag and with it which variant cannot run
-  // (an operand that may be swept by its heads alone needs the one-product variant enqueued too)
-  if (!certainly_three(A, B) || B.try_heads_only) {
+  // (an operand that may be swept by its fp16 heads alone needs that variant enqueued too)
+  if (B.try_heads_only && !certainly_one(A, B)) {
+    if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, 3>(p, A, B, work, st);
+    else launch_sweep_t<KSTEPS, 1, METRIC, MODE, 3>(p, A, B, work, st);
+  }
+  if (!certainly_three(A, B)) {
     if (MODE == 1 && p.RB == 2) launch_sweep_t<KSTEPS, MODE == 1 ? 2 : 1, METRIC, MODE, 0>(p, A, B, work, st);
     else launch_sweep_t<KSTEPS, 1, METRIC, MODE, 0>(p, A, B, work, st);
   }
@@ -1435,18 +1519,19 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   }
 }
 
-template <int METRIC, int MODE, bool THREE>
+template <int METRIC, int MODE, int PREC>
 static void launch_sweep_kc_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                               char* work, hipStream_t st) {
-  constexpr int NPL = THREE ? 2 : 1;
+  constexpr int NPL = PREC == 2 ? 2 : 1;
   const size_t shmem = (size_t)2 * NPL * 2 * 16 * 1024 + 2 * 256 * sizeof(float) +
                        (size_t)256 * (sizeof(int) + 2 * sizeof(float)) + 8 * 128 * (sizeof(u64) + sizeof(int));
-  auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, THREE>;
+  auto kern = &mfma_sweep_kc_kernel<METRIC, MODE, PREC>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   const int64_t per_xcd = (p.row_tiles * p.nsplit + 7) / 8;       // the kernel deals the items out by XCD
-  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(512), shmem, st, A.hi, A.lo,
-                     A.norm, A.info, A.n, B.hi, B.lo, B.norm, B.info, B.n, d, p.nsplit, p.cols_per_split,
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(512), shmem, st,
+                     PREC == 3 ? A.h16 : A.hi, A.lo, A.norm, A.info, A.n,
+                     PREC == 3 ? B.h16 : B.hi, B.lo, B.norm, B.info, B.n, d, p.nsplit, p.cols_per_split,
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
@@ -1457,13 +1542,15 @@ template <int MODE>
 static void launch_sweep(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, int d,
                          int metric, char* work, hipStream_t st) {
   if (p.kc) {   // both operand-precision variants, as below
-    const bool one = !certainly_three(A, B) || B.try_heads_only, three = !certainly_one(A, B);
+    const bool one = !certainly_three(A, B), three = !certainly_one(A, B), f16 = B.try_heads_only && three;
     if (metric == 0) {
-      if (one) launch_sweep_kc_t<0, MODE, false>(p, A, B, d, work, st);
-      if (three) launch_sweep_kc_t<0, MODE, true>(p, A, B, d, work, st);
+      if (f16) launch_sweep_kc_t<0, MODE, 3>(p, A, B, d, work, st);
+      if (one) launch_sweep_kc_t<0, MODE, 0>(p, A, B, d, work, st);
+      if (three) launch_sweep_kc_t<0, MODE, 2>(p, A, B, d, work, st);
     } else {
-      if (one) launch_sweep_kc_t<1, MODE, false>(p, A, B, d, work, st);
-      if (three) launch_sweep_kc_t<1, MODE, true>(p, A, B, d, work, st);
+      if (f16) launch_sweep_kc_t<1, MODE, 3>(p, A, B, d, work, st);
+      if (one) launch_sweep_kc_t<1, MODE, 0>(p, A, B, d, work, st);
+      if (three) launch_sweep_kc_t<1, MODE, 2>(p, A, B, d, work, st);
     }
     return;
   }
@@ -1521,8 +1608,8 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
   const bool tiled = d % 32 == 0;
   const size_t sh2 = (size_t)4 * tot * sizeof(u64) + (size_t)d * sizeof(float) +
                      (tiled ? (size_t)2 * 256 * 36 * sizeof(float) : 0);
-  const FallbackPlan fp = fallback_plan(B.n);
-  const int grid = (int)std::min<int64_t>(A.n * fp.nchunk, 2048);
+  const FallbackPlan fp = fallback_plan(A.n, B.n, k);
+  const int grid = (int)std::min<int64_t>(A.n * (fp.cap_keys > 0 ? 64 : fp.nchunk), 2048);   // (idle workgroups leave at once)
 #define CR(RV, MET)                                                                              \
   do {                                                                                           \
     auto kern = tiled ? &canon_rows_tiled_kernel<RV, MET> : &canon_rows_kernel<RV, MET>;         \
@@ -1530,12 +1617,12 @@ void launch_rerank(const MfmaOperand& A, const MfmaOperand& B, int d, int metric
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh2);           \
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh2, st, A.x, B.x, B.n, d,                   \
-                       k, tot, fp.chunk_cols, fp.nchunk, fb_partial, out, fb_count, fb_rows,     \
+                       k, tot, fp.chunk_cols, fp.nchunk, fp.cap_keys, fb_partial, out, fb_count, fb_rows, \
                        eps_scale < 0.f ? nullptr : const_cast<PrepInfo*>(B.info), A.n);          \
-    if (fp.nchunk > 1)                                                                           \
+    if (fp.nchunk > 1 || fp.cap_keys > 0)                                                        \
       hipLaunchKernelGGL((canon_rows_merge_kernel<RV, MET>), dim3((unsigned)std::min<int64_t>(A.n, 1024)), \
-                         dim3(64), (size_t)tot * sizeof(u64), st, fb_partial, fp.nchunk, k, tot, out, \
-                         fb_count, fb_rows);                                                     \
+                         dim3(64), (size_t)tot * sizeof(u64), st, fb_partial, B.n, fp.chunk_cols, \
+                         fp.nchunk, fp.cap_keys, k, tot, out, fb_count, fb_rows);                \
   } while (0)
   const int R2 = select_regs_for_slots(tot);
   if (R2 == 2) { if (metric == 0) CR(2, 0); else CR(2, 1); }

@@ -692,26 +692,34 @@ def test_random_route_shapes_agree(vs, oracle):
         vs.vs_set_option("knn_path", 0)
 
 
-def test_sweeps_on_bf16_heads_alone_never_change_a_result(vs, oracle):
-    """An index's own operand is first swept by its bf16 heads alone (one matrix product, a wide
+def test_sweeps_on_fp16_heads_alone_never_change_a_result(vs, oracle):
+    """An index's own operand is first swept by its fp16 heads alone (one matrix product, a wide
     error bound); rows that cannot be proven under that bound are redone exactly, and when too many
     are, later calls go back to three products.  Whatever the state, every call returns what the
-    canon tiles return, bit for bit: on data with a large common offset (nearly every row fails the
-    wide bound), on well-separated data (none does), for k = 1 and k > 1, call after call."""
+    canon tiles return, bit for bit: on data with a large common offset (many rows fail the wide
+    bound), on well-separated data (none does), on values so small that their fp16 images are
+    subnormal or zero, on values beyond the fp16 range (where the attempt must not be made), for
+    inner product, for k = 1 and k > 1, call after call."""
     import torch
-    for kind, nb, nq, d in (("offset", 20_000, 700, 64), ("gauss", 30_000, 600, 96), ("offset", 9_000, 300, 256)):
+    cases = (("offset", 20_000, 700, 64, L2, 1.0), ("gauss", 30_000, 600, 96, L2, 1.0),
+             ("offset", 9_000, 300, 256, L2, 1.0), ("gauss", 12_000, 300, 128, L2, 3e-6),
+             ("gauss", 12_000, 300, 64, L2, 2e-8), ("gauss", 12_000, 300, 128, L2, 4e4),
+             ("gauss", 8_000, 200, 512, L2, 1e5), ("gauss", 15_000, 400, 128, IP, 1.0),
+             ("gauss", 9_000, 300, 256, IP, 1e-6))
+    for kind, nb, nq, d, metric, scale in cases:
         g = torch.Generator(device="cuda"); g.manual_seed(77)
         x = torch.randn((nb, d), generator=g, device="cuda")
         q = torch.randn((nq, d), generator=g, device="cuda")
         if kind == "offset":
             x, q = x + 3.0, q + 3.0
-        ix = vs.Flat(d, L2)
+        x, q = x * scale, q * scale
+        ix = vs.Flat(d, metric)
         ix.add(x)
         for k in (1, 10, 1, 10, 10):
-            say("heads alone: %s nb=%d d=%d k=%d" % (kind, nb, d, k))
+            say("heads alone: %s nb=%d d=%d metric=%d scale=%g k=%d" % (kind, nb, d, metric, scale, k))
             vs.vs_set_option("knn_path", 1)
             try:
-                Dc, Ic = [host(t).copy() for t in vs.vs_flat_search(x, q, k, L2)]
+                Dc, Ic = [host(t).copy() for t in vs.vs_flat_search(x, q, k, metric)]
             finally:
                 vs.vs_set_option("knn_path", 0)
             vs.vs_counters_read()
@@ -724,10 +732,10 @@ def test_sweeps_on_bf16_heads_alone_never_change_a_result(vs, oracle):
         vs.vs_counters_read()
         ix.search(q, 10); ix.search(q, 1)
         rows, fallback = vs.vs_counters_read()
-        assert rows == 2 * nq and fallback <= 2 * max(7, nq // 512 + 1), (kind, fallback)
+        assert rows == 2 * nq and fallback <= 2 * max(7, nq // 512 + 1), (kind, scale, fallback)
         ix.close()
-    Do, Io = oracle.flat_search(host(x), host(q)[:50], 10, L2)
-    np.testing.assert_array_equal(I[:50], Io)
+        Do, Io = oracle.flat_search(host(x), host(q)[:20], 10, metric)
+        np.testing.assert_array_equal(I[:20], Io)
 
 
 # ------------------------------------------------- flat index (prepared database)
