@@ -327,8 +327,16 @@ void mfma_sweep_kernel(const unsigned short* __restrict__ Ahi, const unsigned sh
   int qn = 0;                                                     // queue fill (wave-uniform)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
-  const int64_t rt = blockIdx.x / nsplit;
-  const int split = blockIdx.x % nsplit;
+  // Work item = (split of B, row tile), numbered split first.  Workgroup ids go round the eight
+  // XCDs, each with an L2 of its own: XCD x takes a run of consecutive items, so the workgroups
+  // resident on it at a time are row tiles that walk through the SAME split of B in step, and a
+  // tile of B comes from memory once per XCD instead of once per workgroup.
+  const int64_t row_tiles = (na + 128 * RB - 1) / (128 * RB);
+  const int64_t items = row_tiles * nsplit, per_xcd = (items + 7) / 8;
+  const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if ((int64_t)(blockIdx.x >> 3) >= per_xcd || item >= items) return;
+  const int split = (int)(item / row_tiles);
+  const int64_t rt = item - (int64_t)split * row_tiles;
   const int64_t row0 = rt * (128 * RB) + wave * (32 * RB);        // this wavefront's first row
   const int64_t c_begin = (int64_t)split * cols_per_split;
   const int64_t c_end = min(nb, c_begin + cols_per_split);
@@ -1487,7 +1495,8 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   const int64_t row_tiles = (A.n + 128 * RB - 1) / (128 * RB);   // (the lists are per row: any RB fits)
-  hipLaunchKernelGGL(kern, dim3((unsigned)(row_tiles * p.nsplit)), dim3(256), shmem, st,
+  const int64_t per_xcd = (row_tiles * p.nsplit + 7) / 8;         // the kernel deals the items out by XCD
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), shmem, st,
                      PREC == 3 ? A.h16 : A.hi, A.lo, A.norm, A.info, A.n,
                      PREC == 3 ? B.h16 : B.hi, B.lo, B.norm, B.info, B.n, p.nsplit, p.cols_per_split,
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
