@@ -884,7 +884,7 @@ int ivf_assign_and_place(vs_ivfpq* ix, const float* x, int64_t n, size_t extra, 
   // best keys [n] | list_of [n] | caller's extra | dest [n] | new offsets | work space of the placement
   constexpr int64_t kAssignPiece = 1 << 20;
   // The first piece of an index's first large add is a short one: the sweeps start out on the
-  // bf16 heads alone and learn from a call's fallback count whether that does for this data; a
+  // fp16 heads alone and learn from a call's fallback count whether that does for this data; a
   // short first call keeps the price of finding out small.
   constexpr int64_t kProbePiece = 8192;
   const int64_t first_piece = !ix->assign_probed && n > 4 * kProbePiece ? kProbePiece : 0;

@@ -119,7 +119,7 @@ struct PrepInfo {
   u32 all_nonneg;     // no value is negative
   // Of the column operand of a k-nearest-rows call only, and only where that operand outlives the
   // call (an index's centroids or vectors): bit 0 (calls with k = 1) and bit 1 (k > 1) are set
-  // while the sweeps of such calls may use the bf16 heads alone on operands that are not exactly
+  // while the sweeps of such calls may use the fp16 heads alone on operands that are not exactly
   // bf16 (one matrix product instead of three, with the wider error bound that goes with it).  A
   // bit is cleared for good by the exact fallback once more than one row in 512 of a call failed
   // the sufficiency test under that bound.
