@@ -28,6 +28,9 @@ def build(force=False):
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-mfma", "-fopenmp", "-shared", "-fPIC",
                "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
+    if force:   # the sanitizer driver too (plain build: "does it compile"; the test builds it with sanitizers)
+        chk = os.path.join(_HERE, "sanitize_check.c")
+        subprocess.run(["gcc", "-O1", "-ffp-contract=off", "-mfma", "-fsyntax-only", chk], check=True)
     return _SO
 
 
