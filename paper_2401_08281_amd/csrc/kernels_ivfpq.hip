@@ -393,8 +393,9 @@ __global__ __launch_bounds__(256) void ivfpq_scan_kernel(
 // pipelined: the workgroup walks over the chunks of 256 codes of all its lists as one
 // sequence, and the codes of the next chunk -- of the same list or of the next
 // non-empty one -- are requested before the current chunk is summed, so a short list
-// costs no exposed memory latency beyond the first one of the item.  Requests are
-// clamped into the code array; lanes past the end of a list are masked when consumed.
+// costs no exposed memory latency beyond the first one of the item.  Lanes past the end of
+// a list request nothing (with 610-code lists the tail of every list's last chunk was a
+// fifth of the kernel's memory traffic) and are masked when consumed.
 // ---------------------------------------------------------------------------
 template <int NBITS, int R, int W16>
 __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
@@ -427,7 +428,6 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
   const float* __restrict__ qv = q + qi * d;
   const int p_begin = split * ppb;
   const int np = ntotal > 0 ? max(0, min(nprobe, p_begin + ppb) - p_begin) : 0;
-  const int64_t last = ntotal > 0 ? ntotal - 1 : 0;
   const int cs = 16 * W16;
 
   WaveSelect<R> ws;
@@ -454,8 +454,10 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
   int64_t base = p < np ? s_begin[p] : 0;                       // first code of the current chunk
   u32x4 cw[W16], cwn[W16];
   float nrm = 0.f, nrmn = 0.f;
-  if (p < np) {
-    const int64_t i = min(base + tid, last);
+#pragma unroll
+  for (int w = 0; w < W16; ++w) cw[w] = cwn[w] = u32x4{0u, 0u, 0u, 0u};
+  if (p < np && base + tid < s_end[p]) {
+    const int64_t i = base + tid;
 #pragma unroll
     for (int w = 0; w < W16; ++w) cw[w] = reinterpret_cast<const u32x4*>(codes + i * cs)[w];
     if (mode == 2) nrm = norms[i];
@@ -471,8 +473,8 @@ __global__ __launch_bounds__(256) void ivfpq_scan_pipe_kernel(
       while (pn < np && s_begin[pn] == s_end[pn]) ++pn;
       base_n = pn < np ? s_begin[pn] : 0;
     }
-    if (pn < np) {
-      const int64_t i = min(base_n + tid, last);
+    if (pn < np && base_n + tid < s_end[pn]) {
+      const int64_t i = base_n + tid;
 #pragma unroll
       for (int w = 0; w < W16; ++w) cwn[w] = reinterpret_cast<const u32x4*>(codes + i * cs)[w];
       if (mode == 2) nrmn = norms[i];
