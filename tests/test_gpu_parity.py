@@ -596,6 +596,10 @@ ROUTE_CASES = [
     # long database in cluster order: the threshold comes from a sample of the columns
     ("sift_sorted_d128_k100", 200_000, 64, 128, 100, L2, "sift_sorted"),
     ("unit_sorted_d96_k10", 150_000, 96, 96, 10, L2, "unit_sorted"),
+    # a handful of rows against a long database: the forced exact fallback cuts the columns into
+    # its largest number of chunks
+    ("gauss_d128_k50_three_rows", 120_000, 3, 128, 50, L2, "gauss"),
+    ("gauss_d64_k1_ip_one_row", 70_000, 1, 64, 1, IP, "gauss"),
 ]
 
 
