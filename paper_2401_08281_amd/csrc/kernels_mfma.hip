@@ -151,10 +151,12 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ x, 
   if (max_bits) atomicMax(&flags[3], max_bits);
   __syncthreads();
   if (tid == 0) {
-    if (!flags[0]) atomicAnd(&info->all_int, 0u);
-    if (!flags[1]) atomicAnd(&info->all_bf16, 0u);
-    if (!flags[2]) atomicAnd(&info->all_nonneg, 0u);
-    if (flags[3]) atomicMax(&info->max_norm_bits, flags[3]);
+    // (a look first: hundreds of workgroups reporting the same fact to one address, one atomic
+    // after the other, were most of the time of preparing a batch of queries)
+    if (!flags[0] && __atomic_load_n(&info->all_int, __ATOMIC_RELAXED)) atomicAnd(&info->all_int, 0u);
+    if (!flags[1] && __atomic_load_n(&info->all_bf16, __ATOMIC_RELAXED)) atomicAnd(&info->all_bf16, 0u);
+    if (!flags[2] && __atomic_load_n(&info->all_nonneg, __ATOMIC_RELAXED)) atomicAnd(&info->all_nonneg, 0u);
+    if (flags[3] > __atomic_load_n(&info->max_norm_bits, __ATOMIC_RELAXED)) atomicMax(&info->max_norm_bits, flags[3]);
   }
 }
 
@@ -244,10 +246,12 @@ __global__ __launch_bounds__(256) void prep_panel_kernel(const float* __restrict
   if (max_bits) atomicMax(&flags[3], max_bits);
   __syncthreads();
   if (tid == 0) {
-    if (!flags[0]) atomicAnd(&info->all_int, 0u);
-    if (!flags[1]) atomicAnd(&info->all_bf16, 0u);
-    if (!flags[2]) atomicAnd(&info->all_nonneg, 0u);
-    if (flags[3]) atomicMax(&info->max_norm_bits, flags[3]);
+    // (a look first: hundreds of workgroups reporting the same fact to one address, one atomic
+    // after the other, were most of the time of preparing a batch of queries)
+    if (!flags[0] && __atomic_load_n(&info->all_int, __ATOMIC_RELAXED)) atomicAnd(&info->all_int, 0u);
+    if (!flags[1] && __atomic_load_n(&info->all_bf16, __ATOMIC_RELAXED)) atomicAnd(&info->all_bf16, 0u);
+    if (!flags[2] && __atomic_load_n(&info->all_nonneg, __ATOMIC_RELAXED)) atomicAnd(&info->all_nonneg, 0u);
+    if (flags[3] > __atomic_load_n(&info->max_norm_bits, __ATOMIC_RELAXED)) atomicMax(&info->max_norm_bits, flags[3]);
   }
 }
 
@@ -1482,6 +1486,11 @@ static bool certainly_one(const MfmaOperand& A, const MfmaOperand& B) {
 // the sweeps, not the launches, are what a call costs.  The kernels get the same answer as
 // a flag, so that exactly one variant takes the work.
 static bool two_pass_allowed(const MfmaOperand& A) { return A.n >= 256; }
+// ... and not next to the fp16 attempt (one more empty launch per sweep in nearly every call; when
+// the attempt has been given up on such an operand, exactly-bf16 queries take the three-pass variant)
+static bool two_pass_allowed(const MfmaOperand& A, const MfmaOperand& B) {
+  return two_pass_allowed(A) && !B.try_heads_only;
+}
 
 template <int KSTEPS, int RB, int METRIC, int MODE, int PREC>
 static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOperand& B, char* work,
@@ -1502,7 +1511,7 @@ static void launch_sweep_t(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
                      MODE == 0 ? p.stride : 1, p.nphase, p.cols_per_phase,
                      reinterpret_cast<float*>(work + p.o_minima), p.g_raw,
                      reinterpret_cast<const float*>(work + p.o_tau), reinterpret_cast<int*>(work + p.o_cnt),
-                     reinterpret_cast<u64*>(work), p.cap, (two_pass_allowed(A) ? 1 : 0) | (p.hbit << 1));
+                     reinterpret_cast<u64*>(work), p.cap, (two_pass_allowed(A, B) ? 1 : 0) | (p.hbit << 1));
 }
 
 template <int KSTEPS, int METRIC, int MODE>
@@ -1522,7 +1531,7 @@ static void launch_sweep_k(const MfmaPlan& p, const MfmaOperand& A, const MfmaOp
   }
   if (!certainly_one(A, B)) {
     // A exact and B not (integer vectors against trained centroids): two passes instead of three
-    if (two_pass_allowed(A) && A.known_bf16 != 0 && B.known_bf16 != 1)
+    if (two_pass_allowed(A, B) && A.known_bf16 != 0 && B.known_bf16 != 1)
       launch_sweep_t<KSTEPS, 1, METRIC, MODE, 1>(p, A, B, work, st);
     launch_sweep_t<KSTEPS, 1, METRIC, MODE, 2>(p, A, B, work, st);
   }
