@@ -218,6 +218,8 @@ VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* 
  * are returned best first with their stored ids.
  *   q [nq, d] fp32; out_dist [nq, k] fp32; out_ids [nq, k] int64.
  * Errors: null pointers (with nq > 0), k or nprobe < 1 or > VS_MAX_K.
+ * Large batches on L2 indexes of the three fixed shapes are scanned list by list (option
+ * "list_major" below): same results, one read of every probed list per batch.
  * Work space: one grow-only buffer per index (the first call of a size allocates it; later
  * calls only enqueue kernels).  Searches of one index from several host threads or on several
  * streams are serialised on it: a call on another stream than the previous search's first waits,
@@ -235,6 +237,12 @@ VS_API int vs_ivfpq_search(const vs_ivfpq* ix, const float* q, int64_t nq, int32
  *   probed_lists    (query, probe) pairs whose list is not empty
  *   coarse_rows_matrix_core  queries whose probes were found through the matrix-core shortlist
  *   coarse_rows_fallback     ... of which failed the sufficiency test and were redone exactly
+ *   list_major_first_probes  0, or (the batch was scanned list by list, see vs_ivfpq_search) the
+ *                            number of probes per query that were scanned query by query first
+ *   list_major_first_codes   the part of scanned_codes that falls on those probes
+ *   list_major_rescanned     queries whose candidate buffer overflowed in the list-major scan and
+ *                            that were therefore scanned again query by query (their codes are
+ *                            not counted twice in scanned_codes)
  * Results, errors and work space are those of vs_ivfpq_search.  nq == 0 zeroes the block.
  */
 typedef struct vs_search_stats {
@@ -242,6 +250,9 @@ typedef struct vs_search_stats {
   int64_t probed_lists;
   int64_t coarse_rows_matrix_core;
   int64_t coarse_rows_fallback;
+  int64_t list_major_first_probes;
+  int64_t list_major_first_codes;
+  int64_t list_major_rescanned;
 } vs_search_stats;
 VS_API int vs_ivfpq_search_stats(const vs_ivfpq* ix, const float* q, int64_t nq, int32_t k, int32_t nprobe,
                           float* out_dist, int64_t* out_ids, vs_search_stats* stats, void* hip_stream);
@@ -398,7 +409,8 @@ enum {
   VS_STAGE_FLAT_DIST = 4,     /* flat search: query x database distance tiles    */
   VS_STAGE_FLAT_SELECT = 5,   /* flat search: k-selection                        */
   VS_STAGE_REFINE = 6,        /* vs_refine: exact distances of a shortlist + selection */
-  VS_NUM_STAGES = 7
+  VS_STAGE_SCAN_FIRST = 7,    /* list-major search: first probes query by query, pairs grouped by list */
+  VS_NUM_STAGES = 8
 };
 
 /* on != 0: from now on vs_ivfpq_search, vs_flat_search and vs_refine bracket every kernel
@@ -420,6 +432,16 @@ VS_API int vs_profile_read(double* stage_ms, int64_t* launches);
  * "knn_eps_scale": multiplies the error bound used to prove a shortlist
  *   sufficient (default 1; a negative value sends every row to the exact
  *   fallback -- for tests).
+ * "list_major": whether vs_ivfpq_search scans a batch list by list instead of query by query
+ *   (Sec. 4.3 "Compressed-domain search"; L2 indexes with residual tables of PQ8x8 on d = 32,
+ *   PQ16x8 on d = 128 and PQ32x8 on d = 96): every list is then read from memory once per batch
+ *   instead of once per query that probes it.  0 (default): where it pays -- at least 16 probes,
+ *   at least 4096 queries and three (query, list) pairs per list, codes of 512 MB or more; 1:
+ *   wherever the index has one of these shapes; -1: never.  Results are identical either way.
+ * "list_major_first" (default 4, 1..64): how many of its nearest lists every query scans on its
+ *   own first; the k-th best distance found there is the bound under which the list-major scan
+ *   keeps a code.  "list_major_candidates" (default 1024, 64..65536): codes kept per query; a
+ *   query that finds more is scanned again query by query (vs_search_stats counts them).
  * Options are process-wide. */
 VS_API int vs_set_option(const char* name, double value);
 /* counters[0] = rows evaluated through the matrix-core route, counters[1] = rows

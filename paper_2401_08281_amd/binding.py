@@ -160,7 +160,7 @@ def vs_version():
     return lib().vs_version().decode()
 
 
-STAGES = ("coarse_dist", "coarse_select", "scan", "merge", "flat_dist", "flat_select", "refine")
+STAGES = ("coarse_dist", "coarse_select", "scan", "merge", "flat_dist", "flat_select", "refine", "scan_first")
 
 
 def vs_profile_enable(on):
@@ -345,7 +345,8 @@ def vs_ivfpq_search(h, q, k, nprobe, out_dist=None, out_ids=None):
     return out_dist, out_ids
 
 
-SEARCH_STATS_FIELDS = ("scanned_codes", "probed_lists", "coarse_rows_matrix_core", "coarse_rows_fallback")
+SEARCH_STATS_FIELDS = ("scanned_codes", "probed_lists", "coarse_rows_matrix_core", "coarse_rows_fallback",
+                       "list_major_first_probes", "list_major_first_codes", "list_major_rescanned")
 
 
 def vs_ivfpq_search_stats(h, q, k, nprobe):

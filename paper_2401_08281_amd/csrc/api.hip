@@ -148,6 +148,11 @@ constexpr size_t kTileBytes = 128ull << 20;
 
 // ---- run-time options (vs_set_option) -----------------------------------------
 std::atomic<int> g_knn_path{0};          // 0 auto, 1 canon tiles only, 2 MFMA shortlist whenever supported
+// List-major IVF-PQ scan: 0 where it pays (large batch, long code store), 1 wherever the shape
+// allows it, -1 never; and its two sizes: probes scanned query-major first, candidates per query.
+std::atomic<int> g_list_major{0};
+std::atomic<int> g_lm_first{4};
+std::atomic<int> g_lm_cap{1024};
 std::atomic<float> g_knn_eps_scale{1.f}; // multiplies the error bound of the MFMA shortlist test
 std::atomic<long long> g_knn_mfma_rows{0};
 
@@ -396,6 +401,21 @@ int vs_set_option(const char* name, double value) {
     return VS_OK;
   }
   if (!strcmp(name, "knn_eps_scale")) { g_knn_eps_scale = (float)value; return VS_OK; }
+  if (!strcmp(name, "list_major")) {
+    if (value != 0 && value != 1 && value != -1) return fail(VS_ERR_INVALID_ARG, "vs_set_option: list_major must be -1, 0 or 1");
+    g_list_major = (int)value;
+    return VS_OK;
+  }
+  if (!strcmp(name, "list_major_first")) {
+    if (value < 1 || value > 64) return fail(VS_ERR_INVALID_ARG, "vs_set_option: list_major_first outside [1, 64]");
+    g_lm_first = (int)value;
+    return VS_OK;
+  }
+  if (!strcmp(name, "list_major_candidates")) {
+    if (value < 64 || value > 65536) return fail(VS_ERR_INVALID_ARG, "vs_set_option: list_major_candidates outside [64, 65536]");
+    g_lm_cap = (int)value;
+    return VS_OK;
+  }
   return fail(VS_ERR_INVALID_ARG, "vs_set_option: unknown option '%s'", name);
 }
 
@@ -1116,15 +1136,32 @@ namespace {
 struct SearchLayout {
   int npr = 0, nsplit = 1;
   KnnPlan plan;
-  size_t o_knn = 0, o_pr = 0, o_cd = 0, o_part = 0, o_cnt = 0, o_qt = 0, bytes = 0;
+  size_t o_knn = 0, o_pr = 0, o_cd = 0, o_part = 0, o_cnt = 0, o_qt = 0, o_lm = 0, bytes = 0;
   bool query_tables = false;
+  bool list_major = false;      // the scan runs list-major (see ivfpq_scan_listmajor_kernel)
+  int lm_first = 0, lm_cap = 0;
 };
-void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayout* out) {
+void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayout* out, bool allow_list_major = true) {
   SearchLayout& L = *out;
   const IvfpqDims& g = ix->g;
   L.npr = std::min<int>(nprobe, g.nlist);
   // probe splits: enough workgroups to fill the chip when nq is small
   L.nsplit = (int)std::min<int64_t>(L.npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
+  // List-major scan: L2 with residual tables on the shapes of the bank-private kernel, when every
+  // list is probed several times by the batch and the codes do not fit the caches anyway.
+  const int lm = g_list_major.load();
+  const int first = std::min(g_lm_first.load(), L.npr - 1);
+  const bool residual_tables = !(ix->search_type == VS_ST_STORED_NORMS && ix->norms) &&
+                               !(ix->search_type == VS_ST_PRECOMPUTED_TABLES && ix->list_tables);
+  if (allow_list_major && lm >= 0 && ivfpq_listmajor_shape(g) && residual_tables && first >= 1 &&
+      ix->ntotal > 0 && nq * (int64_t)L.npr < (1ll << 32) &&
+      (lm == 1 || (L.nsplit == 1 && L.npr >= 16 && nq * (int64_t)(L.npr - first) >= 3 * (int64_t)g.nlist &&
+                   ix->ntotal * (int64_t)g.code_size >= (512ll << 20)))) {
+    L.list_major = true;
+    L.lm_first = first;
+    L.lm_cap = g_lm_cap.load();
+    L.nsplit = 1;
+  }
   const int ppb = (L.npr + L.nsplit - 1) / L.nsplit;
   L.nsplit = (L.npr + ppb - 1) / ppb;
   L.plan = knn_plan(nq, g.nlist, g.d, L.npr, ix->has_planes);
@@ -1139,6 +1176,7 @@ void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayo
                    (g.metric == VS_METRIC_IP || (ix->search_type == VS_ST_STORED_NORMS && ix->norms) ||
                     (ix->search_type == VS_ST_PRECOMPUTED_TABLES && ix->list_tables));
   if (L.query_tables) L.o_qt = cv.take(ivfpq_query_table_bytes(g, nq));
+  if (L.list_major) L.o_lm = cv.take(ivfpq_listmajor_bytes(g, nq, L.npr, L.lm_cap));
   L.bytes = cv.off;
 }
 
@@ -1169,13 +1207,36 @@ int search_run(const char* who, const vs_ivfpq* ix, const SearchLayout& L, char*
   if (g.metric == VS_METRIC_IP && coarse_metric_of(ix) == VS_METRIC_L2)
     launch_probe_inner_products(q, nq, g.d, ix->centroids, probes, L.npr, cdist, st);
   if (stats)
-    launch_search_stats(probes, nq * L.npr, ix->list_off, fallback_count, L.plan.mfma ? nq : 0,
-                        reinterpret_cast<long long*>(stats), st);
+    launch_search_stats(probes, nq * L.npr, ix->list_off, fallback_count, L.plan.mfma ? nq : 0, L.npr,
+                        L.list_major ? L.lm_first : 0, reinterpret_cast<long long*>(stats), st);
   // search type "stored norms": the per-(query, list) number is |q|^2 - 2 <q, c_l> = coarse
   // distance - |c_l|^2, and the scan adds the stored |x'|^2 of every code (Sec. 4.3)
   const bool with_norms = ix->search_type == VS_ST_STORED_NORMS && ix->norms;
   const bool split = ix->search_type == VS_ST_PRECOMPUTED_TABLES && ix->list_tables;
-  {
+  bool scanned = false;
+  if (L.list_major) {   // (where its selection state does not fit the LDS: the query-major scan below)
+    auto part = [&](int which) {
+      return launch_ivfpq_scan_listmajor(which, g, q, nq, ix->centroids, ix->codebooks, probes, cdist, L.npr,
+                                         L.lm_first, L.lm_cap, ix->list_off, ix->codes, ix->ntotal, k, partial,
+                                         counter, base + L.o_lm, ix->ids, out_dist, out_ids, st);
+    };
+    {
+      StageTimer t(timed ? VS_STAGE_SCAN_FIRST : -1, st);
+      scanned = part(0) == 0;
+    }
+    if (scanned) {
+      {
+        StageTimer t(timed ? VS_STAGE_SCAN : -1, st);
+        (void)part(1);
+      }
+      StageTimer t(timed ? VS_STAGE_MERGE : -1, st);
+      (void)part(2);
+      if (stats)
+        launch_search_stats_rescan(ivfpq_listmajor_rescan_count(g, nq, L.npr, L.lm_cap, base + L.o_lm),
+                                   reinterpret_cast<long long*>(stats), st);
+    }
+  }
+  if (!scanned) {
     StageTimer t(timed ? VS_STAGE_SCAN : -1, st);
     if (launch_ivfpq_scan(g, q, nq, ix->centroids, ix->codebooks, probes, cdist, L.npr, L.nsplit,
                           ix->list_off, ix->codes, with_norms ? ix->norms : nullptr, ix->cnorm,
@@ -1228,7 +1289,7 @@ int vs_ivfpq_search_static(const vs_ivfpq* ix, const float* q, int64_t nq, int32
   if (int rc = search_check_args("vs_ivfpq_search_static", ix, q, nq, k, nprobe, out_dist, out_ids)) return rc;
   if (nq == 0) return VS_OK;
   SearchLayout L;
-  search_layout(ix, nq, k, nprobe, &L);
+  search_layout(ix, nq, k, nprobe, &L, false);   // (the list-major scan's buffers are not for a fixed work space)
   if (L.bytes > kStaticScratchBytes)
     return fail(VS_ERR_INVALID_ARG,
                 "vs_ivfpq_search_static: %lld queries with k = %d, nprobe = %d need %zu bytes of work space, "

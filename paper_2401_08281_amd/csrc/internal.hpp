@@ -97,16 +97,29 @@ int* launch_ivf_place(const int32_t* list_of, int64_t n, int nlist, const int64_
 void launch_probe_inner_products(const float* q, int64_t nq, int d, const float* centroids,
                                  const int32_t* probes, int nprobe, float* cdist, hipStream_t st);
 // stats[0] = sum over the n (query, probe) pairs of the probed list's size, stats[1] = pairs whose
-// list is not empty, stats[2] = mfma_rows, stats[3] = *fallback_count (0 if null); device memory,
+// list is not empty, stats[2] = mfma_rows, stats[3] = *fallback_count (0 if null), stats[4] = p_first
+// (probes per query that a list-major search scans query-major first; 0: the search is query-major),
+// stats[5] = the part of stats[0] that falls on those probes, stats[6] = 0 (set after a list-major
+// scan by launch_search_stats_rescan to the number of queries scanned again); device memory,
 // written in stream order.
 void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
-                         int64_t mfma_rows, long long* stats, hipStream_t st);
+                         int64_t mfma_rows, int nprobe, int p_first, long long* stats, hipStream_t st);
+void launch_search_stats_rescan(const unsigned* rescan_count, long long* stats, hipStream_t st);
 // out [K][M][dsub] = codebooks [M][K][dsub] with the first two axes exchanged.  launch_ivfpq_scan
 // expects it directly behind the codebooks it is given (codebooks + M * K * dsub).
 void launch_pq_codebooks_by_entry(const IvfpqDims& g, const float* codebooks, float* out, hipStream_t st);
 // out [nlist][K][M]: |T_m[j]|^2 + 2 <c_{l,m}, T_m[j]>, the per-list term of the split look-up tables
 void launch_pq_list_tables(const IvfpqDims& g, const float* centroids, const float* codebooks, float* out,
                            hipStream_t st);
+// List-major L2 scan with residual tables for large batches (shapes of the bank-private kernel).
+bool ivfpq_listmajor_shape(const IvfpqDims& g);
+size_t ivfpq_listmajor_bytes(const IvfpqDims& g, int64_t nq, int nprobe, int cap);
+const unsigned* ivfpq_listmajor_rescan_count(const IvfpqDims& g, int64_t nq, int nprobe, int cap, const char* lm);
+int launch_ivfpq_scan_listmajor(int part, const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                                const float* codebooks, const int32_t* probes, const float* cdist, int nprobe,
+                                int p_first, int cap, const int64_t* list_off, const uint8_t* codes,
+                                int64_t ntotal, int k, u64* first, u64* counter, char* lm, const int64_t* ids,
+                                float* out_dist, int64_t* out_ids, hipStream_t st);
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st);
 

@@ -652,7 +652,11 @@ void ivfpq_scan_bank_kernel(
     const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
     const float* __restrict__ norms, const float* __restrict__ cnorm,
     const float* __restrict__ list_tables, int64_t ntotal, int k, int tot,
-    KeySink sink, unsigned long long* __restrict__ next_item) {
+    KeySink sink, unsigned long long* __restrict__ next_item, const u32* __restrict__ item_list,
+    const u32* __restrict__ item_count) {
+  // item_list / item_count: null, or (nsplit = 1 only) the queries to scan and how many they are,
+  // both in device memory: the second launch after a list-major scan, for the queries whose
+  // candidate buffer overflowed (usually none: every workgroup then leaves at its first look)
   // METRIC 0: L2 with a table per (query, list); 1: inner product; 2: L2 through stored norms
   // (one table -2 <q_m, T_m[j]> per query; per list cdist - |c_l|^2 = |q|^2 - 2 <q, c_l>;
   // + |x'|^2 per code); 3: L2 with the table of a (query, list) pair formed as a per-query term
@@ -732,8 +736,8 @@ void ivfpq_scan_bank_kernel(
     if (tid == 0) *s_item = atomicAdd(next_item, 1ull);
     block_sync_lds();
     const int64_t item = (int64_t)*s_item;
-    if (item >= nitems) break;
-    const int64_t qi = item / nsplit;
+    if (item >= (item_count != nullptr ? (int64_t)*item_count : nitems)) break;
+    const int64_t qi = item_list != nullptr ? (int64_t)item_list[item] : item / nsplit;
     const int split = (int)(item % nsplit);
     const int p_begin = split * ppb;
     const int np = ntotal > 0 ? min(nprobe, p_begin + ppb) - p_begin : 0;
@@ -983,8 +987,334 @@ void ivfpq_scan_bank_kernel(
     }
     ws.finish();
     block_sync_lds();
-    block_rank_merge(slots, tot, NW, k, sink, item * k);
+    block_rank_merge(slots, tot, NW, k, sink, (item_list != nullptr ? qi : item) * k);
     block_sync_lds();   // the slots have been read; the next item may reset them
+  }
+}
+
+// ---------------------------------------------------------------------------
+// List-major scan (Sec. 4.3 "Compressed-domain search", L2 with residual tables; the shapes of
+// the bank-private kernel).  In a large batch every list is probed by several queries -- ten at
+// 10,000 queries x 64 probes over 65,536 lists -- and a query-major scan reads it from memory
+// every time: the queries that share a list do not run together.  Here the work item is a LIST:
+// the workgroup takes the (query, list) pairs of its list one after the other, builds each
+// pair's table exactly as the query-major kernel does (same registers, same arithmetic, same
+// look-ups: the distances are the same bits) and scans the list's codes again -- which the
+// first pair brought into the caches.  There is no selection state per pair: a code is kept
+// only if its distance is not worse than the bound of ITS query, the k-th best distance the
+// query-major kernel found in that query's first few lists, and kept codes are appended to the
+// query's candidate buffer (one atomic per wavefront and chunk that has any).  A buffer that
+// overflows flags its query, which a second launch of the query-major kernel then scans in
+// full.  lm_merge_kernel selects the k best of a query's first-stage results and candidates.
+// The pairs of a list come from pair_off / pairs (built by the lm_* kernels below); their
+// order inside a list does not matter for the results.
+// ---------------------------------------------------------------------------
+constexpr int kLmGroup = 64;   // pairs of a list staged in LDS at a time
+
+template <int M, int DSUB, int NT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 128, NT / 128)))
+void ivfpq_scan_listmajor_kernel(
+    const float* __restrict__ q, const float* __restrict__ centroids,
+    const float* __restrict__ codebooks, const float* __restrict__ cdist, int nprobe,
+    const u32* __restrict__ pair_off, const u32* __restrict__ pairs, int nlist,
+    const int64_t* __restrict__ list_off, const uint8_t* __restrict__ codes,
+    const float* __restrict__ qbound, u32* __restrict__ cand_count, u64* __restrict__ cand, int cap,
+    u32* __restrict__ overflow, unsigned long long* __restrict__ next_item) {
+  constexpr int K = 256, D = M * DSUB;
+  constexpr int REP = 32 / M;     // copies of every table
+  constexpr int EPL = K * M / NT; // table entries a lane builds = codewords it keeps
+  static_assert(NT == 256, "two workgroups per CU");
+  static_assert(M == 8 || M == 16 || M == 32, "tables of M sub-quantizers fill 32 banks in 32 / M copies");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* lut0 = reinterpret_cast<float*>(smem);                 // [256][64], at LDS address 0
+  unsigned long long* s_item = reinterpret_cast<unsigned long long*>(smem + kBankTableBytes);
+  int32_t* s_q = reinterpret_cast<int32_t*>(s_item + 1);        // kLmGroup: query of the pair
+  float* s_bias = reinterpret_cast<float*>(s_q + kLmGroup);     // kLmGroup: |q - c_l|^2
+  float* s_bnd = s_bias + kLmGroup;                             // kLmGroup: the query's bound
+  const int tid = threadIdx.x;
+  const int m_own = tid & (M - 1), jg = tid / M;
+  const int rep0 = jg & (REP - 1);
+
+  // codewords in registers as (|t|^2, -2 t), as in the query-major kernel
+  float T[EPL * DSUB];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i)
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u)
+      T[i * DSUB + u] = codebooks[((int64_t)m_own * K + jg * EPL + i) * DSUB + u];
+  wait_all_global_loads();
+  float TN[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    float tn = 0.f;
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) {
+      tn = __builtin_fmaf(T[i * DSUB + u], T[i * DSUB + u], tn);
+      T[i * DSUB + u] *= -2.f;
+    }
+    TN[i] = tn;
+  }
+  u32 col[M / 4];
+#pragma unroll
+  for (int w = 0; w < M / 4; ++w) {
+    u32 v = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      v |= (u32)(4 * (((4 * w + b + tid) & (M - 1)) + M * rep0)) << (8 * b);
+    col[w] = v;
+  }
+  int parity = 0;
+
+  for (;;) {
+    if (tid == 0) *s_item = atomicAdd(next_item, 1ull);
+    block_sync_lds();
+    const int64_t l = (int64_t)*s_item;
+    block_sync_lds();                                           // everyone has read the item number
+    if (l >= nlist) break;
+    const u32 p0 = pair_off[l], p1 = pair_off[l + 1];
+    const u32 cb = (u32)list_off[l], ce = (u32)list_off[l + 1];
+    if (p0 == p1 || cb == ce) continue;                         // (uniform)
+    float cl[DSUB];                                             // this lane's slice of the list's centroid
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) cl[u] = centroids[l * D + m_own * DSUB + u];
+#pragma unroll
+    for (int u = 0; u < DSUB; ++u) asm volatile("" : "+v"(cl[u]));   // in registers before the counted loads start
+
+    for (u32 g0 = p0; g0 < p1; g0 += kLmGroup) {
+      const int nl = (int)min((u32)kLmGroup, p1 - g0);
+      if (tid < nl) {
+        const u32 pr = pairs[g0 + tid];                         // query * nprobe + probe rank
+        const int qi = (int)(pr / (u32)nprobe);
+        s_q[tid] = qi;
+        s_bias[tid] = cdist[pr];
+        s_bnd[tid] = qbound[qi];
+      }
+      block_sync_lds();
+
+      // The (pair, chunk) steps of the group form one sequence; codes are requested two steps
+      // ahead into three register sets, the query slice of the next pair one pair ahead, all by
+      // hand-issued loads with counted waits (see CodeWords).
+      constexpr int NLT = CodeWords<M>::NLOAD;
+      int pc = 0, pp = 0;
+      u32 base_c = cb, base_p = cb;
+      auto request = [&](CodeWords<M>& dst) {
+        const u32 iv = base_p + (u32)tid;
+        const u32 i = iv < ce ? iv : base_p;
+        dst.load_async(codes + (u64)i * M);
+        if (pp < nl) {
+          base_p += NT;
+          if (base_p >= ce) { ++pp; base_p = cb; }
+        }
+      };
+      float qn[DSUB];
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) qn[u] = 0.f;
+      auto request_query = [&](int pl) {
+        if (pl < nl) {
+          const int qi = __builtin_amdgcn_readfirstlane(s_q[pl]);
+          const float* src = q + (int64_t)qi * D + m_own * DSUB;
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u)
+            asm volatile("global_load_dword %0, %1, off" : "=&v"(qn[u]) : "v"(src + u) : "memory");
+        }
+      };
+      CodeWords<M> S0, S1, S2;
+      float bias = 0.f, bnd = 0.f;
+      int qcur = 0;
+      auto consume = [&](CodeWords<M>& cw) {
+        cw.template wait_newer<2 * NLT>();
+        if (base_c == cb) {                                     // (uniform) first chunk of pair pc
+#pragma unroll
+          for (int w = 0; w < M / 4; ++w)
+            col[w] = (col[w] & 0x7f7f7f7fu) | (parity ? 0x80808080u : 0u);
+          float* __restrict__ lutp = lut0 + 32 * parity;
+          // the slice was requested at the first chunk of the pair before (or ahead of the loop):
+          // only this step's request is younger.  r = q - c, one fp32 subtraction per component.
+          float r[DSUB];
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u)
+            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qn[u]), "v"(cl[u]), "n"(NLT) : "memory");
+          request_query(pc + 1);
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) {
+            float acc = TN[i];
+#pragma unroll
+            for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
+#pragma unroll
+            for (int c = 0; c < REP; ++c)
+              lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = acc;
+          }
+          parity ^= 1;
+          bias = s_bias[pc];
+          bnd = s_bnd[pc];
+          qcur = __builtin_amdgcn_readfirstlane(s_q[pc]);
+          block_sync_lds();   // this table is visible; the scan on the other column set has finished everywhere
+        }
+        const u32 i = base_c + (u32)tid;
+        const bool valid = i < ce;
+        float dist = 0.f;
+        if (valid) dist = cw.template adc_banked<true>(smem, col, bias);
+        dist = fmaxf(dist, 0.f);                                // as the query-major kernel
+        // not worse in VALUE than the bound: a code that ties with the k-th best may still win on its id
+        const bool pass = valid && !(dist > bnd);
+        const u64 mask = __ballot(pass);
+        if (mask != 0) {
+          const int n = __popcll(mask);
+          u32 at = 0;
+          if ((tid & (VS_WAVE - 1)) == (int)__builtin_ctzll(mask)) at = atomicAdd(&cand_count[qcur], (u32)n);
+          at = (u32)__builtin_amdgcn_readlane((int)at, (int)__builtin_ctzll(mask));
+          if (pass) {
+            const u32 pos = at + (u32)__popcll(mask & ((1ull << (tid & (VS_WAVE - 1))) - 1ull));
+            if (pos < (u32)cap) cand[(u64)qcur * (u64)cap + pos] = make_key(dist, i, 0);
+            else overflow[qcur] = 1u;
+          }
+        }
+        base_c += NT;
+        if (base_c >= ce) { ++pc; base_c = cb; }
+      };
+      request_query(0);
+      request(S0);
+      request(S1);
+      for (;;) {
+        request(S2); consume(S0);
+        if (pc >= nl) break;
+        request(S0); consume(S1);
+        if (pc >= nl) break;
+        request(S1); consume(S2);
+        if (pc >= nl) break;
+      }
+      // the last requests land while their registers still belong to them (see the query-major kernel)
+      S0.drain(); S1.drain(); S2.drain();
+#pragma unroll
+      for (int u = 0; u < DSUB; ++u) asm volatile("s_waitcnt vmcnt(0)" : "+v"(qn[u]) : : "memory");
+      block_sync_lds();   // everyone is done with the group's entries in LDS
+    }
+  }
+}
+
+// Bounds, counters and flags of a batch, and the number of pairs per list: one lane per (query,
+// probe).  first[q][k] holds the k best keys of the query's first p_first probes, best first; the
+// bound is the value of the k-th (+inf while there are fewer than k).  list_count must be zero.
+__global__ __launch_bounds__(256) void lm_prepare_kernel(const int32_t* __restrict__ probes, int64_t nq,
+                                                         int nprobe, int p_first,
+                                                         const int64_t* __restrict__ list_off,
+                                                         const u64* __restrict__ first, int k,
+                                                         float* __restrict__ qbound, u32* __restrict__ cand_count,
+                                                         u32* __restrict__ overflow, u32* __restrict__ list_count,
+                                                         u32* __restrict__ rescan_count) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nq * nprobe) return;
+  if (i == 0) *rescan_count = 0u;
+  const int64_t qi = i / nprobe;
+  const int p = (int)(i - qi * nprobe);
+  if (p == 0) {
+    const u64 kth = first[qi * k + (k - 1)];
+    qbound[qi] = kth == KEY_EMPTY ? __builtin_inff() : key_value(kth, 0);
+    cand_count[qi] = 0u;
+    overflow[qi] = 0u;
+  }
+  if (p < p_first) return;
+  const int l = probes[i];
+  if (l >= 0 && list_off[l + 1] > list_off[l]) atomicAdd(&list_count[l], 1u);
+}
+
+// pair_off = exclusive prefix sums of list_count (nlist + 1 entries), in two launches: sums of
+// blocks of 1024 lists, then every block scans its lists starting from the sum of the blocks
+// before it (at most a few hundred block sums, added up by every block for itself).  list_count
+// itself is set back to zero to serve as the lists' fill cursors.
+__global__ __launch_bounds__(1024) void lm_block_sums_kernel(const u32* __restrict__ list_count, int nlist,
+                                                             u32* __restrict__ block_sum) {
+  __shared__ u32 part[16];
+  const int l = blockIdx.x * 1024 + threadIdx.x;
+  u32 v = l < nlist ? list_count[l] : 0u;
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u32 t = 0;
+    for (int w = 0; w < 16; ++w) t += part[w];
+    block_sum[blockIdx.x] = t;
+  }
+}
+__global__ __launch_bounds__(1024) void lm_offsets_kernel(u32* __restrict__ list_count, int nlist,
+                                                          const u32* __restrict__ block_sum,
+                                                          u32* __restrict__ pair_off) {
+  __shared__ u32 part[1024];
+  __shared__ u32 before;
+  const int tid = threadIdx.x;
+  const int l = blockIdx.x * 1024 + tid;
+  if (tid == 0) {
+    u32 t = 0;
+    for (int b = 0; b < (int)blockIdx.x; ++b) t += block_sum[b];
+    before = t;
+  }
+  const u32 own = l < nlist ? list_count[l] : 0u;
+  part[tid] = own;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const u32 v = tid >= off ? part[tid - off] : 0u;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  if (l < nlist) {
+    pair_off[l] = before + part[tid] - own;                     // exclusive
+    list_count[l] = 0u;
+    if (l == nlist - 1) pair_off[nlist] = before + part[tid];
+  }
+}
+
+__global__ __launch_bounds__(256) void lm_scatter_kernel(const int32_t* __restrict__ probes, int64_t nq,
+                                                         int nprobe, int p_first,
+                                                         const int64_t* __restrict__ list_off,
+                                                         const u32* __restrict__ pair_off,
+                                                         u32* __restrict__ cursor, u32* __restrict__ pairs) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nq * nprobe) return;
+  const int p = (int)(i % nprobe);
+  if (p < p_first) return;
+  const int l = probes[i];
+  if (l >= 0 && list_off[l + 1] > list_off[l]) pairs[pair_off[l] + atomicAdd(&cursor[l], 1u)] = (u32)i;
+}
+
+// One wavefront per query: the k best of its first-stage keys and its candidates, best first.
+// A query whose candidate buffer overflowed is put on the list of queries to scan again.
+template <int R>
+__global__ __launch_bounds__(64) void lm_merge_kernel(const u64* __restrict__ first,
+                                                      const u32* __restrict__ cand_count,
+                                                      const u64* __restrict__ cand, int cap, int k, int tot,
+                                                      const int64_t* __restrict__ ids,
+                                                      float* __restrict__ out_dist,
+                                                      int64_t* __restrict__ out_ids,
+                                                      const u32* __restrict__ overflow,
+                                                      u32* __restrict__ rescan_list,
+                                                      u32* __restrict__ rescan_count) {
+  extern __shared__ u64 mslots[];
+  const int64_t qi = blockIdx.x;
+  const int lane = lane_id();
+  if (lane == 0 && overflow[qi] != 0u) rescan_list[atomicAdd(rescan_count, 1u)] = (u32)qi;
+  WaveSelect<R> ws;
+  ws.init(mslots, tot, k);
+  for (int j0 = 0; j0 < k; j0 += VS_WAVE) {
+    const int j = j0 + lane;
+    const u64 key = j < k ? first[qi * k + j] : KEY_EMPTY;
+    ws.push(j < k && key != KEY_EMPTY, key);
+  }
+  const int n = (int)min(cand_count[qi], (u32)cap);
+  const u64* __restrict__ src = cand + (u64)qi * (u64)cap;
+  for (int j0 = 0; j0 < n; j0 += VS_WAVE) {
+    const int j = j0 + lane;
+    const u64 key = j < n ? src[j] : KEY_EMPTY;
+    ws.push(j < n, key);
+  }
+  ws.finish();
+  for (int j = lane; j < k; j += VS_WAVE) {
+    const u64 key = ws.s[j];
+    float v; int64_t id;
+    if (key == KEY_EMPTY) { v = __builtin_inff(); id = -1; }
+    else { v = key_value(key, 0); id = ids[key_index(key)]; }
+    out_dist[qi * k + j] = v;
+    out_ids[qi * k + j] = id;
   }
 }
 
@@ -1286,34 +1616,46 @@ __global__ __launch_bounds__(256) void probe_inner_products_kernel(const float* 
 __global__ __launch_bounds__(256) void search_stats_kernel(const int32_t* __restrict__ probes, int64_t n,
                                                            const int64_t* __restrict__ list_off,
                                                            const int* __restrict__ fallback_count,
-                                                           int64_t mfma_rows, unsigned long long* __restrict__ stats) {
-  unsigned long long codes = 0, lists = 0;
+                                                           int64_t mfma_rows, int nprobe, int p_first,
+                                                           unsigned long long* __restrict__ stats) {
+  unsigned long long codes = 0, lists = 0, first = 0;
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     const int l = probes[i];
     if (l < 0) continue;
     const unsigned long long sz = (unsigned long long)(list_off[l + 1] - list_off[l]);
     codes += sz;
     lists += sz > 0 ? 1ull : 0ull;
+    if ((int)(i % nprobe) < p_first) first += sz;
   }
   for (int o = 32; o > 0; o >>= 1) {
     codes += __shfl_down(codes, o, 64);
     lists += __shfl_down(lists, o, 64);
+    first += __shfl_down(first, o, 64);
   }
   // one pair of atomics per workgroup (thousands of wavefronts adding to the same two words
   // serialise: 63 us for 160k pairs)
-  __shared__ unsigned long long part[2][4];
-  if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = codes; part[1][threadIdx.x >> 6] = lists; }
+  __shared__ unsigned long long part[3][4];
+  if ((threadIdx.x & 63) == 0) {
+    part[0][threadIdx.x >> 6] = codes; part[1][threadIdx.x >> 6] = lists; part[2][threadIdx.x >> 6] = first;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     codes = part[0][0] + part[0][1] + part[0][2] + part[0][3];
     lists = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+    first = part[2][0] + part[2][1] + part[2][2] + part[2][3];
     if (codes) atomicAdd(&stats[0], codes);
     if (lists) atomicAdd(&stats[1], lists);
+    if (first) atomicAdd(&stats[5], first);
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     stats[2] = (unsigned long long)mfma_rows;
     stats[3] = fallback_count ? (unsigned long long)*fallback_count : 0ull;
+    stats[4] = (unsigned long long)p_first;
   }
+}
+__global__ void search_stats_rescan_kernel(const unsigned* __restrict__ rescan_count,
+                                           unsigned long long* __restrict__ stats) {
+  stats[6] = (unsigned long long)*rescan_count;
 }
 
 // ------------------------------------------------------------------ launchers
@@ -1417,11 +1759,15 @@ void launch_probe_inner_products(const float* q, int64_t nq, int d, const float*
 }
 
 void launch_search_stats(const int32_t* probes, int64_t n, const int64_t* list_off, const int* fallback_count,
-                         int64_t mfma_rows, long long* stats, hipStream_t st) {
-  launch_fill_u64(reinterpret_cast<u64*>(stats), 4, 0ull, st);
+                         int64_t mfma_rows, int nprobe, int p_first, long long* stats, hipStream_t st) {
+  launch_fill_u64(reinterpret_cast<u64*>(stats), 7, 0ull, st);
   const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(256, (n + 255) / 256));
   hipLaunchKernelGGL(search_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, st, probes, n, list_off,
-                     fallback_count, mfma_rows, reinterpret_cast<unsigned long long*>(stats));
+                     fallback_count, mfma_rows, nprobe, p_first, reinterpret_cast<unsigned long long*>(stats));
+}
+void launch_search_stats_rescan(const unsigned* rescan_count, long long* stats, hipStream_t st) {
+  hipLaunchKernelGGL(search_stats_rescan_kernel, dim3(1), dim3(1), 0, st, rescan_count,
+                     reinterpret_cast<unsigned long long*>(stats));
 }
 
 void launch_pq_codebooks_by_entry(const IvfpqDims& g, const float* codebooks, float* out, hipStream_t st) {
@@ -1462,7 +1808,8 @@ static int launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, cons
                              int nprobe, int ppb, int nsplit, const int64_t* list_off,
                              const uint8_t* codes, const float* norms, const float* cnorm,
                              const float* list_tables, int64_t ntotal, int k, int tot, KeySink sink,
-                             u64* counter, hipStream_t st) {
+                             u64* counter, hipStream_t st, const u32* item_list = nullptr,
+                             const u32* item_count = nullptr) {
   const size_t shmem = bank_scan_lds_bytes(tot, ppb);
   constexpr int NT = kBankThreads;
   auto kern = &ivfpq_scan_bank_kernel<M, DSUB, METRIC, R, NT>;
@@ -1480,7 +1827,7 @@ static int launch_scan_bank(const IvfpqDims& g, const float* q, int64_t nq, cons
   launch_fill_u64(counter, 1, 0ull, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), shmem, st, q, centroids, codebooks,
                      probes, cdist, nprobe, ppb, nsplit, nitems, list_off, codes, norms, cnorm, list_tables,
-                     ntotal, k, tot, sink, reinterpret_cast<unsigned long long*>(counter));
+                     ntotal, k, tot, sink, reinterpret_cast<unsigned long long*>(counter), item_list, item_count);
   return 0;
 }
 
@@ -1644,6 +1991,146 @@ int launch_ivfpq_scan(const IvfpqDims& g, const float* q, int64_t nq, const floa
   return 0;
 }
 
+
+// ---- list-major scan: work space and launches ---------------------------------------------
+// The work space behind `lm`: bounds [nq] f32, candidate counts [nq] u32, overflow flags [nq] u32,
+// the queries to scan again [nq] u32 and their number,
+// pairs per list / fill cursors [nlist] u32, their sums per 1024 lists, pair offsets [nlist + 1] u32, pairs [nq * nprobe]
+// u32, candidates [nq][cap] u64.
+namespace {
+struct LmLayout { size_t o_bound, o_count, o_flag, o_rlist, o_rcount, o_lcount, o_bsum, o_poff, o_pairs, o_cand, bytes; };
+LmLayout lm_layout(int64_t nq, int nprobe, int nlist, int cap) {
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  LmLayout L;
+  size_t o = 0;
+  L.o_bound = o; o += up((size_t)nq * sizeof(float));
+  L.o_count = o; o += up((size_t)nq * sizeof(u32));
+  L.o_flag = o; o += up((size_t)nq * sizeof(u32));
+  L.o_rlist = o; o += up((size_t)nq * sizeof(u32));
+  L.o_rcount = o; o += up(sizeof(u32));
+  L.o_lcount = o; o += up((size_t)nlist * sizeof(u32));
+  L.o_bsum = o; o += up((size_t)((nlist + 1023) / 1024) * sizeof(u32));
+  L.o_poff = o; o += up((size_t)(nlist + 1) * sizeof(u32));
+  L.o_pairs = o; o += up((size_t)nq * nprobe * sizeof(u32));
+  L.o_cand = o; o += up((size_t)nq * cap * sizeof(u64));
+  L.bytes = o;
+  return L;
+}
+size_t lm_scan_lds_bytes() { return (size_t)kBankTableBytes + 16 + (size_t)3 * kLmGroup * 4; }
+}  // namespace
+
+bool ivfpq_listmajor_shape(const IvfpqDims& g) {
+  return ivfpq_codes_rotated(g) && g.metric == 0 &&
+         ((g.M == 32 && g.dsub == 3) || (g.M == 16 && g.dsub == 8) || (g.M == 8 && g.dsub == 4));
+}
+size_t ivfpq_listmajor_bytes(const IvfpqDims& g, int64_t nq, int nprobe, int cap) {
+  return lm_layout(nq, nprobe, g.nlist, cap).bytes;
+}
+
+// The three parts of a list-major search, launched one after the other by the caller (which times
+// them apart): `part` 0 = the first p_first probes of every query, query-major, k best keys per
+// query into `first`, then the bounds and the pairs of the remaining probes grouped by list;
+// 1 = the list-major scan; 2 = k best of first-stage keys and candidates per query, then the
+// query-major kernel over all probes of the queries whose candidate buffer overflowed.
+template <int M, int DSUB>
+static int launch_listmajor_t(int part, const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                              const float* codebooks, const int32_t* probes, const float* cdist, int nprobe,
+                              int p_first, int cap, const int64_t* list_off, const uint8_t* codes,
+                              int64_t ntotal, int k, u64* first, u64* counter, char* lm, const int64_t* ids,
+                              float* out_dist, int64_t* out_ids, hipStream_t st) {
+  const LmLayout L = lm_layout(nq, nprobe, g.nlist, cap);
+  float* qbound = reinterpret_cast<float*>(lm + L.o_bound);
+  u32* cand_count = reinterpret_cast<u32*>(lm + L.o_count);
+  u32* flag = reinterpret_cast<u32*>(lm + L.o_flag);
+  u32* rlist = reinterpret_cast<u32*>(lm + L.o_rlist);
+  u32* rcount = reinterpret_cast<u32*>(lm + L.o_rcount);
+  u32* lcount = reinterpret_cast<u32*>(lm + L.o_lcount);
+  u32* bsum = reinterpret_cast<u32*>(lm + L.o_bsum);
+  u32* poff = reinterpret_cast<u32*>(lm + L.o_poff);
+  u32* pairs = reinterpret_cast<u32*>(lm + L.o_pairs);
+  u64* cand = reinterpret_cast<u64*>(lm + L.o_cand);
+  const int tot_a = bank_slots_for_k(k, p_first), tot_b = bank_slots_for_k(k, nprobe);
+  if (bank_scan_lds_bytes(tot_a, p_first) > 160 * 1024 || bank_scan_lds_bytes(tot_b, nprobe) > 160 * 1024) return -1;
+  auto scan_kern = &ivfpq_scan_listmajor_kernel<M, DSUB, kBankThreads>;
+  static const bool at_zero = dynamic_lds_starts_at_zero(reinterpret_cast<const void*>(scan_kern));
+  if (!at_zero) return -1;
+  if (part == 0) {
+    KeySink keys;
+    keys.metric = 0; keys.keys = first; keys.val = nullptr; keys.id64 = nullptr; keys.idx32 = nullptr; keys.idmap = nullptr;
+    const int ra = tot_a <= 128 ? 2 : (tot_a <= 256 ? 4 : 0);
+#define BANK_A(RR) launch_scan_bank<M, DSUB, 0, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, p_first, 1, \
+                                                    list_off, codes, nullptr, nullptr, nullptr, ntotal, k, tot_a, keys, counter, st)
+    const int rc = ra == 2 ? BANK_A(2) : (ra == 4 ? BANK_A(4) : BANK_A(0));
+#undef BANK_A
+    if (rc != 0) return rc;
+    launch_fill_u64(reinterpret_cast<u64*>(lcount), (int64_t)((g.nlist + 1) / 2), 0ull, st);
+    const unsigned gp = (unsigned)((nq * nprobe + 255) / 256);
+    hipLaunchKernelGGL(lm_prepare_kernel, dim3(gp), dim3(256), 0, st, probes, nq, nprobe, p_first, list_off, first, k,
+                       qbound, cand_count, flag, lcount, rcount);
+    const unsigned nblk = (unsigned)((g.nlist + 1023) / 1024);
+    hipLaunchKernelGGL(lm_block_sums_kernel, dim3(nblk), dim3(1024), 0, st, lcount, g.nlist, bsum);
+    hipLaunchKernelGGL(lm_offsets_kernel, dim3(nblk), dim3(1024), 0, st, lcount, g.nlist, bsum, poff);
+    hipLaunchKernelGGL(lm_scatter_kernel, dim3(gp), dim3(256), 0, st, probes, nq, nprobe, p_first, list_off, poff,
+                       lcount, pairs);
+    launch_fill_u64(counter, 1, 0ull, st);   // (the work counter of the scan that follows)
+    return 0;
+  }
+  if (part == 1) {
+    const size_t shmem = lm_scan_lds_bytes();
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)shmem);
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kern, kBankThreads, shmem) != hipSuccess || per_cu < 1)
+      per_cu = 1;
+    const int64_t grid = std::min<int64_t>(g.nlist, 256ll * per_cu);
+    hipLaunchKernelGGL(scan_kern, dim3((unsigned)grid), dim3(kBankThreads), shmem, st, q, centroids, codebooks, cdist,
+                       nprobe, poff, pairs, g.nlist, list_off, codes, qbound, cand_count, cand, cap, flag,
+                       reinterpret_cast<unsigned long long*>(counter));
+    return 0;
+  }
+  {
+    const int tot = select_slots_for_k(k);
+    const size_t shmem = (size_t)tot * sizeof(u64);
+    const dim3 grid((unsigned)nq), block(64);
+    switch (select_regs_for_slots(tot)) {
+      case 2: hipLaunchKernelGGL((lm_merge_kernel<2>), grid, block, shmem, st, first, cand_count, cand, cap, k, tot, ids, out_dist, out_ids, flag, rlist, rcount); break;
+      case 4: hipLaunchKernelGGL((lm_merge_kernel<4>), grid, block, shmem, st, first, cand_count, cand, cap, k, tot, ids, out_dist, out_ids, flag, rlist, rcount); break;
+      default: hipLaunchKernelGGL((lm_merge_kernel<0>), grid, block, shmem, st, first, cand_count, cand, cap, k, tot, ids, out_dist, out_ids, flag, rlist, rcount); break;
+    }
+  }
+  KeySink fin;
+  fin.metric = 0; fin.keys = nullptr; fin.val = out_dist; fin.id64 = out_ids; fin.idx32 = nullptr; fin.idmap = ids;
+  const int rb = tot_b <= 128 ? 2 : (tot_b <= 256 ? 4 : 0);
+#define BANK_B(RR) launch_scan_bank<M, DSUB, 0, RR>(g, q, nq, centroids, codebooks, probes, cdist, nprobe, nprobe, 1, \
+                                                    list_off, codes, nullptr, nullptr, nullptr, ntotal, k, tot_b, fin, counter, st, rlist, rcount)
+  return rb == 2 ? BANK_B(2) : (rb == 4 ? BANK_B(4) : BANK_B(0));
+#undef BANK_B
+}
+
+// L2 search with residual tables, list-major (see ivfpq_scan_listmajor_kernel), in three parts
+// (0, 1, 2: see launch_listmajor_t).  `first`: nq * k keys; `lm`: ivfpq_listmajor_bytes().
+// Returns -1 where the shape or the LDS does not fit (then from part 0 on: nothing was launched).
+int launch_ivfpq_scan_listmajor(int part, const IvfpqDims& g, const float* q, int64_t nq, const float* centroids,
+                                const float* codebooks, const int32_t* probes, const float* cdist, int nprobe,
+                                int p_first, int cap, const int64_t* list_off, const uint8_t* codes,
+                                int64_t ntotal, int k, u64* first, u64* counter, char* lm, const int64_t* ids,
+                                float* out_dist, int64_t* out_ids, hipStream_t st) {
+  if (nq <= 0) return 0;
+  if (!ivfpq_listmajor_shape(g) || p_first < 1 || p_first >= nprobe) return -1;
+#define LMGO(MM, DS)                                                                                      \
+  if (g.M == MM && g.dsub == DS)                                                                          \
+    return launch_listmajor_t<MM, DS>(part, g, q, nq, centroids, codebooks, probes, cdist, nprobe, p_first, cap, \
+                                      list_off, codes, ntotal, k, first, counter, lm, ids, out_dist, out_ids, st)
+  LMGO(32, 3);
+  LMGO(16, 8);
+  LMGO(8, 4);
+#undef LMGO
+  return -1;
+}
+// where the number of queries scanned again by the last part lies (one u32, device memory)
+const unsigned* ivfpq_listmajor_rescan_count(const IvfpqDims& g, int64_t nq, int nprobe, int cap, const char* lm) {
+  return reinterpret_cast<const unsigned*>(lm + lm_layout(nq, nprobe, g.nlist, cap).o_rcount);
+}
 
 void launch_ivfpq_merge(const u64* partial, int64_t nq, int nsplit, int k, int metric,
                         const int64_t* ids, float* out_dist, int64_t* out_ids, hipStream_t st) {

@@ -211,8 +211,12 @@ def test_bench_traffic_record_is_stamped_and_ignored_when_the_kernels_change(tmp
             w = csv.DictWriter(f, fieldnames=["Kernel_Name", "Counter_Name", "Counter_Value"])
             w.writeheader()
             for v in (scan_kib, scan_kib + 2.0):
-                w.writerow({"Kernel_Name": "void ivfpq_scan_bank_kernel<32, 3, 0, 4, 256>(float const*)",
+                # (C4 is searched list by list: that scan is the dominant kernel; the query-major kernel
+                # runs in the same search, for every query's first probes, and is not counted)
+                w.writerow({"Kernel_Name": "void ivfpq_scan_listmajor_kernel<32, 3, 256>(float const*)",
                             "Counter_Name": counter, "Counter_Value": v})
+                w.writerow({"Kernel_Name": "void ivfpq_scan_bank_kernel<32, 3, 0, 4, 256>(float const*)",
+                            "Counter_Name": counter, "Counter_Value": 7e8})
             w.writerow({"Kernel_Name": "vs_calibrate_copy_kernel(uint4 const*, uint4*, unsigned long)",
                         "Counter_Name": counter, "Counter_Value": copy_kib})
             w.writerow({"Kernel_Name": "other_kernel", "Counter_Name": counter, "Counter_Value": 1e9})
@@ -222,6 +226,7 @@ def test_bench_traffic_record_is_stamped_and_ignored_when_the_kernels_change(tmp
     Args.record_traffic = [counters("f", "FETCH_SIZE", 1000.0, 524288.0), counters("w", "WRITE_SIZE", 10.0, 1048576.0)]
     assert bench.record_traffic(Args) == 0
     rec = json.load(open(tmp_path / "profiles" / "traffic.json"))["ivfpq_scan_C4_nprobe64"]
+    assert rec["kernel"] == "ivfpq_scan_listmajor_kernel"
     assert rec["fetch_scale"] == 2.0 and rec["write_scale"] == 1.0
     assert rec["fetch_bytes"] == int(1001.0 * 1024 * 2.0) and rec["write_bytes"] == int(11.0 * 1024)
     assert bench.load_traffic("ivfpq_scan_C4_nprobe64") == rec["hbm_bytes_per_launch"]

@@ -499,6 +499,74 @@ def test_search_stats_count_what_the_search_read(vs):
     ix.close()
 
 
+LIST_MAJOR_CASES = {
+    # name: (config, [(k, nprobe, first, candidates)]) -- L2, the three shapes of the list-major scan
+    "c3_like": (S.config("C3", nb=150_000, nq=1500, ncomp=200, nlist=256), [(10, 16, 4, 1024), (100, 64, 2, 1024), (1, 8, 1, 256)]),
+    "c4_like": (S.config("C4", nb=120_000, nq=900, ncomp=100, nlist=128), [(100, 32, 4, 1024), (10, 16, 3, 512)]),
+    "c1_like": (S.config("C1", nb=60_000, nq=700, nlist=64), [(10, 8, 2, 1024), (40, 64, 4, 1024)]),
+    # a candidate buffer far too small: most queries overflow and are scanned again query by query
+    "c3_like_overflow": (S.config("C3", nb=150_000, nq=600, ncomp=200, nlist=256), [(10, 32, 1, 64)]),
+    # first lists shorter than k: no bound from the first stage, every code of the other lists is a candidate
+    "c4_like_short_lists": (S.config("C4", nb=6_000, nq=300, ncomp=100, nlist=256), [(100, 32, 1, 128), (100, 64, 4, 65536)]),
+    # a handful of queries
+    "c4_like_few_queries": (S.config("C4", nb=120_000, nq=5, ncomp=100, nlist=128), [(100, 64, 4, 1024)]),
+}
+
+
+@pytest.mark.parametrize("name", list(LIST_MAJOR_CASES))
+def test_list_major_scan_equals_query_major_scan_and_oracle(vs, oracle, name):
+    """The list-major scan (every list read once per batch; codes kept under the bound that the
+    query's first lists give; queries whose candidate buffer overflows scanned again) returns,
+    bit for bit, what the query-major scan returns -- the distances are formed by the same
+    arithmetic -- also when the buffer overflows, when the first lists give no bound, and call
+    after call; both agree with the oracle.  The statistics block says what was done."""
+    cfg, searches = LIST_MAJOR_CASES[name]
+    say("list-major %s nb=%d nq=%d nlist=%d M=%d" % (name, cfg["nb"], cfg["nq"], cfg["nlist"], cfg["M"]))
+    x, q = S.make_data(cfg)
+    ix, orc = build_both(vs, oracle, cfg, x)
+    xn = float(np.sqrt(orc.norms.max()))
+    try:
+        for k, nprobe, first, cand in searches:
+            say("  k=%d nprobe=%d first=%d candidates=%d" % (k, nprobe, first, cand))
+            vs.vs_set_option("list_major", -1)
+            D0, I0, st0 = ix.search_stats(dev(q), k, nprobe)
+            D0, I0 = host(D0).copy(), host(I0).copy()
+            assert st0["list_major_first_probes"] == 0 and st0["list_major_rescanned"] == 0
+            vs.vs_set_option("list_major", 1)
+            vs.vs_set_option("list_major_first", first)
+            vs.vs_set_option("list_major_candidates", cand)
+            for rep in range(2):
+                D1, I1, st1 = ix.search_stats(dev(q), k, nprobe)
+                np.testing.assert_array_equal(host(I1), I0)
+                np.testing.assert_array_equal(host(D1), D0)
+                npr = min(nprobe, cfg["nlist"])
+                assert st1["list_major_first_probes"] == min(first, npr - 1)
+                assert st1["scanned_codes"] == st0["scanned_codes"]
+                assert 0 < st1["list_major_first_codes"] <= st1["scanned_codes"]
+                assert 0 <= st1["list_major_rescanned"] <= cfg["nq"]
+                if name == "c3_like_overflow":
+                    assert st1["list_major_rescanned"] > 0
+                if cand >= 65536:
+                    assert st1["list_major_rescanned"] == 0
+            po, co = oracle.coarse_probe(q, orc.centroids, nprobe, L2)
+            Do, Io = orc.search(q, k + EXTRA, nprobe)
+            tc, te = l2_table_cancel(co, orc.codebooks)
+            same = check_search(host(D1), host(I1), Do, Io, L2, q, xn, cancel=tc, cancel_eps=te)
+            assert same > 0.99, same
+    finally:
+        vs.vs_set_option("list_major", 0)
+        vs.vs_set_option("list_major_first", 4)
+        vs.vs_set_option("list_major_candidates", 1024)
+        ix.close()
+
+
+def test_list_major_option_rules(vs):
+    for name, bad in (("list_major", 2), ("list_major_first", 0), ("list_major_first", 65), ("list_major_candidates", 63)):
+        with pytest.raises(Exception):
+            vs.vs_set_option(name, bad)
+    vs.vs_set_option("list_major", 0)
+
+
 def test_c3_full_size_sampled(vs, oracle):
     """IVF4096,PQ16x8 on 1M vectors in the launch configuration the bench times.
     The oracle cannot add 1M vectors in seconds, so assignments and codes are checked
