@@ -30,6 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix cores, published
+# ADC look-ups per second the vector ALUs can issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations
+# (no packed fp32), 1.5 of them per look-up (its addition + half an address instruction), in units of 1e12
+LOOKUP_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1.5 / 1e12
 # Next to the published peaks the JSON line carries what THIS GPU reached in THIS run on a
 # read-only stream over 2 GiB and on a register-only loop of v_mfma_f32_32x32x16_bf16
 # (libvs_calibrate.so; --no-calibrate-peaks leaves them null).
@@ -137,7 +140,8 @@ def record_traffic(args):
     nq_, npr_ = cfg["nq"], min(nprobe, cfg["nlist"])
     list_major = (args.search_type == "tables" and cfg["metric"] == 0 and cfg["nbits"] == 8 and
                   (cfg["M"], cfg["d"] // cfg["M"]) in ((16, 8), (32, 3), (8, 4)) and nq_ >= 4096 and npr_ >= 16 and
-                  nq_ * (npr_ - 4) >= 3 * cfg["nlist"] and cfg["nb"] * cfg["M"] >= (512 << 20))
+                  nq_ * (npr_ - 4) >= 3 * cfg["nlist"] and cfg["nb"] * cfg["M"] >= (512 << 20) and
+                  cfg["nb"] >= 1024 * cfg["nlist"])
     kernel = scan_kernel_name(cfg, args.search_type, list_major)
     GIB_KIB = float(1 << 20)
     got = {}
@@ -419,6 +423,37 @@ def main():
         "rows_matrix_core": stats["coarse_rows_matrix_core"],
         "rows_exact_fallback": stats_after["coarse_rows_fallback"],
         "rows_exact_fallback_first_call": stats["coarse_rows_fallback"], "traffic": None}
+    roofline = {"bound": "hbm", "kernel": scan_kernel_name(cfg, args.search_type, list_major), "achieved": achieved,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "peak_measured_read_stream": read_now,
+                "frac_of_measured": achieved / read_now if read_now else None,
+                "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
+                "kernel_ms": scan_ms, "pairs_per_launch": pairs,
+                "probed_nonempty_lists_per_launch": stats["probed_lists"]}
+    if list_major:
+        # The list-major scan reads every probed list from HBM about once per batch, so HBM no
+        # longer bounds it: its limit is the issue rate of the vector ALUs.  Algorithmic work: one
+        # fp32 addition per table entry looked up (M per code).  Peak: 256 CUs x 4 SIMDs x 16
+        # lanes x 2.4 GHz = 39.3e12 vector lane-operations/s without packed fp32; a look-up takes
+        # at least its addition and half an address instruction (one address serves the tables
+        # of two queries): 39.3e12 / 1.5 = 26.2e12 look-ups/s.
+        lookups = float(scanned_dominant) * cfg["M"]
+        alu_peak = LOOKUP_PEAK_T
+        alu = lookups / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0
+        roofline = {"bound": "alu", "kernel": roofline["kernel"], "achieved": alu, "peak": alu_peak,
+                    "unit": "TFLOP/s", "frac": alu / alu_peak,
+                    "peak_derivation": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz / 1.5 vector instructions per "
+                                       "look-up (one fp32 addition + half an address instruction); no packed fp32",
+                    "algorithmic_flop_per_launch": lookups, "traffic": traffic, "kernel_ms": scan_ms,
+                    "pairs_per_launch": pairs, "probed_nonempty_lists_per_launch": stats["probed_lists"],
+                    "hbm_equivalent": {"algorithmic_bytes_per_launch": algo_bytes, "achieved_GBps": achieved,
+                                       "frac_of_peak": achieved / HBM_PEAK_GBS,
+                                       "note": "codes visited x code size over the kernel's time; every probed "
+                                               "list comes from HBM about once per batch (see traffic), so this "
+                                               "rate is not an HBM rate and may exceed the HBM peak"},
+                    "list_major": {"first_probes_per_query": stats["list_major_first_probes"],
+                                   "codes_scanned_query_major_first": stats["list_major_first_codes"],
+                                   "queries_rescanned": stats_after["list_major_rescanned"]}}
     out = {
         "metric": "IVF-PQ queries/sec at fixed nprobe & recall@10; ADC-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -434,20 +469,7 @@ def main():
             "imbalance_factor": round(imbalance, 3), "index_build_s": round(t_add, 2),
             "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items() if v},
             **({"refine": refine} if refine else {}), **({"train": train} if train else {})},
-        "roofline": {"bound": "hbm", "kernel": scan_kernel_name(cfg, args.search_type, list_major), "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "peak_measured_read_stream": read_now,
-                     "frac_of_measured": achieved / read_now if read_now else None,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
-                     "kernel_ms": scan_ms, "pairs_per_launch": pairs,
-                     "probed_nonempty_lists_per_launch": stats["probed_lists"],
-                     **({"list_major": {"first_probes_per_query": stats["list_major_first_probes"],
-                                        "codes_scanned_query_major_first": stats["list_major_first_codes"],
-                                        "queries_rescanned": stats_after["list_major_rescanned"],
-                                        "note": "every probed list is read from HBM about once per batch: "
-                                                "traffic is far below the algorithmic bytes, and achieved "
-                                                "(algorithmic bytes / kernel time) may exceed what HBM streams"}}
-                        if list_major else {})},
+        "roofline": roofline,
         "roofline_coarse": roofline_coarse,
         "cpu_baseline": cpu,
     }

@@ -436,7 +436,8 @@ VS_API int vs_profile_read(double* stage_ms, int64_t* launches);
  *   (Sec. 4.3 "Compressed-domain search"; L2 indexes with residual tables of PQ8x8 on d = 32,
  *   PQ16x8 on d = 128 and PQ32x8 on d = 96): every list is then read from memory once per batch
  *   instead of once per query that probes it.  0 (default): where it pays -- at least 16 probes,
- *   at least 4096 queries and three (query, list) pairs per list, codes of 512 MB or more; 1:
+ *   at least 4096 queries and three (query, list) pairs per list, codes of 512 MB or more in
+ *   lists of 1024 codes or more on average; 1:
  *   wherever the index has one of these shapes; -1: never.  Results are identical either way.
  * "list_major_first" (default 4, 1..64): how many of its nearest lists every query scans on its
  *   own first; the k-th best distance found there is the bound under which the list-major scan

@@ -1148,7 +1148,9 @@ void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayo
   // probe splits: enough workgroups to fill the chip when nq is small
   L.nsplit = (int)std::min<int64_t>(L.npr, std::max<int64_t>(1, (4096 + nq - 1) / nq));
   // List-major scan: L2 with residual tables on the shapes of the bank-private kernel, when every
-  // list is probed several times by the batch and the codes do not fit the caches anyway.
+  // list is probed several times by the batch, the codes do not fit the caches anyway and the
+  // lists are long (a list of one or two chunks leaves the list-major kernel, which builds two
+  // tables and then scans, with nothing to overlap the builds with: measured slower at 244 codes).
   const int lm = g_list_major.load();
   const int first = std::min(g_lm_first.load(), L.npr - 1);
   const bool residual_tables = !(ix->search_type == VS_ST_STORED_NORMS && ix->norms) &&
@@ -1156,7 +1158,7 @@ void search_layout(const vs_ivfpq* ix, int64_t nq, int k, int nprobe, SearchLayo
   if (allow_list_major && lm >= 0 && ivfpq_listmajor_shape(g) && residual_tables && first >= 1 &&
       ix->ntotal > 0 && nq * (int64_t)L.npr < (1ll << 32) &&
       (lm == 1 || (L.nsplit == 1 && L.npr >= 16 && nq * (int64_t)(L.npr - first) >= 3 * (int64_t)g.nlist &&
-                   ix->ntotal * (int64_t)g.code_size >= (512ll << 20)))) {
+                   ix->ntotal * (int64_t)g.code_size >= (512ll << 20) && ix->ntotal >= 1024 * (int64_t)g.nlist))) {
     L.list_major = true;
     L.lm_first = first;
     L.lm_cap = g_lm_cap.load();

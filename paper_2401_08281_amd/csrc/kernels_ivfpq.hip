@@ -639,6 +639,36 @@ struct CodeWords {
     }
     return dist;
   }
+  // The same sums for TWO tables at once, one in each column set (32 floats = 128 bytes apart):
+  // one address instruction and one LDS instruction (a two-address read) per pair of look-ups.
+  // Each sum adds its entries in the order of adc_banked: the same bits.
+  __device__ __forceinline__ void adc_banked2(const u32 (&col)[W], float& da, float& db) const {
+    constexpr int G = M < 16 ? M : 16;
+#pragma unroll
+    for (int g0 = 0; g0 < M; g0 += G) {
+      u32 a[G];
+#pragma unroll
+      for (int i = 0; i < G / 4; ++i) {
+        const u32 cwd = word(g0 / 4 + i), cl = col[g0 / 4 + i];
+        a[4 * i] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0400u);
+        a[4 * i + 1] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0501u);
+        a[4 * i + 2] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0602u);
+        a[4 * i + 3] = __builtin_amdgcn_perm(cwd, cl, 0x0c0c0703u);
+      }
+      float va[G], vb[G];
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        const lds_cfloat_ptr e = reinterpret_cast<lds_cfloat_ptr>((uintptr_t)a[t]);
+        va[t] = e[0];
+        vb[t] = e[32];
+      }
+#pragma unroll
+      for (int t = 0; t < G; ++t) { da += va[t]; db += vb[t]; }
+      __builtin_amdgcn_sched_group_barrier(0x002, G, 0);       // the group's address instructions
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * G, 0);   // its reads, back to back
+      __builtin_amdgcn_sched_group_barrier(0x002, 2 * G, 0);   // its additions
+    }
+  }
 };
 
 constexpr int kBankTableBytes = 256 * 64 * (int)sizeof(float);   // 256 rows of 64 floats
@@ -1063,7 +1093,6 @@ void ivfpq_scan_listmajor_kernel(
       v |= (u32)(4 * (((4 * w + b + tid) & (M - 1)) + M * rep0)) << (8 * b);
     col[w] = v;
   }
-  int parity = 0;
 
   for (;;) {
     if (tid == 0) *s_item = atomicAdd(next_item, 1ull);
@@ -1091,102 +1120,128 @@ void ivfpq_scan_listmajor_kernel(
       }
       block_sync_lds();
 
-      // The (pair, chunk) steps of the group form one sequence; codes are requested two steps
-      // ahead into three register sets, the query slice of the next pair one pair ahead, all by
-      // hand-issued loads with counted waits (see CodeWords).
+      // Pairs are taken TWO at a time (a unit): the table of the first in column set 0, of the
+      // second in column set 1, and every code of the list is looked up in both with the same
+      // addresses -- per code and pair half an address instruction and half an LDS instruction
+      // fewer than one table at a time.  (A last pair without a partner runs with itself and a
+      // bound that nothing passes.)  The (unit, chunk) steps of the group form one sequence;
+      // codes are requested two steps ahead into three register sets, the query slices of the
+      // next unit one unit ahead, all by hand-issued loads with counted waits (see CodeWords).
       constexpr int NLT = CodeWords<M>::NLOAD;
+      const int nu = (nl + 1) / 2;
       int pc = 0, pp = 0;
       u32 base_c = cb, base_p = cb;
       auto request = [&](CodeWords<M>& dst) {
         const u32 iv = base_p + (u32)tid;
         const u32 i = iv < ce ? iv : base_p;
         dst.load_async(codes + (u64)i * M);
-        if (pp < nl) {
+        if (pp < nu) {
           base_p += NT;
           if (base_p >= ce) { ++pp; base_p = cb; }
         }
       };
-      float qn[DSUB];
+      float qa[DSUB], qb[DSUB];
 #pragma unroll
-      for (int u = 0; u < DSUB; ++u) qn[u] = 0.f;
-      auto request_query = [&](int pl) {
-        if (pl < nl) {
-          const int qi = __builtin_amdgcn_readfirstlane(s_q[pl]);
-          const float* src = q + (int64_t)qi * D + m_own * DSUB;
+      for (int u = 0; u < DSUB; ++u) qa[u] = qb[u] = 0.f;
+      auto request_queries = [&](int ul) {
+        if (ul < nu) {
+          const int ia = __builtin_amdgcn_readfirstlane(s_q[2 * ul]);
+          const int ib = __builtin_amdgcn_readfirstlane(s_q[min(2 * ul + 1, nl - 1)]);
+          const float* sa = q + (int64_t)ia * D + m_own * DSUB;
+          const float* sb = q + (int64_t)ib * D + m_own * DSUB;
 #pragma unroll
           for (int u = 0; u < DSUB; ++u)
-            asm volatile("global_load_dword %0, %1, off" : "=&v"(qn[u]) : "v"(src + u) : "memory");
+            asm volatile("global_load_dword %0, %1, off" : "=&v"(qa[u]) : "v"(sa + u) : "memory");
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u)
+            asm volatile("global_load_dword %0, %1, off" : "=&v"(qb[u]) : "v"(sb + u) : "memory");
         }
       };
       CodeWords<M> S0, S1, S2;
-      float bias = 0.f, bnd = 0.f;
-      int qcur = 0;
+      float bias_a = 0.f, bias_b = 0.f, bnd_a = 0.f, bnd_b = 0.f;
+      int q_a = 0, q_b = 0;
+      const int lane = tid & (VS_WAVE - 1);
+      // codes that pass their query's bound go to that query's candidate buffer: one atomic per
+      // wavefront and chunk that has any
+      auto append = [&](bool pass, float dist, int qcur, u32 i) {
+        const u64 mask = __ballot(pass);
+        if (mask == 0) return;
+        const int n = __popcll(mask);
+        const int leader = (int)__builtin_ctzll(mask);
+        u32 at = 0;
+        if (lane == leader) at = atomicAdd(&cand_count[qcur], (u32)n);
+        at = (u32)__builtin_amdgcn_readlane((int)at, leader);
+        if (pass) {
+          const u32 pos = at + (u32)__popcll(mask & ((1ull << lane) - 1ull));
+          if (pos < (u32)cap) cand[(u64)qcur * (u64)cap + pos] = make_key(dist, i, 0);
+          else overflow[qcur] = 1u;
+        }
+      };
       auto consume = [&](CodeWords<M>& cw) {
         cw.template wait_newer<2 * NLT>();
-        if (base_c == cb) {                                     // (uniform) first chunk of pair pc
-#pragma unroll
-          for (int w = 0; w < M / 4; ++w)
-            col[w] = (col[w] & 0x7f7f7f7fu) | (parity ? 0x80808080u : 0u);
-          float* __restrict__ lutp = lut0 + 32 * parity;
-          // the slice was requested at the first chunk of the pair before (or ahead of the loop):
+        if (base_c == cb) {                                     // (uniform) first chunk of unit pc
+          // the slices were requested at the first chunk of the unit before (or ahead of the loop):
           // only this step's request is younger.  r = q - c, one fp32 subtraction per component.
-          float r[DSUB];
+          float ra[DSUB], rb[DSUB];
 #pragma unroll
           for (int u = 0; u < DSUB; ++u)
-            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(r[u]) : "v"(qn[u]), "v"(cl[u]), "n"(NLT) : "memory");
-          request_query(pc + 1);
+            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(ra[u]) : "v"(qa[u]), "v"(cl[u]), "n"(NLT) : "memory");
+#pragma unroll
+          for (int u = 0; u < DSUB; ++u)
+            asm volatile("s_waitcnt vmcnt(%3)\n\tv_sub_f32 %0, %1, %2" : "=v"(rb[u]) : "v"(qb[u]), "v"(cl[u]), "n"(NLT) : "memory");
+          request_queries(pc + 1);
+          const bool single = 2 * pc + 1 >= nl;
+          bias_a = s_bias[2 * pc];
+          bnd_a = s_bnd[2 * pc];
+          q_a = __builtin_amdgcn_readfirstlane(s_q[2 * pc]);
+          bias_b = single ? bias_a : s_bias[2 * pc + 1];
+          bnd_b = single ? -__builtin_inff() : s_bnd[2 * pc + 1];
+          q_b = single ? q_a : __builtin_amdgcn_readfirstlane(s_q[2 * pc + 1]);
+          block_sync_lds();   // the scan of the unit before has finished everywhere: its tables may go
 #pragma unroll
           for (int i = 0; i < EPL; ++i) {
-            float acc = TN[i];
+            float acc_a = TN[i], acc_b = TN[i];
 #pragma unroll
-            for (int u = 0; u < DSUB; ++u) acc = __builtin_fmaf(r[u], T[i * DSUB + u], acc);
+            for (int u = 0; u < DSUB; ++u) {
+              acc_a = __builtin_fmaf(ra[u], T[i * DSUB + u], acc_a);
+              acc_b = __builtin_fmaf(rb[u], T[i * DSUB + u], acc_b);
+            }
 #pragma unroll
-            for (int c = 0; c < REP; ++c)
-              lutp[(jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1))] = acc;
+            for (int c = 0; c < REP; ++c) {
+              float* e = lut0 + (jg * EPL + i) * 64 + m_own + M * ((rep0 + c) & (REP - 1));
+              e[0] = acc_a;
+              e[32] = acc_b;
+            }
           }
-          parity ^= 1;
-          bias = s_bias[pc];
-          bnd = s_bnd[pc];
-          qcur = __builtin_amdgcn_readfirstlane(s_q[pc]);
-          block_sync_lds();   // this table is visible; the scan on the other column set has finished everywhere
+          block_sync_lds();   // both tables are visible
         }
         const u32 i = base_c + (u32)tid;
         const bool valid = i < ce;
-        float dist = 0.f;
-        if (valid) dist = cw.template adc_banked<true>(smem, col, bias);
-        dist = fmaxf(dist, 0.f);                                // as the query-major kernel
+        float da = bias_a, db = bias_b;
+        if (valid) cw.adc_banked2(col, da, db);
+        da = fmaxf(da, 0.f);                                    // as the query-major kernel
+        db = fmaxf(db, 0.f);
         // not worse in VALUE than the bound: a code that ties with the k-th best may still win on its id
-        const bool pass = valid && !(dist > bnd);
-        const u64 mask = __ballot(pass);
-        if (mask != 0) {
-          const int n = __popcll(mask);
-          u32 at = 0;
-          if ((tid & (VS_WAVE - 1)) == (int)__builtin_ctzll(mask)) at = atomicAdd(&cand_count[qcur], (u32)n);
-          at = (u32)__builtin_amdgcn_readlane((int)at, (int)__builtin_ctzll(mask));
-          if (pass) {
-            const u32 pos = at + (u32)__popcll(mask & ((1ull << (tid & (VS_WAVE - 1))) - 1ull));
-            if (pos < (u32)cap) cand[(u64)qcur * (u64)cap + pos] = make_key(dist, i, 0);
-            else overflow[qcur] = 1u;
-          }
-        }
+        append(valid && !(da > bnd_a), da, q_a, i);
+        append(valid && !(db > bnd_b), db, q_b, i);
         base_c += NT;
         if (base_c >= ce) { ++pc; base_c = cb; }
       };
-      request_query(0);
+      request_queries(0);
       request(S0);
       request(S1);
       for (;;) {
         request(S2); consume(S0);
-        if (pc >= nl) break;
+        if (pc >= nu) break;
         request(S0); consume(S1);
-        if (pc >= nl) break;
+        if (pc >= nu) break;
         request(S1); consume(S2);
-        if (pc >= nl) break;
+        if (pc >= nu) break;
       }
       // the last requests land while their registers still belong to them (see the query-major kernel)
       S0.drain(); S1.drain(); S2.drain();
 #pragma unroll
-      for (int u = 0; u < DSUB; ++u) asm volatile("s_waitcnt vmcnt(0)" : "+v"(qn[u]) : : "memory");
+      for (int u = 0; u < DSUB; ++u) asm volatile("s_waitcnt vmcnt(0)" : "+v"(qa[u]), "+v"(qb[u]) : : "memory");
       block_sync_lds();   // everyone is done with the group's entries in LDS
     }
   }
