@@ -260,6 +260,35 @@ def test_search_can_be_captured_in_a_hip_graph(vs):
             Df, If = vs.vs_flat_search(dev(x[:1000]), qs, 5, L2)     # unrelated eager work in between
             torch.cuda.synchronize()
             assert torch.equal(Dg, De) and torch.equal(Ig, Ie), "replay %d differs from the eager search" % rep
+    # the same for a search that runs list-major (eight kernels in a row, counters and candidate
+    # buffers reset by kernels of the search itself)
+    vs.vs_set_option("list_major", 1)
+    try:
+        nq = 128
+        say("graph capture of a list-major ivfpq search, nq=%d" % nq)
+        qs = qd[:nq].contiguous().clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                ix.search(qs, 10, 16)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            Dg, Ig = ix.search(qs, 10, 16)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            qs.copy_(qd[rep * nq:(rep + 1) * nq])
+            g.replay()
+            torch.cuda.synchronize()
+            vs.vs_set_option("list_major", -1)
+            De, Ie = ix.search(qs, 10, 16)                           # eager, query-major
+            vs.vs_set_option("list_major", 1)
+            torch.cuda.synchronize()
+            assert torch.equal(Dg, De) and torch.equal(Ig, Ie), "list-major replay %d differs from the eager search" % rep
+    finally:
+        vs.vs_set_option("list_major", 0)
     ix.close()
 
 
