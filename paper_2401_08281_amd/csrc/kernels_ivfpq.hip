@@ -1027,10 +1027,12 @@ void ivfpq_scan_bank_kernel(
 // the bank-private kernel).  In a large batch every list is probed by several queries -- ten at
 // 10,000 queries x 64 probes over 65,536 lists -- and a query-major scan reads it from memory
 // every time: the queries that share a list do not run together.  Here the work item is a LIST:
-// the workgroup takes the (query, list) pairs of its list one after the other, builds each
-// pair's table exactly as the query-major kernel does (same registers, same arithmetic, same
-// look-ups: the distances are the same bits) and scans the list's codes again -- which the
-// first pair brought into the caches.  There is no selection state per pair: a code is kept
+// the workgroup takes the (query, list) pairs of its list two at a time, builds each pair's
+// table exactly as the query-major kernel does (same registers, same arithmetic, and the
+// entries of a code are added in the same order: the distances are the same bits), one table in
+// each column set of the bank-private layout, and scans the list's codes again -- which the
+// first pairs brought into the caches -- looking every code up in both tables with one address
+// and one two-address read per sub-quantizer.  There is no selection state per pair: a code is kept
 // only if its distance is not worse than the bound of ITS query, the k-th best distance the
 // query-major kernel found in that query's first few lists, and kept codes are appended to the
 // query's candidate buffer (one atomic per wavefront and chunk that has any).  A buffer that
