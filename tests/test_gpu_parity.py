@@ -589,6 +589,51 @@ def test_list_major_scan_equals_query_major_scan_and_oracle(vs, oracle, name):
         ix.close()
 
 
+def test_list_major_random_shapes_equal_query_major(vs):
+    """Seeded odd shapes (empty index, one list, half of the lists empty, k beyond the index,
+    nprobe beyond nlist, first-stage probes and candidate buffers of every size): the list-major
+    search returns the query-major search's bits, and says how many queries it scanned again."""
+    import torch
+    rng = np.random.default_rng(2024)
+    shapes = [(128, 16), (96, 32), (32, 8)]
+    try:
+        for case in range(24):
+            d, M = shapes[case % 3]
+            nlist = int(rng.choice([1, 3, 17, 64, 300, 1000]))
+            nb = int(rng.choice([0, 50, 3000, 40_000, 150_000]))
+            nq = int(rng.choice([1, 7, 100, 1000, 5000]))
+            k = int(rng.choice([1, 5, 10, 100, 300, 1000]))
+            nprobe = int(rng.choice([1, 2, 5, 16, 64, 200]))
+            first = int(rng.choice([1, 2, 4, 9]))
+            cap = int(rng.choice([64, 100, 1024, 8192]))
+            say("list-major random %d: d=%d M=%d nlist=%d nb=%d nq=%d k=%d nprobe=%d first=%d candidates=%d" % (
+                case, d, M, nlist, nb, nq, k, nprobe, first, cap))
+            g = torch.Generator(device="cuda"); g.manual_seed(case)
+            cent = torch.randn((nlist, d), generator=g, device="cuda")
+            sel = torch.randint(0, nlist // 2 + 1, (max(nb, 1),), generator=g, device="cuda")[:nb]
+            x = cent[sel] + 0.4 * torch.randn((nb, d), generator=g, device="cuda")
+            q = cent[torch.randint(0, nlist, (nq,), generator=g, device="cuda")] + \
+                0.4 * torch.randn((nq, d), generator=g, device="cuda")
+            cb = 0.4 * torch.randn((M, 256, d // M), generator=g, device="cuda")
+            ix = vs.IVFPQ(d, L2, cent, cb, 8)
+            if nb:
+                ix.add(x)
+            vs.vs_set_option("list_major", -1)
+            D0, I0 = [host(t).copy() for t in ix.search(q, k, nprobe)]
+            vs.vs_set_option("list_major", 1)
+            vs.vs_set_option("list_major_first", first)
+            vs.vs_set_option("list_major_candidates", cap)
+            D1, I1, st = ix.search_stats(q, k, nprobe)
+            np.testing.assert_array_equal(host(I1), I0)
+            np.testing.assert_array_equal(host(D1), D0)
+            assert 0 <= st["list_major_rescanned"] <= nq
+            ix.close()
+    finally:
+        vs.vs_set_option("list_major", 0)
+        vs.vs_set_option("list_major_first", 4)
+        vs.vs_set_option("list_major_candidates", 1024)
+
+
 def test_list_major_option_rules(vs):
     for name, bad in (("list_major", 2), ("list_major_first", 0), ("list_major_first", 65), ("list_major_candidates", 63)):
         with pytest.raises(Exception):
