@@ -219,7 +219,8 @@ VS_API int vs_ivfpq_add(vs_ivfpq* ix, const float* x, int64_t n, const int64_t* 
  *   q [nq, d] fp32; out_dist [nq, k] fp32; out_ids [nq, k] int64.
  * Errors: null pointers (with nq > 0), k or nprobe < 1 or > VS_MAX_K.
  * Large batches on L2 indexes of the three fixed shapes are scanned list by list (option
- * "list_major" below): same results, one read of every probed list per batch.
+ * "list_major" below): same results, one read of every probed list per batch; the work space then
+ * also holds the candidate buffers, 8 bytes x "list_major_candidates" (default 1024) per query.
  * Work space: one grow-only buffer per index (the first call of a size allocates it; later
  * calls only enqueue kernels).  Searches of one index from several host threads or on several
  * streams are serialised on it: a call on another stream than the previous search's first waits,
