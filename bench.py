@@ -448,6 +448,7 @@ def main():
                     "pairs_per_launch": pairs, "probed_nonempty_lists_per_launch": stats["probed_lists"],
                     "hbm_equivalent": {"algorithmic_bytes_per_launch": algo_bytes, "achieved_GBps": achieved,
                                        "frac_of_peak": achieved / HBM_PEAK_GBS,
+                                       "peak_measured_read_stream": read_now,
                                        "note": "codes visited x code size over the kernel's time; every probed "
                                                "list comes from HBM about once per batch (see traffic), so this "
                                                "rate is not an HBM rate and may exceed the HBM peak"},
